@@ -1,0 +1,119 @@
+"""Seeded synthetic inputs: topologies and state/gradient generators.
+
+Holds none of the method's arithmetic: it only makes the inputs (mixing
+matrices as CSR, initial iterates, gradient streams) that are handed, as the
+same numpy arrays, to the HIP library and to the CPU oracle.  Shapes follow
+the paper's workloads (Section 5: ring / torus with n in {4,...,64}, flat
+parameter vectors of about 0.27 M and 28 M entries); the values are random
+stand-ins because the datasets and models are not available.
+"""
+import numpy as np
+
+
+def ring_csr(n, wdtype=np.float32):
+    """Ring of n nodes, uniform weights 1/3 on self and both neighbours
+    (Section 5, Table of topologies; w_ij = 1/max(deg) with the self-loop
+    counted).  n = 1 and n = 2 degenerate to the complete graph."""
+    rows = []
+    for i in range(n):
+        nb = sorted({(i - 1) % n, i, (i + 1) % n})
+        rows.append(nb)
+    return _uniform_rows(rows, wdtype)
+
+
+def torus_csr(rows_, cols_, wdtype=np.float32):
+    """2-D torus rows_ x cols_, uniform weights 1/5 (self + 4 neighbours)."""
+    n = rows_ * cols_
+    rows = []
+    for i in range(n):
+        r, c = divmod(i, cols_)
+        nb = {i, ((r - 1) % rows_) * cols_ + c, ((r + 1) % rows_) * cols_ + c,
+              r * cols_ + (c - 1) % cols_, r * cols_ + (c + 1) % cols_}
+        rows.append(sorted(nb))
+    return _uniform_rows(rows, wdtype)
+
+
+def complete_csr(n, wdtype=np.float32):
+    return _uniform_rows([list(range(n)) for _ in range(n)], wdtype)
+
+
+def _uniform_rows(rows, wdtype=np.float32):
+    """CSR (row_ptr, col_idx, w) with w_ij = 1/len(row) rounded to wdtype.  Only valid
+    (symmetric, doubly stochastic) when all rows have the same length, which
+    holds for the ring, the torus and the complete graph."""
+    n = len(rows)
+    deg = {len(r) for r in rows}
+    assert len(deg) == 1, "uniform weights need a regular graph"
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col, w = [], []
+    for i, r in enumerate(rows):
+        row_ptr[i + 1] = row_ptr[i] + len(r)
+        col.extend(r)
+        w.extend([wdtype(1.0) / wdtype(len(r))] * len(r))
+    return row_ptr, np.asarray(col, dtype=np.int32), np.asarray(w, dtype=wdtype)
+
+
+def metropolis_csr(adj):
+    """Irregular graph given as a symmetric boolean adjacency (no self loops):
+    w_ij = 1/(1 + max(deg i, deg j)) on edges, self weight = the remainder
+    (Section 3: weights from local node degrees)."""
+    adj = np.asarray(adj, dtype=bool)
+    n = adj.shape[0]
+    deg = adj.sum(1)
+    W = np.zeros((n, n), dtype=np.float64)
+    for i in range(n):
+        for j in range(n):
+            if i != j and adj[i, j]:
+                W[i, j] = 1.0 / (1.0 + max(deg[i], deg[j]))
+    for i in range(n):
+        W[i, i] = 1.0 - W[i].sum()
+    return dense_to_csr(W)
+
+
+def dense_to_csr(W):
+    W = np.asarray(W)
+    n = W.shape[0]
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col, w = [], []
+    for i in range(n):
+        nz = [j for j in range(n) if W[i, j] != 0 or j == i]
+        row_ptr[i + 1] = row_ptr[i] + len(nz)
+        col.extend(nz)
+        w.extend(np.float32(W[i, j]) for j in nz)
+    return row_ptr, np.asarray(col, dtype=np.int32), np.asarray(w, dtype=np.float32)
+
+
+def csr_to_dense(row_ptr, col_idx, w, dtype=np.float64):
+    n = len(row_ptr) - 1
+    W = np.zeros((n, n), dtype=dtype)
+    for i in range(n):
+        for p in range(row_ptr[i], row_ptr[i + 1]):
+            W[i, col_idx[p]] = w[p]
+    return W
+
+
+def normal_state(n, d, seed, std=1.0, shared=False, dtype=np.float32):
+    """Initial iterates: iid N(0, std^2); shared=True gives every worker the
+    same row (Algorithm 1 starts all nodes from one point)."""
+    rng = np.random.default_rng(seed)
+    if shared:
+        row = rng.standard_normal(d) * std
+        X = np.repeat(row[None, :], n, axis=0)
+    else:
+        X = rng.standard_normal((n, d)) * std
+    return np.ascontiguousarray(X, dtype=dtype)
+
+
+class GradientStream:
+    """Synthetic non-IID gradients g_i^t = b_i + eps: a fixed per-worker bias
+    b_i ~ N(0, bias_std^2) plus fresh noise eps ~ N(0, noise_std^2) per call."""
+
+    def __init__(self, n, d, seed, noise_std=0.01, bias_std=0.001, dtype=np.float32):
+        self.n, self.d, self.dtype = n, d, dtype
+        self.rng = np.random.default_rng(seed)
+        self.noise_std = noise_std
+        self.bias = (self.rng.standard_normal((n, d)) * bias_std) if bias_std > 0 else 0.0
+
+    def next(self):
+        g = self.rng.standard_normal((self.n, self.d)) * self.noise_std + self.bias
+        return np.ascontiguousarray(g, dtype=self.dtype)
