@@ -1,0 +1,152 @@
+/*
+ * choco.h - C ABI of the MI355X (gfx950) CHOCO-Gossip / CHOCO-SGD step.
+ *
+ * One context holds the state of all n simulated workers on one GPU:
+ *   X     n x ld fp32, row i = private iterate x_i          (caller's buffer)
+ *   Xhat  n x ld fp32, row i = public copy  xhat_i           (in the workspace)
+ *   S     n x ld fp32, row i = sum_j w_ij xhat_j             (in the workspace)
+ * following Algorithm 1 (CHOCO-SGD) of the paper and the remark after it that a
+ * node needs three vectors.  "send q_i / receive q_j" (Algorithm 1, lines 4-6)
+ * is plain device-memory traffic here because all replicas of xhat_j are equal.
+ *
+ * Conventions
+ *   - every function returns CHOCO_OK (0) or a negative error code; nothing is
+ *     printed, nothing aborts, no exception crosses the boundary;
+ *   - pointers named *_dev are device pointers, *_host are host pointers;
+ *   - device buffers are owned by the caller (allocated e.g. with torch); the
+ *     library allocates no device memory, it only carves up the workspace;
+ *   - work is enqueued on the caller's stream and the calls return without
+ *     synchronising, except choco_metrics, choco_last_scalars and choco_sync;
+ *   - inputs must be finite; NaN/Inf give unspecified selections.
+ */
+#ifndef CHOCO_H
+#define CHOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct choco_ctx choco_ctx; /* opaque, host memory, freed by choco_destroy */
+
+enum {
+  CHOCO_OK = 0,
+  CHOCO_E_INVAL = -1,       /* bad argument (see choco_init)                        */
+  CHOCO_E_NOMEM = -2,       /* workspace too small / host allocation failed         */
+  CHOCO_E_HIP = -3,         /* HIP runtime error; see choco_last_hip_error          */
+  CHOCO_E_UNSUPPORTED = -4  /* valid request this build does not implement          */
+};
+
+/* Compression operators Q of Appendix C ("Compression Schemes"). */
+enum {
+  CHOCO_Q_IDENTITY = 0, /* Q(v) = v: exact averaging (Appendix A, first example)    */
+  CHOCO_Q_TOPK = 1,     /* top_a: keep the k entries of largest |v|; ties -> lower index */
+  CHOCO_Q_RANDK = 2,    /* random_a: keep k entries chosen uniformly (Philox, k smallest words) */
+  CHOCO_Q_SIGN = 3,     /* sign: (||v||_1 / d) * sgn(v), sgn = -1 iff v < 0          */
+  CHOCO_Q_QSGD = 4      /* gsgd_b with s = 2^(b-1) levels and random dithering      */
+};
+
+/* Order of the two halves of one gossip step. */
+enum {
+  CHOCO_ORDER_COMPRESS_THEN_MIX = 0, /* Algorithm 1 lines 3-7, then line 2 with the new xhat */
+  CHOCO_ORDER_MIX_THEN_COMPRESS = 1  /* Algorithm 1 as printed: line 2, then lines 3-7       */
+};
+
+/* How line 2 of Algorithm 1, x_i += gamma * sum_j w_ij (xhat_j - xhat_i), is evaluated. */
+enum {
+  CHOCO_MIX_AUTO = 0,          /* INCREMENTAL_S for top_a/random_a, DIRECT otherwise        */
+  CHOCO_MIX_INCREMENTAL_S = 1, /* S_i += sum_j w_ij q_j (CSR order); x_i += gamma (S_i - xhat_i) */
+  CHOCO_MIX_DIRECT = 2         /* acc = sum_j w_ij (xhat_j - xhat_i) in CSR order from 0    */
+};
+
+typedef struct {
+  int32_t n;          /* number of workers, >= 1                                         */
+  int64_t d;          /* coordinates per worker, 1 <= d < 2^31                           */
+  int64_t ld;         /* row stride of X, G and the internal arrays in floats; 0 means d
+                         rounded up to a multiple of 4.  Must be >= d and a multiple of 4 */
+  /* Mixing matrix W of Assumption 1 as CSR.  HOST pointers, copied during choco_init.
+     Row i lists the neighbours of i INCLUDING i itself (Algorithm 1, line 4), columns
+     strictly ascending.  W must be symmetric with non-negative entries and rows summing
+     to 1, each to within 1e-6.  The values are used as given (never renormalised).      */
+  const int32_t *row_ptr_host; /* n + 1 entries */
+  const int32_t *col_idx_host; /* nnz entries   */
+  const float *w_host;         /* nnz entries   */
+  float gamma;           /* consensus stepsize of Algorithm 1, finite and > 0             */
+  int32_t compressor;    /* CHOCO_Q_*                                                     */
+  int64_t k;             /* TOPK / RANDK: kept coordinates floor(a d), 1 <= k <= d        */
+  int32_t levels;        /* QSGD: s = 2^(b-1) >= 1                                        */
+  int32_t qsgd_biased;   /* 1: scale by 1/tau (biased gsgd_b); 0: unbiased gsgd_b         */
+  int32_t randk_rescale; /* 0: x .* u (biased random_a); 1: (d/k) x .* u (unbiased)       */
+  int32_t order;         /* CHOCO_ORDER_*                                                 */
+  int32_t mix_form;      /* CHOCO_MIX_*                                                   */
+  uint64_t seed;         /* shared seed of the random operators (Appendix C, random_a)    */
+  void *stream;          /* hipStream_t owned by the caller; NULL = the null stream       */
+} choco_config;
+
+/* Bytes of device workspace choco_init needs for this configuration (Xhat, S, the CSR
+   copy and scratch for the operators).  Validates the scalar fields of cfg only. */
+int choco_workspace_bytes(const choco_config *cfg, size_t *bytes_host);
+
+/* Algorithm 1, input line: takes X = x^(-1/2) as it stands in x_dev (n*ld floats, 16-byte
+   aligned, caller-owned, updated in place by every step), sets xhat_i^(0) = 0, S = 0,
+   t = 0.  workspace_dev must be 256-byte aligned.  CHOCO_E_INVAL for n < 1, d out of
+   range, bad ld, k outside [1, d], levels < 1, gamma <= 0 or not finite, null pointers,
+   malformed CSR, or a W that violates Assumption 1; CHOCO_E_NOMEM if the workspace is
+   too small.  On error *out is NULL. */
+int choco_init(const choco_config *cfg, float *x_dev, void *workspace_dev, size_t workspace_bytes,
+               choco_ctx **out);
+
+/* One CHOCO-Gossip round for all workers (Algorithm 1 lines 2-7; matrix form in
+   Appendix A, "Example: CHOCO-SGD"): v_i = x_i - xhat_i, q_i = Q(v_i), xhat_j += q_j,
+   x_i += gamma sum_j w_ij (xhat_j - xhat_i), in the configured order.  Asynchronous;
+   advances the step counter t used to key the random operators. */
+int choco_gossip_step(choco_ctx *ctx);
+
+/* Algorithm 1 line 9: x_i <- x_i - lr * g_i.  g_dev: n*ld floats, 16-byte aligned. */
+int choco_sgd_step(choco_ctx *ctx, const float *g_dev, float lr);
+
+/* Algorithm 2 lines 9-10 (momentum with weight decay):
+   m_i <- (g_i + lambda x_i) + beta m_i;  x_i <- x_i - lr m_i.
+   m_dev: n*ld floats of caller-owned momentum memory, zero before the first call. */
+int choco_momentum_step(choco_ctx *ctx, const float *g_dev, float *m_dev, float lr, float beta,
+                        float lambda);
+
+/* Consensus distance (1/n) sum_i ||x_i - xbar||^2 (Section 5), ||xbar||_2 and the Lyapunov
+   function Psi = ||X - Xbar||_F^2 + ||X - Xhat||_F^2 (Assumption 3), accumulated in fp64.
+   Any output pointer may be NULL.  Synchronises the stream. */
+int choco_metrics(choco_ctx *ctx, double *consensus_host, double *mean_norm_host,
+                  double *psi_host);
+
+/* Device pointers to Xhat and S (n*ld floats each, inside the workspace). */
+int choco_xhat(choco_ctx *ctx, float **xhat_dev);
+int choco_nsum(choco_ctx *ctx, float **s_dev);
+
+/* Message read-back for parity checks.
+   choco_last_selection: TOPK/RANDK only; copies the k (index, value) pairs each worker
+   sent in the last gossip step into idx_dev / val_dev (n*k entries each, either may be
+   NULL), in unspecified order within a worker.  Asynchronous.
+   choco_set_capture: SIGN/QSGD only; while codes_dev is non-NULL every gossip step also
+   writes the transmitted code of each entry there (n*ld int32: sign -> +1/-1, gsgd ->
+   sig(v)*level).  NULL switches it off.
+   choco_last_scalars: 4 doubles per worker from the last step, sign: {||v||_1, scale, 0, 0},
+   gsgd: {sum v^2, ||v||_2, s/||v||_2, ||v||_2/(tau s)} (the last two as rounded to fp32);
+   TOPK/RANDK: {threshold key, tie cut-off index, kept count, 0}.  Synchronises. */
+int choco_last_selection(choco_ctx *ctx, int32_t *idx_dev, float *val_dev);
+int choco_set_capture(choco_ctx *ctx, int32_t *codes_dev);
+int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
+
+/* Step counter t (keys the random operators; set it to resume a run exactly). */
+int choco_get_step(choco_ctx *ctx, uint64_t *t_host);
+int choco_set_step(choco_ctx *ctx, uint64_t t);
+
+int choco_sync(choco_ctx *ctx);    /* hipStreamSynchronize on the context's stream */
+int choco_destroy(choco_ctx *ctx); /* frees host memory only; NULL is allowed      */
+const char *choco_strerror(int code);
+int choco_last_hip_error(choco_ctx *ctx); /* raw hipError_t of the last CHOCO_E_HIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHOCO_H */

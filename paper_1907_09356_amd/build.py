@@ -1,0 +1,36 @@
+"""Compile the HIP library for gfx950 into paper_1907_09356_amd/libchoco.so."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = [os.path.join(HERE, "csrc", "choco.hip")]
+DEPS = SRC + [os.path.join(HERE, "csrc", "choco_kernels.h"), os.path.join(ROOT, "include", "choco.h")]
+LIB = os.path.join(HERE, "libchoco.so")
+
+# -ffp-contract=off: every product and sum is rounded on its own, which the
+# bit-exact parity of the discrete decisions relies on.  Packed fp32 ops are
+# switched off as a precaution against their known mis-roundings.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fno-fast-math",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-shared", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    return any(os.path.getmtime(p) > os.path.getmtime(LIB) for p in DEPS)
+
+
+def build(verbose: bool = False) -> str:
+    tmp = LIB + ".tmp%d" % os.getpid()
+    cmd = ["hipcc"] + FLAGS + SRC + ["-o", tmp]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

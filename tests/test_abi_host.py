@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1907_09356_amd import binding as B
+from paper_1907_09356_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "choco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(choco_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 15
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), "missing export " + name
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror():
+    assert B.strerror(B.OK) == "ok"
+    for code in (B.E_INVAL, B.E_NOMEM, B.E_HIP, B.E_UNSUPPORTED, -99):
+        assert isinstance(B.strerror(code), str) and B.strerror(code)
+
+
+def cfg(**over):
+    topo = over.pop("topo", synth.ring_csr(8))
+    kw = dict(n=8, d=1000, gamma=0.1, compressor=B.Q_TOPK, k=10)
+    kw.update(over)
+    return B.make_config(kw.pop("n"), kw.pop("d"), *topo, kw.pop("gamma"), kw.pop("compressor"), **kw)
+
+
+def test_workspace_bytes_scales_with_the_state():
+    c, keep = cfg()
+    small = B.workspace_bytes(c)
+    c2, keep2 = cfg(d=100000, k=1000)
+    big = B.workspace_bytes(c2)
+    assert small >= 2 * 8 * 1000 * 4 and big >= 2 * 8 * 100000 * 4
+    c3, keep3 = cfg(d=100000, compressor=B.Q_SIGN)
+    assert B.workspace_bytes(c3) < big     # direct mix form keeps no S array
+
+
+@pytest.mark.parametrize("over", [
+    dict(n=0), dict(d=0), dict(d=2 ** 31), dict(ld=1001), dict(ld=996), dict(gamma=0.0),
+    dict(gamma=-1.0), dict(gamma=float("nan")), dict(gamma=float("inf")), dict(compressor=7),
+    dict(k=0), dict(k=1001), dict(compressor=B.Q_QSGD, levels=0), dict(order=2), dict(mix_form=3),
+])
+def test_bad_scalars_are_rejected(over):
+    c, keep = cfg(**over)
+    out = ctypes.c_size_t()
+    assert B.lib().choco_workspace_bytes(ctypes.byref(c), ctypes.byref(out)) == B.E_INVAL
+
+
+def test_unsupported_combination_is_reported():
+    c, keep = cfg(compressor=B.Q_SIGN, mix_form=B.MIX_INCREMENTAL_S)
+    out = ctypes.c_size_t()
+    assert B.lib().choco_workspace_bytes(ctypes.byref(c), ctypes.byref(out)) == B.E_UNSUPPORTED
+
+
+def init_code(c, x=0x1000, ws=0x10000, nbytes=1 << 40):
+    ctx = ctypes.c_void_p(1)
+    rc = B.lib().choco_init(ctypes.byref(c), x, ws, nbytes, ctypes.byref(ctx))
+    assert ctx.value is None
+    return rc
+
+
+def test_bad_mixing_matrices_are_rejected_before_any_device_work():
+    # the pointers below are never dereferenced: validation fails first
+    rp, col, w = synth.ring_csr(8)
+    bad = []
+    w2 = w.copy(); w2[0] = 0.5                       # row does not sum to one / asymmetric
+    bad.append((rp, col, w2))
+    w3 = w.copy(); w3[1] = -w3[1]                    # negative weight
+    bad.append((rp, col, w3))
+    col2 = col.copy(); col2[0], col2[1] = col2[1], col2[0]   # columns not ascending
+    bad.append((rp, col2, w))
+    col3 = col.copy(); col3[2] = 99                  # column out of range
+    bad.append((rp, col3, w))
+    rp2 = rp.copy(); rp2[0] = 1
+    bad.append((rp2, col, w))
+    # no self loop: a 4-cycle with weights 1/2 on the two neighbours only
+    rp4 = np.array([0, 2, 4, 6, 8], dtype=np.int32)
+    col4 = np.array([1, 3, 0, 2, 1, 3, 0, 2], dtype=np.int32)
+    w4 = np.full(8, 0.5, dtype=np.float32)
+    c4, k4 = B.make_config(4, 100, rp4, col4, w4, 0.1, B.Q_SIGN)
+    assert init_code(c4) == B.E_INVAL
+    # asymmetric pattern: 0 lists 1 but 1 does not list 0
+    rp5 = np.array([0, 2, 3], dtype=np.int32)
+    col5 = np.array([0, 1, 1], dtype=np.int32)
+    w5 = np.array([0.5, 0.5, 1.0], dtype=np.float32)
+    c5, k5 = B.make_config(2, 100, rp5, col5, w5, 0.1, B.Q_SIGN)
+    assert init_code(c5) == B.E_INVAL
+    for topo in bad:
+        c, keep = cfg(topo=topo)
+        assert init_code(c) == B.E_INVAL
+
+
+def test_null_pointers_alignment_and_small_workspace():
+    c, keep = cfg()
+    assert init_code(c, x=0) == B.E_INVAL
+    assert init_code(c, ws=0) == B.E_INVAL
+    assert init_code(c, x=0x1004) == B.E_INVAL       # X must be 16-byte aligned
+    assert init_code(c, ws=0x10010) == B.E_INVAL     # workspace must be 256-byte aligned
+    assert init_code(c, nbytes=B.workspace_bytes(c) - 1) == B.E_NOMEM
+    c2, keep2 = B.make_config(8, 1000, None, None, None, 0.1, B.Q_SIGN)
+    assert init_code(c2) == B.E_INVAL
+    L = B.lib()
+    assert L.choco_gossip_step(None) == B.E_INVAL
+    assert L.choco_sgd_step(None, 0x1000, 0.1) == B.E_INVAL
+    assert L.choco_destroy(None) == B.OK

@@ -1,0 +1,287 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bar: kept index sets, sign bits, quantisation levels and the per-worker norms/scales are
+bit-exact; X, Xhat and S agree to 1e-6 relative L2 per step (they are in fact required to
+be bit-identical here, because both sides round every operation in the same order).
+"""
+import numpy as np
+import pytest
+
+from paper_1907_09356_amd import binding as B
+from paper_1907_09356_amd import synth
+from tests.parity_util import Pair, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+ORDERS = [B.ORDER_COMPRESS_THEN_MIX, B.ORDER_MIX_THEN_COMPRESS]
+
+COMPRESSORS = {
+    "identity": dict(compressor=B.Q_IDENTITY),
+    "sign": dict(compressor=B.Q_SIGN),
+    "qsgd16": dict(compressor=B.Q_QSGD, levels=16),
+    "qsgd2_unbiased": dict(compressor=B.Q_QSGD, levels=2, qsgd_biased=0),
+    "qsgd_b16": dict(compressor=B.Q_QSGD, levels=32768),
+    "topk": dict(compressor=B.Q_TOPK),
+    "randk": dict(compressor=B.Q_RANDK),
+    "randk_rescaled": dict(compressor=B.Q_RANDK, randk_rescale=1),
+}
+
+
+def topo_for(n):
+    if n == 9:
+        return synth.torus_csr(3, 3)
+    if n == 64:
+        return synth.torus_csr(8, 8)
+    return synth.ring_csr(n)
+
+
+def run(n, d, comp, order, steps=6, mix_form=B.MIX_AUTO, gamma=0.2, frac=0.01, seed=5, lr=0.05,
+        force=False, x0=None):
+    kw = dict(COMPRESSORS[comp])
+    if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+        kw["k"] = max(1, int(frac * d))
+    X0 = synth.normal_state(n, d, seed=seed) if x0 is None else x0
+    pair = Pair(X0, topo_for(n), gamma, order=order, mix_form=mix_form, seed=1234 + seed, **kw)
+    grads = synth.GradientStream(n, d, seed=seed + 1)
+    try:
+        for t in range(steps):
+            if force:
+                pair.force_state()
+            det = pair.gossip_step()
+            pair.check(det, tag="%s n=%d d=%d order=%d step %d" % (comp, n, d, order, t))
+            pair.sgd_step(grads.next(), lr)
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", list(COMPRESSORS))
+@pytest.mark.parametrize("n,d", [(8, 4096), (9, 2000), (8, 70001), (3, 1027), (64, 5000)])
+def test_step_parity_free_running(n, d, comp, order):
+    # several 256-wide tiles, ragged tails (d not a multiple of 4 or 256), ring and torus
+    run(n, d, comp, order)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
+def test_step_parity_teacher_forced(comp, order):
+    run(8, 10000, comp, order, steps=4, force=True)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", ["topk", "randk"])
+def test_sparse_operators_with_direct_mix(comp, order):
+    run(8, 6000, comp, order, mix_form=B.MIX_DIRECT)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", ["identity", "sign", "qsgd16", "topk", "randk"])
+def test_more_workers_than_the_lds_tile_holds(comp, order):
+    # n > 64: the direct mix reads neighbour rows from global memory instead of LDS
+    run(70, 1030, comp, order, steps=3)
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (3, 2), (5, 5), (300, 1), (300, 300), (4096, 2048)])
+@pytest.mark.parametrize("comp", ["topk", "randk"])
+def test_select_extreme_k(comp, d, k):
+    kw = dict(COMPRESSORS[comp])
+    pair = Pair(synth.normal_state(4, d, seed=d + k), synth.ring_csr(4), 0.3, k=k, seed=9, **kw)
+    try:
+        for t in range(3):
+            det = pair.gossip_step()
+            pair.check(det, tag="%s d=%d k=%d step %d" % (comp, d, k, t))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+def test_topk_ties_and_zeros(order):
+    # integer-valued state: thousands of equal magnitudes, so the tie rule (lower index
+    # first) decides most of the selection; all-zero rows as well
+    rng = np.random.default_rng(3)
+    n, d, k = 5, 3000, 100
+    X0 = rng.integers(-3, 4, size=(n, d)).astype(np.float32)
+    X0[2] = 0.0
+    X0[3, ::2] = -0.0
+    pair = Pair(X0, synth.ring_csr(n), 0.25, compressor=B.Q_TOPK, k=k, order=order)
+    try:
+        for t in range(5):
+            det = pair.gossip_step()
+            pair.check(det, tag="ties step %d" % t)
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("comp", ["topk", "randk"])
+def test_select_when_one_digit_overflows_the_candidate_list(comp):
+    # every |v| equal and d far above the candidate capacity: the select has to finish by
+    # scanning the row itself
+    n, d, k = 3, 40000, 10
+    X0 = np.full((n, d), 1.5, dtype=np.float32)
+    X0[:, 1::3] = -1.5
+    kw = dict(COMPRESSORS[comp])
+    pair = Pair(X0, synth.ring_csr(n), 0.25, k=k, seed=2, **kw)
+    try:
+        det = pair.gossip_step()
+        pair.check(det, tag="overflow")
+        if comp == "topk":
+            assert np.array_equal(det["sel"], np.tile(np.arange(k), (n, 1)))
+            assert np.all(pair.gpu.last_scalars()[:, 3] == 2)   # row-scan mode was taken
+        det = pair.gossip_step()
+        pair.check(det, tag="overflow step 2")
+    finally:
+        pair.close()
+
+
+def test_guess_survives_a_sudden_change_of_scale():
+    # the first digit of the threshold jumps by many bins between steps in both directions
+    n, d, k = 4, 20000, 200
+    pair = Pair(synth.normal_state(n, d, seed=1), synth.ring_csr(n), 0.2, compressor=B.Q_TOPK, k=k)
+    try:
+        rng = np.random.default_rng(0)
+        for t, scale in enumerate([1.0, 1.0, 1e-4, 1e-4, 1e5, 1.0, 1.0]):
+            G = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+            pair.sgd_step(G, 1.0)
+            det = pair.gossip_step()
+            pair.check(det, tag="scale jump step %d" % t)
+    finally:
+        pair.close()
+
+
+def test_zero_state_and_zero_norm():
+    n, d = 4, 1000
+    for comp in ("sign", "qsgd16", "topk"):
+        kw = dict(COMPRESSORS[comp])
+        if comp == "topk":
+            kw["k"] = 10
+        pair = Pair(np.zeros((n, d), dtype=np.float32), synth.ring_csr(n), 0.3, **kw)
+        try:
+            for t in range(2):
+                det = pair.gossip_step()
+                pair.check(det, tag="zero %s" % comp)
+        finally:
+            pair.close()
+
+
+def test_sgd_and_momentum_steps_match():
+    import torch
+    from oracle import choco_ref as ref
+    n, d = 6, 12345
+    X0 = synth.normal_state(n, d, seed=2)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, compressor=B.Q_IDENTITY)
+    try:
+        rng = np.random.default_rng(1)
+        V = np.zeros_like(X0)
+        M = torch.zeros_like(pair.X)
+        for t in range(4):
+            G = rng.standard_normal((n, d)).astype(np.float32)
+            Gd = torch.zeros_like(pair.X)
+            Gd[:, :d] = torch.from_numpy(G).cuda()
+            pair.gpu.momentum_step(Gd, M, 0.05, 0.9, 1e-4)
+            pair.ref.momentum_step(V, G, 0.05, 0.9, 1e-4)
+            pair.gpu.sync()
+            assert np.array_equal(pair.X[:, :d].cpu().numpy(), pair.ref.X)
+            assert np.array_equal(M[:, :d].cpu().numpy(), V)
+            pair.sgd_step(G, 0.01)
+            pair.gpu.sync()
+            assert np.array_equal(pair.X[:, :d].cpu().numpy(), pair.ref.X)
+    finally:
+        pair.close()
+
+
+def test_metrics_match():
+    n, d = 9, 5000
+    pair = Pair(synth.normal_state(n, d, seed=4), synth.torus_csr(3, 3), 0.3, compressor=B.Q_SIGN)
+    try:
+        for _ in range(3):
+            pair.gossip_step()
+        g, r = pair.gpu.metrics(), pair.ref.metrics()
+        for key in ("consensus", "mean_norm", "psi"):
+            assert abs(g[key] - r[key]) <= 1e-10 * abs(r[key])
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
+def test_same_call_twice_is_bitwise_repeatable(comp):
+    import torch
+    n, d = 8, 30000
+    outs = []
+    for _ in range(2):
+        kw = dict(COMPRESSORS[comp])
+        if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+            kw["k"] = 300
+        X = torch.from_numpy(synth.normal_state(n, d, seed=8)).cuda().contiguous()
+        ctx = B.Choco(X, d, *synth.ring_csr(n), 0.3, seed=3, **kw)
+        for _ in range(5):
+            ctx.gossip_step()
+        ctx.sync()
+        outs.append((X.cpu().numpy().copy(), ctx.xhat().cpu().numpy().copy()))
+        ctx.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_resume_from_step_counter():
+    # random operators are keyed by (seed, t, worker, index): restoring (X, Xhat, S, t)
+    # continues a run exactly
+    import torch
+    n, d, k = 4, 5000, 50
+    topo = synth.ring_csr(n)
+    X = torch.from_numpy(synth.normal_state(n, d, seed=3)).cuda().contiguous()
+    a = B.Choco(X, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11)
+    for _ in range(3):
+        a.gossip_step()
+    a.sync()
+    X2 = X.clone()
+    b = B.Choco(X2, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11)
+    b.xhat().copy_(a.xhat())
+    b.nsum().copy_(a.nsum())
+    b.set_step(a.get_step())
+    for _ in range(2):
+        a.gossip_step()
+        b.gossip_step()
+    a.sync()
+    b.sync()
+    assert torch.equal(X, X2) and torch.equal(a.xhat(), b.xhat())
+    a.close()
+    b.close()
+
+
+def test_long_run_statistics_small_workload():
+    # the small BASELINE workload: ring of 8, d = 4096, top-1% (k = 41), gamma = 0.05,
+    # 200 gossip steps from distinct x_i; consensus error per step and the mean agree
+    # with the oracle to 1e-4 (free running)
+    n, d, k = 8, 4096, 41
+    pair = Pair(synth.normal_state(n, d, seed=20190709), synth.ring_csr(n), 0.05,
+                compressor=B.Q_TOPK, k=k)
+    try:
+        for t in range(200):
+            pair.gpu.gossip_step()
+            pair.ref.gossip_step()
+            if t % 20 == 19 or t == 0:
+                g, r = pair.gpu.metrics(), pair.ref.metrics()
+                assert abs(g["consensus"] - r["consensus"]) <= 1e-4 * r["consensus"]
+                assert abs(g["mean_norm"] - r["mean_norm"]) <= 1e-4 * r["mean_norm"]
+        X, Xhat, S = pair.gpu_state()
+        assert rel_l2(X, pair.ref.X) <= 1e-6
+    finally:
+        pair.close()
+
+
+def test_long_run_choco_sgd_sign_1000_steps():
+    # datacenter-shaped workload scaled down in d: ring of 8, sign, gamma = 0.4, lr = 0.1,
+    # shared x0 ~ N(0, 0.05^2), non-IID synthetic gradients, 1000 steps of (sgd, gossip)
+    n, d = 8, 2700
+    X0 = synth.normal_state(n, d, seed=7, std=0.05, shared=True)
+    pair = Pair(X0, synth.ring_csr(n), 0.4, compressor=B.Q_SIGN)
+    grads = synth.GradientStream(n, d, seed=8, noise_std=0.01, bias_std=0.001)
+    try:
+        for t in range(1000):
+            pair.sgd_step(grads.next(), 0.1)
+            pair.gpu.gossip_step()
+            pair.ref.gossip_step()
+        g, r = pair.gpu.metrics(), pair.ref.metrics()
+        assert abs(g["consensus"] - r["consensus"]) <= 1e-4 * r["consensus"]
+        assert abs(g["mean_norm"] - r["mean_norm"]) <= 1e-4 * r["mean_norm"]
+    finally:
+        pair.close()
