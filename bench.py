@@ -1,0 +1,286 @@
+#!/usr/bin/env python3
+"""Benchmark of the CHOCO-SGD iteration (local SGD step + CHOCO-Gossip step) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+
+One "step" is one pass of the whole hot path over all n workers: choco_sgd_step followed by
+choco_gossip_step (difference, statistic/select, encode, public-copy update, neighbour sums,
+mix).  Inputs are synthetic, seeded, generated on the device, and resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+The headline workload is the large-model shape (n = 8 ring, d = 28,000,000, top-k 0.1 %),
+the largest single-GPU configuration and the one where the HBM roofline is meaningful;
+--all adds short runs of the other shapes under "other_workloads".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+WORKLOADS = {
+    # name: shape and hyper-parameters of the synthetic stand-ins for the paper's workloads
+    "large_topk": dict(desc="large-model shape: n=8 ring, d=28,000,000 fp32, top-k 0.1% (k=28000), "
+                            "gamma=0.01, lr=0.05, gradients ~ N(0,0.01^2)",
+                       n=8, d=28_000_000, topo="ring", comp="topk", k=28_000, gamma=0.01, lr=0.05,
+                       bias_std=0.0),
+    "large_qsgd": dict(desc="large-model shape: n=8 ring, d=28,000,000 fp32, QSGD s=16 (biased), "
+                            "gamma=0.01, lr=0.05, gradients ~ N(0,0.01^2)",
+                       n=8, d=28_000_000, topo="ring", comp="qsgd", levels=16, gamma=0.01, lr=0.05,
+                       bias_std=0.0),
+    "dc_sign": dict(desc="datacenter shape: n=8 ring, d=270,000 fp32, scaled sign, gamma=0.4, lr=0.1, "
+                         "non-IID gradients",
+                    n=8, d=270_000, topo="ring", comp="sign", gamma=0.4, lr=0.1, bias_std=0.001),
+    "p2p_ring_topk": dict(desc="peer-to-peer shape: n=64 ring, d=270,000 fp32, top-k 1% (k=2700), "
+                               "gamma=0.02, lr=0.1",
+                          n=64, d=270_000, topo="ring", comp="topk", k=2700, gamma=0.02, lr=0.1,
+                          bias_std=0.001),
+    "p2p_torus_topk": dict(desc="peer-to-peer shape: n=64 8x8 torus, d=270,000 fp32, top-k 1%, "
+                                "gamma=0.02, lr=0.1",
+                           n=64, d=270_000, topo="torus", comp="topk", k=2700, gamma=0.02, lr=0.1,
+                           bias_std=0.001),
+    "p2p_ring_randk": dict(desc="peer-to-peer shape: n=64 ring, d=270,000 fp32, random-k 1%, "
+                                "gamma=0.02, lr=0.1",
+                           n=64, d=270_000, topo="ring", comp="randk", k=2700, gamma=0.02, lr=0.1,
+                           bias_std=0.001),
+    "p2p_torus_randk": dict(desc="peer-to-peer shape: n=64 8x8 torus, d=270,000 fp32, random-k 1%, "
+                                 "gamma=0.02, lr=0.1",
+                            n=64, d=270_000, topo="torus", comp="randk", k=2700, gamma=0.02, lr=0.1,
+                            bias_std=0.001),
+}
+
+# Algorithmic bytes each kernel must move per (worker, coordinate): every array it needs is
+# streamed once (reads + writes, fp32), xhat rows shared across neighbours through LDS.
+KERNEL_BYTES_PER_ELEM = {
+    "k_sgd": 12,              # read x, g; write x
+    "k_sel_compact": 8,       # read x, xhat (top-k); random-k reads nothing
+    "k_mix_incremental": 16,  # read x, s, xhat; write x
+    "k_dense_stat": 8,        # read x, xhat
+    "k_dense_apply_mix": 16,  # read x, xhat; write x, xhat
+    "k_tile_mix": 12,         # read x, xhat; write x
+    "k_dense_apply": 12,      # read x, xhat; write xhat
+    "k_mix_direct_global": 12,
+}
+
+
+def make_topology(w):
+    from paper_1907_09356_amd import synth
+    if w["topo"] == "ring":
+        return synth.ring_csr(w["n"])
+    side = int(round(w["n"] ** 0.5))
+    return synth.torus_csr(side, side)
+
+
+def comp_kwargs(w, B):
+    comp = {"topk": B.Q_TOPK, "randk": B.Q_RANDK, "sign": B.Q_SIGN, "qsgd": B.Q_QSGD}[w["comp"]]
+    kw = dict(compressor=comp)
+    if "k" in w:
+        kw["k"] = w["k"]
+    if "levels" in w:
+        kw["levels"] = w["levels"]
+    return kw
+
+
+def device_inputs(w, torch, seed=20190709):
+    """x0 ~ N(0, 0.05^2) shared by all workers; a pool of two gradient buffers
+    g = b_i + eps, eps ~ N(0, 0.01^2), b_i ~ N(0, bias_std^2) fixed per worker."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n, d = w["n"], w["d"]
+    ld = (d + 3) // 4 * 4
+    row = torch.randn(ld, generator=gen, device=dev, dtype=torch.float32) * 0.05
+    X = row.repeat(n, 1).contiguous()
+    pool = []
+    bias = None
+    if w["bias_std"] > 0:
+        bias = torch.randn((n, ld), generator=gen, device=dev, dtype=torch.float32) * w["bias_std"]
+    for _ in range(2):
+        g = torch.randn((n, ld), generator=gen, device=dev, dtype=torch.float32) * 0.01
+        if bias is not None:
+            g += bias
+        pool.append(g.contiguous())
+    return X, pool
+
+
+def run_gpu(w, steps, warmup, profile=True):
+    import torch
+    from paper_1907_09356_amd import binding as B
+    X, pool = device_inputs(w, torch)
+    ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **comp_kwargs(w, B))
+
+    def one_step(t):
+        ctx.sgd_step(pool[t & 1], w["lr"])
+        ctx.gossip_step()
+
+    for t in range(warmup):
+        one_step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        one_step(warmup + t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    out = dict(ms_per_step=1e3 * elapsed / steps, steps_per_s=steps / elapsed)
+
+    if profile:
+        # the same K steps again with every kernel bracketed by HIP events on its stream
+        ctx.set_profiling(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(steps):
+            one_step(warmup + steps + t)
+        torch.cuda.synchronize()
+        out["ms_per_step_profiled"] = 1e3 * (time.perf_counter() - t0) / steps
+        rep = ctx.profile_report()
+        ctx.set_profiling(False)
+        kernels = {}
+        elems = w["n"] * w["d"]
+        for name, (count, total_ms) in rep.items():
+            avg_ms = total_ms / count
+            entry = dict(launches_per_step=count / steps, avg_ms=avg_ms,
+                         ms_per_step=total_ms / steps)
+            bpe = KERNEL_BYTES_PER_ELEM.get(name)
+            if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
+                entry["alg_bytes_per_launch"] = bpe * elems
+                entry["alg_GBps"] = bpe * elems / (avg_ms * 1e-3) / 1e9
+            kernels[name] = entry
+        out["kernels"] = kernels
+    m = ctx.metrics()
+    out["consensus_error"] = m["consensus"]
+    out["mean_norm"] = m["mean_norm"]
+    ctx.close()
+    del ctx, X, pool
+    torch.cuda.empty_cache()
+    return out
+
+
+def step_bytes_per_elem(w, kernels):
+    """Algorithmic bytes of one whole step per (worker, coordinate)."""
+    total = 0.0
+    for name, e in kernels.items():
+        if "alg_bytes_per_launch" in e:
+            total += e["alg_bytes_per_launch"] * e["launches_per_step"]
+    return total / (w["n"] * w["d"])
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The oracle as it stands, one thread, on a bounded sample of the same workload: the
+    same n, topology, operator and hyper-parameters with d cut to d/10 (k cut alike)."""
+    import numpy as np
+    from oracle import choco_ref as ref
+    from paper_1907_09356_amd import synth
+    frac = 10 if w["d"] >= 1_000_000 else 1
+    d = w["d"] // frac
+    n = w["n"]
+    comp = {"topk": ref.TOPK, "randk": ref.RANDK, "sign": ref.SIGN, "qsgd": ref.QSGD}[w["comp"]]
+    kw = dict(compressor=comp)
+    if "k" in w:
+        kw["k"] = max(1, w["k"] // frac)
+    if "levels" in w:
+        kw["levels"] = w["levels"]
+    X0 = synth.normal_state(n, d, seed=1, std=0.05, shared=True)
+    st = ref.RefState(X0, *make_topology(w), gamma=w["gamma"], seed=7, **kw)
+    grads = synth.GradientStream(n, d, seed=2, noise_std=0.01, bias_std=w["bias_std"])
+    G = [grads.next(), grads.next()]
+    st.sgd_step(G[0], w["lr"])   # warm-up step (page in, first-touch)
+    st.gossip_step()
+    steps = 0
+    t0 = time.perf_counter()
+    while True:
+        st.sgd_step(G[steps & 1], w["lr"])
+        st.gossip_step()
+        steps += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or steps >= 20:
+            break
+    elem_rate = steps * n * d / el
+    return dict(value=elem_rate / (n * w["d"]), unit="steps/s", cores=1, kind="oracle",
+                element_updates_per_s=elem_rate,
+                sample="n=%d, d=%d (1/%d of the vector, k scaled alike), %d steps of sgd+gossip in "
+                       "%.1f s, single thread; value = measured element-updates/s divided by the "
+                       "full n*d" % (n, d, frac, steps, el))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="large_topk", choices=sorted(WORKLOADS))
+    ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all n workers live in one n x d array); "
+                 "--gpus N with N > 1 is not supported")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    w = WORKLOADS[args.workload]
+    res = run_gpu(w, args.steps, args.warmup)
+    elems = w["n"] * w["d"]
+    kernels = res["kernels"]
+    timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
+    dominant = max(timed, key=lambda k: timed[k]["ms_per_step"])
+    dk = timed[dominant]
+    roofline = dict(bound="hbm", kernel=dominant, achieved=dk["alg_GBps"], peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=dk["alg_GBps"] / HBM_PEAK_GBS,
+                    alg_bytes_per_launch=dk["alg_bytes_per_launch"], avg_launch_ms=dk["avg_ms"],
+                    traffic=None)
+    bpe = step_bytes_per_elem(w, kernels)
+    line = {
+        "metric": "choco_gossip_steps_per_s",
+        "value": res["steps_per_s"],
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w["desc"], "name": args.workload, "n": w["n"], "d": w["d"],
+                   "step": "choco_sgd_step + choco_gossip_step", "order": "compress_then_mix"},
+        "element_updates_per_s": res["steps_per_s"] * elems,
+        "step_alg_bytes_per_elem": bpe,
+        "step_alg_GBps": bpe * elems * res["steps_per_s"] / 1e9,
+        "step_frac_of_hbm_peak": bpe * elems * res["steps_per_s"] / 1e9 / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "kernels": {k: {kk: (round(vv, 6) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                    for k, v in kernels.items()},
+        "ms_per_step_profiled": res["ms_per_step_profiled"],
+        "consensus_error": res["consensus_error"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    if args.all:
+        others = []
+        for name, ow in WORKLOADS.items():
+            if name == args.workload:
+                continue
+            k = min(args.steps, 100)
+            r = run_gpu(ow, k, min(args.warmup, 10))
+            b = step_bytes_per_elem(ow, r["kernels"])
+            e = ow["n"] * ow["d"]
+            others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],
+                               steps_per_s=r["steps_per_s"],
+                               element_updates_per_s=r["steps_per_s"] * e,
+                               step_alg_bytes_per_elem=b,
+                               step_alg_GBps=b * e * r["steps_per_s"] / 1e9,
+                               kernels={kk: round(v["ms_per_step"], 6) for kk, v in r["kernels"].items()}))
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

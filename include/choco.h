@@ -141,6 +141,15 @@ int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
 int choco_get_step(choco_ctx *ctx, uint64_t *t_host);
 int choco_set_step(choco_ctx *ctx, uint64_t t);
 
+/* Per-kernel timing for measurement (off by default).  While enabled, every kernel the
+   library launches is bracketed by two HIP events recorded on the context's stream (at
+   most 16384 launches are kept; enabling clears earlier records).  choco_profile_report
+   synchronises, writes one text line "kernel_name launches total_milliseconds" per kernel
+   into buf_host (NUL-terminated; CHOCO_E_NOMEM if it does not fit) and clears the records.
+   The events themselves are host-side objects; no device memory is allocated. */
+int choco_set_profiling(choco_ctx *ctx, int enable);
+int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
+
 int choco_sync(choco_ctx *ctx);    /* hipStreamSynchronize on the context's stream */
 int choco_destroy(choco_ctx *ctx); /* frees host memory only; NULL is allowed      */
 const char *choco_strerror(int code);

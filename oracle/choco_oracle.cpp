@@ -81,46 +81,57 @@ uint32_t random_word(uint64_t seed, uint64_t t, int worker, int64_t e, int strea
 // Canonical fp64 sum of d non-negative terms.  The paper does not say how
 // ||v||_1 and ||v||_2 are accumulated; because the quantisation levels and
 // the sign scale depend on every bit of the norm, both sides of the parity
-// test use this fixed tree:
+// test use this fixed three-level tree:
 //   level 1: chunks of 256 consecutive terms; "lane" l (0..63) adds its four
 //            consecutive terms 4l..4l+3 left to right; the 64 lane sums are
 //            combined by halving: for off = 32,16,..,1: t[l] += t[l+off], l<off;
-//   level 2: 256 "lanes"; lane l adds chunk sums l, l+256, l+512, ... in that
+//   level 2: groups of 64 consecutive chunk sums (16384 terms), combined by the
+//            same halving from 32 to 1;
+//   level 3: 256 "lanes"; lane l adds group sums l, l+256, l+512, ... in that
 //            order; the 256 lane sums are combined by halving from 128 to 1.
-// Terms past d count as +0.0 (an exact no-op on non-negative sums).
+// Terms, chunks and groups past the end count as +0.0 (an exact no-op on
+// non-negative sums).
 // ---------------------------------------------------------------------------
 template <class Term>
 double canonical_sum(int64_t d, Term term) {
   const int64_t nchunks = (d + 255) / 256;
-  std::vector<double> chunk_sum((size_t)nchunks);
-  for (int64_t c = 0; c < nchunks; ++c) {
-    double lane[64];
-    for (int l = 0; l < 64; ++l) {
-      double acc = 0.0;
-      for (int m = 0; m < 4; ++m) {
-        const int64_t e = c * 256 + 4 * l + m;
-        const double a = (e < d) ? term(e) : 0.0;
-        acc = (m == 0) ? a : acc + a;
+  const int64_t ngroups = (nchunks + 63) / 64;
+  std::vector<double> group_sum((size_t)ngroups);
+  for (int64_t g = 0; g < ngroups; ++g) {
+    double chunk[64];
+    for (int k = 0; k < 64; ++k) {
+      const int64_t c = g * 64 + k;
+      double lane[64];
+      for (int l = 0; l < 64; ++l) {
+        double acc = 0.0;
+        for (int m = 0; m < 4; ++m) {
+          const int64_t e = c * 256 + 4 * l + m;
+          const double a = (e < d) ? term(e) : 0.0;
+          acc = (m == 0) ? a : acc + a;
+        }
+        lane[l] = acc;
       }
-      lane[l] = acc;
+      for (int off = 32; off >= 1; off >>= 1)
+        for (int l = 0; l < off; ++l) lane[l] = lane[l] + lane[l + off];
+      chunk[k] = lane[0];
     }
     for (int off = 32; off >= 1; off >>= 1)
-      for (int l = 0; l < off; ++l) lane[l] = lane[l] + lane[l + off];
-    chunk_sum[(size_t)c] = lane[0];
+      for (int k = 0; k < off; ++k) chunk[k] = chunk[k] + chunk[k + off];
+    group_sum[(size_t)g] = chunk[0];
   }
-  double lane2[256];
+  double lane3[256];
   for (int l = 0; l < 256; ++l) {
     double acc = 0.0;
     bool first = true;
-    for (int64_t c = l; c < nchunks; c += 256) {
-      acc = first ? chunk_sum[(size_t)c] : acc + chunk_sum[(size_t)c];
+    for (int64_t g = l; g < ngroups; g += 256) {
+      acc = first ? group_sum[(size_t)g] : acc + group_sum[(size_t)g];
       first = false;
     }
-    lane2[l] = acc;
+    lane3[l] = acc;
   }
   for (int off = 128; off >= 1; off >>= 1)
-    for (int l = 0; l < off; ++l) lane2[l] = lane2[l] + lane2[l + off];
-  return lane2[0];
+    for (int l = 0; l < off; ++l) lane3[l] = lane3[l] + lane3[l + off];
+  return lane3[0];
 }
 
 // ---------------------------------------------------------------------------

@@ -21,7 +21,8 @@ EXPORTS = [
     "choco_workspace_bytes", "choco_init", "choco_gossip_step", "choco_sgd_step",
     "choco_momentum_step", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
     "choco_set_capture", "choco_last_scalars", "choco_get_step", "choco_set_step", "choco_sync",
-    "choco_destroy", "choco_strerror", "choco_last_hip_error",
+    "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
+    "choco_profile_report",
 ]
 
 
@@ -81,6 +82,8 @@ def lib():
         L.choco_get_step.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.choco_set_step.argtypes = [vp, ctypes.c_uint64]
         L.choco_sync.argtypes = [vp]
+        L.choco_set_profiling.argtypes = [vp, ctypes.c_int]
+        L.choco_profile_report.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t]
         L.choco_destroy.argtypes = [vp]
         L.choco_strerror.argtypes = [ctypes.c_int]
         L.choco_strerror.restype = ctypes.c_char_p
@@ -234,3 +237,16 @@ class Choco:
 
     def sync(self):
         _check(lib().choco_sync(self.ctx), "choco_sync")
+
+    def set_profiling(self, on):
+        _check(lib().choco_set_profiling(self.ctx, 1 if on else 0), "choco_set_profiling")
+
+    def profile_report(self):
+        """{kernel name: (launches, total milliseconds)} since profiling was switched on."""
+        buf = ctypes.create_string_buffer(8192)
+        _check(lib().choco_profile_report(self.ctx, buf, len(buf)), "choco_profile_report")
+        out = {}
+        for line in buf.value.decode().splitlines():
+            name, count, ms = line.split()
+            out[name] = (int(count), float(ms))
+        return out

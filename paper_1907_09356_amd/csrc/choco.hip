@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -25,12 +26,18 @@ struct choco_ctx {
   bool sparse;            // top_a / random_a
   int mix_form;           // resolved: CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT
   int rpw;                // rows per wave of the tile kernels, 0 = tile does not fit
+  bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   uint64_t t;             // step counter
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
   int metrics_blocks;
   int last_hip_error;
   bool destroyed;
+  // optional per-kernel timing with HIP events on the context's stream
+  bool profiling;
+  std::vector<hipEvent_t> ev_begin, ev_end;
+  std::vector<int> ev_kernel;
+  size_t ev_used;
 };
 
 namespace {
@@ -42,11 +49,11 @@ constexpr int kMaxTileRows = 64;  // n * 1 KiB of LDS for the tile of all rows
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t xhat, s, row_ptr, col, w, ctl, partial, hist, cand, sel_idx, sel_val, bitmap, mpart, mout,
-      total;
-  uint32_t cand_cap;
+  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, bitmap,
+      mpart, mout, total;
+  uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
-  int32_t nchunks;
+  int32_t nchunks, ngroups;
 };
 
 bool is_sparse(int compressor) { return compressor == CHOCO_Q_TOPK || compressor == CHOCO_Q_RANDK; }
@@ -92,7 +99,12 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.w = take((size_t)nnz * sizeof(float));
   L.ctl = take((size_t)c.n * sizeof(WorkerCtl));
   L.nchunks = (int32_t)((c.d + kChunk - 1) / kChunk);
-  L.partial = take(sparse ? 0 : (size_t)c.n * (size_t)L.nchunks * sizeof(double));
+  L.ngroups = (L.nchunks + kGroup - 1) / kGroup;
+  const bool dense_stat = c.compressor == CHOCO_Q_SIGN || c.compressor == CHOCO_Q_QSGD;
+  // chunk sums are only materialised by the tile kernel of the printed order
+  L.chunk_sums = take(dense_stat && c.order == CHOCO_ORDER_MIX_THEN_COMPRESS
+                          ? (size_t)c.n * (size_t)L.nchunks * sizeof(double) : 0);
+  L.group_sums = take(dense_stat ? (size_t)c.n * (size_t)L.ngroups * sizeof(double) : 0);
   int64_t cap = 0;
   if (sparse) {
     cap = 4 * c.k;
@@ -101,9 +113,20 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
     if (cap > c.d) cap = c.d;
   }
   L.cand_cap = (uint32_t)cap;
+  // sub-lists: block b of a worker appends to sub-list b % kSegs; each gets twice its even
+  // share of the capacity, but never more than the blocks feeding it can produce
+  int64_t seg_cap = 0;
+  if (sparse) {
+    const int64_t per_block = 256 * kCompactVecs * 4;
+    const int64_t nblocks = (c.d + per_block - 1) / per_block;
+    const int64_t feeders = (nblocks + kSegs - 1) / kSegs;
+    seg_cap = std::max<int64_t>((2 * cap + kSegs - 1) / kSegs, 1024);
+    seg_cap = std::min<int64_t>(seg_cap, feeders * per_block);
+  }
+  L.seg_cap = (uint32_t)seg_cap;
   L.bitmap_words = sparse ? (c.d + 31) / 32 : 0;
-  L.hist = take(sparse ? (size_t)c.n * kBins * sizeof(uint32_t) : 0);
-  L.cand = take(sparse ? (size_t)c.n * (size_t)cap * sizeof(uint2) : 0);
+  L.hist16 = take(sparse ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
+  L.cand = take(sparse ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(float) : 0);
   L.bitmap = take(sparse ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
@@ -164,15 +187,51 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 
 #define LAUNCH_CHECK(ctx) HIP_TRY(ctx, hipGetLastError())
 
-// grid for the streaming kernels: enough blocks to fill 256 CUs several times
-// over, capped so that the grid-stride loops keep a few float4 per thread
-dim3 stream_grid(int32_t nvec, int32_t n) {
-  int64_t blocks = ((int64_t)nvec + 255) / 256;
-  int64_t cap = 16384 / n;
-  if (cap < 64) cap = 64;
-  if (blocks > cap) blocks = cap;
-  if (blocks < 1) blocks = 1;
-  return dim3((unsigned)blocks, (unsigned)n, 1);
+enum KernelId {
+  KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
+  KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_COUNT
+};
+const char* const kKernelNames[KID_COUNT] = {
+  "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
+  "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update"};
+constexpr size_t kMaxProfiledLaunches = 16384;
+
+// Brackets one launch with two events when profiling is on (no-op otherwise).
+struct Timed {
+  choco_ctx* ctx;
+  size_t slot;
+  bool on;
+  Timed(choco_ctx* c, int kid) : ctx(c), slot(0), on(false) {
+    if (!c->profiling || c->ev_used >= kMaxProfiledLaunches) return;
+    if (c->ev_used == c->ev_begin.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+      c->ev_begin.push_back(a);
+      c->ev_end.push_back(b);
+      c->ev_kernel.push_back(kid);
+    }
+    slot = c->ev_used++;
+    c->ev_kernel[slot] = kid;
+    on = hipEventRecord(c->ev_begin[slot], c->stream) == hipSuccess;
+  }
+  ~Timed() {
+    if (on) (void)hipEventRecord(ctx->ev_end[slot], ctx->stream);
+  }
+};
+// LAUNCH(ctx, kernel id, kernel, grid, block, dynamic LDS bytes, kernel arguments...)
+#define LAUNCH(ctx, kid, kernel, grid, block, lds, ...)                              \
+  do {                                                                               \
+    Timed timed_(ctx, kid);                                                          \
+    hipLaunchKernelGGL(kernel, grid, block, lds, (ctx)->stream, __VA_ARGS__);        \
+  } while (0)
+
+// One block per 256 * vecs consecutive 4-vectors of a row, one grid row per worker.
+dim3 chunk_grid(int32_t nvec, int32_t n, int vecs) {
+  const int64_t per_block = 256 * (int64_t)vecs;
+  return dim3((unsigned)(((int64_t)nvec + per_block - 1) / per_block), (unsigned)n, 1);
 }
 
 int pick_rpw(int n) {
@@ -185,135 +244,137 @@ int pick_rpw(int n) {
   return 16;
 }
 
-template <int COMP, bool CAPTURE>
+// Dispatch on the run-time rows-per-wave and the non-temporal flag.
+#define RPW_SWITCH(rpw, CALL)        \
+  switch (rpw) {                     \
+    case 1: CALL(1); break;          \
+    case 2: CALL(2); break;          \
+    case 4: CALL(4); break;          \
+    case 8: CALL(8); break;          \
+    default: CALL(16); break;        \
+  }
+
+template <int COMP, bool CAPTURE, bool NT>
 void launch_apply_mix(choco_ctx* ctx, const Args& A) {
   const dim3 grid((unsigned)A.nchunks), block(kTileThreads);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
-  switch (ctx->rpw) {
-    case 1: hipLaunchKernelGGL((k_dense_apply_mix<COMP, 1, CAPTURE>), grid, block, lds, ctx->stream, A); break;
-    case 2: hipLaunchKernelGGL((k_dense_apply_mix<COMP, 2, CAPTURE>), grid, block, lds, ctx->stream, A); break;
-    case 4: hipLaunchKernelGGL((k_dense_apply_mix<COMP, 4, CAPTURE>), grid, block, lds, ctx->stream, A); break;
-    case 8: hipLaunchKernelGGL((k_dense_apply_mix<COMP, 8, CAPTURE>), grid, block, lds, ctx->stream, A); break;
-    default: hipLaunchKernelGGL((k_dense_apply_mix<COMP, 16, CAPTURE>), grid, block, lds, ctx->stream, A); break;
-  }
+#define CALL(R) LAUNCH(ctx, KID_DENSE_APPLY_MIX, (k_dense_apply_mix<COMP, R, CAPTURE, NT>), grid, block, lds, A)
+  RPW_SWITCH(ctx->rpw, CALL)
+#undef CALL
 }
 
-template <int STAT>
+template <int STAT, bool NT>
 void launch_tile_mix(choco_ctx* ctx, const Args& A) {
   const dim3 grid((unsigned)A.nchunks), block(kTileThreads);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
-  switch (ctx->rpw) {
-    case 1: hipLaunchKernelGGL((k_tile_mix<STAT, 1>), grid, block, lds, ctx->stream, A); break;
-    case 2: hipLaunchKernelGGL((k_tile_mix<STAT, 2>), grid, block, lds, ctx->stream, A); break;
-    case 4: hipLaunchKernelGGL((k_tile_mix<STAT, 4>), grid, block, lds, ctx->stream, A); break;
-    case 8: hipLaunchKernelGGL((k_tile_mix<STAT, 8>), grid, block, lds, ctx->stream, A); break;
-    default: hipLaunchKernelGGL((k_tile_mix<STAT, 16>), grid, block, lds, ctx->stream, A); break;
-  }
+#define CALL(R) LAUNCH(ctx, KID_TILE_MIX, (k_tile_mix<STAT, R, NT>), grid, block, lds, A)
+  RPW_SWITCH(ctx->rpw, CALL)
+#undef CALL
 }
 
-template <int COMP>
-void launch_dense_apply(choco_ctx* ctx, const Args& A, dim3 grid) {
-  if (A.codes) hipLaunchKernelGGL((k_dense_apply<COMP, true>), grid, dim3(256), 0, ctx->stream, A);
-  else hipLaunchKernelGGL((k_dense_apply<COMP, false>), grid, dim3(256), 0, ctx->stream, A);
+template <int COMP, bool NT>
+void launch_dense_apply(choco_ctx* ctx, const Args& A) {
+  const dim3 grid = chunk_grid((A.d + 3) >> 2, A.n, kStreamVecs);
+  if (A.codes) LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, true, NT>), grid, dim3(256), 0, A);
+  else LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, false, NT>), grid, dim3(256), 0, A);
 }
 
-template <int COMP>
-void launch_apply_mix_cap(choco_ctx* ctx, const Args& A) {
-  if (A.codes) launch_apply_mix<COMP, true>(ctx, A);
-  else launch_apply_mix<COMP, false>(ctx, A);
+void launch_mix_direct_global(choco_ctx* ctx, const Args& A) {
+  LAUNCH(ctx, KID_MIX_DIRECT_GLOBAL, k_mix_direct_global, chunk_grid((A.d + 3) >> 2, A.n, 1), dim3(256), 0, A);
 }
 
 // Dense operators (identity, sign, gsgd), direct mix form.
-template <int COMP>
+template <int COMP, bool NT>
 int gossip_dense(choco_ctx* ctx) {
   const Args& A = ctx->args;
-  const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 sgrid = stream_grid(nvec, A.n);
-  const bool needs_stat = (COMP == Q_SIGN || COMP == Q_QSGD);
-  constexpr int STAT = (COMP == Q_SIGN || COMP == Q_QSGD) ? COMP : Q_NONE;
+  constexpr bool needs_stat = (COMP == Q_SIGN || COMP == Q_QSGD);
+  constexpr int STAT = needs_stat ? COMP : Q_NONE;
+  constexpr int STATK = needs_stat ? COMP : Q_SIGN;   // any valid instantiation where unused
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX) {
     if (needs_stat) {
-      int64_t blocks = ((int64_t)A.nchunks + 3) / 4;
-      int64_t cap = 32768 / A.n;
-      if (cap < 64) cap = 64;
-      if (blocks > cap) blocks = cap;
-      hipLaunchKernelGGL((k_dense_stat<STAT == Q_NONE ? Q_SIGN : STAT>), dim3((unsigned)blocks, (unsigned)A.n),
-                         dim3(256), 0, ctx->stream, A);
-      hipLaunchKernelGGL((k_dense_finalise<STAT == Q_NONE ? Q_SIGN : STAT>), dim3((unsigned)A.n), dim3(256), 0,
-                         ctx->stream, A);
+      LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
+             dim3(256), 0, A);
+      LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
     }
     if (ctx->rpw) {
-      launch_apply_mix_cap<COMP>(ctx, A);
+      if (A.codes) launch_apply_mix<COMP, true, NT>(ctx, A);
+      else launch_apply_mix<COMP, false, NT>(ctx, A);
     } else {
-      launch_dense_apply<COMP>(ctx, A, sgrid);
-      hipLaunchKernelGGL(k_mix_direct_global, sgrid, dim3(256), 0, ctx->stream, A);
+      launch_dense_apply<COMP, NT>(ctx, A);
+      launch_mix_direct_global(ctx, A);
     }
   } else {
     if (ctx->rpw) {
-      launch_tile_mix<STAT>(ctx, A);
+      launch_tile_mix<STAT, NT>(ctx, A);
+      if (needs_stat)
+        LAUNCH(ctx, KID_GROUP_REDUCE, k_group_reduce, dim3((unsigned)((A.ngroups + 3) / 4), (unsigned)A.n),
+               dim3(256), 0, A);
     } else {
-      hipLaunchKernelGGL(k_mix_direct_global, sgrid, dim3(256), 0, ctx->stream, A);
-      if (needs_stat) {
-        int64_t blocks = ((int64_t)A.nchunks + 3) / 4;
-        int64_t cap = 32768 / A.n;
-        if (cap < 64) cap = 64;
-        if (blocks > cap) blocks = cap;
-        hipLaunchKernelGGL((k_dense_stat<STAT == Q_NONE ? Q_SIGN : STAT>), dim3((unsigned)blocks, (unsigned)A.n),
-                           dim3(256), 0, ctx->stream, A);
-      }
+      launch_mix_direct_global(ctx, A);
+      if (needs_stat)
+        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
+               dim3(256), 0, A);
     }
     if (needs_stat)
-      hipLaunchKernelGGL((k_dense_finalise<STAT == Q_NONE ? Q_SIGN : STAT>), dim3((unsigned)A.n), dim3(256), 0,
-                         ctx->stream, A);
-    launch_dense_apply<COMP>(ctx, A, sgrid);
+      LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
+    launch_dense_apply<COMP, NT>(ctx, A);
   }
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;
 }
 
 // Sparsifying operators (top_a, random_a).
-template <int COMP>
+template <int COMP, bool NT>
 int gossip_sparse(choco_ctx* ctx) {
   const Args& A = ctx->args;
   const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 sgrid = stream_grid(nvec, A.n);
+  const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
+  const dim3 cgrid = chunk_grid(nvec, A.n, kCompactVecs);
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
-  bool mixed = false;
+  bool fuse_mix = false;
   if (mix_first) {
-    if (incremental && COMP == Q_TOPK) {
-      // fused below into the first select pass
-    } else if (incremental) {
-      hipLaunchKernelGGL(k_mix_incremental, sgrid, dim3(256), 0, ctx->stream, A);
-      mixed = true;
-    } else {
-      if (ctx->rpw) launch_tile_mix<Q_NONE>(ctx, A);
-      else hipLaunchKernelGGL(k_mix_direct_global, sgrid, dim3(256), 0, ctx->stream, A);
-      mixed = true;
-    }
+    if (incremental && COMP == Q_TOPK) fuse_mix = true;   // folded into the select pass below
+    else if (incremental) LAUNCH(ctx, KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0, A);
+    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A);
+    else launch_mix_direct_global(ctx, A);
   }
-  // select: histogram pass, digit 0, rebuild pass (no-op unless the guess failed), refine + emit
-  dim3 pgrid = sgrid;
-  if (mix_first && !mixed)
-    hipLaunchKernelGGL((k_sel_pass<COMP, true, COMP == Q_TOPK>), pgrid, dim3(256), 0, ctx->stream, A);
+  // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
+  if (fuse_mix)
+    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, A);
   else
-    hipLaunchKernelGGL((k_sel_pass<COMP, true, false>), pgrid, dim3(256), 0, ctx->stream, A);
-  hipLaunchKernelGGL(k_sel_final0, dim3((unsigned)A.n), dim3(256), 0, ctx->stream, A);
-  hipLaunchKernelGGL((k_sel_pass<COMP, false, false>), pgrid, dim3(256), 0, ctx->stream, A);
-  hipLaunchKernelGGL((k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), 0, ctx->stream, A);
+    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, false, NT>), cgrid, dim3(256), 0, A);
+  const int64_t sampled = ((int64_t)nvec + A.sample_stride - 1) / A.sample_stride;
+  const dim3 hgrid((unsigned)((sampled + 256 * kCompactVecs - 1) / (256 * kCompactVecs)), (unsigned)A.n);
+  LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), hgrid, dim3(256), 0, A);
+  LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+  LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_compact<COMP, true, false, false>), cgrid, dim3(256), 0, A);
+  LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
   if (incremental)
-    hipLaunchKernelGGL(k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0,
-                       ctx->stream, A);
-  hipLaunchKernelGGL(k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, ctx->stream, A);
+    LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256),
+           0, A);
+  LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
-    if (incremental) hipLaunchKernelGGL(k_mix_incremental, sgrid, dim3(256), 0, ctx->stream, A);
-    else if (ctx->rpw) launch_tile_mix<Q_NONE>(ctx, A);
-    else hipLaunchKernelGGL(k_mix_direct_global, sgrid, dim3(256), 0, ctx->stream, A);
+    if (incremental) LAUNCH(ctx, KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0, A);
+    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A);
+    else launch_mix_direct_global(ctx, A);
   }
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;
+}
+
+template <bool NT>
+int gossip_any(choco_ctx* ctx) {
+  switch (ctx->cfg.compressor) {
+    case CHOCO_Q_IDENTITY: return gossip_dense<Q_IDENTITY, NT>(ctx);
+    case CHOCO_Q_SIGN: return gossip_dense<Q_SIGN, NT>(ctx);
+    case CHOCO_Q_QSGD: return gossip_dense<Q_QSGD, NT>(ctx);
+    case CHOCO_Q_TOPK: return gossip_sparse<Q_TOPK, NT>(ctx);
+    case CHOCO_Q_RANDK: return gossip_sparse<Q_RANDK, NT>(ctx);
+    default: return CHOCO_E_INVAL;
+  }
 }
 
 }  // namespace
@@ -367,9 +428,14 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sparse = is_sparse(cfg->compressor);
   ctx->mix_form = resolve_mix_form(*cfg);
   ctx->rpw = pick_rpw(cfg->n);
+  // stream past the caches once one state array is larger than what they can keep between kernels
+  ctx->nt = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float) >= ((size_t)48 << 20);
+  if (const char* force = std::getenv("CHOCO_FORCE_NT")) ctx->nt = force[0] == '1';
   ctx->t = 0;
   ctx->last_hip_error = 0;
   ctx->destroyed = false;
+  ctx->profiling = false;
+  ctx->ev_used = 0;
 
   char* base = (char*)workspace_dev;
   Args& A = ctx->args;
@@ -385,8 +451,10 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.w = (const float*)(base + L.w);
   A.ctl = (WorkerCtl*)(base + L.ctl);
   A.gamma = cfg->gamma;
-  A.partial = (double*)(base + L.partial);
+  A.chunk_sums = (double*)(base + L.chunk_sums);
+  A.group_sums = (double*)(base + L.group_sums);
   A.nchunks = L.nchunks;
+  A.ngroups = L.ngroups;
   A.levels = cfg->levels;
   A.tau = 1.0;
   if (cfg->compressor == CHOCO_Q_QSGD && cfg->qsgd_biased) {
@@ -395,9 +463,43 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   }
   A.codes = nullptr;
   A.k = ctx->sparse ? cfg->k : 0;
-  A.hist = (uint32_t*)(base + L.hist);
+  A.hist16 = (uint32_t*)(base + L.hist16);
   A.cand = (uint2*)(base + L.cand);
   A.cand_cap = L.cand_cap;
+  A.seg_cap = L.seg_cap;
+  // candidates wanted beyond k so that the guess survives the step-to-step drift of
+  // the threshold (top_a) or the binomial spread of the count (random_a)
+  uint32_t guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
+  if (ctx->sparse) {
+    const double kk = (double)cfg->k, dd = (double)cfg->d;
+    double extra = std::max(0.5 * kk, 6.0 * std::sqrt(kk) + 32.0);
+    if (extra > 2147483647.0) extra = 2147483647.0;
+    A.extra = (uint32_t)extra;
+    if (cfg->compressor == CHOCO_Q_RANDK) {
+      // keys are uniform on [0, 2^32): the k + extra largest start near (1 - (k+extra)/d) 2^32
+      const double frac = std::min(1.0, (kk + extra) / dd);
+      const double g = (1.0 - frac) * 4294967296.0;
+      guess0 = g <= 0.0 ? 0u : (uint32_t)std::min(g, 4294967295.0);
+      const double d0 = std::min(extra / dd, 1.0) * 4294967296.0;
+      A.delta0 = (uint32_t)std::min(std::max(d0, 1.0), 4294967295.0);
+    } else {
+      A.delta0 = 1u << 19;   // about 6 % in magnitude
+    }
+    // top_a: the k entries kept in a step are absorbed by xhat and drop out, so the next
+    // step's k largest are (about) this step's ranks k+1..2k; random_a draws afresh
+    A.want = A.extra + (cfg->compressor == CHOCO_Q_TOPK ? (uint32_t)std::min<int64_t>(cfg->k, 2000000000) : 0u);
+    // fallback histogram: aim the rebuilt list at max(2k + extra, capacity / 4), at most
+    // half the capacity, and sample the row so that the aim is still >= ~2000 samples
+    double aim = std::max(2.0 * kk + extra, 0.25 * (double)L.cand_cap);
+    aim = std::min(aim, std::max(0.5 * (double)L.cand_cap, kk));
+    uint32_t stride = 1;
+    if (cfg->d > (1 << 21)) {
+      stride = 16;
+      while (stride > 1 && aim / stride < 2048.0) stride >>= 1;
+    }
+    A.sample_stride = stride;
+    A.sample_need = (uint32_t)std::max(1.0, std::ceil(aim / stride));
+  }
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
   A.bitmap = (uint32_t*)(base + L.bitmap);
@@ -425,7 +527,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   if (e == hipSuccess) {
     ctl0.resize((size_t)cfg->n);
     std::memset(ctl0.data(), 0, ctl0.size() * sizeof(WorkerCtl));
-    for (auto& c : ctl0) c.guess_bin = c.guess_next = (uint32_t)kBins;  // no guess yet
+    for (auto& c : ctl0) c.guess_key = guess0;
     e = hipMemcpyAsync(base + L.ctl, ctl0.data(), ctl0.size() * sizeof(WorkerCtl), hipMemcpyHostToDevice,
                        ctx->stream);
   }
@@ -444,15 +546,7 @@ int choco_gossip_step(choco_ctx* ctx) {
   Args& A = ctx->args;
   A.t_lo = (uint32_t)(ctx->t & 0xFFFFFFFFu);
   A.t_hi = (uint32_t)(ctx->t >> 32);
-  int rc;
-  switch (ctx->cfg.compressor) {
-    case CHOCO_Q_IDENTITY: rc = gossip_dense<Q_IDENTITY>(ctx); break;
-    case CHOCO_Q_SIGN: rc = gossip_dense<Q_SIGN>(ctx); break;
-    case CHOCO_Q_QSGD: rc = gossip_dense<Q_QSGD>(ctx); break;
-    case CHOCO_Q_TOPK: rc = gossip_sparse<Q_TOPK>(ctx); break;
-    case CHOCO_Q_RANDK: rc = gossip_sparse<Q_RANDK>(ctx); break;
-    default: rc = CHOCO_E_INVAL;
-  }
+  const int rc = ctx->nt ? gossip_any<true>(ctx) : gossip_any<false>(ctx);
   if (rc == CHOCO_OK) ctx->t += 1;
   return rc;
 }
@@ -461,7 +555,9 @@ int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
   if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
   const Args& A = ctx->args;
   const int32_t nvec = (A.d + 3) >> 2;
-  hipLaunchKernelGGL(k_sgd, stream_grid(nvec, A.n), dim3(256), 0, ctx->stream, A.X, g_dev, A.ld, nvec, lr);
+  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
+  if (ctx->nt) LAUNCH(ctx, KID_SGD, k_sgd<true>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
+  else LAUNCH(ctx, KID_SGD, k_sgd<false>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;
 }
@@ -472,8 +568,11 @@ int choco_momentum_step(choco_ctx* ctx, const float* g_dev, float* m_dev, float 
   if (((uintptr_t)g_dev & 15u) != 0 || ((uintptr_t)m_dev & 15u) != 0) return CHOCO_E_INVAL;
   const Args& A = ctx->args;
   const int32_t nvec = (A.d + 3) >> 2;
-  hipLaunchKernelGGL(k_momentum, stream_grid(nvec, A.n), dim3(256), 0, ctx->stream, A.X, g_dev, m_dev,
-                     A.ld, nvec, lr, beta, lambda);
+  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
+  if (ctx->nt)
+    LAUNCH(ctx, KID_MOMENTUM, k_momentum<true>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
+  else
+    LAUNCH(ctx, KID_MOMENTUM, k_momentum<false>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;
 }
@@ -549,7 +648,7 @@ int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
         o[0] = (double)(uint32_t)(c.kstar >> 32);
         o[1] = (double)(uint32_t)(~(uint32_t)(c.kstar & 0xFFFFFFFFu));
         o[2] = (double)c.kept;
-        o[3] = (double)c.mode;
+        o[3] = (double)c.mode;   // mode of the last step; fallbacks counts the histogram steps
         break;
       default: break;
     }
@@ -575,9 +674,42 @@ int choco_sync(choco_ctx* ctx) {
   return CHOCO_OK;
 }
 
+int choco_set_profiling(choco_ctx* ctx, int enable) {
+  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  ctx->profiling = enable != 0;
+  if (enable) ctx->ev_used = 0;
+  return CHOCO_OK;
+}
+
+int choco_profile_report(choco_ctx* ctx, char* buf_host, size_t buf_bytes) {
+  if (!ctx || ctx->destroyed || !buf_host || buf_bytes == 0) return CHOCO_E_INVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  double total_ms[KID_COUNT] = {0};
+  long count[KID_COUNT] = {0};
+  for (size_t e = 0; e < ctx->ev_used; ++e) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, ctx->ev_begin[e], ctx->ev_end[e]) != hipSuccess) continue;
+    total_ms[ctx->ev_kernel[e]] += (double)ms;
+    count[ctx->ev_kernel[e]] += 1;
+  }
+  size_t used = 0;
+  buf_host[0] = 0;
+  for (int k = 0; k < KID_COUNT; ++k) {
+    if (!count[k]) continue;
+    const int w = snprintf(buf_host + used, buf_bytes - used, "%s %ld %.6f\n", kKernelNames[k], count[k],
+                           total_ms[k]);
+    if (w < 0 || (size_t)w >= buf_bytes - used) return CHOCO_E_NOMEM;
+    used += (size_t)w;
+  }
+  ctx->ev_used = 0;
+  return CHOCO_OK;
+}
+
 int choco_destroy(choco_ctx* ctx) {
   if (!ctx) return CHOCO_OK;
   ctx->destroyed = true;
+  for (hipEvent_t e : ctx->ev_begin) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ctx->ev_end) (void)hipEventDestroy(e);
   delete ctx;
   return CHOCO_OK;
 }

@@ -2,14 +2,20 @@
 //
 // Layout: all arrays are n x ld fp32, row-major, one row per worker, ld a
 // multiple of 4 so every row starts 16-byte aligned and a lane can always load
-// a whole float4 (the pad columns d..ld-1 are read but never take part in a
+// a whole 4-vector (the pad columns d..ld-1 are read but never take part in a
 // norm, a histogram or a selection).
 //
+// Launch shape: the streaming kernels use one block per contiguous chunk (no
+// grid-stride loops) and, for states that do not fit in cache, non-temporal
+// loads and stores; on MI355X that shape measured 6.4 TB/s on a 3-read/1-write
+// stream against 4.9-5.3 TB/s for persistent grid-stride loops.
+//
 // Arithmetic rules shared with no other code: every fp32 product and sum is
-// rounded on its own (the file is compiled with -ffp-contract=off), neighbour
+// rounded on its own (compiled with -ffp-contract=off), neighbour
 // contributions are added in CSR order, norms are accumulated in fp64 over a
-// fixed tree (chunks of 256 consecutive entries, 4 per lane, 64-lane butterfly;
-// then 256 strided lanes over the chunk sums and a halving tree).
+// fixed three-level tree (chunks of 256 consecutive entries, 4 per lane and a
+// 64-lane butterfly; groups of 64 chunk sums, butterfly; 256 strided lanes over
+// the group sums and a halving tree).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -20,12 +26,20 @@ namespace choco {
 enum { Q_IDENTITY = 0, Q_TOPK = 1, Q_RANDK = 2, Q_SIGN = 3, Q_QSGD = 4, Q_NONE = 5 };
 enum { STREAM_RANDK = 1, STREAM_DITHER = 2 };
 
-constexpr int kBins = 2048;      // radix-select digits are at most 11 bits wide
-constexpr int kChunk = 256;      // entries per first-level norm chunk / tile width
-constexpr int kTileThreads = 256;
+typedef float vf4 __attribute__((ext_vector_type(4)));
+typedef int vi4 __attribute__((ext_vector_type(4)));
 
-// Per-worker control block in device memory (written by the small "finalise"
-// kernels, read by the streaming kernels; the host never reads it on the hot path).
+constexpr int kBins = 2048;       // radix-select digits are at most 11 bits wide
+constexpr int kBins16 = 65536;    // first digit of the fallback histogram (16 bits)
+constexpr int kChunk = 256;       // entries per first-level norm chunk / tile width
+constexpr int kGroup = 64;        // chunks per second-level group
+constexpr int kTileThreads = 256;
+constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kernels
+constexpr int kCompactVecs = 2;   // 4-vectors per thread in the select pass
+constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
+
+// Per-worker control block in device memory (written by small "finalise" code,
+// read by the streaming kernels; the host never reads it on the hot path).
 struct WorkerCtl {
   // norms and scales of the dense operators (Appendix C: sign, gsgd_b)
   double stat;        // ||v||_1 (sign) or sum v^2 (gsgd)
@@ -35,16 +49,12 @@ struct WorkerCtl {
   float scale_step;   // gsgd: ||v||_2 / (tau s)
   int32_t nonzero;    // gsgd: ||v||_2 > 0
   // radix select of the sparsifying operators (Appendix C: top_a, random_a)
-  uint32_t guess_bin;   // first-digit bins >= this are appended to the candidate list
-  uint32_t guess_next;  // guess for the next step
-  uint32_t b1;          // first digit of the k-th largest key
-  uint32_t need;        // how many keys to take from digit b1
+  uint32_t guess_key;   // entries with key32 >= this are appended to the candidate list
   uint32_t mode;        // 0: candidate list is complete, 1: rebuild it, 2: scan the row
-  uint32_t cand_count;  // append counter of the candidate list
+  uint32_t seg_count[kSegs];  // entries with key32 >= guess_key appended per sub-list (may exceed seg_cap)
   uint32_t kept;        // number of entries emitted by the last selection
-  uint32_t cnt_b1;      // entries whose first digit is b1
+  uint32_t fallbacks;   // how many steps needed the histogram fallback (diagnostic)
   uint64_t kstar;       // composite key of the k-th largest entry: kept <=> key >= kstar
-  uint64_t pad1;
 };
 
 struct Args {
@@ -60,16 +70,24 @@ struct Args {
   WorkerCtl* ctl;
   float gamma;
   // dense operators
-  double* partial;     // n x nchunks first-level chunk sums
+  double* chunk_sums;  // n x nchunks first-level sums (only the printed-order tile kernel writes them)
+  double* group_sums;  // n x ngroups second-level sums
   int32_t nchunks;
+  int32_t ngroups;
   int32_t levels;      // gsgd: s
   double tau;          // gsgd: 1 + min(d/s^2, sqrt(d)/s) or 1
   int32_t* codes;      // optional capture of the transmitted codes (n x ld)
   // sparse operators
   int64_t k;
-  uint32_t* hist;      // n x kBins
-  uint2* cand;         // n x cand_cap  (a, index)
-  uint32_t cand_cap;
+  uint32_t* hist16;    // n x kBins16 (fallback histogram)
+  uint2* cand;         // n x kSegs x seg_cap  (a, index)
+  uint32_t seg_cap;    // capacity of one sub-list
+  uint32_t cand_cap;   // largest total the fallback aims to stay under
+  uint32_t sample_stride;  // the fallback histogram looks at every sample_stride-th 4-vector
+  uint32_t sample_need;    // rank (within the sample) at which the fallback puts the guess
+  uint32_t want;       // entries the next guess should leave above it now: extra (+ k for top_a)
+  uint32_t extra;      // candidates wanted beyond k: max(k/2, 6 sqrt(k) + 32)
+  uint32_t delta0;     // default distance of the guess below the threshold key
   int32_t* sel_idx;    // n x k
   float* sel_val;      // n x k
   uint32_t* bitmap;    // n x bitmap_words: bit e of row j set <=> worker j kept entry e
@@ -79,6 +97,23 @@ struct Args {
   // randomness
   uint32_t seed_lo, seed_hi, t_lo, t_hi;
 };
+
+// ---------------------------------------------------------------------------
+// Memory helpers.  NT = non-temporal (streaming) access.
+// ---------------------------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ vf4 load4(const float* p) {
+  const vf4* q = reinterpret_cast<const vf4*>(p);
+  return NT ? __builtin_nontemporal_load(q) : *q;
+}
+template <bool NT>
+__device__ __forceinline__ void store4(float* p, vf4 v) {
+  vf4* q = reinterpret_cast<vf4*>(p);
+  if (NT) __builtin_nontemporal_store(v, q);
+  else *q = v;
+}
+__device__ __forceinline__ vf4 lds_load4(const float* p) { return *reinterpret_cast<const vf4*>(p); }
+__device__ __forceinline__ void lds_store4(float* p, vf4 v) { *reinterpret_cast<vf4*>(p) = v; }
 
 // ---------------------------------------------------------------------------
 // Philox4x32, 10 rounds (Salmon et al., SC'11): counter-based, so the word for
@@ -111,17 +146,8 @@ __device__ __forceinline__ uint4 random_words(const Args& A, int worker, uint32_
 __device__ __forceinline__ uint32_t pick(const uint4& v, int c) {
   return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w;
 }
-__device__ __forceinline__ float pick(const float4& v, int c) {
-  return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w;
-}
-__device__ __forceinline__ void put(float4& v, int c, float a) {
-  if (c == 0) v.x = a; else if (c == 1) v.y = a; else if (c == 2) v.z = a; else v.w = a;
-}
 
-__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ void store4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
-
-// 64-lane butterfly sum in fp64; lane 0 ends with the halving-tree result
+// 64-lane butterfly sum in fp64; every lane ends with the halving-tree result
 // t[l] += t[l+off] for off = 32,16,...,1 (the sum is commutative, so the xor
 // exchange builds exactly that tree in every lane).
 __device__ __forceinline__ double wave_tree_sum(double t) {
@@ -163,44 +189,77 @@ __device__ __forceinline__ float encode(float v, const RowScale<COMP>& sc, uint3
   return neg ? -mag : mag;
 }
 
+// xhat += Q(x - xhat) on one 4-vector (Algorithm 1 lines 3 and 6).
+template <int COMP>
+__device__ __forceinline__ vf4 absorb(const vf4& x, vf4 xh, const RowScale<COMP>& sc, const uint4& words,
+                                      vi4& code) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    int32_t cd;
+    const float v = x[c] - xh[c];
+    const float qv = encode<COMP>(v, sc, pick(words, c), cd);
+    xh[c] = xh[c] + qv;
+    code[c] = cd;
+  }
+  return xh;
+}
+
 // ---------------------------------------------------------------------------
 // Local updates (Algorithm 1 line 9; Algorithm 2 lines 9-10).
-// grid: (blocks over ld/4, n)
+// grid (ceil(nvec / (256 * kStreamVecs)), n)
 // ---------------------------------------------------------------------------
+template <bool NT>
 __global__ __launch_bounds__(256) void k_sgd(float* X, const float* G, int64_t ld, int32_t nvec, float lr) {
   const int64_t row = (int64_t)blockIdx.y * ld;
-  for (int m = blockIdx.x * 256 + threadIdx.x; m < nvec; m += gridDim.x * 256) {
-    float4 x = load4(X + row + 4 * (int64_t)m);
-    const float4 g = load4(G + row + 4 * (int64_t)m);
-    x.x = x.x - lr * g.x; x.y = x.y - lr * g.y; x.z = x.z - lr * g.z; x.w = x.w - lr * g.w;
-    store4(X + row + 4 * (int64_t)m, x);
+  const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
+  vf4 x[kStreamVecs], g[kStreamVecs];
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      x[u] = load4<NT>(X + row + 4 * (int64_t)m);
+      g[u] = load4<NT>(G + row + 4 * (int64_t)m);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[u][c] = x[u][c] - lr * g[u][c];
+      store4<NT>(X + row + 4 * (int64_t)m, x[u]);
+    }
   }
 }
 
+template <bool NT>
 __global__ __launch_bounds__(256) void k_momentum(float* X, const float* G, float* M, int64_t ld,
                                                   int32_t nvec, float lr, float beta, float lambda) {
   const int64_t row = (int64_t)blockIdx.y * ld;
-  for (int m = blockIdx.x * 256 + threadIdx.x; m < nvec; m += gridDim.x * 256) {
-    const int64_t o = row + 4 * (int64_t)m;
-    float4 x = load4(X + o);
-    const float4 g = load4(G + o);
-    float4 mo = load4(M + o);
+  const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float xc = pick(x, c);
-      const float gg = pick(g, c) + lambda * xc;
-      const float mn = gg + beta * pick(mo, c);
-      put(mo, c, mn);
-      put(x, c, xc - lr * mn);
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      const int64_t o = row + 4 * (int64_t)m;
+      vf4 x = load4<NT>(X + o);
+      const vf4 g = load4<NT>(G + o);
+      vf4 mo = load4<NT>(M + o);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float gg = g[c] + lambda * x[c];
+        const float mn = gg + beta * mo[c];
+        mo[c] = mn;
+        x[c] = x[c] - lr * mn;
+      }
+      store4<NT>(M + o, mo);
+      store4<NT>(X + o, x);
     }
-    store4(M + o, mo);
-    store4(X + o, x);
   }
 }
 
 // ---------------------------------------------------------------------------
-// Dense operators, statistic pass: chunk sums of |v| (sign) or v^2 (gsgd) with
-// v = x - xhat.  One wave per 256-entry chunk; grid (blocks, n), 4 waves/block.
+// Norm tree.
 // ---------------------------------------------------------------------------
 template <int COMP>
 __device__ __forceinline__ double norm_term(float v) {
@@ -208,58 +267,40 @@ __device__ __forceinline__ double norm_term(float v) {
   return COMP == Q_SIGN ? fabs(a) : a * a;
 }
 
+// ((t0 + t1) + t2) + t3 with entries past d counting as +0.0
 template <int COMP>
-__device__ __forceinline__ double lane_terms(const float4& v, int e, int d) {
-  // ((t0 + t1) + t2) + t3 with entries past d counting as +0.0
-  double acc = (e < d) ? norm_term<COMP>(v.x) : 0.0;
-  acc = acc + ((e + 1 < d) ? norm_term<COMP>(v.y) : 0.0);
-  acc = acc + ((e + 2 < d) ? norm_term<COMP>(v.z) : 0.0);
-  acc = acc + ((e + 3 < d) ? norm_term<COMP>(v.w) : 0.0);
+__device__ __forceinline__ double lane_terms(const vf4& v, int e, int d) {
+  double acc = (e < d) ? norm_term<COMP>(v[0]) : 0.0;
+  acc = acc + ((e + 1 < d) ? norm_term<COMP>(v[1]) : 0.0);
+  acc = acc + ((e + 2 < d) ? norm_term<COMP>(v[2]) : 0.0);
+  acc = acc + ((e + 3 < d) ? norm_term<COMP>(v[3]) : 0.0);
   return acc;
 }
 
-template <int COMP>
-__global__ __launch_bounds__(256) void k_dense_stat(Args A) {
-  const int i = blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const float* x = A.X + (int64_t)i * A.ld;
-  const float* xh = A.Xhat + (int64_t)i * A.ld;
-  double* partial = A.partial + (int64_t)i * A.nchunks;
-  for (int c = blockIdx.x * 4 + wave; c < A.nchunks; c += gridDim.x * 4) {
-    const int e = c * kChunk + lane * 4;
-    double t = 0.0;
-    if (e < A.d) {
-      const float4 a = load4(x + e), b = load4(xh + e);
-      float4 v;
-      v.x = a.x - b.x; v.y = a.y - b.y; v.z = a.z - b.z; v.w = a.w - b.w;
-      t = lane_terms<COMP>(v, e, A.d);
-    }
-    t = wave_tree_sum(t);
-    if (lane == 0) partial[c] = t;
-  }
-}
-
-// Second level of the norm tree and the per-worker scales.  grid n, block 256.
+// Third level of the tree over the group sums and the per-worker scales.
+// grid n, block 256.  (A separate launch on purpose: handing the group sums to a
+// "last block" of the producing kernel needs a device-scope fence per block,
+// which on this multi-die part writes back the L2 and cost 8x the pass itself.)
 template <int COMP>
 __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
-  __shared__ double t[256];
+  __shared__ double sh[256];
   const int i = blockIdx.x, l = threadIdx.x;
-  const double* partial = A.partial + (int64_t)i * A.nchunks;
+  const double* gs = A.group_sums + (int64_t)i * A.ngroups;
   double acc = 0.0;
   bool first = true;
-  for (int c = l; c < A.nchunks; c += 256) {
-    acc = first ? partial[c] : acc + partial[c];
+  for (int g = l; g < A.ngroups; g += 256) {
+    acc = first ? gs[g] : acc + gs[g];
     first = false;
   }
-  t[l] = acc;
+  sh[l] = acc;
   __syncthreads();
   for (int off = 128; off >= 1; off >>= 1) {
-    if (l < off) t[l] = t[l] + t[l + off];
+    if (l < off) sh[l] = sh[l] + sh[l + off];
     __syncthreads();
   }
   if (l == 0) {
     WorkerCtl* ctl = A.ctl + i;
-    const double total = t[0];
+    const double total = sh[0];
     ctl->stat = total;
     if (COMP == Q_SIGN) {
       ctl->nrm = 0.0;
@@ -275,6 +316,60 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
   }
 }
 
+// Dense operators, statistic pass (compress-then-mix order): v = x - xhat, one
+// block per group of 64 chunks (16384 entries), wave w takes chunks 16w..16w+15
+// four at a time.  grid (ngroups, n), block 256.
+template <int COMP, bool NT>
+__global__ __launch_bounds__(256) void k_dense_stat(Args A) {
+  __shared__ double cs[kGroup];
+  const int i = blockIdx.y, g = blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const float* x = A.X + (int64_t)i * A.ld;
+  const float* xh = A.Xhat + (int64_t)i * A.ld;
+  for (int it = 0; it < 16; it += 4) {
+    vf4 a[4], b[4];
+    int e[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = g * kGroup + 16 * wave + it + u;
+      e[u] = c < A.nchunks ? c * kChunk + lane * 4 : A.d;   // chunks past the end hold nothing
+      if (e[u] < A.d) {
+        a[u] = load4<NT>(x + e[u]);
+        b[u] = load4<NT>(xh + e[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      double t = 0.0;
+      if (e[u] < A.d) {
+        const vf4 v = a[u] - b[u];
+        t = lane_terms<COMP>(v, e[u], A.d);
+      }
+      t = wave_tree_sum(t);
+      if (lane == 0) cs[16 * wave + it + u] = t;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const double t = wave_tree_sum(cs[lane]);
+    if (lane == 0) A.group_sums[(int64_t)i * A.ngroups + g] = t;
+  }
+}
+
+// Second level from chunk sums already in memory (printed order: the tile kernel
+// below produces chunk sums).  One wave per group; grid (ceil(ngroups/4), n).
+__global__ __launch_bounds__(256) void k_group_reduce(Args A) {
+  const int i = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int g = blockIdx.x * 4 + wave;
+  if (g < A.ngroups) {
+    const int c = g * kGroup + lane;
+    double t = (c < A.nchunks) ? A.chunk_sums[(int64_t)i * A.nchunks + c] : 0.0;
+    t = wave_tree_sum(t);
+    if (lane == 0) A.group_sums[(int64_t)i * A.ngroups + g] = t;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Dense operators, fused apply + mix, compress-then-mix order, direct form.
 // One block owns a tile of 256 consecutive columns for ALL n rows, so every
@@ -285,198 +380,195 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
 // Wave w owns rows w, w+4, ...; RPW = rows per wave (compile-time bound, x stays
 // in registers between the phases).  Dynamic LDS: n * 256 floats.
 // ---------------------------------------------------------------------------
-template <int COMP, int RPW, bool CAPTURE>
+template <int RPW>
+__device__ __forceinline__ void tile_mix_rows(const Args& A, const float* tile, int wave, int lane,
+                                              bool valid, vf4 (&xr)[RPW]) {
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = wave + 4 * q;
+    if (r < A.n && valid) {
+      const vf4 me = lds_load4(tile + r * kChunk + lane * 4);
+      vf4 acc = {0.f, 0.f, 0.f, 0.f};
+      const int pend = A.row_ptr[r + 1];
+      for (int p = A.row_ptr[r]; p < pend; ++p) {
+        const float wj = A.w[p];
+        const vf4 o = lds_load4(tile + A.col[p] * kChunk + lane * 4);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = acc[c] + wj * (o[c] - me[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) xr[q][c] = xr[q][c] + A.gamma * acc[c];
+    }
+  }
+}
+
+template <int COMP, int RPW, bool CAPTURE, bool NT>
 __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
-  float4 xr[RPW];
-#pragma unroll
-  for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
-    if (r < A.n) {
-      float4 xh = make_float4(0.f, 0.f, 0.f, 0.f);
-      xr[q] = xh;
-      if (valid) {
-        const int64_t o = (int64_t)r * A.ld + e;
-        xr[q] = load4(A.X + o);
-        xh = load4(A.Xhat + o);
-        RowScale<COMP> sc;
-        sc.load(A.ctl + r);
-        uint4 words = make_uint4(0, 0, 0, 0);
-        if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
-        int32_t code[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float v = pick(xr[q], c) - pick(xh, c);
-          const float qv = encode<COMP>(v, sc, pick(words, c), code[c]);
-          put(xh, c, pick(xh, c) + qv);
-        }
-        store4(A.Xhat + o, xh);
-        if (CAPTURE) *reinterpret_cast<int4*>(A.codes + o) = make_int4(code[0], code[1], code[2], code[3]);
-      }
-      store4(tile + r * kChunk + lane * 4, xh);
-    }
-  }
-  __syncthreads();
+  vf4 xr[RPW], xh[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + 4 * q;
     if (r < A.n && valid) {
-      const float4 me = load4(tile + r * kChunk + lane * 4);
-      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      const int pend = A.row_ptr[r + 1];
-      for (int p = A.row_ptr[r]; p < pend; ++p) {
-        const float wj = A.w[p];
-        const float4 o = load4(tile + A.col[p] * kChunk + lane * 4);
-        acc.x = acc.x + wj * (o.x - me.x);
-        acc.y = acc.y + wj * (o.y - me.y);
-        acc.z = acc.z + wj * (o.z - me.z);
-        acc.w = acc.w + wj * (o.w - me.w);
-      }
-      float4 x = xr[q];
-      x.x = x.x + A.gamma * acc.x;
-      x.y = x.y + A.gamma * acc.y;
-      x.z = x.z + A.gamma * acc.z;
-      x.w = x.w + A.gamma * acc.w;
-      store4(A.X + (int64_t)r * A.ld + e, x);
+      const int64_t o = (int64_t)r * A.ld + e;
+      xr[q] = load4<NT>(A.X + o);
+      xh[q] = load4<NT>(A.Xhat + o);
     }
+  }
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = wave + 4 * q;
+    if (r < A.n) {
+      vf4 nh = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
+        const int64_t o = (int64_t)r * A.ld + e;
+        RowScale<COMP> sc;
+        sc.load(A.ctl + r);
+        uint4 words = make_uint4(0, 0, 0, 0);
+        if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
+        vi4 code;
+        nh = absorb<COMP>(xr[q], xh[q], sc, words, code);
+        store4<NT>(A.Xhat + o, nh);
+        if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
+      }
+      lds_store4(tile + r * kChunk + lane * 4, nh);
+    }
+  }
+  __syncthreads();
+  tile_mix_rows<RPW>(A, tile, wave, lane, valid, xr);
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = wave + 4 * q;
+    if (r < A.n && valid) store4<NT>(A.X + (int64_t)r * A.ld + e, xr[q]);
   }
 }
 
 // ---------------------------------------------------------------------------
 // Tile mix with the xhat that is in memory now (Algorithm 1 line 2, direct
-// form), optionally followed by the statistic of v = x_new - xhat for the
+// form), optionally followed by the chunk sums of v = x_new - xhat for the
 // printed order (mix, then compress).  Same tiling as above; the tile is one
 // first-level norm chunk, so the chunk sum falls out of one wave butterfly.
 // ---------------------------------------------------------------------------
-template <int STAT, int RPW>
+template <int STAT, int RPW, bool NT>
 __global__ __launch_bounds__(kTileThreads) void k_tile_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
-  float4 xr[RPW];
+  vf4 xr[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + 4 * q;
     if (r < A.n) {
-      float4 xh = make_float4(0.f, 0.f, 0.f, 0.f);
-      xr[q] = xh;
+      vf4 xh = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
         const int64_t o = (int64_t)r * A.ld + e;
-        xr[q] = load4(A.X + o);
-        xh = load4(A.Xhat + o);
+        xr[q] = load4<NT>(A.X + o);
+        xh = load4<NT>(A.Xhat + o);
       }
-      store4(tile + r * kChunk + lane * 4, xh);
+      lds_store4(tile + r * kChunk + lane * 4, xh);
     }
   }
   __syncthreads();
+  tile_mix_rows<RPW>(A, tile, wave, lane, valid, xr);
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + 4 * q;
     if (r < A.n) {
       double t = 0.0;
       if (valid) {
-        const float4 me = load4(tile + r * kChunk + lane * 4);
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        const int pend = A.row_ptr[r + 1];
-        for (int p = A.row_ptr[r]; p < pend; ++p) {
-          const float wj = A.w[p];
-          const float4 o = load4(tile + A.col[p] * kChunk + lane * 4);
-          acc.x = acc.x + wj * (o.x - me.x);
-          acc.y = acc.y + wj * (o.y - me.y);
-          acc.z = acc.z + wj * (o.z - me.z);
-          acc.w = acc.w + wj * (o.w - me.w);
-        }
-        float4 x = xr[q];
-        x.x = x.x + A.gamma * acc.x;
-        x.y = x.y + A.gamma * acc.y;
-        x.z = x.z + A.gamma * acc.z;
-        x.w = x.w + A.gamma * acc.w;
-        store4(A.X + (int64_t)r * A.ld + e, x);
+        store4<NT>(A.X + (int64_t)r * A.ld + e, xr[q]);
         if (STAT != Q_NONE) {
-          float4 v;
-          v.x = x.x - me.x; v.y = x.y - me.y; v.z = x.z - me.z; v.w = x.w - me.w;
+          const vf4 v = xr[q] - lds_load4(tile + r * kChunk + lane * 4);
           t = lane_terms<STAT>(v, e, A.d);
         }
       }
       if (STAT != Q_NONE) {
         t = wave_tree_sum(t);
-        if (lane == 0) A.partial[(int64_t)r * A.nchunks + blockIdx.x] = t;
+        if (lane == 0) A.chunk_sums[(int64_t)r * A.nchunks + blockIdx.x] = t;
       }
     }
   }
 }
 
 // Element-wise xhat += Q(x - xhat) (Algorithm 1 lines 3-6) with no mixing.
-// grid (blocks over ld/4, n)
-template <int COMP, bool CAPTURE>
+// grid (ceil(nvec / (256 * kStreamVecs)), n)
+template <int COMP, bool CAPTURE, bool NT>
 __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
   const int i = blockIdx.y;
   RowScale<COMP> sc;
   sc.load(A.ctl + i);
   const int nvec = (A.d + 3) >> 2;
-  for (int m = blockIdx.x * 256 + threadIdx.x; m < nvec; m += gridDim.x * 256) {
-    const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
-    const float4 x = load4(A.X + o);
-    float4 xh = load4(A.Xhat + o);
-    uint4 words = make_uint4(0, 0, 0, 0);
-    if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
-    int32_t code[4];
+  const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float v = pick(x, c) - pick(xh, c);
-      const float qv = encode<COMP>(v, sc, pick(words, c), code[c]);
-      put(xh, c, pick(xh, c) + qv);
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+      const vf4 x = load4<NT>(A.X + o);
+      const vf4 xh = load4<NT>(A.Xhat + o);
+      uint4 words = make_uint4(0, 0, 0, 0);
+      if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
+      vi4 code;
+      const vf4 nh = absorb<COMP>(x, xh, sc, words, code);
+      store4<NT>(A.Xhat + o, nh);
+      if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
     }
-    store4(A.Xhat + o, xh);
-    if (CAPTURE) *reinterpret_cast<int4*>(A.codes + o) = make_int4(code[0], code[1], code[2], code[3]);
   }
 }
 
 // Direct-form mix reading neighbour rows from global memory (any n; used when
-// the tile of all rows does not fit in LDS).  grid (blocks over ld/4, n)
+// the tile of all rows does not fit in LDS).  grid (ceil(nvec/256), n)
 __global__ __launch_bounds__(256) void k_mix_direct_global(Args A) {
   const int i = blockIdx.y;
   const int nvec = (A.d + 3) >> 2;
   const int pbeg = A.row_ptr[i], pend = A.row_ptr[i + 1];
-  for (int m = blockIdx.x * 256 + threadIdx.x; m < nvec; m += gridDim.x * 256) {
-    const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
-    const float4 me = load4(A.Xhat + o);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p = pbeg; p < pend; ++p) {
-      const float wj = A.w[p];
-      const float4 ot = load4(A.Xhat + (int64_t)A.col[p] * A.ld + 4 * (int64_t)m);
-      acc.x = acc.x + wj * (ot.x - me.x);
-      acc.y = acc.y + wj * (ot.y - me.y);
-      acc.z = acc.z + wj * (ot.z - me.z);
-      acc.w = acc.w + wj * (ot.w - me.w);
-    }
-    float4 x = load4(A.X + o);
-    x.x = x.x + A.gamma * acc.x;
-    x.y = x.y + A.gamma * acc.y;
-    x.z = x.z + A.gamma * acc.z;
-    x.w = x.w + A.gamma * acc.w;
-    store4(A.X + o, x);
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m >= nvec) return;
+  const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+  const vf4 me = load4<false>(A.Xhat + o);
+  vf4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int p = pbeg; p < pend; ++p) {
+    const float wj = A.w[p];
+    const vf4 ot = load4<false>(A.Xhat + (int64_t)A.col[p] * A.ld + 4 * (int64_t)m);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = acc[c] + wj * (ot[c] - me[c]);
   }
+  vf4 x = load4<false>(A.X + o);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) x[c] = x[c] + A.gamma * acc[c];
+  store4<false>(A.X + o, x);
 }
 
 // Incremental-form mix: x_i += gamma (S_i - xhat_i).  Pure streaming, 16 B/entry.
+// grid (ceil(nvec / (256 * kStreamVecs)), n)
+template <bool NT>
 __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
   const int i = blockIdx.y;
   const int nvec = (A.d + 3) >> 2;
-  for (int m = blockIdx.x * 256 + threadIdx.x; m < nvec; m += gridDim.x * 256) {
-    const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
-    float4 x = load4(A.X + o);
-    const float4 s = load4(A.S + o);
-    const float4 xh = load4(A.Xhat + o);
-    x.x = x.x + A.gamma * (s.x - xh.x);
-    x.y = x.y + A.gamma * (s.y - xh.y);
-    x.z = x.z + A.gamma * (s.z - xh.z);
-    x.w = x.w + A.gamma * (s.w - xh.w);
-    store4(A.X + o, x);
+  const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
+  vf4 x[kStreamVecs], s[kStreamVecs], xh[kStreamVecs];
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+      x[u] = load4<NT>(A.X + o);
+      s[u] = load4<NT>(A.S + o);
+      xh[u] = load4<NT>(A.Xhat + o);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[u][c] = x[u][c] + A.gamma * (s[u][c] - xh[u][c]);
+      store4<NT>(A.X + (int64_t)i * A.ld + 4 * (int64_t)m, x[u]);
+    }
   }
 }
 
@@ -488,23 +580,27 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
 //   random_a: key32 = ~word                  (k smallest words = k largest ~word)
 // All composites of a worker are distinct, so "the k largest K" is exactly the
 // selection rule (|v| descending, or word ascending; ties to the lower index).
-// The select finds kstar = the k-th largest K digit by digit; digit 0 (11 bits)
-// is histogrammed over the whole row, the remaining digits only over a short
-// candidate list of the entries whose digit 0 is >= a guess carried over from
-// the previous step (verified against the exact histogram every step).
+//
+// Fast path (every step): ONE pass over the row appends the entries with
+// key32 >= guess to a short candidate list; if the list holds at least k (and at
+// most its capacity) entries it contains the k largest, and the exact k-th
+// composite kstar is found by a radix select over the list alone.  The guess for
+// the next step is placed below this step's threshold so that about k + extra
+// entries qualify.  Fallback (first step, or when the distribution moved): a
+// 16-bit histogram of key32 over the row fixes a guess that is certainly low
+// enough, and the list is rebuilt; if even one 16-bit bucket overflows the list,
+// the select scans the row itself.  Either way the result is exact.
 // ---------------------------------------------------------------------------
 template <int COMP>
 struct Digits {
-  // shifts of the six digits inside the composite key, most significant first
+  // the six digits of the composite key, most significant first
   __device__ __forceinline__ static int shift(int level) {
-    if (COMP == Q_TOPK) { const int s[6] = {52, 41, 32, 21, 10, 0}; return s[level]; }
-    const int s[6] = {53, 42, 32, 21, 10, 0};
-    return s[level];
+    if (COMP == Q_TOPK) return level == 0 ? 52 : level == 1 ? 41 : level == 2 ? 32 : level == 3 ? 21 : level == 4 ? 10 : 0;
+    return level == 0 ? 53 : level == 1 ? 42 : level == 2 ? 32 : level == 3 ? 21 : level == 4 ? 10 : 0;
   }
   __device__ __forceinline__ static int bits(int level) {
-    if (COMP == Q_TOPK) { const int b[6] = {11, 11, 9, 11, 11, 10}; return b[level]; }
-    const int b[6] = {11, 11, 10, 11, 11, 10};
-    return b[level];
+    if (COMP == Q_TOPK) return level == 2 ? 9 : level == 5 ? 10 : 11;
+    return (level == 2 || level == 5) ? 10 : 11;
   }
   __device__ __forceinline__ static uint32_t key32(uint32_t a) {
     return COMP == Q_TOPK ? (a & 0x7fffffffu) : a;
@@ -512,101 +608,224 @@ struct Digits {
   __device__ __forceinline__ static uint64_t composite(uint32_t a, uint32_t idx) {
     return ((uint64_t)key32(a) << 32) | (uint64_t)(~idx);
   }
-  __device__ __forceinline__ static uint32_t bin0(uint32_t a) {
-    return COMP == Q_TOPK ? (key32(a) >> 20) : (a >> 21);
+  __device__ __forceinline__ static uint32_t bin16(uint32_t a) {
+    return COMP == Q_TOPK ? (key32(a) >> 15) : (a >> 16);
+  }
+  __device__ __forceinline__ static uint32_t bin16_floor(uint32_t bin) {   // smallest key32 in a bucket
+    return COMP == Q_TOPK ? (bin << 15) : (bin << 16);
   }
 };
 
-// Append (a, idx) of the lanes with pred set to a list, one atomic per wave.
-// Must be reached by all 64 lanes of the wave.
-__device__ __forceinline__ void wave_append(bool pred, uint32_t a, uint32_t idx, uint32_t* counter,
-                                            uint2* list, uint32_t cap) {
-  const uint64_t mask = __ballot(pred);
-  if (mask == 0) return;
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((unsigned long long)mask) - 1;
-  uint32_t base = 0;
-  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
-  base = __shfl(base, leader, 64);
-  if (pred) {
-    const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-    if (slot < cap) list[slot] = make_uint2(a, idx);
+// The candidate list of a worker holds the k largest entries iff at least k
+// entries qualified in total and no sub-list overflowed.
+__device__ __forceinline__ bool list_is_good(const WorkerCtl* ctl, const Args& A) {
+  uint64_t total = 0;
+  bool fits = true;
+#pragma unroll
+  for (int s = 0; s < kSegs; ++s) {
+    const uint32_t c = ctl->seg_count[s];
+    total += c;
+    fits = fits && (c <= A.seg_cap);
+  }
+  return fits && total >= (uint64_t)A.k;
+}
+
+// a[c] for the four entries of 4-vector m of worker i (raw bits of v for top_a,
+// complemented random word for random_a).  DO_MIX (top_a, printed order with
+// incremental sums): first x += gamma (S - xhat), stored, then v = x - xhat.
+template <int COMP, bool DO_MIX, bool NT>
+__device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t (&a)[4]) {
+  if (COMP == Q_TOPK) {
+    const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+    vf4 x = load4<NT>(A.X + o);
+    const vf4 xh = load4<NT>(A.Xhat + o);
+    if (DO_MIX) {
+      const vf4 s = load4<NT>(A.S + o);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[c] = x[c] + A.gamma * (s[c] - xh[c]);
+      store4<NT>(A.X + o, x);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) a[c] = __float_as_uint(x[c] - xh[c]);
+  } else {
+    const uint4 wds = random_words(A, i, (uint32_t)m, STREAM_RANDK);
+    a[0] = ~wds.x; a[1] = ~wds.y; a[2] = ~wds.z; a[3] = ~wds.w;
   }
 }
 
-// One pass over the rows.  HIST: count digit 0 of every entry (first pass of a
-// step, all workers).  !HIST: rebuild pass, only for workers whose guess failed.
-// DO_MIX (top_a, printed order): first x += gamma (S - xhat), then key x - xhat.
-// grid (blocks, n), block 256.
-template <int COMP, bool HIST, bool DO_MIX>
-__global__ __launch_bounds__(256) void k_sel_pass(Args A) {
-  __shared__ uint32_t h[HIST ? kBins : 1];
+// The one pass of the fast path (REBUILD = false, all workers) and the rebuild
+// pass of the fallback (REBUILD = true, only workers in mode 1).  Hits are
+// staged in LDS and flushed with one global atomic per block.
+// grid (ceil(nvec / (256 * kCompactVecs)), n), block 256.
+template <int COMP, bool REBUILD, bool DO_MIX, bool NT>
+__global__ __launch_bounds__(256) void k_sel_compact(Args A) {
+  __shared__ uint2 stage[256 * kCompactVecs * 4];
+  __shared__ uint32_t s_count, s_base;
   const int i = blockIdx.y;
   WorkerCtl* ctl = A.ctl + i;
-  if (!HIST && ctl->mode != 1u) return;
-  if (HIST) {
-    for (int b = threadIdx.x; b < kBins; b += 256) h[b] = 0;
-    __syncthreads();
-  }
-  const uint32_t guess = ctl->guess_bin;
-  uint2* cand = A.cand + (int64_t)i * A.cand_cap;
+  if (REBUILD && ctl->mode != 1u) return;
+  if (threadIdx.x == 0) s_count = 0;
+  __syncthreads();
+  const uint32_t guess = ctl->guess_key;
   const int nvec = (A.d + 3) >> 2;
-  for (int base = blockIdx.x * 256; base < nvec; base += gridDim.x * 256) {
-    const int m = base + threadIdx.x;
-    const bool valid = m < nvec;
-    const int e = 4 * m;
-    uint32_t a[4] = {0, 0, 0, 0};
-    if (COMP == Q_TOPK) {
-      if (valid) {
-        const int64_t o = (int64_t)i * A.ld + e;
-        float4 x = load4(A.X + o);
-        const float4 xh = load4(A.Xhat + o);
-        if (DO_MIX) {
-          const float4 s = load4(A.S + o);
-          x.x = x.x + A.gamma * (s.x - xh.x);
-          x.y = x.y + A.gamma * (s.y - xh.y);
-          x.z = x.z + A.gamma * (s.z - xh.z);
-          x.w = x.w + A.gamma * (s.w - xh.w);
-          store4(A.X + o, x);
-        }
-        a[0] = __float_as_uint(x.x - xh.x);
-        a[1] = __float_as_uint(x.y - xh.y);
-        a[2] = __float_as_uint(x.z - xh.z);
-        a[3] = __float_as_uint(x.w - xh.w);
-      }
-    } else {
-      if (valid) {
-        const uint4 wds = random_words(A, i, (uint32_t)m, STREAM_RANDK);
-        a[0] = ~wds.x; a[1] = ~wds.y; a[2] = ~wds.z; a[3] = ~wds.w;
-      }
-    }
-    bool pred[4];
-    bool any = false;
+  const int m0 = blockIdx.x * (256 * kCompactVecs) + threadIdx.x;
+  uint32_t a[kCompactVecs][4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool ok = valid && (e + c < A.d);
-      const uint32_t bin = Digits<COMP>::bin0(a[c]);
-      if (HIST && ok) atomicAdd(&h[bin], 1u);
-      pred[c] = ok && bin >= guess;
-      any = any || pred[c];
+  for (int u = 0; u < kCompactVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) entry_bits<COMP, DO_MIX, NT>(A, i, m, a[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kCompactVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int e = 4 * m + c;
+        if (e < A.d && Digits<COMP>::key32(a[u][c]) >= guess) {
+          const uint32_t slot = atomicAdd(&s_count, 1u);
+          stage[slot] = make_uint2(a[u][c], (uint32_t)e);
+        }
+      }
     }
-    if (__any(any)) {
+  }
+  __syncthreads();
+  const uint32_t count = s_count;
+  if (count == 0) return;
+  const int seg = blockIdx.x % kSegs;
+  if (threadIdx.x == 0) s_base = atomicAdd(&ctl->seg_count[seg], count);
+  __syncthreads();
+  const uint32_t base = s_base;
+  uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
+  for (uint32_t t = threadIdx.x; t < count; t += 256)
+    if (base + t < A.seg_cap) cand[base + t] = stage[t];
+}
+
+// Fallback, step 1: 16-bit histogram of key32 over a sample (every
+// sample_stride-th 4-vector; stride 1 = the whole row) of the rows whose list
+// is not good.  grid (ceil(ceil(nvec / stride) / (256 * kCompactVecs)), n)
+template <int COMP>
+__global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
+  const int i = blockIdx.y;
+  const WorkerCtl* ctl = A.ctl + i;
+  if (list_is_good(ctl, A)) return;
+  uint32_t* hist = A.hist16 + (int64_t)i * kBins16;
+  const int nvec = (A.d + 3) >> 2;
+  const int64_t j0 = (int64_t)blockIdx.x * (256 * kCompactVecs) + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < kCompactVecs; ++u) {
+    const int64_t m64 = (j0 + u * 256) * (int64_t)A.sample_stride;
+    if (m64 < nvec) {
+      const int m = (int)m64;
+      uint32_t a[4];
+      entry_bits<COMP, false, false>(A, i, m, a);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        wave_append(pred[c], a[c], (uint32_t)(e + c), &ctl->cand_count, cand, A.cand_cap);
+        if (4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
     }
-  }
-  if (HIST) {
-    __syncthreads();
-    uint32_t* hist = A.hist + (int64_t)i * kBins;
-    for (int b = threadIdx.x; b < kBins; b += 256)
-      if (h[b]) atomicAdd(&hist[b], h[b]);
   }
 }
 
-// Walk a 2048-bin histogram in LDS from the top and find the digit at which the
-// running count first reaches `need`.  Called by all threads of a block with
-// >= 256 threads; grp is 256 words of LDS scratch; results through LDS words.
+// Fallback, step 2: walk the (sampled) histogram from the top to the bucket at
+// which the count reaches sample_need and put the guess at its floor; with the
+// whole row histogrammed, also check that the rebuilt list will fit.  Sets the
+// mode of every worker for this step and clears the histogram it used.
+// grid n, block 1024.
+template <int COMP>
+__global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
+  __shared__ uint32_t part[1024];
+  __shared__ uint32_t s_grp, s_above;
+  const int i = blockIdx.x;
+  WorkerCtl* ctl = A.ctl + i;
+  if (list_is_good(ctl, A)) {
+    if (threadIdx.x == 0) ctl->mode = 0;
+    return;
+  }
+  uint32_t* hist = A.hist16 + (int64_t)i * kBins16;
+  const int t = threadIdx.x;
+  uint32_t mine[64];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int b = 0; b < 64; ++b) {
+    mine[b] = hist[64 * t + b];
+    hist[64 * t + b] = 0;
+    sum += mine[b];
+  }
+  part[t] = sum;
+  __syncthreads();
+  const uint64_t need = A.sample_need;
+  if (t == 0) {
+    uint32_t cum = 0;
+    int g = 1023;
+    for (; g > 0; --g) {
+      if ((uint64_t)cum + part[g] >= need) break;
+      cum += part[g];
+    }
+    s_grp = (uint32_t)g;
+    s_above = cum;
+  }
+  __syncthreads();
+  if ((uint32_t)t == s_grp) {
+    uint32_t cum = s_above;
+    int b = 63;
+    for (; b > 0; --b) {
+      if ((uint64_t)cum + mine[b] >= need) break;
+      cum += mine[b];
+    }
+    const uint32_t bin = 64u * (uint32_t)t + (uint32_t)b;
+    const uint64_t listed = (uint64_t)cum + (uint64_t)mine[b];   // sampled entries with key32 >= floor(bin)
+    ctl->guess_key = Digits<COMP>::bin16_floor(bin);
+    // an exact histogram knows whether the rebuilt list fits; a sampled one lets the
+    // rebuild find out (the select then scans the row if it does not)
+    ctl->mode = (A.sample_stride > 1u || listed <= (uint64_t)A.cand_cap) ? 1u : 2u;
+    ctl->fallbacks += 1;
+    if (ctl->mode == 1u)
+      for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
+  }
+}
+
+// Radix select over the candidate list (ROW = false) or, in the degenerate case
+// that one 16-bit bucket overflows the list, over the row itself (ROW = true);
+// emits the kept (index, value) pairs, marks them in the bitmap and places the
+// guess for the next step.  grid n, block 1024.
+template <int COMP>
+__device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint32_t& a, uint32_t& idx) {
+  idx = t;
+  if (COMP == Q_TOPK) {
+    const int64_t o = (int64_t)i * A.ld + t;
+    a = __float_as_uint(A.X[o] - A.Xhat[o]);
+  } else {
+    const uint4 wds = random_words(A, i, t >> 2, STREAM_RANDK);
+    a = ~pick(wds, (int)(t & 3u));
+  }
+}
+
+// Visit every entry of the domain (ROW: the whole row; else the candidate
+// sub-lists, lens[s] entries each) with f(a, idx).  All threads of the block
+// take part; the trip counts are uniform.
+template <int COMP, bool ROW, class F>
+__device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint32_t* lens, F f) {
+  if (ROW) {
+    for (uint32_t t = threadIdx.x; t < (uint32_t)A.d; t += blockDim.x) {
+      uint32_t a, idx;
+      row_entry<COMP>(A, i, t, a, idx);
+      f(a, idx);
+    }
+  } else {
+    for (int s = 0; s < kSegs; ++s) {
+      const uint2* cand = A.cand + ((int64_t)i * kSegs + s) * A.seg_cap;
+      const uint32_t len = lens[s];
+      for (uint32_t t = threadIdx.x; t < len; t += blockDim.x) {
+        const uint2 c = cand[t];
+        f(c.x, c.y);
+      }
+    }
+  }
+}
+
+// Walk a histogram of up to 2048 bins in LDS from the top and find the digit at
+// which the running count first reaches `need`.  All threads of a block with
+// >= 256 threads call it; grp is 256 words of LDS scratch.
 __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uint32_t need,
                                            uint32_t* out_digit, uint32_t* out_above) {
   const int t = threadIdx.x;
@@ -635,97 +854,26 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uin
   __syncthreads();
 }
 
-// Digit 0: find b1, decide whether the candidate list built with the old guess
-// is complete, set the next guess.  grid n, block 256.  Clears the histogram.
-__global__ __launch_bounds__(256) void k_sel_final0(Args A) {
-  __shared__ uint32_t h[kBins];
-  __shared__ uint32_t grp[256];
-  __shared__ uint32_t s_digit, s_above;
-  const int i = blockIdx.x;
-  WorkerCtl* ctl = A.ctl + i;
-  uint32_t* hist = A.hist + (int64_t)i * kBins;
-  for (int b = threadIdx.x; b < kBins; b += 256) {
-    h[b] = hist[b];
-    hist[b] = 0;
-  }
-  __syncthreads();
-  find_digit(h, grp, (uint32_t)A.k, &s_digit, &s_above);
-  if (threadIdx.x == 0) {
-    const uint32_t b1 = s_digit, above = s_above;
-    const uint32_t guess = ctl->guess_bin;
-    // exact number of entries the old guess put (or tried to put) on the list
-    uint64_t listed = 0;
-    for (uint32_t b = guess; b < (uint32_t)kBins; ++b) listed += h[b];
-    const bool ok = (guess <= b1) && (listed <= (uint64_t)A.cand_cap);
-    uint32_t mode = 0;
-    if (!ok) {
-      const uint64_t rebuilt = (uint64_t)above + (uint64_t)h[b1];
-      if (rebuilt <= (uint64_t)A.cand_cap) {
-        mode = 1;
-        ctl->guess_bin = b1;
-        ctl->cand_count = 0;
-      } else {
-        mode = 2;
-      }
-    }
-    // next step: one digit of slack below b1 if that list still fits
-    uint32_t next = b1;
-    if (b1 > 0) {
-      const uint64_t wide = (uint64_t)above + (uint64_t)h[b1] + (uint64_t)h[b1 - 1];
-      if (wide <= (uint64_t)A.cand_cap) next = b1 - 1;
-    }
-    ctl->guess_next = next;
-    ctl->b1 = b1;
-    ctl->cnt_b1 = h[b1];
-    ctl->need = (uint32_t)A.k - above;
-    ctl->mode = mode;
-  }
-}
-
-// Finish the select on the candidate list (or, in the degenerate case that the
-// list cannot hold digit b1, on the row itself), emit the kept (index, value)
-// pairs and mark them in the bitmap.  grid n, block 1024.
 template <int COMP, bool ROW>
-__device__ __forceinline__ void fetch_entry(const Args& A, int i, const uint2* cand, uint32_t t,
-                                            uint32_t& a, uint32_t& idx) {
-  if (!ROW) {
-    const uint2 c = cand[t];
-    a = c.x;
-    idx = c.y;
-  } else {
-    idx = t;
-    if (COMP == Q_TOPK) {
-      const int64_t o = (int64_t)i * A.ld + t;
-      a = __float_as_uint(A.X[o] - A.Xhat[o]);
-    } else {
-      const uint4 wds = random_words(A, i, t >> 2, STREAM_RANDK);
-      a = ~pick(wds, (int)(t & 3u));
-    }
-  }
-}
-
-template <int COMP, bool ROW>
-__device__ void refine_and_emit(const Args& A, int i, uint32_t count, uint32_t* h, uint32_t* grp,
-                                uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
+__device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint32_t total, uint32_t* h,
+                                uint32_t* grp, uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
                                 uint32_t* s_above, uint32_t* s_emit) {
   WorkerCtl* ctl = A.ctl + i;
-  const uint2* cand = A.cand + (int64_t)i * A.cand_cap;
-  int last = 0;  // last digit that has been resolved
-  // digit 0 is known; if all of digit b1 is needed there is nothing to refine
-  bool done = (ctl->cnt_b1 == *s_need);
-  for (int level = 1; level < 6 && !done; ++level) {
+  int last = 0;
+  bool done = false;
+  for (int level = 0; level < 6 && !done; ++level) {
     for (int b = threadIdx.x; b < kBins; b += blockDim.x) h[b] = 0;
     __syncthreads();
     const uint64_t prefix = *s_prefix;
-    const int sprev = Digits<COMP>::shift(level - 1);
     const int scur = Digits<COMP>::shift(level);
+    const int sprev = level > 0 ? Digits<COMP>::shift(level - 1) : 63;
     const uint32_t mask = (1u << Digits<COMP>::bits(level)) - 1u;
-    for (uint32_t t = threadIdx.x; t < count; t += blockDim.x) {
-      uint32_t a, idx;
-      fetch_entry<COMP, ROW>(A, i, cand, t, a, idx);
+    for_each_entry<COMP, ROW>(A, i, lens, [&](uint32_t a, uint32_t idx) {
       const uint64_t K = Digits<COMP>::composite(a, idx);
-      if ((K >> sprev) == prefix) atomicAdd(&h[(uint32_t)(K >> scur) & mask], 1u);
-    }
+      // level 0: every entry takes part (nothing of the composite lies above digit 0)
+      const bool match = level == 0 ? true : ((K >> sprev) == prefix);
+      if (match) atomicAdd(&h[(uint32_t)(K >> scur) & mask], 1u);
+    });
     __syncthreads();
     find_digit(h, grp, *s_need, s_digit, s_above);
     const uint32_t digit = *s_digit, above = *s_above;
@@ -733,7 +881,7 @@ __device__ void refine_and_emit(const Args& A, int i, uint32_t count, uint32_t* 
     const uint32_t need = *s_need - above;
     __syncthreads();
     if (threadIdx.x == 0) {
-      *s_prefix = (prefix << Digits<COMP>::bits(level)) | (uint64_t)digit;
+      *s_prefix = (level == 0 ? 0ull : (prefix << Digits<COMP>::bits(level))) | (uint64_t)digit;
       *s_need = need;
     }
     last = level;
@@ -745,46 +893,40 @@ __device__ void refine_and_emit(const Args& A, int i, uint32_t count, uint32_t* 
   int32_t* sel_idx = A.sel_idx + (int64_t)i * A.k;
   float* sel_val = A.sel_val + (int64_t)i * A.k;
   uint32_t* bitmap = A.bitmap + (int64_t)i * A.bitmap_words;
-  const uint32_t rounds = (count + blockDim.x - 1) / blockDim.x;
-  for (uint32_t rd = 0; rd < rounds; ++rd) {
-    const uint32_t t = rd * blockDim.x + threadIdx.x;
-    uint32_t a = 0, idx = 0;
-    bool keep = false;
-    if (t < count) {
-      fetch_entry<COMP, ROW>(A, i, cand, t, a, idx);
-      keep = Digits<COMP>::composite(a, idx) >= kstar;
-    }
-    const uint64_t mask = __ballot(keep);
-    if (mask != 0) {
-      const int lane = threadIdx.x & 63;
-      const int leader = __ffsll((unsigned long long)mask) - 1;
-      uint32_t base = 0;
-      if (lane == leader) base = atomicAdd(s_emit, (uint32_t)__popcll(mask));
-      base = __shfl(base, leader, 64);
-      if (keep) {
-        const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (slot < (uint32_t)A.k) {
-          float val;
-          if (COMP == Q_TOPK) {
-            val = __uint_as_float(a);
-          } else {
-            const int64_t o = (int64_t)i * A.ld + idx;
-            val = A.X[o] - A.Xhat[o];
-            if (A.randk_rescale) val = A.randk_scale * val;
-          }
-          sel_idx[slot] = (int32_t)idx;
-          sel_val[slot] = val;
-          atomicOr(&bitmap[idx >> 5], 1u << (idx & 31u));
+  for_each_entry<COMP, ROW>(A, i, lens, [&](uint32_t a, uint32_t idx) {
+    if (Digits<COMP>::composite(a, idx) >= kstar) {
+      const uint32_t slot = atomicAdd(s_emit, 1u);
+      if (slot < (uint32_t)A.k) {
+        float val;
+        if (COMP == Q_TOPK) {
+          val = __uint_as_float(a);
+        } else {
+          const int64_t o = (int64_t)i * A.ld + idx;
+          val = A.X[o] - A.Xhat[o];
+          if (A.randk_rescale) val = A.randk_scale * val;
         }
+        sel_idx[slot] = (int32_t)idx;
+        sel_val[slot] = val;
+        atomicOr(&bitmap[idx >> 5], 1u << (idx & 31u));
       }
     }
-  }
+  });
   __syncthreads();
   if (threadIdx.x == 0) {
+    // next guess: below this step's threshold key by the distance that, at the key
+    // density seen between the old guess and the threshold, holds `want` entries
+    // (for top_a the k entries kept now leave the race, so want includes k)
+    const uint32_t T = (uint32_t)(kstar >> 32);
+    const uint32_t G = ctl->guess_key;
+    uint64_t delta = A.delta0;
+    if (!ROW && total > (uint32_t)A.k && T > G)
+      delta = (uint64_t)(T - G) * (uint64_t)A.want / (uint64_t)(total - (uint32_t)A.k);
+    if (delta < 1) delta = 1;
+    ctl->guess_key = delta >= (uint64_t)T ? 0u : T - (uint32_t)delta;
     ctl->kstar = kstar;
     ctl->kept = *s_emit;
-    ctl->cand_count = 0;
-    ctl->guess_bin = ctl->guess_next;
+    ctl->mode = ROW ? 2u : ctl->mode;
+    for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
   }
 }
 
@@ -792,25 +934,29 @@ template <int COMP>
 __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t grp[256];
+  __shared__ uint32_t lens[kSegs];
   __shared__ uint64_t s_prefix;
-  __shared__ uint32_t s_need, s_digit, s_above, s_emit;
+  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good;
   const int i = blockIdx.x;
   WorkerCtl* ctl = A.ctl + i;
-  const uint32_t mode = ctl->mode;
   if (threadIdx.x == 0) {
-    s_prefix = ctl->b1;
-    s_need = ctl->need;
+    s_prefix = 0;
+    s_need = (uint32_t)A.k;
     s_emit = 0;
+    s_good = list_is_good(ctl, A) ? 1u : 0u;
+    uint32_t total = 0;
+    for (int s = 0; s < kSegs; ++s) {
+      const uint32_t c = ctl->seg_count[s];
+      lens[s] = c < A.seg_cap ? c : A.seg_cap;
+      total += lens[s];
+    }
+    s_total = total;
   }
   __syncthreads();
-  if (mode == 2u) {
-    refine_and_emit<COMP, true>(A, i, (uint32_t)A.d, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
-  } else {
-    uint32_t count = ctl->cand_count;
-    if (count > A.cand_cap) count = A.cand_cap;
-    __syncthreads();
-    refine_and_emit<COMP, false>(A, i, count, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
-  }
+  if (!s_good)
+    refine_and_emit<COMP, true>(A, i, lens, s_total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+  else
+    refine_and_emit<COMP, false>(A, i, lens, s_total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
 }
 
 // S_i[e] += sum_p w_p q_j[e] over the neighbours j = col[p] that kept entry e,
