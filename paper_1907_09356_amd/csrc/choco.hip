@@ -49,10 +49,9 @@ constexpr int kMaxTileRows = 64;  // n * 1 KiB of LDS for the tile of all rows
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, bitmap,
+  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, keptmap,
       mpart, mout, total;
   uint32_t cand_cap, seg_cap;
-  int64_t bitmap_words;
   int32_t nchunks, ngroups;
 };
 
@@ -124,12 +123,11 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
     seg_cap = std::min<int64_t>(seg_cap, feeders * per_block);
   }
   L.seg_cap = (uint32_t)seg_cap;
-  L.bitmap_words = sparse ? (c.d + 31) / 32 : 0;
   L.hist16 = take(sparse ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
   L.cand = take(sparse ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(float) : 0);
-  L.bitmap = take(sparse ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
+  L.keptmap = take(sparse ? (size_t)c.n * (size_t)ld : 0);
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -293,7 +291,7 @@ int gossip_dense(choco_ctx* ctx) {
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX) {
     if (needs_stat) {
       LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
-             dim3(256), 0, A);
+             dim3(kStatThreads), 0, A);
       LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
     }
     if (ctx->rpw) {
@@ -313,7 +311,7 @@ int gossip_dense(choco_ctx* ctx) {
       launch_mix_direct_global(ctx, A);
       if (needs_stat)
         LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
-               dim3(256), 0, A);
+               dim3(kStatThreads), 0, A);
     }
     if (needs_stat)
       LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
@@ -341,14 +339,13 @@ int gossip_sparse(choco_ctx* ctx) {
   }
   // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
   if (fuse_mix)
-    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, A);
+    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, A);
   else
-    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, false, NT>), cgrid, dim3(256), 0, A);
-  const int64_t sampled = ((int64_t)nvec + A.sample_stride - 1) / A.sample_stride;
-  const dim3 hgrid((unsigned)((sampled + 256 * kCompactVecs - 1) / (256 * kCompactVecs)), (unsigned)A.n);
-  LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), hgrid, dim3(256), 0, A);
+    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, NT>), cgrid, dim3(256), 0, A);
+  const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
+  LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
   LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-  LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_compact<COMP, true, false, false>), cgrid, dim3(256), 0, A);
+  LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
   LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
@@ -470,6 +467,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   // candidates wanted beyond k so that the guess survives the step-to-step drift of
   // the threshold (top_a) or the binomial spread of the count (random_a)
   uint32_t guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
+  uint32_t shift0 = 0;
   if (ctx->sparse) {
     const double kk = (double)cfg->k, dd = (double)cfg->d;
     double extra = std::max(0.5 * kk, 6.0 * std::sqrt(kk) + 32.0);
@@ -480,6 +478,9 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
       const double frac = std::min(1.0, (kk + extra) / dd);
       const double g = (1.0 - frac) * 4294967296.0;
       guess0 = g <= 0.0 ? 0u : (uint32_t)std::min(g, 4294967295.0);
+      // 2048 candidate bins over the keys above the guess
+      const uint64_t range = 4294967296ull - (uint64_t)guess0;
+      while ((range >> shift0) > (uint64_t)kBins) ++shift0;
       const double d0 = std::min(extra / dd, 1.0) * 4294967296.0;
       A.delta0 = (uint32_t)std::min(std::max(d0, 1.0), 4294967295.0);
     } else {
@@ -502,8 +503,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   }
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
-  A.bitmap = (uint32_t*)(base + L.bitmap);
-  A.bitmap_words = L.bitmap_words;
+  A.keptmap = (uint8_t*)(base + L.keptmap);
   A.randk_rescale = cfg->randk_rescale ? 1 : 0;
   A.randk_scale = ctx->sparse ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
@@ -527,7 +527,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   if (e == hipSuccess) {
     ctl0.resize((size_t)cfg->n);
     std::memset(ctl0.data(), 0, ctl0.size() * sizeof(WorkerCtl));
-    for (auto& c : ctl0) c.guess_key = guess0;
+    for (auto& c : ctl0) { c.guess_key = guess0; c.bin_shift = shift0; }
     e = hipMemcpyAsync(base + L.ctl, ctl0.data(), ctl0.size() * sizeof(WorkerCtl), hipMemcpyHostToDevice,
                        ctx->stream);
   }

@@ -35,7 +35,11 @@ constexpr int kChunk = 256;       // entries per first-level norm chunk / tile w
 constexpr int kGroup = 64;        // chunks per second-level group
 constexpr int kTileThreads = 256;
 constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kernels
-constexpr int kCompactVecs = 2;   // 4-vectors per thread in the select pass
+constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass
+constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
+constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
+constexpr int kStatThreads = 1024;  // one wave per 4 chunks of a 64-chunk group
+constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
 
 // Per-worker control block in device memory (written by small "finalise" code,
@@ -50,6 +54,7 @@ struct WorkerCtl {
   int32_t nonzero;    // gsgd: ||v||_2 > 0
   // radix select of the sparsifying operators (Appendix C: top_a, random_a)
   uint32_t guess_key;   // entries with key32 >= this are appended to the candidate list
+  uint32_t bin_shift;   // the select bins candidates by min((key32 - guess_key) >> bin_shift, 2047)
   uint32_t mode;        // 0: candidate list is complete, 1: rebuild it, 2: scan the row
   uint32_t seg_count[kSegs];  // entries with key32 >= guess_key appended per sub-list (may exceed seg_cap)
   uint32_t kept;        // number of entries emitted by the last selection
@@ -90,8 +95,7 @@ struct Args {
   uint32_t delta0;     // default distance of the guess below the threshold key
   int32_t* sel_idx;    // n x k
   float* sel_val;      // n x k
-  uint32_t* bitmap;    // n x bitmap_words: bit e of row j set <=> worker j kept entry e
-  int64_t bitmap_words;
+  uint8_t* keptmap;    // n x ld bytes: byte e of row j non-zero <=> worker j kept entry e this step
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
   // randomness
@@ -317,37 +321,35 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
 }
 
 // Dense operators, statistic pass (compress-then-mix order): v = x - xhat, one
-// block per group of 64 chunks (16384 entries), wave w takes chunks 16w..16w+15
-// four at a time.  grid (ngroups, n), block 256.
+// block per group of 64 chunks (16384 entries), one wave per 4 chunks, all four
+// in flight at once.  grid (ngroups, n), block 1024.
 template <int COMP, bool NT>
-__global__ __launch_bounds__(256) void k_dense_stat(Args A) {
+__global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   __shared__ double cs[kGroup];
   const int i = blockIdx.y, g = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const float* x = A.X + (int64_t)i * A.ld;
   const float* xh = A.Xhat + (int64_t)i * A.ld;
-  for (int it = 0; it < 16; it += 4) {
-    vf4 a[4], b[4];
-    int e[4];
+  vf4 a[4], b[4];
+  int e[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int c = g * kGroup + 16 * wave + it + u;
-      e[u] = c < A.nchunks ? c * kChunk + lane * 4 : A.d;   // chunks past the end hold nothing
-      if (e[u] < A.d) {
-        a[u] = load4<NT>(x + e[u]);
-        b[u] = load4<NT>(xh + e[u]);
-      }
+  for (int u = 0; u < 4; ++u) {
+    const int c = g * kGroup + 4 * wave + u;
+    e[u] = c < A.nchunks ? c * kChunk + lane * 4 : A.d;   // chunks past the end hold nothing
+    if (e[u] < A.d) {
+      a[u] = load4<NT>(x + e[u]);
+      b[u] = load4<NT>(xh + e[u]);
     }
+  }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      double t = 0.0;
-      if (e[u] < A.d) {
-        const vf4 v = a[u] - b[u];
-        t = lane_terms<COMP>(v, e[u], A.d);
-      }
-      t = wave_tree_sum(t);
-      if (lane == 0) cs[16 * wave + it + u] = t;
+  for (int u = 0; u < 4; ++u) {
+    double t = 0.0;
+    if (e[u] < A.d) {
+      const vf4 v = a[u] - b[u];
+      t = lane_terms<COMP>(v, e[u], A.d);
     }
+    t = wave_tree_sum(t);
+    if (lane == 0) cs[4 * wave + u] = t;
   }
   __syncthreads();
   if (wave == 0) {
@@ -653,22 +655,18 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
   }
 }
 
-// The one pass of the fast path (REBUILD = false, all workers) and the rebuild
-// pass of the fallback (REBUILD = true, only workers in mode 1).  Hits are
-// staged in LDS and flushed with one global atomic per block.
-// grid (ceil(nvec / (256 * kCompactVecs)), n), block 256.
-template <int COMP, bool REBUILD, bool DO_MIX, bool NT>
-__global__ __launch_bounds__(256) void k_sel_compact(Args A) {
-  __shared__ uint2 stage[256 * kCompactVecs * 4];
-  __shared__ uint32_t s_count, s_base;
-  const int i = blockIdx.y;
+// Append the candidates (key32 >= guess) among the 256 * kCompactVecs 4-vectors of
+// one chunk of worker i to sub-list chunk % kSegs.  Hits are staged in LDS and
+// flushed with one global atomic per block.
+template <int COMP, bool DO_MIX, bool NT>
+__device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, uint2* stage,
+                                              uint32_t* s_count, uint32_t* s_base) {
   WorkerCtl* ctl = A.ctl + i;
-  if (REBUILD && ctl->mode != 1u) return;
-  if (threadIdx.x == 0) s_count = 0;
-  __syncthreads();
   const uint32_t guess = ctl->guess_key;
+  const int seg = chunk % kSegs;
+  uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
   const int nvec = (A.d + 3) >> 2;
-  const int m0 = blockIdx.x * (256 * kCompactVecs) + threadIdx.x;
+  const int m0 = chunk * (256 * kCompactVecs) + threadIdx.x;
   uint32_t a[kCompactVecs][4];
 #pragma unroll
   for (int u = 0; u < kCompactVecs; ++u) {
@@ -682,28 +680,63 @@ __global__ __launch_bounds__(256) void k_sel_compact(Args A) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int e = 4 * m + c;
-        if (e < A.d && Digits<COMP>::key32(a[u][c]) >= guess) {
-          const uint32_t slot = atomicAdd(&s_count, 1u);
-          stage[slot] = make_uint2(a[u][c], (uint32_t)e);
+        const uint32_t key = Digits<COMP>::key32(a[u][c]);
+        if (e < A.d && key >= guess) {
+          const uint32_t slot = atomicAdd(s_count, 1u);
+          if (slot < (uint32_t)kStageCap) {
+            stage[slot] = make_uint2(a[u][c], (uint32_t)e);
+          } else {   // more hits than the stage holds: append one by one
+            const uint32_t pos = atomicAdd(&ctl->seg_count[seg], 1u);
+            if (pos < A.seg_cap) cand[pos] = make_uint2(a[u][c], (uint32_t)e);
+          }
         }
       }
     }
   }
   __syncthreads();
-  const uint32_t count = s_count;
-  if (count == 0) return;
-  const int seg = blockIdx.x % kSegs;
-  if (threadIdx.x == 0) s_base = atomicAdd(&ctl->seg_count[seg], count);
+  const uint32_t count = *s_count < (uint32_t)kStageCap ? *s_count : (uint32_t)kStageCap;
+  if (count != 0) {
+    if (threadIdx.x == 0) *s_base = atomicAdd(&ctl->seg_count[seg], count);
+    __syncthreads();
+    const uint32_t base = *s_base;
+    for (uint32_t t = threadIdx.x; t < count; t += 256)
+      if (base + t < A.seg_cap) cand[base + t] = stage[t];
+  }
+}
+
+// The one pass of the fast path: every worker, one block per chunk.
+// grid (ceil(nvec / (256 * kCompactVecs)), n), block 256.
+template <int COMP, bool DO_MIX, bool NT>
+__global__ __launch_bounds__(256) void k_sel_compact(Args A) {
+  __shared__ uint2 stage[kStageCap];
+  __shared__ uint32_t s_count, s_base;
+  if (threadIdx.x == 0) s_count = 0;
   __syncthreads();
-  const uint32_t base = s_base;
-  uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
-  for (uint32_t t = threadIdx.x; t < count; t += 256)
-    if (base + t < A.seg_cap) cand[base + t] = stage[t];
+  compact_chunk<COMP, DO_MIX, NT>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
+}
+
+// The rebuild pass of the fallback: only workers in mode 1; a few blocks per
+// worker loop over the chunks, so that the launch costs next to nothing when no
+// worker needs it.  grid (kFallbackBlocks, n), block 256.
+template <int COMP>
+__global__ __launch_bounds__(256) void k_sel_rebuild(Args A) {
+  __shared__ uint2 stage[kStageCap];
+  __shared__ uint32_t s_count, s_base;
+  const int i = blockIdx.y;
+  if (A.ctl[i].mode != 1u) return;
+  const int nvec = (A.d + 3) >> 2;
+  const int nchunk = (nvec + 256 * kCompactVecs - 1) / (256 * kCompactVecs);
+  for (int chunk = blockIdx.x; chunk < nchunk; chunk += gridDim.x) {
+    __syncthreads();
+    if (threadIdx.x == 0) s_count = 0;
+    __syncthreads();
+    compact_chunk<COMP, false, false>(A, i, chunk, stage, &s_count, &s_base);
+  }
 }
 
 // Fallback, step 1: 16-bit histogram of key32 over a sample (every
 // sample_stride-th 4-vector; stride 1 = the whole row) of the rows whose list
-// is not good.  grid (ceil(ceil(nvec / stride) / (256 * kCompactVecs)), n)
+// is not good.  grid (kFallbackBlocks, n), block 256.
 template <int COMP>
 __global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
   const int i = blockIdx.y;
@@ -711,18 +744,14 @@ __global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
   if (list_is_good(ctl, A)) return;
   uint32_t* hist = A.hist16 + (int64_t)i * kBins16;
   const int nvec = (A.d + 3) >> 2;
-  const int64_t j0 = (int64_t)blockIdx.x * (256 * kCompactVecs) + threadIdx.x;
+  const int64_t nsample = ((int64_t)nvec + A.sample_stride - 1) / A.sample_stride;
+  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nsample; j += (int64_t)gridDim.x * 256) {
+    const int m = (int)(j * (int64_t)A.sample_stride);
+    uint32_t a[4];
+    entry_bits<COMP, false, false>(A, i, m, a);
 #pragma unroll
-  for (int u = 0; u < kCompactVecs; ++u) {
-    const int64_t m64 = (j0 + u * 256) * (int64_t)A.sample_stride;
-    if (m64 < nvec) {
-      const int m = (int)m64;
-      uint32_t a[4];
-      entry_bits<COMP, false, false>(A, i, m, a);
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        if (4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
-    }
+    for (int c = 0; c < 4; ++c)
+      if (4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
   }
 }
 
@@ -775,6 +804,7 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
     const uint32_t bin = 64u * (uint32_t)t + (uint32_t)b;
     const uint64_t listed = (uint64_t)cum + (uint64_t)mine[b];   // sampled entries with key32 >= floor(bin)
     ctl->guess_key = Digits<COMP>::bin16_floor(bin);
+    ctl->bin_shift = COMP == Q_TOPK ? 9u : 10u;   // 64 candidate bins per 16-bit bucket
     // an exact histogram knows whether the rebuilt list fits; a sampled one lets the
     // rebuild find out (the select then scans the row if it does not)
     ctl->mode = (A.sample_stride > 1u || listed <= (uint64_t)A.cand_cap) ? 1u : 2u;
@@ -854,6 +884,59 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uin
   __syncthreads();
 }
 
+// Hand one kept entry to the message list of worker i (wave-aggregated slot).
+// Every lane of the wave must call it (keep = false for lanes with nothing).
+template <int COMP>
+__device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint32_t a, uint32_t idx,
+                                           uint32_t* s_emit) {
+  const uint64_t mask = __ballot(keep);
+  if (mask == 0) return;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((unsigned long long)mask) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(s_emit, (uint32_t)__popcll(mask));
+  base = __shfl(base, leader, 64);
+  if (keep) {
+    const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+    if (slot < (uint32_t)A.k) {
+      float val;
+      if (COMP == Q_TOPK) {
+        val = __uint_as_float(a);
+      } else {
+        const int64_t o = (int64_t)i * A.ld + idx;
+        val = A.X[o] - A.Xhat[o];
+        if (A.randk_rescale) val = A.randk_scale * val;
+      }
+      A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
+      A.sel_val[(int64_t)i * A.k + slot] = val;
+      A.keptmap[(int64_t)i * A.ld + idx] = 1;   // plain byte store: no two kept entries share a byte
+    }
+  }
+}
+
+// Place the guess (and the bin width) for the next step below this step's
+// threshold key T: by the distance that, at the key density seen between the old
+// guess and T, holds `want` entries (for top_a the k entries kept now leave the
+// race, so want includes k).  Also resets the per-step counters.
+__device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64_t kstar, uint32_t total,
+                                           bool from_list, uint32_t emitted, uint32_t mode) {
+  const uint32_t T = (uint32_t)(kstar >> 32);
+  const uint32_t G = ctl->guess_key;
+  uint64_t delta = A.delta0;
+  if (from_list && total > (uint32_t)A.k && T > G)
+    delta = (uint64_t)(T - G) * (uint64_t)A.want / (uint64_t)(total - (uint32_t)A.k);
+  if (delta < 1) delta = 1;
+  if (delta > 0xFFFFFFFFull) delta = 0xFFFFFFFFull;
+  ctl->guess_key = delta >= (uint64_t)T ? 0u : T - (uint32_t)delta;
+  // about 1024 bins between the guess and where the threshold is expected
+  const int lg = 63 - __clzll((unsigned long long)delta);
+  ctl->bin_shift = lg > 10 ? (uint32_t)(lg - 10) : 0u;
+  ctl->kstar = kstar;
+  ctl->kept = emitted;
+  ctl->mode = mode;
+  for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
+}
+
 template <int COMP, bool ROW>
 __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint32_t total, uint32_t* h,
                                 uint32_t* grp, uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
@@ -890,9 +973,6 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
   }
   const uint64_t kstar = *s_prefix << Digits<COMP>::shift(last);
   // emit every entry with composite >= kstar
-  int32_t* sel_idx = A.sel_idx + (int64_t)i * A.k;
-  float* sel_val = A.sel_val + (int64_t)i * A.k;
-  uint32_t* bitmap = A.bitmap + (int64_t)i * A.bitmap_words;
   for_each_entry<COMP, ROW>(A, i, lens, [&](uint32_t a, uint32_t idx) {
     if (Digits<COMP>::composite(a, idx) >= kstar) {
       const uint32_t slot = atomicAdd(s_emit, 1u);
@@ -905,58 +985,141 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
           val = A.X[o] - A.Xhat[o];
           if (A.randk_rescale) val = A.randk_scale * val;
         }
-        sel_idx[slot] = (int32_t)idx;
-        sel_val[slot] = val;
-        atomicOr(&bitmap[idx >> 5], 1u << (idx & 31u));
+        A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
+        A.sel_val[(int64_t)i * A.k + slot] = val;
+        A.keptmap[(int64_t)i * A.ld + idx] = 1;
       }
     }
   });
   __syncthreads();
-  if (threadIdx.x == 0) {
-    // next guess: below this step's threshold key by the distance that, at the key
-    // density seen between the old guess and the threshold, holds `want` entries
-    // (for top_a the k entries kept now leave the race, so want includes k)
-    const uint32_t T = (uint32_t)(kstar >> 32);
-    const uint32_t G = ctl->guess_key;
-    uint64_t delta = A.delta0;
-    if (!ROW && total > (uint32_t)A.k && T > G)
-      delta = (uint64_t)(T - G) * (uint64_t)A.want / (uint64_t)(total - (uint32_t)A.k);
-    if (delta < 1) delta = 1;
-    ctl->guess_key = delta >= (uint64_t)T ? 0u : T - (uint32_t)delta;
-    ctl->kstar = kstar;
-    ctl->kept = *s_emit;
-    ctl->mode = ROW ? 2u : ctl->mode;
-    for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
-  }
+  if (threadIdx.x == 0) next_guess(A, ctl, kstar, total, !ROW, *s_emit, ROW ? 2u : 0u);
 }
 
+// Exact selection from the candidates, emission of the kept (index, value) pairs
+// and of the bitmap, next guess.  Fast path: the candidate histogram written by
+// the pass over the rows already tells which bin holds the k-th largest key; one
+// sweep over the list emits everything above that bin and ranks the few entries
+// inside it directly in LDS.  If that bin is crowded (ties) the generic
+// digit-by-digit select runs on the list; if the list itself is not good, on the
+// row.  grid n, block 1024.
 template <int COMP>
 __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t grp[256];
   __shared__ uint32_t lens[kSegs];
-  __shared__ uint64_t s_prefix;
-  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good;
+  __shared__ uint32_t pre[kSegs + 1];
+  __shared__ uint2 small[kSmallCap];
+  __shared__ uint64_t s_prefix, s_kstar;
+  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good, s_small;
   const int i = blockIdx.x;
   WorkerCtl* ctl = A.ctl + i;
+  for (int b = threadIdx.x; b < kBins; b += 1024) h[b] = 0;
   if (threadIdx.x == 0) {
     s_prefix = 0;
     s_need = (uint32_t)A.k;
     s_emit = 0;
+    s_small = 0;
     s_good = list_is_good(ctl, A) ? 1u : 0u;
     uint32_t total = 0;
     for (int s = 0; s < kSegs; ++s) {
       const uint32_t c = ctl->seg_count[s];
       lens[s] = c < A.seg_cap ? c : A.seg_cap;
+      pre[s] = total;
       total += lens[s];
     }
+    pre[kSegs] = total;
     s_total = total;
   }
   __syncthreads();
-  if (!s_good)
-    refine_and_emit<COMP, true>(A, i, lens, s_total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
-  else
-    refine_and_emit<COMP, false>(A, i, lens, s_total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+  const uint32_t total = s_total;
+  if (!s_good) {
+    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+    return;
+  }
+  const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
+  // flat position f of the concatenated sub-lists -> entry
+  auto entry_at = [&](uint32_t f) -> uint2 {
+    int lo = 0;   // sub-list holding f: largest s with pre[s] <= f
+#pragma unroll
+    for (int step = kSegs / 2; step >= 1; step >>= 1)
+      if (pre[lo + step] <= f) lo += step;
+    return A.cand[((int64_t)i * kSegs + lo) * A.seg_cap + (f - pre[lo])];
+  };
+  auto bin_of = [&](uint32_t a) -> uint32_t {
+    const uint32_t bin = (Digits<COMP>::key32(a) - guess) >> shift;
+    return bin < (uint32_t)kBins ? bin : (uint32_t)kBins - 1u;
+  };
+  // sweep 1: histogram of the candidates by their distance above the guess (eight
+  // entries per thread in flight; a list of up to 8192 entries stays in registers)
+  uint2 c[8];
+  bool have[8];
+  const bool resident = total <= 1024u * 8u;
+  for (uint32_t base = 0; base < total; base += 1024u * 8u) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
+      have[u] = f < total;
+      if (have[u]) c[u] = entry_at(f);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (have[u]) atomicAdd(&h[bin_of(c[u].x)], 1u);
+  }
+  __syncthreads();
+  find_digit(h, grp, (uint32_t)A.k, &s_digit, &s_above);
+  const uint32_t tbin = s_digit;            // bin of the k-th largest key
+  const uint32_t need_in_bin = (uint32_t)A.k - s_above;
+  const uint32_t in_bin = h[tbin];
+  if (in_bin > (uint32_t)kSmallCap) {
+    __syncthreads();
+    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+    return;
+  }
+  // sweep 2: emit everything above the threshold bin, collect the bin itself
+  for (uint32_t base = 0; base < total; base += 1024u * 8u) {
+    if (!resident) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
+        have[u] = f < total;
+        if (have[u]) c[u] = entry_at(f);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      bool above = false;
+      if (have[u]) {
+        const uint32_t bin = bin_of(c[u].x);
+        above = bin > tbin;
+        if (bin == tbin) {
+          const uint32_t pos = atomicAdd(&s_small, 1u);
+          if (pos < (uint32_t)kSmallCap) small[pos] = c[u];
+        }
+      }
+      emit_entry<COMP>(A, i, above, c[u].x, c[u].y, &s_emit);
+    }
+  }
+  __syncthreads();
+  // rank the entries of the threshold bin against each other; the need_in_bin largest are kept
+  const uint32_t m = s_small < (uint32_t)kSmallCap ? s_small : (uint32_t)kSmallCap;
+  {
+    bool keep = false;
+    uint2 mine = make_uint2(0, 0);
+    if (threadIdx.x < m) {
+      mine = small[threadIdx.x];
+      const uint64_t K = Digits<COMP>::composite(mine.x, mine.y);
+      uint32_t rank = 0;
+      for (uint32_t u = 0; u < m; ++u) {
+        const uint2 o = small[u];
+        rank += Digits<COMP>::composite(o.x, o.y) > K ? 1u : 0u;
+      }
+      keep = rank < need_in_bin;
+      if (rank + 1u == need_in_bin) s_kstar = K;
+    }
+    emit_entry<COMP>(A, i, keep, mine.x, mine.y, &s_emit);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, s_emit, 0u);
 }
 
 // S_i[e] += sum_p w_p q_j[e] over the neighbours j = col[p] that kept entry e,
@@ -973,15 +1136,14 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   if (m >= A.k || p >= pend) return;
   const int j = A.col[p];
   const int e = A.sel_idx[(int64_t)j * A.k + m];
-  const uint32_t word = (uint32_t)e >> 5, bit = 1u << ((uint32_t)e & 31u);
   for (int p2 = pbeg; p2 < p; ++p2)
-    if (A.bitmap[(int64_t)A.col[p2] * A.bitmap_words + word] & bit) return;
+    if (A.keptmap[(int64_t)A.col[p2] * A.ld + e]) return;
   float* s = A.S + (int64_t)i * A.ld + e;
   float acc = *s;
   acc = acc + A.w[p] * A.sel_val[(int64_t)j * A.k + m];
   for (int p2 = p + 1; p2 < pend; ++p2) {
     const int j2 = A.col[p2];
-    if (A.bitmap[(int64_t)j2 * A.bitmap_words + word] & bit) {
+    if (A.keptmap[(int64_t)j2 * A.ld + e]) {
       const int64_t o = (int64_t)j2 * A.ld + e;
       float q = A.X[o] - A.Xhat[o];
       if (A.randk_rescale) q = A.randk_scale * q;
@@ -992,7 +1154,7 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
 }
 
 // xhat_j[e] += q_j[e] for the kept entries (Algorithm 1 line 6); clears the
-// bitmap words it touched.  grid (ceil(k/256), n)
+// kept-map bytes it used.  grid (ceil(k/256), n)
 __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int j = blockIdx.y;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1000,7 +1162,7 @@ __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int e = A.sel_idx[(int64_t)j * A.k + m];
   float* xh = A.Xhat + (int64_t)j * A.ld + e;
   *xh = *xh + A.sel_val[(int64_t)j * A.k + m];
-  A.bitmap[(int64_t)j * A.bitmap_words + ((uint32_t)e >> 5)] = 0u;
+  A.keptmap[(int64_t)j * A.ld + e] = 0;
 }
 
 // ---------------------------------------------------------------------------
