@@ -109,6 +109,23 @@ def device_inputs(w, torch, seed=20190709):
     return X, pool
 
 
+def calibration_copy(torch, nbytes=896_000_000, reps=10):
+    """A plain device copy of known size (reads nbytes, writes nbytes), run before the
+    timed region so that a `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` pass over this same
+    command line also records what those counters read for a known amount of traffic."""
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    el = (time.perf_counter() - t0) / reps
+    del a, b
+    torch.cuda.empty_cache()
+    return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9)
+
+
 def run_gpu(w, steps, warmup, profile=True):
     import torch
     from paper_1907_09356_amd import binding as B
@@ -225,6 +242,7 @@ def main():
         sys.exit("bench.py: no GPU visible")
 
     w = WORKLOADS[args.workload]
+    copy_ref = calibration_copy(torch)
     res = run_gpu(w, args.steps, args.warmup)
     elems = w["n"] * w["d"]
     kernels = res["kernels"]
@@ -260,6 +278,7 @@ def main():
                     for k, v in kernels.items()},
         "ms_per_step_profiled": res["ms_per_step_profiled"],
         "consensus_error": res["consensus_error"],
+        "device_copy_reference": copy_ref,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
