@@ -292,7 +292,8 @@ int gossip_dense(choco_ctx* ctx) {
     if (needs_stat) {
       LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
              dim3(kStatThreads), 0, A);
-      LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
+      if (!A.fold_finalise)
+        LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
     }
     if (ctx->rpw) {
       if (A.codes) launch_apply_mix<COMP, true, NT>(ctx, A);
@@ -425,9 +426,10 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sparse = is_sparse(cfg->compressor);
   ctx->mix_form = resolve_mix_form(*cfg);
   ctx->rpw = pick_rpw(cfg->n);
-  // stream past the caches once one state array is larger than what they can keep between kernels
-  ctx->nt = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float) >= ((size_t)48 << 20);
-  if (const char* force = std::getenv("CHOCO_FORCE_NT")) ctx->nt = force[0] == '1';
+  // Non-temporal accesses for all but tiny states: measured faster even when the state
+  // would fit in cache (a kernel boundary on this multi-die part writes dirty L2 lines
+  // back anyway); the cached path stays for states under 4 MB per array.
+  ctx->nt = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float) >= ((size_t)4 << 20);
   ctx->t = 0;
   ctx->last_hip_error = 0;
   ctx->destroyed = false;
@@ -459,6 +461,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     A.tau = 1.0 + std::min(dd / (s * s), std::sqrt(dd) / s);
   }
   A.codes = nullptr;
+  // with few group sums the fused apply kernel finishes the norm tree itself (one launch less)
+  A.fold_finalise = (ctx->rpw != 0 && cfg->order == CHOCO_ORDER_COMPRESS_THEN_MIX && L.ngroups <= 256) ? 1 : 0;
   A.k = ctx->sparse ? cfg->k : 0;
   A.hist16 = (uint32_t*)(base + L.hist16);
   A.cand = (uint2*)(base + L.cand);

@@ -82,6 +82,7 @@ struct Args {
   int32_t levels;      // gsgd: s
   double tau;          // gsgd: 1 + min(d/s^2, sqrt(d)/s) or 1
   int32_t* codes;      // optional capture of the transmitted codes (n x ld)
+  int32_t fold_finalise;  // ngroups <= 256: the apply kernel does level 3 of the norm tree itself
   // sparse operators
   int64_t k;
   uint32_t* hist16;    // n x kBins16 (fallback histogram)
@@ -281,6 +282,49 @@ __device__ __forceinline__ double lane_terms(const vf4& v, int e, int d) {
   return acc;
 }
 
+// Per-worker scales from the finished norm sum (Appendix C: sign, gsgd_b); fp64
+// sqrt and divisions, rounded once to fp32.  Optionally recorded in the control block.
+template <int COMP>
+__device__ __forceinline__ void scales_from_total(const Args& A, double total, RowScale<COMP>& sc,
+                                                  WorkerCtl* record) {
+  double nrm = 0.0;
+  sc.c = sc.r = sc.step = 0.0f;
+  sc.nonzero = 0;
+  if (COMP == Q_SIGN) {
+    sc.c = (float)(total / (double)A.d);
+  } else if (COMP == Q_QSGD) {
+    nrm = sqrt(total);
+    const double s = (double)A.levels;
+    sc.nonzero = nrm > 0.0 ? 1 : 0;
+    sc.r = nrm > 0.0 ? (float)(s / nrm) : 0.0f;
+    sc.step = nrm > 0.0 ? (float)(nrm / (A.tau * s)) : 0.0f;
+  }
+  if (record) {
+    record->stat = total;
+    record->nrm = nrm;
+    record->scale_c = sc.c;
+    record->scale_r = sc.r;
+    record->scale_step = sc.step;
+    record->nonzero = sc.nonzero;
+  }
+}
+
+// Level 3 of the norm tree done by one wave when there are at most 256 group
+// sums: lane l stands for tree lanes l, l+64, l+128, l+192 (one group sum each),
+// the halvings by 128 and 64 are two adds in registers and the rest is the wave
+// butterfly - the same additions in the same order as k_dense_finalise.
+__device__ __forceinline__ double wave_level3(const Args& A, int i, int lane) {
+  const double* gs = A.group_sums + (int64_t)i * A.ngroups;
+  double a0 = lane < A.ngroups ? gs[lane] : 0.0;
+  double a1 = lane + 64 < A.ngroups ? gs[lane + 64] : 0.0;
+  const double a2 = lane + 128 < A.ngroups ? gs[lane + 128] : 0.0;
+  const double a3 = lane + 192 < A.ngroups ? gs[lane + 192] : 0.0;
+  a0 = a0 + a2;
+  a1 = a1 + a3;
+  a0 = a0 + a1;
+  return wave_tree_sum(a0);
+}
+
 // Third level of the tree over the group sums and the per-worker scales.
 // grid n, block 256.  (A separate launch on purpose: handing the group sums to a
 // "last block" of the producing kernel needs a device-scope fence per block,
@@ -303,20 +347,8 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
     __syncthreads();
   }
   if (l == 0) {
-    WorkerCtl* ctl = A.ctl + i;
-    const double total = sh[0];
-    ctl->stat = total;
-    if (COMP == Q_SIGN) {
-      ctl->nrm = 0.0;
-      ctl->scale_c = (float)(total / (double)A.d);
-    } else {
-      const double nrm = sqrt(total);
-      const double s = (double)A.levels;
-      ctl->nrm = nrm;
-      ctl->nonzero = nrm > 0.0 ? 1 : 0;
-      ctl->scale_r = nrm > 0.0 ? (float)(s / nrm) : 0.0f;
-      ctl->scale_step = nrm > 0.0 ? (float)(nrm / (A.tau * s)) : 0.0f;
-    }
+    RowScale<COMP> sc;
+    scales_from_total<COMP>(A, sh[0], sc, A.ctl + i);
   }
 }
 
@@ -420,6 +452,20 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
       xh[q] = load4<NT>(A.Xhat + o);
     }
   }
+  // scales of this wave's rows: read from the control block, or (few group sums) finished here
+  RowScale<COMP> sc[RPW];
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = wave + 4 * q;
+    if (r < A.n) {
+      if ((COMP == Q_SIGN || COMP == Q_QSGD) && A.fold_finalise) {
+        const double total = wave_level3(A, r, lane);
+        scales_from_total<COMP>(A, total, sc[q], (blockIdx.x == 0 && lane == 0) ? A.ctl + r : nullptr);
+      } else {
+        sc[q].load(A.ctl + r);
+      }
+    }
+  }
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + 4 * q;
@@ -427,12 +473,10 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
       vf4 nh = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
         const int64_t o = (int64_t)r * A.ld + e;
-        RowScale<COMP> sc;
-        sc.load(A.ctl + r);
         uint4 words = make_uint4(0, 0, 0, 0);
         if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
         vi4 code;
-        nh = absorb<COMP>(xr[q], xh[q], sc, words, code);
+        nh = absorb<COMP>(xr[q], xh[q], sc[q], words, code);
         store4<NT>(A.Xhat + o, nh);
         if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
       }
@@ -853,9 +897,12 @@ __device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint3
   }
 }
 
-// Walk a histogram of up to 2048 bins in LDS from the top and find the digit at
-// which the running count first reaches `need`.  All threads of a block with
-// >= 256 threads call it; grp is 256 words of LDS scratch.
+// Walk a histogram of 2048 bins in LDS from the top and find the digit at which
+// the running count first reaches `need` (the last digit if it never does).  All
+// threads of a block with >= 256 threads call it; grp is 256 words of LDS
+// scratch.  Wave 0 does the search: lane l owns bins 32l..32l+31, a suffix scan
+// over the lane totals finds the lane in which the count is reached, and that
+// lane walks its 32 bins.
 __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uint32_t need,
                                            uint32_t* out_digit, uint32_t* out_above) {
   const int t = threadIdx.x;
@@ -866,20 +913,30 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uin
     grp[t] = g;
   }
   __syncthreads();
-  if (t == 0) {
-    uint32_t cum = 0;
-    int g = 255;
-    for (; g > 0; --g) {
-      if (cum + grp[g] >= need) break;
-      cum += grp[g];
+  if (t < 64) {
+    const uint32_t mine = grp[4 * t] + grp[4 * t + 1] + grp[4 * t + 2] + grp[4 * t + 3];
+    // inclusive suffix sum over lanes: incl = sum of lane totals of lanes >= t
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t other = __shfl_down(incl, off, 64);
+      if (t + off < 64) incl += other;
     }
-    int b = 8 * g + 7;
-    for (; b > 8 * g; --b) {
-      if (cum + h[b] >= need) break;
-      cum += h[b];
+    const uint32_t above_lane = incl - mine;          // entries in bins above this lane's range
+    const bool here = above_lane < need && incl >= need;
+    const uint64_t found = __ballot(here);
+    if (found == 0) {                                 // fewer than `need` entries in total
+      if (t == 0) { *out_digit = 0; *out_above = incl - h[0]; }
+    } else if (here) {
+      uint32_t cum = above_lane;
+      int b = 32 * t + 31;
+      for (; b > 32 * t; --b) {
+        if (cum + h[b] >= need) break;
+        cum += h[b];
+      }
+      *out_digit = (uint32_t)b;
+      *out_above = cum;
     }
-    *out_digit = (uint32_t)b;
-    *out_above = cum;   // entries in digits above b
   }
   __syncthreads();
 }
