@@ -66,6 +66,11 @@ KERNEL_BYTES_PER_ELEM = {
     "k_tile_mix": 12,         # read x, xhat; write x
     "k_dense_apply": 12,      # read x, xhat; write xhat
     "k_mix_direct_global": 12,
+    # first pass of a fused choco_step: also reads g and writes x
+    "k_dense_stat_sgd": 16,       # read x, g, xhat; write x
+    "k_sel_compact_sgd": 16,      # read x, g, xhat; write x
+    "k_tile_mix_sgd": 16,         # read x, g, xhat; write x
+    "k_mix_incremental_sgd": 20,  # read x, g, s, xhat; write x
 }
 
 
@@ -126,15 +131,21 @@ def calibration_copy(torch, nbytes=896_000_000, reps=10):
     return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9)
 
 
-def run_gpu(w, steps, warmup, profile=True):
+def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None):
     import torch
     from paper_1907_09356_amd import binding as B
     X, pool = device_inputs(w, torch)
-    ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **comp_kwargs(w, B))
+    kw = comp_kwargs(w, B)
+    if mix_form is not None:
+        kw["mix_form"] = mix_form
+    ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **kw)
 
     def one_step(t):
-        ctx.sgd_step(pool[t & 1], w["lr"])
-        ctx.gossip_step()
+        if fused:
+            ctx.step(pool[t & 1], w["lr"])      # choco_step = sgd step + gossip step in one call
+        else:
+            ctx.sgd_step(pool[t & 1], w["lr"])
+            ctx.gossip_step()
 
     for t in range(warmup):
         one_step(t)
@@ -233,6 +244,8 @@ def main():
     ap.add_argument("--workload", default="large_topk", choices=sorted(WORKLOADS))
     ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="call choco_sgd_step + choco_gossip_step instead of the fused choco_step")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all n workers live in one n x d array); "
@@ -243,7 +256,7 @@ def main():
 
     w = WORKLOADS[args.workload]
     copy_ref = calibration_copy(torch)
-    res = run_gpu(w, args.steps, args.warmup)
+    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused)
     elems = w["n"] * w["d"]
     kernels = res["kernels"]
     timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
@@ -268,7 +281,10 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w["desc"], "name": args.workload, "n": w["n"], "d": w["d"],
-                   "step": "choco_sgd_step + choco_gossip_step", "order": "compress_then_mix"},
+                   "step": ("choco_sgd_step + choco_gossip_step" if args.unfused else
+                            "choco_step (= choco_sgd_step + choco_gossip_step, local update fused "
+                            "into the first pass)"),
+                   "order": "compress_then_mix"},
         "element_updates_per_s": res["steps_per_s"] * elems,
         "step_alg_bytes_per_elem": bpe,
         "step_alg_GBps": bpe * elems * res["steps_per_s"] / 1e9,
@@ -288,7 +304,7 @@ def main():
             if name == args.workload:
                 continue
             k = min(args.steps, 100)
-            r = run_gpu(ow, k, min(args.warmup, 10))
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused)
             b = step_bytes_per_elem(ow, r["kernels"])
             e = ow["n"] * ow["d"]
             others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],

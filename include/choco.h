@@ -107,6 +107,14 @@ int choco_gossip_step(choco_ctx *ctx);
 /* Algorithm 1 line 9: x_i <- x_i - lr * g_i.  g_dev: n*ld floats, 16-byte aligned. */
 int choco_sgd_step(choco_ctx *ctx, const float *g_dev, float lr);
 
+/* One whole iteration in the order of Algorithm 3 (Appendix A): the stochastic gradient
+   update of line 2 there (= Algorithm 1 line 9) with (g, lr), then the gossip step.  The
+   result is bit for bit that of choco_sgd_step followed by choco_gossip_step; where the
+   configured operator starts with a dense pass over X (sign, gsgd, top_a; or the mix of the
+   printed order) the local update is folded into that pass, which saves one read and one
+   write of X.  g_dev: n*ld floats, 16-byte aligned.  Asynchronous; advances t. */
+int choco_step(choco_ctx *ctx, const float *g_dev, float lr);
+
 /* Algorithm 2 lines 9-10 (momentum with weight decay):
    m_i <- (g_i + lambda x_i) + beta m_i;  x_i <- x_i - lr m_i.
    m_dev: n*ld floats of caller-owned momentum memory, zero before the first call. */

@@ -18,7 +18,7 @@ ORDER_COMPRESS_THEN_MIX, ORDER_MIX_THEN_COMPRESS = 0, 1
 MIX_AUTO, MIX_INCREMENTAL_S, MIX_DIRECT = 0, 1, 2
 
 EXPORTS = [
-    "choco_workspace_bytes", "choco_init", "choco_gossip_step", "choco_sgd_step",
+    "choco_workspace_bytes", "choco_init", "choco_gossip_step", "choco_sgd_step", "choco_step",
     "choco_momentum_step", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
     "choco_set_capture", "choco_last_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
@@ -71,6 +71,7 @@ def lib():
         L.choco_init.argtypes = [cfgp, vp, vp, ctypes.c_size_t, ctypes.POINTER(vp)]
         L.choco_gossip_step.argtypes = [vp]
         L.choco_sgd_step.argtypes = [vp, vp, ctypes.c_float]
+        L.choco_step.argtypes = [vp, vp, ctypes.c_float]
         L.choco_momentum_step.argtypes = [vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         dp = ctypes.POINTER(ctypes.c_double)
         L.choco_metrics.argtypes = [vp, dp, dp, dp]
@@ -176,6 +177,11 @@ class Choco:
     def sgd_step(self, G, lr):
         assert G.is_cuda and G.is_contiguous() and G.shape == self.X.shape and G.dtype == self.X.dtype
         _check(lib().choco_sgd_step(self.ctx, G.data_ptr(), float(lr)), "choco_sgd_step")
+
+    def step(self, G, lr):
+        """sgd_step(G, lr) followed by gossip_step(), fused where the operator allows."""
+        assert G.is_cuda and G.is_contiguous() and G.shape == self.X.shape and G.dtype == self.X.dtype
+        _check(lib().choco_step(self.ctx, G.data_ptr(), float(lr)), "choco_step")
 
     def momentum_step(self, G, M, lr, beta, lam):
         for T in (G, M):

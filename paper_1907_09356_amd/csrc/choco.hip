@@ -26,6 +26,7 @@ struct choco_ctx {
   bool sparse;            // top_a / random_a
   int mix_form;           // resolved: CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT
   int rpw;                // rows per wave of the tile kernels, 0 = tile does not fit
+  bool fused;             // the step being enqueued carries the local update in its first pass
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   uint64_t t;             // step counter
   double* metrics_part;   // device scratch of the metrics kernels
@@ -188,12 +189,13 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update"};
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update",
+  "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
 // Brackets one launch with two events when profiling is on (no-op otherwise).
@@ -262,10 +264,11 @@ void launch_apply_mix(choco_ctx* ctx, const Args& A) {
 }
 
 template <int STAT, bool NT>
-void launch_tile_mix(choco_ctx* ctx, const Args& A) {
+void launch_tile_mix(choco_ctx* ctx, const Args& A, bool fused) {
   const dim3 grid((unsigned)A.nchunks), block(kTileThreads);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
-#define CALL(R) LAUNCH(ctx, KID_TILE_MIX, (k_tile_mix<STAT, R, NT>), grid, block, lds, A)
+  const int kid = fused ? KID_TILE_MIX_SGD : KID_TILE_MIX;
+#define CALL(R) LAUNCH(ctx, kid, (k_tile_mix<STAT, R, NT>), grid, block, lds, A)
   RPW_SWITCH(ctx->rpw, CALL)
 #undef CALL
 }
@@ -281,17 +284,24 @@ void launch_mix_direct_global(choco_ctx* ctx, const Args& A) {
   LAUNCH(ctx, KID_MIX_DIRECT_GLOBAL, k_mix_direct_global, chunk_grid((A.d + 3) >> 2, A.n, 1), dim3(256), 0, A);
 }
 
+// In the two functions below `F` is the argument block for the FIRST kernel that reads X
+// in the step (it may carry the fused local update, F.G != nullptr) and `A` the block for
+// every later kernel (A.G == nullptr).
+
 // Dense operators (identity, sign, gsgd), direct mix form.
 template <int COMP, bool NT>
-int gossip_dense(choco_ctx* ctx) {
-  const Args& A = ctx->args;
+int gossip_dense(choco_ctx* ctx, const Args& F) {
+  Args A = F;
+  A.G = nullptr;
+  const bool fused = F.G != nullptr;
   constexpr bool needs_stat = (COMP == Q_SIGN || COMP == Q_QSGD);
   constexpr int STAT = needs_stat ? COMP : Q_NONE;
   constexpr int STATK = needs_stat ? COMP : Q_SIGN;   // any valid instantiation where unused
+  const dim3 stat_grid((unsigned)A.ngroups, (unsigned)A.n);
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX) {
     if (needs_stat) {
-      LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
-             dim3(kStatThreads), 0, A);
+      LAUNCH(ctx, fused ? KID_DENSE_STAT_SGD : KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid,
+             dim3(kStatThreads), 0, F);
       if (!A.fold_finalise)
         LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
     }
@@ -304,15 +314,14 @@ int gossip_dense(choco_ctx* ctx) {
     }
   } else {
     if (ctx->rpw) {
-      launch_tile_mix<STAT, NT>(ctx, A);
+      launch_tile_mix<STAT, NT>(ctx, F, fused);
       if (needs_stat)
         LAUNCH(ctx, KID_GROUP_REDUCE, k_group_reduce, dim3((unsigned)((A.ngroups + 3) / 4), (unsigned)A.n),
                dim3(256), 0, A);
     } else {
       launch_mix_direct_global(ctx, A);
       if (needs_stat)
-        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), dim3((unsigned)A.ngroups, (unsigned)A.n),
-               dim3(kStatThreads), 0, A);
+        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid, dim3(kStatThreads), 0, A);
     }
     if (needs_stat)
       LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
@@ -324,25 +333,36 @@ int gossip_dense(choco_ctx* ctx) {
 
 // Sparsifying operators (top_a, random_a).
 template <int COMP, bool NT>
-int gossip_sparse(choco_ctx* ctx) {
-  const Args& A = ctx->args;
+int gossip_sparse(choco_ctx* ctx, const Args& F) {
+  Args A = F;
+  A.G = nullptr;
+  const bool fused = F.G != nullptr;
   const int32_t nvec = (A.d + 3) >> 2;
   const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
   const dim3 cgrid = chunk_grid(nvec, A.n, kCompactVecs);
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
-  bool fuse_mix = false;
+  bool fuse_mix = false;     // the mix rides on the select pass (top_a, printed order, incremental sums)
+  bool x_touched = false;    // has a kernel of this step already read X (and taken the fused update)?
   if (mix_first) {
-    if (incremental && COMP == Q_TOPK) fuse_mix = true;   // folded into the select pass below
-    else if (incremental) LAUNCH(ctx, KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0, A);
-    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A);
-    else launch_mix_direct_global(ctx, A);
+    if (incremental && COMP == Q_TOPK) {
+      fuse_mix = true;
+    } else {
+      if (incremental)
+        LAUNCH(ctx, fused ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
+               dim3(256), 0, F);
+      else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, F, fused);
+      else launch_mix_direct_global(ctx, A);
+      x_touched = true;
+    }
   }
   // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
+  const Args& C = x_touched ? A : F;
+  const int kid_compact = (!x_touched && fused) ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
   if (fuse_mix)
-    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, A);
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, C);
   else
-    LAUNCH(ctx, KID_SEL_COMPACT, (k_sel_compact<COMP, false, NT>), cgrid, dim3(256), 0, A);
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT>), cgrid, dim3(256), 0, C);
   const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
   LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
   LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
@@ -356,7 +376,7 @@ int gossip_sparse(choco_ctx* ctx) {
   LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
     if (incremental) LAUNCH(ctx, KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0, A);
-    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A);
+    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A, false);
     else launch_mix_direct_global(ctx, A);
   }
   LAUNCH_CHECK(ctx);
@@ -364,15 +384,50 @@ int gossip_sparse(choco_ctx* ctx) {
 }
 
 template <bool NT>
-int gossip_any(choco_ctx* ctx) {
+int gossip_any(choco_ctx* ctx, const Args& A) {
   switch (ctx->cfg.compressor) {
-    case CHOCO_Q_IDENTITY: return gossip_dense<Q_IDENTITY, NT>(ctx);
-    case CHOCO_Q_SIGN: return gossip_dense<Q_SIGN, NT>(ctx);
-    case CHOCO_Q_QSGD: return gossip_dense<Q_QSGD, NT>(ctx);
-    case CHOCO_Q_TOPK: return gossip_sparse<Q_TOPK, NT>(ctx);
-    case CHOCO_Q_RANDK: return gossip_sparse<Q_RANDK, NT>(ctx);
+    case CHOCO_Q_IDENTITY: return gossip_dense<Q_IDENTITY, NT>(ctx, A);
+    case CHOCO_Q_SIGN: return gossip_dense<Q_SIGN, NT>(ctx, A);
+    case CHOCO_Q_QSGD: return gossip_dense<Q_QSGD, NT>(ctx, A);
+    case CHOCO_Q_TOPK: return gossip_sparse<Q_TOPK, NT>(ctx, A);
+    case CHOCO_Q_RANDK: return gossip_sparse<Q_RANDK, NT>(ctx, A);
     default: return CHOCO_E_INVAL;
   }
+}
+
+// Does the first kernel of a gossip step in this configuration read and write X densely,
+// so that the local update can ride on it?
+bool first_pass_can_carry_sgd(const choco_ctx* ctx) {
+  const int comp = ctx->cfg.compressor;
+  const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
+  if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX)
+    return comp == CHOCO_Q_SIGN || comp == CHOCO_Q_QSGD || comp == CHOCO_Q_TOPK;
+  // printed order: the first kernel is the mix
+  if (ctx->sparse) return incremental || ctx->rpw != 0;   // k_sel_compact(+mix) / k_mix_incremental / k_tile_mix
+  return ctx->rpw != 0;                                    // k_tile_mix
+}
+
+int launch_sgd(choco_ctx* ctx, const float* g_dev, float lr) {
+  const Args& A = ctx->args;
+  const int32_t nvec = (A.d + 3) >> 2;
+  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
+  if (ctx->nt) LAUNCH(ctx, KID_SGD, k_sgd<true>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
+  else LAUNCH(ctx, KID_SGD, k_sgd<false>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
+int run_gossip(choco_ctx* ctx, const float* fused_g, float lr) {
+  Args A = ctx->args;
+  A.t_lo = (uint32_t)(ctx->t & 0xFFFFFFFFu);
+  A.t_hi = (uint32_t)(ctx->t >> 32);
+  A.G = fused_g;
+  A.lr = lr;
+  ctx->fused = fused_g != nullptr;
+  const int rc = ctx->nt ? gossip_any<true>(ctx, A) : gossip_any<false>(ctx, A);
+  ctx->fused = false;
+  if (rc == CHOCO_OK) ctx->t += 1;
+  return rc;
 }
 
 }  // namespace
@@ -434,6 +489,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->last_hip_error = 0;
   ctx->destroyed = false;
   ctx->profiling = false;
+  ctx->fused = false;
   ctx->ev_used = 0;
 
   char* base = (char*)workspace_dev;
@@ -547,23 +603,20 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
 
 int choco_gossip_step(choco_ctx* ctx) {
   if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
-  Args& A = ctx->args;
-  A.t_lo = (uint32_t)(ctx->t & 0xFFFFFFFFu);
-  A.t_hi = (uint32_t)(ctx->t >> 32);
-  const int rc = ctx->nt ? gossip_any<true>(ctx) : gossip_any<false>(ctx);
-  if (rc == CHOCO_OK) ctx->t += 1;
-  return rc;
+  return run_gossip(ctx, nullptr, 0.0f);
 }
 
 int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
   if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
-  const Args& A = ctx->args;
-  const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
-  if (ctx->nt) LAUNCH(ctx, KID_SGD, k_sgd<true>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
-  else LAUNCH(ctx, KID_SGD, k_sgd<false>, grid, dim3(256), 0, A.X, g_dev, A.ld, nvec, lr);
-  LAUNCH_CHECK(ctx);
-  return CHOCO_OK;
+  return launch_sgd(ctx, g_dev, lr);
+}
+
+int choco_step(choco_ctx* ctx, const float* g_dev, float lr) {
+  if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
+  if (first_pass_can_carry_sgd(ctx)) return run_gossip(ctx, g_dev, lr);
+  const int rc = launch_sgd(ctx, g_dev, lr);
+  if (rc != CHOCO_OK) return rc;
+  return run_gossip(ctx, nullptr, 0.0f);
 }
 
 int choco_momentum_step(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta,

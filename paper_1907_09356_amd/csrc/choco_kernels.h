@@ -74,6 +74,10 @@ struct Args {
   const float* w;
   WorkerCtl* ctl;
   float gamma;
+  // fused local update (choco_step): when G is non-null the first pass over X of the step
+  // also does x <- x - lr * g (Algorithm 1 line 9) before using x
+  const float* G;
+  float lr;
   // dense operators
   double* chunk_sums;  // n x nchunks first-level sums (only the printed-order tile kernel writes them)
   double* group_sums;  // n x ngroups second-level sums
@@ -116,6 +120,12 @@ __device__ __forceinline__ void store4(float* p, vf4 v) {
   vf4* q = reinterpret_cast<vf4*>(p);
   if (NT) __builtin_nontemporal_store(v, q);
   else *q = v;
+}
+// x <- x - lr * g on one 4-vector (product rounded, then the difference).
+__device__ __forceinline__ vf4 sgd4(vf4 x, const vf4& g, float lr) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) x[c] = x[c] - lr * g[c];
+  return x;
 }
 __device__ __forceinline__ vf4 lds_load4(const float* p) { return *reinterpret_cast<const vf4*>(p); }
 __device__ __forceinline__ void lds_store4(float* p, vf4 v) { *reinterpret_cast<vf4*>(p) = v; }
@@ -373,6 +383,17 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
       b[u] = load4<NT>(xh + e[u]);
     }
   }
+  if (A.G) {   // fused local update: x <- x - lr g, stored for the apply pass
+    const float* gr = A.G + (int64_t)i * A.ld;
+    float* xw = A.X + (int64_t)i * A.ld;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < A.d) {
+        a[u] = sgd4(a[u], load4<NT>(gr + e[u]), A.lr);
+        store4<NT>(xw + e[u], a[u]);
+      }
+    }
+  }
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     double t = 0.0;
@@ -514,6 +535,7 @@ __global__ __launch_bounds__(kTileThreads) void k_tile_mix(Args A) {
         const int64_t o = (int64_t)r * A.ld + e;
         xr[q] = load4<NT>(A.X + o);
         xh = load4<NT>(A.Xhat + o);
+        if (A.G) xr[q] = sgd4(xr[q], load4<NT>(A.G + o), A.lr);
       }
       lds_store4(tile + r * kChunk + lane * 4, xh);
     }
@@ -605,6 +627,7 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
       x[u] = load4<NT>(A.X + o);
       s[u] = load4<NT>(A.S + o);
       xh[u] = load4<NT>(A.Xhat + o);
+      if (A.G) x[u] = sgd4(x[u], load4<NT>(A.G + o), A.lr);
     }
   }
 #pragma unroll
@@ -679,18 +702,22 @@ __device__ __forceinline__ bool list_is_good(const WorkerCtl* ctl, const Args& A
 // a[c] for the four entries of 4-vector m of worker i (raw bits of v for top_a,
 // complemented random word for random_a).  DO_MIX (top_a, printed order with
 // incremental sums): first x += gamma (S - xhat), stored, then v = x - xhat.
-template <int COMP, bool DO_MIX, bool NT>
+// FIRST: this is the step's first pass over X (the only one that may carry the fused
+// local update x <- x - lr g).
+template <int COMP, bool DO_MIX, bool NT, bool FIRST>
 __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t (&a)[4]) {
   if (COMP == Q_TOPK) {
     const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
     vf4 x = load4<NT>(A.X + o);
     const vf4 xh = load4<NT>(A.Xhat + o);
+    const bool sgd = FIRST && A.G != nullptr;
+    if (sgd) x = sgd4(x, load4<NT>(A.G + o), A.lr);
     if (DO_MIX) {
       const vf4 s = load4<NT>(A.S + o);
 #pragma unroll
       for (int c = 0; c < 4; ++c) x[c] = x[c] + A.gamma * (s[c] - xh[c]);
-      store4<NT>(A.X + o, x);
     }
+    if (DO_MIX || sgd) store4<NT>(A.X + o, x);
 #pragma unroll
     for (int c = 0; c < 4; ++c) a[c] = __float_as_uint(x[c] - xh[c]);
   } else {
@@ -702,7 +729,7 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
 // Append the candidates (key32 >= guess) among the 256 * kCompactVecs 4-vectors of
 // one chunk of worker i to sub-list chunk % kSegs.  Hits are staged in LDS and
 // flushed with one global atomic per block.
-template <int COMP, bool DO_MIX, bool NT>
+template <int COMP, bool DO_MIX, bool NT, bool FIRST>
 __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, uint2* stage,
                                               uint32_t* s_count, uint32_t* s_base) {
   WorkerCtl* ctl = A.ctl + i;
@@ -715,7 +742,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
 #pragma unroll
   for (int u = 0; u < kCompactVecs; ++u) {
     const int m = m0 + u * 256;
-    if (m < nvec) entry_bits<COMP, DO_MIX, NT>(A, i, m, a[u]);
+    if (m < nvec) entry_bits<COMP, DO_MIX, NT, FIRST>(A, i, m, a[u]);
   }
 #pragma unroll
   for (int u = 0; u < kCompactVecs; ++u) {
@@ -756,7 +783,7 @@ __global__ __launch_bounds__(256) void k_sel_compact(Args A) {
   __shared__ uint32_t s_count, s_base;
   if (threadIdx.x == 0) s_count = 0;
   __syncthreads();
-  compact_chunk<COMP, DO_MIX, NT>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
+  compact_chunk<COMP, DO_MIX, NT, true>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
 }
 
 // The rebuild pass of the fallback: only workers in mode 1; a few blocks per
@@ -774,7 +801,7 @@ __global__ __launch_bounds__(256) void k_sel_rebuild(Args A) {
     __syncthreads();
     if (threadIdx.x == 0) s_count = 0;
     __syncthreads();
-    compact_chunk<COMP, false, false>(A, i, chunk, stage, &s_count, &s_base);
+    compact_chunk<COMP, false, false, false>(A, i, chunk, stage, &s_count, &s_base);
   }
 }
 
@@ -792,7 +819,7 @@ __global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
   for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nsample; j += (int64_t)gridDim.x * 256) {
     const int m = (int)(j * (int64_t)A.sample_stride);
     uint32_t a[4];
-    entry_bits<COMP, false, false>(A, i, m, a);
+    entry_bits<COMP, false, false, false>(A, i, m, a);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
       if (4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);

@@ -72,6 +72,15 @@ class Pair:
         self.gpu.gossip_step()
         return self.ref.gossip_step(want_details=True)
 
+    def step(self, G, lr):
+        """One fused iteration on the GPU; the oracle does the two halves one after the other."""
+        t = self.torch
+        Gd = t.zeros((self.n, self.ld), dtype=t.float32, device=self.X.device)
+        Gd[:, :self.d] = t.from_numpy(np.ascontiguousarray(G, dtype=np.float32)).to(self.X.device)
+        self.gpu.step(Gd, lr)
+        self.ref.sgd_step(G, lr)
+        return self.ref.gossip_step(want_details=True)
+
     def gpu_state(self):
         self.gpu.sync()
         X = self.X[:, :self.d].cpu().numpy()

@@ -163,6 +163,28 @@ def test_zero_state_and_zero_norm():
             pair.close()
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", list(COMPRESSORS))
+@pytest.mark.parametrize("n,d,mix_form", [(8, 70001, B.MIX_AUTO), (9, 2000, B.MIX_AUTO), (70, 1030, B.MIX_AUTO),
+                                          (8, 6000, B.MIX_DIRECT)])
+def test_fused_step_equals_sgd_then_gossip(n, d, mix_form, comp, order):
+    kw = dict(COMPRESSORS[comp])
+    sparse = kw["compressor"] in (B.Q_TOPK, B.Q_RANDK)
+    if mix_form == B.MIX_DIRECT and not sparse:
+        pytest.skip("dense operators already use the direct form")
+    if sparse:
+        kw["k"] = max(1, d // 100)
+    pair = Pair(synth.normal_state(n, d, seed=3), topo_for(n), 0.2, order=order, mix_form=mix_form,
+                seed=77, **kw)
+    grads = synth.GradientStream(n, d, seed=4)
+    try:
+        for t in range(5):
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="fused %s n=%d d=%d order=%d step %d" % (comp, n, d, order, t))
+    finally:
+        pair.close()
+
+
 def test_sgd_and_momentum_steps_match():
     import torch
     from oracle import choco_ref as ref
