@@ -244,6 +244,9 @@ def main():
     ap.add_argument("--workload", default="large_topk", choices=sorted(WORKLOADS))
     ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mix", choices=["auto", "incremental", "direct"], default="auto",
+                    help="evaluation of the mix: auto = incremental neighbour sums for top-k/random-k "
+                         "(the library default), direct = LDS-tiled, no S array")
     ap.add_argument("--unfused", action="store_true",
                     help="call choco_sgd_step + choco_gossip_step instead of the fused choco_step")
     args = ap.parse_args()
@@ -256,7 +259,11 @@ def main():
 
     w = WORKLOADS[args.workload]
     copy_ref = calibration_copy(torch)
-    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused)
+    from paper_1907_09356_amd import binding as B
+    mix_form = {"auto": None, "incremental": B.MIX_INCREMENTAL_S, "direct": B.MIX_DIRECT}[args.mix]
+    if w["comp"] in ("sign", "qsgd"):
+        mix_form = None   # dense operators always use the direct form
+    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form)
     elems = w["n"] * w["d"]
     kernels = res["kernels"]
     timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
@@ -284,7 +291,7 @@ def main():
                    "step": ("choco_sgd_step + choco_gossip_step" if args.unfused else
                             "choco_step (= choco_sgd_step + choco_gossip_step, local update fused "
                             "into the first pass)"),
-                   "order": "compress_then_mix"},
+                   "order": "compress_then_mix", "mix": args.mix},
         "element_updates_per_s": res["steps_per_s"] * elems,
         "step_alg_bytes_per_elem": bpe,
         "step_alg_GBps": bpe * elems * res["steps_per_s"] / 1e9,
@@ -304,7 +311,8 @@ def main():
             if name == args.workload:
                 continue
             k = min(args.steps, 100)
-            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused)
+            omix = None if ow["comp"] in ("sign", "qsgd") else mix_form
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix)
             b = step_bytes_per_elem(ow, r["kernels"])
             e = ow["n"] * ow["d"]
             others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],

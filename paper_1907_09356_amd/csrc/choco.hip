@@ -27,6 +27,7 @@ struct choco_ctx {
   int mix_form;           // resolved: CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT
   int rpw;                // rows per wave of the tile kernels, 0 = tile does not fit
   bool fused;             // the step being enqueued carries the local update in its first pass
+  bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   uint64_t t;             // step counter
   double* metrics_part;   // device scratch of the metrics kernels
@@ -50,9 +51,10 @@ constexpr int kMaxTileRows = 64;  // n * 1 KiB of LDS for the tile of all rows
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, keptmap,
+  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, keptmap, bitmap,
       mpart, mout, total;
   uint32_t cand_cap, seg_cap;
+  int64_t bitmap_words;
   int32_t nchunks, ngroups;
 };
 
@@ -128,7 +130,11 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.cand = take(sparse ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(float) : 0);
-  L.keptmap = take(sparse ? (size_t)c.n * (size_t)ld : 0);
+  // kept entries: a bitmap per worker if it fits in the select block's LDS (40 KiB beside its
+  // other arrays), else one byte per entry
+  L.bitmap_words = (sparse && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
+  L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
+  L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -234,42 +240,45 @@ dim3 chunk_grid(int32_t nvec, int32_t n, int vecs) {
   return dim3((unsigned)(((int64_t)nvec + per_block - 1) / per_block), (unsigned)n, 1);
 }
 
+// Tile kernels: waves per block (4 up to 16 workers, else 16) and rows per wave.
 int pick_rpw(int n) {
   if (n > kMaxTileRows) return 0;
-  const int rows = (n + 3) / 4;
-  if (rows <= 1) return 1;
-  if (rows <= 2) return 2;
-  if (rows <= 4) return 4;
-  if (rows <= 8) return 8;
-  return 16;
+  const int nw = n <= 16 ? 4 : 16;
+  const int rows = (n + nw - 1) / nw;
+  return rows <= 1 ? 1 : rows <= 2 ? 2 : 4;
 }
 
-// Dispatch on the run-time rows-per-wave and the non-temporal flag.
-#define RPW_SWITCH(rpw, CALL)        \
-  switch (rpw) {                     \
-    case 1: CALL(1); break;          \
-    case 2: CALL(2); break;          \
-    case 4: CALL(4); break;          \
-    case 8: CALL(8); break;          \
-    default: CALL(16); break;        \
+#define TILE_SWITCH(n, rpw, CALL)                      \
+  if ((n) <= 16) {                                     \
+    switch (rpw) {                                     \
+      case 1: CALL(1, 4); break;                       \
+      case 2: CALL(2, 4); break;                       \
+      default: CALL(4, 4); break;                      \
+    }                                                  \
+  } else {                                             \
+    switch (rpw) {                                     \
+      case 1: CALL(1, 16); break;                      \
+      case 2: CALL(2, 16); break;                      \
+      default: CALL(4, 16); break;                     \
+    }                                                  \
   }
 
 template <int COMP, bool CAPTURE, bool NT>
 void launch_apply_mix(choco_ctx* ctx, const Args& A) {
-  const dim3 grid((unsigned)A.nchunks), block(kTileThreads);
+  const dim3 grid((unsigned)A.nchunks), block(A.n <= 16 ? 256 : 1024);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
-#define CALL(R) LAUNCH(ctx, KID_DENSE_APPLY_MIX, (k_dense_apply_mix<COMP, R, CAPTURE, NT>), grid, block, lds, A)
-  RPW_SWITCH(ctx->rpw, CALL)
+#define CALL(R, W) LAUNCH(ctx, KID_DENSE_APPLY_MIX, (k_dense_apply_mix<COMP, R, W, CAPTURE, NT>), grid, block, lds, A)
+  TILE_SWITCH(A.n, ctx->rpw, CALL)
 #undef CALL
 }
 
 template <int STAT, bool NT>
 void launch_tile_mix(choco_ctx* ctx, const Args& A, bool fused) {
-  const dim3 grid((unsigned)A.nchunks), block(kTileThreads);
+  const dim3 grid((unsigned)A.nchunks), block(A.n <= 16 ? 256 : 1024);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
   const int kid = fused ? KID_TILE_MIX_SGD : KID_TILE_MIX;
-#define CALL(R) LAUNCH(ctx, kid, (k_tile_mix<STAT, R, NT>), grid, block, lds, A)
-  RPW_SWITCH(ctx->rpw, CALL)
+#define CALL(R, W) LAUNCH(ctx, kid, (k_tile_mix<STAT, R, W, NT>), grid, block, lds, A)
+  TILE_SWITCH(A.n, ctx->rpw, CALL)
 #undef CALL
 }
 
@@ -335,8 +344,10 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
 template <int COMP, bool NT>
 int gossip_sparse(choco_ctx* ctx, const Args& F) {
   Args A = F;
-  A.G = nullptr;
-  const bool fused = F.G != nullptr;
+  // a deferred local update (random_a) keeps G visible to the kernels that gather single
+  // entries of x; otherwise only the first pass may see it
+  if (!F.deferred_sgd) A.G = nullptr;
+  const bool fused = F.G != nullptr && !F.deferred_sgd;
   const int32_t nvec = (A.d + 3) >> 2;
   const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
   const dim3 cgrid = chunk_grid(nvec, A.n, kCompactVecs);
@@ -363,11 +374,14 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, C);
   else
     LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT>), cgrid, dim3(256), 0, C);
-  const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
-  LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
-  LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-  LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
-  LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+  if (ctx->fallback_chain) {
+    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
+    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
+  }
+  LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
+         (size_t)A.bitmap_words * sizeof(uint32_t), A);
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
   if (incremental)
@@ -375,8 +389,14 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
            0, A);
   LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
-    if (incremental) LAUNCH(ctx, KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0, A);
-    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, A, false);
+    // random_a under choco_step: the deferred local update rides on this last pass
+    const bool last_carries = F.deferred_sgd != 0;
+    Args L = A;
+    if (last_carries) L.G = F.G;
+    if (incremental)
+      LAUNCH(ctx, last_carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
+             dim3(256), 0, L);
+    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, L, last_carries);
     else launch_mix_direct_global(ctx, A);
   }
   LAUNCH_CHECK(ctx);
@@ -417,12 +437,20 @@ int launch_sgd(choco_ctx* ctx, const float* g_dev, float lr) {
   return CHOCO_OK;
 }
 
-int run_gossip(choco_ctx* ctx, const float* fused_g, float lr) {
+// Under choco_step with random_a in the compress-then-mix order nothing reads X densely
+// before the final mix, so the local update is deferred into that mix.
+bool last_pass_carries_sgd(const choco_ctx* ctx) {
+  return ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
+         (ctx->mix_form == CHOCO_MIX_INCREMENTAL_S || ctx->rpw != 0);
+}
+
+int run_gossip(choco_ctx* ctx, const float* fused_g, float lr, bool deferred = false) {
   Args A = ctx->args;
   A.t_lo = (uint32_t)(ctx->t & 0xFFFFFFFFu);
   A.t_hi = (uint32_t)(ctx->t >> 32);
   A.G = fused_g;
   A.lr = lr;
+  A.deferred_sgd = deferred ? 1 : 0;
   ctx->fused = fused_g != nullptr;
   const int rc = ctx->nt ? gossip_any<true>(ctx, A) : gossip_any<false>(ctx, A);
   ctx->fused = false;
@@ -481,6 +509,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sparse = is_sparse(cfg->compressor);
   ctx->mix_form = resolve_mix_form(*cfg);
   ctx->rpw = pick_rpw(cfg->n);
+  // A failed guess (first step, or the distribution moved) is repaired by three extra passes
+  // (sampled histogram, new guess, rebuild) that are launched every step and normally exit at
+  // once.  For short rows even those idle launches show, and the select kernel's own row scan
+  // (one block per worker) is quick enough, so they are left out.
+  ctx->fallback_chain = cfg->d > ((int64_t)1 << 21);
   // Non-temporal accesses for all but tiny states: measured faster even when the state
   // would fit in cache (a kernel boundary on this multi-die part writes dirty L2 lines
   // back anyway); the cached path stays for states under 4 MB per array.
@@ -564,6 +597,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
   A.keptmap = (uint8_t*)(base + L.keptmap);
+  A.bitmap = (uint32_t*)(base + L.bitmap);
+  A.bitmap_words = L.bitmap_words;
   A.randk_rescale = cfg->randk_rescale ? 1 : 0;
   A.randk_scale = ctx->sparse ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
@@ -614,6 +649,7 @@ int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
 int choco_step(choco_ctx* ctx, const float* g_dev, float lr) {
   if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
   if (first_pass_can_carry_sgd(ctx)) return run_gossip(ctx, g_dev, lr);
+  if (last_pass_carries_sgd(ctx)) return run_gossip(ctx, g_dev, lr, true);
   const int rc = launch_sgd(ctx, g_dev, lr);
   if (rc != CHOCO_OK) return rc;
   return run_gossip(ctx, nullptr, 0.0f);

@@ -33,7 +33,6 @@ constexpr int kBins = 2048;       // radix-select digits are at most 11 bits wid
 constexpr int kBins16 = 65536;    // first digit of the fallback histogram (16 bits)
 constexpr int kChunk = 256;       // entries per first-level norm chunk / tile width
 constexpr int kGroup = 64;        // chunks per second-level group
-constexpr int kTileThreads = 256;
 constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kernels
 constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass
 constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
@@ -78,6 +77,7 @@ struct Args {
   // also does x <- x - lr * g (Algorithm 1 line 9) before using x
   const float* G;
   float lr;
+  int32_t deferred_sgd;  // the local update is applied by the LAST kernel of the step (random_a)
   // dense operators
   double* chunk_sums;  // n x nchunks first-level sums (only the printed-order tile kernel writes them)
   double* group_sums;  // n x ngroups second-level sums
@@ -101,6 +101,8 @@ struct Args {
   int32_t* sel_idx;    // n x k
   float* sel_val;      // n x k
   uint8_t* keptmap;    // n x ld bytes: byte e of row j non-zero <=> worker j kept entry e this step
+  uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
+  int64_t bitmap_words;  // 0: use the byte map
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
   // randomness
@@ -126,6 +128,14 @@ __device__ __forceinline__ vf4 sgd4(vf4 x, const vf4& g, float lr) {
 #pragma unroll
   for (int c = 0; c < 4; ++c) x[c] = x[c] - lr * g[c];
   return x;
+}
+// One entry of x as this step sees it.  random_a under choco_step: no pass reads X before
+// the final mix, so the local update is folded into that mix and the few entries that the
+// select and the scatter gather are updated on the fly (same product, same difference).
+template <class ArgsT>
+__device__ __forceinline__ float x_entry(const ArgsT& A, int64_t o) {
+  const float x = A.X[o];
+  return A.deferred_sgd ? x - A.lr * A.G[o] : x;
 }
 __device__ __forceinline__ vf4 lds_load4(const float* p) { return *reinterpret_cast<const vf4*>(p); }
 __device__ __forceinline__ void lds_store4(float* p, vf4 v) { *reinterpret_cast<vf4*>(p) = v; }
@@ -432,15 +442,16 @@ __global__ __launch_bounds__(256) void k_group_reduce(Args A) {
 // workers that mix with it:
 //   phase 1  q = Q(x - xhat), xhat += q   (Algorithm 1 lines 3-6), new xhat -> HBM + LDS
 //   phase 2  x += gamma * sum_p w_p (xhat_j - xhat_i)   (line 2), CSR order, from LDS
-// Wave w owns rows w, w+4, ...; RPW = rows per wave (compile-time bound, x stays
-// in registers between the phases).  Dynamic LDS: n * 256 floats.
+// A block has NW waves (4 for n <= 16, else 16); wave w owns rows w, w+NW, ...; RPW = rows
+// per wave (compile-time bound, x stays in registers between the phases).  Dynamic LDS:
+// n * 256 floats (64 KiB at n = 64: two 1024-thread blocks per CU keep it fully occupied).
 // ---------------------------------------------------------------------------
-template <int RPW>
+template <int RPW, int NW>
 __device__ __forceinline__ void tile_mix_rows(const Args& A, const float* tile, int wave, int lane,
                                               bool valid, vf4 (&xr)[RPW]) {
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n && valid) {
       const vf4 me = lds_load4(tile + r * kChunk + lane * 4);
       vf4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -457,8 +468,8 @@ __device__ __forceinline__ void tile_mix_rows(const Args& A, const float* tile, 
   }
 }
 
-template <int COMP, int RPW, bool CAPTURE, bool NT>
-__global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
+template <int COMP, int RPW, int NW, bool CAPTURE, bool NT>
+__global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
@@ -466,7 +477,7 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
   vf4 xr[RPW], xh[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n && valid) {
       const int64_t o = (int64_t)r * A.ld + e;
       xr[q] = load4<NT>(A.X + o);
@@ -477,7 +488,7 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
   RowScale<COMP> sc[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n) {
       if ((COMP == Q_SIGN || COMP == Q_QSGD) && A.fold_finalise) {
         const double total = wave_level3(A, r, lane);
@@ -489,7 +500,7 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
   }
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n) {
       vf4 nh = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
@@ -505,10 +516,10 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
     }
   }
   __syncthreads();
-  tile_mix_rows<RPW>(A, tile, wave, lane, valid, xr);
+  tile_mix_rows<RPW, NW>(A, tile, wave, lane, valid, xr);
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n && valid) store4<NT>(A.X + (int64_t)r * A.ld + e, xr[q]);
   }
 }
@@ -519,8 +530,8 @@ __global__ __launch_bounds__(kTileThreads) void k_dense_apply_mix(Args A) {
 // printed order (mix, then compress).  Same tiling as above; the tile is one
 // first-level norm chunk, so the chunk sum falls out of one wave butterfly.
 // ---------------------------------------------------------------------------
-template <int STAT, int RPW, bool NT>
-__global__ __launch_bounds__(kTileThreads) void k_tile_mix(Args A) {
+template <int STAT, int RPW, int NW, bool NT>
+__global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
@@ -528,7 +539,7 @@ __global__ __launch_bounds__(kTileThreads) void k_tile_mix(Args A) {
   vf4 xr[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n) {
       vf4 xh = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
@@ -541,10 +552,10 @@ __global__ __launch_bounds__(kTileThreads) void k_tile_mix(Args A) {
     }
   }
   __syncthreads();
-  tile_mix_rows<RPW>(A, tile, wave, lane, valid, xr);
+  tile_mix_rows<RPW, NW>(A, tile, wave, lane, valid, xr);
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
-    const int r = wave + 4 * q;
+    const int r = wave + NW * q;
     if (r < A.n) {
       double t = 0.0;
       if (valid) {
@@ -879,7 +890,7 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
     // an exact histogram knows whether the rebuilt list fits; a sampled one lets the
     // rebuild find out (the select then scans the row if it does not)
     ctl->mode = (A.sample_stride > 1u || listed <= (uint64_t)A.cand_cap) ? 1u : 2u;
-    ctl->fallbacks += 1;
+    if (ctl->mode == 1u) ctl->fallbacks += 1;
     if (ctl->mode == 1u)
       for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
   }
@@ -894,7 +905,7 @@ __device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint
   idx = t;
   if (COMP == Q_TOPK) {
     const int64_t o = (int64_t)i * A.ld + t;
-    a = __float_as_uint(A.X[o] - A.Xhat[o]);
+    a = __float_as_uint(A.X[o] - A.Xhat[o]);   // top_a never defers the local update
   } else {
     const uint4 wds = random_words(A, i, t >> 2, STREAM_RANDK);
     a = ~pick(wds, (int)(t & 3u));
@@ -970,9 +981,58 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uin
 
 // Hand one kept entry to the message list of worker i (wave-aggregated slot).
 // Every lane of the wave must call it (keep = false for lanes with nothing).
+// Record that worker i kept entry idx: in the block's LDS bitmap when the row is short
+// enough to have one (it is copied to global memory at the end), else as a byte of the
+// kept-map (plain store: no two kept entries share a byte).
+__device__ __forceinline__ void mark_kept(const Args& A, int i, uint32_t idx, uint32_t* lbits) {
+  if (A.bitmap_words) atomicOr(&lbits[idx >> 5], 1u << (idx & 31u));
+  else A.keptmap[(int64_t)i * A.ld + idx] = 1;
+}
+
+// Did worker j keep entry e in this step?
+__device__ __forceinline__ bool was_kept(const Args& A, int j, int e) {
+  if (A.bitmap_words) return (A.bitmap[(int64_t)j * A.bitmap_words + ((uint32_t)e >> 5)] >> ((uint32_t)e & 31u)) & 1u;
+  return A.keptmap[(int64_t)j * A.ld + e] != 0;
+}
+
+// random_a: the kept values q = x - xhat (rescaled on request) are gathered by the whole
+// block once the indices are known (k independent random reads, not one chain per wave).
+// Call after a __syncthreads() that follows the last emit_entry.
+template <int COMP>
+__device__ __forceinline__ void gather_values(const Args& A, int i) {
+  if (COMP != Q_RANDK) return;
+  for (int64_t base = 0; base < A.k; base += 4 * (int64_t)blockDim.x) {
+    int64_t o[4];
+    float xv[4], hv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t m = base + u * (int64_t)blockDim.x + threadIdx.x;
+      o[u] = m < A.k ? (int64_t)i * A.ld + A.sel_idx[(int64_t)i * A.k + m] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (o[u] >= 0) { xv[u] = x_entry(A, o[u]); hv[u] = A.Xhat[o[u]]; }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t m = base + u * (int64_t)blockDim.x + threadIdx.x;
+      if (o[u] >= 0) {
+        float val = xv[u] - hv[u];
+        if (A.randk_rescale) val = A.randk_scale * val;
+        A.sel_val[(int64_t)i * A.k + m] = val;
+      }
+    }
+  }
+}
+
+// Copy the block's LDS bitmap of kept entries to global memory (rows short enough to have one).
+__device__ __forceinline__ void publish_bitmap(const Args& A, int i, const uint32_t* lbits) {
+  for (int64_t wd = threadIdx.x; wd < A.bitmap_words; wd += blockDim.x)
+    A.bitmap[(int64_t)i * A.bitmap_words + wd] = lbits[wd];
+}
+
 template <int COMP>
 __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint32_t a, uint32_t idx,
-                                           uint32_t* s_emit) {
+                                           uint32_t* s_emit, uint32_t* lbits) {
   const uint64_t mask = __ballot(keep);
   if (mask == 0) return;
   const int lane = threadIdx.x & 63;
@@ -983,17 +1043,10 @@ __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint
   if (keep) {
     const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
     if (slot < (uint32_t)A.k) {
-      float val;
-      if (COMP == Q_TOPK) {
-        val = __uint_as_float(a);
-      } else {
-        const int64_t o = (int64_t)i * A.ld + idx;
-        val = A.X[o] - A.Xhat[o];
-        if (A.randk_rescale) val = A.randk_scale * val;
-      }
+      // top_a carries the value in the entry; random_a gathers it afterwards (gather_values)
       A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
-      A.sel_val[(int64_t)i * A.k + slot] = val;
-      A.keptmap[(int64_t)i * A.ld + idx] = 1;   // plain byte store: no two kept entries share a byte
+      if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
+      mark_kept(A, i, idx, lbits);
     }
   }
 }
@@ -1003,12 +1056,15 @@ __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint
 // guess and T, holds `want` entries (for top_a the k entries kept now leave the
 // race, so want includes k).  Also resets the per-step counters.
 __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64_t kstar, uint32_t total,
-                                           bool from_list, uint32_t emitted, uint32_t mode) {
+                                           bool from_list, uint32_t emitted, uint32_t mode,
+                                           bool have_floor = false, uint32_t floor_key = 0) {
   const uint32_t T = (uint32_t)(kstar >> 32);
   const uint32_t G = ctl->guess_key;
   uint64_t delta = A.delta0;
   if (from_list && total > (uint32_t)A.k && T > G)
     delta = (uint64_t)(T - G) * (uint64_t)A.want / (uint64_t)(total - (uint32_t)A.k);
+  else if (have_floor && T > floor_key)
+    delta = (uint64_t)(T - floor_key);   // row scan: the first-digit histogram located rank k + want
   if (delta < 1) delta = 1;
   if (delta > 0xFFFFFFFFull) delta = 0xFFFFFFFFull;
   ctl->guess_key = delta >= (uint64_t)T ? 0u : T - (uint32_t)delta;
@@ -1018,16 +1074,18 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   ctl->kstar = kstar;
   ctl->kept = emitted;
   ctl->mode = mode;
+  if (mode == 2u) ctl->fallbacks += 1;
   for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
 }
 
 template <int COMP, bool ROW>
 __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint32_t total, uint32_t* h,
                                 uint32_t* grp, uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
-                                uint32_t* s_above, uint32_t* s_emit) {
+                                uint32_t* s_above, uint32_t* s_emit, uint32_t* lbits) {
   WorkerCtl* ctl = A.ctl + i;
   int last = 0;
   bool done = false;
+  uint32_t floor_key = 0;
   for (int level = 0; level < 6 && !done; ++level) {
     for (int b = threadIdx.x; b < kBins; b += blockDim.x) h[b] = 0;
     __syncthreads();
@@ -1042,6 +1100,15 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
       if (match) atomicAdd(&h[(uint32_t)(K >> scur) & mask], 1u);
     });
     __syncthreads();
+    if (ROW && level == 0) {
+      // whole-row histogram of the first digit: also tells where rank k + want lies, which
+      // becomes the floor of the next step's guess
+      uint64_t target = (uint64_t)A.k + (uint64_t)A.want;
+      if (target > (uint64_t)A.d) target = (uint64_t)A.d;
+      find_digit(h, grp, (uint32_t)target, s_digit, s_above);
+      floor_key = (uint32_t)(((uint64_t)*s_digit << scur) >> 32);
+      __syncthreads();
+    }
     find_digit(h, grp, *s_need, s_digit, s_above);
     const uint32_t digit = *s_digit, above = *s_above;
     const uint32_t in_digit = h[digit];
@@ -1061,22 +1128,17 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
     if (Digits<COMP>::composite(a, idx) >= kstar) {
       const uint32_t slot = atomicAdd(s_emit, 1u);
       if (slot < (uint32_t)A.k) {
-        float val;
-        if (COMP == Q_TOPK) {
-          val = __uint_as_float(a);
-        } else {
-          const int64_t o = (int64_t)i * A.ld + idx;
-          val = A.X[o] - A.Xhat[o];
-          if (A.randk_rescale) val = A.randk_scale * val;
-        }
         A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
-        A.sel_val[(int64_t)i * A.k + slot] = val;
-        A.keptmap[(int64_t)i * A.ld + idx] = 1;
+        if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
+        mark_kept(A, i, idx, lbits);
       }
     }
   });
   __syncthreads();
-  if (threadIdx.x == 0) next_guess(A, ctl, kstar, total, !ROW, *s_emit, ROW ? 2u : 0u);
+  gather_values<COMP>(A, i);
+  publish_bitmap(A, i, lbits);
+  __syncthreads();
+  if (threadIdx.x == 0) next_guess(A, ctl, kstar, total, !ROW, *s_emit, ROW ? 2u : 0u, ROW, floor_key);
 }
 
 // Exact selection from the candidates, emission of the kept (index, value) pairs
@@ -1095,9 +1157,11 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __shared__ uint2 small[kSmallCap];
   __shared__ uint64_t s_prefix, s_kstar;
   __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good, s_small;
+  extern __shared__ uint32_t lbits[];   // bitmap_words words: kept entries of this worker (short rows)
   const int i = blockIdx.x;
   WorkerCtl* ctl = A.ctl + i;
   for (int b = threadIdx.x; b < kBins; b += 1024) h[b] = 0;
+  for (int64_t wd = threadIdx.x; wd < A.bitmap_words; wd += 1024) lbits[wd] = 0;
   if (threadIdx.x == 0) {
     s_prefix = 0;
     s_need = (uint32_t)A.k;
@@ -1117,7 +1181,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
-    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
     return;
   }
   const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
@@ -1156,7 +1220,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   const uint32_t in_bin = h[tbin];
   if (in_bin > (uint32_t)kSmallCap) {
     __syncthreads();
-    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit);
+    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
     return;
   }
   // sweep 2: emit everything above the threshold bin, collect the bin itself
@@ -1180,7 +1244,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
           if (pos < (uint32_t)kSmallCap) small[pos] = c[u];
         }
       }
-      emit_entry<COMP>(A, i, above, c[u].x, c[u].y, &s_emit);
+      emit_entry<COMP>(A, i, above, c[u].x, c[u].y, &s_emit, lbits);
     }
   }
   __syncthreads();
@@ -1200,9 +1264,11 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
       keep = rank < need_in_bin;
       if (rank + 1u == need_in_bin) s_kstar = K;
     }
-    emit_entry<COMP>(A, i, keep, mine.x, mine.y, &s_emit);
+    emit_entry<COMP>(A, i, keep, mine.x, mine.y, &s_emit, lbits);
   }
   __syncthreads();
+  gather_values<COMP>(A, i);
+  publish_bitmap(A, i, lbits);
   if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, s_emit, 0u);
 }
 
@@ -1221,15 +1287,15 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   const int j = A.col[p];
   const int e = A.sel_idx[(int64_t)j * A.k + m];
   for (int p2 = pbeg; p2 < p; ++p2)
-    if (A.keptmap[(int64_t)A.col[p2] * A.ld + e]) return;
+    if (was_kept(A, A.col[p2], e)) return;
   float* s = A.S + (int64_t)i * A.ld + e;
   float acc = *s;
   acc = acc + A.w[p] * A.sel_val[(int64_t)j * A.k + m];
   for (int p2 = p + 1; p2 < pend; ++p2) {
     const int j2 = A.col[p2];
-    if (A.keptmap[(int64_t)j2 * A.ld + e]) {
+    if (was_kept(A, j2, e)) {
       const int64_t o = (int64_t)j2 * A.ld + e;
-      float q = A.X[o] - A.Xhat[o];
+      float q = x_entry(A, o) - A.Xhat[o];
       if (A.randk_rescale) q = A.randk_scale * q;
       acc = acc + A.w[p2] * q;
     }
@@ -1246,7 +1312,7 @@ __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int e = A.sel_idx[(int64_t)j * A.k + m];
   float* xh = A.Xhat + (int64_t)j * A.ld + e;
   *xh = *xh + A.sel_val[(int64_t)j * A.k + m];
-  A.keptmap[(int64_t)j * A.ld + e] = 0;
+  if (!A.bitmap_words) A.keptmap[(int64_t)j * A.ld + e] = 0;   // the bitmap is rewritten whole every step
 }
 
 // ---------------------------------------------------------------------------
