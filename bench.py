@@ -180,6 +180,10 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None):
                 entry["alg_GBps"] = bpe * elems / (avg_ms * 1e-3) / 1e9
             kernels[name] = entry
         out["kernels"] = kernels
+    if w["comp"] in ("topk", "randk"):
+        sc = ctx.last_scalars()
+        out["select"] = dict(fallback_steps=int(sc[:, 4].max()), last_mode=int(sc[:, 3].max()),
+                             candidates_per_worker=float(sc[:, 5].mean()), k=w["k"])
     m = ctx.metrics()
     out["consensus_error"] = m["consensus"]
     out["mean_norm"] = m["mean_norm"]
@@ -303,6 +307,8 @@ def main():
         "consensus_error": res["consensus_error"],
         "device_copy_reference": copy_ref,
     }
+    if "select" in res:
+        line["select"] = res["select"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     if args.all:
@@ -320,6 +326,7 @@ def main():
                                element_updates_per_s=r["steps_per_s"] * e,
                                step_alg_bytes_per_elem=b,
                                step_alg_GBps=b * e * r["steps_per_s"] / 1e9,
+                               select=r.get("select"),
                                kernels={kk: round(v["ms_per_step"], 6) for kk, v in r["kernels"].items()}))
         line["other_workloads"] = others
     print(json.dumps(line))

@@ -138,9 +138,11 @@ int choco_nsum(choco_ctx *ctx, float **s_dev);
    choco_set_capture: SIGN/QSGD only; while codes_dev is non-NULL every gossip step also
    writes the transmitted code of each entry there (n*ld int32: sign -> +1/-1, gsgd ->
    sig(v)*level).  NULL switches it off.
-   choco_last_scalars: 4 doubles per worker from the last step, sign: {||v||_1, scale, 0, 0},
-   gsgd: {sum v^2, ||v||_2, s/||v||_2, ||v||_2/(tau s)} (the last two as rounded to fp32);
-   TOPK/RANDK: {threshold key, tie cut-off index, kept count, 0}.  Synchronises. */
+   choco_last_scalars: 6 doubles per worker from the last step, sign: {||v||_1, scale, 0...},
+   gsgd: {sum v^2, ||v||_2, s/||v||_2, ||v||_2/(tau s), 0, 0} (the scales as rounded to fp32);
+   TOPK/RANDK: {threshold key, tie cut-off index, kept count, select mode of the last step
+   (0 = guessed threshold held, 1 = list rebuilt from the histogram, 2 = row scan), number of
+   steps so far that needed mode 1 or 2, length of the last candidate list}.  Synchronises. */
 int choco_last_selection(choco_ctx *ctx, int32_t *idx_dev, float *val_dev);
 int choco_set_capture(choco_ctx *ctx, int32_t *codes_dev);
 int choco_last_scalars(choco_ctx *ctx, double *scalars_host);

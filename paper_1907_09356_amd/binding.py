@@ -228,7 +228,7 @@ class Choco:
                "choco_set_capture")
 
     def last_scalars(self):
-        out = np.zeros((self.n, 4), dtype=np.float64)
+        out = np.zeros((self.n, 6), dtype=np.float64)
         _check(lib().choco_last_scalars(self.ctx, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))),
                "choco_last_scalars")
         return out

@@ -195,12 +195,12 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update",
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
@@ -384,6 +384,8 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
          (size_t)A.bitmap_words * sizeof(uint32_t), A);
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
+  if (COMP == Q_RANDK)
+    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (incremental)
     LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256),
            0, A);
@@ -730,9 +732,9 @@ int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
                               ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   for (int i = 0; i < A.n; ++i) {
-    double* o = scalars_host + 4 * i;
+    double* o = scalars_host + 6 * i;
     const WorkerCtl& c = ctl[(size_t)i];
-    o[0] = o[1] = o[2] = o[3] = 0.0;
+    o[0] = o[1] = o[2] = o[3] = o[4] = o[5] = 0.0;
     switch (ctx->cfg.compressor) {
       case CHOCO_Q_SIGN: o[0] = c.stat; o[1] = (double)c.scale_c; break;
       case CHOCO_Q_QSGD: o[0] = c.stat; o[1] = c.nrm; o[2] = (double)c.scale_r; o[3] = (double)c.scale_step; break;
@@ -741,7 +743,9 @@ int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
         o[0] = (double)(uint32_t)(c.kstar >> 32);
         o[1] = (double)(uint32_t)(~(uint32_t)(c.kstar & 0xFFFFFFFFu));
         o[2] = (double)c.kept;
-        o[3] = (double)c.mode;   // mode of the last step; fallbacks counts the histogram steps
+        o[3] = (double)c.mode;
+        o[4] = (double)c.fallbacks;
+        o[5] = (double)c.last_candidates;
         break;
       default: break;
     }

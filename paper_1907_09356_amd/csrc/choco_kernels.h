@@ -57,7 +57,8 @@ struct WorkerCtl {
   uint32_t mode;        // 0: candidate list is complete, 1: rebuild it, 2: scan the row
   uint32_t seg_count[kSegs];  // entries with key32 >= guess_key appended per sub-list (may exceed seg_cap)
   uint32_t kept;        // number of entries emitted by the last selection
-  uint32_t fallbacks;   // how many steps needed the histogram fallback (diagnostic)
+  uint32_t fallbacks;   // how many steps needed a fallback (histogram rebuild or row scan)
+  uint32_t last_candidates;  // length of the candidate list the last select worked on
   uint64_t kstar;       // composite key of the k-th largest entry: kept <=> key >= kstar
 };
 
@@ -995,35 +996,6 @@ __device__ __forceinline__ bool was_kept(const Args& A, int j, int e) {
   return A.keptmap[(int64_t)j * A.ld + e] != 0;
 }
 
-// random_a: the kept values q = x - xhat (rescaled on request) are gathered by the whole
-// block once the indices are known (k independent random reads, not one chain per wave).
-// Call after a __syncthreads() that follows the last emit_entry.
-template <int COMP>
-__device__ __forceinline__ void gather_values(const Args& A, int i) {
-  if (COMP != Q_RANDK) return;
-  for (int64_t base = 0; base < A.k; base += 4 * (int64_t)blockDim.x) {
-    int64_t o[4];
-    float xv[4], hv[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t m = base + u * (int64_t)blockDim.x + threadIdx.x;
-      o[u] = m < A.k ? (int64_t)i * A.ld + A.sel_idx[(int64_t)i * A.k + m] : -1;
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (o[u] >= 0) { xv[u] = x_entry(A, o[u]); hv[u] = A.Xhat[o[u]]; }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t m = base + u * (int64_t)blockDim.x + threadIdx.x;
-      if (o[u] >= 0) {
-        float val = xv[u] - hv[u];
-        if (A.randk_rescale) val = A.randk_scale * val;
-        A.sel_val[(int64_t)i * A.k + m] = val;
-      }
-    }
-  }
-}
-
 // Copy the block's LDS bitmap of kept entries to global memory (rows short enough to have one).
 __device__ __forceinline__ void publish_bitmap(const Args& A, int i, const uint32_t* lbits) {
   for (int64_t wd = threadIdx.x; wd < A.bitmap_words; wd += blockDim.x)
@@ -1043,7 +1015,7 @@ __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint
   if (keep) {
     const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
     if (slot < (uint32_t)A.k) {
-      // top_a carries the value in the entry; random_a gathers it afterwards (gather_values)
+      // top_a carries the value in the entry; random_a gathers it afterwards (k_sel_values)
       A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
       if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
       mark_kept(A, i, idx, lbits);
@@ -1073,6 +1045,7 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   ctl->bin_shift = lg > 10 ? (uint32_t)(lg - 10) : 0u;
   ctl->kstar = kstar;
   ctl->kept = emitted;
+  ctl->last_candidates = total;
   ctl->mode = mode;
   if (mode == 2u) ctl->fallbacks += 1;
   for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
@@ -1135,7 +1108,6 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
     }
   });
   __syncthreads();
-  gather_values<COMP>(A, i);
   publish_bitmap(A, i, lbits);
   __syncthreads();
   if (threadIdx.x == 0) next_guess(A, ctl, kstar, total, !ROW, *s_emit, ROW ? 2u : 0u, ROW, floor_key);
@@ -1267,9 +1239,22 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
     emit_entry<COMP>(A, i, keep, mine.x, mine.y, &s_emit, lbits);
   }
   __syncthreads();
-  gather_values<COMP>(A, i);
   publish_bitmap(A, i, lbits);
   if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, s_emit, 0u);
+}
+
+// random_a: the kept values q = x - xhat (rescaled on request) are gathered once the
+// indices are known; top_a carries the value in the candidate entry instead.  A launch of
+// its own so that the k*n random reads are spread over all CUs (inside the one-block-per-
+// worker select they took longer than the select itself).  grid (ceil(k/256), n)
+__global__ __launch_bounds__(256) void k_sel_values(Args A) {
+  const int j = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= A.k) return;
+  const int64_t o = (int64_t)j * A.ld + A.sel_idx[(int64_t)j * A.k + m];
+  float val = x_entry(A, o) - A.Xhat[o];
+  if (A.randk_rescale) val = A.randk_scale * val;
+  A.sel_val[(int64_t)j * A.k + m] = val;
 }
 
 // S_i[e] += sum_p w_p q_j[e] over the neighbours j = col[p] that kept entry e,
