@@ -27,6 +27,7 @@ struct choco_ctx {
   int mix_form;           // resolved: CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT
   int rpw;                // rows per wave of the tile kernels, 0 = tile does not fit
   bool fused;             // the step being enqueued carries the local update in its first pass
+  bool multipart;         // long candidate lists: the select runs as three multi-block launches
   bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   uint64_t t;             // step counter
@@ -51,10 +52,11 @@ constexpr int kMaxTileRows = 64;  // n * 1 KiB of LDS for the tile of all rows
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, sel_idx, sel_val, keptmap, bitmap,
+  size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       mpart, mout, total;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
+  bool multipart;
   int32_t nchunks, ngroups;
 };
 
@@ -86,6 +88,22 @@ int check_scalars(const choco_config* c) {
     return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
+
+// Candidates wanted beyond k so that the guess survives the step-to-step drift of the
+// threshold (top_a) or the binomial spread of the count (random_a).
+double extra_candidates(const choco_config& c) {
+  const double kk = (double)c.k;
+  return std::min(std::max(0.5 * kk, 6.0 * std::sqrt(kk) + 32.0), 2147483647.0);
+}
+
+// Entries the guess aims to leave above it beyond the k kept ones.  top_a: the k entries
+// kept in a step are absorbed by xhat and drop out, so the next step's k largest are (about)
+// this step's ranks k+1..2k; random_a draws afresh every step.
+double want_candidates(const choco_config& c) {
+  return extra_candidates(c) + (c.compressor == CHOCO_Q_TOPK ? (double)c.k : 0.0);
+}
+
+double expected_candidates(const choco_config& c) { return (double)c.k + want_candidates(c); }
 
 Layout make_layout(const choco_config& c, int32_t nnz) {
   Layout L{};
@@ -130,9 +148,12 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.cand = take(sparse ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(float) : 0);
-  // kept entries: a bitmap per worker if it fits in the select block's LDS (40 KiB beside its
-  // other arrays), else one byte per entry
-  L.bitmap_words = (sparse && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
+  L.multipart = sparse && expected_candidates(c) > 16384.0;
+  L.hist_parts = take(L.multipart ? (size_t)c.n * kRefineParts * kBins * sizeof(uint32_t) : 0);
+  L.small_list = take(L.multipart ? (size_t)c.n * kSmallCap * sizeof(uint2) : 0);
+  // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
+  // beside its other arrays), else one byte per entry
+  L.bitmap_words = (sparse && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
@@ -195,12 +216,12 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values",
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
@@ -380,8 +401,15 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
     LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
   }
-  LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
-         (size_t)A.bitmap_words * sizeof(uint32_t), A);
+  if (ctx->multipart) {
+    const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST_PARTS, (k_sel_hist_parts<COMP>), pgrid, dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_EMIT_PARTS, (k_sel_emit_parts<COMP>), pgrid, dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_FINISH, (k_sel_finish<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+  } else {
+    LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
+           (size_t)A.bitmap_words * sizeof(uint32_t), A);
+  }
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
   if (COMP == Q_RANDK)
@@ -559,15 +587,16 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.cand = (uint2*)(base + L.cand);
   A.cand_cap = L.cand_cap;
   A.seg_cap = L.seg_cap;
-  // candidates wanted beyond k so that the guess survives the step-to-step drift of
-  // the threshold (top_a) or the binomial spread of the count (random_a)
+  A.hist_parts = (uint32_t*)(base + L.hist_parts);
+  A.small_list = (uint2*)(base + L.small_list);
+  ctx->multipart = L.multipart;
   uint32_t guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
   uint32_t shift0 = 0;
   if (ctx->sparse) {
     const double kk = (double)cfg->k, dd = (double)cfg->d;
-    double extra = std::max(0.5 * kk, 6.0 * std::sqrt(kk) + 32.0);
-    if (extra > 2147483647.0) extra = 2147483647.0;
+    const double extra = extra_candidates(*cfg);
     A.extra = (uint32_t)extra;
+    A.want = (uint32_t)std::min(want_candidates(*cfg), 4294967295.0);
     if (cfg->compressor == CHOCO_Q_RANDK) {
       // keys are uniform on [0, 2^32): the k + extra largest start near (1 - (k+extra)/d) 2^32
       const double frac = std::min(1.0, (kk + extra) / dd);
@@ -581,9 +610,6 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     } else {
       A.delta0 = 1u << 19;   // about 6 % in magnitude
     }
-    // top_a: the k entries kept in a step are absorbed by xhat and drop out, so the next
-    // step's k largest are (about) this step's ranks k+1..2k; random_a draws afresh
-    A.want = A.extra + (cfg->compressor == CHOCO_Q_TOPK ? (uint32_t)std::min<int64_t>(cfg->k, 2000000000) : 0u);
     // fallback histogram: aim the rebuilt list at max(2k + extra, capacity / 4), at most
     // half the capacity, and sample the row so that the aim is still >= ~2000 samples
     double aim = std::max(2.0 * kk + extra, 0.25 * (double)L.cand_cap);

@@ -39,6 +39,7 @@ constexpr int kStageCap = 1024;   // candidates one block stages in LDS before i
 constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
 constexpr int kStatThreads = 1024;  // one wave per 4 chunks of a 64-chunk group
 constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
+constexpr int kRefineParts = 16;    // blocks per worker of the select when the candidate lists are long
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
 
 // Per-worker control block in device memory (written by small "finalise" code,
@@ -59,6 +60,8 @@ struct WorkerCtl {
   uint32_t kept;        // number of entries emitted by the last selection
   uint32_t fallbacks;   // how many steps needed a fallback (histogram rebuild or row scan)
   uint32_t last_candidates;  // length of the candidate list the last select worked on
+  uint32_t emit_count;  // multi-block select: kept entries emitted so far
+  uint32_t small_count; // multi-block select: entries of the threshold bin collected so far
   uint64_t kstar;       // composite key of the k-th largest entry: kept <=> key >= kstar
 };
 
@@ -92,6 +95,8 @@ struct Args {
   int64_t k;
   uint32_t* hist16;    // n x kBins16 (fallback histogram)
   uint2* cand;         // n x kSegs x seg_cap  (a, index)
+  uint32_t* hist_parts; // n x kRefineParts x kBins: per-block candidate histograms (multi-block select)
+  uint2* small_list;   // n x kSmallCap: entries of the threshold bin (multi-block select)
   uint32_t seg_cap;    // capacity of one sub-list
   uint32_t cand_cap;   // largest total the fallback aims to stay under
   uint32_t sample_stride;  // the fallback histogram looks at every sample_stride-th 4-vector
@@ -1002,6 +1007,49 @@ __device__ __forceinline__ void publish_bitmap(const Args& A, int i, const uint3
     A.bitmap[(int64_t)i * A.bitmap_words + wd] = lbits[wd];
 }
 
+// Lengths and prefix offsets of the candidate sub-lists of worker i (thread 0 writes them to
+// LDS; callers synchronise afterwards).  *good: the list holds the k largest entries.
+__device__ __forceinline__ void list_layout(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
+                                            uint32_t* total_out, uint32_t* good_out) {
+  uint32_t total = 0;
+  for (int s = 0; s < kSegs; ++s) {
+    const uint32_t c = ctl->seg_count[s];
+    lens[s] = c < A.seg_cap ? c : A.seg_cap;
+    pre[s] = total;
+    total += lens[s];
+  }
+  pre[kSegs] = total;
+  *total_out = total;
+  *good_out = list_is_good(ctl, A) ? 1u : 0u;
+}
+
+// Entry at flat position f of the concatenated sub-lists (pre = prefix offsets in LDS).
+__device__ __forceinline__ uint2 list_entry(const Args& A, int i, const uint32_t* pre, uint32_t f) {
+  int lo = 0;   // sub-list holding f: largest s with pre[s] <= f
+#pragma unroll
+  for (int step = kSegs / 2; step >= 1; step >>= 1)
+    if (pre[lo + step] <= f) lo += step;
+  return A.cand[((int64_t)i * kSegs + lo) * A.seg_cap + (f - pre[lo])];
+}
+
+// Bin of a candidate by its distance above the guess.
+template <int COMP>
+__device__ __forceinline__ uint32_t cand_bin(uint32_t a, uint32_t guess, uint32_t shift) {
+  const uint32_t bin = (Digits<COMP>::key32(a) - guess) >> shift;
+  return bin < (uint32_t)kBins ? bin : (uint32_t)kBins - 1u;
+}
+
+// Store one kept entry at a known slot of worker i's message list and mark it.
+template <int COMP>
+__device__ __forceinline__ void store_kept(const Args& A, int i, uint32_t slot, uint32_t a, uint32_t idx,
+                                           uint32_t* lbits) {
+  if (slot >= (uint32_t)A.k) return;
+  // top_a carries the value in the entry; random_a gathers it afterwards (k_sel_values)
+  A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
+  if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
+  mark_kept(A, i, idx, lbits);
+}
+
 template <int COMP>
 __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint32_t a, uint32_t idx,
                                            uint32_t* s_emit, uint32_t* lbits) {
@@ -1014,12 +1062,7 @@ __device__ __forceinline__ void emit_entry(const Args& A, int i, bool keep, uint
   base = __shfl(base, leader, 64);
   if (keep) {
     const uint32_t slot = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-    if (slot < (uint32_t)A.k) {
-      // top_a carries the value in the entry; random_a gathers it afterwards (k_sel_values)
-      A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
-      if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
-      mark_kept(A, i, idx, lbits);
-    }
+    store_kept<COMP>(A, i, slot, a, idx, lbits);
   }
 }
 
@@ -1047,6 +1090,8 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   ctl->kept = emitted;
   ctl->last_candidates = total;
   ctl->mode = mode;
+  ctl->emit_count = 0;
+  ctl->small_count = 0;
   if (mode == 2u) ctl->fallbacks += 1;
   for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
 }
@@ -1139,16 +1184,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
     s_need = (uint32_t)A.k;
     s_emit = 0;
     s_small = 0;
-    s_good = list_is_good(ctl, A) ? 1u : 0u;
-    uint32_t total = 0;
-    for (int s = 0; s < kSegs; ++s) {
-      const uint32_t c = ctl->seg_count[s];
-      lens[s] = c < A.seg_cap ? c : A.seg_cap;
-      pre[s] = total;
-      total += lens[s];
-    }
-    pre[kSegs] = total;
-    s_total = total;
+    list_layout(A, ctl, lens, pre, &s_total, &s_good);
   }
   __syncthreads();
   const uint32_t total = s_total;
@@ -1157,18 +1193,8 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
     return;
   }
   const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
-  // flat position f of the concatenated sub-lists -> entry
-  auto entry_at = [&](uint32_t f) -> uint2 {
-    int lo = 0;   // sub-list holding f: largest s with pre[s] <= f
-#pragma unroll
-    for (int step = kSegs / 2; step >= 1; step >>= 1)
-      if (pre[lo + step] <= f) lo += step;
-    return A.cand[((int64_t)i * kSegs + lo) * A.seg_cap + (f - pre[lo])];
-  };
-  auto bin_of = [&](uint32_t a) -> uint32_t {
-    const uint32_t bin = (Digits<COMP>::key32(a) - guess) >> shift;
-    return bin < (uint32_t)kBins ? bin : (uint32_t)kBins - 1u;
-  };
+  auto entry_at = [&](uint32_t f) -> uint2 { return list_entry(A, i, pre, f); };
+  auto bin_of = [&](uint32_t a) -> uint32_t { return cand_bin<COMP>(a, guess, shift); };
   // sweep 1: histogram of the candidates by their distance above the guess (eight
   // entries per thread in flight; a list of up to 8192 entries stays in registers)
   uint2 c[8];
@@ -1241,6 +1267,190 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __syncthreads();
   publish_bitmap(A, i, lbits);
   if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, s_emit, 0u);
+}
+
+// ---------------------------------------------------------------------------
+// Multi-block select for long candidate lists (k + want > 16384 per worker): the
+// one-block-per-worker kernel above would leave all but n CUs idle.  Three launches:
+//   k_sel_hist_parts  kRefineParts blocks per worker histogram a slice of the list each
+//   k_sel_emit_parts  every block sums the partial histograms, finds the threshold bin,
+//                     emits the entries of its slice above that bin (one global atomic per
+//                     block) and hands the entries inside the bin to a short global list
+//   k_sel_finish      one block per worker ranks that short list, emits the rest, places
+//                     the next guess; also takes the digit-by-digit and row-scan paths when
+//                     the threshold bin is crowded or the list is not good
+// grid (kRefineParts, n) for the first two, n for the last; block 1024.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void part_slice(uint32_t total, uint32_t part, uint32_t* lo, uint32_t* hi) {
+  const uint32_t per = (total + (uint32_t)kRefineParts - 1u) / (uint32_t)kRefineParts;
+  *lo = part * per < total ? part * per : total;
+  *hi = (part + 1u) * per < total ? (part + 1u) * per : total;
+}
+
+template <int COMP>
+__global__ __launch_bounds__(1024) void k_sel_hist_parts(Args A) {
+  __shared__ uint32_t h[kBins];
+  __shared__ uint32_t lens[kSegs];
+  __shared__ uint32_t pre[kSegs + 1];
+  __shared__ uint32_t s_total, s_good;
+  const int i = blockIdx.y;
+  const WorkerCtl* ctl = A.ctl + i;
+  for (int b = threadIdx.x; b < kBins; b += 1024) h[b] = 0;
+  if (threadIdx.x == 0) list_layout(A, ctl, lens, pre, &s_total, &s_good);
+  __syncthreads();
+  if (!s_good) return;
+  uint32_t lo, hi;
+  part_slice(s_total, blockIdx.x, &lo, &hi);
+  const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
+  for (uint32_t base = lo; base < hi; base += 1024u * 8u) {
+    uint2 c[8];
+    bool have[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
+      have[u] = f < hi;
+      if (have[u]) c[u] = list_entry(A, i, pre, f);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (have[u]) atomicAdd(&h[cand_bin<COMP>(c[u].x, guess, shift)], 1u);
+  }
+  __syncthreads();
+  uint32_t* out = A.hist_parts + ((int64_t)i * kRefineParts + blockIdx.x) * kBins;
+  for (int b = threadIdx.x; b < kBins; b += 1024) out[b] = h[b];
+}
+
+// Sum of the partial histograms of worker i into LDS (all threads; caller synchronises).
+__device__ __forceinline__ void sum_hist_parts(const Args& A, int i, uint32_t* h) {
+  for (int b = threadIdx.x; b < kBins; b += blockDim.x) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int p = 0; p < kRefineParts; ++p) acc += A.hist_parts[((int64_t)i * kRefineParts + p) * kBins + b];
+    h[b] = acc;
+  }
+}
+
+template <int COMP>
+__global__ __launch_bounds__(1024) void k_sel_emit_parts(Args A) {
+  __shared__ uint32_t h[kBins];
+  __shared__ uint32_t grp[256];
+  __shared__ uint32_t lens[kSegs];
+  __shared__ uint32_t pre[kSegs + 1];
+  __shared__ uint32_t s_total, s_good, s_digit, s_above, s_count, s_base;
+  const int i = blockIdx.y;
+  WorkerCtl* ctl = A.ctl + i;
+  if (threadIdx.x == 0) list_layout(A, ctl, lens, pre, &s_total, &s_good);
+  __syncthreads();
+  if (!s_good) return;
+  sum_hist_parts(A, i, h);
+  __syncthreads();
+  find_digit(h, grp, (uint32_t)A.k, &s_digit, &s_above);
+  const uint32_t tbin = s_digit;
+  if (h[tbin] > (uint32_t)kSmallCap) return;   // crowded threshold bin: k_sel_finish selects digit by digit
+  uint32_t lo, hi;
+  part_slice(s_total, blockIdx.x, &lo, &hi);
+  const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
+  const int lane = threadIdx.x & 63;
+  for (uint32_t base = lo; base < hi; base += 1024u * 8u) {
+    __syncthreads();
+    if (threadIdx.x == 0) s_count = 0;
+    __syncthreads();
+    uint2 c[8];
+    bool have[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
+      have[u] = f < hi;
+      if (have[u]) c[u] = list_entry(A, i, pre, f);
+    }
+    // which of my entries lie above the threshold bin; the bin's own entries go to the short list
+    uint64_t masks[8];
+    uint32_t wave_total = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      bool above = false;
+      if (have[u]) {
+        const uint32_t bin = cand_bin<COMP>(c[u].x, guess, shift);
+        above = bin > tbin;
+        if (bin == tbin) {
+          const uint32_t pos = atomicAdd(&ctl->small_count, 1u);
+          if (pos < (uint32_t)kSmallCap) A.small_list[(int64_t)i * kSmallCap + pos] = c[u];
+        }
+      }
+      masks[u] = __ballot(above);
+      wave_total += (uint32_t)__popcll(masks[u]);
+    }
+    // slots: wave offset inside the block through LDS, block offset through one global atomic
+    uint32_t wave_base = 0;
+    if (lane == 0 && wave_total) wave_base = atomicAdd(&s_count, wave_total);
+    wave_base = __shfl(wave_base, 0, 64);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_count) s_base = atomicAdd(&ctl->emit_count, s_count);
+    __syncthreads();
+    uint32_t running = s_base + wave_base;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if ((masks[u] >> lane) & 1ull) {
+        const uint32_t slot = running + (uint32_t)__popcll(masks[u] & ((1ull << lane) - 1ull));
+        store_kept<COMP>(A, i, slot, c[u].x, c[u].y, nullptr);
+      }
+      running += (uint32_t)__popcll(masks[u]);
+    }
+  }
+}
+
+template <int COMP>
+__global__ __launch_bounds__(1024) void k_sel_finish(Args A) {
+  __shared__ uint32_t h[kBins];
+  __shared__ uint32_t grp[256];
+  __shared__ uint32_t lens[kSegs];
+  __shared__ uint32_t pre[kSegs + 1];
+  __shared__ uint2 small[kSmallCap];
+  __shared__ uint64_t s_prefix, s_kstar;
+  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good;
+  const int i = blockIdx.x;
+  WorkerCtl* ctl = A.ctl + i;
+  if (threadIdx.x == 0) {
+    s_prefix = 0;
+    s_need = (uint32_t)A.k;
+    s_emit = 0;
+    list_layout(A, ctl, lens, pre, &s_total, &s_good);
+  }
+  __syncthreads();
+  const uint32_t total = s_total;
+  if (!s_good) {
+    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
+    return;
+  }
+  sum_hist_parts(A, i, h);
+  __syncthreads();
+  find_digit(h, grp, (uint32_t)A.k, &s_digit, &s_above);
+  const uint32_t tbin = s_digit, above = s_above;
+  const uint32_t need_in_bin = (uint32_t)A.k - above;
+  const uint32_t in_bin = h[tbin];
+  if (in_bin > (uint32_t)kSmallCap) {
+    __syncthreads();
+    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
+    return;
+  }
+  // the blocks of k_sel_emit_parts emitted `above` entries into slots 0..above-1 and collected
+  // the in_bin entries of the threshold bin; rank those and emit the need_in_bin largest
+  const uint32_t m = in_bin;
+  for (uint32_t t = threadIdx.x; t < m; t += 1024) small[t] = A.small_list[(int64_t)i * kSmallCap + t];
+  __syncthreads();
+  if (threadIdx.x < m) {
+    const uint2 mine = small[threadIdx.x];
+    const uint64_t K = Digits<COMP>::composite(mine.x, mine.y);
+    uint32_t rank = 0;
+    for (uint32_t u = 0; u < m; ++u) {
+      const uint2 o = small[u];
+      rank += Digits<COMP>::composite(o.x, o.y) > K ? 1u : 0u;
+    }
+    if (rank < need_in_bin) store_kept<COMP>(A, i, above + rank, mine.x, mine.y, nullptr);
+    if (rank + 1u == need_in_bin) s_kstar = K;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, above + need_in_bin, 0u);
 }
 
 // random_a: the kept values q = x - xhat (rescaled on request) are gathered once the

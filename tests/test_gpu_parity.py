@@ -133,6 +133,39 @@ def test_select_when_one_digit_overflows_the_candidate_list(comp):
         pair.close()
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp,k", [("topk", 8000), ("randk", 12000), ("randk_rescaled", 12000)])
+def test_long_candidate_lists_take_the_multi_block_select(comp, k, order):
+    # k + slack above 16384 candidates per worker: histogram parts, parallel emission, finish
+    n, d = 4, 200000
+    kw = dict(COMPRESSORS[comp])
+    pair = Pair(synth.normal_state(n, d, seed=6), synth.ring_csr(n), 0.2, k=k, order=order, seed=5, **kw)
+    grads = synth.GradientStream(n, d, seed=7)
+    try:
+        for t in range(5):
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="multi-block %s step %d" % (comp, t))
+    finally:
+        pair.close()
+
+
+def test_multi_block_select_with_crowded_threshold_bin_and_overflow():
+    # integer-valued state (thousands of ties around the threshold) and a constant state (one
+    # key for the whole row) with k large enough for the multi-block select: its finish kernel
+    # has to take the digit-by-digit path on the list, resp. the row scan
+    n, d, k = 3, 120000, 9000
+    rng = np.random.default_rng(8)
+    for X0 in (rng.integers(-4, 5, size=(n, d)).astype(np.float32),
+               np.full((n, d), -2.5, dtype=np.float32)):
+        pair = Pair(X0, synth.ring_csr(n), 0.25, compressor=B.Q_TOPK, k=k)
+        try:
+            for t in range(3):
+                det = pair.gossip_step()
+                pair.check(det, tag="multi-block ties step %d" % t)
+        finally:
+            pair.close()
+
+
 def test_guess_survives_a_sudden_change_of_scale():
     # the first digit of the threshold jumps by many bins between steps in both directions
     n, d, k = 4, 20000, 200
