@@ -131,13 +131,15 @@ def calibration_copy(torch, nbytes=896_000_000, reps=10):
     return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9)
 
 
-def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None):
+def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=None):
     import torch
     from paper_1907_09356_amd import binding as B
     X, pool = device_inputs(w, torch)
     kw = comp_kwargs(w, B)
     if mix_form is not None:
         kw["mix_form"] = mix_form
+    if order is not None:
+        kw["order"] = order
     ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **kw)
 
     def one_step(t):
@@ -175,6 +177,9 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None):
             entry = dict(launches_per_step=count / steps, avg_ms=avg_ms,
                          ms_per_step=total_ms / steps)
             bpe = KERNEL_BYTES_PER_ELEM.get(name)
+            if (bpe is not None and name.startswith("k_sel_compact") and w["comp"] == "topk"
+                    and order == B.ORDER_MIX_THEN_COMPRESS and mix_form != B.MIX_DIRECT):
+                bpe += 4 if name.endswith("_sgd") else 8   # the mix rides on this pass: + read s (+ write x)
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
                 entry["alg_bytes_per_launch"] = bpe * elems
                 entry["alg_GBps"] = bpe * elems / (avg_ms * 1e-3) / 1e9
@@ -251,6 +256,9 @@ def main():
     ap.add_argument("--mix", choices=["auto", "incremental", "direct"], default="auto",
                     help="evaluation of the mix: auto = incremental neighbour sums for top-k/random-k "
                          "(the library default), direct = LDS-tiled, no S array")
+    ap.add_argument("--order", choices=["compress_then_mix", "mix_then_compress"],
+                    default="compress_then_mix",
+                    help="order of the two halves of the gossip step (the second is Algorithm 1 as printed)")
     ap.add_argument("--unfused", action="store_true",
                     help="call choco_sgd_step + choco_gossip_step instead of the fused choco_step")
     args = ap.parse_args()
@@ -267,7 +275,9 @@ def main():
     mix_form = {"auto": None, "incremental": B.MIX_INCREMENTAL_S, "direct": B.MIX_DIRECT}[args.mix]
     if w["comp"] in ("sign", "qsgd"):
         mix_form = None   # dense operators always use the direct form
-    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form)
+    order = (B.ORDER_MIX_THEN_COMPRESS if args.order == "mix_then_compress"
+             else B.ORDER_COMPRESS_THEN_MIX)
+    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form, order=order)
     elems = w["n"] * w["d"]
     kernels = res["kernels"]
     timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
@@ -295,7 +305,7 @@ def main():
                    "step": ("choco_sgd_step + choco_gossip_step" if args.unfused else
                             "choco_step (= choco_sgd_step + choco_gossip_step, local update fused "
                             "into the first pass)"),
-                   "order": "compress_then_mix", "mix": args.mix},
+                   "order": args.order, "mix": args.mix},
         "element_updates_per_s": res["steps_per_s"] * elems,
         "step_alg_bytes_per_elem": bpe,
         "step_alg_GBps": bpe * elems * res["steps_per_s"] / 1e9,
@@ -312,13 +322,29 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     if args.all:
+        # the same workload in the other supported formulations (same results as the oracle's
+        # corresponding form): Algorithm 1's printed order, and the direct mix without S
+        alts = []
+        if w["comp"] in ("topk", "randk"):
+            variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=mix_form)),
+                        ("mix=direct", dict(order=order, mix_form=B.MIX_DIRECT))]
+        else:
+            variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=None))]
+        for label, kw in variants:
+            k = min(args.steps, 50)
+            r = run_gpu(w, k, min(args.warmup, 10), fused=not args.unfused, **kw)
+            b = step_bytes_per_elem(w, r["kernels"])
+            alts.append(dict(variant=label, steps=k, ms_per_step=r["ms_per_step"],
+                             steps_per_s=r["steps_per_s"], step_alg_bytes_per_elem=b,
+                             step_alg_GBps=b * elems * r["steps_per_s"] / 1e9))
+        line["alternatives"] = alts
         others = []
         for name, ow in WORKLOADS.items():
             if name == args.workload:
                 continue
             k = min(args.steps, 100)
             omix = None if ow["comp"] in ("sign", "qsgd") else mix_form
-            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix)
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix, order=order)
             b = step_bytes_per_elem(ow, r["kernels"])
             e = ow["n"] * ow["d"]
             others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],
