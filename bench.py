@@ -74,6 +74,15 @@ KERNEL_BYTES_PER_ELEM = {
 }
 
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
+# counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
+# WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
+MEASURED_TRAFFIC_BYTES = {
+    ("large_topk", "k_sel_compact_sgd"): 3_588_852_531,
+    ("large_topk", "k_mix_incremental"): 3_584_030_720,
+}
+
+
 def make_topology(w):
     from paper_1907_09356_amd import synth
     if w["topo"] == "ring":
@@ -286,7 +295,9 @@ def main():
     roofline = dict(bound="hbm", kernel=dominant, achieved=dk["alg_GBps"], peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=dk["alg_GBps"] / HBM_PEAK_GBS,
                     alg_bytes_per_launch=dk["alg_bytes_per_launch"], avg_launch_ms=dk["avg_ms"],
-                    traffic=None)
+                    traffic=(MEASURED_TRAFFIC_BYTES.get((args.workload, dominant))
+                             if args.mix == "auto" and args.order == "compress_then_mix" and not args.unfused
+                             else None))
     bpe = step_bytes_per_elem(w, kernels)
     line = {
         "metric": "choco_gossip_steps_per_s",
