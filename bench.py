@@ -140,7 +140,7 @@ def calibration_copy(torch, nbytes=896_000_000, reps=10):
     return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9)
 
 
-def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=None):
+def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=None, momentum=False):
     import torch
     from paper_1907_09356_amd import binding as B
     X, pool = device_inputs(w, torch)
@@ -150,9 +150,13 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
     if order is not None:
         kw["order"] = order
     ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **kw)
+    M = torch.zeros_like(X) if momentum else None   # momentum memory of Algorithm 2
 
     def one_step(t):
-        if fused:
+        if momentum:
+            # Algorithm 2 (momentum 0.9, weight decay 1e-4) + gossip step, fused
+            ctx.step_momentum(pool[t & 1], M, w["lr"], 0.9, 1e-4)
+        elif fused:
             ctx.step(pool[t & 1], w["lr"])      # choco_step = sgd step + gossip step in one call
         else:
             ctx.sgd_step(pool[t & 1], w["lr"])
@@ -189,6 +193,8 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
             if (bpe is not None and name.startswith("k_sel_compact") and w["comp"] == "topk"
                     and order == B.ORDER_MIX_THEN_COMPRESS and mix_form != B.MIX_DIRECT):
                 bpe += 4 if name.endswith("_sgd") else 8   # the mix rides on this pass: + read s (+ write x)
+            if bpe is not None and momentum and name.endswith("_sgd"):
+                bpe += 8                                   # + read and write the momentum memory
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
                 entry["alg_bytes_per_launch"] = bpe * elems
                 entry["alg_GBps"] = bpe * elems / (avg_ms * 1e-3) / 1e9
@@ -268,6 +274,8 @@ def main():
     ap.add_argument("--order", choices=["compress_then_mix", "mix_then_compress"],
                     default="compress_then_mix",
                     help="order of the two halves of the gossip step (the second is Algorithm 1 as printed)")
+    ap.add_argument("--momentum", action="store_true",
+                    help="local update = Algorithm 2 (momentum 0.9, weight decay 1e-4) via choco_step_momentum")
     ap.add_argument("--unfused", action="store_true",
                     help="call choco_sgd_step + choco_gossip_step instead of the fused choco_step")
     args = ap.parse_args()
@@ -286,7 +294,8 @@ def main():
         mix_form = None   # dense operators always use the direct form
     order = (B.ORDER_MIX_THEN_COMPRESS if args.order == "mix_then_compress"
              else B.ORDER_COMPRESS_THEN_MIX)
-    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form, order=order)
+    res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form, order=order,
+                  momentum=args.momentum)
     elems = w["n"] * w["d"]
     kernels = res["kernels"]
     timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
@@ -296,7 +305,7 @@ def main():
                     unit="GB/s", frac=dk["alg_GBps"] / HBM_PEAK_GBS,
                     alg_bytes_per_launch=dk["alg_bytes_per_launch"], avg_launch_ms=dk["avg_ms"],
                     traffic=(MEASURED_TRAFFIC_BYTES.get((args.workload, dominant))
-                             if args.mix == "auto" and args.order == "compress_then_mix" and not args.unfused
+                             if args.mix == "auto" and args.order == "compress_then_mix" and not args.unfused and not args.momentum
                              else None))
     bpe = step_bytes_per_elem(w, kernels)
     line = {
@@ -316,7 +325,8 @@ def main():
                    "step": ("choco_sgd_step + choco_gossip_step" if args.unfused else
                             "choco_step (= choco_sgd_step + choco_gossip_step, local update fused "
                             "into the first pass)"),
-                   "order": args.order, "mix": args.mix},
+                   "order": args.order, "mix": args.mix,
+                   "local_update": "momentum 0.9, weight decay 1e-4 (Algorithm 2)" if args.momentum else "sgd"},
         "element_updates_per_s": res["steps_per_s"] * elems,
         "step_alg_bytes_per_elem": bpe,
         "step_alg_GBps": bpe * elems * res["steps_per_s"] / 1e9,
@@ -343,7 +353,7 @@ def main():
             variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=None))]
         for label, kw in variants:
             k = min(args.steps, 50)
-            r = run_gpu(w, k, min(args.warmup, 10), fused=not args.unfused, **kw)
+            r = run_gpu(w, k, min(args.warmup, 10), fused=not args.unfused, momentum=args.momentum, **kw)
             b = step_bytes_per_elem(w, r["kernels"])
             alts.append(dict(variant=label, steps=k, ms_per_step=r["ms_per_step"],
                              steps_per_s=r["steps_per_s"], step_alg_bytes_per_elem=b,
@@ -355,7 +365,8 @@ def main():
                 continue
             k = min(args.steps, 100)
             omix = None if ow["comp"] in ("sign", "qsgd") else mix_form
-            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix, order=order)
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix, order=order,
+                        momentum=args.momentum)
             b = step_bytes_per_elem(ow, r["kernels"])
             e = ow["n"] * ow["d"]
             others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],

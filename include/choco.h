@@ -121,6 +121,12 @@ int choco_step(choco_ctx *ctx, const float *g_dev, float lr);
 int choco_momentum_step(choco_ctx *ctx, const float *g_dev, float *m_dev, float lr, float beta,
                         float lambda);
 
+/* One whole iteration of the momentum variant (Algorithm 2): lines 9-10 there, then the
+   gossip step; bit for bit choco_momentum_step followed by choco_gossip_step, with the
+   local update folded into a dense pass over X like choco_step.  m_dev as above. */
+int choco_step_momentum(choco_ctx *ctx, const float *g_dev, float *m_dev, float lr, float beta,
+                        float lambda);
+
 /* Consensus distance (1/n) sum_i ||x_i - xbar||^2 (Section 5), ||xbar||_2 and the Lyapunov
    function Psi = ||X - Xbar||_F^2 + ||X - Xhat||_F^2 (Assumption 3), accumulated in fp64.
    Any output pointer may be NULL.  Synchronises the stream. */

@@ -19,7 +19,7 @@ MIX_AUTO, MIX_INCREMENTAL_S, MIX_DIRECT = 0, 1, 2
 
 EXPORTS = [
     "choco_workspace_bytes", "choco_init", "choco_gossip_step", "choco_sgd_step", "choco_step",
-    "choco_momentum_step", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
+    "choco_momentum_step", "choco_step_momentum", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
     "choco_set_capture", "choco_last_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
     "choco_profile_report",
@@ -73,6 +73,7 @@ def lib():
         L.choco_sgd_step.argtypes = [vp, vp, ctypes.c_float]
         L.choco_step.argtypes = [vp, vp, ctypes.c_float]
         L.choco_momentum_step.argtypes = [vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.choco_step_momentum.argtypes = [vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         dp = ctypes.POINTER(ctypes.c_double)
         L.choco_metrics.argtypes = [vp, dp, dp, dp]
         L.choco_xhat.argtypes = [vp, ctypes.POINTER(vp)]
@@ -188,6 +189,13 @@ class Choco:
             assert T.is_cuda and T.is_contiguous() and T.shape == self.X.shape and T.dtype == self.X.dtype
         _check(lib().choco_momentum_step(self.ctx, G.data_ptr(), M.data_ptr(), float(lr), float(beta),
                                          float(lam)), "choco_momentum_step")
+
+    def step_momentum(self, G, M, lr, beta, lam):
+        """momentum_step(G, M, ...) followed by gossip_step(), fused where the operator allows."""
+        for T in (G, M):
+            assert T.is_cuda and T.is_contiguous() and T.shape == self.X.shape and T.dtype == self.X.dtype
+        _check(lib().choco_step_momentum(self.ctx, G.data_ptr(), M.data_ptr(), float(lr), float(beta),
+                                         float(lam)), "choco_step_momentum")
 
     def metrics(self):
         c, m, p = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()

@@ -474,18 +474,50 @@ bool last_pass_carries_sgd(const choco_ctx* ctx) {
          (ctx->mix_form == CHOCO_MIX_INCREMENTAL_S || ctx->rpw != 0);
 }
 
-int run_gossip(choco_ctx* ctx, const float* fused_g, float lr, bool deferred = false) {
+struct LocalUpdate {      // the local update a fused step carries (g == nullptr: none)
+  const float* g = nullptr;
+  float lr = 0.0f;
+  float* m = nullptr;     // momentum memory, or nullptr for plain SGD
+  float beta = 0.0f, lambda = 0.0f;
+};
+
+int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   Args A = ctx->args;
   A.t_lo = (uint32_t)(ctx->t & 0xFFFFFFFFu);
   A.t_hi = (uint32_t)(ctx->t >> 32);
-  A.G = fused_g;
-  A.lr = lr;
+  A.G = u.g;
+  A.lr = u.lr;
+  A.M = u.g ? u.m : nullptr;
+  A.beta = u.beta;
+  A.lambda = u.lambda;
   A.deferred_sgd = deferred ? 1 : 0;
-  ctx->fused = fused_g != nullptr;
+  ctx->fused = u.g != nullptr;
   const int rc = ctx->nt ? gossip_any<true>(ctx, A) : gossip_any<false>(ctx, A);
   ctx->fused = false;
   if (rc == CHOCO_OK) ctx->t += 1;
   return rc;
+}
+
+int launch_momentum(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta, float lambda) {
+  const Args& A = ctx->args;
+  const int32_t nvec = (A.d + 3) >> 2;
+  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
+  if (ctx->nt)
+    LAUNCH(ctx, KID_MOMENTUM, k_momentum<true>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
+  else
+    LAUNCH(ctx, KID_MOMENTUM, k_momentum<false>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
+// One whole iteration: the local update (plain or momentum), then the gossip step; fused
+// into the first (or, for random_a, the last) dense pass where the configuration has one.
+int fused_iteration(choco_ctx* ctx, const LocalUpdate& u) {
+  if (first_pass_can_carry_sgd(ctx)) return run_gossip(ctx, u);
+  if (last_pass_carries_sgd(ctx)) return run_gossip(ctx, u, true);
+  const int rc = u.m ? launch_momentum(ctx, u.g, u.m, u.lr, u.beta, u.lambda) : launch_sgd(ctx, u.g, u.lr);
+  if (rc != CHOCO_OK) return rc;
+  return run_gossip(ctx, LocalUpdate());
 }
 
 }  // namespace
@@ -666,7 +698,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
 
 int choco_gossip_step(choco_ctx* ctx) {
   if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
-  return run_gossip(ctx, nullptr, 0.0f);
+  return run_gossip(ctx, LocalUpdate());
 }
 
 int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
@@ -676,26 +708,30 @@ int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
 
 int choco_step(choco_ctx* ctx, const float* g_dev, float lr) {
   if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
-  if (first_pass_can_carry_sgd(ctx)) return run_gossip(ctx, g_dev, lr);
-  if (last_pass_carries_sgd(ctx)) return run_gossip(ctx, g_dev, lr, true);
-  const int rc = launch_sgd(ctx, g_dev, lr);
-  if (rc != CHOCO_OK) return rc;
-  return run_gossip(ctx, nullptr, 0.0f);
+  LocalUpdate u;
+  u.g = g_dev;
+  u.lr = lr;
+  return fused_iteration(ctx, u);
 }
 
 int choco_momentum_step(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta,
                         float lambda) {
   if (!ctx || ctx->destroyed || !g_dev || !m_dev) return CHOCO_E_INVAL;
   if (((uintptr_t)g_dev & 15u) != 0 || ((uintptr_t)m_dev & 15u) != 0) return CHOCO_E_INVAL;
-  const Args& A = ctx->args;
-  const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 grid = chunk_grid(nvec, A.n, kStreamVecs);
-  if (ctx->nt)
-    LAUNCH(ctx, KID_MOMENTUM, k_momentum<true>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
-  else
-    LAUNCH(ctx, KID_MOMENTUM, k_momentum<false>, grid, dim3(256), 0, A.X, g_dev, m_dev, A.ld, nvec, lr, beta, lambda);
-  LAUNCH_CHECK(ctx);
-  return CHOCO_OK;
+  return launch_momentum(ctx, g_dev, m_dev, lr, beta, lambda);
+}
+
+int choco_step_momentum(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta,
+                        float lambda) {
+  if (!ctx || ctx->destroyed || !g_dev || !m_dev) return CHOCO_E_INVAL;
+  if (((uintptr_t)g_dev & 15u) != 0 || ((uintptr_t)m_dev & 15u) != 0) return CHOCO_E_INVAL;
+  LocalUpdate u;
+  u.g = g_dev;
+  u.lr = lr;
+  u.m = m_dev;
+  u.beta = beta;
+  u.lambda = lambda;
+  return fused_iteration(ctx, u);
 }
 
 int choco_metrics(choco_ctx* ctx, double* consensus_host, double* mean_norm_host, double* psi_host) {

@@ -81,6 +81,8 @@ struct Args {
   // also does x <- x - lr * g (Algorithm 1 line 9) before using x
   const float* G;
   float lr;
+  float* M;              // momentum memory (Algorithm 2) or null for plain SGD
+  float beta, lambda;    // momentum factor and weight decay of Algorithm 2
   int32_t deferred_sgd;  // the local update is applied by the LAST kernel of the step (random_a)
   // dense operators
   double* chunk_sums;  // n x nchunks first-level sums (only the printed-order tile kernel writes them)
@@ -129,19 +131,44 @@ __device__ __forceinline__ void store4(float* p, vf4 v) {
   if (NT) __builtin_nontemporal_store(v, q);
   else *q = v;
 }
-// x <- x - lr * g on one 4-vector (product rounded, then the difference).
-__device__ __forceinline__ vf4 sgd4(vf4 x, const vf4& g, float lr) {
+// The local update of one 4-vector at offset o, riding on a pass that has x in registers:
+//   plain (Algorithm 1 line 9):      x <- x - lr g
+//   momentum (Algorithm 2, l. 9-10): m <- (g + lambda x) + beta m (stored);  x <- x - lr m
+// Every product and sum rounded on its own, as in k_sgd / k_momentum.
+template <bool NT, class ArgsT>
+__device__ __forceinline__ vf4 local_update4(const ArgsT& A, int64_t o, vf4 x) {
+  const vf4 g = load4<NT>(A.G + o);
+  if (A.M) {
+    vf4 m = load4<NT>(A.M + o);
 #pragma unroll
-  for (int c = 0; c < 4; ++c) x[c] = x[c] - lr * g[c];
+    for (int c = 0; c < 4; ++c) {
+      const float gg = g[c] + A.lambda * x[c];
+      const float mn = gg + A.beta * m[c];
+      m[c] = mn;
+      x[c] = x[c] - A.lr * mn;
+    }
+    store4<NT>(A.M + o, m);
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) x[c] = x[c] - A.lr * g[c];
+  }
   return x;
 }
+
 // One entry of x as this step sees it.  random_a under choco_step: no pass reads X before
 // the final mix, so the local update is folded into that mix and the few entries that the
-// select and the scatter gather are updated on the fly (same product, same difference).
+// select and the scatter gather are updated on the fly (same operations on the same, not
+// yet updated, x, g and m).
 template <class ArgsT>
 __device__ __forceinline__ float x_entry(const ArgsT& A, int64_t o) {
   const float x = A.X[o];
-  return A.deferred_sgd ? x - A.lr * A.G[o] : x;
+  if (!A.deferred_sgd) return x;
+  if (A.M) {
+    const float gg = A.G[o] + A.lambda * x;
+    const float mn = gg + A.beta * A.M[o];
+    return x - A.lr * mn;
+  }
+  return x - A.lr * A.G[o];
 }
 __device__ __forceinline__ vf4 lds_load4(const float* p) { return *reinterpret_cast<const vf4*>(p); }
 __device__ __forceinline__ void lds_store4(float* p, vf4 v) { *reinterpret_cast<vf4*>(p) = v; }
@@ -400,12 +427,11 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
     }
   }
   if (A.G) {   // fused local update: x <- x - lr g, stored for the apply pass
-    const float* gr = A.G + (int64_t)i * A.ld;
     float* xw = A.X + (int64_t)i * A.ld;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < A.d) {
-        a[u] = sgd4(a[u], load4<NT>(gr + e[u]), A.lr);
+        a[u] = local_update4<NT>(A, (int64_t)i * A.ld + e[u], a[u]);
         store4<NT>(xw + e[u], a[u]);
       }
     }
@@ -552,7 +578,7 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
         const int64_t o = (int64_t)r * A.ld + e;
         xr[q] = load4<NT>(A.X + o);
         xh = load4<NT>(A.Xhat + o);
-        if (A.G) xr[q] = sgd4(xr[q], load4<NT>(A.G + o), A.lr);
+        if (A.G) xr[q] = local_update4<NT>(A, o, xr[q]);
       }
       lds_store4(tile + r * kChunk + lane * 4, xh);
     }
@@ -644,7 +670,7 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
       x[u] = load4<NT>(A.X + o);
       s[u] = load4<NT>(A.S + o);
       xh[u] = load4<NT>(A.Xhat + o);
-      if (A.G) x[u] = sgd4(x[u], load4<NT>(A.G + o), A.lr);
+      if (A.G) x[u] = local_update4<NT>(A, o, x[u]);
     }
   }
 #pragma unroll
@@ -728,7 +754,7 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
     vf4 x = load4<NT>(A.X + o);
     const vf4 xh = load4<NT>(A.Xhat + o);
     const bool sgd = FIRST && A.G != nullptr;
-    if (sgd) x = sgd4(x, load4<NT>(A.G + o), A.lr);
+    if (sgd) x = local_update4<NT>(A, o, x);
     if (DO_MIX) {
       const vf4 s = load4<NT>(A.S + o);
 #pragma unroll
@@ -906,6 +932,31 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
 // that one 16-bit bucket overflows the list, over the row itself (ROW = true);
 // emits the kept (index, value) pairs, marks them in the bitmap and places the
 // guess for the next step.  grid n, block 1024.
+// Lengths and prefix offsets of the candidate sub-lists of worker i (thread 0 writes them to
+// LDS; callers synchronise afterwards).  *good: the list holds the k largest entries.
+__device__ __forceinline__ void list_layout(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
+                                            uint32_t* total_out, uint32_t* good_out) {
+  uint32_t total = 0;
+  for (int s = 0; s < kSegs; ++s) {
+    const uint32_t c = ctl->seg_count[s];
+    lens[s] = c < A.seg_cap ? c : A.seg_cap;
+    pre[s] = total;
+    total += lens[s];
+  }
+  pre[kSegs] = total;
+  *total_out = total;
+  *good_out = list_is_good(ctl, A) ? 1u : 0u;
+}
+
+// Entry at flat position f of the concatenated sub-lists (pre = prefix offsets in LDS).
+__device__ __forceinline__ uint2 list_entry(const Args& A, int i, const uint32_t* pre, uint32_t f) {
+  int lo = 0;   // sub-list holding f: largest s with pre[s] <= f
+#pragma unroll
+  for (int step = kSegs / 2; step >= 1; step >>= 1)
+    if (pre[lo + step] <= f) lo += step;
+  return A.cand[((int64_t)i * kSegs + lo) * A.seg_cap + (f - pre[lo])];
+}
+
 template <int COMP>
 __device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint32_t& a, uint32_t& idx) {
   idx = t;
@@ -918,11 +969,11 @@ __device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint
   }
 }
 
-// Visit every entry of the domain (ROW: the whole row; else the candidate
-// sub-lists, lens[s] entries each) with f(a, idx).  All threads of the block
-// take part; the trip counts are uniform.
+// Visit every entry of the domain (ROW: the whole row; else the concatenated candidate
+// sub-lists, pre = their prefix offsets in LDS, total entries) with f(a, idx).  All threads
+// of the block take part; list entries are fetched eight per thread at a time.
 template <int COMP, bool ROW, class F>
-__device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint32_t* lens, F f) {
+__device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint32_t* pre, uint32_t total, F f) {
   if (ROW) {
     for (uint32_t t = threadIdx.x; t < (uint32_t)A.d; t += blockDim.x) {
       uint32_t a, idx;
@@ -930,13 +981,18 @@ __device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint3
       f(a, idx);
     }
   } else {
-    for (int s = 0; s < kSegs; ++s) {
-      const uint2* cand = A.cand + ((int64_t)i * kSegs + s) * A.seg_cap;
-      const uint32_t len = lens[s];
-      for (uint32_t t = threadIdx.x; t < len; t += blockDim.x) {
-        const uint2 c = cand[t];
-        f(c.x, c.y);
+    for (uint32_t base = 0; base < total; base += blockDim.x * 8u) {
+      uint2 c[8];
+      bool have[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t p = base + (uint32_t)u * blockDim.x + threadIdx.x;
+        have[u] = p < total;
+        if (have[u]) c[u] = list_entry(A, i, pre, p);
       }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (have[u]) f(c[u].x, c[u].y);
     }
   }
 }
@@ -1007,31 +1063,6 @@ __device__ __forceinline__ void publish_bitmap(const Args& A, int i, const uint3
     A.bitmap[(int64_t)i * A.bitmap_words + wd] = lbits[wd];
 }
 
-// Lengths and prefix offsets of the candidate sub-lists of worker i (thread 0 writes them to
-// LDS; callers synchronise afterwards).  *good: the list holds the k largest entries.
-__device__ __forceinline__ void list_layout(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
-                                            uint32_t* total_out, uint32_t* good_out) {
-  uint32_t total = 0;
-  for (int s = 0; s < kSegs; ++s) {
-    const uint32_t c = ctl->seg_count[s];
-    lens[s] = c < A.seg_cap ? c : A.seg_cap;
-    pre[s] = total;
-    total += lens[s];
-  }
-  pre[kSegs] = total;
-  *total_out = total;
-  *good_out = list_is_good(ctl, A) ? 1u : 0u;
-}
-
-// Entry at flat position f of the concatenated sub-lists (pre = prefix offsets in LDS).
-__device__ __forceinline__ uint2 list_entry(const Args& A, int i, const uint32_t* pre, uint32_t f) {
-  int lo = 0;   // sub-list holding f: largest s with pre[s] <= f
-#pragma unroll
-  for (int step = kSegs / 2; step >= 1; step >>= 1)
-    if (pre[lo + step] <= f) lo += step;
-  return A.cand[((int64_t)i * kSegs + lo) * A.seg_cap + (f - pre[lo])];
-}
-
 // Bin of a candidate by its distance above the guess.
 template <int COMP>
 __device__ __forceinline__ uint32_t cand_bin(uint32_t a, uint32_t guess, uint32_t shift) {
@@ -1083,9 +1114,10 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   if (delta < 1) delta = 1;
   if (delta > 0xFFFFFFFFull) delta = 0xFFFFFFFFull;
   ctl->guess_key = delta >= (uint64_t)T ? 0u : T - (uint32_t)delta;
-  // about 1024 bins between the guess and where the threshold is expected
+  // 256-511 bins between the guess and where the threshold is expected: the 2048 bins then
+  // still resolve a threshold that lands 4-8 times further above the guess than predicted
   const int lg = 63 - __clzll((unsigned long long)delta);
-  ctl->bin_shift = lg > 10 ? (uint32_t)(lg - 10) : 0u;
+  ctl->bin_shift = lg > 8 ? (uint32_t)(lg - 8) : 0u;
   ctl->kstar = kstar;
   ctl->kept = emitted;
   ctl->last_candidates = total;
@@ -1097,7 +1129,7 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
 }
 
 template <int COMP, bool ROW>
-__device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint32_t total, uint32_t* h,
+__device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint32_t total, uint32_t* h,
                                 uint32_t* grp, uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
                                 uint32_t* s_above, uint32_t* s_emit, uint32_t* lbits) {
   WorkerCtl* ctl = A.ctl + i;
@@ -1111,7 +1143,7 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
     const int scur = Digits<COMP>::shift(level);
     const int sprev = level > 0 ? Digits<COMP>::shift(level - 1) : 63;
     const uint32_t mask = (1u << Digits<COMP>::bits(level)) - 1u;
-    for_each_entry<COMP, ROW>(A, i, lens, [&](uint32_t a, uint32_t idx) {
+    for_each_entry<COMP, ROW>(A, i, pre, total, [&](uint32_t a, uint32_t idx) {
       const uint64_t K = Digits<COMP>::composite(a, idx);
       // level 0: every entry takes part (nothing of the composite lies above digit 0)
       const bool match = level == 0 ? true : ((K >> sprev) == prefix);
@@ -1142,7 +1174,7 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* lens, uint
   }
   const uint64_t kstar = *s_prefix << Digits<COMP>::shift(last);
   // emit every entry with composite >= kstar
-  for_each_entry<COMP, ROW>(A, i, lens, [&](uint32_t a, uint32_t idx) {
+  for_each_entry<COMP, ROW>(A, i, pre, total, [&](uint32_t a, uint32_t idx) {
     if (Digits<COMP>::composite(a, idx) >= kstar) {
       const uint32_t slot = atomicAdd(s_emit, 1u);
       if (slot < (uint32_t)A.k) {
@@ -1189,7 +1221,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
-    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
+    refine_and_emit<COMP, true>(A, i, pre, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
     return;
   }
   const uint32_t guess = ctl->guess_key, shift = ctl->bin_shift;
@@ -1218,7 +1250,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   const uint32_t in_bin = h[tbin];
   if (in_bin > (uint32_t)kSmallCap) {
     __syncthreads();
-    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
+    refine_and_emit<COMP, false>(A, i, pre, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, lbits);
     return;
   }
   // sweep 2: emit everything above the threshold bin, collect the bin itself
@@ -1419,7 +1451,7 @@ __global__ __launch_bounds__(1024) void k_sel_finish(Args A) {
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
-    refine_and_emit<COMP, true>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
+    refine_and_emit<COMP, true>(A, i, pre, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
     return;
   }
   sum_hist_parts(A, i, h);
@@ -1430,7 +1462,7 @@ __global__ __launch_bounds__(1024) void k_sel_finish(Args A) {
   const uint32_t in_bin = h[tbin];
   if (in_bin > (uint32_t)kSmallCap) {
     __syncthreads();
-    refine_and_emit<COMP, false>(A, i, lens, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
+    refine_and_emit<COMP, false>(A, i, pre, total, h, grp, &s_prefix, &s_need, &s_digit, &s_above, &s_emit, nullptr);
     return;
   }
   // the blocks of k_sel_emit_parts emitted `above` entries into slots 0..above-1 and collected

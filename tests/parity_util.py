@@ -81,6 +81,22 @@ class Pair:
         self.ref.sgd_step(G, lr)
         return self.ref.gossip_step(want_details=True)
 
+    def step_momentum(self, G, lr, beta, lam):
+        """One fused momentum iteration (Algorithm 2) on the GPU; the oracle does the momentum
+        update and the gossip step one after the other.  The momentum memories are compared."""
+        t = self.torch
+        if not hasattr(self, "M"):
+            self.M = t.zeros_like(self.X)
+            self.V = np.zeros_like(self.ref.X)
+        Gd = t.zeros((self.n, self.ld), dtype=t.float32, device=self.X.device)
+        Gd[:, :self.d] = t.from_numpy(np.ascontiguousarray(G, dtype=np.float32)).to(self.X.device)
+        self.gpu.step_momentum(Gd, self.M, lr, beta, lam)
+        self.ref.momentum_step(self.V, G, lr, beta, lam)
+        det = self.ref.gossip_step(want_details=True)
+        self.gpu.sync()
+        assert np.array_equal(self.M[:, :self.d].cpu().numpy(), self.V), "momentum memory differs"
+        return det
+
     def gpu_state(self):
         self.gpu.sync()
         X = self.X[:, :self.d].cpu().numpy()

@@ -218,6 +218,28 @@ def test_fused_step_equals_sgd_then_gossip(n, d, mix_form, comp, order):
         pair.close()
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", ["identity", "sign", "qsgd16", "topk", "randk", "randk_rescaled"])
+@pytest.mark.parametrize("n,d,mix_form", [(8, 70001, B.MIX_AUTO), (70, 1030, B.MIX_AUTO), (8, 6000, B.MIX_DIRECT)])
+def test_fused_momentum_step_equals_momentum_then_gossip(n, d, mix_form, comp, order):
+    # Algorithm 2: v <- (g + lambda x) + beta v; x <- x - eta v, then the gossip step
+    kw = dict(COMPRESSORS[comp])
+    sparse = kw["compressor"] in (B.Q_TOPK, B.Q_RANDK)
+    if mix_form == B.MIX_DIRECT and not sparse:
+        pytest.skip("dense operators already use the direct form")
+    if sparse:
+        kw["k"] = max(1, d // 100)
+    pair = Pair(synth.normal_state(n, d, seed=3), topo_for(n), 0.2, order=order, mix_form=mix_form,
+                seed=78, **kw)
+    grads = synth.GradientStream(n, d, seed=5)
+    try:
+        for t in range(5):
+            det = pair.step_momentum(grads.next(), 0.05, 0.9, 1e-4)
+            pair.check(det, tag="fused momentum %s n=%d d=%d order=%d step %d" % (comp, n, d, order, t))
+    finally:
+        pair.close()
+
+
 def test_sgd_and_momentum_steps_match():
     import torch
     from oracle import choco_ref as ref
