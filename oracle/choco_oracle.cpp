@@ -85,8 +85,8 @@ uint32_t random_word(uint64_t seed, uint64_t t, int worker, int64_t e, int strea
 //   level 1: chunks of 256 consecutive terms; "lane" l (0..63) adds its four
 //            consecutive terms 4l..4l+3 left to right; the 64 lane sums are
 //            combined by halving: for off = 32,16,..,1: t[l] += t[l+off], l<off;
-//   level 2: groups of 64 consecutive chunk sums (16384 terms), combined by the
-//            same halving from 32 to 1;
+//   level 2: groups of 16 consecutive chunk sums (4096 terms), combined by
+//            halving from 8 to 1;
 //   level 3: 256 "lanes"; lane l adds group sums l, l+256, l+512, ... in that
 //            order; the 256 lane sums are combined by halving from 128 to 1.
 // Terms, chunks and groups past the end count as +0.0 (an exact no-op on
@@ -95,12 +95,13 @@ uint32_t random_word(uint64_t seed, uint64_t t, int worker, int64_t e, int strea
 template <class Term>
 double canonical_sum(int64_t d, Term term) {
   const int64_t nchunks = (d + 255) / 256;
-  const int64_t ngroups = (nchunks + 63) / 64;
+  const int chunks_per_group = 16;
+  const int64_t ngroups = (nchunks + chunks_per_group - 1) / chunks_per_group;
   std::vector<double> group_sum((size_t)ngroups);
   for (int64_t g = 0; g < ngroups; ++g) {
-    double chunk[64];
-    for (int k = 0; k < 64; ++k) {
-      const int64_t c = g * 64 + k;
+    double chunk[chunks_per_group];
+    for (int k = 0; k < chunks_per_group; ++k) {
+      const int64_t c = g * chunks_per_group + k;
       double lane[64];
       for (int l = 0; l < 64; ++l) {
         double acc = 0.0;
@@ -115,7 +116,7 @@ double canonical_sum(int64_t d, Term term) {
         for (int l = 0; l < off; ++l) lane[l] = lane[l] + lane[l + off];
       chunk[k] = lane[0];
     }
-    for (int off = 32; off >= 1; off >>= 1)
+    for (int off = chunks_per_group / 2; off >= 1; off >>= 1)
       for (int k = 0; k < off; ++k) chunk[k] = chunk[k] + chunk[k + off];
     group_sum[(size_t)g] = chunk[0];
   }

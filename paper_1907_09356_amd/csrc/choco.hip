@@ -346,7 +346,7 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
     if (ctx->rpw) {
       launch_tile_mix<STAT, NT>(ctx, F, fused);
       if (needs_stat)
-        LAUNCH(ctx, KID_GROUP_REDUCE, k_group_reduce, dim3((unsigned)((A.ngroups + 3) / 4), (unsigned)A.n),
+        LAUNCH(ctx, KID_GROUP_REDUCE, k_group_reduce, dim3((unsigned)((A.ngroups + 15) / 16), (unsigned)A.n),
                dim3(256), 0, A);
     } else {
       launch_mix_direct_global(ctx, A);
@@ -667,7 +667,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->metrics_out = (double*)(base + L.mout);
   ctx->metrics_blocks = kMetricsBlocks;
 
-  // zero everything but the caller's X: xhat^(0) = 0, S = 0, counters, histograms, bitmap
+  // zero everything but the caller's X: xhat^(0) = 0, S = 0, counters, histograms, kept-entry map
   hipError_t e = hipMemsetAsync(workspace_dev, 0, L.total, ctx->stream);
   if (e == hipSuccess)
     e = hipMemcpyAsync(base + L.row_ptr, cfg->row_ptr_host, (size_t)(cfg->n + 1) * sizeof(int32_t),

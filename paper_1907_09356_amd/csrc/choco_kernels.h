@@ -14,7 +14,7 @@
 // rounded on its own (compiled with -ffp-contract=off), neighbour
 // contributions are added in CSR order, norms are accumulated in fp64 over a
 // fixed three-level tree (chunks of 256 consecutive entries, 4 per lane and a
-// 64-lane butterfly; groups of 64 chunk sums, butterfly; 256 strided lanes over
+// 64-lane butterfly; groups of 16 chunk sums, butterfly; 256 strided lanes over
 // the group sums and a halving tree).
 #pragma once
 
@@ -32,12 +32,12 @@ typedef int vi4 __attribute__((ext_vector_type(4)));
 constexpr int kBins = 2048;       // radix-select digits are at most 11 bits wide
 constexpr int kBins16 = 65536;    // first digit of the fallback histogram (16 bits)
 constexpr int kChunk = 256;       // entries per first-level norm chunk / tile width
-constexpr int kGroup = 64;        // chunks per second-level group
+constexpr int kGroup = 16;        // chunks per second-level group (4096 entries)
 constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kernels
 constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass
 constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
 constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
-constexpr int kStatThreads = 1024;  // one wave per 4 chunks of a 64-chunk group
+constexpr int kStatThreads = 256;   // one wave per 4 chunks of a 16-chunk group
 constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
 constexpr int kRefineParts = 16;    // blocks per worker of the select when the candidate lists are long
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
@@ -214,6 +214,14 @@ __device__ __forceinline__ double wave_tree_sum(double t) {
   return t;
 }
 
+// The same over aligned sub-groups of kGroup = 16 lanes (halving 8,4,2,1): lanes
+// 16q..16q+15 end with the tree sum of their own 16 values.
+__device__ __forceinline__ double group_tree_sum(double t) {
+#pragma unroll
+  for (int off = kGroup / 2; off >= 1; off >>= 1) t = t + __shfl_xor(t, off, 64);
+  return t;
+}
+
 // ---------------------------------------------------------------------------
 // Element-wise encoders of the dense operators.  v is one entry of x - xhat.
 // ---------------------------------------------------------------------------
@@ -387,11 +395,23 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
   __shared__ double sh[256];
   const int i = blockIdx.x, l = threadIdx.x;
   const double* gs = A.group_sums + (int64_t)i * A.ngroups;
+  // lane l adds group sums l, l+256, ... in that order; loads run eight ahead of the adds
   double acc = 0.0;
   bool first = true;
-  for (int g = l; g < A.ngroups; g += 256) {
-    acc = first ? gs[g] : acc + gs[g];
-    first = false;
+  for (int g0 = l; g0 < A.ngroups; g0 += 256 * 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int g = g0 + 256 * u;
+      v[u] = g < A.ngroups ? gs[g] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (g0 + 256 * u < A.ngroups) {
+        acc = first ? v[u] : acc + v[u];
+        first = false;
+      }
+    }
   }
   sh[l] = acc;
   __syncthreads();
@@ -406,8 +426,8 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
 }
 
 // Dense operators, statistic pass (compress-then-mix order): v = x - xhat, one
-// block per group of 64 chunks (16384 entries), one wave per 4 chunks, all four
-// in flight at once.  grid (ngroups, n), block 1024.
+// block per group of 16 chunks (4096 entries), one wave per 4 chunks, all four
+// in flight at once.  grid (ngroups, n), block 256.
 template <int COMP, bool NT>
 __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   __shared__ double cs[kGroup];
@@ -448,23 +468,21 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   }
   __syncthreads();
   if (wave == 0) {
-    const double t = wave_tree_sum(cs[lane]);
+    const double t = group_tree_sum(lane < kGroup ? cs[lane] : 0.0);
     if (lane == 0) A.group_sums[(int64_t)i * A.ngroups + g] = t;
   }
 }
 
 // Second level from chunk sums already in memory (printed order: the tile kernel
-// below produces chunk sums).  One wave per group; grid (ceil(ngroups/4), n).
+// below produces chunk sums).  Sixteen lanes per group, four groups per wave;
+// grid (ceil(ngroups/16), n), block 256.
 __global__ __launch_bounds__(256) void k_group_reduce(Args A) {
   const int i = blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int g = blockIdx.x * 4 + wave;
-  if (g < A.ngroups) {
-    const int c = g * kGroup + lane;
-    double t = (c < A.nchunks) ? A.chunk_sums[(int64_t)i * A.nchunks + c] : 0.0;
-    t = wave_tree_sum(t);
-    if (lane == 0) A.group_sums[(int64_t)i * A.ngroups + g] = t;
-  }
+  const int g = (blockIdx.x * 256 + threadIdx.x) / kGroup;
+  const int c = g * kGroup + (threadIdx.x & (kGroup - 1));
+  double t = (g < A.ngroups && c < A.nchunks) ? A.chunk_sums[(int64_t)i * A.nchunks + c] : 0.0;
+  t = group_tree_sum(t);
+  if (g < A.ngroups && (threadIdx.x & (kGroup - 1)) == 0) A.group_sums[(int64_t)i * A.ngroups + g] = t;
 }
 
 // ---------------------------------------------------------------------------
@@ -928,10 +946,10 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
   }
 }
 
-// Radix select over the candidate list (ROW = false) or, in the degenerate case
-// that one 16-bit bucket overflows the list, over the row itself (ROW = true);
-// emits the kept (index, value) pairs, marks them in the bitmap and places the
-// guess for the next step.  grid n, block 1024.
+// ---------------------------------------------------------------------------
+// The exact select on the candidates of one worker (device functions shared by the
+// one-block and the multi-block kernels below).
+// ---------------------------------------------------------------------------
 // Lengths and prefix offsets of the candidate sub-lists of worker i (thread 0 writes them to
 // LDS; callers synchronise afterwards).  *good: the list holds the k largest entries.
 __device__ __forceinline__ void list_layout(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
@@ -1128,6 +1146,9 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
 }
 
+// Digit-by-digit radix select over the composite keys of the candidate list (ROW = false)
+// or of the row itself (ROW = true: the list is not good); emits the kept entries, marks
+// them and places the next guess.  All threads of a 1024-thread block.
 template <int COMP, bool ROW>
 __device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint32_t total, uint32_t* h,
                                 uint32_t* grp, uint64_t* s_prefix, uint32_t* s_need, uint32_t* s_digit,
@@ -1190,13 +1211,14 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint3
   if (threadIdx.x == 0) next_guess(A, ctl, kstar, total, !ROW, *s_emit, ROW ? 2u : 0u, ROW, floor_key);
 }
 
-// Exact selection from the candidates, emission of the kept (index, value) pairs
-// and of the bitmap, next guess.  Fast path: the candidate histogram written by
-// the pass over the rows already tells which bin holds the k-th largest key; one
-// sweep over the list emits everything above that bin and ranks the few entries
-// inside it directly in LDS.  If that bin is crowded (ties) the generic
-// digit-by-digit select runs on the list; if the list itself is not good, on the
-// row.  grid n, block 1024.
+// Exact selection from the candidates by one block per worker: emission of the kept
+// (index, value) pairs and of the kept-entry map, next guess.  Fast path: an LDS
+// histogram of the candidates by their distance above the guess tells which bin holds
+// the k-th largest key; everything above that bin is emitted as it is and the few
+// entries inside it are ranked against each other in LDS (lists of up to 8192 entries
+// stay in registers between the two sweeps).  If that bin is crowded (ties) the
+// digit-by-digit select runs on the list; if the list itself is not good, on the row.
+// grid n, block 1024, dynamic LDS = the worker's bitmap (short rows) or nothing.
 template <int COMP>
 __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
   __shared__ uint32_t h[kBins];
