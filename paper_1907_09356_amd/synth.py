@@ -70,6 +70,28 @@ def metropolis_csr(adj):
     return dense_to_csr(W)
 
 
+def irregular_graph(n, max_degree, seed):
+    """Connected irregular graph standing in for the paper's 32-node social network
+    (Section 5: maximum degree 14): a ring for connectivity plus random chords, with one
+    hub raised to max_degree.  Returns a symmetric boolean adjacency without self loops."""
+    rng = np.random.default_rng(seed)
+    adj = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        adj[i, (i + 1) % n] = adj[(i + 1) % n, i] = True
+    for _ in range(2 * n):
+        a, b = rng.integers(0, n, size=2)
+        if a != b and adj[a].sum() < max_degree - 1 and adj[b].sum() < max_degree - 1:
+            adj[a, b] = adj[b, a] = True
+    hub = 0
+    others = [j for j in rng.permutation(n) if j != hub]
+    for j in others:
+        if adj[hub].sum() >= max_degree:
+            break
+        if adj[j].sum() < max_degree:
+            adj[hub, j] = adj[j, hub] = True
+    return adj
+
+
 def dense_to_csr(W):
     W = np.asarray(W)
     n = W.shape[0]

@@ -166,6 +166,52 @@ def test_multi_block_select_with_crowded_threshold_bin_and_overflow():
             pair.close()
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", list(COMPRESSORS))
+@pytest.mark.parametrize("n", [1, 2])
+def test_single_and_two_workers(n, comp, order):
+    # degenerate graphs: one node (W = [1]) and two nodes (complete graph, weights 1/2)
+    run(n, 3000, comp, order, steps=3)
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
+def test_irregular_graph_with_local_degree_weights(comp, order):
+    # 32 nodes, maximum degree 14, weights 1/(1 + max(deg i, deg j)) with the remainder on the
+    # self loop: rows of different lengths and different weights per edge
+    adj = synth.irregular_graph(32, 14, seed=3)
+    assert adj.sum(1).max() == 14
+    topo = synth.metropolis_csr(adj)
+    kw = dict(COMPRESSORS[comp])
+    if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+        kw["k"] = 40
+    n, d = 32, 4000
+    pair = Pair(synth.normal_state(n, d, seed=2), topo, 0.3, order=order, seed=4, **kw)
+    grads = synth.GradientStream(n, d, seed=3)
+    try:
+        for t in range(5):
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="irregular %s step %d" % (comp, t))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("comp", ["sign", "qsgd16"])
+def test_norm_finalise_kernel_for_long_rows(comp):
+    # more than 256 group sums per row (d > 2^20): the norm tree's last level runs in its own
+    # kernel instead of inside the apply kernel
+    kw = dict(COMPRESSORS[comp])
+    n, d = 2, (1 << 20) + 4096 * 3 + 77
+    pair = Pair(synth.normal_state(n, d, seed=9), synth.ring_csr(n), 0.3, seed=1, **kw)
+    grads = synth.GradientStream(n, d, seed=10)
+    try:
+        for t in range(2):
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="long rows %s step %d" % (comp, t))
+    finally:
+        pair.close()
+
+
 def test_guess_survives_a_sudden_change_of_scale():
     # the first digit of the threshold jumps by many bins between steps in both directions
     n, d, k = 4, 20000, 200
