@@ -417,12 +417,15 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   if (incremental)
     LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256),
            0, A);
-  LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  // short rows: the final mix reads the bitmap and applies xhat += q itself
+  const bool fold_xhat = !mix_first && incremental && A.bitmap_words > 0;
+  if (!fold_xhat) LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
     // random_a under choco_step: the deferred local update rides on this last pass
     const bool last_carries = F.deferred_sgd != 0;
     Args L = A;
     if (last_carries) L.G = F.G;
+    L.fold_xhat = fold_xhat ? 1 : 0;
     if (incremental)
       LAUNCH(ctx, last_carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
              dim3(256), 0, L);

@@ -111,6 +111,7 @@ struct Args {
   uint8_t* keptmap;    // n x ld bytes: byte e of row j non-zero <=> worker j kept entry e this step
   uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
   int64_t bitmap_words;  // 0: use the byte map
+  int32_t fold_xhat;     // the final mix also applies xhat += q (bitmap rows, compress-then-mix)
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
   // randomness
@@ -689,6 +690,22 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
       s[u] = load4<NT>(A.S + o);
       xh[u] = load4<NT>(A.Xhat + o);
       if (A.G) x[u] = local_update4<NT>(A, o, x[u]);
+      if (A.fold_xhat) {
+        // short rows, compress-then-mix order: xhat += q for this step's kept entries
+        // (Algorithm 1 line 6) rides on this pass, read off the worker's bitmap
+        const uint32_t e = 4u * (uint32_t)m;
+        const uint32_t bits = (A.bitmap[(int64_t)i * A.bitmap_words + (e >> 5)] >> (e & 31u)) & 0xFu;
+        if (bits) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if ((bits >> c) & 1u) {
+              float q = x[u][c] - xh[u][c];
+              if (A.randk_rescale) q = A.randk_scale * q;
+              xh[u][c] = xh[u][c] + q;
+            }
+          store4<false>(A.Xhat + o, xh[u]);
+        }
+      }
     }
   }
 #pragma unroll
