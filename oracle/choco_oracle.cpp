@@ -175,9 +175,9 @@ void select_topk(int64_t d, const R* v, int64_t k, std::vector<int32_t>& sel) {
 // this build's choice: every coordinate draws a 32-bit word and the k
 // smallest words win, equal words ordered by ascending index.
 void select_randk(int64_t d, int64_t k, uint64_t seed, uint64_t t, int worker,
-                  std::vector<int32_t>& sel) {
+                  std::vector<int32_t>& sel, int64_t e0 = 0) {
   std::vector<uint32_t> r((size_t)d);
-  for (int64_t e = 0; e < d; ++e) r[(size_t)e] = random_word(seed, t, worker, e, STREAM_RANDK);
+  for (int64_t e = 0; e < d; ++e) r[(size_t)e] = random_word(seed, t, worker, e0 + e, STREAM_RANDK);
   std::vector<int32_t> order((size_t)d);
   for (int64_t e = 0; e < d; ++e) order[(size_t)e] = (int32_t)e;
   auto before = [&r](int32_t a, int32_t b) {
@@ -189,9 +189,11 @@ void select_randk(int64_t d, int64_t k, uint64_t seed, uint64_t t, int worker,
   std::sort(sel.begin(), sel.end());
 }
 
+// e0 is the index that v[0] has in the worker's whole vector: the random word of
+// entry e of v is the one of coordinate e0 + e (e0 = 0 unless v is one layer of it).
 template <class R>
 void compress(const QParams& P, int64_t d, const R* v, uint64_t t, int worker, R* q,
-              int32_t* sel_out, int32_t* codes, double* scal) {
+              int32_t* sel_out, int32_t* codes, double* scal, int64_t e0 = 0) {
   if (scal) scal[0] = scal[1] = scal[2] = scal[3] = 0.0;
   switch (P.compressor) {
     case Q_IDENTITY: {
@@ -202,7 +204,7 @@ void compress(const QParams& P, int64_t d, const R* v, uint64_t t, int worker, R
     case Q_RANDK: {
       std::vector<int32_t> sel;
       if (P.compressor == Q_TOPK) select_topk(d, v, P.k, sel);
-      else select_randk(d, P.k, P.seed, t, worker, sel);
+      else select_randk(d, P.k, P.seed, t, worker, sel, e0);
       for (int64_t e = 0; e < d; ++e) q[e] = (R)0;
       const bool rescale = (P.compressor == Q_RANDK) && P.randk_rescale;
       const R scale = (R)((double)d / (double)P.k);
@@ -245,7 +247,7 @@ void compress(const QParams& P, int64_t d, const R* v, uint64_t t, int worker, R
         const bool neg = v[e] < (R)0;
         int32_t level = 0;
         if (nrm > 0.0) {
-          const uint32_t word = random_word(P.seed, t, worker, e, STREAM_DITHER);
+          const uint32_t word = random_word(P.seed, t, worker, e0 + e, STREAM_DITHER);
           const R u = (R)(word >> 8) * (R)(1.0 / 16777216.0);
           const R a = std::fabs(v[e]) * r;
           level = (int32_t)std::floor(a + u);
@@ -305,32 +307,67 @@ void mix_half(int n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx, 
   }
 }
 
+// Layers.  The experiments apply the operator to every layer of the network on its
+// own (Section 5, set-up of the ResNet-20 runs): layer l is the slice
+// [start[l], start[l] + len[l]) of a worker's vector and is compressed as a vector of
+// its own, with len[l] in the place of d (norms, tau, d/k) and k[l] in the place of k.
+// Slices are disjoint and ascending; entries that lie in no slice are never sent
+// (q = 0 there).  k[l] = 0 sends nothing of layer l.  nseg = 0: the whole vector is
+// the only layer.
+struct Segments {
+  int32_t nseg;
+  const int64_t* start;
+  const int64_t* len;
+  const int64_t* k;   // used by top_a / random_a only
+};
+
 template <class R>
-void compress_half(const QParams& P, int n, int64_t d, const int32_t* row_ptr,
+void compress_half(const QParams& P, const Segments& G, int n, int64_t d, const int32_t* row_ptr,
                    const int32_t* col_idx, const R* w, int mix_form, uint64_t t, const R* X,
                    R* Xhat, R* S, int32_t* sel_out, int32_t* codes, double* scal) {
   const bool sparse = (P.compressor == Q_TOPK || P.compressor == Q_RANDK);
-  std::vector<R> Qall((size_t)n * (size_t)d);
-  std::vector<int32_t> sel_all;
-  if (sparse) sel_all.resize((size_t)n * (size_t)P.k);
+  const int32_t nseg = G.nseg > 0 ? G.nseg : 1;
+  const int64_t whole_start = 0, whole_len = d, whole_k = P.k;
+  const int64_t* start = G.nseg > 0 ? G.start : &whole_start;
+  const int64_t* len = G.nseg > 0 ? G.len : &whole_len;
+  const int64_t* kk = G.nseg > 0 ? G.k : &whole_k;
+  int64_t ktot = 0;   // kept entries per worker over all layers
+  if (sparse) for (int32_t l = 0; l < nseg; ++l) ktot += kk[l];
+  std::vector<R> Qall((size_t)n * (size_t)d, (R)0);
+  std::vector<int32_t> sel_all((size_t)n * (size_t)ktot);
   std::vector<R> v((size_t)d);
-  for (int i = 0; i < n; ++i) {  // line 3: q_i = Q(x_i - xhat_i)
+  for (int i = 0; i < n; ++i) {  // line 3: q_i = Q(x_i - xhat_i), layer by layer
     for (int64_t e = 0; e < d; ++e) v[(size_t)e] = X[(int64_t)i * d + e] - Xhat[(int64_t)i * d + e];
-    compress<R>(P, d, v.data(), t, i, Qall.data() + (int64_t)i * d,
-                sparse ? sel_all.data() + (int64_t)i * P.k : nullptr,
-                codes ? codes + (int64_t)i * d : nullptr, scal ? scal + 4 * i : nullptr);
+    int64_t filled = 0;
+    for (int32_t l = 0; l < nseg; ++l) {
+      double* sc = scal ? scal + 4 * ((int64_t)i * nseg + l) : nullptr;
+      if (sparse && kk[l] == 0) {
+        if (sc) sc[0] = sc[1] = sc[2] = sc[3] = 0.0;
+        continue;
+      }
+      QParams Pl = P;
+      Pl.k = kk[l];
+      int32_t* sel_l = sparse ? sel_all.data() + (int64_t)i * ktot + filled : nullptr;
+      compress<R>(Pl, len[l], v.data() + start[l], t, i, Qall.data() + (int64_t)i * d + start[l],
+                  sel_l, codes ? codes + (int64_t)i * d + start[l] : nullptr, sc, start[l]);
+      if (sparse) {
+        for (int64_t m = 0; m < kk[l]; ++m) sel_l[m] += (int32_t)start[l];
+        filled += kk[l];
+      }
+    }
   }
-  if (sparse && sel_out) std::memcpy(sel_out, sel_all.data(), sel_all.size() * sizeof(int32_t));
+  if (sparse && sel_out && ktot > 0) std::memcpy(sel_out, sel_all.data(), sel_all.size() * sizeof(int32_t));
   for (int j = 0; j < n; ++j) {  // line 6: xhat_j += q_j (one copy stands for all replicas)
     R* xh = Xhat + (int64_t)j * d;
     const R* q = Qall.data() + (int64_t)j * d;
     if (sparse) {
-      for (int64_t m = 0; m < P.k; ++m) {
-        const int32_t e = sel_all[(size_t)((int64_t)j * P.k + m)];
+      for (int64_t m = 0; m < ktot; ++m) {
+        const int32_t e = sel_all[(size_t)((int64_t)j * ktot + m)];
         xh[e] = xh[e] + q[e];
       }
     } else {
-      for (int64_t e = 0; e < d; ++e) xh[e] = xh[e] + q[e];
+      for (int32_t l = 0; l < nseg; ++l)
+        for (int64_t e = start[l]; e < start[l] + len[l]; ++e) xh[e] = xh[e] + q[e];
     }
   }
   if (mix_form == MIX_INCREMENTAL_S) {  // s_i += sum_j w_ij q_j, CSR order
@@ -340,34 +377,48 @@ void compress_half(const QParams& P, int n, int64_t d, const int32_t* row_ptr,
         const int j = col_idx[p];
         const R* q = Qall.data() + (int64_t)j * d;
         if (sparse) {
-          for (int64_t m = 0; m < P.k; ++m) {
-            const int32_t e = sel_all[(size_t)((int64_t)j * P.k + m)];
+          for (int64_t m = 0; m < ktot; ++m) {
+            const int32_t e = sel_all[(size_t)((int64_t)j * ktot + m)];
             const R prod = w[p] * q[e];
             s[e] = s[e] + prod;
           }
         } else {
-          for (int64_t e = 0; e < d; ++e) {
-            const R prod = w[p] * q[e];
-            s[e] = s[e] + prod;
-          }
+          for (int32_t l = 0; l < nseg; ++l)
+            for (int64_t e = start[l]; e < start[l] + len[l]; ++e) {
+              const R prod = w[p] * q[e];
+              s[e] = s[e] + prod;
+            }
         }
       }
     }
   }
 }
 
+bool segments_ok(const Segments& G, int64_t d, bool sparse) {
+  int64_t end = 0;
+  for (int32_t l = 0; l < G.nseg; ++l) {
+    if (G.start[l] < end || G.len[l] < 1) return false;
+    end = G.start[l] + G.len[l];
+    if (end > d) return false;
+    if (sparse && (G.k[l] < 0 || G.k[l] > G.len[l])) return false;
+  }
+  return true;
+}
+
 template <class R>
 int gossip_step(int n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx, const R* w,
-                R gamma, const QParams& P, int order, int mix_form, uint64_t t, R* X, R* Xhat,
-                R* S, int32_t* sel_out, int32_t* codes, double* scal) {
+                R gamma, const QParams& P, const Segments& G, int order, int mix_form, uint64_t t,
+                R* X, R* Xhat, R* S, int32_t* sel_out, int32_t* codes, double* scal) {
   if (n < 1 || d < 1) return -1;
-  if ((P.compressor == Q_TOPK || P.compressor == Q_RANDK) && (P.k < 1 || P.k > d)) return -1;
+  const bool sparse = (P.compressor == Q_TOPK || P.compressor == Q_RANDK);
+  if (G.nseg == 0 && sparse && (P.k < 1 || P.k > d)) return -1;
+  if (G.nseg < 0 || (G.nseg > 0 && !segments_ok(G, d, sparse))) return -1;
   if (P.compressor == Q_QSGD && P.levels < 1) return -1;
   if (order == ORDER_MIX_THEN_COMPRESS) {
     mix_half<R>(n, d, row_ptr, col_idx, w, gamma, mix_form, X, Xhat, S);
-    compress_half<R>(P, n, d, row_ptr, col_idx, w, mix_form, t, X, Xhat, S, sel_out, codes, scal);
+    compress_half<R>(P, G, n, d, row_ptr, col_idx, w, mix_form, t, X, Xhat, S, sel_out, codes, scal);
   } else {
-    compress_half<R>(P, n, d, row_ptr, col_idx, w, mix_form, t, X, Xhat, S, sel_out, codes, scal);
+    compress_half<R>(P, G, n, d, row_ptr, col_idx, w, mix_form, t, X, Xhat, S, sel_out, codes, scal);
     mix_half<R>(n, d, row_ptr, col_idx, w, gamma, mix_form, X, Xhat, S);
   }
   return 0;
@@ -455,7 +506,21 @@ double choco_ref_canonical_sum(int64_t d, const double* terms) {
       int32_t order, int32_t mix_form, uint64_t seed, uint64_t t, R* X, R* Xhat, R* S,            \
       int32_t* sel, int32_t* codes, double* scal) {                                               \
     QParams P{compressor, k, levels, qsgd_biased, randk_rescale, seed};                           \
-    return gossip_step<R>(n, d, row_ptr, col_idx, w, gamma, P, order, mix_form, t, X, Xhat, S,    \
+    const Segments G{0, nullptr, nullptr, nullptr};                                               \
+    return gossip_step<R>(n, d, row_ptr, col_idx, w, gamma, P, G, order, mix_form, t, X, Xhat, S, \
+                          sel, codes, scal);                                                      \
+  }                                                                                               \
+  /* layer-wise: sel is n x sum(k), scal is n x nseg x 4 */                                       \
+  int choco_ref_gossip_step_layers_##SUFFIX(                                                      \
+      int32_t n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx, const R* w, R gamma,  \
+      int32_t compressor, int32_t nseg, const int64_t* seg_start, const int64_t* seg_len,         \
+      const int64_t* seg_k, int32_t levels, int32_t qsgd_biased, int32_t randk_rescale,           \
+      int32_t order, int32_t mix_form, uint64_t seed, uint64_t t, R* X, R* Xhat, R* S,            \
+      int32_t* sel, int32_t* codes, double* scal) {                                               \
+    if (nseg < 1) return -1;                                                                      \
+    QParams P{compressor, 0, levels, qsgd_biased, randk_rescale, seed};                           \
+    const Segments G{nseg, seg_start, seg_len, seg_k};                                            \
+    return gossip_step<R>(n, d, row_ptr, col_idx, w, gamma, P, G, order, mix_form, t, X, Xhat, S, \
                           sel, codes, scal);                                                      \
   }                                                                                               \
   void choco_ref_sgd_step_##SUFFIX(int32_t n, int64_t d, R* X, const R* G, R lr) {                \

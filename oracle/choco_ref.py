@@ -20,6 +20,7 @@ _lib = None
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
 _f64p = ctypes.POINTER(ctypes.c_double)
 
 
@@ -49,6 +50,12 @@ def lib():
                           ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
                           ctypes.c_uint64, rp, rp, rp, _i32p, _i32p, _f64p]
+            f = getattr(_lib, "choco_ref_gossip_step_layers_" + suf)
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_int32, ctypes.c_int64, _i32p, _i32p, rp, real,
+                          ctypes.c_int32, ctypes.c_int32, _i64p, _i64p, _i64p, ctypes.c_int32,
+                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                          ctypes.c_uint64, ctypes.c_uint64, rp, rp, rp, _i32p, _i32p, _f64p]
             f = getattr(_lib, "choco_ref_sgd_step_" + suf)
             f.restype = None
             f.argtypes = [ctypes.c_int32, ctypes.c_int64, rp, rp, real]
@@ -115,7 +122,11 @@ class RefState:
     """State (X, Xhat, S, t) of all n workers, stepped by the oracle."""
 
     def __init__(self, X, row_ptr, col_idx, w, gamma, compressor, k=1, levels=1, qsgd_biased=1,
-                 randk_rescale=0, order=COMPRESS_THEN_MIX, mix_form=INCREMENTAL_S, seed=0):
+                 randk_rescale=0, order=COMPRESS_THEN_MIX, mix_form=INCREMENTAL_S, seed=0,
+                 layers=None):
+        """layers = (start, length, k) arrays: the operator is applied to each slice
+        [start, start + length) on its own, keeping k[l] entries of slice l (top_a /
+        random_a; ignored by the others).  None: the whole vector is one layer."""
         self.X = np.array(X, order="C", copy=True)
         self.suf, self.real = _suffix(self.X.dtype)
         self.n, self.d = self.X.shape
@@ -129,8 +140,39 @@ class RefState:
         self.qsgd_biased, self.randk_rescale = int(qsgd_biased), int(randk_rescale)
         self.order, self.mix_form, self.seed = int(order), int(mix_form), int(seed)
         self.t = 0
+        self.layers = None
+        if layers is not None:
+            self.layers = tuple(np.ascontiguousarray(a, dtype=np.int64) for a in layers)
+            assert len(self.layers) == 3 and len({a.size for a in self.layers}) == 1
+
+    def _layered_step(self, want_details):
+        sparse = self.compressor in (TOPK, RANDK)
+        start, length, k = self.layers
+        nseg = start.size
+        ktot = int(k.sum()) if sparse else 0
+        sel = codes = scal = None
+        if want_details:
+            if sparse:
+                sel = np.empty((self.n, ktot), dtype=np.int32)
+            if self.compressor in (SIGN, QSGD):
+                codes = np.zeros((self.n, self.d), dtype=np.int32)
+            scal = np.zeros((self.n, nseg, 4), dtype=np.float64)
+        rc = getattr(lib(), "choco_ref_gossip_step_layers_" + self.suf)(
+            self.n, self.d, _ptr(self.row_ptr, ctypes.c_int32), _ptr(self.col_idx, ctypes.c_int32),
+            _ptr(self.w, self.real), self.gamma, self.compressor, nseg,
+            _ptr(start, ctypes.c_int64), _ptr(length, ctypes.c_int64), _ptr(k, ctypes.c_int64),
+            self.levels, self.qsgd_biased, self.randk_rescale, self.order, self.mix_form,
+            self.seed, self.t, _ptr(self.X, self.real), _ptr(self.Xhat, self.real),
+            _ptr(self.S, self.real), _ptr(sel, ctypes.c_int32), _ptr(codes, ctypes.c_int32),
+            _ptr(scal, ctypes.c_double))
+        if rc != 0:
+            raise ValueError("oracle rejected the step arguments")
+        self.t += 1
+        return dict(sel=sel, codes=codes, scal=scal)
 
     def gossip_step(self, want_details=False):
+        if self.layers is not None:
+            return self._layered_step(want_details)
         sparse = self.compressor in (TOPK, RANDK)
         sel = codes = scal = None
         if want_details:

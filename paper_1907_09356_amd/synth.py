@@ -92,6 +92,48 @@ def irregular_graph(n, max_degree, seed):
     return adj
 
 
+def layer_table(lengths, fraction=0.01, pad=4):
+    """(start, length, k) int64 arrays for layers laid end to end, every start rounded up
+    to a multiple of pad; k[l] = max(1, floor(fraction * length[l])) (the paper's floor(a d)
+    applied per layer, with at least one entry so that no layer is silent)."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    start = np.zeros_like(lengths)
+    pos = 0
+    for l, ln in enumerate(lengths):
+        start[l] = pos
+        pos = (pos + int(ln) + pad - 1) // pad * pad
+    k = np.maximum(1, np.floor(fraction * lengths).astype(np.int64))
+    return start, lengths.copy(), k
+
+
+def layers_dim(layers):
+    """Length of the flat vector that a layer table describes."""
+    start, length, _ = layers
+    return int(start[-1] + length[-1])
+
+
+def resnet20_like_lengths():
+    """Parameter counts, layer by layer, of a 20-layer CIFAR residual network with 16/32/64
+    channels, batch-norm scale and shift after every convolution and 1x1 projection
+    shortcuts (272,474 parameters in all: the 0.27 M model of Section 5).  Only the
+    sizes matter here: they give the mix of many small and a few 36,864-entry layers that
+    per-layer compression meets."""
+    out = []
+
+    def conv(cin, cout, ksz):
+        out.extend([cin * cout * ksz * ksz, cout, cout])   # weights, bn scale, bn shift
+
+    conv(3, 16, 3)
+    for stage, (cin, cout) in enumerate(((16, 16), (16, 32), (32, 64))):
+        for block in range(3):
+            conv(cin if block == 0 else cout, cout, 3)
+            conv(cout, cout, 3)
+            if block == 0 and stage > 0:
+                conv(cin, cout, 1)
+    out.extend([64 * 10, 10])
+    return np.asarray(out, dtype=np.int64)
+
+
 def dense_to_csr(W):
     W = np.asarray(W)
     n = W.shape[0]

@@ -562,3 +562,153 @@ def test_metrics_against_numpy():
     assert math.isclose(m["mean_norm"], np.linalg.norm(xbar), rel_tol=1e-12)
     assert math.isclose(m["psi"], ((X - xbar) ** 2).sum() + ((X - st.Xhat) ** 2).sum(),
                         rel_tol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# layer-wise compression (Section 5: the operator is applied to every layer on its own)
+# --------------------------------------------------------------------------
+LAYER_Q = [
+    dict(compressor=ref.TOPK),
+    dict(compressor=ref.RANDK),
+    dict(compressor=ref.RANDK, randk_rescale=1),
+    dict(compressor=ref.SIGN),
+    dict(compressor=ref.QSGD, levels=4),
+    dict(compressor=ref.QSGD, levels=4, qsgd_biased=0),
+]
+
+
+def test_layer_sizes_of_the_small_model():
+    # Section 5: the image model has 0.27 million parameters; Table 1 prints 1.04 MB for
+    # the uncompressed fp32 vector, i.e. 4 d bytes in MiB
+    lengths = synth.resnet20_like_lengths()
+    d = int(lengths.sum())
+    assert round(d / 1e6, 2) == 0.27
+    assert round(4 * d / 2**20, 2) == 1.04
+    start, length, k = synth.layer_table(lengths, fraction=0.01)
+    assert np.all(start % 4 == 0) and np.all(start[1:] >= start[:-1] + length[:-1])
+    assert synth.layers_dim((start, length, k)) == d     # only the last layer is ragged
+
+
+@pytest.mark.parametrize("q", LAYER_Q)
+@pytest.mark.parametrize("order", [ref.COMPRESS_THEN_MIX, ref.MIX_THEN_COMPRESS])
+def test_one_layer_is_the_whole_vector(q, order):
+    n, d, k = 5, 300, 17
+    X = synth.normal_state(n, d, seed=4)
+    topo = synth.ring_csr(n)
+    flat = ref.RefState(X, *topo, gamma=0.3, k=k, order=order, seed=9, **q)
+    lay = ref.RefState(X, *topo, gamma=0.3, order=order, seed=9,
+                       layers=([0], [d], [k]), **q)
+    for _ in range(4):
+        a = flat.gossip_step(want_details=True)
+        b = lay.gossip_step(want_details=True)
+        for name in ("sel", "codes"):
+            assert (a[name] is None) == (b[name] is None)
+            if a[name] is not None:
+                assert np.array_equal(a[name], b[name])
+        assert np.array_equal(a["scal"], b["scal"][:, 0, :])
+        assert np.array_equal(flat.X, lay.X) and np.array_equal(flat.Xhat, lay.Xhat)
+        assert np.array_equal(flat.S, lay.S)
+
+
+@pytest.mark.parametrize("q", [dict(compressor=ref.TOPK), dict(compressor=ref.SIGN)])
+def test_layers_of_deterministic_operators_are_compressed_alone(q):
+    # each slice gets exactly what the operator gives for that slice as a vector of its own
+    # (own norm, own length in the scale, own k); entries in no layer are never sent
+    n = 3
+    start = np.array([0, 12, 40, 300], dtype=np.int64)
+    length = np.array([10, 28, 257, 45], dtype=np.int64)   # gaps at 10..11 and 297..299
+    k = np.array([3, 1, 40, 0], dtype=np.int64)
+    d = 350                                                # and a tail 345..349 in no layer
+    X = synth.normal_state(n, d, seed=8, dtype=np.float64)
+    st = ref.RefState(X, *synth.ring_csr(n, wdtype=np.float64), gamma=0.2,
+                      layers=(start, length, k), **q)
+    st.gossip_step()
+    covered = np.zeros(d, dtype=bool)
+    for i in range(n):
+        for l in range(4):
+            sl = slice(start[l], start[l] + length[l])
+            covered[sl] = True
+            if q["compressor"] == ref.TOPK and k[l] == 0:
+                assert not st.Xhat[i, sl].any()
+                continue
+            alone = ref.compress(q["compressor"], X[i, sl], k=int(max(k[l], 1)))
+            assert np.array_equal(st.Xhat[i, sl], alone["q"])   # xhat was 0, so xhat = q
+    assert not st.Xhat[:, ~covered].any()
+
+
+def test_random_layers_use_the_words_of_their_global_coordinates():
+    # random_a per layer: the k[l] smallest words among the layer's own coordinates win,
+    # each coordinate drawing the word of its index in the whole vector
+    n, seed = 2, 77
+    start = np.array([0, 20, 100], dtype=np.int64)
+    length = np.array([18, 80, 61], dtype=np.int64)
+    k = np.array([4, 9, 61], dtype=np.int64)
+    d = 161
+    X = synth.normal_state(n, d, seed=3)
+    st = ref.RefState(X, *synth.ring_csr(n), gamma=0.2, compressor=ref.RANDK, seed=seed,
+                      layers=(start, length, k))
+    for t in range(3):
+        det = st.gossip_step(want_details=True)
+        for i in range(n):
+            want = []
+            for l in range(3):
+                es = np.arange(start[l], start[l] + length[l])
+                words = np.array([ref.random_word(seed, t, i, int(e), ref.STREAM_RANDK) for e in es])
+                order = np.lexsort((es, words))
+                want.extend(sorted(es[order[:k[l]]]))
+            assert list(det["sel"][i]) == want
+
+
+def test_quantised_layers_have_their_own_norm_and_tau():
+    # gsgd_b per layer, formula of Appendix C retyped for a slice: norm and tau from the
+    # slice, dither word from the global coordinate
+    n, s, seed = 2, 4, 5
+    start = np.array([0, 8], dtype=np.int64)
+    length = np.array([7, 33], dtype=np.int64)
+    d = 41
+    X = synth.normal_state(n, d, seed=12, dtype=np.float64)
+    X[:, 8:] *= 100.0                                     # very different norms
+    st = ref.RefState(X, *synth.ring_csr(n, wdtype=np.float64), gamma=0.1, compressor=ref.QSGD,
+                      levels=s, seed=seed, layers=(start, length, [0, 0]))
+    det = st.gossip_step(want_details=True)
+    for i in range(n):
+        for l in range(2):
+            sl = slice(start[l], start[l] + length[l])
+            v = X[i, sl]
+            nrm = math.sqrt(float((v * v).sum()))
+            dl = int(length[l])
+            tau = 1.0 + min(dl / s**2, math.sqrt(dl) / s)
+            assert det["scal"][i, l, 1] == pytest.approx(nrm, rel=1e-14)
+            for j, e in enumerate(range(start[l], start[l] + length[l])):
+                u = (ref.random_word(seed, 0, i, e, ref.STREAM_DITHER) >> 8) / 2.0**24
+                level = math.floor(s * abs(v[j]) / nrm + u)
+                want = math.copysign(level * nrm / (tau * s), v[j])
+                assert abs(det["codes"][i, e]) == level
+                assert st.Xhat[i, e] == pytest.approx(want, rel=1e-12, abs=1e-300)
+    assert not st.Xhat[:, 7].any()     # the gap
+
+
+@pytest.mark.parametrize("q", LAYER_Q)
+def test_layered_steps_keep_the_average_and_converge(q):
+    # Assumption 3 does not depend on how Q is built: the average is preserved, and with
+    # a contractive operator per layer the consensus error still decays (Theorem 2 applies
+    # with the smallest per-layer delta)
+    lengths = [40, 5, 130, 64]
+    layers = synth.layer_table(lengths, fraction=0.25)
+    d = synth.layers_dim(layers)
+    n = 6
+    X = synth.normal_state(n, d, seed=21, dtype=np.float64)
+    inside = np.zeros(d, dtype=bool)
+    for a, ln in zip(layers[0], layers[1]):
+        inside[a:a + ln] = True
+    X[:, ~inside] = 0.0      # padding between layers is never sent, so it must not differ
+    st = ref.RefState(X, *synth.ring_csr(n, wdtype=np.float64), gamma=0.05, seed=2, layers=layers, **q)
+    mean0 = st.X.mean(0)
+    c0 = st.metrics()["consensus"]
+    for _ in range(600):
+        st.gossip_step()
+    m = st.metrics()
+    assert np.linalg.norm(st.X.mean(0) - mean0) <= 1e-11 * max(1.0, float(np.abs(st.Xhat).max()))
+    unbiased = q.get("randk_rescale") or q.get("qsgd_biased") == 0
+    if not unbiased:
+        assert m["consensus"] < 1e-3 * c0
