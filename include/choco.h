@@ -83,7 +83,28 @@ typedef struct {
   int32_t mix_form;      /* CHOCO_MIX_*                                                   */
   uint64_t seed;         /* shared seed of the random operators (Appendix C, random_a)    */
   void *stream;          /* hipStream_t owned by the caller; NULL = the null stream       */
+  /* Layer-wise compression (Section 5, set-up of the deep-learning experiments: the
+     operator is applied to every layer of the network on its own).  nlayers = 0: the whole
+     vector is one layer and the three pointers are ignored.  Otherwise HOST arrays of
+     nlayers entries, copied during choco_init: layer l is the slice
+     [layer_start[l], layer_start[l] + layer_len[l]) of every worker's vector and is
+     compressed as a vector of its own - its own norm and its own length in the scales of
+     SIGN and QSGD, layer_k[l] kept entries (0 <= layer_k[l] <= layer_len[l], at least one
+     entry kept over all layers) for TOPK and RANDK, the field k above is then ignored.
+     The layers must tile the vector in order, each start padded to a multiple of 4:
+     layer_start[0] = 0, layer_start[l+1] = layer_start[l] + layer_len[l] rounded up to a
+     multiple of 4, d = layer_start[nlayers-1] + layer_len[nlayers-1].  The padding entries
+     are never transmitted (keep them zero in X and G).  A layer may have at most
+     CHOCO_MAX_LAYER_LEN entries (it is compressed by one workgroup out of its registers);
+     IDENTITY, a non-default mix_form and layers beyond that length are
+     CHOCO_E_UNSUPPORTED.  layer_k_host may be NULL for SIGN and QSGD.                    */
+  int32_t nlayers;
+  const int64_t *layer_start_host;
+  const int64_t *layer_len_host;
+  const int64_t *layer_k_host;
 } choco_config;
+
+#define CHOCO_MAX_LAYER_LEN 40960
 
 /* Bytes of device workspace choco_init needs for this configuration (Xhat, S, the CSR
    copy and scratch for the operators).  Validates the scalar fields of cfg only. */
@@ -152,6 +173,14 @@ int choco_nsum(choco_ctx *ctx, float **s_dev);
 int choco_last_selection(choco_ctx *ctx, int32_t *idx_dev, float *val_dev);
 int choco_set_capture(choco_ctx *ctx, int32_t *codes_dev);
 int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
+/* Layer-wise configurations only (else CHOCO_E_INVAL): 4 doubles per worker and layer
+   (n * nlayers * 4, worker-major) from the last step.  SIGN: {||v_l||_1, scale, 0, 0};
+   QSGD: {sum v_l^2, ||v_l||_2, s/||v_l||_2, ||v_l||_2/(tau_l s)}; TOPK/RANDK: {threshold
+   key, entries kept at the threshold key, entries holding that key, layer_k[l]}.  With
+   layers, choco_last_selection returns sum(layer_k) pairs per worker, layer after layer,
+   and choco_last_scalars is CHOCO_E_UNSUPPORTED.  Synchronises the stream. */
+int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
+
 
 /* Step counter t (keys the random operators; set it to resume a run exactly). */
 int choco_get_step(choco_ctx *ctx, uint64_t *t_host);

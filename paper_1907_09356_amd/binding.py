@@ -20,7 +20,7 @@ MIX_AUTO, MIX_INCREMENTAL_S, MIX_DIRECT = 0, 1, 2
 EXPORTS = [
     "choco_workspace_bytes", "choco_init", "choco_gossip_step", "choco_sgd_step", "choco_step",
     "choco_momentum_step", "choco_step_momentum", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
-    "choco_set_capture", "choco_last_scalars", "choco_get_step", "choco_set_step", "choco_sync",
+    "choco_set_capture", "choco_last_scalars", "choco_layer_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
     "choco_profile_report",
 ]
@@ -44,6 +44,10 @@ class ChocoConfig(ctypes.Structure):
         ("mix_form", ctypes.c_int32),
         ("seed", ctypes.c_uint64),
         ("stream", ctypes.c_void_p),
+        ("nlayers", ctypes.c_int32),
+        ("layer_start_host", ctypes.POINTER(ctypes.c_int64)),
+        ("layer_len_host", ctypes.POINTER(ctypes.c_int64)),
+        ("layer_k_host", ctypes.POINTER(ctypes.c_int64)),
     ]
 
 
@@ -81,6 +85,7 @@ def lib():
         L.choco_last_selection.argtypes = [vp, vp, vp]
         L.choco_set_capture.argtypes = [vp, vp]
         L.choco_last_scalars.argtypes = [vp, dp]
+        L.choco_layer_scalars.argtypes = [vp, dp]
         L.choco_get_step.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.choco_set_step.argtypes = [vp, ctypes.c_uint64]
         L.choco_sync.argtypes = [vp]
@@ -108,9 +113,10 @@ def _check(code, what):
 
 def make_config(n, d, row_ptr, col_idx, w, gamma, compressor, k=1, levels=1, qsgd_biased=1,
                 randk_rescale=0, order=ORDER_COMPRESS_THEN_MIX, mix_form=MIX_AUTO, seed=0, ld=0,
-                stream=None):
+                stream=None, layers=None):
     """Fill a choco_config.  Returns (config, keepalive) - the numpy arrays the
-    config points into must outlive the calls that read it."""
+    config points into must outlive the calls that read it.  layers = (start, length, k)
+    arrays switches layer-wise compression on (k may be None for SIGN / QSGD)."""
     row_ptr = None if row_ptr is None else np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = None if col_idx is None else np.ascontiguousarray(col_idx, dtype=np.int32)
     w = None if w is None else np.ascontiguousarray(w, dtype=np.float32)
@@ -124,7 +130,24 @@ def make_config(n, d, row_ptr, col_idx, w, gamma, compressor, k=1, levels=1, qsg
     cfg.qsgd_biased, cfg.randk_rescale = int(qsgd_biased), int(randk_rescale)
     cfg.order, cfg.mix_form, cfg.seed = int(order), int(mix_form), int(seed)
     cfg.stream = stream
-    return cfg, (row_ptr, col_idx, w)
+    keep = [row_ptr, col_idx, w]
+    cfg.nlayers = 0
+    if layers is not None:
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        start, length, lk = layers
+        start = np.ascontiguousarray(start, dtype=np.int64)
+        length = np.ascontiguousarray(length, dtype=np.int64)
+        assert start.size == length.size
+        cfg.nlayers = int(start.size)
+        cfg.layer_start_host = start.ctypes.data_as(i64p)
+        cfg.layer_len_host = length.ctypes.data_as(i64p)
+        keep += [start, length]
+        if lk is not None:
+            lk = np.ascontiguousarray(lk, dtype=np.int64)
+            assert lk.size == start.size
+            cfg.layer_k_host = lk.ctypes.data_as(i64p)
+            keep.append(lk)
+    return cfg, tuple(keep)
 
 
 def workspace_bytes(cfg):
@@ -159,6 +182,9 @@ class Choco:
                                 ctypes.byref(ctx)), "choco_init")
         self.ctx = ctx
         self.k = int(self.cfg.k)
+        self.nlayers = int(self.cfg.nlayers)
+        if self.nlayers and compressor in (Q_TOPK, Q_RANDK):
+            self.k = int(np.asarray(kw["layers"][2], dtype=np.int64).sum())   # pairs per worker
         self._capture = None
 
     def close(self):
@@ -239,6 +265,12 @@ class Choco:
         out = np.zeros((self.n, 6), dtype=np.float64)
         _check(lib().choco_last_scalars(self.ctx, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))),
                "choco_last_scalars")
+        return out
+
+    def layer_scalars(self):
+        out = np.zeros((self.n, self.nlayers, 4), dtype=np.float64)
+        _check(lib().choco_layer_scalars(self.ctx, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))),
+               "choco_layer_scalars")
         return out
 
     def get_step(self):

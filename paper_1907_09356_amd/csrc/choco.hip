@@ -14,6 +14,7 @@
 
 #include "choco.h"
 #include "choco_kernels.h"
+#include "choco_layers.h"
 
 using namespace choco;
 
@@ -30,6 +31,8 @@ struct choco_ctx {
   bool multipart;         // long candidate lists: the select runs as three multi-block launches
   bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
+  int nlayers;            // > 0: the operator is applied layer by layer
+  int class_first[4];     // layer_ids[class_first[c] .. class_first[c+1]) = layers of size class c
   uint64_t t;             // step counter
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
@@ -53,7 +56,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
-      mpart, mout, total;
+      layers, layer_ids, layer_scal, mpart, mout, total;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
   bool multipart;
@@ -70,15 +73,58 @@ int resolve_mix_form(const choco_config& c) {
 
 int64_t resolve_ld(const choco_config& c) { return c.ld == 0 ? (c.d + 3) / 4 * 4 : c.ld; }
 
+// Kept entries per worker and step: k, or the sum over the layers.
+int64_t kept_per_worker(const choco_config& c) {
+  if (!is_sparse(c.compressor)) return 0;
+  if (c.nlayers <= 0) return c.k;
+  int64_t sum = 0;
+  for (int32_t l = 0; l < c.nlayers; ++l) sum += c.layer_k_host[l];
+  return sum;
+}
+
+// Size classes of the layer kernel: 64, 256 or 1024 threads, kLayerVecs 4-vectors each.
+int layer_class(int64_t len) {
+  const int64_t per_thread = 4 * kLayerVecs;
+  return len <= 64 * per_thread ? 0 : len <= 256 * per_thread ? 1 : 2;
+}
+
+int check_layers(const choco_config* c) {
+  if (c->nlayers < 0) return CHOCO_E_INVAL;
+  if (c->nlayers == 0) return CHOCO_OK;
+  if (!c->layer_start_host || !c->layer_len_host) return CHOCO_E_INVAL;
+  const bool sparse = is_sparse(c->compressor);
+  if (sparse && !c->layer_k_host) return CHOCO_E_INVAL;
+  int64_t expect = 0, end = 0, ktot = 0;
+  bool too_long = false;
+  for (int32_t l = 0; l < c->nlayers; ++l) {
+    const int64_t start = c->layer_start_host[l], len = c->layer_len_host[l];
+    if (start != expect || len < 1) return CHOCO_E_INVAL;
+    end = start + len;
+    if (end > c->d) return CHOCO_E_INVAL;
+    expect = (end + 3) / 4 * 4;
+    if (len > kMaxLayerLen) too_long = true;
+    if (sparse) {
+      const int64_t k = c->layer_k_host[l];
+      if (k < 0 || k > len) return CHOCO_E_INVAL;
+      ktot += k;
+    }
+  }
+  if (end != c->d || (sparse && ktot < 1)) return CHOCO_E_INVAL;
+  if (too_long || c->compressor == CHOCO_Q_IDENTITY || c->mix_form != CHOCO_MIX_AUTO)
+    return CHOCO_E_UNSUPPORTED;
+  return CHOCO_OK;
+}
+
 // Scalar-field validation shared by choco_workspace_bytes and choco_init.
 int check_scalars(const choco_config* c) {
   if (!c) return CHOCO_E_INVAL;
   if (c->n < 1 || c->d < 1 || c->d >= (int64_t)1 << 31) return CHOCO_E_INVAL;
+  if (c->n > 65535) return CHOCO_E_UNSUPPORTED;   // workers are a grid dimension of the launches
   const int64_t ld = resolve_ld(*c);
   if (ld < c->d || (ld & 3) != 0) return CHOCO_E_INVAL;
   if (!(c->gamma > 0.0f) || !std::isfinite(c->gamma)) return CHOCO_E_INVAL;
   if (c->compressor < CHOCO_Q_IDENTITY || c->compressor > CHOCO_Q_QSGD) return CHOCO_E_INVAL;
-  if (is_sparse(c->compressor) && (c->k < 1 || c->k > c->d)) return CHOCO_E_INVAL;
+  if (is_sparse(c->compressor) && c->nlayers == 0 && (c->k < 1 || c->k > c->d)) return CHOCO_E_INVAL;
   if (c->compressor == CHOCO_Q_QSGD && c->levels < 1) return CHOCO_E_INVAL;
   if (c->order != CHOCO_ORDER_COMPRESS_THEN_MIX && c->order != CHOCO_ORDER_MIX_THEN_COMPRESS)
     return CHOCO_E_INVAL;
@@ -86,7 +132,7 @@ int check_scalars(const choco_config* c) {
   // combinations this build does not implement
   if (!is_sparse(c->compressor) && resolve_mix_form(*c) == CHOCO_MIX_INCREMENTAL_S)
     return CHOCO_E_UNSUPPORTED;
-  return CHOCO_OK;
+  return check_layers(c);
 }
 
 // Candidates wanted beyond k so that the guess survives the step-to-step drift of the
@@ -110,6 +156,9 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   const int64_t ld = resolve_ld(c);
   const size_t state = (size_t)c.n * (size_t)ld * sizeof(float);
   const bool sparse = is_sparse(c.compressor);
+  const bool layered = c.nlayers > 0;
+  const bool guessed = sparse && !layered;   // whole-row select by guessed threshold
+  const int64_t kept = kept_per_worker(c);
   size_t off = 0;
   auto take = [&off](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   L.xhat = take(state);
@@ -126,7 +175,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
                           ? (size_t)c.n * (size_t)L.nchunks * sizeof(double) : 0);
   L.group_sums = take(dense_stat ? (size_t)c.n * (size_t)L.ngroups * sizeof(double) : 0);
   int64_t cap = 0;
-  if (sparse) {
+  if (guessed) {
     cap = 4 * c.k;
     if (cap < c.d / 128) cap = c.d / 128;
     if (cap < 8192) cap = 8192;
@@ -136,7 +185,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // sub-lists: block b of a worker appends to sub-list b % kSegs; each gets twice its even
   // share of the capacity, but never more than the blocks feeding it can produce
   int64_t seg_cap = 0;
-  if (sparse) {
+  if (guessed) {
     const int64_t per_block = 256 * kCompactVecs * 4;
     const int64_t nblocks = (c.d + per_block - 1) / per_block;
     const int64_t feeders = (nblocks + kSegs - 1) / kSegs;
@@ -144,18 +193,21 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
     seg_cap = std::min<int64_t>(seg_cap, feeders * per_block);
   }
   L.seg_cap = (uint32_t)seg_cap;
-  L.hist16 = take(sparse ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
-  L.cand = take(sparse ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
-  L.sel_idx = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(int32_t) : 0);
-  L.sel_val = take(sparse ? (size_t)c.n * (size_t)c.k * sizeof(float) : 0);
-  L.multipart = sparse && expected_candidates(c) > 16384.0;
+  L.hist16 = take(guessed ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
+  L.cand = take(guessed ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
+  L.sel_idx = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
+  L.sel_val = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(float) : 0);
+  L.multipart = guessed && expected_candidates(c) > 16384.0;
   L.hist_parts = take(L.multipart ? (size_t)c.n * kRefineParts * kBins * sizeof(uint32_t) : 0);
   L.small_list = take(L.multipart ? (size_t)c.n * kSmallCap * sizeof(uint2) : 0);
   // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
   // beside its other arrays), else one byte per entry
-  L.bitmap_words = (sparse && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
+  L.bitmap_words = (guessed && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
+  L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
+  L.layer_ids = take((size_t)c.nlayers * sizeof(int32_t));
+  L.layer_scal = take((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -216,13 +268,14 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
   "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
-  "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd"};
+  "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
+  "k_layer_compress", "k_layer_compress_sgd"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
 // Brackets one launch with two events when profiling is on (no-op otherwise).
@@ -436,8 +489,74 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   return CHOCO_OK;
 }
 
+// Layer-wise operators: one block per (worker, layer) does the whole compression of the
+// layer; the mix and (for top_a / random_a) the message kernels are those of the whole-row
+// path.  Dense operators use the direct mix form, sparsifying ones the neighbour sums.
+template <int COMP, bool NT>
+int gossip_layers(choco_ctx* ctx, const Args& F) {
+  constexpr bool sparse = (COMP == Q_TOPK || COMP == Q_RANDK);
+  Args A = F;
+  if (!F.deferred_sgd) A.G = nullptr;
+  const bool fused = F.G != nullptr && !F.deferred_sgd;
+  const int32_t nvec = (A.d + 3) >> 2;
+  const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
+  const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
+  auto launch_mix = [&](const Args& M, bool carries) {
+    if (sparse)
+      LAUNCH(ctx, carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
+             dim3(256), 0, M);
+    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, M, carries);
+    else launch_mix_direct_global(ctx, M);
+  };
+  bool x_touched = false;
+  if (mix_first) {
+    // only a mix kernel that can carry the local update is handed F
+    const bool carries = fused && (sparse || ctx->rpw != 0);
+    launch_mix(carries ? F : A, carries);
+    x_touched = true;
+  }
+  // random_a never reads X in the layer kernel, so it cannot carry the local update
+  Args C = (x_touched || COMP == Q_RANDK) ? A : F;
+  if (COMP == Q_RANDK) C.G = nullptr;
+  const int kid = (C.G != nullptr) ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
+  const int* cf = ctx->class_first;
+  if (cf[1] > cf[0])
+    LAUNCH(ctx, kid, (k_layer_compress<COMP, 64, NT>), dim3((unsigned)(cf[1] - cf[0]), (unsigned)A.n), dim3(64),
+           0, C, (int32_t)cf[0]);
+  if (cf[2] > cf[1])
+    LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(cf[2] - cf[1]), (unsigned)A.n), dim3(256),
+           0, C, (int32_t)cf[1]);
+  if (cf[3] > cf[2])
+    LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)(cf[3] - cf[2]), (unsigned)A.n),
+           dim3(1024), 0, C, (int32_t)cf[2]);
+  if (sparse) {
+    const unsigned kblocks = (unsigned)((A.k + 255) / 256);
+    if (COMP == Q_RANDK)
+      LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+    LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
+    LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  }
+  if (!mix_first) {
+    const bool last_carries = F.deferred_sgd != 0;
+    Args L = A;
+    if (last_carries) L.G = F.G;
+    launch_mix(L, last_carries);
+  }
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
 template <bool NT>
 int gossip_any(choco_ctx* ctx, const Args& A) {
+  if (ctx->nlayers > 0) {
+    switch (ctx->cfg.compressor) {
+      case CHOCO_Q_SIGN: return gossip_layers<Q_SIGN, NT>(ctx, A);
+      case CHOCO_Q_QSGD: return gossip_layers<Q_QSGD, NT>(ctx, A);
+      case CHOCO_Q_TOPK: return gossip_layers<Q_TOPK, NT>(ctx, A);
+      case CHOCO_Q_RANDK: return gossip_layers<Q_RANDK, NT>(ctx, A);
+      default: return CHOCO_E_UNSUPPORTED;
+    }
+  }
   switch (ctx->cfg.compressor) {
     case CHOCO_Q_IDENTITY: return gossip_dense<Q_IDENTITY, NT>(ctx, A);
     case CHOCO_Q_SIGN: return gossip_dense<Q_SIGN, NT>(ctx, A);
@@ -568,6 +687,9 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->cfg.row_ptr_host = nullptr;
   ctx->cfg.col_idx_host = nullptr;
   ctx->cfg.w_host = nullptr;
+  ctx->cfg.layer_start_host = nullptr;
+  ctx->cfg.layer_len_host = nullptr;
+  ctx->cfg.layer_k_host = nullptr;
   ctx->stream = (hipStream_t)cfg->stream;
   ctx->maxdeg = maxdeg;
   ctx->nnz = nnz;
@@ -578,7 +700,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   // (sampled histogram, new guess, rebuild) that are launched every step and normally exit at
   // once.  For short rows even those idle launches show, and the select kernel's own row scan
   // (one block per worker) is quick enough, so they are left out.
-  ctx->fallback_chain = cfg->d > ((int64_t)1 << 21);
+  ctx->fallback_chain = cfg->d > ((int64_t)1 << 21) && cfg->nlayers == 0;
+  ctx->nlayers = cfg->nlayers;
   // Non-temporal accesses for all but tiny states: measured faster even when the state
   // would fit in cache (a kernel boundary on this multi-die part writes dirty L2 lines
   // back anyway); the cached path stays for states under 4 MB per array.
@@ -617,7 +740,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.codes = nullptr;
   // with few group sums the fused apply kernel finishes the norm tree itself (one launch less)
   A.fold_finalise = (ctx->rpw != 0 && cfg->order == CHOCO_ORDER_COMPRESS_THEN_MIX && L.ngroups <= 256) ? 1 : 0;
-  A.k = ctx->sparse ? cfg->k : 0;
+  A.k = kept_per_worker(*cfg);
   A.hist16 = (uint32_t*)(base + L.hist16);
   A.cand = (uint2*)(base + L.cand);
   A.cand_cap = L.cand_cap;
@@ -627,7 +750,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->multipart = L.multipart;
   uint32_t guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
   uint32_t shift0 = 0;
-  if (ctx->sparse) {
+  if (ctx->sparse && cfg->nlayers == 0) {
     const double kk = (double)cfg->k, dd = (double)cfg->d;
     const double extra = extra_candidates(*cfg);
     A.extra = (uint32_t)extra;
@@ -663,7 +786,32 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.bitmap = (uint32_t*)(base + L.bitmap);
   A.bitmap_words = L.bitmap_words;
   A.randk_rescale = cfg->randk_rescale ? 1 : 0;
-  A.randk_scale = ctx->sparse ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
+  A.randk_scale = (ctx->sparse && cfg->nlayers == 0) ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
+  A.qsgd_biased = cfg->qsgd_biased ? 1 : 0;
+  // layer tables: descriptors in layer order, layer numbers grouped by size class
+  std::vector<LayerDesc> layers((size_t)cfg->nlayers);
+  std::vector<int32_t> layer_ids;
+  A.nlayers = cfg->nlayers;
+  A.layers = (const LayerDesc*)(base + L.layers);
+  A.layer_ids = (const int32_t*)(base + L.layer_ids);
+  A.layer_scal = (double*)(base + L.layer_scal);
+  if (cfg->nlayers > 0) {
+    int64_t sel_base = 0;
+    for (int32_t l = 0; l < cfg->nlayers; ++l) {
+      LayerDesc& D = layers[(size_t)l];
+      D.start = (int32_t)cfg->layer_start_host[l];
+      D.len = (int32_t)cfg->layer_len_host[l];
+      D.k = ctx->sparse ? (int32_t)cfg->layer_k_host[l] : 0;
+      D.sel_base = (int32_t)sel_base;
+      sel_base += D.k;
+    }
+    for (int cls = 0; cls < 3; ++cls) {
+      ctx->class_first[cls] = (int)layer_ids.size();
+      for (int32_t l = 0; l < cfg->nlayers; ++l)
+        if (layer_class(layers[(size_t)l].len) == cls) layer_ids.push_back(l);
+    }
+    ctx->class_first[3] = (int)layer_ids.size();
+  }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
   ctx->metrics_part = (double*)(base + L.mpart);
@@ -681,6 +829,12 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   if (e == hipSuccess)
     e = hipMemcpyAsync(base + L.w, cfg->w_host, (size_t)nnz * sizeof(float), hipMemcpyHostToDevice,
                        ctx->stream);
+  if (e == hipSuccess && cfg->nlayers > 0)
+    e = hipMemcpyAsync(base + L.layers, layers.data(), layers.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
+                       ctx->stream);
+  if (e == hipSuccess && cfg->nlayers > 0)
+    e = hipMemcpyAsync(base + L.layer_ids, layer_ids.data(), layer_ids.size() * sizeof(int32_t),
+                       hipMemcpyHostToDevice, ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {
     ctl0.resize((size_t)cfg->n);
@@ -789,8 +943,18 @@ int choco_set_capture(choco_ctx* ctx, int32_t* codes_dev) {
   return CHOCO_OK;
 }
 
+int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
+  if (!ctx || ctx->destroyed || !scalars_host || ctx->nlayers == 0) return CHOCO_E_INVAL;
+  const Args& A = ctx->args;
+  HIP_TRY(ctx, hipMemcpyAsync(scalars_host, A.layer_scal, (size_t)A.n * (size_t)A.nlayers * 4 * sizeof(double),
+                              hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return CHOCO_OK;
+}
+
 int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
   if (!ctx || ctx->destroyed || !scalars_host) return CHOCO_E_INVAL;
+  if (ctx->nlayers > 0) return CHOCO_E_UNSUPPORTED;
   const Args& A = ctx->args;
   std::vector<WorkerCtl> ctl((size_t)A.n);
   HIP_TRY(ctx, hipMemcpyAsync(ctl.data(), A.ctl, ctl.size() * sizeof(WorkerCtl), hipMemcpyDeviceToHost,

@@ -65,6 +65,14 @@ struct WorkerCtl {
   uint64_t kstar;       // composite key of the k-th largest entry: kept <=> key >= kstar
 };
 
+// One layer of a worker's vector when the operator is applied layer by layer.
+struct LayerDesc {
+  int32_t start;     // first entry (a multiple of 4)
+  int32_t len;       // entries
+  int32_t k;         // top_a / random_a: entries kept of this layer
+  int32_t sel_base;  // where the layer's kept entries start in the worker's selection list
+};
+
 struct Args {
   int32_t n;
   int32_t d;
@@ -114,9 +122,34 @@ struct Args {
   int32_t fold_xhat;     // the final mix also applies xhat += q (bitmap rows, compress-then-mix)
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
+  // layer-wise compression (nlayers = 0: the whole row is compressed as one vector)
+  const LayerDesc* layers;   // sorted by start; they tile the row up to the 4-entry padding
+  int32_t nlayers;
+  const int32_t* layer_ids;  // layer numbers grouped by size class
+  double* layer_scal;        // n x nlayers x 4: norms and scales / threshold of the last step
+  int32_t qsgd_biased;
   // randomness
   uint32_t seed_lo, seed_hi, t_lo, t_hi;
 };
+
+// The layer that holds entry e of a row.
+__device__ __forceinline__ int layer_of(const Args& A, int e) {
+  int lo = 0, hi = A.nlayers - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (A.layers[mid].start <= e) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
+// random_a, unbiased version: the factor d / k of the vector entry e was compressed in
+// (Appendix C) - the whole row, or the layer of e.
+__device__ __forceinline__ float randk_scale_at(const Args& A, int e) {
+  if (!A.nlayers) return A.randk_scale;
+  const LayerDesc L = A.layers[layer_of(A, e)];
+  return (float)((double)L.len / (double)L.k);
+}
 
 // ---------------------------------------------------------------------------
 // Memory helpers.  NT = non-temporal (streaming) access.
@@ -1532,9 +1565,10 @@ __global__ __launch_bounds__(256) void k_sel_values(Args A) {
   const int j = blockIdx.y;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= A.k) return;
-  const int64_t o = (int64_t)j * A.ld + A.sel_idx[(int64_t)j * A.k + m];
+  const int e = A.sel_idx[(int64_t)j * A.k + m];
+  const int64_t o = (int64_t)j * A.ld + e;
   float val = x_entry(A, o) - A.Xhat[o];
-  if (A.randk_rescale) val = A.randk_scale * val;
+  if (A.randk_rescale) val = randk_scale_at(A, e) * val;
   A.sel_val[(int64_t)j * A.k + m] = val;
 }
 
@@ -1562,7 +1596,7 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
     if (was_kept(A, j2, e)) {
       const int64_t o = (int64_t)j2 * A.ld + e;
       float q = x_entry(A, o) - A.Xhat[o];
-      if (A.randk_rescale) q = A.randk_scale * q;
+      if (A.randk_rescale) q = randk_scale_at(A, e) * q;
       acc = acc + A.w[p2] * q;
     }
   }

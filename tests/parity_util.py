@@ -27,7 +27,7 @@ class Pair:
     """One GPU context and one oracle state built from the same X0."""
 
     def __init__(self, X0, topo, gamma, compressor, k=1, levels=1, qsgd_biased=1, randk_rescale=0,
-                 order=binding.ORDER_COMPRESS_THEN_MIX, mix_form=binding.MIX_AUTO, seed=0):
+                 order=binding.ORDER_COMPRESS_THEN_MIX, mix_form=binding.MIX_AUTO, seed=0, layers=None):
         import torch
         self.torch = torch
         X0 = np.ascontiguousarray(X0, dtype=np.float32)
@@ -36,14 +36,19 @@ class Pair:
         dev = torch.device("cuda:0")
         self.X = torch.zeros((self.n, self.ld), dtype=torch.float32, device=dev)
         self.X[:, :self.d] = torch.from_numpy(X0).to(dev)
-        self.compressor, self.k = compressor, k
+        self.compressor, self.k, self.layers = compressor, k, layers
+        extra = {}
+        if layers is not None:
+            extra["layers"] = layers
+            if compressor in (binding.Q_TOPK, binding.Q_RANDK):
+                self.k = int(np.asarray(layers[2]).sum())
         self.gpu = binding.Choco(self.X, self.d, *topo, gamma, compressor, k=k, levels=levels,
                                  qsgd_biased=qsgd_biased, randk_rescale=randk_rescale, order=order,
-                                 mix_form=mix_form, seed=seed)
+                                 mix_form=mix_form, seed=seed, **extra)
         self.mix = resolved_mix(compressor, mix_form)
         self.ref = ref.RefState(X0, *topo, gamma=gamma, compressor=compressor, k=k, levels=levels,
                                 qsgd_biased=qsgd_biased, randk_rescale=randk_rescale, order=order,
-                                mix_form=REF_MIX[self.mix], seed=seed)
+                                mix_form=REF_MIX[self.mix], seed=seed, layers=layers)
         self.codes = None
         if compressor in (binding.Q_SIGN, binding.Q_QSGD):
             self.codes = torch.zeros((self.n, self.ld), dtype=torch.int32, device=dev)
@@ -115,14 +120,22 @@ class Pair:
             val = val.cpu().numpy()
             order = np.argsort(idx, axis=1, kind="stable")
             idx_sorted = np.take_along_axis(idx, order, axis=1)
-            assert np.array_equal(idx_sorted, det["sel"]), tag + ": kept index sets differ"
-            scal = self.gpu.last_scalars()
-            assert np.all(scal[:, 2] == self.k), tag + ": kept count != k"
+            assert np.array_equal(idx_sorted, np.sort(det["sel"], axis=1)), tag + ": kept index sets differ"
+            if self.layers is None:
+                scal = self.gpu.last_scalars()
+                assert np.all(scal[:, 2] == self.k), tag + ": kept count != k"
+            else:
+                scal = self.gpu.layer_scalars()
+                assert np.all(scal[:, :, 3] == np.asarray(self.layers[2])[None, :]), tag + ": layer k"
+                assert np.all(scal[:, :, 1] <= scal[:, :, 2]), tag + ": kept more ties than there are"
         if self.codes is not None:
             codes = self.codes[:, :self.d].cpu().numpy()
             assert np.array_equal(codes, det["codes"]), tag + ": transmitted codes differ"
-            scal = self.gpu.last_scalars()
-            assert np.array_equal(scal[:, :4], det["scal"]), tag + ": norms / scales differ"
+            if self.layers is None:
+                scal = self.gpu.last_scalars()[:, :4]
+            else:
+                scal = self.gpu.layer_scalars()
+            assert np.array_equal(scal, det["scal"]), tag + ": norms / scales differ"
         for name, got, want in (("X", X, self.ref.X), ("Xhat", Xhat, self.ref.Xhat),
                                 ("S", S, self.ref.S)):
             if got is None:

@@ -119,3 +119,42 @@ def test_null_pointers_alignment_and_small_workspace():
     assert L.choco_gossip_step(None) == B.E_INVAL
     assert L.choco_sgd_step(None, 0x1000, 0.1) == B.E_INVAL
     assert L.choco_destroy(None) == B.OK
+
+
+# layer tables are validated on the host before any device work
+def layer_code(d, start, length, k, **over):
+    c, keep = cfg(d=d, layers=(start, length, k), **over)
+    out = ctypes.c_size_t()
+    return B.lib().choco_workspace_bytes(ctypes.byref(c), ctypes.byref(out))
+
+
+def test_layer_tables_are_validated():
+    assert layer_code(1000, [0, 400], [400, 600], [4, 6]) == B.OK
+    assert layer_code(1000, [0, 400], [398, 600], [4, 6]) == B.OK          # start padded to 4
+    assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_SIGN) == B.OK
+    assert layer_code(1000, [0, 400], [400, 600], None) == B.E_INVAL       # top_a needs k per layer
+    assert layer_code(1000, [0, 398], [398, 602], [4, 6]) == B.E_INVAL     # start not padded
+    assert layer_code(1000, [0, 404], [400, 596], [4, 6]) == B.E_INVAL     # gap beyond the padding
+    assert layer_code(1000, [0, 400], [400, 500], [4, 6]) == B.E_INVAL     # does not end at d
+    assert layer_code(1000, [0, 400], [400, 601], [4, 6]) == B.E_INVAL     # runs past d
+    assert layer_code(1000, [4, 400], [396, 600], [4, 6]) == B.E_INVAL     # does not start at 0
+    assert layer_code(1000, [0, 400], [400, 600], [401, 6]) == B.E_INVAL   # k above the length
+    assert layer_code(1000, [0, 400], [400, 600], [0, 0]) == B.E_INVAL     # nothing ever sent
+    assert layer_code(1000, [0, 400], [400, 600], [0, 6]) == B.OK          # one silent layer is fine
+    assert layer_code(1000, [0, 400], [400, 0], [4, 0]) == B.E_INVAL
+
+
+def test_layer_limits_are_reported_as_unsupported():
+    limit = 40960    # CHOCO_MAX_LAYER_LEN
+    assert layer_code(limit + 8, [0, 8], [8, limit], [1, 10]) == B.OK
+    assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 10]) == B.E_UNSUPPORTED
+    assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT) == B.E_UNSUPPORTED
+    assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_IDENTITY) == B.E_UNSUPPORTED
+
+
+def test_layered_workspace_needs_no_candidate_lists():
+    c, keep = cfg(d=100000, k=1000)
+    flat = B.workspace_bytes(c)
+    start, length, k = synth.layer_table([25000] * 4, fraction=0.01)
+    c2, keep2 = cfg(d=100000, layers=(start, length, k))
+    assert B.workspace_bytes(c2) < flat

@@ -1,0 +1,134 @@
+"""GPU parity of layer-wise compression (Section 5: the operator is applied to every layer
+on its own) against the oracle: kept sets, codes, per-layer norms and scales and the whole
+state, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_1907_09356_amd import binding, synth
+from tests.parity_util import Pair
+
+pytestmark = pytest.mark.gpu
+
+OPERATORS = [
+    ("topk", dict(compressor=binding.Q_TOPK)),
+    ("randk", dict(compressor=binding.Q_RANDK)),
+    ("randk_rescaled", dict(compressor=binding.Q_RANDK, randk_rescale=1)),
+    ("sign", dict(compressor=binding.Q_SIGN)),
+    ("qsgd16", dict(compressor=binding.Q_QSGD, levels=16)),
+    ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
+]
+ORDERS = [binding.ORDER_COMPRESS_THEN_MIX, binding.ORDER_MIX_THEN_COMPRESS]
+
+# every size class of the layer kernel (up to 2,560 / 10,240 / 40,960 entries), ragged
+# lengths, one-entry and sub-vector layers, chunk and group boundaries of the norm tree
+MIXED_LENGTHS = [432, 16, 1, 3, 2304, 255, 256, 257, 2560, 2561, 4097, 9216, 10240, 10241, 36864, 7, 40960, 10]
+
+
+def mixed_layers(fraction=0.01):
+    start, length, k = synth.layer_table(MIXED_LENGTHS, fraction=fraction)
+    k[1] = 0            # a silent layer
+    k[3] = length[3]    # a layer sent whole
+    return start, length, k
+
+
+def padded_state(n, layers, seed, std=1.0):
+    d = synth.layers_dim(layers)
+    X = synth.normal_state(n, d, seed=seed, std=std)
+    inside = np.zeros(d, dtype=bool)
+    for a, ln in zip(layers[0], layers[1]):
+        inside[a:a + ln] = True
+    X[:, ~inside] = 0.0
+    return X, inside
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_layered_gossip_steps(name, q, order):
+    layers = mixed_layers()
+    n = 5
+    X0, _ = padded_state(n, layers, seed=11)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=5, layers=layers, **q)
+    for t in range(4):
+        det = pair.gossip_step()
+        pair.check(det, tag="%s step %d" % (name, t))
+    pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_layered_fused_iterations(name, q, order):
+    layers = mixed_layers(fraction=0.05)
+    n = 6
+    X0, inside = padded_state(n, layers, seed=12)
+    pair = Pair(X0, synth.torus_csr(2, 3), 0.2, order=order, seed=6, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=3, noise_std=0.05, bias_std=0.02)
+    for t in range(4):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        det = pair.step(G, 0.1)
+        pair.check(det, tag="%s fused step %d" % (name, t))
+    pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3]])
+def test_layered_momentum_iterations(name, q):
+    layers = mixed_layers(fraction=0.02)
+    n = 4
+    X0, inside = padded_state(n, layers, seed=13)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=4, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        det = pair.step_momentum(G, 0.05, 0.9, 1e-4)
+        pair.check(det, tag="%s momentum step %d" % (name, t))
+    pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+def test_layered_topk_ties_go_to_the_lower_index(order):
+    # few distinct magnitudes, many exact zeros: the threshold key is shared by far more
+    # entries than may be kept, in every size class
+    lengths = [100, 2500, 9000, 30000]
+    layers = synth.layer_table(lengths, fraction=0.3)
+    d = synth.layers_dim(layers)
+    n = 3
+    rng = np.random.default_rng(5)
+    X0 = rng.integers(-2, 3, size=(n, d)).astype(np.float32) * 0.5
+    pair = Pair(X0, synth.ring_csr(n), 0.5, compressor=binding.Q_TOPK, order=order, layers=layers)
+    for t in range(3):
+        det = pair.gossip_step()
+        pair.check(det, tag="ties step %d" % t)
+    scal = pair.gpu.layer_scalars()
+    assert np.any(scal[:, :, 2] > scal[:, :, 1])      # the tie rule really was exercised
+    pair.close()
+
+
+def test_layered_zero_difference_sends_zeros():
+    # x = xhat after a full-precision round: norms are 0, gsgd sends level 0 everywhere
+    layers = synth.layer_table([40, 3000], fraction=0.1)
+    d = synth.layers_dim(layers)
+    X0 = np.zeros((3, d), dtype=np.float32)
+    for q in (dict(compressor=binding.Q_QSGD, levels=4), dict(compressor=binding.Q_SIGN),
+              dict(compressor=binding.Q_TOPK)):
+        pair = Pair(X0, synth.ring_csr(3), 0.4, layers=layers, **q)
+        det = pair.gossip_step()
+        pair.check(det, tag="zero state")
+        pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[2], OPERATORS[3], OPERATORS[4]])
+def test_layers_of_the_small_image_model(name, q):
+    # the layer sizes of Section 5's 0.27 M-parameter model, 1 % per layer, on the ring of
+    # Table 1 (n = 8)
+    layers = synth.layer_table(synth.resnet20_like_lengths(), fraction=0.01)
+    n = 8
+    X0, inside = padded_state(n, layers, seed=14, std=0.1)
+    pair = Pair(X0, synth.ring_csr(n), 0.05, seed=8, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=5)
+    for t in range(3):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        det = pair.step(G, 0.1)
+        pair.check(det, tag="%s resnet-like step %d" % (name, t))
+    pair.close()
