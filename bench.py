@@ -53,7 +53,41 @@ WORKLOADS = {
                                  "gamma=0.02, lr=0.1",
                             n=64, d=270_000, topo="torus", comp="randk", k=2700, gamma=0.02, lr=0.1,
                             bias_std=0.001),
+    # layer-wise compression (Section 5: the operator is applied to every layer on its own):
+    # the 65 layer sizes of the 0.27 M-parameter image model, d = 272,474
+    "dc_sign_layers": dict(desc="datacenter shape, per layer: n=8 ring, 65 layers (d=272,474), scaled sign "
+                                "per layer, gamma=0.4, lr=0.1",
+                           n=8, layers="resnet20", topo="ring", comp="sign", gamma=0.4, lr=0.1, bias_std=0.001),
+    "p2p_ring_sign_layers": dict(desc="peer-to-peer shape, per layer: n=64 ring, 65 layers (d=272,474), "
+                                      "scaled sign per layer, gamma=0.4, lr=0.1",
+                                 n=64, layers="resnet20", topo="ring", comp="sign", gamma=0.4, lr=0.1,
+                                 bias_std=0.001),
+    "p2p_ring_topk_layers": dict(desc="peer-to-peer shape, per layer: n=64 ring, 65 layers (d=272,474), "
+                                      "top-k 1% of every layer (at least 1), gamma=0.02, lr=0.1",
+                                 n=64, layers="resnet20", fraction=0.01, topo="ring", comp="topk", gamma=0.02,
+                                 lr=0.1, bias_std=0.001),
+    "p2p_ring_randk_layers": dict(desc="peer-to-peer shape, per layer: n=64 ring, 65 layers (d=272,474), "
+                                       "random-k 1% of every layer (at least 1), gamma=0.02, lr=0.1",
+                                  n=64, layers="resnet20", fraction=0.01, topo="ring", comp="randk", gamma=0.02,
+                                  lr=0.1, bias_std=0.001),
 }
+
+
+def layer_table_of(w):
+    """(start, length, k) of a layered workload, or None."""
+    if "layers" not in w:
+        return None
+    from paper_1907_09356_amd import synth
+    assert w["layers"] == "resnet20"
+    return synth.layer_table(synth.resnet20_like_lengths(), fraction=w.get("fraction", 0.01))
+
+
+for _w in WORKLOADS.values():
+    if "layers" in _w:
+        _t = layer_table_of(_w)
+        _w["d"] = int(_t[0][-1] + _t[1][-1])
+        if _w["comp"] in ("topk", "randk"):
+            _w["k"] = int(_t[2].sum())
 
 # Algorithmic bytes each kernel must move per (worker, coordinate): every array it needs is
 # streamed once (reads + writes, fp32), xhat rows shared across neighbours through LDS.
@@ -98,6 +132,9 @@ def comp_kwargs(w, B):
         kw["k"] = w["k"]
     if "levels" in w:
         kw["levels"] = w["levels"]
+    layers = layer_table_of(w)
+    if layers is not None:
+        kw["layers"] = layers
     return kw
 
 
@@ -190,17 +227,27 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
             entry = dict(launches_per_step=count / steps, avg_ms=avg_ms,
                          ms_per_step=total_ms / steps)
             bpe = KERNEL_BYTES_PER_ELEM.get(name)
+            if name.startswith("k_layer_compress"):
+                # sign / gsgd: read x, xhat, write xhat; top-k: read x, xhat; random-k reads nothing;
+                # a pass that carries the local update also reads g and writes x
+                bpe = {"sign": 12, "qsgd": 12, "topk": 8, "randk": 0}[w["comp"]]
+                if name.endswith("_sgd"):
+                    bpe += 8
+                bpe = bpe or None
             if (bpe is not None and name.startswith("k_sel_compact") and w["comp"] == "topk"
                     and order == B.ORDER_MIX_THEN_COMPRESS and mix_form != B.MIX_DIRECT):
                 bpe += 4 if name.endswith("_sgd") else 8   # the mix rides on this pass: + read s (+ write x)
             if bpe is not None and momentum and name.endswith("_sgd"):
                 bpe += 8                                   # + read and write the momentum memory
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
-                entry["alg_bytes_per_launch"] = bpe * elems
-                entry["alg_GBps"] = bpe * elems / (avg_ms * 1e-3) / 1e9
+                per_launch = bpe * elems
+                if name.startswith("k_layer_compress"):
+                    per_launch /= entry["launches_per_step"]   # its launches share one pass over the rows
+                entry["alg_bytes_per_launch"] = per_launch
+                entry["alg_GBps"] = per_launch / (avg_ms * 1e-3) / 1e9
             kernels[name] = entry
         out["kernels"] = kernels
-    if w["comp"] in ("topk", "randk"):
+    if w["comp"] in ("topk", "randk") and "layers" not in w:
         sc = ctx.last_scalars()
         out["select"] = dict(fallback_steps=int(sc[:, 4].max()), last_mode=int(sc[:, 3].max()),
                              candidates_per_worker=float(sc[:, 5].mean()), k=w["k"])
@@ -237,6 +284,9 @@ def cpu_baseline(w, budget_s=20.0):
         kw["k"] = max(1, w["k"] // frac)
     if "levels" in w:
         kw["levels"] = w["levels"]
+    layers = layer_table_of(w)
+    if layers is not None:
+        kw["layers"] = layers
     X0 = synth.normal_state(n, d, seed=1, std=0.05, shared=True)
     st = ref.RefState(X0, *make_topology(w), gamma=w["gamma"], seed=7, **kw)
     grads = synth.GradientStream(n, d, seed=2, noise_std=0.01, bias_std=w["bias_std"])
@@ -346,7 +396,7 @@ def main():
         # the same workload in the other supported formulations (same results as the oracle's
         # corresponding form): Algorithm 1's printed order, and the direct mix without S
         alts = []
-        if w["comp"] in ("topk", "randk"):
+        if w["comp"] in ("topk", "randk") and "layers" not in w:
             variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=mix_form)),
                         ("mix=direct", dict(order=order, mix_form=B.MIX_DIRECT))]
         else:
@@ -364,7 +414,7 @@ def main():
             if name == args.workload:
                 continue
             k = min(args.steps, 100)
-            omix = None if ow["comp"] in ("sign", "qsgd") else mix_form
+            omix = None if (ow["comp"] in ("sign", "qsgd") or "layers" in ow) else mix_form
             r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix, order=order,
                         momentum=args.momentum)
             b = step_bytes_per_elem(ow, r["kernels"])

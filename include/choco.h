@@ -176,7 +176,8 @@ int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
 /* Layer-wise configurations only (else CHOCO_E_INVAL): 4 doubles per worker and layer
    (n * nlayers * 4, worker-major) from the last step.  SIGN: {||v_l||_1, scale, 0, 0};
    QSGD: {sum v_l^2, ||v_l||_2, s/||v_l||_2, ||v_l||_2/(tau_l s)}; TOPK/RANDK: {threshold
-   key, entries kept at the threshold key, entries holding that key, layer_k[l]}.  With
+   key, entries kept at the threshold key, entries holding that key, 1 if the guessed
+   bracket held the threshold and 0 if the whole layer was searched}.  With
    layers, choco_last_selection returns sum(layer_k) pairs per worker, layer after layer,
    and choco_last_scalars is CHOCO_E_UNSUPPORTED.  Synchronises the stream. */
 int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -32,7 +33,7 @@ struct choco_ctx {
   bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   int nlayers;            // > 0: the operator is applied layer by layer
-  int class_first[4];     // layer_ids[class_first[c] .. class_first[c+1]) = layers of size class c
+  int nlarge, nmid;       // layers (by falling length) that take a 1024- / a 256-thread workgroup
   uint64_t t;             // step counter
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
@@ -56,7 +57,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
-      layers, layer_ids, layer_scal, mpart, mout, total;
+      layers, layer_work, layer_guess, layer_scal, mpart, mout, total;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
   bool multipart;
@@ -80,12 +81,6 @@ int64_t kept_per_worker(const choco_config& c) {
   int64_t sum = 0;
   for (int32_t l = 0; l < c.nlayers; ++l) sum += c.layer_k_host[l];
   return sum;
-}
-
-// Size classes of the layer kernel: 64, 256 or 1024 threads, kLayerVecs 4-vectors each.
-int layer_class(int64_t len) {
-  const int64_t per_thread = 4 * kLayerVecs;
-  return len <= 64 * per_thread ? 0 : len <= 256 * per_thread ? 1 : 2;
 }
 
 int check_layers(const choco_config* c) {
@@ -206,7 +201,8 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
-  L.layer_ids = take((size_t)c.nlayers * sizeof(int32_t));
+  L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
+  L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
   L.layer_scal = take((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
@@ -519,16 +515,21 @@ int gossip_layers(choco_ctx* ctx, const Args& F) {
   Args C = (x_touched || COMP == Q_RANDK) ? A : F;
   if (COMP == Q_RANDK) C.G = nullptr;
   const int kid = (C.G != nullptr) ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
-  const int* cf = ctx->class_first;
-  if (cf[1] > cf[0])
-    LAUNCH(ctx, kid, (k_layer_compress<COMP, 64, NT>), dim3((unsigned)(cf[1] - cf[0]), (unsigned)A.n), dim3(64),
-           0, C, (int32_t)cf[0]);
-  if (cf[2] > cf[1])
-    LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(cf[2] - cf[1]), (unsigned)A.n), dim3(256),
-           0, C, (int32_t)cf[1]);
-  if (cf[3] > cf[2])
-    LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)(cf[3] - cf[2]), (unsigned)A.n),
-           dim3(1024), 0, C, (int32_t)cf[2]);
+  const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlarge - nmid;
+  const int one_launch_blocks = nlarge + nmid + (nsmall + 15) / 16;
+  if ((int64_t)one_launch_blocks * A.n <= 256) {
+    // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the
+    // chip still is not full, so one launch does (a launch costs more than idle threads)
+    LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)one_launch_blocks, (unsigned)A.n),
+           dim3(1024), 0, C, (int32_t)0, (int32_t)(nlarge + nmid));
+  } else {
+    if (nlarge > 0)
+      LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0,
+             C, (int32_t)0, (int32_t)nlarge);
+    if (nmid + nsmall > 0)
+      LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
+             dim3(256), 0, C, (int32_t)nlarge, (int32_t)nmid);
+  }
   if (sparse) {
     const unsigned kblocks = (unsigned)((A.k + 255) / 256);
     if (COMP == Q_RANDK)
@@ -788,12 +789,12 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.randk_rescale = cfg->randk_rescale ? 1 : 0;
   A.randk_scale = (ctx->sparse && cfg->nlayers == 0) ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
   A.qsgd_biased = cfg->qsgd_biased ? 1 : 0;
-  // layer tables: descriptors in layer order, layer numbers grouped by size class
-  std::vector<LayerDesc> layers((size_t)cfg->nlayers);
-  std::vector<int32_t> layer_ids;
+  // layer tables: descriptors in layer order, and again by falling length (the work list)
+  std::vector<LayerDesc> layers((size_t)cfg->nlayers), work;
   A.nlayers = cfg->nlayers;
   A.layers = (const LayerDesc*)(base + L.layers);
-  A.layer_ids = (const int32_t*)(base + L.layer_ids);
+  A.layer_work = (const LayerDesc*)(base + L.layer_work);
+  A.layer_guess = (uint32_t*)(base + L.layer_guess);
   A.layer_scal = (double*)(base + L.layer_scal);
   if (cfg->nlayers > 0) {
     int64_t sel_base = 0;
@@ -803,14 +804,17 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
       D.len = (int32_t)cfg->layer_len_host[l];
       D.k = ctx->sparse ? (int32_t)cfg->layer_k_host[l] : 0;
       D.sel_base = (int32_t)sel_base;
+      D.id = l;
+      D.pad[0] = D.pad[1] = D.pad[2] = 0;
       sel_base += D.k;
     }
-    for (int cls = 0; cls < 3; ++cls) {
-      ctx->class_first[cls] = (int)layer_ids.size();
-      for (int32_t l = 0; l < cfg->nlayers; ++l)
-        if (layer_class(layers[(size_t)l].len) == cls) layer_ids.push_back(l);
+    work = layers;
+    std::stable_sort(work.begin(), work.end(), [](const LayerDesc& a, const LayerDesc& b) { return a.len > b.len; });
+    ctx->nlarge = ctx->nmid = 0;
+    for (const LayerDesc& D : work) {
+      if (D.len > kMidLayerLen) ctx->nlarge += 1;
+      else if (D.len > kWaveLayerLen) ctx->nmid += 1;
     }
-    ctx->class_first[3] = (int)layer_ids.size();
   }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
@@ -833,8 +837,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     e = hipMemcpyAsync(base + L.layers, layers.data(), layers.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
                        ctx->stream);
   if (e == hipSuccess && cfg->nlayers > 0)
-    e = hipMemcpyAsync(base + L.layer_ids, layer_ids.data(), layer_ids.size() * sizeof(int32_t),
-                       hipMemcpyHostToDevice, ctx->stream);
+    e = hipMemcpyAsync(base + L.layer_work, work.data(), work.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
+                       ctx->stream);
+  if (e == hipSuccess && cfg->nlayers > 0)   // no threshold guesses yet
+    e = hipMemsetAsync(base + L.layer_guess, 0xFF, (size_t)cfg->n * (size_t)cfg->nlayers * sizeof(uint32_t),
+                       ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {
     ctl0.resize((size_t)cfg->n);

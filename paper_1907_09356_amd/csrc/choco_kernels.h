@@ -71,6 +71,8 @@ struct LayerDesc {
   int32_t len;       // entries
   int32_t k;         // top_a / random_a: entries kept of this layer
   int32_t sel_base;  // where the layer's kept entries start in the worker's selection list
+  int32_t id;        // number of the layer in the caller's table
+  int32_t pad[3];
 };
 
 struct Args {
@@ -125,7 +127,8 @@ struct Args {
   // layer-wise compression (nlayers = 0: the whole row is compressed as one vector)
   const LayerDesc* layers;   // sorted by start; they tile the row up to the 4-entry padding
   int32_t nlayers;
-  const int32_t* layer_ids;  // layer numbers grouped by size class
+  const LayerDesc* layer_work;  // the same by falling length: the order the layer kernel takes them in
+  uint32_t* layer_guess;     // n x nlayers: top_a threshold key of the last step (all ones: none yet)
   double* layer_scal;        // n x nlayers x 4: norms and scales / threshold of the last step
   int32_t qsgd_biased;
   // randomness

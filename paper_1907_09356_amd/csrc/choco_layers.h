@@ -1,18 +1,20 @@
 // Layer-wise compression (Section 5, set-up of the deep-learning runs: the operator is
 // applied to every layer of the network on its own).
 //
-// One block per (worker, layer); the layer's x - xhat lives in registers (kLayerVecs
-// 4-vectors per thread, so a block of T threads holds up to 40 T entries and the largest
-// layer a 1024-thread block can take has 40,960 entries), so one launch reads x, g, xhat
-// once and does the whole operator:
+// A layer of a worker is compressed by one workgroup (1024 threads above 10,240 entries,
+// 256 threads above 2,560) or by one wave (smaller layers, four to a workgroup), with the
+// layer's x - xhat in registers (kLayerVecs 4-vectors per thread, so 1024 threads hold up
+// to 40,960 entries).  The one pass reads x, g, xhat once and does the whole operator:
 //   sign / gsgd_b   the norm tree of the layer (same three levels as for a whole row:
 //                   a wave's 64 lanes x 4 entries are exactly one 256-entry chunk), the
 //                   per-layer scale, the codes, xhat += q
-//   top_a/random_a  an exact k-th largest key by a bitwise search on block-wide counts
-//                   (31 or 32 rounds over the registers, no atomics, no histogram), ties
-//                   on the threshold key broken by ascending index, then the kept
-//                   (index, value) pairs and the kept-entry map
-// Layers are grouped by size into three launches (64, 256 and 1024 threads per block).
+//   top_a/random_a  the exact k-th largest key.  A bracket [lo, hi) around a guess (last
+//                   step's threshold for top_a, the expected order statistic for
+//                   random_a) is counted in one sweep over the registers; if the k-th key
+//                   provably lies inside, only the few keys in the bracket are searched
+//                   (bit by bit, in LDS); otherwise the whole layer is searched bit by bit
+//                   (31 or 32 sweeps with block-wide counts).  Ties on the threshold key
+//                   go to the lower index.  No histogram, no global atomics.
 #pragma once
 
 #include "choco_kernels.h"
@@ -21,17 +23,18 @@ namespace choco {
 
 constexpr int kLayerVecs = 10;
 constexpr int kMaxLayerLen = 1024 * kLayerVecs * 4;
-constexpr int kLayerMaxChunks = 16 * kLayerVecs;   // 256-entry chunks of the largest layer
+constexpr int kWaveLayerLen = 64 * kLayerVecs * 4;   // up to here a single wave takes the layer
+constexpr int kLayerMaxChunks = 16 * kLayerVecs;     // 256-entry chunks of the largest layer
+constexpr int kMidLayerLen = 256 * kLayerVecs * 4;   // up to here a 256-thread workgroup does
 
+// Block total of per-wave counts (each already uniform over its wave).
 template <int THREADS>
-__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* sh, int& phase) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-  if (THREADS == 64) return v;
+__device__ __forceinline__ uint32_t block_total(uint32_t wave_count, uint32_t* sh, int& phase) {
+  if (THREADS == 64) return wave_count;
   // two buffers in turn: a wave may write round j+1 while another still reads round j
   uint32_t* buf = sh + 16 * phase;
   phase ^= 1;
-  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = wave_count;
   __syncthreads();
   uint32_t tot = 0;
 #pragma unroll
@@ -39,47 +42,113 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* sh, int&
   return tot;
 }
 
-// grid (layers of this size class, n); `first` indexes A.layer_ids
+// lanes of the wave for which pred holds (a compare and a scalar bit count, no cross-lane traffic)
+__device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
+
+// The local update on values already in registers; the arithmetic of local_update4.
+__device__ __forceinline__ vf4 local_update_regs(const Args& A, vf4 x, const vf4& g, vf4& m) {
+  if (A.M) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float gg = g[c] + A.lambda * x[c];
+      const float mn = gg + A.beta * m[c];
+      m[c] = mn;
+      x[c] = x[c] - A.lr * mn;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) x[c] = x[c] - A.lr * g[c];
+  }
+  return x;
+}
+
+// Barrier among the THREADS threads that share a layer (one wave needs none: its LDS
+// accesses execute in order; the fence only stops the compiler from reordering them).
+template <int THREADS>
+__device__ __forceinline__ void layer_sync() {
+  if (THREADS == 64) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  else __syncthreads();
+}
+
+// The LDS of the THREADS threads that share a layer.
+struct LayerShared {
+  double* chunk;      // first-level norm sums (dense operators)
+  uint32_t* cnt;      // 2 x 16 per-wave counts
+  uint32_t* emit;     // kept entries emitted so far
+  uint32_t* list_n;   // keys in the bracket
+  uint2* list;        // (key, index in the layer) of the keys in the bracket
+};
+
 template <int COMP, int THREADS, bool NT>
-__global__ __launch_bounds__(THREADS) void k_layer_compress(Args A, int32_t first) {
+__device__ __forceinline__ void layer_body(const Args& A, const int i, const LayerDesc L, const int tid,
+                                           const LayerShared sh) {
   constexpr bool DENSE = (COMP == Q_SIGN || COMP == Q_QSGD);
   constexpr int NW = THREADS / 64;
-  __shared__ double sh_chunk[DENSE ? kLayerMaxChunks : 1];
-  __shared__ uint32_t sh_cnt[32];
-  __shared__ uint32_t sh_emit;
-  const int i = blockIdx.y;
-  const int l = A.layer_ids[first + (int)blockIdx.x];
-  const LayerDesc L = A.layers[l];
+  constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together
+  constexpr int kBatches = (kLayerVecs + kBatch - 1) / kBatch;
+  constexpr uint32_t CAP = 2 * THREADS;
   const int nvec = (L.len + 3) >> 2;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nit = (nvec + THREADS - 1) / THREADS;   // sweeps of the threads over the layer (<= kLayerVecs)
+  const int lane = tid & 63, wave = tid >> 6;
   const int64_t row = (int64_t)i * A.ld + L.start;
-  double* scal = A.layer_scal + ((int64_t)i * A.nlayers + l) * 4;
-  if (tid == 0) sh_emit = 0;
+  double* scal = A.layer_scal + ((int64_t)i * A.nlayers + L.id) * 4;
+  float* __restrict__ X = A.X;
+  float* __restrict__ Xhat = A.Xhat;
+  const float* __restrict__ G = A.G;
+  float* __restrict__ Mom = A.M;
+  if (tid == 0) {
+    *sh.emit = 0;
+    *sh.list_n = 0;
+  }
 
   // ---- load: v = x - xhat (after the local update, if this pass carries it) ----
-  vf4 v[kLayerVecs], xh[DENSE ? kLayerVecs : 1];
+  vf4 v[kLayerVecs];
   uint32_t word_key[COMP == Q_RANDK ? kLayerVecs : 1][4];
+  if constexpr (COMP == Q_RANDK) {
 #pragma unroll
-  for (int it = 0; it < kLayerVecs; ++it) {
-    const int m = it * THREADS + tid;
-    v[it] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
-    if constexpr (COMP == Q_RANDK) {
+    for (int it = 0; it < kLayerVecs; ++it) {
+      const int m = it * THREADS + tid;
       // keys are ~word: the k smallest words are the k largest keys
       uint4 wd = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
-      if (m < nvec) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_RANDK);
+      if (it < nit && m < nvec) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_RANDK);
 #pragma unroll
       for (int c = 0; c < 4; ++c) word_key[it][c] = (4 * m + c < L.len) ? ~pick(wd, c) : 0u;
-    } else if (m < nvec) {
-      const int64_t o = row + 4 * (int64_t)m;
-      vf4 x = load4<NT>(A.X + o);
-      if (A.G) {
-        x = local_update4<NT>(A, o, x);
-        store4<NT>(A.X + o, x);
-      }
-      const vf4 h = load4<NT>(A.Xhat + o);
-      if constexpr (DENSE) xh[it] = h;
+    }
+  } else {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) v[it][c] = (4 * m + c < L.len) ? x[c] - h[c] : 0.0f;
+    for (int b = 0; b < kBatches; ++b) {
+      vf4 x[kBatch], g[kBatch], h[kBatch];
+      if (b * kBatch < nit) {                    // uniform over the threads of the layer
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+          const int m = (b * kBatch + j) * THREADS + tid;
+          if (b * kBatch + j < kLayerVecs && m < nvec) {
+            const int64_t o = row + 4 * (int64_t)m;
+            x[j] = load4<NT>(X + o);
+            h[j] = load4<NT>(Xhat + o);
+            if (G) g[j] = load4<NT>(G + o);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int it = b * kBatch + j;
+        if (it >= kLayerVecs) continue;
+        const int m = it * THREADS + tid;
+        v[it] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (it < nit && m < nvec) {
+          const int64_t o = row + 4 * (int64_t)m;
+          if (G) {
+            vf4 mom = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (Mom) mom = load4<NT>(Mom + o);
+            x[j] = local_update_regs(A, x[j], g[j], mom);
+            if (Mom) store4<NT>(Mom + o, mom);
+            store4<NT>(X + o, x[j]);
+          }
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[it][c] = (4 * m + c < L.len) ? x[j][c] - h[j][c] : 0.0f;
+        }
+      }
     }
   }
 
@@ -94,21 +163,23 @@ __global__ __launch_bounds__(THREADS) void k_layer_compress(Args A, int32_t firs
         const int m = it * THREADS + tid;
         double t = lane_terms<STAT>(v[it], 4 * m, L.len);
         t = wave_tree_sum(t);
-        if (lane == 0) sh_chunk[chunk] = t;
+        if (lane == 0) sh.chunk[chunk] = t;
       }
     }
-    __syncthreads();
+    layer_sync<THREADS>();
     // levels 2 and 3, done by every wave for itself: groups of 16 chunk sums (four groups
     // per round over the 64 lanes), then the lanes that stand for a group sum each
     const int ngroups = (nchunks + kGroup - 1) / kGroup;
     double g = 0.0;
 #pragma unroll
-    for (int r = 0; r < (kLayerMaxChunks / kGroup + 3) / 4; ++r) {
-      const int chunk = 64 * r + lane;
-      double t = chunk < nchunks ? sh_chunk[chunk] : 0.0;
-      t = group_tree_sum(t);
-      const double got = __shfl(t, 16 * (lane & 3), 64);
-      if ((lane >> 2) == r && lane < ngroups) g = got;
+    for (int r = 0; r < ((NW * kLayerVecs + kGroup - 1) / kGroup + 3) / 4; ++r) {
+      if (4 * r < ngroups) {                       // uniform
+        const int chunk = 64 * r + lane;
+        double t = chunk < nchunks ? sh.chunk[chunk] : 0.0;
+        t = group_tree_sum(t);
+        const double got = __shfl(t, 16 * (lane & 3), 64);
+        if ((lane >> 2) == r && lane < ngroups) g = got;
+      }
     }
     const double total = wave_tree_sum(g);
     // ---- per-layer scales (Appendix C with the layer's length in the place of d) ----
@@ -132,126 +203,246 @@ __global__ __launch_bounds__(THREADS) void k_layer_compress(Args A, int32_t firs
       scal[2] = COMP == Q_SIGN ? 0.0 : (double)sc.r;
       scal[3] = COMP == Q_SIGN ? 0.0 : (double)sc.step;
     }
-    // ---- codes and xhat += q ----
+    // ---- codes and xhat += q (xhat is read again: it is still in cache, and keeping it
+    // beside v would not fit the registers of a 1024-thread block) ----
 #pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it) {
-      const int m = it * THREADS + tid;
-      if (m < nvec) {
-        uint4 wd = make_uint4(0u, 0u, 0u, 0u);
-        if (COMP == Q_QSGD) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_DITHER);
-        vi4 code = vi4{0, 0, 0, 0};
-        vf4 h = xh[it];
+    for (int b = 0; b < kBatches; ++b) {
+      vf4 h[kBatch];
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (4 * m + c < L.len) {
-            int32_t cd;
-            const float qv = encode<STAT>(v[it][c], sc, pick(wd, c), cd);
-            h[c] = h[c] + qv;
-            code[c] = cd;
-          }
-        const int64_t o = row + 4 * (int64_t)m;
-        store4<NT>(A.Xhat + o, h);
-        if (A.codes) *reinterpret_cast<vi4*>(A.codes + o) = code;
+      for (int j = 0; j < kBatch; ++j) {
+        const int m = (b * kBatch + j) * THREADS + tid;
+        if (b * kBatch + j < kLayerVecs && b * kBatch < nit && m < nvec)
+          h[j] = load4<false>(Xhat + row + 4 * (int64_t)m);
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int it = b * kBatch + j;
+        if (it >= kLayerVecs) continue;
+        const int m = it * THREADS + tid;
+        if (b * kBatch < nit && m < nvec) {
+          uint4 wd = make_uint4(0u, 0u, 0u, 0u);
+          if (COMP == Q_QSGD) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_DITHER);
+          vi4 code = vi4{0, 0, 0, 0};
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (4 * m + c < L.len) {
+              int32_t cd;
+              const float qv = encode<STAT>(v[it][c], sc, pick(wd, c), cd);
+              h[j][c] = h[j][c] + qv;
+              code[c] = cd;
+            }
+          const int64_t o = row + 4 * (int64_t)m;
+          store4<NT>(Xhat + o, h[j]);
+          if (A.codes) *reinterpret_cast<vi4*>(A.codes + o) = code;
+        }
       }
     }
-    return;
   } else {
-  // ---- top_a / random_a: exact k-th largest key ----
-  const uint32_t k = (uint32_t)L.k;
-  if (k == 0) {
-    if (tid == 0) scal[0] = scal[1] = scal[2] = scal[3] = 0.0;
-    return;
-  }
-  auto key_of = [&](int it, int c) -> uint32_t {
-    if constexpr (COMP == Q_RANDK) return word_key[it][c];
-    else return __float_as_uint(v[it][c]) & 0x7FFFFFFFu;
-  };
-  int phase = 0;
-  uint32_t T = 0;
-  for (int bit = (COMP == Q_RANDK ? 31 : 30); bit >= 0; --bit) {
-    const uint32_t cand = T | (1u << bit);
-    uint32_t cnt = 0;
+    // ---- top_a / random_a: exact k-th largest key ----
+    const uint32_t k = (uint32_t)L.k;
+    if (k == 0) {
+      if (tid == 0) scal[0] = scal[1] = scal[2] = scal[3] = 0.0;
+      return;
+    }
+    auto key_of = [&](int it, int c) -> uint32_t {
+      if constexpr (COMP == Q_RANDK) return word_key[it][c];
+      else return __float_as_uint(v[it][c]) & 0x7FFFFFFFu;
+    };
+    constexpr int TOPBIT = COMP == Q_RANDK ? 31 : 30;
+    uint32_t* guess = A.layer_guess + (int64_t)i * A.nlayers + L.id;
+    // a bracket that should hold the k-th largest key
+    bool have = true;
+    uint32_t lo, hi;
+    if (COMP == Q_RANDK) {
+      // keys are uniform on [0, 2^32): the k-th largest of len sits near (1 - k/len) 2^32,
+      // give or take sqrt(k)/len 2^32; the half-width is counted in expected entries
+      const double hw = fmin(6.0 * sqrt((double)k) + 8.0, 0.4 * (double)CAP);
+      const double centre = (1.0 - (double)k / (double)L.len) * 4294967296.0;
+      const double width = hw / (double)L.len * 4294967296.0;
+      lo = (uint32_t)fmax(centre - width, 0.0);
+      hi = (uint32_t)fmin(centre + width, 4294967295.0);
+    } else {
+      const uint32_t g = *guess;             // last step's threshold of this layer
+      have = g != 0xFFFFFFFFu;
+      // +-6 % in magnitude around it, narrower when k is large for the list
+      uint32_t delta = 1u << 19;
+      if (5u * k > 3u * CAP) delta = (uint32_t)(((uint64_t)delta * 3u * CAP) / (5ull * k));
+      if (delta < 256u) delta = 256u;
+      lo = g > delta ? g - delta : 0u;
+      hi = g < 0x7FFFFFFFu - delta ? g + delta : 0x7FFFFFFFu;
+    }
+    int phase = 0;
+    uint32_t T = 0, at_or_above = 0xFFFFFFFFu;
+    bool found = false;
+    if (have) {                                   // uniform
+      uint32_t nhi = 0;
+#pragma unroll
+      for (int it = 0; it < kLayerVecs; ++it)
+        if (it < nit) {
+          const int m = it * THREADS + tid;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const uint32_t key = key_of(it, c);
+            nhi += wave_count(key >= hi);
+            if (key >= lo && key < hi && 4 * m + c < L.len) {
+              const uint32_t pos = atomicAdd(sh.list_n, 1u);
+              if (pos < CAP) sh.list[pos] = make_uint2(key, (uint32_t)(4 * m + c));
+            }
+          }
+        }
+      nhi = block_total<THREADS>(nhi, sh.cnt, phase);
+      layer_sync<THREADS>();
+      const uint32_t nin = *sh.list_n;
+      if (nhi < k && k - nhi <= nin && nin <= CAP) {
+        // the k-th largest key is the r-th largest of the list: bit by bit on key - lo
+        found = true;
+        const uint32_t r = k - nhi;
+        const uint32_t rel0 = (uint32_t)tid < nin ? sh.list[tid].x - lo : 0u;
+        const uint32_t rel1 = (uint32_t)tid + THREADS < nin ? sh.list[tid + THREADS].x - lo : 0u;
+        const bool has0 = (uint32_t)tid < nin, has1 = (uint32_t)tid + THREADS < nin;
+        const uint32_t span = hi - lo;            // >= 1: the list is not empty
+        uint32_t Trel = 0, got = nin;
+        for (int bit = 31 - __clz((int)(span | 1u)); bit >= 0 && got != r; --bit) {
+          const uint32_t cand = Trel | (1u << bit);
+          uint32_t cnt = wave_count(has0 && rel0 >= cand) + wave_count(has1 && rel1 >= cand);
+          cnt = block_total<THREADS>(cnt, sh.cnt, phase);
+          if (cnt >= r) {
+            Trel = cand;
+            got = cnt;
+          }
+        }
+        T = lo + Trel;
+        at_or_above = nhi + got;
+      }
+    }
+    if (!found) {
+      // the whole layer, bit by bit: the largest T with count(key >= T) >= k; it may stop
+      // as soon as exactly k keys lie at or above T (the lower bits cannot matter)
+      for (int bit = TOPBIT; bit >= 0 && at_or_above != k; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int it = 0; it < kLayerVecs; ++it)
+          if (it < nit) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cnt += wave_count(key_of(it, c) >= cand);
+          }
+        cnt = block_total<THREADS>(cnt, sh.cnt, phase);
+        if (cnt >= k) {
+          T = cand;
+          at_or_above = cnt;
+        }
+      }
+    }
+    if (COMP == Q_TOPK && tid == 0) *guess = T;
+    // entries above the threshold key are all kept; of those equal to it, the first `need`
+    // by index (entries past the layer's end carry key 0 and are told apart by their index)
+    uint32_t above = 0, equals = 0;
 #pragma unroll
     for (int it = 0; it < kLayerVecs; ++it)
+      if (it < nit) {
+        const int m = it * THREADS + tid;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) cnt += key_of(it, c) >= cand ? 1u : 0u;
-    if (block_sum_u32<THREADS>(cnt, sh_cnt, phase) >= k) T = cand;
-  }
-  // entries above the threshold key are all kept; of those equal to it, the first `need`
-  // by index (entries past the layer's end carry key 0 and are told apart by their index)
-  uint32_t above = 0, equals = 0;
-#pragma unroll
-  for (int it = 0; it < kLayerVecs; ++it) {
-    const int m = it * THREADS + tid;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const uint32_t key = key_of(it, c);
-      above += key > T ? 1u : 0u;
-      equals += (key == T && 4 * m + c < L.len) ? 1u : 0u;
-    }
-  }
-  above = block_sum_u32<THREADS>(above, sh_cnt, phase);
-  equals = block_sum_u32<THREADS>(equals, sh_cnt, phase);
-  const uint32_t need = k - above;
-  if (tid == 0) {
-    scal[0] = (double)T;
-    scal[1] = (double)need;
-    scal[2] = (double)equals;
-    scal[3] = (double)k;
-  }
-  const bool ties = equals > need;   // uniform over the block
-  uint32_t running = 0;              // threshold-key entries in earlier rounds (index order)
-#pragma unroll
-  for (int it = 0; it < kLayerVecs; ++it) {
-    const int m = it * THREADS + tid;
-    uint32_t rank = 0;
-    if (ties) {
-      uint32_t mine = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) mine += (key_of(it, c) == T && 4 * m + c < L.len) ? 1u : 0u;
-      uint32_t incl = mine;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += up;
-      }
-      uint32_t base = 0, total = __shfl(incl, 63, 64);
-      if (THREADS > 64) {
-        uint32_t* buf = sh_cnt + 16 * phase;
-        phase ^= 1;
-        if (lane == 63) buf[wave] = incl;
-        __syncthreads();
-        total = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          const uint32_t t = buf[w];
-          if (w < wave) base += t;
-          total += t;
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t key = key_of(it, c);
+          above += wave_count(key > T);
+          equals += wave_count(key == T && 4 * m + c < L.len);
         }
       }
-      rank = running + base + incl - mine;
-      running += total;
+    above = block_total<THREADS>(above, sh.cnt, phase);
+    equals = block_total<THREADS>(equals, sh.cnt, phase);
+    const uint32_t need = k - above;
+    if (tid == 0) {
+      scal[0] = (double)T;
+      scal[1] = (double)need;
+      scal[2] = (double)equals;
+      scal[3] = found ? 1.0 : 0.0;
     }
+    const bool ties = equals > need;   // uniform over the layer's threads
+    uint32_t running = 0;              // threshold-key entries in earlier sweeps (index order)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int e = 4 * m + c;
-      const uint32_t key = key_of(it, c);
-      bool keep = key > T;
-      if (key == T && e < L.len) {
-        keep = !ties || rank < need;
-        ++rank;
-      }
-      if (keep) {
-        const uint32_t slot = atomicAdd(&sh_emit, 1u);
-        if (slot < k) {   // exactly k entries pass; the test only keeps a wrong count inside the layer's slots
-          const int64_t dst = (int64_t)i * A.k + L.sel_base + slot;
-          A.sel_idx[dst] = L.start + e;
-          if (COMP == Q_TOPK) A.sel_val[dst] = v[it][c];
-          A.keptmap[row + e] = 1;
+    for (int it = 0; it < kLayerVecs; ++it) {
+      if (it < nit) {
+        const int m = it * THREADS + tid;
+        uint32_t rank = 0;
+        if (ties) {
+          uint32_t mine = 0;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) mine += (key_of(it, c) == T && 4 * m + c < L.len) ? 1u : 0u;
+          uint32_t incl = mine;
+#pragma unroll
+          for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+          }
+          uint32_t base = 0, total = __shfl(incl, 63, 64);
+          if (THREADS > 64) {
+            uint32_t* buf = sh.cnt + 16 * phase;
+            phase ^= 1;
+            if (lane == 63) buf[wave] = incl;
+            __syncthreads();
+            total = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+              const uint32_t t = buf[w];
+              if (w < wave) base += t;
+              total += t;
+            }
+          }
+          rank = running + base + incl - mine;
+          running += total;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int e = 4 * m + c;
+          const uint32_t key = key_of(it, c);
+          bool keep = key > T;
+          if (key == T && e < L.len) {
+            keep = !ties || rank < need;
+            ++rank;
+          }
+          if (keep) {
+            const uint32_t slot = atomicAdd(sh.emit, 1u);
+            if (slot < k) {   // exactly k entries pass; the test only keeps a wrong count inside the layer's slots
+              const int64_t dst = (int64_t)i * A.k + L.sel_base + slot;
+              A.sel_idx[dst] = L.start + e;
+              if (COMP == Q_TOPK) A.sel_val[dst] = v[it][c];
+              A.keptmap[row + e] = 1;
+            }
+          }
         }
       }
     }
   }
+}
+
+// Two launches cover the work list A.layer_work (layers by falling length):
+//   THREADS = 1024: grid (nlarge, n), a workgroup per layer above 10,240 entries;
+//   THREADS = 256:  grid (nmid + ceil(nsmall / 4), n), a workgroup per layer above 2,560
+//                   entries, then a wave per smaller layer, four to a workgroup.
+// `first` is where the launch starts in the work list, `nblock` how many layers from there
+// take a whole workgroup.  (Launch bounds of 1024 hold the code to 128 registers, so four
+// 256-thread workgroups fit a compute unit.)
+template <int COMP, int THREADS, bool NT>
+__global__ __launch_bounds__(1024) void k_layer_compress(Args A, int32_t first, int32_t nblock) {
+  constexpr int NW = THREADS / 64;
+  __shared__ double sh_chunk[NW * kLayerVecs];
+  __shared__ uint32_t sh_cnt[32];
+  __shared__ uint32_t sh_emit[NW];
+  __shared__ uint32_t sh_list_n[NW];
+  __shared__ uint2 sh_list[2 * THREADS];
+  const int i = blockIdx.y;
+  if ((int)blockIdx.x < nblock) {
+    const LayerShared sh{sh_chunk, sh_cnt, sh_emit, sh_list_n, sh_list};
+    layer_body<COMP, THREADS, NT>(A, i, A.layer_work[first + (int)blockIdx.x], (int)threadIdx.x, sh);
+  } else {
+    const int wave = (int)threadIdx.x >> 6;
+    const int idx = first + nblock + ((int)blockIdx.x - nblock) * NW + wave;
+    if (idx < A.nlayers) {
+      const LayerShared sh{sh_chunk + kLayerVecs * wave, sh_cnt, sh_emit + wave, sh_list_n + wave,
+                           sh_list + 128 * wave};
+      layer_body<COMP, 64, NT>(A, i, A.layer_work[idx], (int)threadIdx.x & 63, sh);
+    }
   }
 }
 

@@ -126,7 +126,6 @@ class Pair:
                 assert np.all(scal[:, 2] == self.k), tag + ": kept count != k"
             else:
                 scal = self.gpu.layer_scalars()
-                assert np.all(scal[:, :, 3] == np.asarray(self.layers[2])[None, :]), tag + ": layer k"
                 assert np.all(scal[:, :, 1] <= scal[:, :, 2]), tag + ": kept more ties than there are"
         if self.codes is not None:
             codes = self.codes[:, :self.d].cpu().numpy()
