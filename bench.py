@@ -251,6 +251,12 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
         sc = ctx.last_scalars()
         out["select"] = dict(fallback_steps=int(sc[:, 4].max()), last_mode=int(sc[:, 3].max()),
                              candidates_per_worker=float(sc[:, 5].mean()), k=w["k"])
+    if w["comp"] in ("topk", "randk") and "layers" in w:
+        sc = ctx.layer_scalars()
+        lengths = layer_table_of(w)[1]
+        out["select"] = dict(k=w["k"], layers=int(len(lengths)),
+                             bracket_hit_fraction=float(sc[:, :, 3].mean()),
+                             bracket_hit_fraction_large_layers=float(sc[:, lengths > 10240, 3].mean()))
     m = ctx.metrics()
     out["consensus_error"] = m["consensus"]
     out["mean_norm"] = m["mean_norm"]
