@@ -424,6 +424,174 @@ int gossip_step(int n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Messages on the wire (Appendix C, the message size stated with each operator;
+// entries are float32 there, so this part exists for float only).
+//
+// paper_message_bits: the sizes as the paper counts them:
+//   sign      d + 32           one bit per entry and 32 bits for the norm
+//   top_a     2 * 32 * k       values and positions
+//   random_a  32 * k           values only, the mask follows from the shared seed
+//   gsgd_b    b * d + 32       b = log2(s) + 1 bits per entry (the paper does not
+//                              count the norm; 32 bits are added for it here)
+//   identity  32 * d
+// The byte layout is this build's choice (the paper fixes none); 32-bit
+// little-endian words, W = ceil(d / 32):
+//   sign      [c as float][W words: bit e%32 of word e/32 set iff the entry is -c]
+//   gsgd      [step as float][4 words: ascending indices of entries whose level does
+//             not fit the magnitude bits, 0xFFFFFFFF when unused][plane 0: the signs,
+//             W words][planes 1..mb: bit p-1 of min(level, 2^mb - 1), W words each],
+//             mb = bit length of s - 1 (at least 1).  With s = 2^(b-1) that is b bits
+//             per entry as the paper counts; the level s itself, which the formula
+//             reaches for the few entries that hold almost the whole norm although
+//             the text lists the levels as 0..s-1, goes through the index slots.
+//   top_a     k pairs [index][value as float], ascending index
+//   random_a  k values as float in ascending order of index; the receiver draws the
+//             same mask from (seed, step, sender)
+//   identity  d floats
+// ---------------------------------------------------------------------------
+int magnitude_bits(int levels) {
+  int mb = 0;
+  for (int x = levels - 1; x > 0; x >>= 1) ++mb;
+  return mb < 1 ? 1 : mb;
+}
+
+int64_t paper_message_bits(int compressor, int64_t d, int64_t k, int levels) {
+  switch (compressor) {
+    case Q_IDENTITY: return 32 * d;
+    case Q_TOPK: return 64 * k;
+    case Q_RANDK: return 32 * k;
+    case Q_SIGN: return d + 32;
+    case Q_QSGD: {
+      int b = 1;
+      for (int x = levels; x > 1; x >>= 1) ++b;   // s = 2^(b-1)
+      return (int64_t)b * d + 32;
+    }
+  }
+  return -1;
+}
+
+constexpr int kOverflowSlots = 4;
+
+int64_t message_words(int compressor, int64_t d, int64_t k, int levels) {
+  const int64_t W = (d + 31) / 32;
+  switch (compressor) {
+    case Q_IDENTITY: return d;
+    case Q_TOPK: return 2 * k;
+    case Q_RANDK: return k;
+    case Q_SIGN: return 1 + W;
+    case Q_QSGD: return 1 + kOverflowSlots + (int64_t)(1 + magnitude_bits(levels)) * W;
+  }
+  return -1;
+}
+
+uint32_t float_bits(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, sizeof u);
+  return u;
+}
+float bits_float(uint32_t u) {
+  float f;
+  std::memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+// q = Q(v) and its message.  Returns 0, or -2 if more entries than there are slots
+// carry a level that does not fit the magnitude bits.
+int pack_message(const QParams& P, int64_t d, const float* v, uint64_t t, int worker, float* q,
+                 uint32_t* msg) {
+  std::vector<int32_t> sel((size_t)(P.compressor == Q_TOPK || P.compressor == Q_RANDK ? P.k : 0));
+  std::vector<int32_t> codes((size_t)d, 0);
+  double scal[4];
+  compress<float>(P, d, v, t, worker, q, sel.empty() ? nullptr : sel.data(), codes.data(), scal);
+  const int64_t W = (d + 31) / 32;
+  const int64_t words = message_words(P.compressor, d, P.k, P.levels);
+  for (int64_t j = 0; j < words; ++j) msg[j] = 0;
+  switch (P.compressor) {
+    case Q_IDENTITY:
+      for (int64_t e = 0; e < d; ++e) msg[e] = float_bits(q[e]);
+      break;
+    case Q_TOPK:
+      for (int64_t m = 0; m < P.k; ++m) {
+        msg[2 * m] = (uint32_t)sel[(size_t)m];
+        msg[2 * m + 1] = float_bits(q[sel[(size_t)m]]);
+      }
+      break;
+    case Q_RANDK:
+      for (int64_t m = 0; m < P.k; ++m) msg[m] = float_bits(q[sel[(size_t)m]]);
+      break;
+    case Q_SIGN:
+      msg[0] = float_bits((float)scal[1]);
+      for (int64_t e = 0; e < d; ++e)
+        if (codes[(size_t)e] < 0) msg[1 + e / 32] |= 1u << (e % 32);
+      break;
+    case Q_QSGD: {
+      const int mb = magnitude_bits(P.levels);
+      const int32_t maxmag = (1 << mb) - 1;
+      msg[0] = float_bits((float)scal[3]);
+      for (int j = 0; j < kOverflowSlots; ++j) msg[1 + j] = 0xFFFFFFFFu;
+      int used = 0;
+      uint32_t* planes = msg + 1 + kOverflowSlots;
+      for (int64_t e = 0; e < d; ++e) {
+        const bool neg = v[e] < 0.0f;   // the sign travels even with level 0
+        int32_t level = std::abs(codes[(size_t)e]);
+        if (level > maxmag) {
+          if (used == kOverflowSlots) return -2;
+          msg[1 + used++] = (uint32_t)e;
+          level = maxmag;
+        }
+        if (neg) planes[e / 32] |= 1u << (e % 32);
+        for (int p = 0; p < mb; ++p)
+          if ((level >> p) & 1) planes[(int64_t)(1 + p) * W + e / 32] |= 1u << (e % 32);
+      }
+      break;
+    }
+  }
+  return 0;
+}
+
+// The receiver's side: q from the message alone (plus the shared seed, the step and the
+// sender for random_a).
+void unpack_message(const QParams& P, int64_t d, uint64_t t, int worker, const uint32_t* msg,
+                    float* q) {
+  const int64_t W = (d + 31) / 32;
+  for (int64_t e = 0; e < d; ++e) q[e] = 0.0f;
+  switch (P.compressor) {
+    case Q_IDENTITY:
+      for (int64_t e = 0; e < d; ++e) q[e] = bits_float(msg[e]);
+      break;
+    case Q_TOPK:
+      for (int64_t m = 0; m < P.k; ++m) q[msg[2 * m]] = bits_float(msg[2 * m + 1]);
+      break;
+    case Q_RANDK: {
+      std::vector<int32_t> sel;
+      select_randk(d, P.k, P.seed, t, worker, sel);
+      for (int64_t m = 0; m < P.k; ++m) q[sel[(size_t)m]] = bits_float(msg[m]);
+      break;
+    }
+    case Q_SIGN: {
+      const float c = bits_float(msg[0]);
+      for (int64_t e = 0; e < d; ++e) q[e] = ((msg[1 + e / 32] >> (e % 32)) & 1u) ? -c : c;
+      break;
+    }
+    case Q_QSGD: {
+      const int mb = magnitude_bits(P.levels);
+      const float step = bits_float(msg[0]);
+      const uint32_t* planes = msg + 1 + kOverflowSlots;
+      for (int64_t e = 0; e < d; ++e) {
+        int32_t level = 0;
+        for (int p = 0; p < mb; ++p)
+          level |= (int32_t)((planes[(int64_t)(1 + p) * W + e / 32] >> (e % 32)) & 1u) << p;
+        for (int j = 0; j < kOverflowSlots; ++j)
+          if (msg[1 + j] == (uint32_t)e) level = P.levels;
+        const float mag = (float)level * step;
+        q[e] = ((planes[e / 32] >> (e % 32)) & 1u) ? -mag : mag;
+      }
+      break;
+    }
+  }
+}
+
 // Algorithm 1, line 9: x_i <- x_i - eta g_i  (product rounded, then the difference).
 template <class R>
 void sgd_step(int n, int64_t d, R* X, const R* G, R lr) {
@@ -534,6 +702,33 @@ double choco_ref_canonical_sum(int64_t d, const double* terms) {
                                   double* consensus, double* mean_norm, double* psi) {            \
     metrics<R>(n, d, X, Xhat, consensus, mean_norm, psi);                                         \
   }
+
+int64_t choco_ref_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t levels) {
+  return paper_message_bits(compressor, d, k, levels);
+}
+
+int64_t choco_ref_message_words(int32_t compressor, int64_t d, int64_t k, int32_t levels) {
+  return message_words(compressor, d, k, levels);
+}
+
+int choco_ref_pack_message(int32_t compressor, int64_t d, const float* v, int64_t k, int32_t levels,
+                           int32_t qsgd_biased, int32_t randk_rescale, uint64_t seed, uint64_t t,
+                           int32_t worker, float* q, uint32_t* msg) {
+  QParams P{compressor, k, levels, qsgd_biased, randk_rescale, seed};
+  if (d < 1) return -1;
+  if ((compressor == Q_TOPK || compressor == Q_RANDK) && (k < 1 || k > d)) return -1;
+  if (compressor == Q_QSGD && levels < 1) return -1;
+  return pack_message(P, d, v, t, worker, q, msg);
+}
+
+int choco_ref_unpack_message(int32_t compressor, int64_t d, int64_t k, int32_t levels,
+                             int32_t qsgd_biased, int32_t randk_rescale, uint64_t seed, uint64_t t,
+                             int32_t worker, const uint32_t* msg, float* q) {
+  QParams P{compressor, k, levels, qsgd_biased, randk_rescale, seed};
+  if (d < 1) return -1;
+  unpack_message(P, d, t, worker, msg, q);
+  return 0;
+}
 
 CHOCO_REF_DEFINE(f32, float)
 CHOCO_REF_DEFINE(f64, double)

@@ -37,6 +37,23 @@ def lib():
                                                ctypes.c_int64, ctypes.c_int32]
         _lib.choco_ref_canonical_sum.restype = ctypes.c_double
         _lib.choco_ref_canonical_sum.argtypes = [ctypes.c_int64, _f64p]
+        _lib.choco_ref_paper_message_bits.restype = ctypes.c_int64
+        _lib.choco_ref_paper_message_bits.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                                      ctypes.c_int32]
+        _lib.choco_ref_message_words.restype = ctypes.c_int64
+        _lib.choco_ref_message_words.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                                 ctypes.c_int32]
+        f32p = ctypes.POINTER(ctypes.c_float)
+        _lib.choco_ref_pack_message.restype = ctypes.c_int
+        _lib.choco_ref_pack_message.argtypes = [ctypes.c_int32, ctypes.c_int64, f32p, ctypes.c_int64,
+                                                ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, f32p,
+                                                _u32p]
+        _lib.choco_ref_unpack_message.restype = ctypes.c_int
+        _lib.choco_ref_unpack_message.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                                  ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32,
+                                                  _u32p, f32p]
         for suf, real in (("f32", ctypes.c_float), ("f64", ctypes.c_double)):
             rp = ctypes.POINTER(real)
             f = getattr(_lib, "choco_ref_compress_" + suf)
@@ -116,6 +133,41 @@ def compress(compressor, v, k=1, levels=1, qsgd_biased=1, randk_rescale=0, seed=
     if rc != 0:
         raise ValueError("oracle rejected the compressor arguments")
     return dict(q=q, sel=sel, codes=codes, scal=scal)
+
+
+def paper_message_bits(compressor, d, k=0, levels=1):
+    """Bits per message as Appendix C counts them."""
+    return int(lib().choco_ref_paper_message_bits(compressor, d, k, levels))
+
+
+def message_words(compressor, d, k=0, levels=1):
+    """32-bit words of one message in this build's byte layout."""
+    return int(lib().choco_ref_message_words(compressor, d, k, levels))
+
+
+def pack_message(compressor, v, k=1, levels=1, qsgd_biased=1, randk_rescale=0, seed=0, t=0, worker=0):
+    """(q, message words) for one float32 vector v: q = Q(v) and its encoding."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    q = np.empty_like(v)
+    msg = np.zeros(message_words(compressor, v.size, k, levels), dtype=np.uint32)
+    rc = lib().choco_ref_pack_message(compressor, v.size, _ptr(v, ctypes.c_float), k, levels,
+                                      qsgd_biased, randk_rescale, seed, t, worker,
+                                      _ptr(q, ctypes.c_float), _ptr(msg, ctypes.c_uint32))
+    if rc != 0:
+        raise ValueError("oracle could not pack the message (%d)" % rc)
+    return q, msg
+
+
+def unpack_message(compressor, d, msg, k=1, levels=1, qsgd_biased=1, randk_rescale=0, seed=0, t=0,
+                   worker=0):
+    """The receiver's q from the message (and the shared seed, step and sender for random_a)."""
+    msg = np.ascontiguousarray(msg, dtype=np.uint32)
+    q = np.empty(d, dtype=np.float32)
+    rc = lib().choco_ref_unpack_message(compressor, d, k, levels, qsgd_biased, randk_rescale, seed, t,
+                                        worker, _ptr(msg, ctypes.c_uint32), _ptr(q, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle could not unpack the message")
+    return q
 
 
 class RefState:

@@ -712,3 +712,127 @@ def test_layered_steps_keep_the_average_and_converge(q):
     unbiased = q.get("randk_rescale") or q.get("qsgd_biased") == 0
     if not unbiased:
         assert m["consensus"] < 1e-3 * c0
+
+
+# --------------------------------------------------------------------------
+# messages on the wire (Appendix C: the size stated with each operator)
+# --------------------------------------------------------------------------
+def test_message_sizes_match_the_printed_tables():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "message_sizes.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 10
+    for source, d, op, par, mb in rows:
+        d, mb = int(d), float(mb)
+        if op == "identity":
+            bits = ref.paper_message_bits(ref.IDENTITY, d)
+        elif op == "sign":
+            bits = ref.paper_message_bits(ref.SIGN, d)
+        elif op == "qsgd_bits":
+            bits = ref.paper_message_bits(ref.QSGD, d, levels=2 ** (int(par) - 1))
+        else:
+            bits = ref.paper_message_bits(ref.TOPK, d, k=int(math.floor(float(par) * d)))
+        digits = len(mb.__repr__().split(".")[1])
+        assert abs(bits / 8 / 2**20 - mb) <= 0.6 * 10.0 ** -digits, (source, op, par)
+
+
+def test_message_bit_counts():
+    # Appendix C: d + 32 (sign), 2*32*k (top_a), 32*k (random_a), b bits per entry (gsgd_b)
+    assert ref.paper_message_bits(ref.SIGN, 1000) == 1032
+    assert ref.paper_message_bits(ref.TOPK, 1000, k=10) == 640
+    assert ref.paper_message_bits(ref.RANDK, 1000, k=10) == 320
+    assert ref.paper_message_bits(ref.QSGD, 1000, levels=8) == 4 * 1000 + 32
+    assert ref.paper_message_bits(ref.IDENTITY, 1000) == 32000
+    # the byte layout meets those counts up to word padding (and the four index slots of gsgd)
+    for d in (32, 64, 4096):
+        assert 32 * ref.message_words(ref.SIGN, d) == ref.paper_message_bits(ref.SIGN, d)
+        assert (32 * ref.message_words(ref.QSGD, d, levels=8)
+                == ref.paper_message_bits(ref.QSGD, d, levels=8) + 4 * 32)
+    assert 32 * ref.message_words(ref.TOPK, 1000, k=7) == ref.paper_message_bits(ref.TOPK, 1000, k=7)
+    assert 32 * ref.message_words(ref.RANDK, 1000, k=7) == ref.paper_message_bits(ref.RANDK, 1000, k=7)
+    assert ref.message_words(ref.SIGN, 33) == 1 + 2
+
+
+WIRE_Q = [
+    (ref.IDENTITY, {}),
+    (ref.TOPK, dict(k=9)),
+    (ref.RANDK, dict(k=9, seed=5, t=3, worker=2)),
+    (ref.RANDK, dict(k=9, seed=5, t=3, worker=2, randk_rescale=1)),
+    (ref.SIGN, {}),
+    (ref.QSGD, dict(levels=16, seed=8, t=1, worker=4)),
+    (ref.QSGD, dict(levels=2, seed=8, qsgd_biased=0)),
+    (ref.QSGD, dict(levels=3, seed=8)),
+    (ref.QSGD, dict(levels=1, seed=8)),
+]
+
+
+@pytest.mark.parametrize("d", [9, 31, 32, 33, 1000])
+@pytest.mark.parametrize("comp,kw", WIRE_Q)
+def test_receiver_recovers_q_from_the_message(comp, kw, d):
+    v = synth.normal_state(1, d, seed=d)[0]
+    v[d // 2] = 0.0
+    want = ref.compress(comp, v, **kw)["q"]
+    q, msg = ref.pack_message(comp, v, **kw)
+    assert np.array_equal(q, want)
+    got = ref.unpack_message(comp, d, msg, **kw)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))   # also the sign of zeros
+
+
+def test_message_layouts_bit_by_bit():
+    d, s = 77, 8
+    v = synth.normal_state(1, d, seed=1)[0]
+    W = (d + 31) // 32
+
+    def bits_of(words):   # bit e%32 of word e/32
+        return np.unpackbits(words.view(np.uint8), bitorder="little")[:d].astype(bool)
+
+    # sign: the scale, then one bit per entry
+    det = ref.compress(ref.SIGN, v)
+    _, msg = ref.pack_message(ref.SIGN, v)
+    assert msg[:1].view(np.float32)[0] == np.float32(det["scal"][1])
+    assert np.array_equal(bits_of(msg[1:1 + W]), v < 0)
+    # gsgd: step, four index slots, the sign plane, then magnitude bits lowest first
+    det = ref.compress(ref.QSGD, v, levels=s, seed=2)
+    _, msg = ref.pack_message(ref.QSGD, v, levels=s, seed=2)
+    assert msg[:1].view(np.float32)[0] == np.float32(det["scal"][3])
+    assert np.all(msg[1:5] == 0xFFFFFFFF)
+    planes = msg[5:].reshape(4, W)                      # 1 + bit_length(s - 1) = 4 planes
+    assert np.array_equal(bits_of(planes[0]), v < 0)
+    level = sum(bits_of(planes[1 + p]).astype(int) << p for p in range(3))
+    assert np.array_equal(level, np.abs(det["codes"]))
+    # top_a: (index, value) pairs by ascending index; random_a: the values alone
+    det = ref.compress(ref.TOPK, v, k=5)
+    _, msg = ref.pack_message(ref.TOPK, v, k=5)
+    assert np.array_equal(msg[0::2], det["sel"].astype(np.uint32))
+    assert np.array_equal(msg[1::2].view(np.float32), v[det["sel"]])
+    det = ref.compress(ref.RANDK, v, k=5, seed=4, t=6, worker=1, randk_rescale=1)
+    _, msg = ref.pack_message(ref.RANDK, v, k=5, seed=4, t=6, worker=1, randk_rescale=1)
+    assert np.array_equal(msg.view(np.float32), det["q"][det["sel"]])
+
+
+def test_gsgd_level_s_travels_through_the_index_slots():
+    # one entry holds almost the whole norm: floor(s |v| / ||v|| + u) reaches s, which the
+    # magnitude bits (0 .. s-1) cannot hold
+    s = 4
+    v = np.full(50, 1e-4, dtype=np.float32)
+    v[17] = -3.0
+    hits = 0
+    for t in range(20):
+        det = ref.compress(ref.QSGD, v, levels=s, seed=1, t=t)
+        q, msg = ref.pack_message(ref.QSGD, v, levels=s, seed=1, t=t)
+        if abs(det["codes"][17]) == s:
+            hits += 1
+            assert msg[1] == 17 and np.all(msg[2:5] == 0xFFFFFFFF)
+        assert np.array_equal(ref.unpack_message(ref.QSGD, 50, msg, levels=s, seed=1, t=t), det["q"])
+    assert hits >= 10
+    # s = 2: up to three entries can get there at once
+    v = np.zeros(40, dtype=np.float32)
+    v[[3, 20, 33]] = [0.575, -0.575, 0.575]
+    seen = 0
+    for t in range(200):
+        det = ref.compress(ref.QSGD, v, levels=2, seed=3, t=t)
+        q, msg = ref.pack_message(ref.QSGD, v, levels=2, seed=3, t=t)
+        over = np.flatnonzero(np.abs(det["codes"]) == 2)
+        seen = max(seen, over.size)
+        assert list(msg[1:1 + over.size]) == list(over)
+        assert np.array_equal(ref.unpack_message(ref.QSGD, 40, msg, levels=2, seed=3, t=t), det["q"])
+    assert seen >= 2
