@@ -182,6 +182,33 @@ int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
    and choco_last_scalars is CHOCO_E_UNSUPPORTED.  Synchronises the stream. */
 int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
 
+/* Messages on the wire (Appendix C states a size with each operator).
+   choco_paper_message_bits: that size in bits, host arithmetic only: SIGN d + 32, TOPK
+   2*32*k, RANDK 32*k, QSGD b*d + 32 with b = log2(levels) + 1, IDENTITY 32*d.
+   choco_pack_messages encodes what every worker sent in the LAST gossip step into
+   msgs_dev (n messages of choco_message_bytes each, back to back, 4-byte aligned), in
+   32-bit words, W = ceil(d/32):
+     SIGN   [scale as float][W words: bit e%32 of word e/32 set iff the entry is -scale]
+     QSGD   [step as float][4 words: ascending indices of the entries at level `levels`
+            when that exceeds the magnitude bits, 0xFFFFFFFF if unused][W words: signs of
+            the non-zero levels][mb planes of W words: bit p of min(level, 2^mb - 1)],
+            mb = bit length of levels - 1 (at least 1): b bits per entry for levels = 2^(b-1)
+     TOPK   k pairs [index][value as float], order of the pairs unspecified
+     RANDK  k values as float, ascending index (the receiver repeats the draw of the mask)
+   SIGN and QSGD read the codes of the last step from the buffer given to choco_set_capture
+   (CHOCO_E_INVAL if capture is off); QSGD synchronises and returns CHOCO_E_UNSUPPORTED if
+   more than 4 entries sit at level `levels`.  choco_unpack_messages is the receiver's
+   side: it writes the dense q of every worker (n*ld floats, 16-byte aligned, zero where
+   nothing was sent); for RANDK the mask is the one the library drew in the last step.
+   Not implemented (CHOCO_E_UNSUPPORTED): IDENTITY, layer-wise configurations, RANDK with
+   d > 327,680.  These calls are not part of the timed path. */
+int choco_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t levels,
+                             int64_t *bits_host);
+int choco_message_bytes(choco_ctx *ctx, size_t *bytes_host);
+int choco_pack_messages(choco_ctx *ctx, void *msgs_dev);
+int choco_unpack_messages(choco_ctx *ctx, const void *msgs_dev, float *q_dev);
+
+
 
 /* Step counter t (keys the random operators; set it to resume a run exactly). */
 int choco_get_step(choco_ctx *ctx, uint64_t *t_host);

@@ -439,8 +439,8 @@ int gossip_step(int n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx
 // little-endian words, W = ceil(d / 32):
 //   sign      [c as float][W words: bit e%32 of word e/32 set iff the entry is -c]
 //   gsgd      [step as float][4 words: ascending indices of entries whose level does
-//             not fit the magnitude bits, 0xFFFFFFFF when unused][plane 0: the signs,
-//             W words][planes 1..mb: bit p-1 of min(level, 2^mb - 1), W words each],
+//             not fit the magnitude bits, 0xFFFFFFFF when unused][plane 0: the signs of
+//             the entries with a non-zero level (a zero is sent as +0), W words][planes 1..mb: bit p-1 of min(level, 2^mb - 1), W words each],
 //             mb = bit length of s - 1 (at least 1).  With s = 2^(b-1) that is b bits
 //             per entry as the paper counts; the level s itself, which the formula
 //             reaches for the few entries that hold almost the whole norm although
@@ -533,7 +533,7 @@ int pack_message(const QParams& P, int64_t d, const float* v, uint64_t t, int wo
       int used = 0;
       uint32_t* planes = msg + 1 + kOverflowSlots;
       for (int64_t e = 0; e < d; ++e) {
-        const bool neg = v[e] < 0.0f;   // the sign travels even with level 0
+        const bool neg = codes[(size_t)e] < 0;   // a zero level carries no sign
         int32_t level = std::abs(codes[(size_t)e]);
         if (level > maxmag) {
           if (used == kOverflowSlots) return -2;

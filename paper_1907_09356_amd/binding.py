@@ -22,7 +22,8 @@ EXPORTS = [
     "choco_momentum_step", "choco_step_momentum", "choco_metrics", "choco_xhat", "choco_nsum", "choco_last_selection",
     "choco_set_capture", "choco_last_scalars", "choco_layer_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
-    "choco_profile_report",
+    "choco_profile_report", "choco_paper_message_bits", "choco_message_bytes", "choco_pack_messages",
+    "choco_unpack_messages",
 ]
 
 
@@ -86,6 +87,11 @@ def lib():
         L.choco_set_capture.argtypes = [vp, vp]
         L.choco_last_scalars.argtypes = [vp, dp]
         L.choco_layer_scalars.argtypes = [vp, dp]
+        L.choco_paper_message_bits.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                               ctypes.POINTER(ctypes.c_int64)]
+        L.choco_message_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+        L.choco_pack_messages.argtypes = [vp, vp]
+        L.choco_unpack_messages.argtypes = [vp, vp, vp]
         L.choco_get_step.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.choco_set_step.argtypes = [vp, ctypes.c_uint64]
         L.choco_sync.argtypes = [vp]
@@ -148,6 +154,14 @@ def make_config(n, d, row_ptr, col_idx, w, gamma, compressor, k=1, levels=1, qsg
             cfg.layer_k_host = lk.ctypes.data_as(i64p)
             keep.append(lk)
     return cfg, tuple(keep)
+
+
+def paper_message_bits(compressor, d, k=1, levels=1):
+    """Bits of one message as Appendix C counts them."""
+    out = ctypes.c_int64(0)
+    _check(lib().choco_paper_message_bits(int(compressor), int(d), int(k), int(levels), ctypes.byref(out)),
+           "choco_paper_message_bits")
+    return out.value
 
 
 def workspace_bytes(cfg):
@@ -272,6 +286,27 @@ class Choco:
         _check(lib().choco_layer_scalars(self.ctx, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))),
                "choco_layer_scalars")
         return out
+
+    def message_bytes(self):
+        out = ctypes.c_size_t(0)
+        _check(lib().choco_message_bytes(self.ctx, ctypes.byref(out)), "choco_message_bytes")
+        return out.value
+
+    def pack_messages(self):
+        """The messages of the last gossip step: uint32 CUDA tensor (n, words per message)."""
+        torch = self.torch
+        words = self.message_bytes() // 4
+        msgs = torch.empty((self.n, words), dtype=torch.int32, device=self.X.device)
+        _check(lib().choco_pack_messages(self.ctx, msgs.data_ptr()), "choco_pack_messages")
+        return msgs
+
+    def unpack_messages(self, msgs):
+        """Dense q (n, ld) decoded from messages as pack_messages returns them."""
+        assert msgs.is_cuda and msgs.is_contiguous() and msgs.dtype == self.torch.int32
+        assert msgs.shape == (self.n, self.message_bytes() // 4)
+        q = self.torch.empty_like(self.X)
+        _check(lib().choco_unpack_messages(self.ctx, msgs.data_ptr(), q.data_ptr()), "choco_unpack_messages")
+        return q
 
     def get_step(self):
         t = ctypes.c_uint64()

@@ -16,6 +16,7 @@
 #include "choco.h"
 #include "choco_kernels.h"
 #include "choco_layers.h"
+#include "choco_wire.h"
 
 using namespace choco;
 
@@ -35,6 +36,7 @@ struct choco_ctx {
   int nlayers;            // > 0: the operator is applied layer by layer
   int nlarge, nmid;       // layers (by falling length) that take a 1024- / a 256-thread workgroup
   uint64_t t;             // step counter
+  uint32_t* wire;         // device scratch of the message encoder: n counters, n x 4 index slots, n status words
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
   int metrics_blocks;
@@ -57,7 +59,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
-      layers, layer_work, layer_guess, layer_scal, mpart, mout, total;
+      layers, layer_work, layer_guess, layer_scal, wire, mpart, mout, total;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
   bool multipart;
@@ -204,6 +206,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
   L.layer_scal = take((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
+  L.wire = take((size_t)c.n * (2 + kOverflowSlots) * sizeof(uint32_t));   // message encoder: counters, index slots, status
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -264,14 +267,14 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_WIRE, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
   "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
-  "k_layer_compress", "k_layer_compress_sgd"};
+  "k_layer_compress", "k_layer_compress_sgd", "k_wire"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
 // Brackets one launch with two events when profiling is on (no-op otherwise).
@@ -643,6 +646,55 @@ int fused_iteration(choco_ctx* ctx, const LocalUpdate& u) {
   return run_gossip(ctx, LocalUpdate());
 }
 
+int magnitude_bits(int levels) {
+  int mb = 0;
+  for (int x = levels - 1; x > 0; x >>= 1) ++mb;
+  return mb < 1 ? 1 : mb;
+}
+
+// 32-bit words of one worker's message in the layout of choco_wire.h.
+int64_t message_words(int compressor, int64_t d, int64_t k, int levels) {
+  const int64_t W = (d + 31) / 32;
+  switch (compressor) {
+    case CHOCO_Q_TOPK: return 2 * k;
+    case CHOCO_Q_RANDK: return k;
+    case CHOCO_Q_SIGN: return 1 + W;
+    case CHOCO_Q_QSGD: return 1 + kOverflowSlots + (int64_t)(1 + magnitude_bits(levels)) * W;
+    default: return -1;
+  }
+}
+
+// Which configurations the message kernels cover.
+int wire_supported(const choco_ctx* ctx) {
+  if (ctx->nlayers > 0 || ctx->cfg.compressor == CHOCO_Q_IDENTITY) return CHOCO_E_UNSUPPORTED;
+  if (ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->args.bitmap_words == 0) return CHOCO_E_UNSUPPORTED;
+  return CHOCO_OK;
+}
+
+WireArgs wire_args(const choco_ctx* ctx) {
+  const Args& A = ctx->args;
+  WireArgs Wa;
+  std::memset(&Wa, 0, sizeof(Wa));
+  Wa.n = A.n;
+  Wa.d = A.d;
+  Wa.ld = A.ld;
+  Wa.words = message_words(ctx->cfg.compressor, A.d, A.k, ctx->cfg.levels);
+  Wa.W = ((int64_t)A.d + 31) / 32;
+  Wa.mb = magnitude_bits(ctx->cfg.levels);
+  Wa.levels = ctx->cfg.levels;
+  Wa.codes = A.codes;
+  Wa.ctl = A.ctl;
+  Wa.ovf_count = ctx->wire;
+  Wa.ovf_idx = ctx->wire + A.n;
+  Wa.status = ctx->wire + (size_t)A.n * (1 + kOverflowSlots);
+  Wa.k = A.k;
+  Wa.sel_idx = A.sel_idx;
+  Wa.sel_val = A.sel_val;
+  Wa.bitmap = A.bitmap;
+  Wa.bitmap_words = A.bitmap_words;
+  return Wa;
+}
+
 }  // namespace
 
 extern "C" {
@@ -818,6 +870,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
+  ctx->wire = (uint32_t*)(base + L.wire);
   ctx->metrics_part = (double*)(base + L.mpart);
   ctx->metrics_out = (double*)(base + L.mout);
   ctx->metrics_blocks = kMetricsBlocks;
@@ -939,6 +992,99 @@ int choco_last_selection(choco_ctx* ctx, int32_t* idx_dev, float* val_dev) {
   if (val_dev)
     HIP_TRY(ctx, hipMemcpyAsync(val_dev, A.sel_val, count * sizeof(float), hipMemcpyDeviceToDevice,
                                 ctx->stream));
+  return CHOCO_OK;
+}
+
+int choco_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t levels, int64_t* bits_host) {
+  if (!bits_host || d < 1) return CHOCO_E_INVAL;
+  switch (compressor) {
+    case CHOCO_Q_IDENTITY: *bits_host = 32 * d; return CHOCO_OK;
+    case CHOCO_Q_TOPK:
+    case CHOCO_Q_RANDK:
+      if (k < 1 || k > d) return CHOCO_E_INVAL;
+      *bits_host = (compressor == CHOCO_Q_TOPK ? 64 : 32) * k;
+      return CHOCO_OK;
+    case CHOCO_Q_SIGN: *bits_host = d + 32; return CHOCO_OK;
+    case CHOCO_Q_QSGD: {
+      if (levels < 1) return CHOCO_E_INVAL;
+      int b = 1;
+      for (int x = levels; x > 1; x >>= 1) ++b;
+      *bits_host = (int64_t)b * d + 32;
+      return CHOCO_OK;
+    }
+    default: return CHOCO_E_INVAL;
+  }
+}
+
+int choco_message_bytes(choco_ctx* ctx, size_t* bytes_host) {
+  if (!ctx || ctx->destroyed || !bytes_host) return CHOCO_E_INVAL;
+  const int rc = wire_supported(ctx);
+  if (rc != CHOCO_OK) return rc;
+  *bytes_host = (size_t)message_words(ctx->cfg.compressor, ctx->args.d, ctx->args.k, ctx->cfg.levels) * 4;
+  return CHOCO_OK;
+}
+
+int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
+  if (!ctx || ctx->destroyed || !msgs_dev || ((uintptr_t)msgs_dev & 3u) != 0) return CHOCO_E_INVAL;
+  int rc = wire_supported(ctx);
+  if (rc != CHOCO_OK) return rc;
+  const WireArgs Wa = wire_args(ctx);
+  uint32_t* msg = (uint32_t*)msgs_dev;
+  const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
+  const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
+  switch (ctx->cfg.compressor) {
+    case CHOCO_Q_SIGN:
+      if (!Wa.codes) return CHOCO_E_INVAL;   // the codes of the last step come from choco_set_capture
+      LAUNCH(ctx, KID_WIRE, k_pack_sign, wgrid, dim3(256), 0, Wa, msg);
+      break;
+    case CHOCO_Q_QSGD: {
+      if (!Wa.codes) return CHOCO_E_INVAL;
+      LAUNCH(ctx, KID_WIRE, k_pack_gsgd, wgrid, dim3(256), 0, Wa, msg);
+      LAUNCH(ctx, KID_WIRE, k_pack_gsgd_finish, dim3((unsigned)Wa.n), dim3(64), 0, Wa, msg);
+      LAUNCH_CHECK(ctx);
+      std::vector<uint32_t> status((size_t)Wa.n);
+      HIP_TRY(ctx, hipMemcpyAsync(status.data(), Wa.status, status.size() * sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                  ctx->stream));
+      HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+      for (uint32_t st : status)
+        if (st) return CHOCO_E_UNSUPPORTED;   // more entries at level s than the message has slots for
+      return CHOCO_OK;
+    }
+    case CHOCO_Q_TOPK:
+      LAUNCH(ctx, KID_WIRE, k_pack_topk, kgrid, dim3(256), 0, Wa, msg);
+      break;
+    case CHOCO_Q_RANDK:
+      LAUNCH(ctx, KID_WIRE, k_pack_randk, dim3((unsigned)Wa.n), dim3(1024), (size_t)Wa.bitmap_words * sizeof(uint32_t),
+             Wa, msg);
+      break;
+    default: return CHOCO_E_UNSUPPORTED;
+  }
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
+int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
+  if (!ctx || ctx->destroyed || !msgs_dev || !q_dev) return CHOCO_E_INVAL;
+  if (((uintptr_t)msgs_dev & 3u) != 0 || ((uintptr_t)q_dev & 15u) != 0) return CHOCO_E_INVAL;
+  const int rc = wire_supported(ctx);
+  if (rc != CHOCO_OK) return rc;
+  const WireArgs Wa = wire_args(ctx);
+  const uint32_t* msg = (const uint32_t*)msgs_dev;
+  const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
+  const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
+  // every entry of q is written: pad columns and entries not sent are zero
+  LAUNCH(ctx, KID_WIRE, k_wire_zero, dim3((unsigned)((Wa.ld + 1023) / 1024), (unsigned)Wa.n), dim3(256), 0, q_dev, Wa.ld);
+  switch (ctx->cfg.compressor) {
+    case CHOCO_Q_SIGN: LAUNCH(ctx, KID_WIRE, k_unpack_sign, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
+    case CHOCO_Q_QSGD: LAUNCH(ctx, KID_WIRE, k_unpack_gsgd, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
+    case CHOCO_Q_TOPK: LAUNCH(ctx, KID_WIRE, k_unpack_topk, kgrid, dim3(256), 0, Wa, msg, q_dev); break;
+    case CHOCO_Q_RANDK:
+      LAUNCH(ctx, KID_WIRE, k_unpack_randk, dim3((unsigned)Wa.n), dim3(1024),
+             (size_t)Wa.bitmap_words * sizeof(uint32_t), Wa, msg, q_dev);
+      break;
+    default: return CHOCO_E_UNSUPPORTED;
+  }
+  LAUNCH_CHECK(ctx);
   return CHOCO_OK;
 }
 

@@ -1,0 +1,267 @@
+// Messages on the wire (Appendix C states a size with each operator: d + 32 bits for
+// sign, 2*32*k for top_a, 32*k for random_a, b bits per entry for gsgd_b).  These kernels
+// encode the q of the last gossip step into those sizes and decode them again; they are
+// not on the timed path (on one GPU "sending" is memory traffic), they are what a
+// worker-per-GPU mapping would put on the links.
+//
+// Layout, 32-bit words, W = ceil(d / 32), one message per worker, messages back to back:
+//   sign      [c as float][W words: bit e%32 of word e/32 set iff the entry is -c]
+//   gsgd      [step as float][4 words: ascending indices of entries whose level exceeds
+//             the magnitude bits, 0xFFFFFFFF when unused][plane 0: signs of the non-zero
+//             levels][planes 1..mb: bit p-1 of min(level, 2^mb - 1)], mb = bit length of s-1
+//   top_a     k pairs [index][value]; the order of the pairs is not specified
+//   random_a  k values in ascending order of index (the receiver draws the same mask)
+#pragma once
+
+#include "choco_kernels.h"
+
+namespace choco {
+
+constexpr int kOverflowSlots = 4;
+
+struct WireArgs {
+  int32_t n, d;
+  int64_t ld;
+  int64_t words;            // words per message
+  int64_t W;                // words per bit plane
+  int32_t mb;               // gsgd: magnitude bits
+  int32_t levels;
+  const int32_t* codes;     // n x ld transmitted codes of the last step (sign, gsgd)
+  const WorkerCtl* ctl;
+  uint32_t* ovf_count;      // n
+  uint32_t* ovf_idx;        // n x kOverflowSlots
+  uint32_t* status;         // n: non-zero if a message could not be encoded
+  int64_t k;
+  const int32_t* sel_idx;
+  const float* sel_val;
+  const uint32_t* bitmap;
+  int64_t bitmap_words;
+};
+
+// The 32 codes behind word w of a row's bit planes; entries past d read as 0.
+__device__ __forceinline__ void load_codes32(const WireArgs& A, int i, int64_t w, int32_t (&c)[32]) {
+  const int32_t* src = A.codes + (int64_t)i * A.ld + 32 * w;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    vi4 q = vi4{0, 0, 0, 0};
+    if (32 * w + 4 * j < A.d) q = *reinterpret_cast<const vi4*>(src + 4 * j);   // ld is a multiple of 4
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c[4 * j + u] = (32 * w + 4 * j + u < A.d) ? q[u] : 0;
+  }
+}
+
+// grid (ceil(W / 256), n): one thread per word of the sign plane
+__global__ __launch_bounds__(256) void k_pack_sign(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.y;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t* out = msg + (int64_t)i * A.words;
+  if (w == 0) out[0] = __float_as_uint(A.ctl[i].scale_c);
+  if (w >= A.W) return;
+  int32_t c[32];
+  load_codes32(A, i, w, c);
+  uint32_t bits = 0;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) bits |= (c[j] < 0 ? 1u : 0u) << j;
+  out[1 + w] = bits;
+}
+
+// grid (ceil(W / 256), n): one thread per word position, all planes
+__global__ __launch_bounds__(256) void k_pack_gsgd(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.y;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t* out = msg + (int64_t)i * A.words;
+  if (w == 0) out[0] = __float_as_uint(A.ctl[i].scale_step);
+  if (w >= A.W) return;
+  int32_t c[32];
+  load_codes32(A, i, w, c);
+  const int32_t maxmag = (1 << A.mb) - 1;
+  uint32_t* planes = out + 1 + kOverflowSlots;
+  uint32_t sign = 0;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    sign |= (c[j] < 0 ? 1u : 0u) << j;
+    c[j] = c[j] < 0 ? -c[j] : c[j];
+    if (c[j] > maxmag) {   // the level s itself: rare, goes through the index slots
+      const uint32_t slot = atomicAdd(A.ovf_count + i, 1u);
+      if (slot < (uint32_t)kOverflowSlots) A.ovf_idx[i * kOverflowSlots + slot] = (uint32_t)(32 * w + j);
+      c[j] = maxmag;
+    }
+  }
+  planes[w] = sign;
+  for (int p = 0; p < A.mb; ++p) {
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) bits |= (uint32_t)((c[j] >> p) & 1) << j;
+    planes[(int64_t)(1 + p) * A.W + w] = bits;
+  }
+}
+
+// grid n, one wave: orders the index slots, flags a message with too many, re-arms the counter
+__global__ __launch_bounds__(64) void k_pack_gsgd_finish(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  uint32_t* out = msg + (int64_t)i * A.words;
+  const uint32_t cnt = A.ovf_count[i];
+  uint32_t v[kOverflowSlots];
+  for (int j = 0; j < kOverflowSlots; ++j) v[j] = (uint32_t)j < cnt ? A.ovf_idx[i * kOverflowSlots + j] : 0xFFFFFFFFu;
+  for (int a = 1; a < kOverflowSlots; ++a)
+    for (int b = a; b > 0 && v[b] < v[b - 1]; --b) {
+      const uint32_t t = v[b];
+      v[b] = v[b - 1];
+      v[b - 1] = t;
+    }
+  for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
+  A.status[i] = cnt > (uint32_t)kOverflowSlots ? 1u : 0u;
+  A.ovf_count[i] = 0;
+}
+
+// grid (ceil(k / 256), n)
+__global__ __launch_bounds__(256) void k_pack_topk(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= A.k) return;
+  uint32_t* out = msg + (int64_t)i * A.words;
+  out[2 * m] = (uint32_t)A.sel_idx[(int64_t)i * A.k + m];
+  out[2 * m + 1] = __float_as_uint(A.sel_val[(int64_t)i * A.k + m]);
+}
+
+// Exclusive prefix of the bit counts of a worker's kept-entry bitmap into LDS.
+// block 1024; pre holds bitmap_words entries.
+__device__ __forceinline__ void bitmap_prefix(const WireArgs& A, int i, uint32_t* pre, uint32_t* sh_wave) {
+  const uint32_t* bm = A.bitmap + (int64_t)i * A.bitmap_words;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t per = (A.bitmap_words + 1023) / 1024;      // consecutive words per thread
+  const int64_t w0 = (int64_t)tid * per;
+  uint32_t mine = 0;
+  for (int64_t w = w0; w < w0 + per && w < A.bitmap_words; ++w) mine += __popc(bm[w]);
+  uint32_t incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) sh_wave[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += sh_wave[w];
+  uint32_t run = base + incl - mine;
+  for (int64_t w = w0; w < w0 + per && w < A.bitmap_words; ++w) {
+    pre[w] = run;
+    run += __popc(bm[w]);
+  }
+  __syncthreads();
+}
+
+// random_a with a bitmap per worker: the value of kept entry e goes to position
+// rank(e) = number of kept entries below e.  grid n, block 1024, dynamic LDS = bitmap_words words
+__global__ __launch_bounds__(1024) void k_pack_randk(WireArgs A, uint32_t* msg) {
+  extern __shared__ uint32_t pre[];
+  __shared__ uint32_t sh_wave[16];
+  const int i = blockIdx.x;
+  bitmap_prefix(A, i, pre, sh_wave);
+  const uint32_t* bm = A.bitmap + (int64_t)i * A.bitmap_words;
+  uint32_t* out = msg + (int64_t)i * A.words;
+  for (int64_t m = threadIdx.x; m < A.k; m += 1024) {
+    const uint32_t e = (uint32_t)A.sel_idx[(int64_t)i * A.k + m];
+    const uint32_t rank = pre[e >> 5] + __popc(bm[e >> 5] & ((1u << (e & 31u)) - 1u));
+    out[rank] = __float_as_uint(A.sel_val[(int64_t)i * A.k + m]);
+  }
+}
+
+// ---- the receiver's side: dense q (n x ld) from the messages ----
+
+// grid (ceil(ld / 1024), n): q = 0
+__global__ __launch_bounds__(256) void k_wire_zero(float* q, int64_t ld) {
+  const int64_t o = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (o < ld) *reinterpret_cast<vf4*>(q + (int64_t)blockIdx.y * ld + o) = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+}
+
+__device__ __forceinline__ void store32(const WireArgs& A, float* q, int i, int64_t w, const float (&v)[32]) {
+  float* dst = q + (int64_t)i * A.ld + 32 * w;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (32 * w + 4 * j < A.d) {   // pad columns of the last 4-vector get the zeros set by the caller of this helper
+      vf4 o;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = (32 * w + 4 * j + u < A.d) ? v[4 * j + u] : 0.0f;
+      *reinterpret_cast<vf4*>(dst + 4 * j) = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_unpack_sign(WireArgs A, const uint32_t* msg, float* q) {
+  const int i = blockIdx.y;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (w >= A.W) return;
+  const uint32_t* in = msg + (int64_t)i * A.words;
+  const float c = __uint_as_float(in[0]);
+  const uint32_t bits = in[1 + w];
+  float v[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) v[j] = ((bits >> j) & 1u) ? -c : c;
+  store32(A, q, i, w, v);
+}
+
+__global__ __launch_bounds__(256) void k_unpack_gsgd(WireArgs A, const uint32_t* msg, float* q) {
+  const int i = blockIdx.y;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (w >= A.W) return;
+  const uint32_t* in = msg + (int64_t)i * A.words;
+  const float step = __uint_as_float(in[0]);
+  const uint32_t* planes = in + 1 + kOverflowSlots;
+  int32_t level[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) level[j] = 0;
+  for (int p = 0; p < A.mb; ++p) {
+    const uint32_t bits = planes[(int64_t)(1 + p) * A.W + w];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) level[j] |= (int32_t)((bits >> j) & 1u) << p;
+  }
+  for (int s = 0; s < kOverflowSlots; ++s) {
+    const uint32_t e = in[1 + s];
+    if (e != 0xFFFFFFFFu && (int64_t)(e >> 5) == w) {
+#pragma unroll
+      for (int j = 0; j < 32; ++j)
+        if ((int)(e & 31u) == j) level[j] = A.levels;
+    }
+  }
+  const uint32_t sign = planes[w];
+  float v[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const float mag = (float)level[j] * step;
+    v[j] = ((sign >> j) & 1u) ? -mag : mag;
+  }
+  store32(A, q, i, w, v);
+}
+
+// after k_wire_zero.  grid (ceil(k / 256), n)
+__global__ __launch_bounds__(256) void k_unpack_topk(WireArgs A, const uint32_t* msg, float* q) {
+  const int i = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= A.k) return;
+  const uint32_t* in = msg + (int64_t)i * A.words;
+  const uint32_t e = in[2 * m];
+  if (e < (uint32_t)A.d) q[(int64_t)i * A.ld + e] = __uint_as_float(in[2 * m + 1]);
+}
+
+// after k_wire_zero; the mask is the bitmap of the last step (the draw a receiver repeats
+// from the shared seed).  grid n, block 1024, dynamic LDS = bitmap_words words
+__global__ __launch_bounds__(1024) void k_unpack_randk(WireArgs A, const uint32_t* msg, float* q) {
+  extern __shared__ uint32_t pre[];
+  __shared__ uint32_t sh_wave[16];
+  const int i = blockIdx.x;
+  bitmap_prefix(A, i, pre, sh_wave);
+  const uint32_t* bm = A.bitmap + (int64_t)i * A.bitmap_words;
+  const uint32_t* in = msg + (int64_t)i * A.words;
+  for (int64_t w = threadIdx.x; w < A.bitmap_words; w += 1024) {
+    uint32_t bits = bm[w];
+    uint32_t rank = pre[w];
+    while (bits) {
+      const int j = __ffs((int)bits) - 1;
+      bits &= bits - 1;
+      q[(int64_t)i * A.ld + 32 * w + j] = __uint_as_float(in[rank++]);
+    }
+  }
+}
+
+}  // namespace choco

@@ -158,3 +158,15 @@ def test_layered_workspace_needs_no_candidate_lists():
     start, length, k = synth.layer_table([25000] * 4, fraction=0.01)
     c2, keep2 = cfg(d=100000, layers=(start, length, k))
     assert B.workspace_bytes(c2) < flat
+
+
+def test_paper_message_bits_is_host_arithmetic():
+    # Appendix C: d + 32 (sign), 2*32*k (top_a), 32*k (random_a), b bits per entry (gsgd_b)
+    assert B.paper_message_bits(B.Q_SIGN, 272474) == 272474 + 32
+    assert B.paper_message_bits(B.Q_TOPK, 272474, k=2724) == 64 * 2724
+    assert B.paper_message_bits(B.Q_RANDK, 272474, k=2724) == 32 * 2724
+    assert B.paper_message_bits(B.Q_QSGD, 1000, levels=128) == 8 * 1000 + 32
+    assert B.paper_message_bits(B.Q_IDENTITY, 1000) == 32000
+    out = ctypes.c_int64()
+    assert B.lib().choco_paper_message_bits(B.Q_TOPK, 100, 0, 1, ctypes.byref(out)) == B.E_INVAL
+    assert B.lib().choco_paper_message_bits(9, 100, 1, 1, ctypes.byref(out)) == B.E_INVAL

@@ -1,0 +1,107 @@
+"""GPU parity of the message encoder / decoder (Appendix C: the size stated with each
+operator) against the oracle's: the packed words of every worker's message of a gossip step
+and the q a receiver decodes from them."""
+import numpy as np
+import pytest
+
+from oracle import choco_ref as ref
+from paper_1907_09356_amd import binding, synth
+from tests.parity_util import Pair
+
+pytestmark = pytest.mark.gpu
+
+OPERATORS = [
+    ("topk", dict(compressor=binding.Q_TOPK, k=123)),
+    ("randk", dict(compressor=binding.Q_RANDK, k=123)),
+    ("randk_rescaled", dict(compressor=binding.Q_RANDK, k=123, randk_rescale=1)),
+    ("sign", dict(compressor=binding.Q_SIGN)),
+    ("qsgd16", dict(compressor=binding.Q_QSGD, levels=16)),
+    ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
+    ("qsgd3", dict(compressor=binding.Q_QSGD, levels=3)),
+]
+
+
+def oracle_messages(pair, q, t):
+    """Messages and dense q of all workers for the compress half about to run on the oracle."""
+    v = pair.ref.X - pair.ref.Xhat          # line 3 of Algorithm 1, fp32 like both sides
+    msgs, dense = [], []
+    for i in range(pair.n):
+        dq, m = ref.pack_message(q["compressor"], v[i], k=q.get("k", 1), levels=q.get("levels", 1),
+                                 qsgd_biased=q.get("qsgd_biased", 1), randk_rescale=q.get("randk_rescale", 0),
+                                 seed=pair.ref.seed, t=t, worker=i)
+        msgs.append(m)
+        dense.append(dq)
+    return np.stack(msgs), np.stack(dense)
+
+
+def sorted_pairs(words):
+    pairs = words.reshape(words.shape[0], -1, 2)
+    order = np.argsort(pairs[:, :, 0], axis=1, kind="stable")
+    return np.take_along_axis(pairs, order[:, :, None], axis=1)
+
+
+@pytest.mark.parametrize("d", [1000, 4133])
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_messages_match_the_oracle(name, q, d):
+    n = 5
+    X0 = synth.normal_state(n, d, seed=31)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, **q)
+    grads = synth.GradientStream(n, d, seed=6, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        pair.sgd_step(grads.next(), 0.1)
+        want_msgs, want_q = oracle_messages(pair, q, t)
+        det = pair.gossip_step()
+        pair.check(det, tag="%s step %d" % (name, t))
+        msgs = pair.gpu.pack_messages()
+        assert msgs.shape[1] * 32 >= binding.paper_message_bits(q["compressor"], d, q.get("k", 1), q.get("levels", 1)) - 32
+        got = msgs.cpu().numpy().view(np.uint32)
+        if q["compressor"] == binding.Q_TOPK:
+            assert np.array_equal(sorted_pairs(got), sorted_pairs(want_msgs)), name + ": pairs differ"
+        else:
+            assert np.array_equal(got, want_msgs), name + ": message words differ"
+        dense = pair.gpu.unpack_messages(msgs)
+        pair.gpu.sync()
+        dense = dense.cpu().numpy()
+        assert np.array_equal(dense[:, :d], want_q), name + ": decoded q differs"
+        assert not dense[:, d:].any()
+    pair.close()
+
+
+def test_level_s_goes_through_the_index_slots():
+    # one entry of every worker holds almost the whole norm
+    n, d, s = 3, 500, 4
+    X0 = np.full((n, d), 1e-4, dtype=np.float32)
+    X0[np.arange(n), [7, 250, 499]] = [5.0, -4.0, 3.0]
+    q = dict(compressor=binding.Q_QSGD, levels=s)
+    pair = Pair(X0, synth.ring_csr(n), 0.1, seed=2, **q)
+    hits = 0
+    for t in range(6):
+        want_msgs, want_q = oracle_messages(pair, q, t)
+        det = pair.gossip_step()
+        hits += int((np.abs(det["codes"]) == s).sum())
+        msgs = pair.gpu.pack_messages()
+        assert np.array_equal(msgs.cpu().numpy().view(np.uint32), want_msgs)
+        dense = pair.gpu.unpack_messages(msgs)
+        pair.gpu.sync()
+        assert np.array_equal(dense.cpu().numpy()[:, :d], want_q)
+    assert hits > 0
+    pair.close()
+
+
+def test_message_calls_say_what_they_do_not_cover():
+    n, d = 4, 600
+    X0 = synth.normal_state(n, d, seed=1)
+    import torch
+    X = torch.from_numpy(np.pad(X0, ((0, 0), (0, 0)))).cuda().contiguous()
+    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_SIGN)
+    g.gossip_step()
+    with pytest.raises(binding.ChocoError) as err:      # no capture buffer: the codes are gone
+        g.pack_messages()
+    assert err.value.code == binding.E_INVAL
+    g.close()
+    layers = synth.layer_table([200, 400], fraction=0.1)
+    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_TOPK, layers=layers)
+    with pytest.raises(binding.ChocoError) as err:
+        g.message_bytes()
+    assert err.value.code == binding.E_UNSUPPORTED
+    g.close()
