@@ -266,6 +266,39 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
     return out
 
 
+def wire_bench(w, reps=20):
+    """Time of encoding and decoding the messages of one gossip step (not part of `value`)."""
+    import torch
+    from paper_1907_09356_amd import binding as B
+    X, pool = device_inputs(w, torch)
+    kw = comp_kwargs(w, B)
+    ctx = B.Choco(X, w["d"], *make_topology(w), w["gamma"], seed=7, **kw)
+    if w["comp"] in ("sign", "qsgd"):
+        codes = torch.zeros_like(X, dtype=torch.int32)
+        ctx.set_capture(codes)
+    for t in range(3):
+        ctx.step(pool[t & 1], w["lr"])
+    msgs = ctx.pack_messages()
+    ctx.unpack_messages(msgs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        msgs = ctx.pack_messages()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        ctx.unpack_messages(msgs)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    out = dict(message_bytes_per_worker=ctx.message_bytes(),
+               paper_bits_per_message=B.paper_message_bits(kw["compressor"], w["d"], kw.get("k", 1),
+                                                           kw.get("levels", 1)),
+               dense_bytes_per_worker=4 * w["d"],
+               pack_us=1e6 * (t1 - t0) / reps, unpack_us=1e6 * (t2 - t1) / reps)
+    ctx.close()
+    return out
+
+
 def step_bytes_per_elem(w, kernels):
     """Algorithmic bytes of one whole step per (worker, coordinate)."""
     total = 0.0
@@ -415,6 +448,9 @@ def main():
                              steps_per_s=r["steps_per_s"], step_alg_bytes_per_elem=b,
                              step_alg_GBps=b * elems * r["steps_per_s"] / 1e9))
         line["alternatives"] = alts
+        # encoder / decoder of the messages (Appendix C sizes) for the shapes they cover
+        line["wire"] = [dict(name=name, **wire_bench(WORKLOADS[name]))
+                        for name in ("dc_sign", "large_qsgd", "p2p_ring_topk", "p2p_ring_randk", "large_topk")]
         others = []
         for name, ow in WORKLOADS.items():
             if name == args.workload:

@@ -1072,8 +1072,11 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
   const uint32_t* msg = (const uint32_t*)msgs_dev;
   const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
   const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
-  // every entry of q is written: pad columns and entries not sent are zero
-  LAUNCH(ctx, KID_WIRE, k_wire_zero, dim3((unsigned)((Wa.ld + 1023) / 1024), (unsigned)Wa.n), dim3(256), 0, q_dev, Wa.ld);
+  // every entry of q is written: pad columns and entries not sent are zero (the dense decoders
+  // write whole 4-vectors up to d themselves, so they need the fill only for a wider ld)
+  if (ctx->sparse || Wa.ld > ((int64_t)Wa.d + 3) / 4 * 4)
+    LAUNCH(ctx, KID_WIRE, k_wire_zero, dim3((unsigned)((Wa.ld + 1023) / 1024), (unsigned)Wa.n), dim3(256), 0, q_dev,
+           Wa.ld);
   switch (ctx->cfg.compressor) {
     case CHOCO_Q_SIGN: LAUNCH(ctx, KID_WIRE, k_unpack_sign, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
     case CHOCO_Q_QSGD: LAUNCH(ctx, KID_WIRE, k_unpack_gsgd, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
