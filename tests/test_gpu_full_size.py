@@ -11,16 +11,20 @@ from tests.parity_util import Pair
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-def run(n, d, topo, steps, gamma, lr, bias_std, **kw):
+def run(n, d, topo, steps, gamma, lr, bias_std, fused=True, layers=None, **kw):
+    """fused=True drives choco_step, the call bench.py times; False the two separate calls."""
     X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
-    pair = Pair(X0, topo, gamma, seed=7, **kw)
+    pair = Pair(X0, topo, gamma, seed=7, layers=layers, **kw)
     grads = synth.GradientStream(n, d, seed=11, noise_std=0.01, bias_std=bias_std)
     try:
         for t in range(steps):
-            pair.sgd_step(grads.next(), lr)
-            det = pair.gossip_step()
+            if fused:
+                det = pair.step(grads.next(), lr)
+            else:
+                pair.sgd_step(grads.next(), lr)
+                det = pair.gossip_step()
             pair.check(det, tag="full size step %d" % t)
-        return pair.gpu.last_scalars()
+        return pair.gpu.last_scalars() if layers is None else pair.gpu.layer_scalars()
     finally:
         pair.close()
 
@@ -43,5 +47,54 @@ def test_peer_to_peer_shape(comp, topo):
     run(64, 270_000, csr, 4, 0.02, 0.1, 0.001, compressor=comp, k=2700)
 
 
-def test_datacenter_shape_sign():
-    run(8, 270_000, synth.ring_csr(8), 10, 0.4, 0.1, 0.001, compressor=B.Q_SIGN)
+@pytest.mark.parametrize("fused", [True, False])
+def test_datacenter_shape_sign(fused):
+    run(8, 270_000, synth.ring_csr(8), 10, 0.4, 0.1, 0.001, fused=fused, compressor=B.Q_SIGN)
+
+
+def test_large_model_shape_topk_separate_calls():
+    run(8, 28_000_000, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, fused=False, compressor=B.Q_TOPK, k=28_000)
+
+
+@pytest.mark.parametrize("n,comp", [(8, B.Q_SIGN), (64, B.Q_SIGN), (64, B.Q_TOPK), (64, B.Q_RANDK)])
+def test_layer_wise_shapes(n, comp):
+    # the 65 layers of the 0.27 M-parameter model (d = 272,474), 1 % of every layer
+    layers = synth.layer_table(synth.resnet20_like_lengths(), fraction=0.01)
+    d = synth.layers_dim(layers)
+    scal = run(n, d, synth.ring_csr(n), 3, 0.4 if comp == B.Q_SIGN else 0.02, 0.1, 0.001, layers=layers,
+               compressor=comp)
+    if comp == B.Q_RANDK:
+        big = layers[1] > 10240
+        assert np.all(scal[:, big, 3] == 1)     # the bracket around the expected order statistic held
+
+
+@pytest.mark.parametrize("n,kw", [(8, dict(compressor=B.Q_SIGN)), (64, dict(compressor=B.Q_TOPK, k=2700)),
+                                  (64, dict(compressor=B.Q_RANDK, k=2700))])
+def test_messages_at_full_size(n, kw):
+    from oracle import choco_ref as ref
+    d = 270_000
+    X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
+    pair = Pair(X0, synth.ring_csr(n), 0.1, seed=7, **kw)
+    grads = synth.GradientStream(n, d, seed=11, noise_std=0.01, bias_std=0.001)
+    try:
+        for t in range(2):
+            pair.sgd_step(grads.next(), 0.1)
+            v = pair.ref.X - pair.ref.Xhat
+            det = pair.gossip_step()
+            pair.check(det, tag="step %d" % t)
+            msgs = pair.gpu.pack_messages()
+            dense = pair.gpu.unpack_messages(msgs)
+            pair.gpu.sync()
+            got = msgs.cpu().numpy().view(np.uint32)
+            dense = dense.cpu().numpy()
+            for i in range(0, n, max(1, n // 8)):      # every worker at n = 8, a sample of 8 at n = 64
+                q, want = ref.pack_message(kw["compressor"], v[i], k=kw.get("k", 1), seed=7, t=t, worker=i)
+                if kw["compressor"] == B.Q_TOPK:
+                    a = got[i].reshape(-1, 2)
+                    a = a[np.argsort(a[:, 0], kind="stable")]
+                    assert np.array_equal(a.reshape(-1), want)
+                else:
+                    assert np.array_equal(got[i], want)
+                assert np.array_equal(dense[i, :d], q)
+    finally:
+        pair.close()
