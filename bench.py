@@ -10,7 +10,9 @@ timed region.  Prints ONE JSON line.
 
 The headline workload is the large-model shape (n = 8 ring, d = 28,000,000, top-k 0.1 %),
 the largest single-GPU configuration and the one where the HBM roofline is meaningful;
---all adds short runs of the other shapes under "other_workloads".
+--all adds the same workload in the other supported formulations ("alternatives"), short
+runs of the other shapes, the layer-wise ones among them ("other_workloads"), and the time
+of the message encoder and decoder ("wire").
 """
 import argparse
 import json
@@ -112,8 +114,8 @@ KERNEL_BYTES_PER_ELEM = {
 # counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("large_topk", "k_sel_compact_sgd"): 3_588_852_531,
-    ("large_topk", "k_mix_incremental"): 3_584_030_720,
+    ("large_topk", "k_sel_compact_sgd"): 3_588_776_650,
+    ("large_topk", "k_mix_incremental"): 3_583_975_425,
 }
 
 
