@@ -84,7 +84,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
                                            const LayerShared sh) {
   constexpr bool DENSE = (COMP == Q_SIGN || COMP == Q_QSGD);
   constexpr int NW = THREADS / 64;
-  constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together
+  constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together (5 spills)
   constexpr int kBatches = (kLayerVecs + kBatch - 1) / kBatch;
   constexpr uint32_t CAP = 2 * THREADS;
   const int nvec = (L.len + 3) >> 2;
@@ -156,15 +156,30 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     // ---- norm tree of the layer ----
     constexpr int STAT = DENSE ? COMP : Q_SIGN;
     const int nchunks = (L.len + kChunk - 1) / kChunk;
+    // xhat is read again for the final xhat += q (keeping it beside v and the loads in flight
+    // above would not fit the registers of a 1024-thread block); asked for here, out of the
+    // cache, so that it arrives while the norm tree is being summed
+    vf4 h[kLayerVecs];
+#pragma unroll
+    for (int it = 0; it < kLayerVecs; ++it) {
+      const int m = it * THREADS + tid;
+      if (it < nit && m < nvec) h[it] = load4<false>(Xhat + row + 4 * (int64_t)m);
+    }
+    // the wave's chunks side by side: the butterflies of different chunks are independent,
+    // so each exchange step is issued for all of them before the next one is needed
+    double ct[kLayerVecs];
+#pragma unroll
+    for (int it = 0; it < kLayerVecs; ++it) ct[it] = lane_terms<STAT>(v[it], 4 * (it * THREADS + tid), L.len);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+      for (int it = 0; it < kLayerVecs; ++it)
+        if (it < nit) ct[it] = ct[it] + __shfl_xor(ct[it], off, 64);
+    }
 #pragma unroll
     for (int it = 0; it < kLayerVecs; ++it) {
       const int chunk = it * NW + wave;
-      if (chunk < nchunks) {                       // uniform over the wave
-        const int m = it * THREADS + tid;
-        double t = lane_terms<STAT>(v[it], 4 * m, L.len);
-        t = wave_tree_sum(t);
-        if (lane == 0) sh.chunk[chunk] = t;
-      }
+      if (chunk < nchunks && lane == 0) sh.chunk[chunk] = ct[it];
     }
     layer_sync<THREADS>();
     // levels 2 and 3, done by every wave for itself: groups of 16 chunk sums (four groups
@@ -203,38 +218,25 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
       scal[2] = COMP == Q_SIGN ? 0.0 : (double)sc.r;
       scal[3] = COMP == Q_SIGN ? 0.0 : (double)sc.step;
     }
-    // ---- codes and xhat += q (xhat is read again: it is still in cache, and keeping it
-    // beside v would not fit the registers of a 1024-thread block) ----
+    // ---- codes and xhat += q ----
 #pragma unroll
-    for (int b = 0; b < kBatches; ++b) {
-      vf4 h[kBatch];
+    for (int it = 0; it < kLayerVecs; ++it) {
+      const int m = it * THREADS + tid;
+      if (it < nit && m < nvec) {
+        uint4 wd = make_uint4(0u, 0u, 0u, 0u);
+        if (COMP == Q_QSGD) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_DITHER);
+        vi4 code = vi4{0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        const int m = (b * kBatch + j) * THREADS + tid;
-        if (b * kBatch + j < kLayerVecs && b * kBatch < nit && m < nvec)
-          h[j] = load4<false>(Xhat + row + 4 * (int64_t)m);
-      }
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        const int it = b * kBatch + j;
-        if (it >= kLayerVecs) continue;
-        const int m = it * THREADS + tid;
-        if (b * kBatch < nit && m < nvec) {
-          uint4 wd = make_uint4(0u, 0u, 0u, 0u);
-          if (COMP == Q_QSGD) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_DITHER);
-          vi4 code = vi4{0, 0, 0, 0};
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (4 * m + c < L.len) {
-              int32_t cd;
-              const float qv = encode<STAT>(v[it][c], sc, pick(wd, c), cd);
-              h[j][c] = h[j][c] + qv;
-              code[c] = cd;
-            }
-          const int64_t o = row + 4 * (int64_t)m;
-          store4<NT>(Xhat + o, h[j]);
-          if (A.codes) *reinterpret_cast<vi4*>(A.codes + o) = code;
-        }
+        for (int c = 0; c < 4; ++c)
+          if (4 * m + c < L.len) {
+            int32_t cd;
+            const float qv = encode<STAT>(v[it][c], sc, pick(wd, c), cd);
+            h[it][c] = h[it][c] + qv;
+            code[c] = cd;
+          }
+        const int64_t o = row + 4 * (int64_t)m;
+        store4<NT>(Xhat + o, h[it]);
+        if (A.codes) *reinterpret_cast<vi4*>(A.codes + o) = code;
       }
     }
   } else {
