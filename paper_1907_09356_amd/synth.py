@@ -181,3 +181,40 @@ class GradientStream:
     def next(self):
         g = self.rng.standard_normal((self.n, self.d)) * self.noise_std + self.bias
         return np.ascontiguousarray(g, dtype=self.dtype)
+
+
+class LogisticProblem:
+    """Synthetic L2-regularised logistic regression split over n workers: per worker
+    `samples` feature rows ~ N(0, 1) scaled to unit norm, labels +-1 from a planted w* with a
+    fraction `flip` of them flipped.  gradient(X, t) draws a fresh minibatch per worker and
+    step (seeded by (seed, t, worker)) and returns the stochastic gradients at the rows of X,
+    the regulariser lam * x included.  This is the objective's arithmetic, an INPUT of the
+    path under test (it plays the role of the model's backward pass)."""
+
+    def __init__(self, n, d, samples=1000, seed=0, flip=0.05, lam=1e-4, batch=32):
+        rng = np.random.default_rng(seed)
+        self.n, self.d, self.samples, self.seed, self.lam, self.batch = n, d, samples, seed, lam, batch
+        A = rng.standard_normal((n, samples, d))
+        A /= np.linalg.norm(A, axis=2, keepdims=True)
+        w_star = rng.standard_normal(d)
+        y = np.sign(A @ w_star)
+        y[y == 0] = 1.0
+        y[rng.random((n, samples)) < flip] *= -1.0
+        self.A, self.y = A, y
+
+    def gradient(self, X, t):
+        X = np.asarray(X, dtype=np.float64)
+        G = np.empty_like(X)
+        for i in range(self.n):
+            idx = np.random.default_rng([self.seed, t, i]).integers(0, self.samples, size=self.batch)
+            a, y = self.A[i, idx], self.y[i, idx]
+            margin = y * (a @ X[i])
+            coef = -y / (1.0 + np.exp(margin))
+            G[i] = (coef[:, None] * a).mean(0) + self.lam * X[i]
+        return np.ascontiguousarray(G, dtype=np.float32)
+
+    def loss(self, x):
+        """Full objective at one point x (every worker's data)."""
+        x = np.asarray(x, dtype=np.float64)
+        margin = self.y * (self.A @ x)
+        return float(np.logaddexp(0.0, -margin).mean() + 0.5 * self.lam * (x @ x))

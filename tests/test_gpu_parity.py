@@ -408,3 +408,31 @@ def test_long_run_choco_sgd_sign_1000_steps():
         assert abs(g["mean_norm"] - r["mean_norm"]) <= 1e-4 * r["mean_norm"]
     finally:
         pair.close()
+
+
+def test_logistic_regression_workload_2000_steps():
+    # CHOCO-SGD on synthetic L2-regularised logistic regression: 9 workers on a 3 x 3 torus
+    # (weights 1/5), d = 2000, 1000 samples per worker, minibatch 32, scaled sign,
+    # lr = 0.1 / (1 + t / 100), 2000 fused iterations.  The gradients are taken at the
+    # oracle's iterates; as long as the two sides agree bit for bit (checked on the way)
+    # they are the GPU's iterates too.
+    n, d = 9, 2000
+    prob = synth.LogisticProblem(n, d, samples=1000, seed=5, lam=1e-4, batch=32)
+    X0 = np.zeros((n, d), dtype=np.float32)
+    pair = Pair(X0, synth.torus_csr(3, 3), 0.1, compressor=B.Q_SIGN)
+    loss0 = prob.loss(X0.mean(0))
+    try:
+        for t in range(2000):
+            G = prob.gradient(pair.ref.X, t)
+            det = pair.step(G, 0.1 / (1.0 + t / 100.0))
+            if t % 250 == 249 or t < 3:
+                pair.check(det, tag="logistic step %d" % t)
+        g, r = pair.gpu.metrics(), pair.ref.metrics()
+        assert abs(g["consensus"] - r["consensus"]) <= 1e-4 * r["consensus"]
+        assert abs(g["mean_norm"] - r["mean_norm"]) <= 1e-4 * r["mean_norm"]
+        X, _, _ = pair.gpu_state()
+        assert prob.loss(X.mean(0)) < loss0 - 0.002        # it did learn (unit-norm features, decaying lr: slowly)
+        spread = np.linalg.norm(X - X.mean(0), axis=1).max()
+        assert spread < 0.2 * np.linalg.norm(X.mean(0))    # and the workers agree
+    finally:
+        pair.close()
