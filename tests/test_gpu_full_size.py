@@ -98,3 +98,28 @@ def test_messages_at_full_size(n, kw):
                 assert np.array_equal(dense[i, :d], q)
     finally:
         pair.close()
+
+
+def long_run(n, d, topo, steps, gamma, lr, **kw):
+    """Free-running fused iterations at full size; the long-run statistics to 1e-4 and (the
+    two sides never having parted) the final state bit for bit."""
+    X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
+    pair = Pair(X0, topo, gamma, seed=7, **kw)
+    grads = synth.GradientStream(n, d, seed=11, noise_std=0.01, bias_std=0.001)
+    try:
+        for t in range(steps):
+            det = pair.step(grads.next(), lr)
+        pair.check(det, tag="after %d steps" % steps)
+        g, r = pair.gpu.metrics(), pair.ref.metrics()
+        assert abs(g["consensus"] - r["consensus"]) <= 1e-4 * r["consensus"]
+        assert abs(g["mean_norm"] - r["mean_norm"]) <= 1e-4 * r["mean_norm"]
+    finally:
+        pair.close()
+
+
+def test_datacenter_shape_sign_1000_steps():
+    long_run(8, 270_000, synth.ring_csr(8), 1000, 0.4, 0.1, compressor=B.Q_SIGN)
+
+
+def test_peer_to_peer_ring_topk_100_steps():
+    long_run(64, 270_000, synth.ring_csr(64), 100, 0.02, 0.1, compressor=B.Q_TOPK, k=2700)
