@@ -16,7 +16,8 @@
  *   - device buffers are owned by the caller (allocated e.g. with torch); the
  *     library allocates no device memory, it only carves up the workspace;
  *   - work is enqueued on the caller's stream and the calls return without
- *     synchronising, except choco_metrics, choco_last_scalars and choco_sync;
+ *     synchronising, except choco_metrics, choco_last_scalars, choco_layer_scalars,
+ *     choco_profile_report, choco_sync and (for QSGD) choco_pack_messages;
  *   - inputs must be finite; NaN/Inf give unspecified selections.
  */
 #ifndef CHOCO_H
@@ -224,7 +225,10 @@ int choco_set_profiling(choco_ctx *ctx, int enable);
 int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
 
 int choco_sync(choco_ctx *ctx);    /* hipStreamSynchronize on the context's stream */
-int choco_destroy(choco_ctx *ctx); /* frees host memory only; NULL is allowed      */
+/* Frees the context (host memory and its profiling events) without waiting for the stream:
+   call choco_sync first if X or the workspace are to be freed or reused right away.  The
+   handle is invalid afterwards.  NULL is allowed. */
+int choco_destroy(choco_ctx *ctx);
 const char *choco_strerror(int code);
 int choco_last_hip_error(choco_ctx *ctx); /* raw hipError_t of the last CHOCO_E_HIP */
 

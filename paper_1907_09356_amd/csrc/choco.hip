@@ -41,7 +41,6 @@ struct choco_ctx {
   double* metrics_out;
   int metrics_blocks;
   int last_hip_error;
-  bool destroyed;
   // optional per-kernel timing with HIP events on the context's stream
   bool profiling;
   std::vector<hipEvent_t> ev_begin, ev_end;
@@ -761,7 +760,6 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->nt = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float) >= ((size_t)4 << 20);
   ctx->t = 0;
   ctx->last_hip_error = 0;
-  ctx->destroyed = false;
   ctx->profiling = false;
   ctx->fused = false;
   ctx->ev_used = 0;
@@ -914,17 +912,17 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
 }
 
 int choco_gossip_step(choco_ctx* ctx) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   return run_gossip(ctx, LocalUpdate());
 }
 
 int choco_sgd_step(choco_ctx* ctx, const float* g_dev, float lr) {
-  if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
+  if (!ctx || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
   return launch_sgd(ctx, g_dev, lr);
 }
 
 int choco_step(choco_ctx* ctx, const float* g_dev, float lr) {
-  if (!ctx || ctx->destroyed || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
+  if (!ctx || !g_dev || ((uintptr_t)g_dev & 15u) != 0) return CHOCO_E_INVAL;
   LocalUpdate u;
   u.g = g_dev;
   u.lr = lr;
@@ -933,14 +931,14 @@ int choco_step(choco_ctx* ctx, const float* g_dev, float lr) {
 
 int choco_momentum_step(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta,
                         float lambda) {
-  if (!ctx || ctx->destroyed || !g_dev || !m_dev) return CHOCO_E_INVAL;
+  if (!ctx || !g_dev || !m_dev) return CHOCO_E_INVAL;
   if (((uintptr_t)g_dev & 15u) != 0 || ((uintptr_t)m_dev & 15u) != 0) return CHOCO_E_INVAL;
   return launch_momentum(ctx, g_dev, m_dev, lr, beta, lambda);
 }
 
 int choco_step_momentum(choco_ctx* ctx, const float* g_dev, float* m_dev, float lr, float beta,
                         float lambda) {
-  if (!ctx || ctx->destroyed || !g_dev || !m_dev) return CHOCO_E_INVAL;
+  if (!ctx || !g_dev || !m_dev) return CHOCO_E_INVAL;
   if (((uintptr_t)g_dev & 15u) != 0 || ((uintptr_t)m_dev & 15u) != 0) return CHOCO_E_INVAL;
   LocalUpdate u;
   u.g = g_dev;
@@ -952,7 +950,7 @@ int choco_step_momentum(choco_ctx* ctx, const float* g_dev, float* m_dev, float 
 }
 
 int choco_metrics(choco_ctx* ctx, double* consensus_host, double* mean_norm_host, double* psi_host) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   const Args& A = ctx->args;
   int blocks = (A.d + 255) / 256;
   if (blocks > ctx->metrics_blocks) blocks = ctx->metrics_blocks;
@@ -971,19 +969,19 @@ int choco_metrics(choco_ctx* ctx, double* consensus_host, double* mean_norm_host
 }
 
 int choco_xhat(choco_ctx* ctx, float** xhat_dev) {
-  if (!ctx || ctx->destroyed || !xhat_dev) return CHOCO_E_INVAL;
+  if (!ctx || !xhat_dev) return CHOCO_E_INVAL;
   *xhat_dev = ctx->args.Xhat;
   return CHOCO_OK;
 }
 
 int choco_nsum(choco_ctx* ctx, float** s_dev) {
-  if (!ctx || ctx->destroyed || !s_dev) return CHOCO_E_INVAL;
+  if (!ctx || !s_dev) return CHOCO_E_INVAL;
   *s_dev = ctx->args.S;
   return CHOCO_OK;
 }
 
 int choco_last_selection(choco_ctx* ctx, int32_t* idx_dev, float* val_dev) {
-  if (!ctx || ctx->destroyed || !ctx->sparse) return CHOCO_E_INVAL;
+  if (!ctx || !ctx->sparse) return CHOCO_E_INVAL;
   const Args& A = ctx->args;
   const size_t count = (size_t)A.n * (size_t)A.k;
   if (idx_dev)
@@ -1017,7 +1015,7 @@ int choco_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t l
 }
 
 int choco_message_bytes(choco_ctx* ctx, size_t* bytes_host) {
-  if (!ctx || ctx->destroyed || !bytes_host) return CHOCO_E_INVAL;
+  if (!ctx || !bytes_host) return CHOCO_E_INVAL;
   const int rc = wire_supported(ctx);
   if (rc != CHOCO_OK) return rc;
   *bytes_host = (size_t)message_words(ctx->cfg.compressor, ctx->args.d, ctx->args.k, ctx->cfg.levels) * 4;
@@ -1025,7 +1023,7 @@ int choco_message_bytes(choco_ctx* ctx, size_t* bytes_host) {
 }
 
 int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
-  if (!ctx || ctx->destroyed || !msgs_dev || ((uintptr_t)msgs_dev & 3u) != 0) return CHOCO_E_INVAL;
+  if (!ctx || !msgs_dev || ((uintptr_t)msgs_dev & 3u) != 0) return CHOCO_E_INVAL;
   int rc = wire_supported(ctx);
   if (rc != CHOCO_OK) return rc;
   const WireArgs Wa = wire_args(ctx);
@@ -1064,7 +1062,7 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
 }
 
 int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
-  if (!ctx || ctx->destroyed || !msgs_dev || !q_dev) return CHOCO_E_INVAL;
+  if (!ctx || !msgs_dev || !q_dev) return CHOCO_E_INVAL;
   if (((uintptr_t)msgs_dev & 3u) != 0 || ((uintptr_t)q_dev & 15u) != 0) return CHOCO_E_INVAL;
   const int rc = wire_supported(ctx);
   if (rc != CHOCO_OK) return rc;
@@ -1092,7 +1090,7 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
 }
 
 int choco_set_capture(choco_ctx* ctx, int32_t* codes_dev) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   if (ctx->cfg.compressor != CHOCO_Q_SIGN && ctx->cfg.compressor != CHOCO_Q_QSGD) return CHOCO_E_INVAL;
   if (((uintptr_t)codes_dev & 15u) != 0) return CHOCO_E_INVAL;
   ctx->args.codes = codes_dev;
@@ -1100,7 +1098,7 @@ int choco_set_capture(choco_ctx* ctx, int32_t* codes_dev) {
 }
 
 int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
-  if (!ctx || ctx->destroyed || !scalars_host || ctx->nlayers == 0) return CHOCO_E_INVAL;
+  if (!ctx || !scalars_host || ctx->nlayers == 0) return CHOCO_E_INVAL;
   const Args& A = ctx->args;
   HIP_TRY(ctx, hipMemcpyAsync(scalars_host, A.layer_scal, (size_t)A.n * (size_t)A.nlayers * 4 * sizeof(double),
                               hipMemcpyDeviceToHost, ctx->stream));
@@ -1109,7 +1107,7 @@ int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
 }
 
 int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
-  if (!ctx || ctx->destroyed || !scalars_host) return CHOCO_E_INVAL;
+  if (!ctx || !scalars_host) return CHOCO_E_INVAL;
   if (ctx->nlayers > 0) return CHOCO_E_UNSUPPORTED;
   const Args& A = ctx->args;
   std::vector<WorkerCtl> ctl((size_t)A.n);
@@ -1139,32 +1137,32 @@ int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
 }
 
 int choco_get_step(choco_ctx* ctx, uint64_t* t_host) {
-  if (!ctx || ctx->destroyed || !t_host) return CHOCO_E_INVAL;
+  if (!ctx || !t_host) return CHOCO_E_INVAL;
   *t_host = ctx->t;
   return CHOCO_OK;
 }
 
 int choco_set_step(choco_ctx* ctx, uint64_t t) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   ctx->t = t;
   return CHOCO_OK;
 }
 
 int choco_sync(choco_ctx* ctx) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   return CHOCO_OK;
 }
 
 int choco_set_profiling(choco_ctx* ctx, int enable) {
-  if (!ctx || ctx->destroyed) return CHOCO_E_INVAL;
+  if (!ctx) return CHOCO_E_INVAL;
   ctx->profiling = enable != 0;
   if (enable) ctx->ev_used = 0;
   return CHOCO_OK;
 }
 
 int choco_profile_report(choco_ctx* ctx, char* buf_host, size_t buf_bytes) {
-  if (!ctx || ctx->destroyed || !buf_host || buf_bytes == 0) return CHOCO_E_INVAL;
+  if (!ctx || !buf_host || buf_bytes == 0) return CHOCO_E_INVAL;
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   double total_ms[KID_COUNT] = {0};
   long count[KID_COUNT] = {0};
@@ -1189,7 +1187,6 @@ int choco_profile_report(choco_ctx* ctx, char* buf_host, size_t buf_bytes) {
 
 int choco_destroy(choco_ctx* ctx) {
   if (!ctx) return CHOCO_OK;
-  ctx->destroyed = true;
   for (hipEvent_t e : ctx->ev_begin) (void)hipEventDestroy(e);
   for (hipEvent_t e : ctx->ev_end) (void)hipEventDestroy(e);
   delete ctx;
