@@ -107,6 +107,9 @@ KERNEL_BYTES_PER_ELEM = {
     "k_sel_compact_sgd": 16,      # read x, g, xhat; write x
     "k_tile_mix_sgd": 16,         # read x, g, xhat; write x
     "k_mix_incremental_sgd": 20,  # read x, g, s, xhat; write x
+    # layer-wise sign / gsgd: the norm pass over (layer, group) work items
+    "k_layer_stat": 8,            # read x, xhat
+    "k_layer_stat_sgd": 16,       # read x, g, xhat; write x
 }
 
 
@@ -230,9 +233,9 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
                          ms_per_step=total_ms / steps)
             bpe = KERNEL_BYTES_PER_ELEM.get(name)
             if name.startswith("k_layer_compress"):
-                # sign / gsgd: read x, xhat, write xhat; top-k: read x, xhat; random-k reads nothing;
-                # a pass that carries the local update also reads g and writes x
-                bpe = {"sign": 12, "qsgd": 12, "topk": 8, "randk": 0}[w["comp"]]
+                # top-k: read x, xhat; random-k reads nothing; a pass that carries the local update
+                # also reads g and writes x
+                bpe = {"topk": 8, "randk": 0}[w["comp"]]
                 if name.endswith("_sgd"):
                     bpe += 8
                 bpe = bpe or None

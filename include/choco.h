@@ -95,10 +95,11 @@ typedef struct {
      The layers must tile the vector in order, each start padded to a multiple of 4:
      layer_start[0] = 0, layer_start[l+1] = layer_start[l] + layer_len[l] rounded up to a
      multiple of 4, d = layer_start[nlayers-1] + layer_len[nlayers-1].  The padding entries
-     are never transmitted (keep them zero in X and G).  A layer may have at most
-     CHOCO_MAX_LAYER_LEN entries (it is compressed by one workgroup out of its registers);
-     IDENTITY, a non-default mix_form and layers beyond that length are
-     CHOCO_E_UNSUPPORTED.  layer_k_host may be NULL for SIGN and QSGD.                    */
+     are never transmitted (keep them zero in X and G).  For TOPK and RANDK a layer may
+     have at most CHOCO_MAX_LAYER_LEN entries (one workgroup selects it out of its
+     registers); SIGN and QSGD take layers of any length.  IDENTITY, a non-default
+     mix_form and longer TOPK / RANDK layers are CHOCO_E_UNSUPPORTED.  layer_k_host may be
+     NULL for SIGN and QSGD.                                                              */
   int32_t nlayers;
   const int64_t *layer_start_host;
   const int64_t *layer_len_host;

@@ -58,7 +58,9 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
-      layers, layer_work, layer_guess, layer_scal, wire, mpart, mout, total;
+      layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
+      chunk_layer, wire, mpart, mout, total;
+  int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
   bool multipart;
@@ -98,7 +100,7 @@ int check_layers(const choco_config* c) {
     end = start + len;
     if (end > c->d) return CHOCO_E_INVAL;
     expect = (end + 3) / 4 * 4;
-    if (len > kMaxLayerLen) too_long = true;
+    if (sparse && len > kMaxLayerLen) too_long = true;   // selected out of one workgroup's registers
     if (sparse) {
       const int64_t k = c->layer_k_host[l];
       if (k < 0 || k > len) return CHOCO_E_INVAL;
@@ -205,6 +207,17 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
   L.layer_scal = take((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
+  // sign / gsgd layer by layer: work items of the norm pass (groups of 16 chunks of one layer)
+  const bool dense_layers = layered && dense_stat;
+  int64_t items = 0;
+  if (dense_layers)
+    for (int32_t l = 0; l < c.nlayers; ++l) items += (c.layer_len_host[l] + kGroup * kChunk - 1) / (kGroup * kChunk);
+  L.ngroup_items = (int32_t)items;
+  L.layer_groups = take((size_t)items * sizeof(LayerGroup));
+  L.layer_group_first = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int32_t) : 0);
+  L.layer_group_sums = take((size_t)c.n * (size_t)items * sizeof(double));
+  L.layer_scale = take(dense_layers ? (size_t)c.n * (size_t)c.nlayers * sizeof(LayerScale) : 0);
+  L.chunk_layer = take(dense_layers ? (size_t)L.nchunks * sizeof(int32_t) : 0);
   L.wire = take((size_t)c.n * (2 + kOverflowSlots) * sizeof(uint32_t));   // message encoder: counters, index slots, status
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
@@ -266,14 +279,14 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_WIRE, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
   "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
-  "k_layer_compress", "k_layer_compress_sgd", "k_wire"};
+  "k_layer_compress", "k_layer_compress_sgd", "k_layer_stat", "k_layer_stat_sgd", "k_layer_finalise", "k_wire"};
 constexpr size_t kMaxProfiledLaunches = 16384;
 
 // Brackets one launch with two events when profiling is on (no-op otherwise).
@@ -335,11 +348,12 @@ int pick_rpw(int n) {
     }                                                  \
   }
 
-template <int COMP, bool CAPTURE, bool NT>
+template <int COMP, bool CAPTURE, bool NT, bool LAYERED = false>
 void launch_apply_mix(choco_ctx* ctx, const Args& A) {
   const dim3 grid((unsigned)A.nchunks), block(A.n <= 16 ? 256 : 1024);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
-#define CALL(R, W) LAUNCH(ctx, KID_DENSE_APPLY_MIX, (k_dense_apply_mix<COMP, R, W, CAPTURE, NT>), grid, block, lds, A)
+#define CALL(R, W) \
+  LAUNCH(ctx, KID_DENSE_APPLY_MIX, (k_dense_apply_mix<COMP, R, W, CAPTURE, NT, LAYERED>), grid, block, lds, A)
   TILE_SWITCH(A.n, ctx->rpw, CALL)
 #undef CALL
 }
@@ -354,11 +368,11 @@ void launch_tile_mix(choco_ctx* ctx, const Args& A, bool fused) {
 #undef CALL
 }
 
-template <int COMP, bool NT>
+template <int COMP, bool NT, bool LAYERED = false>
 void launch_dense_apply(choco_ctx* ctx, const Args& A) {
   const dim3 grid = chunk_grid((A.d + 3) >> 2, A.n, kStreamVecs);
-  if (A.codes) LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, true, NT>), grid, dim3(256), 0, A);
-  else LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, false, NT>), grid, dim3(256), 0, A);
+  if (A.codes) LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, true, NT, LAYERED>), grid, dim3(256), 0, A);
+  else LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, false, NT, LAYERED>), grid, dim3(256), 0, A);
 }
 
 void launch_mix_direct_global(choco_ctx* ctx, const Args& A) {
@@ -487,30 +501,49 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   return CHOCO_OK;
 }
 
-// Layer-wise operators: one block per (worker, layer) does the whole compression of the
-// layer; the mix and (for top_a / random_a) the message kernels are those of the whole-row
-// path.  Dense operators use the direct mix form, sparsifying ones the neighbour sums.
+// Layer-wise sign / gsgd: the whole-row pipeline with per-layer norms (norm pass over
+// (layer, group) work items, per-layer scales, apply kernels that look the scale up by layer).
 template <int COMP, bool NT>
-int gossip_layers(choco_ctx* ctx, const Args& F) {
-  constexpr bool sparse = (COMP == Q_TOPK || COMP == Q_RANDK);
+int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
+  Args A = F;
+  A.G = nullptr;
+  const bool fused = F.G != nullptr;
+  const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
+  bool x_touched = false;
+  if (mix_first) {
+    if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, F, fused);   // carries the local update if there is one
+    else launch_mix_direct_global(ctx, A);                     // (never handed one: see first_pass_can_carry_sgd)
+    x_touched = true;
+  }
+  const Args& C = x_touched ? A : F;
+  LAUNCH(ctx, C.G ? KID_LAYER_STAT_SGD : KID_LAYER_STAT, (k_layer_stat<COMP, NT>),
+         dim3((unsigned)A.ngroup_items, (unsigned)A.n), dim3(kStatThreads), 0, C);
+  LAUNCH(ctx, KID_LAYER_FINALISE, (k_layer_finalise<COMP>), dim3((unsigned)A.nlayers, (unsigned)A.n), dim3(256), 0, A);
+  if (!mix_first && ctx->rpw) {
+    if (A.codes) launch_apply_mix<COMP, true, NT, true>(ctx, A);
+    else launch_apply_mix<COMP, false, NT, true>(ctx, A);
+  } else {
+    launch_dense_apply<COMP, NT, true>(ctx, A);
+    if (!mix_first) launch_mix_direct_global(ctx, A);
+  }
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
+// Layer-wise top_a / random_a: one workgroup or wave per (worker, layer) selects the layer's
+// kept entries; the message kernels and the mix are those of the whole-row path.
+template <int COMP, bool NT>
+int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   Args A = F;
   if (!F.deferred_sgd) A.G = nullptr;
   const bool fused = F.G != nullptr && !F.deferred_sgd;
   const int32_t nvec = (A.d + 3) >> 2;
   const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
-  auto launch_mix = [&](const Args& M, bool carries) {
-    if (sparse)
-      LAUNCH(ctx, carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
-             dim3(256), 0, M);
-    else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, M, carries);
-    else launch_mix_direct_global(ctx, M);
-  };
   bool x_touched = false;
   if (mix_first) {
-    // only a mix kernel that can carry the local update is handed F
-    const bool carries = fused && (sparse || ctx->rpw != 0);
-    launch_mix(carries ? F : A, carries);
+    LAUNCH(ctx, fused ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0,
+           fused ? F : A);
     x_touched = true;
   }
   // random_a never reads X in the layer kernel, so it cannot carry the local update
@@ -532,18 +565,17 @@ int gossip_layers(choco_ctx* ctx, const Args& F) {
       LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
              dim3(256), 0, C, (int32_t)nlarge, (int32_t)nmid);
   }
-  if (sparse) {
-    const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-    if (COMP == Q_RANDK)
-      LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
-    LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
-    LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
-  }
+  const unsigned kblocks = (unsigned)((A.k + 255) / 256);
+  if (COMP == Q_RANDK)
+    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
+  LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
     const bool last_carries = F.deferred_sgd != 0;
     Args L = A;
     if (last_carries) L.G = F.G;
-    launch_mix(L, last_carries);
+    LAUNCH(ctx, last_carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
+           dim3(256), 0, L);
   }
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;
@@ -553,10 +585,10 @@ template <bool NT>
 int gossip_any(choco_ctx* ctx, const Args& A) {
   if (ctx->nlayers > 0) {
     switch (ctx->cfg.compressor) {
-      case CHOCO_Q_SIGN: return gossip_layers<Q_SIGN, NT>(ctx, A);
-      case CHOCO_Q_QSGD: return gossip_layers<Q_QSGD, NT>(ctx, A);
-      case CHOCO_Q_TOPK: return gossip_layers<Q_TOPK, NT>(ctx, A);
-      case CHOCO_Q_RANDK: return gossip_layers<Q_RANDK, NT>(ctx, A);
+      case CHOCO_Q_SIGN: return gossip_layers_dense<Q_SIGN, NT>(ctx, A);
+      case CHOCO_Q_QSGD: return gossip_layers_dense<Q_QSGD, NT>(ctx, A);
+      case CHOCO_Q_TOPK: return gossip_layers_sparse<Q_TOPK, NT>(ctx, A);
+      case CHOCO_Q_RANDK: return gossip_layers_sparse<Q_RANDK, NT>(ctx, A);
       default: return CHOCO_E_UNSUPPORTED;
     }
   }
@@ -866,6 +898,28 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
       else if (D.len > kWaveLayerLen) ctx->nmid += 1;
     }
   }
+  std::vector<LayerGroup> groups;
+  std::vector<int32_t> group_first, chunk_layer;
+  A.layer_groups = (const LayerGroup*)(base + L.layer_groups);
+  A.layer_group_first = (const int32_t*)(base + L.layer_group_first);
+  A.ngroup_items = L.ngroup_items;
+  A.layer_group_sums = (double*)(base + L.layer_group_sums);
+  A.layer_scale = (LayerScale*)(base + L.layer_scale);
+  A.chunk_layer = (const int32_t*)(base + L.chunk_layer);
+  if (cfg->nlayers > 0 && !ctx->sparse) {
+    const int32_t span = kGroup * kChunk;
+    for (const LayerDesc& D : layers) {
+      group_first.push_back((int32_t)groups.size());
+      for (int32_t off = 0; off < D.len; off += span) groups.push_back(LayerGroup{D.start + off, D.len - off, D.id, 0});
+    }
+    group_first.push_back((int32_t)groups.size());
+    chunk_layer.resize((size_t)L.nchunks);
+    int32_t lay = 0;
+    for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+      while (lay + 1 < cfg->nlayers && layers[(size_t)lay + 1].start <= ch * kChunk) ++lay;
+      chunk_layer[(size_t)ch] = lay;
+    }
+  }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
   ctx->wire = (uint32_t*)(base + L.wire);
@@ -893,6 +947,15 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   if (e == hipSuccess && cfg->nlayers > 0)   // no threshold guesses yet
     e = hipMemsetAsync(base + L.layer_guess, 0xFF, (size_t)cfg->n * (size_t)cfg->nlayers * sizeof(uint32_t),
                        ctx->stream);
+  if (e == hipSuccess && !groups.empty())
+    e = hipMemcpyAsync(base + L.layer_groups, groups.data(), groups.size() * sizeof(LayerGroup), hipMemcpyHostToDevice,
+                       ctx->stream);
+  if (e == hipSuccess && !groups.empty())
+    e = hipMemcpyAsync(base + L.layer_group_first, group_first.data(), group_first.size() * sizeof(int32_t),
+                       hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess && !groups.empty())
+    e = hipMemcpyAsync(base + L.chunk_layer, chunk_layer.data(), chunk_layer.size() * sizeof(int32_t),
+                       hipMemcpyHostToDevice, ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {
     ctl0.resize((size_t)cfg->n);

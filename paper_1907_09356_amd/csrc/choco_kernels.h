@@ -75,6 +75,20 @@ struct LayerDesc {
   int32_t pad[3];
 };
 
+// Scales of one layer of one worker (dense operators applied layer by layer).
+struct LayerScale {
+  float c, r, step;
+  int32_t nonzero;
+};
+
+// One work item of the layer-wise norm pass: a group of up to 16 chunks of one layer.
+struct LayerGroup {
+  int32_t off;   // first entry of the group in the row (a multiple of 4)
+  int32_t rem;   // entries of the layer from there to its end
+  int32_t id;    // the layer
+  int32_t pad;
+};
+
 struct Args {
   int32_t n;
   int32_t d;
@@ -129,6 +143,12 @@ struct Args {
   int32_t nlayers;
   const LayerDesc* layer_work;  // the same by falling length: the order the layer kernel takes them in
   uint32_t* layer_guess;     // n x nlayers: top_a threshold key of the last step (all ones: none yet)
+  const LayerGroup* layer_groups;   // ngroup_items work items of the layer-wise norm pass, layer after layer
+  const int32_t* layer_group_first; // nlayers + 1: where each layer's items start
+  int32_t ngroup_items;
+  double* layer_group_sums;  // n x ngroup_items second-level norm sums
+  LayerScale* layer_scale;   // n x nlayers: scales of the last step (sign, gsgd)
+  const int32_t* chunk_layer; // per 256-entry chunk of a row: the layer that holds its first entry
   double* layer_scal;        // n x nlayers x 4: norms and scales / threshold of the last step
   int32_t qsgd_biased;
   // randomness
@@ -144,6 +164,29 @@ __device__ __forceinline__ int layer_of(const Args& A, int e) {
     else hi = mid - 1;
   }
   return lo;
+}
+
+// The same for the first entry e of a 4-vector through the per-chunk table: the layer
+// that holds the chunk's first entry, then forward (layers shorter than a chunk are rare).
+// Every 4-vector starts inside a layer; `nvalid` is how many of its entries the layer has.
+__device__ __forceinline__ int layer_of_vector(const Args& A, int e, int& nvalid) {
+  int lay = A.chunk_layer[e >> 8];
+  while (lay + 1 < A.nlayers && A.layers[lay + 1].start <= e) ++lay;
+  const LayerDesc L = A.layers[lay];
+  const int left = L.start + L.len - e;
+  nvalid = left < 4 ? left : 4;
+  return lay;
+}
+
+// Entries of a 4-vector that lie in the padding after a layer are not compressed: they
+// keep their xhat and send the code 0.
+__device__ __forceinline__ void mask_padding(int nvalid, const vf4& xh_old, vf4& xh_new, vi4& code) {
+#pragma unroll
+  for (int c = 1; c < 4; ++c)
+    if (c >= nvalid) {
+      xh_new[c] = xh_old[c];
+      code[c] = 0;
+    }
 }
 
 // random_a, unbiased version: the factor d / k of the vector entry e was compressed in
@@ -269,6 +312,9 @@ struct RowScale {
   __device__ __forceinline__ void load(const WorkerCtl* ctl) {
     if (COMP == Q_SIGN) c = ctl->scale_c;
     if (COMP == Q_QSGD) { r = ctl->scale_r; step = ctl->scale_step; nonzero = ctl->nonzero; }
+  }
+  __device__ __forceinline__ void load(const LayerScale& ls) {
+    c = ls.c; r = ls.r; step = ls.step; nonzero = ls.nonzero;
   }
 };
 
@@ -555,12 +601,16 @@ __device__ __forceinline__ void tile_mix_rows(const Args& A, const float* tile, 
   }
 }
 
-template <int COMP, int RPW, int NW, bool CAPTURE, bool NT>
+// LAYERED: the operator is applied layer by layer; the scales come per (worker, layer) from
+// the layer-wise norm pass.
+template <int COMP, int RPW, int NW, bool CAPTURE, bool NT, bool LAYERED>
 __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
+  int lay = 0, nvalid = 4;
+  if (LAYERED && valid) lay = layer_of_vector(A, e, nvalid);
   vf4 xr[RPW], xh[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
@@ -576,7 +626,9 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + NW * q;
-    if (r < A.n) {
+    if (LAYERED) {
+      if (r < A.n && valid) sc[q].load(A.layer_scale[(int64_t)r * A.nlayers + lay]);
+    } else if (r < A.n) {
       if ((COMP == Q_SIGN || COMP == Q_QSGD) && A.fold_finalise) {
         const double total = wave_level3(A, r, lane);
         scales_from_total<COMP>(A, total, sc[q], (blockIdx.x == 0 && lane == 0) ? A.ctl + r : nullptr);
@@ -596,6 +648,7 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
         if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
         vi4 code;
         nh = absorb<COMP>(xr[q], xh[q], sc[q], words, code);
+        if (LAYERED) mask_padding(nvalid, xh[q], nh, code);
         store4<NT>(A.Xhat + o, nh);
         if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
       }
@@ -662,11 +715,11 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
 
 // Element-wise xhat += Q(x - xhat) (Algorithm 1 lines 3-6) with no mixing.
 // grid (ceil(nvec / (256 * kStreamVecs)), n)
-template <int COMP, bool CAPTURE, bool NT>
+template <int COMP, bool CAPTURE, bool NT, bool LAYERED>
 __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
   const int i = blockIdx.y;
   RowScale<COMP> sc;
-  sc.load(A.ctl + i);
+  if (!LAYERED) sc.load(A.ctl + i);
   const int nvec = (A.d + 3) >> 2;
   const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
 #pragma unroll
@@ -679,7 +732,10 @@ __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
       uint4 words = make_uint4(0, 0, 0, 0);
       if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
       vi4 code;
-      const vf4 nh = absorb<COMP>(x, xh, sc, words, code);
+      int nvalid = 4;
+      if (LAYERED) sc.load(A.layer_scale[(int64_t)i * A.nlayers + layer_of_vector(A, 4 * m, nvalid)]);
+      vf4 nh = absorb<COMP>(x, xh, sc, words, code);
+      if (LAYERED) mask_padding(nvalid, xh, nh, code);
       store4<NT>(A.Xhat + o, nh);
       if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
     }

@@ -1,20 +1,22 @@
 // Layer-wise compression (Section 5, set-up of the deep-learning runs: the operator is
 // applied to every layer of the network on its own).
 //
-// A layer of a worker is compressed by one workgroup (1024 threads above 10,240 entries,
-// 256 threads above 2,560) or by one wave (smaller layers, four to a workgroup), with the
-// layer's x - xhat in registers (kLayerVecs 4-vectors per thread, so 1024 threads hold up
-// to 40,960 entries).  The one pass reads x, g, xhat once and does the whole operator:
-//   sign / gsgd_b   the norm tree of the layer (same three levels as for a whole row:
-//                   a wave's 64 lanes x 4 entries are exactly one 256-entry chunk), the
-//                   per-layer scale, the codes, xhat += q
-//   top_a/random_a  the exact k-th largest key.  A bracket [lo, hi) around a guess (last
-//                   step's threshold for top_a, the expected order statistic for
-//                   random_a) is counted in one sweep over the registers; if the k-th key
-//                   provably lies inside, only the few keys in the bracket are searched
-//                   (bit by bit, in LDS); otherwise the whole layer is searched bit by bit
-//                   (31 or 32 sweeps with block-wide counts).  Ties on the threshold key
-//                   go to the lower index.  No histogram, no global atomics.
+// sign / gsgd_b: the whole-row pipeline with per-layer norms.  k_layer_stat streams the rows
+// once (one block per group of up to 16 chunks of ONE layer: the norm tree of a layer
+// starts at the layer's first entry), k_layer_finalise sums each layer's group sums and
+// turns them into the layer's scales, and the apply kernels of the whole-row path look the
+// scale of each 4-vector up by its layer.  Any layer length.
+//
+// top_a / random_a: k_layer_compress.  A layer of a worker is selected by one workgroup
+// (1024 threads above 10,240 entries, 256 threads above 2,560) or by one wave (smaller
+// layers, four to a workgroup), with the layer's x - xhat (or its random words) in
+// registers: kLayerVecs 4-vectors per thread, so 1024 threads hold up to 40,960 entries.
+// The exact k-th largest key: a bracket [lo, hi) around a guess (last step's threshold for
+// top_a, the expected order statistic for random_a) is counted in one sweep over the
+// registers; if the k-th key provably lies inside, only the few keys in the bracket are
+// searched (bit by bit, in LDS); otherwise the whole layer is searched bit by bit (31 or 32
+// sweeps with block-wide counts).  Ties on the threshold key go to the lower index.  No
+// histogram, no global atomics.
 #pragma once
 
 #include "choco_kernels.h"
@@ -72,7 +74,6 @@ __device__ __forceinline__ void layer_sync() {
 
 // The LDS of the THREADS threads that share a layer.
 struct LayerShared {
-  double* chunk;      // first-level norm sums (dense operators)
   uint32_t* cnt;      // 2 x 16 per-wave counts
   uint32_t* emit;     // kept entries emitted so far
   uint32_t* list_n;   // keys in the bracket
@@ -82,7 +83,7 @@ struct LayerShared {
 template <int COMP, int THREADS, bool NT>
 __device__ __forceinline__ void layer_body(const Args& A, const int i, const LayerDesc L, const int tid,
                                            const LayerShared sh) {
-  constexpr bool DENSE = (COMP == Q_SIGN || COMP == Q_QSGD);
+  static_assert(COMP == Q_TOPK || COMP == Q_RANDK, "sign and gsgd layers go through k_layer_stat");
   constexpr int NW = THREADS / 64;
   constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together (5 spills)
   constexpr int kBatches = (kLayerVecs + kBatch - 1) / kBatch;
@@ -152,94 +153,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     }
   }
 
-  if constexpr (DENSE) {
-    // ---- norm tree of the layer ----
-    constexpr int STAT = DENSE ? COMP : Q_SIGN;
-    const int nchunks = (L.len + kChunk - 1) / kChunk;
-    // xhat is read again for the final xhat += q (keeping it beside v and the loads in flight
-    // above would not fit the registers of a 1024-thread block); asked for here, out of the
-    // cache, so that it arrives while the norm tree is being summed
-    vf4 h[kLayerVecs];
-#pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it) {
-      const int m = it * THREADS + tid;
-      if (it < nit && m < nvec) h[it] = load4<false>(Xhat + row + 4 * (int64_t)m);
-    }
-    // the wave's chunks side by side: the butterflies of different chunks are independent,
-    // so each exchange step is issued for all of them before the next one is needed
-    double ct[kLayerVecs];
-#pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it) ct[it] = lane_terms<STAT>(v[it], 4 * (it * THREADS + tid), L.len);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-#pragma unroll
-      for (int it = 0; it < kLayerVecs; ++it)
-        if (it < nit) ct[it] = ct[it] + __shfl_xor(ct[it], off, 64);
-    }
-#pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it) {
-      const int chunk = it * NW + wave;
-      if (chunk < nchunks && lane == 0) sh.chunk[chunk] = ct[it];
-    }
-    layer_sync<THREADS>();
-    // levels 2 and 3, done by every wave for itself: groups of 16 chunk sums (four groups
-    // per round over the 64 lanes), then the lanes that stand for a group sum each
-    const int ngroups = (nchunks + kGroup - 1) / kGroup;
-    double g = 0.0;
-#pragma unroll
-    for (int r = 0; r < ((NW * kLayerVecs + kGroup - 1) / kGroup + 3) / 4; ++r) {
-      if (4 * r < ngroups) {                       // uniform
-        const int chunk = 64 * r + lane;
-        double t = chunk < nchunks ? sh.chunk[chunk] : 0.0;
-        t = group_tree_sum(t);
-        const double got = __shfl(t, 16 * (lane & 3), 64);
-        if ((lane >> 2) == r && lane < ngroups) g = got;
-      }
-    }
-    const double total = wave_tree_sum(g);
-    // ---- per-layer scales (Appendix C with the layer's length in the place of d) ----
-    RowScale<STAT> sc;
-    sc.c = sc.r = sc.step = 0.0f;
-    sc.nonzero = 0;
-    double nrm = 0.0;
-    if (COMP == Q_SIGN) {
-      sc.c = (float)(total / (double)L.len);
-    } else {
-      nrm = sqrt(total);
-      const double s = (double)A.levels, dl = (double)L.len;
-      const double tau = A.qsgd_biased ? 1.0 + fmin(dl / (s * s), sqrt(dl) / s) : 1.0;
-      sc.nonzero = nrm > 0.0 ? 1 : 0;
-      sc.r = nrm > 0.0 ? (float)(s / nrm) : 0.0f;
-      sc.step = nrm > 0.0 ? (float)(nrm / (tau * s)) : 0.0f;
-    }
-    if (tid == 0) {
-      scal[0] = total;
-      scal[1] = COMP == Q_SIGN ? (double)sc.c : nrm;
-      scal[2] = COMP == Q_SIGN ? 0.0 : (double)sc.r;
-      scal[3] = COMP == Q_SIGN ? 0.0 : (double)sc.step;
-    }
-    // ---- codes and xhat += q ----
-#pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it) {
-      const int m = it * THREADS + tid;
-      if (it < nit && m < nvec) {
-        uint4 wd = make_uint4(0u, 0u, 0u, 0u);
-        if (COMP == Q_QSGD) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_DITHER);
-        vi4 code = vi4{0, 0, 0, 0};
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (4 * m + c < L.len) {
-            int32_t cd;
-            const float qv = encode<STAT>(v[it][c], sc, pick(wd, c), cd);
-            h[it][c] = h[it][c] + qv;
-            code[c] = cd;
-          }
-        const int64_t o = row + 4 * (int64_t)m;
-        store4<NT>(Xhat + o, h[it]);
-        if (A.codes) *reinterpret_cast<vi4*>(A.codes + o) = code;
-      }
-    }
-  } else {
+  {
     // ---- top_a / random_a: exact k-th largest key ----
     const uint32_t k = (uint32_t)L.k;
     if (k == 0) {
@@ -428,24 +342,131 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
 template <int COMP, int THREADS, bool NT>
 __global__ __launch_bounds__(1024) void k_layer_compress(Args A, int32_t first, int32_t nblock) {
   constexpr int NW = THREADS / 64;
-  __shared__ double sh_chunk[NW * kLayerVecs];
   __shared__ uint32_t sh_cnt[32];
   __shared__ uint32_t sh_emit[NW];
   __shared__ uint32_t sh_list_n[NW];
   __shared__ uint2 sh_list[2 * THREADS];
   const int i = blockIdx.y;
   if ((int)blockIdx.x < nblock) {
-    const LayerShared sh{sh_chunk, sh_cnt, sh_emit, sh_list_n, sh_list};
+    const LayerShared sh{sh_cnt, sh_emit, sh_list_n, sh_list};
     layer_body<COMP, THREADS, NT>(A, i, A.layer_work[first + (int)blockIdx.x], (int)threadIdx.x, sh);
   } else {
     const int wave = (int)threadIdx.x >> 6;
     const int idx = first + nblock + ((int)blockIdx.x - nblock) * NW + wave;
     if (idx < A.nlayers) {
-      const LayerShared sh{sh_chunk + kLayerVecs * wave, sh_cnt, sh_emit + wave, sh_list_n + wave,
-                           sh_list + 128 * wave};
+      const LayerShared sh{sh_cnt, sh_emit + wave, sh_list_n + wave, sh_list + 128 * wave};
       layer_body<COMP, 64, NT>(A, i, A.layer_work[idx], (int)threadIdx.x & 63, sh);
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// sign / gsgd_b layer by layer: norm pass and scales.
+// ---------------------------------------------------------------------------
+
+// v = x - xhat over one group (up to 16 chunks = 4096 entries) of one layer: chunk and
+// group sums of the layer's norm tree.  One wave per 4 chunks, all four in flight at once
+// (the shape of k_dense_stat); carries the fused local update.  The work items tile every
+// row, padding included, so the update reaches every entry.  grid (ngroup_items, n), block 256.
+template <int COMP, bool NT>
+__global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
+  __shared__ double cs[kGroup];
+  const int i = blockIdx.y;
+  const LayerGroup item = A.layer_groups[blockIdx.x];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)i * A.ld + item.off;
+  vf4 a[4], b[4];
+  int e[4];   // index of the lane's first entry counted from the group's start
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    e[u] = (4 * wave + u) * kChunk + lane * 4;
+    if (e[u] < item.rem) {
+      a[u] = load4<NT>(A.X + row + e[u]);
+      b[u] = load4<NT>(A.Xhat + row + e[u]);
+    }
+  }
+  if (A.G) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < item.rem) {
+        a[u] = local_update4<NT>(A, row + e[u], a[u]);
+        store4<NT>(A.X + row + e[u], a[u]);
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    double t = 0.0;
+    if (e[u] < item.rem) {
+      const vf4 v = a[u] - b[u];
+      t = lane_terms<COMP>(v, e[u], item.rem);
+    }
+    t = wave_tree_sum(t);
+    if (lane == 0) cs[4 * wave + u] = t;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const double t = group_tree_sum(lane < kGroup ? cs[lane] : 0.0);
+    if (lane == 0) A.layer_group_sums[(int64_t)i * A.ngroup_items + blockIdx.x] = t;
+  }
+}
+
+// Third level of a layer's norm tree (256 strided lanes over its group sums, then the
+// halving tree, as k_dense_finalise) and the layer's scales (Appendix C with the layer's
+// length in the place of d).  grid (nlayers, n), block 256.
+template <int COMP>
+__global__ __launch_bounds__(256) void k_layer_finalise(Args A) {
+  __shared__ double sh[256];
+  const int lay = blockIdx.x, i = blockIdx.y, l = threadIdx.x;
+  const int g_first = A.layer_group_first[lay];
+  const int ngroups = A.layer_group_first[lay + 1] - g_first;
+  const double* gs = A.layer_group_sums + (int64_t)i * A.ngroup_items + g_first;
+  double acc = 0.0;
+  bool first = true;
+  for (int g0 = l; g0 < ngroups; g0 += 256 * 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int g = g0 + 256 * u;
+      v[u] = g < ngroups ? gs[g] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (g0 + 256 * u < ngroups) {
+        acc = first ? v[u] : acc + v[u];
+        first = false;
+      }
+    }
+  }
+  sh[l] = acc;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if (l < off) sh[l] = sh[l] + sh[l + off];
+    __syncthreads();
+  }
+  if (l != 0) return;
+  const double total = sh[0];
+  const int len = A.layers[lay].len;
+  LayerScale ls;
+  ls.c = ls.r = ls.step = 0.0f;
+  ls.nonzero = 0;
+  double nrm = 0.0;
+  if (COMP == Q_SIGN) {
+    ls.c = (float)(total / (double)len);
+  } else {
+    nrm = sqrt(total);
+    const double s = (double)A.levels, dl = (double)len;
+    const double tau = A.qsgd_biased ? 1.0 + fmin(dl / (s * s), sqrt(dl) / s) : 1.0;
+    ls.nonzero = nrm > 0.0 ? 1 : 0;
+    ls.r = nrm > 0.0 ? (float)(s / nrm) : 0.0f;
+    ls.step = nrm > 0.0 ? (float)(nrm / (tau * s)) : 0.0f;
+  }
+  A.layer_scale[(int64_t)i * A.nlayers + lay] = ls;
+  double* scal = A.layer_scal + ((int64_t)i * A.nlayers + lay) * 4;
+  scal[0] = total;
+  scal[1] = COMP == Q_SIGN ? (double)ls.c : nrm;
+  scal[2] = COMP == Q_SIGN ? 0.0 : (double)ls.r;
+  scal[3] = COMP == Q_SIGN ? 0.0 : (double)ls.step;
 }
 
 }  // namespace choco

@@ -148,6 +148,7 @@ def test_layer_limits_are_reported_as_unsupported():
     limit = 40960    # CHOCO_MAX_LAYER_LEN
     assert layer_code(limit + 8, [0, 8], [8, limit], [1, 10]) == B.OK
     assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 10]) == B.E_UNSUPPORTED
+    assert layer_code(limit + 9, [0, 8], [8, limit + 1], None, compressor=B.Q_SIGN) == B.OK   # dense: any length
     assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT) == B.E_UNSUPPORTED
     assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_IDENTITY) == B.E_UNSUPPORTED
 

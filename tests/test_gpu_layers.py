@@ -132,3 +132,33 @@ def test_layers_of_the_small_image_model(name, q):
         det = pair.step(G, 0.1)
         pair.check(det, tag="%s resnet-like step %d" % (name, t))
     pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", [OPERATORS[3], OPERATORS[4]])
+def test_dense_layers_of_any_length(name, q, order):
+    # sign / gsgd stream the rows with per-layer norms: layers far above what one workgroup
+    # could hold, with more than 256 group sums (the third tree level wraps), next to tiny ones
+    lengths = [5, 1_200_001, 16, 100_003, 4096, 4097, 36864]
+    layers = synth.layer_table(lengths, fraction=0.01)
+    n = 3
+    X0, inside = padded_state(n, layers, seed=15)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=4, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=7, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        det = pair.step(G, 0.1)
+        pair.check(det, tag="%s long layers step %d" % (name, t))
+    pair.close()
+
+
+def test_dense_layers_with_more_workers_than_the_lds_tile_holds():
+    layers = synth.layer_table([300, 5000, 70], fraction=0.01)
+    n = 70
+    X0, inside = padded_state(n, layers, seed=16)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=4, layers=layers, compressor=binding.Q_SIGN)
+    for t in range(2):
+        det = pair.gossip_step()
+        pair.check(det, tag="sign, 70 workers, step %d" % t)
+    pair.close()
