@@ -66,7 +66,9 @@ typedef struct {
   int32_t n;          /* number of workers, >= 1                                         */
   int64_t d;          /* coordinates per worker, 1 <= d < 2^31                           */
   int64_t ld;         /* row stride of X, G and the internal arrays in floats; 0 means d
-                         rounded up to a multiple of 4.  Must be >= d and a multiple of 4 */
+                         rounded up to a multiple of 4.  Must be >= d and a multiple of 4;
+                         a multiple of 64 (rows on 256-byte boundaries) streams fastest.
+                         Columns d..ld-1 are never compressed, selected or sent         */
   /* Mixing matrix W of Assumption 1 as CSR.  HOST pointers, copied during choco_init.
      Row i lists the neighbours of i INCLUDING i itself (Algorithm 1, line 4), columns
      strictly ascending.  W must be symmetric with non-negative entries and rows summing

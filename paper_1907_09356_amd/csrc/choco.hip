@@ -217,7 +217,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_group_first = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int32_t) : 0);
   L.layer_group_sums = take((size_t)c.n * (size_t)items * sizeof(double));
   L.layer_scale = take(dense_layers ? (size_t)c.n * (size_t)c.nlayers * sizeof(LayerScale) : 0);
-  L.chunk_layer = take(dense_layers ? (size_t)L.nchunks * sizeof(int32_t) : 0);
+  L.chunk_layer = take(dense_layers ? (size_t)L.nchunks * sizeof(int4) : 0);
   L.wire = take((size_t)c.n * (2 + kOverflowSlots) * sizeof(uint32_t));   // message encoder: counters, index slots, status
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
@@ -899,13 +899,14 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     }
   }
   std::vector<LayerGroup> groups;
-  std::vector<int32_t> group_first, chunk_layer;
+  std::vector<int32_t> group_first;
+  std::vector<int4> chunk_layer;
   A.layer_groups = (const LayerGroup*)(base + L.layer_groups);
   A.layer_group_first = (const int32_t*)(base + L.layer_group_first);
   A.ngroup_items = L.ngroup_items;
   A.layer_group_sums = (double*)(base + L.layer_group_sums);
   A.layer_scale = (LayerScale*)(base + L.layer_scale);
-  A.chunk_layer = (const int32_t*)(base + L.chunk_layer);
+  A.chunk_layer = (const int4*)(base + L.chunk_layer);
   if (cfg->nlayers > 0 && !ctx->sparse) {
     const int32_t span = kGroup * kChunk;
     for (const LayerDesc& D : layers) {
@@ -917,7 +918,9 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     int32_t lay = 0;
     for (int32_t ch = 0; ch < L.nchunks; ++ch) {
       while (lay + 1 < cfg->nlayers && layers[(size_t)lay + 1].start <= ch * kChunk) ++lay;
-      chunk_layer[(size_t)ch] = lay;
+      const LayerDesc& D = layers[(size_t)lay];
+      const int32_t next = lay + 1 < cfg->nlayers ? layers[(size_t)lay + 1].start : INT32_MAX;
+      chunk_layer[(size_t)ch] = make_int4(lay, D.start + D.len, next, 0);
     }
   }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
@@ -954,7 +957,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     e = hipMemcpyAsync(base + L.layer_group_first, group_first.data(), group_first.size() * sizeof(int32_t),
                        hipMemcpyHostToDevice, ctx->stream);
   if (e == hipSuccess && !groups.empty())
-    e = hipMemcpyAsync(base + L.chunk_layer, chunk_layer.data(), chunk_layer.size() * sizeof(int32_t),
+    e = hipMemcpyAsync(base + L.chunk_layer, chunk_layer.data(), chunk_layer.size() * sizeof(int4),
                        hipMemcpyHostToDevice, ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {

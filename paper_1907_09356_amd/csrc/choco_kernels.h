@@ -148,7 +148,7 @@ struct Args {
   int32_t ngroup_items;
   double* layer_group_sums;  // n x ngroup_items second-level norm sums
   LayerScale* layer_scale;   // n x nlayers: scales of the last step (sign, gsgd)
-  const int32_t* chunk_layer; // per 256-entry chunk of a row: the layer that holds its first entry
+  const int4* chunk_layer;   // per 256-entry chunk of a row: layer of its first entry, that layer's end, next layer's start
   double* layer_scal;        // n x nlayers x 4: norms and scales / threshold of the last step
   int32_t qsgd_biased;
   // randomness
@@ -170,16 +170,20 @@ __device__ __forceinline__ int layer_of(const Args& A, int e) {
 // that holds the chunk's first entry, then forward (layers shorter than a chunk are rare).
 // Every 4-vector starts inside a layer; `nvalid` is how many of its entries the layer has.
 __device__ __forceinline__ int layer_of_vector(const Args& A, int e, int& nvalid) {
-  int lay = A.chunk_layer[e >> 8];
-  while (lay + 1 < A.nlayers && A.layers[lay + 1].start <= e) ++lay;
-  const LayerDesc L = A.layers[lay];
-  const int left = L.start + L.len - e;
+  const int4 ci = A.chunk_layer[e >> 8];   // {layer of the chunk's first entry, its end, start of the next layer}
+  int lay = ci.x, end = ci.y;
+  if (e >= ci.z) {                         // the chunk holds a layer boundary and e lies past it
+    while (lay + 1 < A.nlayers && A.layers[lay + 1].start <= e) ++lay;
+    const LayerDesc L = A.layers[lay];
+    end = L.start + L.len;
+  }
+  const int left = end - e;
   nvalid = left < 4 ? left : 4;
   return lay;
 }
 
-// Entries of a 4-vector that lie in the padding after a layer are not compressed: they
-// keep their xhat and send the code 0.
+// Entries of a 4-vector that lie in the padding after a layer (or in the pad columns after
+// the row's last entry) are not compressed: they keep their xhat and send the code 0.
 __device__ __forceinline__ void mask_padding(int nvalid, const vf4& xh_old, vf4& xh_new, vi4& code) {
 #pragma unroll
   for (int c = 1; c < 4; ++c)
@@ -609,7 +613,7 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
-  int lay = 0, nvalid = 4;
+  int lay = 0, nvalid = A.d - e < 4 ? A.d - e : 4;   // the last 4-vector of a row may end in pad columns
   if (LAYERED && valid) lay = layer_of_vector(A, e, nvalid);
   vf4 xr[RPW], xh[RPW];
 #pragma unroll
@@ -648,7 +652,7 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
         if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
         vi4 code;
         nh = absorb<COMP>(xr[q], xh[q], sc[q], words, code);
-        if (LAYERED) mask_padding(nvalid, xh[q], nh, code);
+        mask_padding(nvalid, xh[q], nh, code);
         store4<NT>(A.Xhat + o, nh);
         if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
       }
@@ -732,10 +736,10 @@ __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
       uint4 words = make_uint4(0, 0, 0, 0);
       if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
       vi4 code;
-      int nvalid = 4;
+      int nvalid = A.d - 4 * m < 4 ? A.d - 4 * m : 4;   // the last 4-vector of a row may end in pad columns
       if (LAYERED) sc.load(A.layer_scale[(int64_t)i * A.nlayers + layer_of_vector(A, 4 * m, nvalid)]);
       vf4 nh = absorb<COMP>(x, xh, sc, words, code);
-      if (LAYERED) mask_padding(nvalid, xh, nh, code);
+      mask_padding(nvalid, xh, nh, code);
       store4<NT>(A.Xhat + o, nh);
       if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
     }

@@ -134,6 +134,18 @@ def resnet20_like_lengths():
     return np.asarray(out, dtype=np.int64)
 
 
+def lstm_like_lengths(vocab=33278, hidden=650, layers=3):
+    """Parameter tensors of a word-level language model in the style of Section 5's second
+    model (three LSTM layers of hidden size 650 over a tied embedding): one embedding matrix
+    of tens of millions of entries, 1.69 M-entry weight matrices, 2,600-entry biases.  Only the
+    mix of sizes matters here (31.8 M entries in all; the paper's own count is 28.95 M)."""
+    out = [vocab * hidden]
+    for _ in range(layers):
+        out.extend([4 * hidden * hidden, 4 * hidden * hidden, 4 * hidden, 4 * hidden])
+    out.append(vocab)
+    return np.asarray(out, dtype=np.int64)
+
+
 def dense_to_csr(W):
     W = np.asarray(W)
     n = W.shape[0]

@@ -27,12 +27,13 @@ class Pair:
     """One GPU context and one oracle state built from the same X0."""
 
     def __init__(self, X0, topo, gamma, compressor, k=1, levels=1, qsgd_biased=1, randk_rescale=0,
-                 order=binding.ORDER_COMPRESS_THEN_MIX, mix_form=binding.MIX_AUTO, seed=0, layers=None):
+                 order=binding.ORDER_COMPRESS_THEN_MIX, mix_form=binding.MIX_AUTO, seed=0, layers=None,
+                 ld_align=4):
         import torch
         self.torch = torch
         X0 = np.ascontiguousarray(X0, dtype=np.float32)
         self.n, self.d = X0.shape
-        self.ld = (self.d + 3) // 4 * 4
+        self.ld = (self.d + ld_align - 1) // ld_align * ld_align   # row stride in floats (a multiple of 4)
         dev = torch.device("cuda:0")
         self.X = torch.zeros((self.n, self.ld), dtype=torch.float32, device=dev)
         self.X[:, :self.d] = torch.from_numpy(X0).to(dev)

@@ -123,3 +123,10 @@ def test_datacenter_shape_sign_1000_steps():
 
 def test_peer_to_peer_ring_topk_100_steps():
     long_run(64, 270_000, synth.ring_csr(64), 100, 0.02, 0.1, compressor=B.Q_TOPK, k=2700)
+
+
+def test_layer_wise_sign_on_the_language_model_sizes():
+    # layers of up to 21.6 M entries (5,281 group sums: the third tree level wraps 20 times)
+    layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
+    d = synth.layers_dim(layers)
+    run(8, d, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, layers=layers, compressor=B.Q_SIGN)

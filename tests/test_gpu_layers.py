@@ -162,3 +162,20 @@ def test_dense_layers_with_more_workers_than_the_lds_tile_holds():
         det = pair.gossip_step()
         pair.check(det, tag="sign, 70 workers, step %d" % t)
     pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3], OPERATORS[4]])
+def test_layers_with_a_wider_row_stride(name, q):
+    layers = synth.layer_table([432, 16, 2304, 37, 9216, 10], fraction=0.02)
+    n = 4
+    X0, inside = padded_state(n, layers, seed=17)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=4, layers=layers, ld_align=64, **q)
+    assert pair.ld > pair.d + 3
+    grads = synth.GradientStream(n, pair.d, seed=7, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        det = pair.step(G, 0.1)
+        pair.check(det, tag="%s wide rows step %d" % (name, t))
+    assert not pair.gpu.xhat()[:, pair.d:].any()
+    pair.close()

@@ -436,3 +436,27 @@ def test_logistic_regression_workload_2000_steps():
         assert spread < 0.2 * np.linalg.norm(X.mean(0))    # and the workers agree
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
+@pytest.mark.parametrize("order", ORDERS)
+def test_row_stride_wider_than_the_vector(comp, order):
+    # ld rounded up to 64 floats (rows 256-byte aligned, the layout the benchmark uses) and
+    # then some: the pad columns are read but never counted, selected or sent
+    n, d = 6, 5003
+    X0 = synth.normal_state(n, d, seed=41)
+    kw = dict(COMPRESSORS[comp])
+    if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+        kw["k"] = 50
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=3, ld_align=64, **kw)
+    assert pair.ld == 5056
+    grads = synth.GradientStream(n, d, seed=9, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        det = pair.step(grads.next(), 0.1)
+        pair.check(det, tag="%s wide rows step %d" % (comp, t))
+    assert not pair.gpu.xhat()[:, d:].any() and not pair.X[:, d:].any()
+    msgs = pair.gpu.pack_messages()
+    dense = pair.gpu.unpack_messages(msgs)
+    pair.gpu.sync()
+    assert not dense[:, d:].any()
+    pair.close()
