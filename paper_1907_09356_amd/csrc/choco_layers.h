@@ -26,7 +26,6 @@ namespace choco {
 constexpr int kLayerVecs = 10;
 constexpr int kMaxLayerLen = 1024 * kLayerVecs * 4;
 constexpr int kWaveLayerLen = 64 * kLayerVecs * 4;   // up to here a single wave takes the layer
-constexpr int kLayerMaxChunks = 16 * kLayerVecs;     // 256-entry chunks of the largest layer
 constexpr int kMidLayerLen = 256 * kLayerVecs * 4;   // up to here a 256-thread workgroup does
 
 // Block total of per-wave counts (each already uniform over its wave).
