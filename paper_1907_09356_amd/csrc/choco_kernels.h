@@ -239,6 +239,25 @@ __device__ __forceinline__ vf4 local_update4(const ArgsT& A, int64_t o, vf4 x) {
   return x;
 }
 
+// The same on values already in registers (g, and m if there is a momentum memory, loaded
+// by the caller together with its other loads); m is updated in place, the caller stores it.
+template <class ArgsT>
+__device__ __forceinline__ vf4 local_update_regs(const ArgsT& A, vf4 x, const vf4& g, vf4& m) {
+  if (A.M) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float gg = g[c] + A.lambda * x[c];
+      const float mn = gg + A.beta * m[c];
+      m[c] = mn;
+      x[c] = x[c] - A.lr * mn;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) x[c] = x[c] - A.lr * g[c];
+  }
+  return x;
+}
+
 // One entry of x as this step sees it.  random_a under choco_step: no pass reads X before
 // the final mix, so the local update is folded into that mix and the few entries that the
 // select and the scatter gather are updated on the fly (same operations on the same, not
@@ -535,10 +554,19 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   }
   if (A.G) {   // fused local update: x <- x - lr g, stored for the apply pass
     float* xw = A.X + (int64_t)i * A.ld;
+    vf4 g[4], mm[4];   // all loads before the first store (see compact_chunk)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < A.d) {
-        a[u] = local_update4<NT>(A, (int64_t)i * A.ld + e[u], a[u]);
+        g[u] = load4<NT>(A.G + (int64_t)i * A.ld + e[u]);
+        if (A.M) mm[u] = load4<NT>(A.M + (int64_t)i * A.ld + e[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < A.d) {
+        a[u] = local_update_regs(A, a[u], g[u], mm[u]);
+        if (A.M) store4<NT>(A.M + (int64_t)i * A.ld + e[u], mm[u]);
         store4<NT>(xw + e[u], a[u]);
       }
     }
@@ -913,10 +941,56 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
   const int nvec = (A.d + 3) >> 2;
   const int m0 = chunk * (256 * kCompactVecs) + threadIdx.x;
   uint32_t a[kCompactVecs][4];
+  if (COMP == Q_TOPK) {
+    // all loads of the chunk first, then the arithmetic and the stores: a store to X between
+    // two groups of loads would hold the later loads back (the compiler must assume that the
+    // arrays overlap)
+    const bool sgd = FIRST && A.G != nullptr;
+    const bool mom = sgd && A.M != nullptr;
+    vf4 x[kCompactVecs], xh[kCompactVecs], g[kCompactVecs], sm[kCompactVecs];   // sm: S (DO_MIX) or the momentum
 #pragma unroll
-  for (int u = 0; u < kCompactVecs; ++u) {
-    const int m = m0 + u * 256;
-    if (m < nvec) entry_bits<COMP, DO_MIX, NT, FIRST>(A, i, m, a[u]);
+    for (int u = 0; u < kCompactVecs; ++u) {
+      const int m = m0 + u * 256;
+      if (m < nvec) {
+        const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+        x[u] = load4<NT>(A.X + o);
+        xh[u] = load4<NT>(A.Xhat + o);
+        if (sgd) g[u] = load4<NT>(A.G + o);
+        if (DO_MIX) sm[u] = load4<NT>(A.S + o);
+        else if (mom) sm[u] = load4<NT>(A.M + o);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kCompactVecs; ++u) {
+      const int m = m0 + u * 256;
+      if (m < nvec) {
+        const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+        if (sgd) {
+          if (DO_MIX) {           // S occupies the spare registers: the momentum is read here
+            vf4 mm = vf4{0.f, 0.f, 0.f, 0.f};
+            if (mom) mm = load4<NT>(A.M + o);
+            x[u] = local_update_regs(A, x[u], g[u], mm);
+            if (mom) store4<NT>(A.M + o, mm);
+          } else {
+            x[u] = local_update_regs(A, x[u], g[u], sm[u]);
+            if (mom) store4<NT>(A.M + o, sm[u]);
+          }
+        }
+        if (DO_MIX) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) x[u][c] = x[u][c] + A.gamma * (sm[u][c] - xh[u][c]);
+        }
+        if (DO_MIX || sgd) store4<NT>(A.X + o, x[u]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[u][c] = __float_as_uint(x[u][c] - xh[u][c]);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < kCompactVecs; ++u) {
+      const int m = m0 + u * 256;
+      if (m < nvec) entry_bits<COMP, DO_MIX, NT, FIRST>(A, i, m, a[u]);
+    }
   }
 #pragma unroll
   for (int u = 0; u < kCompactVecs; ++u) {

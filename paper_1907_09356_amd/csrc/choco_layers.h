@@ -46,23 +46,6 @@ __device__ __forceinline__ uint32_t block_total(uint32_t wave_count, uint32_t* s
 // lanes of the wave for which pred holds (a compare and a scalar bit count, no cross-lane traffic)
 __device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
 
-// The local update on values already in registers; the arithmetic of local_update4.
-__device__ __forceinline__ vf4 local_update_regs(const Args& A, vf4 x, const vf4& g, vf4& m) {
-  if (A.M) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float gg = g[c] + A.lambda * x[c];
-      const float mn = gg + A.beta * m[c];
-      m[c] = mn;
-      x[c] = x[c] - A.lr * mn;
-    }
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) x[c] = x[c] - A.lr * g[c];
-  }
-  return x;
-}
-
 // Barrier among the THREADS threads that share a layer (one wave needs none: its LDS
 // accesses execute in order; the fence only stops the compiler from reordering them).
 template <int THREADS>
@@ -385,10 +368,19 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
     }
   }
   if (A.G) {
+    vf4 g[4], mm[4];   // all loads before the first store
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < item.rem) {
-        a[u] = local_update4<NT>(A, row + e[u], a[u]);
+        g[u] = load4<NT>(A.G + row + e[u]);
+        if (A.M) mm[u] = load4<NT>(A.M + row + e[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < item.rem) {
+        a[u] = local_update_regs(A, a[u], g[u], mm[u]);
+        if (A.M) store4<NT>(A.M + row + e[u], mm[u]);
         store4<NT>(A.X + row + e[u], a[u]);
       }
     }
