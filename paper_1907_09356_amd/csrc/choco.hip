@@ -184,7 +184,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // share of the capacity, but never more than the blocks feeding it can produce
   int64_t seg_cap = 0;
   if (guessed) {
-    const int64_t per_block = 256 * kCompactVecs * 4;
+    const int64_t per_block = 256 * kCompactVecs * 4;   // (short rows use half-size blocks: the bound below still holds)
     const int64_t nblocks = (c.d + per_block - 1) / per_block;
     const int64_t feeders = (nblocks + kSegs - 1) / kSegs;
     seg_cap = std::max<int64_t>((2 * cap + kSegs - 1) / kSegs, 1024);
@@ -436,7 +436,8 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   const bool fused = F.G != nullptr && !F.deferred_sgd;
   const int32_t nvec = (A.d + 3) >> 2;
   const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
-  const dim3 cgrid = chunk_grid(nvec, A.n, kCompactVecs);
+  const int cvecs = ctx->fallback_chain ? kCompactVecs : 2;   // long rows: 4 four-vectors per thread, short: 2
+  const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
   bool fuse_mix = false;     // the mix rides on the select pass (top_a, printed order, incremental sums)
@@ -456,10 +457,13 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
   const Args& C = x_touched ? A : F;
   const int kid_compact = (!x_touched && fused) ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
-  if (fuse_mix)
-    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT>), cgrid, dim3(256), 0, C);
-  else
-    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT>), cgrid, dim3(256), 0, C);
+  if (fuse_mix) {
+    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 2>), cgrid, dim3(256), 0, C);
+    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
+  } else {
+    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), 0, C);
+    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
+  }
   if (ctx->fallback_chain) {
     const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
     LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);

@@ -34,7 +34,7 @@ constexpr int kBins16 = 65536;    // first digit of the fallback histogram (16 b
 constexpr int kChunk = 256;       // entries per first-level norm chunk / tile width
 constexpr int kGroup = 16;        // chunks per second-level group (4096 entries)
 constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kernels
-constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass
+constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass (long rows; short rows take 2)
 constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
 constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
 constexpr int kStatThreads = 256;   // one wave per 4 chunks of a 16-chunk group
@@ -928,10 +928,10 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
   }
 }
 
-// Append the candidates (key32 >= guess) among the 256 * kCompactVecs 4-vectors of
+// Append the candidates (key32 >= guess) among the 256 * VECS 4-vectors of
 // one chunk of worker i to sub-list chunk % kSegs.  Hits are staged in LDS and
 // flushed with one global atomic per block.
-template <int COMP, bool DO_MIX, bool NT, bool FIRST>
+template <int COMP, bool DO_MIX, bool NT, bool FIRST, int VECS>
 __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, uint2* stage,
                                               uint32_t* s_count, uint32_t* s_base) {
   WorkerCtl* ctl = A.ctl + i;
@@ -939,17 +939,17 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
   const int seg = chunk % kSegs;
   uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
   const int nvec = (A.d + 3) >> 2;
-  const int m0 = chunk * (256 * kCompactVecs) + threadIdx.x;
-  uint32_t a[kCompactVecs][4];
+  const int m0 = chunk * (256 * VECS) + threadIdx.x;
+  uint32_t a[VECS][4];
   if (COMP == Q_TOPK) {
     // all loads of the chunk first, then the arithmetic and the stores: a store to X between
     // two groups of loads would hold the later loads back (the compiler must assume that the
     // arrays overlap)
     const bool sgd = FIRST && A.G != nullptr;
     const bool mom = sgd && A.M != nullptr;
-    vf4 x[kCompactVecs], xh[kCompactVecs], g[kCompactVecs], sm[kCompactVecs];   // sm: S (DO_MIX) or the momentum
+    vf4 x[VECS], xh[VECS], g[VECS], sm[VECS];   // sm: S (DO_MIX) or the momentum
 #pragma unroll
-    for (int u = 0; u < kCompactVecs; ++u) {
+    for (int u = 0; u < VECS; ++u) {
       const int m = m0 + u * 256;
       if (m < nvec) {
         const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
@@ -961,7 +961,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
       }
     }
 #pragma unroll
-    for (int u = 0; u < kCompactVecs; ++u) {
+    for (int u = 0; u < VECS; ++u) {
       const int m = m0 + u * 256;
       if (m < nvec) {
         const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
@@ -987,13 +987,13 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
     }
   } else {
 #pragma unroll
-    for (int u = 0; u < kCompactVecs; ++u) {
+    for (int u = 0; u < VECS; ++u) {
       const int m = m0 + u * 256;
       if (m < nvec) entry_bits<COMP, DO_MIX, NT, FIRST>(A, i, m, a[u]);
     }
   }
 #pragma unroll
-  for (int u = 0; u < kCompactVecs; ++u) {
+  for (int u = 0; u < VECS; ++u) {
     const int m = m0 + u * 256;
     if (m < nvec) {
 #pragma unroll
@@ -1024,14 +1024,16 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
 }
 
 // The one pass of the fast path: every worker, one block per chunk.
-// grid (ceil(nvec / (256 * kCompactVecs)), n), block 256.
-template <int COMP, bool DO_MIX, bool NT>
+// grid (ceil(nvec / (256 * VECS)), n), block 256.  VECS 4-vectors per thread: 4 for long rows
+// (more loads in flight per thread: 6.0 against 5.5 TB/s at d = 28 M), 2 for short ones (twice
+// the blocks and the occupancy: 49 against 57 us at n = 64, d = 270 k).
+template <int COMP, bool DO_MIX, bool NT, int VECS>
 __global__ __launch_bounds__(256) void k_sel_compact(Args A) {
   __shared__ uint2 stage[kStageCap];
   __shared__ uint32_t s_count, s_base;
   if (threadIdx.x == 0) s_count = 0;
   __syncthreads();
-  compact_chunk<COMP, DO_MIX, NT, true>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
+  compact_chunk<COMP, DO_MIX, NT, true, VECS>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
 }
 
 // The rebuild pass of the fallback: only workers in mode 1; a few blocks per
@@ -1049,7 +1051,7 @@ __global__ __launch_bounds__(256) void k_sel_rebuild(Args A) {
     __syncthreads();
     if (threadIdx.x == 0) s_count = 0;
     __syncthreads();
-    compact_chunk<COMP, false, false, false>(A, i, chunk, stage, &s_count, &s_base);
+    compact_chunk<COMP, false, false, false, kCompactVecs>(A, i, chunk, stage, &s_count, &s_base);
   }
 }
 
