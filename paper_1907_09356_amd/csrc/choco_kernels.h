@@ -409,23 +409,31 @@ __global__ __launch_bounds__(256) void k_momentum(float* X, const float* G, floa
                                                   int32_t nvec, float lr, float beta, float lambda) {
   const int64_t row = (int64_t)blockIdx.y * ld;
   const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
+  vf4 x[kStreamVecs], g[kStreamVecs], mo[kStreamVecs];   // all loads before the first store
 #pragma unroll
   for (int u = 0; u < kStreamVecs; ++u) {
     const int m = m0 + u * 256;
     if (m < nvec) {
       const int64_t o = row + 4 * (int64_t)m;
-      vf4 x = load4<NT>(X + o);
-      const vf4 g = load4<NT>(G + o);
-      vf4 mo = load4<NT>(M + o);
+      x[u] = load4<NT>(X + o);
+      g[u] = load4<NT>(G + o);
+      mo[u] = load4<NT>(M + o);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      const int64_t o = row + 4 * (int64_t)m;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const float gg = g[c] + lambda * x[c];
-        const float mn = gg + beta * mo[c];
-        mo[c] = mn;
-        x[c] = x[c] - lr * mn;
+        const float gg = g[u][c] + lambda * x[u][c];
+        const float mn = gg + beta * mo[u][c];
+        mo[u][c] = mn;
+        x[u][c] = x[u][c] - lr * mn;
       }
-      store4<NT>(M + o, mo);
-      store4<NT>(X + o, x);
+      store4<NT>(M + o, mo[u]);
+      store4<NT>(X + o, x[u]);
     }
   }
 }
@@ -754,13 +762,23 @@ __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
   if (!LAYERED) sc.load(A.ctl + i);
   const int nvec = (A.d + 3) >> 2;
   const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
+  vf4 xs[kStreamVecs], xhs[kStreamVecs];   // all loads before the first store
 #pragma unroll
   for (int u = 0; u < kStreamVecs; ++u) {
     const int m = m0 + u * 256;
     if (m < nvec) {
       const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
-      const vf4 x = load4<NT>(A.X + o);
-      const vf4 xh = load4<NT>(A.Xhat + o);
+      xs[u] = load4<NT>(A.X + o);
+      xhs[u] = load4<NT>(A.Xhat + o);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kStreamVecs; ++u) {
+    const int m = m0 + u * 256;
+    if (m < nvec) {
+      const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
+      const vf4 x = xs[u];
+      const vf4 xh = xhs[u];
       uint4 words = make_uint4(0, 0, 0, 0);
       if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
       vi4 code;
