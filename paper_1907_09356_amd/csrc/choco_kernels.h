@@ -562,19 +562,18 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   }
   if (A.G) {   // fused local update: x <- x - lr g, stored for the apply pass
     float* xw = A.X + (int64_t)i * A.ld;
-    vf4 g[4], mm[4];   // all loads before the first store (see compact_chunk)
+    vf4 g[4];   // all gradient loads before the first store (see compact_chunk); the momentum
+                // memory, when there is one, is read in turn: registers for it would cost occupancy
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (e[u] < A.d) g[u] = load4<NT>(A.G + (int64_t)i * A.ld + e[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < A.d) {
-        g[u] = load4<NT>(A.G + (int64_t)i * A.ld + e[u]);
-        if (A.M) mm[u] = load4<NT>(A.M + (int64_t)i * A.ld + e[u]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (e[u] < A.d) {
-        a[u] = local_update_regs(A, a[u], g[u], mm[u]);
-        if (A.M) store4<NT>(A.M + (int64_t)i * A.ld + e[u], mm[u]);
+        vf4 mm = vf4{0.f, 0.f, 0.f, 0.f};
+        if (A.M) mm = load4<NT>(A.M + (int64_t)i * A.ld + e[u]);
+        a[u] = local_update_regs(A, a[u], g[u], mm);
+        if (A.M) store4<NT>(A.M + (int64_t)i * A.ld + e[u], mm);
         store4<NT>(xw + e[u], a[u]);
       }
     }

@@ -368,19 +368,17 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
     }
   }
   if (A.G) {
-    vf4 g[4], mm[4];   // all loads before the first store
+    vf4 g[4];   // all gradient loads before the first store; the momentum memory is read in turn
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (e[u] < item.rem) g[u] = load4<NT>(A.G + row + e[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < item.rem) {
-        g[u] = load4<NT>(A.G + row + e[u]);
-        if (A.M) mm[u] = load4<NT>(A.M + row + e[u]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (e[u] < item.rem) {
-        a[u] = local_update_regs(A, a[u], g[u], mm[u]);
-        if (A.M) store4<NT>(A.M + row + e[u], mm[u]);
+        vf4 mm = vf4{0.f, 0.f, 0.f, 0.f};
+        if (A.M) mm = load4<NT>(A.M + row + e[u]);
+        a[u] = local_update_regs(A, a[u], g[u], mm);
+        if (A.M) store4<NT>(A.M + row + e[u], mm);
         store4<NT>(A.X + row + e[u], a[u]);
       }
     }
