@@ -378,6 +378,17 @@ void launch_dense_apply(choco_ctx* ctx, const Args& A) {
   else LAUNCH(ctx, KID_DENSE_APPLY, (k_dense_apply<COMP, false, NT, LAYERED>), grid, dim3(256), 0, A);
 }
 
+// x += gamma (S - xhat), 4 four-vectors per thread for long rows and 2 for short ones.
+template <bool NT>
+void launch_mix_incremental(choco_ctx* ctx, const Args& A, bool carries_update) {
+  const int kid = carries_update ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL;
+  const int32_t nvec = (A.d + 3) >> 2;
+  if (ctx->fallback_chain)   // long rows
+    LAUNCH(ctx, kid, (k_mix_incremental<NT, 4>), chunk_grid(nvec, A.n, 4), dim3(256), 0, A);
+  else
+    LAUNCH(ctx, kid, (k_mix_incremental<NT, 2>), chunk_grid(nvec, A.n, 2), dim3(256), 0, A);
+}
+
 void launch_mix_direct_global(choco_ctx* ctx, const Args& A) {
   LAUNCH(ctx, KID_MIX_DIRECT_GLOBAL, k_mix_direct_global, chunk_grid((A.d + 3) >> 2, A.n, 1), dim3(256), 0, A);
 }
@@ -449,9 +460,7 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     if (incremental && COMP == Q_TOPK) {
       fuse_mix = true;
     } else {
-      if (incremental)
-        LAUNCH(ctx, fused ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
-               dim3(256), 0, F);
+      if (incremental) launch_mix_incremental<NT>(ctx, F, fused);
       else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, F, fused);
       else launch_mix_direct_global(ctx, A);
       x_touched = true;
@@ -498,9 +507,7 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     Args L = A;
     if (last_carries) L.G = F.G;
     L.fold_xhat = fold_xhat ? 1 : 0;
-    if (incremental)
-      LAUNCH(ctx, last_carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
-             dim3(256), 0, L);
+    if (incremental) launch_mix_incremental<NT>(ctx, L, last_carries);
     else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, L, last_carries);
     else launch_mix_direct_global(ctx, A);
   }
@@ -549,8 +556,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
   bool x_touched = false;
   if (mix_first) {
-    LAUNCH(ctx, fused ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid, dim3(256), 0,
-           fused ? F : A);
+    launch_mix_incremental<NT>(ctx, fused ? F : A, fused);
     x_touched = true;
   }
   // random_a never reads X in the layer kernel, so it cannot carry the local update
@@ -581,8 +587,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     const bool last_carries = F.deferred_sgd != 0;
     Args L = A;
     if (last_carries) L.G = F.G;
-    LAUNCH(ctx, last_carries ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL, (k_mix_incremental<NT>), sgrid,
-           dim3(256), 0, L);
+    launch_mix_incremental<NT>(ctx, L, last_carries);
   }
   LAUNCH_CHECK(ctx);
   return CHOCO_OK;

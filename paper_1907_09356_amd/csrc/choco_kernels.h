@@ -815,16 +815,19 @@ __global__ __launch_bounds__(256) void k_mix_direct_global(Args A) {
 }
 
 // Incremental-form mix: x_i += gamma (S_i - xhat_i).  Pure streaming, 16 B/entry.
-// grid (ceil(nvec / (256 * kStreamVecs)), n)
-template <bool NT>
+// grid (ceil(nvec / (256 * VECS)), n).  VECS 4-vectors per thread, a wave's pieces consecutive
+// (VECS KiB per array and wave): 4 for long rows (6.1 against 6.0 TB/s at d = 28 M), 2 for
+// short ones (twice the blocks: 50 against 53 us at n = 64, d = 270 k).
+template <bool NT, int VECS>
 __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
   const int i = blockIdx.y;
   const int nvec = (A.d + 3) >> 2;
-  const int m0 = blockIdx.x * (256 * kStreamVecs) + threadIdx.x;
-  vf4 x[kStreamVecs], s[kStreamVecs], xh[kStreamVecs];
+  // a wave's VECS 4-vectors are consecutive 1 KiB pieces (wave-contiguous)
+  const int m0 = blockIdx.x * (256 * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
+  vf4 x[VECS], s[VECS], xh[VECS];
 #pragma unroll
-  for (int u = 0; u < kStreamVecs; ++u) {
-    const int m = m0 + u * 256;
+  for (int u = 0; u < VECS; ++u) {
+    const int m = m0 + u * 64;
     if (m < nvec) {
       const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
       x[u] = load4<NT>(A.X + o);
@@ -850,8 +853,8 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
     }
   }
 #pragma unroll
-  for (int u = 0; u < kStreamVecs; ++u) {
-    const int m = m0 + u * 256;
+  for (int u = 0; u < VECS; ++u) {
+    const int m = m0 + u * 64;
     if (m < nvec) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) x[u][c] = x[u][c] + A.gamma * (s[u][c] - xh[u][c]);
@@ -956,7 +959,8 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
   const int seg = chunk % kSegs;
   uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
   const int nvec = (A.d + 3) >> 2;
-  const int m0 = chunk * (256 * VECS) + threadIdx.x;
+  // a wave's VECS 4-vectors are consecutive 1 KiB pieces of the row
+  const int m0 = chunk * (256 * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
   uint32_t a[VECS][4];
   if (COMP == Q_TOPK) {
     // all loads of the chunk first, then the arithmetic and the stores: a store to X between
@@ -967,7 +971,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
     vf4 x[VECS], xh[VECS], g[VECS], sm[VECS];   // sm: S (DO_MIX) or the momentum
 #pragma unroll
     for (int u = 0; u < VECS; ++u) {
-      const int m = m0 + u * 256;
+      const int m = m0 + u * 64;
       if (m < nvec) {
         const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
         x[u] = load4<NT>(A.X + o);
@@ -979,7 +983,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
     }
 #pragma unroll
     for (int u = 0; u < VECS; ++u) {
-      const int m = m0 + u * 256;
+      const int m = m0 + u * 64;
       if (m < nvec) {
         const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
         if (sgd) {
@@ -1005,13 +1009,13 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
   } else {
 #pragma unroll
     for (int u = 0; u < VECS; ++u) {
-      const int m = m0 + u * 256;
+      const int m = m0 + u * 64;
       if (m < nvec) entry_bits<COMP, DO_MIX, NT, FIRST>(A, i, m, a[u]);
     }
   }
 #pragma unroll
   for (int u = 0; u < VECS; ++u) {
-    const int m = m0 + u * 256;
+    const int m = m0 + u * 64;
     if (m < nvec) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
