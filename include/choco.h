@@ -204,8 +204,12 @@ int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
    more than 4 entries sit at level `levels`.  choco_unpack_messages is the receiver's
    side: it writes the dense q of every worker (n*ld floats, 16-byte aligned, zero where
    nothing was sent); for RANDK the mask is the one the library drew in the last step.
-   Not implemented (CHOCO_E_UNSUPPORTED): IDENTITY, layer-wise configurations, RANDK with
-   d > 327,680.  These calls are not part of the timed path. */
+   Layer-wise configurations: a worker's message is the messages of its layers one after
+   the other, each with its own scale / step / index slots (these count inside the layer)
+   and its own padding to whole words; TOPK pairs carry positions in the whole vector.
+   Not implemented (CHOCO_E_UNSUPPORTED): IDENTITY, RANDK layer by layer or with
+   d > 327,680 (no bitmap to put the values in order).  These calls are not part of the
+   timed path. */
 int choco_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t levels,
                              int64_t *bits_host);
 int choco_message_bytes(choco_ctx *ctx, size_t *bytes_host);

@@ -499,11 +499,11 @@ float bits_float(uint32_t u) {
 // q = Q(v) and its message.  Returns 0, or -2 if more entries than there are slots
 // carry a level that does not fit the magnitude bits.
 int pack_message(const QParams& P, int64_t d, const float* v, uint64_t t, int worker, float* q,
-                 uint32_t* msg) {
+                 uint32_t* msg, int64_t e0 = 0) {
   std::vector<int32_t> sel((size_t)(P.compressor == Q_TOPK || P.compressor == Q_RANDK ? P.k : 0));
   std::vector<int32_t> codes((size_t)d, 0);
   double scal[4];
-  compress<float>(P, d, v, t, worker, q, sel.empty() ? nullptr : sel.data(), codes.data(), scal);
+  compress<float>(P, d, v, t, worker, q, sel.empty() ? nullptr : sel.data(), codes.data(), scal, e0);
   const int64_t W = (d + 31) / 32;
   const int64_t words = message_words(P.compressor, d, P.k, P.levels);
   for (int64_t j = 0; j < words; ++j) msg[j] = 0;
@@ -553,7 +553,7 @@ int pack_message(const QParams& P, int64_t d, const float* v, uint64_t t, int wo
 // The receiver's side: q from the message alone (plus the shared seed, the step and the
 // sender for random_a).
 void unpack_message(const QParams& P, int64_t d, uint64_t t, int worker, const uint32_t* msg,
-                    float* q) {
+                    float* q, int64_t e0 = 0) {
   const int64_t W = (d + 31) / 32;
   for (int64_t e = 0; e < d; ++e) q[e] = 0.0f;
   switch (P.compressor) {
@@ -565,7 +565,7 @@ void unpack_message(const QParams& P, int64_t d, uint64_t t, int worker, const u
       break;
     case Q_RANDK: {
       std::vector<int32_t> sel;
-      select_randk(d, P.k, P.seed, t, worker, sel);
+      select_randk(d, P.k, P.seed, t, worker, sel, e0);
       for (int64_t m = 0; m < P.k; ++m) q[sel[(size_t)m]] = bits_float(msg[m]);
       break;
     }
@@ -589,6 +589,53 @@ void unpack_message(const QParams& P, int64_t d, uint64_t t, int worker, const u
       }
       break;
     }
+  }
+}
+
+// Layer by layer (Section 5): a worker's message is the messages of its layers one after
+// the other, each with its own scale / step / index slots and its own word padding;
+// positions in top_a pairs count in the whole vector.  A layer with k = 0 sends nothing.
+int64_t layer_message_words(const QParams& P, const Segments& G, int32_t l) {
+  const bool sparse = (P.compressor == Q_TOPK || P.compressor == Q_RANDK);
+  if (sparse && G.k[l] == 0) return 0;
+  return message_words(P.compressor, G.len[l], sparse ? G.k[l] : 0, P.levels);
+}
+
+int pack_layers(const QParams& P, const Segments& G, int64_t d, const float* v, uint64_t t, int worker,
+                float* q, uint32_t* msg) {
+  const bool sparse = (P.compressor == Q_TOPK || P.compressor == Q_RANDK);
+  for (int64_t e = 0; e < d; ++e) q[e] = 0.0f;
+  int64_t off = 0;
+  for (int32_t l = 0; l < G.nseg; ++l) {
+    const int64_t words = layer_message_words(P, G, l);
+    if (words == 0) continue;
+    QParams Pl = P;
+    Pl.k = sparse ? G.k[l] : 0;
+    const int rc = pack_message(Pl, G.len[l], v + G.start[l], t, worker, q + G.start[l], msg + off, G.start[l]);
+    if (rc != 0) return rc;
+    if (P.compressor == Q_TOPK)
+      for (int64_t m = 0; m < Pl.k; ++m) msg[off + 2 * m] += (uint32_t)G.start[l];
+    off += words;
+  }
+  return 0;
+}
+
+void unpack_layers(const QParams& P, const Segments& G, int64_t d, uint64_t t, int worker,
+                   const uint32_t* msg, float* q) {
+  const bool sparse = (P.compressor == Q_TOPK || P.compressor == Q_RANDK);
+  for (int64_t e = 0; e < d; ++e) q[e] = 0.0f;
+  int64_t off = 0;
+  for (int32_t l = 0; l < G.nseg; ++l) {
+    const int64_t words = layer_message_words(P, G, l);
+    if (words == 0) continue;
+    QParams Pl = P;
+    Pl.k = sparse ? G.k[l] : 0;
+    if (P.compressor == Q_TOPK) {
+      for (int64_t m = 0; m < Pl.k; ++m) q[msg[off + 2 * m]] = bits_float(msg[off + 2 * m + 1]);
+    } else {
+      unpack_message(Pl, G.len[l], t, worker, msg + off, q + G.start[l], G.start[l]);
+    }
+    off += words;
   }
 }
 
@@ -727,6 +774,38 @@ int choco_ref_unpack_message(int32_t compressor, int64_t d, int64_t k, int32_t l
   QParams P{compressor, k, levels, qsgd_biased, randk_rescale, seed};
   if (d < 1) return -1;
   unpack_message(P, d, t, worker, msg, q);
+  return 0;
+}
+
+int64_t choco_ref_layers_message_words(int32_t compressor, int32_t nseg, const int64_t* seg_len,
+                                       const int64_t* seg_k, int32_t levels) {
+  QParams P{compressor, 0, levels, 1, 0, 0};
+  const Segments G{nseg, nullptr, seg_len, seg_k};
+  int64_t words = 0;
+  for (int32_t l = 0; l < nseg; ++l) words += layer_message_words(P, G, l);
+  return words;
+}
+
+int choco_ref_pack_layers(int32_t compressor, int64_t d, const float* v, int32_t nseg,
+                          const int64_t* seg_start, const int64_t* seg_len, const int64_t* seg_k,
+                          int32_t levels, int32_t qsgd_biased, int32_t randk_rescale, uint64_t seed,
+                          uint64_t t, int32_t worker, float* q, uint32_t* msg) {
+  QParams P{compressor, 0, levels, qsgd_biased, randk_rescale, seed};
+  const Segments G{nseg, seg_start, seg_len, seg_k};
+  const bool sparse = (compressor == Q_TOPK || compressor == Q_RANDK);
+  if (nseg < 1 || !segments_ok(G, d, sparse)) return -1;
+  return pack_layers(P, G, d, v, t, worker, q, msg);
+}
+
+int choco_ref_unpack_layers(int32_t compressor, int64_t d, int32_t nseg, const int64_t* seg_start,
+                            const int64_t* seg_len, const int64_t* seg_k, int32_t levels,
+                            int32_t qsgd_biased, int32_t randk_rescale, uint64_t seed, uint64_t t,
+                            int32_t worker, const uint32_t* msg, float* q) {
+  QParams P{compressor, 0, levels, qsgd_biased, randk_rescale, seed};
+  const Segments G{nseg, seg_start, seg_len, seg_k};
+  const bool sparse = (compressor == Q_TOPK || compressor == Q_RANDK);
+  if (nseg < 1 || !segments_ok(G, d, sparse)) return -1;
+  unpack_layers(P, G, d, t, worker, msg, q);
   return 0;
 }
 

@@ -54,6 +54,17 @@ def lib():
                                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                   ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32,
                                                   _u32p, f32p]
+        _lib.choco_ref_layers_message_words.restype = ctypes.c_int64
+        _lib.choco_ref_layers_message_words.argtypes = [ctypes.c_int32, ctypes.c_int32, _i64p, _i64p,
+                                                        ctypes.c_int32]
+        _lib.choco_ref_pack_layers.restype = ctypes.c_int
+        _lib.choco_ref_pack_layers.argtypes = [ctypes.c_int32, ctypes.c_int64, f32p, ctypes.c_int32, _i64p,
+                                               _i64p, _i64p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, f32p, _u32p]
+        _lib.choco_ref_unpack_layers.restype = ctypes.c_int
+        _lib.choco_ref_unpack_layers.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, _i64p, _i64p,
+                                                 _i64p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                 ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, _u32p, f32p]
         for suf, real in (("f32", ctypes.c_float), ("f64", ctypes.c_double)):
             rp = ctypes.POINTER(real)
             f = getattr(_lib, "choco_ref_compress_" + suf)
@@ -167,6 +178,50 @@ def unpack_message(compressor, d, msg, k=1, levels=1, qsgd_biased=1, randk_resca
                                         worker, _ptr(msg, ctypes.c_uint32), _ptr(q, ctypes.c_float))
     if rc != 0:
         raise ValueError("oracle could not unpack the message")
+    return q
+
+
+def _layer_arrays(layers):
+    start, length, k = layers
+    start = np.ascontiguousarray(start, dtype=np.int64)
+    length = np.ascontiguousarray(length, dtype=np.int64)
+    k = np.zeros_like(start) if k is None else np.ascontiguousarray(k, dtype=np.int64)
+    return start, length, k
+
+
+def layers_message_words(compressor, layers, levels=1):
+    start, length, k = _layer_arrays(layers)
+    return int(lib().choco_ref_layers_message_words(compressor, start.size, _ptr(length, ctypes.c_int64),
+                                                    _ptr(k, ctypes.c_int64), levels))
+
+
+def pack_layers(compressor, v, layers, levels=1, qsgd_biased=1, randk_rescale=0, seed=0, t=0, worker=0):
+    """(q, message words) with the operator applied layer by layer: the layers' messages one
+    after the other."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    start, length, k = _layer_arrays(layers)
+    q = np.empty_like(v)
+    msg = np.zeros(layers_message_words(compressor, (start, length, k), levels), dtype=np.uint32)
+    rc = lib().choco_ref_pack_layers(compressor, v.size, _ptr(v, ctypes.c_float), start.size,
+                                     _ptr(start, ctypes.c_int64), _ptr(length, ctypes.c_int64),
+                                     _ptr(k, ctypes.c_int64), levels, qsgd_biased, randk_rescale, seed, t,
+                                     worker, _ptr(q, ctypes.c_float), _ptr(msg, ctypes.c_uint32))
+    if rc != 0:
+        raise ValueError("oracle could not pack the layered message (%d)" % rc)
+    return q, msg
+
+
+def unpack_layers(compressor, d, msg, layers, levels=1, qsgd_biased=1, randk_rescale=0, seed=0, t=0,
+                  worker=0):
+    msg = np.ascontiguousarray(msg, dtype=np.uint32)
+    start, length, k = _layer_arrays(layers)
+    q = np.empty(d, dtype=np.float32)
+    rc = lib().choco_ref_unpack_layers(compressor, d, start.size, _ptr(start, ctypes.c_int64),
+                                       _ptr(length, ctypes.c_int64), _ptr(k, ctypes.c_int64), levels,
+                                       qsgd_biased, randk_rescale, seed, t, worker,
+                                       _ptr(msg, ctypes.c_uint32), _ptr(q, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("oracle could not unpack the layered message")
     return q
 
 

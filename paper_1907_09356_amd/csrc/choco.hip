@@ -36,7 +36,10 @@ struct choco_ctx {
   int nlayers;            // > 0: the operator is applied layer by layer
   int nlarge, nmid;       // layers (by falling length) that take a 1024- / a 256-thread workgroup
   uint64_t t;             // step counter
-  uint32_t* wire;         // device scratch of the message encoder: n counters, n x 4 index slots, n status words
+  uint32_t* wire;         // device scratch of the message encoder: n status words, then counters and index slots
+  const int64_t* wire_word_off;   // layer by layer: where each layer's message starts / prefix of plane lengths
+  const int64_t* wire_plane_off;
+  int64_t wire_words, wire_plane_words;
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
   int metrics_blocks;
@@ -59,7 +62,8 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
-      chunk_layer, wire, mpart, mout, total;
+      chunk_layer, wire, wire_word_off, wire_plane_off, mpart, mout, total;
+  int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
@@ -149,6 +153,24 @@ double want_candidates(const choco_config& c) {
 
 double expected_candidates(const choco_config& c) { return (double)c.k + want_candidates(c); }
 
+int magnitude_bits(int levels) {
+  int mb = 0;
+  for (int x = levels - 1; x > 0; x >>= 1) ++mb;
+  return mb < 1 ? 1 : mb;
+}
+
+// 32-bit words of one worker's message in the layout of choco_wire.h.
+int64_t message_words(int compressor, int64_t d, int64_t k, int levels) {
+  const int64_t W = (d + 31) / 32;
+  switch (compressor) {
+    case CHOCO_Q_TOPK: return 2 * k;
+    case CHOCO_Q_RANDK: return k;
+    case CHOCO_Q_SIGN: return 1 + W;
+    case CHOCO_Q_QSGD: return 1 + kOverflowSlots + (int64_t)(1 + magnitude_bits(levels)) * W;
+    default: return -1;
+  }
+}
+
 Layout make_layout(const choco_config& c, int32_t nnz) {
   Layout L{};
   const int64_t ld = resolve_ld(c);
@@ -218,7 +240,17 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_group_sums = take((size_t)c.n * (size_t)items * sizeof(double));
   L.layer_scale = take(dense_layers ? (size_t)c.n * (size_t)c.nlayers * sizeof(LayerScale) : 0);
   L.chunk_layer = take(dense_layers ? (size_t)L.nchunks * sizeof(int4) : 0);
-  L.wire = take((size_t)c.n * (2 + kOverflowSlots) * sizeof(uint32_t));   // message encoder: counters, index slots, status
+  // message encoder: n status words, then per (worker, layer) a counter and the index slots
+  const size_t wire_units = (size_t)c.n * (size_t)(layered ? c.nlayers : 1);
+  L.wire = take(((size_t)c.n + wire_units * (1 + kOverflowSlots)) * sizeof(uint32_t));
+  L.wire_word_off = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int64_t) : 0);
+  L.wire_plane_off = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int64_t) : 0);
+  L.wire_words = L.wire_plane_words = 0;
+  if (dense_layers)
+    for (int32_t l = 0; l < c.nlayers; ++l) {
+      L.wire_words += message_words(c.compressor, c.layer_len_host[l], 0, c.levels);
+      L.wire_plane_words += (c.layer_len_host[l] + 31) / 32;
+    }
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -689,27 +721,10 @@ int fused_iteration(choco_ctx* ctx, const LocalUpdate& u) {
   return run_gossip(ctx, LocalUpdate());
 }
 
-int magnitude_bits(int levels) {
-  int mb = 0;
-  for (int x = levels - 1; x > 0; x >>= 1) ++mb;
-  return mb < 1 ? 1 : mb;
-}
-
-// 32-bit words of one worker's message in the layout of choco_wire.h.
-int64_t message_words(int compressor, int64_t d, int64_t k, int levels) {
-  const int64_t W = (d + 31) / 32;
-  switch (compressor) {
-    case CHOCO_Q_TOPK: return 2 * k;
-    case CHOCO_Q_RANDK: return k;
-    case CHOCO_Q_SIGN: return 1 + W;
-    case CHOCO_Q_QSGD: return 1 + kOverflowSlots + (int64_t)(1 + magnitude_bits(levels)) * W;
-    default: return -1;
-  }
-}
-
 // Which configurations the message kernels cover.
 int wire_supported(const choco_ctx* ctx) {
-  if (ctx->nlayers > 0 || ctx->cfg.compressor == CHOCO_Q_IDENTITY) return CHOCO_E_UNSUPPORTED;
+  if (ctx->cfg.compressor == CHOCO_Q_IDENTITY) return CHOCO_E_UNSUPPORTED;
+  // random_a needs the kept-entry bitmap to order its values (short rows, whole-vector mode)
   if (ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->args.bitmap_words == 0) return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
@@ -721,15 +736,22 @@ WireArgs wire_args(const choco_ctx* ctx) {
   Wa.n = A.n;
   Wa.d = A.d;
   Wa.ld = A.ld;
-  Wa.words = message_words(ctx->cfg.compressor, A.d, A.k, ctx->cfg.levels);
+  const bool dense_layers = ctx->nlayers > 0 && !ctx->sparse;
+  Wa.words = dense_layers ? ctx->wire_words : message_words(ctx->cfg.compressor, A.d, A.k, ctx->cfg.levels);
   Wa.W = ((int64_t)A.d + 31) / 32;
   Wa.mb = magnitude_bits(ctx->cfg.levels);
   Wa.levels = ctx->cfg.levels;
   Wa.codes = A.codes;
   Wa.ctl = A.ctl;
-  Wa.ovf_count = ctx->wire;
-  Wa.ovf_idx = ctx->wire + A.n;
-  Wa.status = ctx->wire + (size_t)A.n * (1 + kOverflowSlots);
+  const size_t units = (size_t)A.n * (size_t)(ctx->nlayers > 0 ? ctx->nlayers : 1);
+  Wa.status = ctx->wire;
+  Wa.ovf_count = ctx->wire + A.n;
+  Wa.ovf_idx = ctx->wire + A.n + units;
+  Wa.layers = A.layers;
+  Wa.nlayers = dense_layers ? ctx->nlayers : 0;
+  Wa.layer_word_off = ctx->wire_word_off;
+  Wa.layer_plane_off = ctx->wire_plane_off;
+  Wa.layer_scale = A.layer_scale;
   Wa.k = A.k;
   Wa.sel_idx = A.sel_idx;
   Wa.sel_val = A.sel_val;
@@ -938,6 +960,22 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
   ctx->wire = (uint32_t*)(base + L.wire);
+  ctx->wire_word_off = (const int64_t*)(base + L.wire_word_off);
+  ctx->wire_plane_off = (const int64_t*)(base + L.wire_plane_off);
+  ctx->wire_words = L.wire_words;
+  ctx->wire_plane_words = L.wire_plane_words;
+  std::vector<int64_t> word_off, plane_off;
+  if (cfg->nlayers > 0 && !ctx->sparse) {
+    int64_t wo = 0, po = 0;
+    for (int32_t l = 0; l < cfg->nlayers; ++l) {
+      word_off.push_back(wo);
+      plane_off.push_back(po);
+      wo += message_words(cfg->compressor, cfg->layer_len_host[l], 0, cfg->levels);
+      po += (cfg->layer_len_host[l] + 31) / 32;
+    }
+    word_off.push_back(wo);
+    plane_off.push_back(po);
+  }
   ctx->metrics_part = (double*)(base + L.mpart);
   ctx->metrics_out = (double*)(base + L.mout);
   ctx->metrics_blocks = kMetricsBlocks;
@@ -970,6 +1008,12 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
                        hipMemcpyHostToDevice, ctx->stream);
   if (e == hipSuccess && !groups.empty())
     e = hipMemcpyAsync(base + L.chunk_layer, chunk_layer.data(), chunk_layer.size() * sizeof(int4),
+                       hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess && !word_off.empty())
+    e = hipMemcpyAsync(base + L.wire_word_off, word_off.data(), word_off.size() * sizeof(int64_t),
+                       hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess && !plane_off.empty())
+    e = hipMemcpyAsync(base + L.wire_plane_off, plane_off.data(), plane_off.size() * sizeof(int64_t),
                        hipMemcpyHostToDevice, ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {
@@ -1096,7 +1140,7 @@ int choco_message_bytes(choco_ctx* ctx, size_t* bytes_host) {
   if (!ctx || !bytes_host) return CHOCO_E_INVAL;
   const int rc = wire_supported(ctx);
   if (rc != CHOCO_OK) return rc;
-  *bytes_host = (size_t)message_words(ctx->cfg.compressor, ctx->args.d, ctx->args.k, ctx->cfg.levels) * 4;
+  *bytes_host = (size_t)wire_args(ctx).words * 4;
   return CHOCO_OK;
 }
 
@@ -1108,15 +1152,24 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
   uint32_t* msg = (uint32_t*)msgs_dev;
   const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
   const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
+  const dim3 lgrid((unsigned)((ctx->wire_plane_words + 255) / 256), (unsigned)Wa.n);
   switch (ctx->cfg.compressor) {
     case CHOCO_Q_SIGN:
       if (!Wa.codes) return CHOCO_E_INVAL;   // the codes of the last step come from choco_set_capture
-      LAUNCH(ctx, KID_WIRE, k_pack_sign, wgrid, dim3(256), 0, Wa, msg);
+      if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<false>, lgrid, dim3(256), 0, Wa, msg);
+      else LAUNCH(ctx, KID_WIRE, k_pack_sign, wgrid, dim3(256), 0, Wa, msg);
       break;
     case CHOCO_Q_QSGD: {
       if (!Wa.codes) return CHOCO_E_INVAL;
-      LAUNCH(ctx, KID_WIRE, k_pack_gsgd, wgrid, dim3(256), 0, Wa, msg);
-      LAUNCH(ctx, KID_WIRE, k_pack_gsgd_finish, dim3((unsigned)Wa.n), dim3(64), 0, Wa, msg);
+      if (Wa.nlayers) {
+        HIP_TRY(ctx, hipMemsetAsync(Wa.status, 0, (size_t)Wa.n * sizeof(uint32_t), ctx->stream));
+        LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg);
+        LAUNCH(ctx, KID_WIRE, k_pack_gsgd_layers_finish, dim3((unsigned)Wa.nlayers, (unsigned)Wa.n), dim3(64), 0, Wa,
+               msg);
+      } else {
+        LAUNCH(ctx, KID_WIRE, k_pack_gsgd, wgrid, dim3(256), 0, Wa, msg);
+        LAUNCH(ctx, KID_WIRE, k_pack_gsgd_finish, dim3((unsigned)Wa.n), dim3(64), 0, Wa, msg);
+      }
       LAUNCH_CHECK(ctx);
       std::vector<uint32_t> status((size_t)Wa.n);
       HIP_TRY(ctx, hipMemcpyAsync(status.data(), Wa.status, status.size() * sizeof(uint32_t), hipMemcpyDeviceToHost,
@@ -1148,14 +1201,21 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
   const uint32_t* msg = (const uint32_t*)msgs_dev;
   const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
   const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
+  const dim3 lgrid((unsigned)((ctx->wire_plane_words + 255) / 256), (unsigned)Wa.n);
   // every entry of q is written: pad columns and entries not sent are zero (the dense decoders
   // write whole 4-vectors up to d themselves, so they need the fill only for a wider ld)
-  if (ctx->sparse || Wa.ld > ((int64_t)Wa.d + 3) / 4 * 4)
+  if (ctx->sparse || Wa.nlayers || Wa.ld > ((int64_t)Wa.d + 3) / 4 * 4)
     LAUNCH(ctx, KID_WIRE, k_wire_zero, dim3((unsigned)((Wa.ld + 1023) / 1024), (unsigned)Wa.n), dim3(256), 0, q_dev,
            Wa.ld);
   switch (ctx->cfg.compressor) {
-    case CHOCO_Q_SIGN: LAUNCH(ctx, KID_WIRE, k_unpack_sign, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
-    case CHOCO_Q_QSGD: LAUNCH(ctx, KID_WIRE, k_unpack_gsgd, wgrid, dim3(256), 0, Wa, msg, q_dev); break;
+    case CHOCO_Q_SIGN:
+      if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_unpack_dense_layers<false>, lgrid, dim3(256), 0, Wa, msg, q_dev);
+      else LAUNCH(ctx, KID_WIRE, k_unpack_sign, wgrid, dim3(256), 0, Wa, msg, q_dev);
+      break;
+    case CHOCO_Q_QSGD:
+      if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_unpack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg, q_dev);
+      else LAUNCH(ctx, KID_WIRE, k_unpack_gsgd, wgrid, dim3(256), 0, Wa, msg, q_dev);
+      break;
     case CHOCO_Q_TOPK: LAUNCH(ctx, KID_WIRE, k_unpack_topk, kgrid, dim3(256), 0, Wa, msg, q_dev); break;
     case CHOCO_Q_RANDK:
       LAUNCH(ctx, KID_WIRE, k_unpack_randk, dim3((unsigned)Wa.n), dim3(1024),

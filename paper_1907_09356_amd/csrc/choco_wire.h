@@ -36,7 +36,134 @@ struct WireArgs {
   const float* sel_val;
   const uint32_t* bitmap;
   int64_t bitmap_words;
+  // layer by layer: a worker's message is its layers' messages one after the other
+  const LayerDesc* layers;
+  int32_t nlayers;
+  const int64_t* layer_word_off;    // nlayers + 1: where each layer's message starts (words)
+  const int64_t* layer_plane_off;   // nlayers + 1: prefix of the layers' plane lengths ceil(len / 32)
+  const LayerScale* layer_scale;    // n x nlayers
 };
+
+// The layer that holds word pw of the row's concatenated bit planes.
+__device__ __forceinline__ int plane_layer(const WireArgs& A, int64_t pw) {
+  int lo = 0, hi = A.nlayers - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (A.layer_plane_off[mid] <= pw) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
+// The 32 codes behind word w of layer L's bit planes; entries past the layer's end read as 0.
+__device__ __forceinline__ void load_layer_codes32(const WireArgs& A, int i, const LayerDesc& L, int64_t w,
+                                                   int32_t (&c)[32]) {
+  const int32_t* src = A.codes + (int64_t)i * A.ld + L.start + 32 * w;   // 16-byte aligned: start is a multiple of 4
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    vi4 q = vi4{0, 0, 0, 0};
+    if (32 * w + 4 * j < L.len) q = *reinterpret_cast<const vi4*>(src + 4 * j);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c[4 * j + u] = (32 * w + 4 * j + u < L.len) ? q[u] : 0;
+  }
+}
+
+// sign / gsgd layer by layer.  grid (ceil(total plane words / 256), n): one thread per word position
+// of one layer, all planes.  GSGD = false: sign.
+template <bool GSGD>
+__global__ __launch_bounds__(256) void k_pack_dense_layers(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.y;
+  const int64_t pw = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (pw >= A.layer_plane_off[A.nlayers]) return;
+  const int lay = plane_layer(A, pw);
+  const LayerDesc L = A.layers[lay];
+  const int64_t w = pw - A.layer_plane_off[lay];
+  const int64_t W = A.layer_plane_off[lay + 1] - A.layer_plane_off[lay];
+  uint32_t* out = msg + (int64_t)i * A.words + A.layer_word_off[lay];
+  const LayerScale ls = A.layer_scale[(int64_t)i * A.nlayers + lay];
+  if (w == 0) out[0] = __float_as_uint(GSGD ? ls.step : ls.c);
+  int32_t c[32];
+  load_layer_codes32(A, i, L, w, c);
+  uint32_t sign = 0;
+  if (!GSGD) {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) sign |= (c[j] < 0 ? 1u : 0u) << j;
+    out[1 + w] = sign;
+    return;
+  }
+  const int32_t maxmag = (1 << A.mb) - 1;
+  uint32_t* planes = out + 1 + kOverflowSlots;
+  const int64_t slot0 = ((int64_t)i * A.nlayers + lay);
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    sign |= (c[j] < 0 ? 1u : 0u) << j;
+    c[j] = c[j] < 0 ? -c[j] : c[j];
+    if (c[j] > maxmag) {
+      const uint32_t slot = atomicAdd(A.ovf_count + slot0, 1u);
+      if (slot < (uint32_t)kOverflowSlots) A.ovf_idx[slot0 * kOverflowSlots + slot] = (uint32_t)(32 * w + j);
+      c[j] = maxmag;
+    }
+  }
+  planes[w] = sign;
+  for (int p = 0; p < A.mb; ++p) {
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) bits |= (uint32_t)((c[j] >> p) & 1) << j;
+    planes[(int64_t)(1 + p) * W + w] = bits;
+  }
+}
+
+// grid (nlayers, n), one wave: the index slots of every layer's gsgd message
+__global__ __launch_bounds__(64) void k_pack_gsgd_layers_finish(WireArgs A, uint32_t* msg) {
+  const int lay = blockIdx.x, i = blockIdx.y;
+  if (threadIdx.x != 0) return;
+  uint32_t* out = msg + (int64_t)i * A.words + A.layer_word_off[lay];
+  const int64_t slot0 = (int64_t)i * A.nlayers + lay;
+  const uint32_t cnt = A.ovf_count[slot0];
+  uint32_t v[kOverflowSlots];
+  for (int j = 0; j < kOverflowSlots; ++j) v[j] = (uint32_t)j < cnt ? A.ovf_idx[slot0 * kOverflowSlots + j] : 0xFFFFFFFFu;
+  for (int a = 1; a < kOverflowSlots; ++a)
+    for (int b = a; b > 0 && v[b] < v[b - 1]; --b) {
+      const uint32_t t = v[b];
+      v[b] = v[b - 1];
+      v[b - 1] = t;
+    }
+  for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
+  if (cnt > (uint32_t)kOverflowSlots) A.status[i] = 1u;   // cleared by the host before the launch
+  A.ovf_count[slot0] = 0;
+}
+
+// after k_wire_zero.  grid (ceil(total plane words / 256), n)
+template <bool GSGD>
+__global__ __launch_bounds__(256) void k_unpack_dense_layers(WireArgs A, const uint32_t* msg, float* q) {
+  const int i = blockIdx.y;
+  const int64_t pw = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (pw >= A.layer_plane_off[A.nlayers]) return;
+  const int lay = plane_layer(A, pw);
+  const LayerDesc L = A.layers[lay];
+  const int64_t w = pw - A.layer_plane_off[lay];
+  const int64_t W = A.layer_plane_off[lay + 1] - A.layer_plane_off[lay];
+  const uint32_t* in = msg + (int64_t)i * A.words + A.layer_word_off[lay];
+  const float scale = __uint_as_float(in[0]);
+  float* dst = q + (int64_t)i * A.ld + L.start + 32 * w;
+  if (!GSGD) {
+    const uint32_t bits = in[1 + w];
+    for (int j = 0; j < 32; ++j)
+      if (32 * w + j < L.len) dst[j] = ((bits >> j) & 1u) ? -scale : scale;
+    return;
+  }
+  const uint32_t* planes = in + 1 + kOverflowSlots;
+  const uint32_t sign = planes[w];
+  for (int j = 0; j < 32; ++j) {
+    if (32 * w + j >= L.len) break;
+    int32_t level = 0;
+    for (int p = 0; p < A.mb; ++p) level |= (int32_t)((planes[(int64_t)(1 + p) * W + w] >> j) & 1u) << p;
+    for (int s = 0; s < kOverflowSlots; ++s)
+      if (in[1 + s] == (uint32_t)(32 * w + j)) level = A.levels;
+    const float mag = (float)level * scale;
+    dst[j] = ((sign >> j) & 1u) ? -mag : mag;
+  }
+}
 
 // The 32 codes behind word w of a row's bit planes; entries past d read as 0.
 __device__ __forceinline__ void load_codes32(const WireArgs& A, int i, int64_t w, int32_t (&c)[32]) {

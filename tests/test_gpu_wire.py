@@ -100,8 +100,59 @@ def test_message_calls_say_what_they_do_not_cover():
     assert err.value.code == binding.E_INVAL
     g.close()
     layers = synth.layer_table([200, 400], fraction=0.1)
-    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_TOPK, layers=layers)
-    with pytest.raises(binding.ChocoError) as err:
+    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_RANDK, layers=layers)
+    with pytest.raises(binding.ChocoError) as err:      # random_a layer by layer: no bitmap to rank by
         g.message_bytes()
     assert err.value.code == binding.E_UNSUPPORTED
     g.close()
+
+
+LAYERED = [
+    ("topk", dict(compressor=binding.Q_TOPK)),
+    ("sign", dict(compressor=binding.Q_SIGN)),
+    ("qsgd8", dict(compressor=binding.Q_QSGD, levels=8)),
+    ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
+]
+
+
+@pytest.mark.parametrize("name,q", LAYERED)
+def test_layered_messages_match_the_oracle(name, q):
+    # the layers' messages one after the other, each with its own scale and word padding
+    lengths = [432, 16, 1, 3, 2304, 33, 4097, 10]
+    start, length, k = synth.layer_table(lengths, fraction=0.05)
+    k[1] = 0
+    layers = (start, length, k)
+    d = synth.layers_dim(layers)
+    n = 4
+    X0 = synth.normal_state(n, d, seed=33)
+    inside = np.zeros(d, dtype=bool)
+    for a, ln in zip(start, length):
+        inside[a:a + ln] = True
+    X0[:, ~inside] = 0.0
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, layers=layers, **q)
+    grads = synth.GradientStream(n, d, seed=6, noise_std=0.05, bias_std=0.02)
+    for t in range(3):
+        G = grads.next()
+        G[:, ~inside] = 0.0
+        pair.sgd_step(G, 0.1)
+        v = pair.ref.X - pair.ref.Xhat
+        want = [ref.pack_layers(q["compressor"], v[i], layers, levels=q.get("levels", 1),
+                                qsgd_biased=q.get("qsgd_biased", 1), seed=pair.ref.seed, t=t, worker=i)
+                for i in range(n)]
+        det = pair.gossip_step()
+        pair.check(det, tag="%s step %d" % (name, t))
+        msgs = pair.gpu.pack_messages()
+        got = msgs.cpu().numpy().view(np.uint32)
+        assert got.shape[1] == ref.layers_message_words(q["compressor"], layers, q.get("levels", 1))
+        for i in range(n):
+            if q["compressor"] == binding.Q_TOPK:
+                assert np.array_equal(sorted_pairs(got[i:i + 1]), sorted_pairs(want[i][1][None, :]))
+            else:
+                assert np.array_equal(got[i], want[i][1]), "%s: worker %d message differs" % (name, i)
+        dense = pair.gpu.unpack_messages(msgs)
+        pair.gpu.sync()
+        dense = dense.cpu().numpy()
+        for i in range(n):
+            assert np.array_equal(dense[i, :d], want[i][0])
+        assert not dense[:, d:].any()
+    pair.close()

@@ -840,3 +840,44 @@ def test_gsgd_level_s_travels_through_the_index_slots():
         assert list(msg[1:1 + over.size]) == list(over)
         assert np.array_equal(ref.unpack_message(ref.QSGD, 40, msg, levels=2, seed=3, t=t), det["q"])
     assert seen >= 2
+
+
+@pytest.mark.parametrize("comp,kw", [(ref.TOPK, {}), (ref.RANDK, dict(seed=5, t=3, worker=2)),
+                                      (ref.SIGN, {}), (ref.QSGD, dict(levels=8, seed=8, t=1, worker=4))])
+def test_layered_messages_are_the_layers_messages_one_after_the_other(comp, kw):
+    start = np.array([0, 12, 40, 300], dtype=np.int64)
+    length = np.array([10, 28, 257, 45], dtype=np.int64)
+    k = np.array([3, 0, 40, 5], dtype=np.int64)
+    d = 350
+    v = synth.normal_state(1, d, seed=2)[0]
+    q, msg = ref.pack_layers(comp, v, (start, length, k), **kw)
+    # q is what a layered step sends (checked against one) ...
+    st = ref.RefState(v[None, :], [0, 1], [0], [1.0], gamma=0.5, compressor=comp, layers=(start, length, k),
+                      levels=kw.get("levels", 1), seed=kw.get("seed", 0))
+    st.t = kw.get("t", 0)
+    if kw.get("worker", 0) == 0:
+        st.gossip_step()
+        assert np.array_equal(st.Xhat[0], q)
+    # ... the message is the concatenation of the per-layer messages (top_a positions global) ...
+    off = 0
+    sparse = comp in (ref.TOPK, ref.RANDK)
+    for l in range(4):
+        if sparse and k[l] == 0:
+            continue
+        sl = slice(start[l], start[l] + length[l])
+        ql, ml = ref.pack_message(comp, v[sl], k=int(k[l]) if sparse else 1, **kw) if not kw.get("seed") else (None, None)
+        words = ref.message_words(comp, int(length[l]), int(k[l]) if sparse else 0, kw.get("levels", 1))
+        if ml is not None:          # operators without random words: the slice alone gives the same message
+            ml = ml.copy()
+            if comp == ref.TOPK:
+                ml[0::2] += np.uint32(start[l])
+            assert np.array_equal(msg[off:off + words], ml)
+        off += words
+    assert off == msg.size == ref.layers_message_words(comp, (start, length, k), kw.get("levels", 1))
+    # ... and the receiver gets q back
+    back = ref.unpack_layers(comp, d, msg, (start, length, k), **kw)
+    assert np.array_equal(back, q)
+    inside = np.zeros(d, dtype=bool)
+    for a, ln in zip(start, length):
+        inside[a:a + ln] = True
+    assert not q[~inside].any()
