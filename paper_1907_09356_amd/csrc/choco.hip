@@ -820,10 +820,17 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   // (one block per worker) is quick enough, so they are left out.
   ctx->fallback_chain = cfg->d > ((int64_t)1 << 21) && cfg->nlayers == 0;
   ctx->nlayers = cfg->nlayers;
-  // Non-temporal accesses for all but tiny states: measured faster even when the state
-  // would fit in cache (a kernel boundary on this multi-die part writes dirty L2 lines
-  // back anyway); the cached path stays for states under 4 MB per array.
-  ctx->nt = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float) >= ((size_t)4 << 20);
+  // Non-temporal (streaming) or ordinary cached accesses, by the size of one state array;
+  // measured on MI355X with 64 workers on a ring unless said otherwise (ms per step, NT / cached):
+  //   8.6 MB (n = 8) sign 0.0189 / 0.0216;  16 MB sign 0.0326 / 0.0319;  33 MB sign 0.0567 / 0.0536,
+  //   top-k 0.0772 / 0.0676;  69 MB top-k 0.131 / 0.124, sign per layer 0.117 / 0.101;
+  //   132 MB top-k 0.258 / 0.316;  264 MB top-k 0.542 / 0.685.
+  // The three or four arrays of a step stay in the 256 MB last-level cache between kernels when
+  // they fit, and ordinary accesses then beat the streaming ones; small states lose more at
+  // the kernel boundaries (dirty lines are written back there), large ones only thrash.
+  const size_t state_bytes = (size_t)cfg->n * (size_t)resolve_ld(*cfg) * sizeof(float);
+  const bool cache_resident = state_bytes >= ((size_t)12 << 20) && state_bytes <= ((size_t)96 << 20);
+  ctx->nt = state_bytes >= ((size_t)4 << 20) && !cache_resident;
   ctx->t = 0;
   ctx->last_hip_error = 0;
   ctx->profiling = false;
