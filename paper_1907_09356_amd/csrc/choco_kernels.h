@@ -221,7 +221,7 @@ __device__ __forceinline__ void store4(float* p, vf4 v) {
 // Every product and sum rounded on its own, as in k_sgd / k_momentum.
 template <bool NT, class ArgsT>
 __device__ __forceinline__ vf4 local_update4(const ArgsT& A, int64_t o, vf4 x) {
-  const vf4 g = load4<NT>(A.G + o);
+  const vf4 g = load4<true>(A.G + o);   // a gradient is read once: always streamed
   if (A.M) {
     vf4 m = load4<NT>(A.M + o);
 #pragma unroll
@@ -566,7 +566,7 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
                 // memory, when there is one, is read in turn: registers for it would cost occupancy
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (e[u] < A.d) g[u] = load4<NT>(A.G + (int64_t)i * A.ld + e[u]);
+      if (e[u] < A.d) g[u] = load4<true>(A.G + (int64_t)i * A.ld + e[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < A.d) {
@@ -976,7 +976,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
         const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
         x[u] = load4<NT>(A.X + o);
         xh[u] = load4<NT>(A.Xhat + o);
-        if (sgd) g[u] = load4<NT>(A.G + o);
+        if (sgd) g[u] = load4<true>(A.G + o);
         if (DO_MIX) sm[u] = load4<NT>(A.S + o);
         else if (mom) sm[u] = load4<NT>(A.M + o);
       }

@@ -109,7 +109,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
             const int64_t o = row + 4 * (int64_t)m;
             x[j] = load4<NT>(X + o);
             h[j] = load4<NT>(Xhat + o);
-            if (G) g[j] = load4<NT>(G + o);
+            if (G) g[j] = load4<true>(G + o);
           }
         }
       }
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
     vf4 g[4];   // all gradient loads before the first store; the momentum memory is read in turn
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (e[u] < item.rem) g[u] = load4<NT>(A.G + row + e[u]);
+      if (e[u] < item.rem) g[u] = load4<true>(A.G + row + e[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < item.rem) {
