@@ -125,8 +125,8 @@ KERNEL_BYTES_PER_ELEM = {
 # counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("large_topk", "k_sel_compact_sgd"): 3_588_869_321,
-    ("large_topk", "k_mix_incremental"): 3_583_993_856,
+    ("large_topk", "k_sel_compact_sgd"): 3_588_875_055,
+    ("large_topk", "k_mix_incremental"): 3_583_998_976,
 }
 
 
