@@ -15,7 +15,8 @@
  *   - pointers named *_dev are device pointers, *_host are host pointers;
  *   - device buffers are owned by the caller (allocated e.g. with torch); the
  *     library allocates no device memory, it only carves up the workspace;
- *   - work is enqueued on the caller's stream and the calls return without
+ *   - work is enqueued on the caller's stream (one documented exception: the look-ahead
+ *     selection of RANDK, see choco_set_lookahead) and the calls return without
  *     synchronising, except choco_metrics, choco_last_scalars, choco_layer_scalars,
  *     choco_profile_report, choco_sync and (for QSGD) choco_pack_messages;
  *   - inputs must be finite; NaN/Inf give unspecified selections.
@@ -230,6 +231,15 @@ int choco_set_step(choco_ctx *ctx, uint64_t t);
    The events themselves are host-side objects; no device memory is allocated. */
 int choco_set_profiling(choco_ctx *ctx, int enable);
 int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
+
+/* RANDK in whole-vector mode with d <= 327,680: the mask of a step depends on (seed, step,
+   worker) only (Appendix C, random_a: the receiver can recover it from the seed), so while
+   one step's messages and mix run on the caller's stream the library already selects the
+   NEXT step's mask on a stream of its own (created by choco_init, default priority, joined
+   with events; no device memory is allocated).  Results do not change.  On by default
+   where it applies; switch it off (enable = 0) if every call must leave all of its work
+   on the caller's stream, e.g. under stream capture.  A no-op for other configurations. */
+int choco_set_lookahead(choco_ctx *ctx, int enable);
 
 int choco_sync(choco_ctx *ctx);    /* hipStreamSynchronize on the context's stream */
 /* Frees the context (host memory and its profiling events) without waiting for the stream:

@@ -23,7 +23,7 @@ EXPORTS = [
     "choco_set_capture", "choco_last_scalars", "choco_layer_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
     "choco_profile_report", "choco_paper_message_bits", "choco_message_bytes", "choco_pack_messages",
-    "choco_unpack_messages",
+    "choco_unpack_messages", "choco_set_lookahead",
 ]
 
 
@@ -95,6 +95,7 @@ def lib():
         L.choco_get_step.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.choco_set_step.argtypes = [vp, ctypes.c_uint64]
         L.choco_sync.argtypes = [vp]
+        L.choco_set_lookahead.argtypes = [vp, ctypes.c_int]
         L.choco_set_profiling.argtypes = [vp, ctypes.c_int]
         L.choco_profile_report.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t]
         L.choco_destroy.argtypes = [vp]
@@ -315,6 +316,9 @@ class Choco:
 
     def set_step(self, t):
         _check(lib().choco_set_step(self.ctx, int(t)), "choco_set_step")
+
+    def set_lookahead(self, on):
+        _check(lib().choco_set_lookahead(self.ctx, 1 if on else 0), "choco_set_lookahead")
 
     def sync(self):
         _check(lib().choco_sync(self.ctx), "choco_sync")

@@ -24,6 +24,19 @@ struct choco_ctx {
   choco_config cfg;       // scalar fields as given (host CSR pointers are not kept)
   Args args;              // kernel arguments (device pointers into the workspace)
   hipStream_t stream;
+  // random_a on short rows: the mask of a step depends on (seed, step, worker) only, so while
+  // a step's messages and mix run on the caller's stream the NEXT step's selection already
+  // runs on this one.  Two copies of the kept-index lists and of the bitmap take turns.
+  hipStream_t aux_stream;
+  hipEvent_t ev_fork, ev_ahead;
+  bool lookahead;         // the configuration allows it and it has not been switched off
+  bool can_lookahead;     // the configuration allows it (random_a, whole-vector mode, short rows)
+  bool ahead_pending;     // a selection is in flight (or done) on aux_stream and not yet joined
+  bool ahead_valid;       // ... and it is the selection of step ahead_t
+  uint64_t ahead_t;
+  int32_t* sel_idx_buf[2];
+  uint32_t* bitmap_buf[2];
+  int last_buf;           // which copy the last finished step used
   int32_t maxdeg;
   int32_t nnz;
   bool sparse;            // top_a / random_a
@@ -62,7 +75,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
-      chunk_layer, wire, wire_word_off, wire_plane_off, mpart, mout, total;
+      chunk_layer, wire, wire_word_off, wire_plane_off, sel_idx2, bitmap2, mpart, mout, total;
   int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
@@ -225,6 +238,10 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.bitmap_words = (guessed && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
+  // second copies for the look-ahead selection of random_a (short rows, whole-vector mode)
+  const bool ahead = c.compressor == CHOCO_Q_RANDK && L.bitmap_words > 0;
+  L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
+  L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
@@ -307,6 +324,29 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
   } while (0)
 
 #define LAUNCH_CHECK(ctx) HIP_TRY(ctx, hipGetLastError())
+
+// Frees the host-side objects of a context (its own stream and events; never device memory).
+void release_ctx(choco_ctx* ctx) {
+  if (ctx->aux_stream) {
+    (void)hipStreamSynchronize(ctx->aux_stream);
+    (void)hipStreamDestroy(ctx->aux_stream);
+  }
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_ahead) (void)hipEventDestroy(ctx->ev_ahead);
+  for (hipEvent_t e : ctx->ev_begin) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ctx->ev_end) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+// The caller's stream waits for a look-ahead selection that is still in flight.
+int join_lookahead(choco_ctx* ctx) {
+  if (ctx->ahead_pending) {
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_ahead, 0));
+    ctx->ahead_pending = false;
+  }
+  return CHOCO_OK;
+}
+
 
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
@@ -501,7 +541,17 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
   const Args& C = x_touched ? A : F;
   const int kid_compact = (!x_touched && fused) ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
-  if (fuse_mix) {
+  // random_a on short rows: this step's selection may already have been made (or be under way)
+  // on the second stream; then it is only waited for
+  const bool ahead = COMP == Q_RANDK && ctx->lookahead && !ctx->profiling;
+  const bool selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
+  {
+    const int rc = join_lookahead(ctx);
+    if (rc != CHOCO_OK) return rc;
+  }
+  if (selected) {
+    // nothing to launch
+  } else if (fuse_mix) {
     if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 2>), cgrid, dim3(256), 0, C);
     else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
   } else {
@@ -519,9 +569,33 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     LAUNCH(ctx, KID_SEL_HIST_PARTS, (k_sel_hist_parts<COMP>), pgrid, dim3(1024), 0, A);
     LAUNCH(ctx, KID_SEL_EMIT_PARTS, (k_sel_emit_parts<COMP>), pgrid, dim3(1024), 0, A);
     LAUNCH(ctx, KID_SEL_FINISH, (k_sel_finish<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-  } else {
+  } else if (!selected) {
     LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
            (size_t)A.bitmap_words * sizeof(uint32_t), A);
+  }
+  ctx->ahead_valid = false;
+  if (ahead) {
+    // the NEXT step's selection, into the other copy of the lists and of the bitmap, side by
+    // side with the rest of this step (it reads no state: the keys are Philox words)
+    Args P = A;
+    P.G = nullptr;
+    P.M = nullptr;
+    P.deferred_sgd = 0;
+    const uint64_t tn = ctx->t + 1;
+    P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
+    P.t_hi = (uint32_t)(tn >> 32);
+    P.sel_idx = ctx->sel_idx_buf[tn & 1u];
+    P.bitmap = ctx->bitmap_buf[tn & 1u];
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    hipLaunchKernelGGL((k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), 0, ctx->aux_stream, P);
+    hipLaunchKernelGGL((k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), (size_t)A.bitmap_words * sizeof(uint32_t),
+                       ctx->aux_stream, P);
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
+    ctx->ahead_pending = true;
+    ctx->ahead_valid = true;
+    ctx->ahead_t = tn;
   }
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
@@ -692,10 +766,16 @@ int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   A.beta = u.beta;
   A.lambda = u.lambda;
   A.deferred_sgd = deferred ? 1 : 0;
+  const int buf = (int)(ctx->t & 1u);      // the two copies take turns (they are one and the same
+  A.sel_idx = ctx->sel_idx_buf[buf];       // unless the configuration selects ahead)
+  A.bitmap = ctx->bitmap_buf[buf];
   ctx->fused = u.g != nullptr;
   const int rc = ctx->nt ? gossip_any<true>(ctx, A) : gossip_any<false>(ctx, A);
   ctx->fused = false;
-  if (rc == CHOCO_OK) ctx->t += 1;
+  if (rc == CHOCO_OK) {
+    ctx->last_buf = buf;
+    ctx->t += 1;
+  }
   return rc;
 }
 
@@ -753,9 +833,9 @@ WireArgs wire_args(const choco_ctx* ctx) {
   Wa.layer_plane_off = ctx->wire_plane_off;
   Wa.layer_scale = A.layer_scale;
   Wa.k = A.k;
-  Wa.sel_idx = A.sel_idx;
+  Wa.sel_idx = ctx->sel_idx_buf[ctx->last_buf];   // of the last finished step
   Wa.sel_val = A.sel_val;
-  Wa.bitmap = A.bitmap;
+  Wa.bitmap = ctx->bitmap_buf[ctx->last_buf];
   Wa.bitmap_words = A.bitmap_words;
   return Wa;
 }
@@ -809,6 +889,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->cfg.layer_len_host = nullptr;
   ctx->cfg.layer_k_host = nullptr;
   ctx->stream = (hipStream_t)cfg->stream;
+  ctx->aux_stream = nullptr;
+  ctx->ev_fork = ctx->ev_ahead = nullptr;
+  ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = ctx->ahead_valid = false;
+  ctx->ahead_t = 0;
+  ctx->last_buf = 0;
   ctx->maxdeg = maxdeg;
   ctx->nnz = nnz;
   ctx->sparse = is_sparse(cfg->compressor);
@@ -909,6 +994,20 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.keptmap = (uint8_t*)(base + L.keptmap);
   A.bitmap = (uint32_t*)(base + L.bitmap);
   A.bitmap_words = L.bitmap_words;
+  ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
+  ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
+  if (cfg->compressor == CHOCO_Q_RANDK && cfg->nlayers == 0 && L.bitmap_words > 0) {
+    ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
+    ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
+    hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
+    if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
+    if (se != hipSuccess) {
+      release_ctx(ctx);
+      return CHOCO_E_HIP;
+    }
+    ctx->lookahead = ctx->can_lookahead = true;
+  }
   A.randk_rescale = cfg->randk_rescale ? 1 : 0;
   A.randk_scale = (ctx->sparse && cfg->nlayers == 0) ? (float)((double)cfg->d / (double)cfg->k) : 1.0f;
   A.qsgd_biased = cfg->qsgd_biased ? 1 : 0;
@@ -1033,7 +1132,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   // the host buffers above are pageable: wait until the copies have read them
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) {
-    delete ctx;
+    release_ctx(ctx);
     return CHOCO_E_HIP;
   }
   *out = ctx;
@@ -1114,8 +1213,8 @@ int choco_last_selection(choco_ctx* ctx, int32_t* idx_dev, float* val_dev) {
   const Args& A = ctx->args;
   const size_t count = (size_t)A.n * (size_t)A.k;
   if (idx_dev)
-    HIP_TRY(ctx, hipMemcpyAsync(idx_dev, A.sel_idx, count * sizeof(int32_t), hipMemcpyDeviceToDevice,
-                                ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(idx_dev, ctx->sel_idx_buf[ctx->last_buf], count * sizeof(int32_t),
+                                hipMemcpyDeviceToDevice, ctx->stream));
   if (val_dev)
     HIP_TRY(ctx, hipMemcpyAsync(val_dev, A.sel_val, count * sizeof(float), hipMemcpyDeviceToDevice,
                                 ctx->stream));
@@ -1254,6 +1353,10 @@ int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
 int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
   if (!ctx || !scalars_host) return CHOCO_E_INVAL;
   if (ctx->nlayers > 0) return CHOCO_E_UNSUPPORTED;
+  {
+    const int rc = join_lookahead(ctx);   // the control blocks may be under the next step's selection
+    if (rc != CHOCO_OK) return rc;
+  }
   const Args& A = ctx->args;
   std::vector<WorkerCtl> ctl((size_t)A.n);
   HIP_TRY(ctx, hipMemcpyAsync(ctl.data(), A.ctl, ctl.size() * sizeof(WorkerCtl), hipMemcpyDeviceToHost,
@@ -1289,7 +1392,15 @@ int choco_get_step(choco_ctx* ctx, uint64_t* t_host) {
 
 int choco_set_step(choco_ctx* ctx, uint64_t t) {
   if (!ctx) return CHOCO_E_INVAL;
+  if (t != ctx->t) ctx->ahead_valid = false;   // a selection made ahead was for the old counter
   ctx->t = t;
+  return CHOCO_OK;
+}
+
+int choco_set_lookahead(choco_ctx* ctx, int enable) {
+  if (!ctx) return CHOCO_E_INVAL;
+  ctx->lookahead = ctx->can_lookahead && enable != 0;
+  if (!ctx->lookahead) ctx->ahead_valid = false;   // a selection already under way is joined and made again
   return CHOCO_OK;
 }
 
@@ -1332,9 +1443,7 @@ int choco_profile_report(choco_ctx* ctx, char* buf_host, size_t buf_bytes) {
 
 int choco_destroy(choco_ctx* ctx) {
   if (!ctx) return CHOCO_OK;
-  for (hipEvent_t e : ctx->ev_begin) (void)hipEventDestroy(e);
-  for (hipEvent_t e : ctx->ev_end) (void)hipEventDestroy(e);
-  delete ctx;
+  release_ctx(ctx);
   return CHOCO_OK;
 }
 

@@ -460,3 +460,30 @@ def test_row_stride_wider_than_the_vector(comp, order):
     pair.gpu.sync()
     assert not dense[:, d:].any()
     pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+def test_random_masks_selected_ahead_or_not_are_the_same(order):
+    # random_a on short rows selects the next step's mask on a second stream; switching that
+    # off, on again, moving the step counter and timing the kernels must not change a bit
+    n, d, k = 6, 30011, 300
+    X0 = synth.normal_state(n, d, seed=51)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=8, compressor=B.Q_RANDK, k=k, randk_rescale=1)
+    grads = synth.GradientStream(n, d, seed=12, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(12):
+            if t == 3:
+                pair.gpu.set_lookahead(False)
+            if t == 6:
+                pair.gpu.set_lookahead(True)
+            if t == 8:
+                pair.gpu.set_profiling(True)
+            if t == 10:
+                pair.gpu.set_profiling(False)
+            if t == 9:       # jump ahead: a mask selected for step 9 must not be used for step 40
+                pair.gpu.set_step(40)
+                pair.ref.t = 40
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="lookahead step %d" % t)
+    finally:
+        pair.close()
