@@ -36,6 +36,9 @@ struct choco_ctx {
   uint64_t ahead_t;
   int32_t* sel_idx_buf[2];
   uint32_t* bitmap_buf[2];
+  uint8_t* keptmap_buf[2];
+  double* layer_scal_buf[2];
+  int ahead_map_buf;      // layer by layer: the byte-map copy that holds a selection made ahead and not yet used (-1: none)
   int last_buf;           // which copy the last finished step used
   int32_t maxdeg;
   int32_t nnz;
@@ -75,7 +78,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
-      chunk_layer, wire, wire_word_off, wire_plane_off, sel_idx2, bitmap2, mpart, mout, total;
+      chunk_layer, wire, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, mpart, mout, total;
   int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
@@ -239,9 +242,12 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   // second copies for the look-ahead selection of random_a (short rows, whole-vector mode)
-  const bool ahead = c.compressor == CHOCO_Q_RANDK && L.bitmap_words > 0;
+  // (short rows in whole-vector mode: lists and bitmap; layer by layer: lists and byte map)
+  const bool ahead = c.compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || layered);
   L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
+  L.keptmap2 = take(ahead && layered ? (size_t)c.n * (size_t)ld : 0);
+  L.layer_scal2 = take(ahead && layered ? (size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double) : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
@@ -671,18 +677,62 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   const int kid = (C.G != nullptr) ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
   const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlarge - nmid;
   const int one_launch_blocks = nlarge + nmid + (nsmall + 15) / 16;
-  if ((int64_t)one_launch_blocks * A.n <= 256) {
-    // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the
-    // chip still is not full, so one launch does (a launch costs more than idle threads)
-    LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)one_launch_blocks, (unsigned)A.n),
-           dim3(1024), 0, C, (int32_t)0, (int32_t)(nlarge + nmid));
-  } else {
-    if (nlarge > 0)
-      LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0,
-             C, (int32_t)0, (int32_t)nlarge);
-    if (nmid + nsmall > 0)
-      LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
-             dim3(256), 0, C, (int32_t)nlarge, (int32_t)nmid);
+  // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the chip
+  // still is not full, so one launch does (a launch costs more than idle threads)
+  const bool one_launch = (int64_t)one_launch_blocks * A.n <= 256;
+  // the layer kernel(s), timed on the caller's stream or plain on the look-ahead stream
+  auto select_layers = [&](const Args& S, bool on_aux) {
+    auto go = [&](auto kernel, dim3 grid, dim3 block, int32_t first, int32_t nblock) {
+      if (on_aux) hipLaunchKernelGGL(kernel, grid, block, 0, ctx->aux_stream, S, first, nblock);
+      else LAUNCH(ctx, kid, kernel, grid, block, 0, S, first, nblock);
+    };
+    if (one_launch) {
+      go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)one_launch_blocks, (unsigned)A.n), dim3(1024), 0,
+         nlarge + nmid);
+    } else {
+      if (nlarge > 0) go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0, nlarge);
+      if (nmid + nsmall > 0)
+        go(k_layer_compress<COMP, 256, NT>, dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n), dim3(256),
+           nlarge, nmid);
+    }
+  };
+  // random_a: this step's masks may already have been drawn on the second stream
+  const bool ahead = COMP == Q_RANDK && ctx->lookahead && !ctx->profiling;
+  const bool selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
+  {
+    const int rc = join_lookahead(ctx);
+    if (rc != CHOCO_OK) return rc;
+  }
+  if (!selected && ctx->ahead_map_buf >= 0) {
+    // a selection made ahead is dropped (counter set, look-ahead or timing switched): its
+    // marks would never be cleared by an xhat update
+    const int64_t words = (int64_t)A.n * A.ld / 4;   // ld is a multiple of 4
+    LAUNCH(ctx, KID_XHAT_UPDATE, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+           (uint32_t*)ctx->keptmap_buf[ctx->ahead_map_buf], words);
+  }
+  ctx->ahead_map_buf = -1;
+  if (!selected) select_layers(C, false);
+  ctx->ahead_valid = false;
+  if (ahead) {
+    Args P = A;
+    P.G = nullptr;
+    P.M = nullptr;
+    P.deferred_sgd = 0;
+    const uint64_t tn = ctx->t + 1;
+    P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
+    P.t_hi = (uint32_t)(tn >> 32);
+    P.sel_idx = ctx->sel_idx_buf[tn & 1u];
+    P.keptmap = ctx->keptmap_buf[tn & 1u];
+    P.layer_scal = ctx->layer_scal_buf[tn & 1u];
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    select_layers(P, true);
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
+    ctx->ahead_pending = true;
+    ctx->ahead_valid = true;
+    ctx->ahead_t = tn;
+    ctx->ahead_map_buf = (int)(tn & 1u);
   }
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
   if (COMP == Q_RANDK)
@@ -769,6 +819,8 @@ int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   const int buf = (int)(ctx->t & 1u);      // the two copies take turns (they are one and the same
   A.sel_idx = ctx->sel_idx_buf[buf];       // unless the configuration selects ahead)
   A.bitmap = ctx->bitmap_buf[buf];
+  A.keptmap = ctx->keptmap_buf[buf];
+  if (ctx->nlayers > 0) A.layer_scal = ctx->layer_scal_buf[buf];
   ctx->fused = u.g != nullptr;
   const int rc = ctx->nt ? gossip_any<true>(ctx, A) : gossip_any<false>(ctx, A);
   ctx->fused = false;
@@ -894,6 +946,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = ctx->ahead_valid = false;
   ctx->ahead_t = 0;
   ctx->last_buf = 0;
+  ctx->ahead_map_buf = -1;
   ctx->maxdeg = maxdeg;
   ctx->nnz = nnz;
   ctx->sparse = is_sparse(cfg->compressor);
@@ -996,9 +1049,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.bitmap_words = L.bitmap_words;
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
   ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
-  if (cfg->compressor == CHOCO_Q_RANDK && cfg->nlayers == 0 && L.bitmap_words > 0) {
+  ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
+  if (cfg->compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || cfg->nlayers > 0)) {
     ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
-    ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
+    if (cfg->nlayers > 0) ctx->keptmap_buf[1] = (uint8_t*)(base + L.keptmap2);
+    else ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
     hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
@@ -1018,6 +1073,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.layer_work = (const LayerDesc*)(base + L.layer_work);
   A.layer_guess = (uint32_t*)(base + L.layer_guess);
   A.layer_scal = (double*)(base + L.layer_scal);
+  ctx->layer_scal_buf[0] = ctx->layer_scal_buf[1] = A.layer_scal;
+  if (ctx->can_lookahead && cfg->nlayers > 0) ctx->layer_scal_buf[1] = (double*)(base + L.layer_scal2);
   if (cfg->nlayers > 0) {
     int64_t sel_base = 0;
     for (int32_t l = 0; l < cfg->nlayers; ++l) {
@@ -1343,8 +1400,9 @@ int choco_set_capture(choco_ctx* ctx, int32_t* codes_dev) {
 
 int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
   if (!ctx || !scalars_host || ctx->nlayers == 0) return CHOCO_E_INVAL;
+
   const Args& A = ctx->args;
-  HIP_TRY(ctx, hipMemcpyAsync(scalars_host, A.layer_scal, (size_t)A.n * (size_t)A.nlayers * 4 * sizeof(double),
+  HIP_TRY(ctx, hipMemcpyAsync(scalars_host, ctx->layer_scal_buf[ctx->last_buf], (size_t)A.n * (size_t)A.nlayers * 4 * sizeof(double),
                               hipMemcpyDeviceToHost, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   return CHOCO_OK;

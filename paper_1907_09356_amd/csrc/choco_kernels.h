@@ -1763,6 +1763,12 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   *s = acc;
 }
 
+// p[0 .. words) = 0.  grid (ceil(words / 256))
+__global__ __launch_bounds__(256) void k_zero_words(uint32_t* p, int64_t words) {
+  const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (o < words) p[o] = 0u;
+}
+
 // xhat_j[e] += q_j[e] for the kept entries (Algorithm 1 line 6); clears the
 // kept-map bytes it used.  grid (ceil(k/256), n)
 __global__ __launch_bounds__(256) void k_xhat_update(Args A) {

@@ -83,6 +83,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     *sh.emit = 0;
     *sh.list_n = 0;
   }
+  layer_sync<THREADS>();   // no wave may count into the list before it is reset (waves start in any order)
 
   // ---- load: v = x - xhat (after the local update, if this pass carries it) ----
   vf4 v[kLayerVecs];

@@ -179,3 +179,35 @@ def test_layers_with_a_wider_row_stride(name, q):
         pair.check(det, tag="%s wide rows step %d" % (name, t))
     assert not pair.gpu.xhat()[:, pair.d:].any()
     pair.close()
+
+
+@pytest.mark.parametrize("order", ORDERS)
+def test_layered_random_masks_selected_ahead_or_not_are_the_same(order):
+    # layer-wise random_a draws the next step's masks on a second stream; switching that off
+    # and on, moving the step counter (a mask drawn for step 9 is dropped, its marks with it)
+    # and timing the kernels must not change a bit
+    layers = mixed_layers(fraction=0.03)
+    n = 6
+    X0, inside = padded_state(n, layers, seed=21)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=9, layers=layers, compressor=binding.Q_RANDK,
+                randk_rescale=1)
+    grads = synth.GradientStream(n, pair.d, seed=13, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(13):
+            if t == 3:
+                pair.gpu.set_lookahead(False)
+            if t == 6:
+                pair.gpu.set_lookahead(True)
+            if t == 8:
+                pair.gpu.set_profiling(True)
+            if t == 10:
+                pair.gpu.set_profiling(False)
+            if t == 9 or t == 12:   # 12: dropped while the look-ahead is on and a mask is pending
+                pair.gpu.set_step(40 + t)
+                pair.ref.t = 40 + t
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step(G, 0.05)
+            pair.check(det, tag="layered lookahead step %d" % t)
+    finally:
+        pair.close()
