@@ -80,6 +80,16 @@ WORKLOADS = {
     "large_sign_layers": dict(desc="large-model shape, per layer: n=8 ring, 14 layers of a 3-layer LSTM language "
                                    "model (d=31,819,578), scaled sign per layer, gamma=0.01, lr=0.05",
                               n=8, layers="lstm", topo="ring", comp="sign", gamma=0.01, lr=0.05, bias_std=0.0),
+    # the same layers, sparsified: the seven long layers take the guessed-threshold select one
+    # after the other, the biases the layer kernel
+    "large_topk_layers": dict(desc="large-model shape, per layer: n=8 ring, 14 layers of a 3-layer LSTM language "
+                                   "model (d=31,819,578), top-k 0.1% of every layer, gamma=0.01, lr=0.05",
+                              n=8, layers="lstm", fraction=0.001, topo="ring", comp="topk", gamma=0.01, lr=0.05,
+                              bias_std=0.0),
+    "large_randk_layers": dict(desc="large-model shape, per layer: n=8 ring, 14 layers of a 3-layer LSTM language "
+                                    "model (d=31,819,578), random-k 0.1% of every layer, gamma=0.01, lr=0.05",
+                               n=8, layers="lstm", fraction=0.001, topo="ring", comp="randk", gamma=0.01, lr=0.05,
+                               bias_std=0.0),
 }
 
 
@@ -254,8 +264,13 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
                 bpe += 8                                   # + read and write the momentum memory
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
                 per_launch = bpe * elems
-                if name.startswith("k_layer_compress"):
-                    per_launch /= entry["launches_per_step"]   # its launches share one pass over the rows
+                if "layers" in w and (name.startswith("k_layer_compress") or name.startswith("k_sel_compact")):
+                    # layers above 40,960 entries go through k_sel_compact, the others through
+                    # k_layer_compress; the launches of each share its part of one pass over the rows
+                    lengths = layer_table_of(w)[1]
+                    long_part = float(lengths[lengths > 40960].sum()) / float(lengths.sum())
+                    per_launch *= long_part if name.startswith("k_sel_compact") else 1.0 - long_part
+                    per_launch /= entry["launches_per_step"]
                 entry["alg_bytes_per_launch"] = per_launch
                 entry["alg_GBps"] = per_launch / (avg_ms * 1e-3) / 1e9
             kernels[name] = entry

@@ -98,11 +98,11 @@ typedef struct {
      The layers must tile the vector in order, each start padded to a multiple of 4:
      layer_start[0] = 0, layer_start[l+1] = layer_start[l] + layer_len[l] rounded up to a
      multiple of 4, d = layer_start[nlayers-1] + layer_len[nlayers-1].  The padding entries
-     are never transmitted (keep them zero in X and G).  For TOPK and RANDK a layer may
-     have at most CHOCO_MAX_LAYER_LEN entries (one workgroup selects it out of its
-     registers); SIGN and QSGD take layers of any length.  IDENTITY, a non-default
-     mix_form and longer TOPK / RANDK layers are CHOCO_E_UNSUPPORTED.  layer_k_host may be
-     NULL for SIGN and QSGD.                                                              */
+     are never transmitted (keep them zero in X and G).  Layers may have any length; for
+     TOPK and RANDK one workgroup selects a layer of up to CHOCO_MAX_LAYER_LEN entries out
+     of its registers and longer layers take the whole-vector select one after the other
+     (they cost workspace for its candidate lists).  IDENTITY and a non-default mix_form
+     are CHOCO_E_UNSUPPORTED with layers.  layer_k_host may be NULL for SIGN and QSGD.     */
   int32_t nlayers;
   const int64_t *layer_start_host;
   const int64_t *layer_len_host;
@@ -182,7 +182,9 @@ int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
    (n * nlayers * 4, worker-major) from the last step.  SIGN: {||v_l||_1, scale, 0, 0};
    QSGD: {sum v_l^2, ||v_l||_2, s/||v_l||_2, ||v_l||_2/(tau_l s)}; TOPK/RANDK: {threshold
    key, entries kept at the threshold key, entries holding that key, 1 if the guessed
-   bracket held the threshold and 0 if the whole layer was searched}.  With
+   bracket held the threshold and 0 if the whole layer was searched}; for a layer above
+   CHOCO_MAX_LAYER_LEN {threshold key, 0, 0, 0 if the select had to scan the layer itself
+   and 1 otherwise}.  With
    layers, choco_last_selection returns sum(layer_k) pairs per worker, layer after layer,
    and choco_last_scalars is CHOCO_E_UNSUPPORTED.  Synchronises the stream. */
 int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);

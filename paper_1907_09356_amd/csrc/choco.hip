@@ -20,6 +20,25 @@
 
 using namespace choco;
 
+// How the guessed-threshold select (Appendix C: top_a, random_a) is run on one "row" of d
+// entries of which k are kept: the whole vector, or one long layer of it.
+struct SelectPlan {
+  int64_t d, k;
+  uint32_t cand_cap, seg_cap;          // candidate list: aimed-at total and capacity of a sub-list
+  uint32_t extra, want, delta0;        // see Args
+  uint32_t guess0, shift0;             // first guess and bin width (all ones: none, the first step falls back)
+  uint32_t sample_stride, sample_need; // fallback histogram
+  bool multipart;                      // long candidate lists: three multi-block launches instead of one block
+  bool fallback_chain;                 // long rows: histogram passes repair a failed guess (else a row scan)
+};
+
+// A layer too long for the register-resident layer kernel: it takes the select chain of the
+// whole-vector path on its own piece of the rows.
+struct LongLayer {
+  int32_t start, len, k, sel_base, id;
+  SelectPlan plan;
+};
+
 struct choco_ctx {
   choco_config cfg;       // scalar fields as given (host CSR pointers are not kept)
   Args args;              // kernel arguments (device pointers into the workspace)
@@ -50,7 +69,11 @@ struct choco_ctx {
   bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   int nlayers;            // > 0: the operator is applied layer by layer
-  int nlarge, nmid;       // layers (by falling length) that take a 1024- / a 256-thread workgroup
+  int nlarge, nmid;       // layers (by falling length, after the long ones) that take a 1024- / a 256-thread workgroup
+  SelectPlan plan;        // whole-vector top_a / random_a
+  std::vector<LongLayer> long_layers;   // top_a / random_a layer by layer: layers above CHOCO_MAX_LAYER_LEN
+  bool long_silent;       // one of them keeps nothing (its pass cannot carry the local update)
+  bool long_rows;         // d > 2^21: four 4-vectors per thread in the streaming kernels
   uint64_t t;             // step counter
   uint32_t* wire;         // device scratch of the message encoder: n status words, then counters and index slots
   const int64_t* wire_word_off;   // layer by layer: where each layer's message starts / prefix of plane lengths
@@ -113,14 +136,12 @@ int check_layers(const choco_config* c) {
   const bool sparse = is_sparse(c->compressor);
   if (sparse && !c->layer_k_host) return CHOCO_E_INVAL;
   int64_t expect = 0, end = 0, ktot = 0;
-  bool too_long = false;
   for (int32_t l = 0; l < c->nlayers; ++l) {
     const int64_t start = c->layer_start_host[l], len = c->layer_len_host[l];
     if (start != expect || len < 1) return CHOCO_E_INVAL;
     end = start + len;
     if (end > c->d) return CHOCO_E_INVAL;
     expect = (end + 3) / 4 * 4;
-    if (sparse && len > kMaxLayerLen) too_long = true;   // selected out of one workgroup's registers
     if (sparse) {
       const int64_t k = c->layer_k_host[l];
       if (k < 0 || k > len) return CHOCO_E_INVAL;
@@ -128,7 +149,7 @@ int check_layers(const choco_config* c) {
     }
   }
   if (end != c->d || (sparse && ktot < 1)) return CHOCO_E_INVAL;
-  if (too_long || c->compressor == CHOCO_Q_IDENTITY || c->mix_form != CHOCO_MIX_AUTO)
+  if (c->compressor == CHOCO_Q_IDENTITY || c->mix_form != CHOCO_MIX_AUTO)
     return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
@@ -155,19 +176,108 @@ int check_scalars(const choco_config* c) {
 
 // Candidates wanted beyond k so that the guess survives the step-to-step drift of the
 // threshold (top_a) or the binomial spread of the count (random_a).
-double extra_candidates(const choco_config& c) {
-  const double kk = (double)c.k;
+double extra_candidates(int64_t k) {
+  const double kk = (double)k;
   return std::min(std::max(0.5 * kk, 6.0 * std::sqrt(kk) + 32.0), 2147483647.0);
 }
 
 // Entries the guess aims to leave above it beyond the k kept ones.  top_a: the k entries
 // kept in a step are absorbed by xhat and drop out, so the next step's k largest are (about)
 // this step's ranks k+1..2k; random_a draws afresh every step.
-double want_candidates(const choco_config& c) {
-  return extra_candidates(c) + (c.compressor == CHOCO_Q_TOPK ? (double)c.k : 0.0);
+double want_candidates(int compressor, int64_t k) {
+  return extra_candidates(k) + (compressor == CHOCO_Q_TOPK ? (double)k : 0.0);
 }
 
-double expected_candidates(const choco_config& c) { return (double)c.k + want_candidates(c); }
+double expected_candidates(int compressor, int64_t k) { return (double)k + want_candidates(compressor, k); }
+
+SelectPlan plan_select(int compressor, int64_t d, int64_t k) {
+  SelectPlan P{};
+  P.d = d;
+  P.k = k;
+  int64_t cap = 4 * k;
+  if (cap < d / 128) cap = d / 128;
+  if (cap < 8192) cap = 8192;
+  if (cap > d) cap = d;
+  P.cand_cap = (uint32_t)cap;
+  // sub-lists: block b of a worker appends to sub-list b % kSegs; each gets twice its even
+  // share of the capacity, but never more than the blocks feeding it can produce
+  const int64_t per_block = 256 * kCompactVecs * 4;   // (short rows use half-size blocks: the bound below still holds)
+  const int64_t nblocks = (d + per_block - 1) / per_block;
+  const int64_t feeders = (nblocks + kSegs - 1) / kSegs;
+  int64_t seg_cap = std::max<int64_t>((2 * cap + kSegs - 1) / kSegs, 1024);
+  seg_cap = std::min<int64_t>(seg_cap, feeders * per_block);
+  P.seg_cap = (uint32_t)seg_cap;
+  P.multipart = expected_candidates(compressor, k) > 16384.0;
+  // A failed guess (first step, or the distribution moved) is repaired by three extra passes
+  // (sampled histogram, new guess, rebuild) that are launched every step and normally exit at
+  // once.  For short rows even those idle launches show, and the select kernel's own row scan
+  // (one block per worker) is quick enough, so they are left out.
+  P.fallback_chain = d > ((int64_t)1 << 21);
+  const double kk = (double)k, dd = (double)d;
+  const double extra = extra_candidates(k);
+  P.extra = (uint32_t)extra;
+  P.want = (uint32_t)std::min(want_candidates(compressor, k), 4294967295.0);
+  P.guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
+  P.shift0 = 0;
+  if (compressor == CHOCO_Q_RANDK) {
+    // keys are uniform on [0, 2^32): the k + extra largest start near (1 - (k+extra)/d) 2^32
+    const double frac = std::min(1.0, (kk + extra) / dd);
+    const double g = (1.0 - frac) * 4294967296.0;
+    P.guess0 = g <= 0.0 ? 0u : (uint32_t)std::min(g, 4294967295.0);
+    // 2048 candidate bins over the keys above the guess
+    const uint64_t range = 4294967296ull - (uint64_t)P.guess0;
+    while ((range >> P.shift0) > (uint64_t)kBins) ++P.shift0;
+    const double d0 = std::min(extra / dd, 1.0) * 4294967296.0;
+    P.delta0 = (uint32_t)std::min(std::max(d0, 1.0), 4294967295.0);
+  } else {
+    P.delta0 = 1u << 19;   // about 6 % in magnitude
+  }
+  // fallback histogram: aim the rebuilt list at max(2k + extra, capacity / 4), at most
+  // half the capacity, and sample the row so that the aim is still >= ~2000 samples
+  double aim = std::max(2.0 * kk + extra, 0.25 * (double)P.cand_cap);
+  aim = std::min(aim, std::max(0.5 * (double)P.cand_cap, kk));
+  uint32_t stride = 1;
+  if (d > (1 << 21)) {
+    stride = 16;
+    while (stride > 1 && aim / stride < 2048.0) stride >>= 1;
+  }
+  P.sample_stride = stride;
+  P.sample_need = (uint32_t)std::max(1.0, std::ceil(aim / stride));
+  return P;
+}
+
+// The layers of a top_a / random_a configuration that are too long for the layer kernel.
+std::vector<LongLayer> long_layers_of(const choco_config& c) {
+  std::vector<LongLayer> out;
+  if (c.nlayers <= 0 || !is_sparse(c.compressor)) return out;
+  int64_t sel_base = 0;
+  for (int32_t l = 0; l < c.nlayers; ++l) {
+    const int64_t len = c.layer_len_host[l], k = c.layer_k_host[l];
+    if (len > kMaxLayerLen) {
+      LongLayer B{};
+      B.start = (int32_t)c.layer_start_host[l];
+      B.len = (int32_t)len;
+      B.k = (int32_t)k;
+      B.sel_base = (int32_t)sel_base;
+      B.id = l;
+      B.plan = plan_select(c.compressor, len, std::max<int64_t>(k, 1));
+      out.push_back(B);
+    }
+    sel_base += k;
+  }
+  return out;
+}
+
+// Put the plan's numbers into a kernel argument block.
+void apply_plan(Args& A, const SelectPlan& P) {
+  A.cand_cap = P.cand_cap;
+  A.seg_cap = P.seg_cap;
+  A.extra = P.extra;
+  A.want = P.want;
+  A.delta0 = P.delta0;
+  A.sample_stride = P.sample_stride;
+  A.sample_need = P.sample_need;
+}
 
 int magnitude_bits(int levels) {
   int mb = 0;
@@ -193,7 +303,13 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   const size_t state = (size_t)c.n * (size_t)ld * sizeof(float);
   const bool sparse = is_sparse(c.compressor);
   const bool layered = c.nlayers > 0;
-  const bool guessed = sparse && !layered;   // whole-row select by guessed threshold
+  // selects by guessed threshold: the whole row, or every long layer in turn (they share the
+  // candidate lists and histograms, each has control blocks of its own)
+  const std::vector<LongLayer> longs = long_layers_of(c);
+  const bool guessed = sparse && (!layered || !longs.empty());
+  std::vector<SelectPlan> plans;
+  if (sparse && !layered) plans.push_back(plan_select(c.compressor, c.d, c.k));
+  for (const LongLayer& B : longs) plans.push_back(B.plan);
   const int64_t kept = kept_per_worker(c);
   size_t off = 0;
   auto take = [&off](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -202,7 +318,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.row_ptr = take((size_t)(c.n + 1) * sizeof(int32_t));
   L.col = take((size_t)nnz * sizeof(int32_t));
   L.w = take((size_t)nnz * sizeof(float));
-  L.ctl = take((size_t)c.n * sizeof(WorkerCtl));
+  L.ctl = take((size_t)c.n * std::max<size_t>(1, longs.size()) * sizeof(WorkerCtl));
   L.nchunks = (int32_t)((c.d + kChunk - 1) / kChunk);
   L.ngroups = (L.nchunks + kGroup - 1) / kGroup;
   const bool dense_stat = c.compressor == CHOCO_Q_SIGN || c.compressor == CHOCO_Q_QSGD;
@@ -210,40 +326,30 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.chunk_sums = take(dense_stat && c.order == CHOCO_ORDER_MIX_THEN_COMPRESS
                           ? (size_t)c.n * (size_t)L.nchunks * sizeof(double) : 0);
   L.group_sums = take(dense_stat ? (size_t)c.n * (size_t)L.ngroups * sizeof(double) : 0);
-  int64_t cap = 0;
-  if (guessed) {
-    cap = 4 * c.k;
-    if (cap < c.d / 128) cap = c.d / 128;
-    if (cap < 8192) cap = 8192;
-    if (cap > c.d) cap = c.d;
+  int64_t cap = 0, seg_cap = 0;
+  bool multipart = false;
+  for (const SelectPlan& P : plans) {
+    cap = std::max<int64_t>(cap, P.cand_cap);
+    seg_cap = std::max<int64_t>(seg_cap, P.seg_cap);
+    multipart = multipart || P.multipart;
   }
   L.cand_cap = (uint32_t)cap;
-  // sub-lists: block b of a worker appends to sub-list b % kSegs; each gets twice its even
-  // share of the capacity, but never more than the blocks feeding it can produce
-  int64_t seg_cap = 0;
-  if (guessed) {
-    const int64_t per_block = 256 * kCompactVecs * 4;   // (short rows use half-size blocks: the bound below still holds)
-    const int64_t nblocks = (c.d + per_block - 1) / per_block;
-    const int64_t feeders = (nblocks + kSegs - 1) / kSegs;
-    seg_cap = std::max<int64_t>((2 * cap + kSegs - 1) / kSegs, 1024);
-    seg_cap = std::min<int64_t>(seg_cap, feeders * per_block);
-  }
   L.seg_cap = (uint32_t)seg_cap;
   L.hist16 = take(guessed ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
   L.cand = take(guessed ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(float) : 0);
-  L.multipart = guessed && expected_candidates(c) > 16384.0;
+  L.multipart = guessed && multipart;
   L.hist_parts = take(L.multipart ? (size_t)c.n * kRefineParts * kBins * sizeof(uint32_t) : 0);
   L.small_list = take(L.multipart ? (size_t)c.n * kSmallCap * sizeof(uint2) : 0);
   // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
   // beside its other arrays), else one byte per entry
-  L.bitmap_words = (guessed && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
+  L.bitmap_words = (guessed && !layered && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   // second copies for the look-ahead selection of random_a (short rows, whole-vector mode)
   // (short rows in whole-vector mode: lists and bitmap; layer by layer: lists and byte map)
-  const bool ahead = c.compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || layered);
+  const bool ahead = c.compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || (layered && longs.empty()));
   L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
   L.keptmap2 = take(ahead && layered ? (size_t)c.n * (size_t)ld : 0);
@@ -461,7 +567,7 @@ template <bool NT>
 void launch_mix_incremental(choco_ctx* ctx, const Args& A, bool carries_update) {
   const int kid = carries_update ? KID_MIX_INCREMENTAL_SGD : KID_MIX_INCREMENTAL;
   const int32_t nvec = (A.d + 3) >> 2;
-  if (ctx->fallback_chain)   // long rows
+  if (ctx->long_rows)
     LAUNCH(ctx, kid, (k_mix_incremental<NT, 4>), chunk_grid(nvec, A.n, 4), dim3(256), 0, A);
   else
     LAUNCH(ctx, kid, (k_mix_incremental<NT, 2>), chunk_grid(nvec, A.n, 2), dim3(256), 0, A);
@@ -656,8 +762,56 @@ int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
   return CHOCO_OK;
 }
 
+// The guessed-threshold select of one long layer (number `which` of ctx->long_layers): the
+// launches of the whole-vector path on argument blocks that point at the layer's piece of the
+// rows.  C is the block for the first pass (it may carry the local update), A the one without.
+template <int COMP, bool NT>
+void select_long_layer(choco_ctx* ctx, const Args& C, const Args& A, int which) {
+  const LongLayer& B = ctx->long_layers[(size_t)which];
+  if (B.k == 0) return;
+  auto narrow = [&](const Args& src) {
+    Args R = src;
+    R.X += B.start;
+    R.Xhat += B.start;
+    if (R.G) R.G += B.start;
+    if (R.M) R.M += B.start;
+    R.keptmap += B.start;
+    R.d = B.len;
+    R.k = B.k;
+    R.ctl = src.ctl + (int64_t)which * src.n;
+    R.sel_idx += B.sel_base;     // sel_stride stays the worker's whole list
+    R.sel_val += B.sel_base;
+    R.idx_base = B.start;
+    R.vec_base = (uint32_t)B.start >> 2;
+    apply_plan(R, B.plan);
+    return R;
+  };
+  const Args Cl = narrow(C), Al = narrow(A);
+  const int kid_compact = Cl.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
+  const int32_t nvec = (B.len + 3) >> 2;
+  if (B.plan.fallback_chain) {
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), chunk_grid(nvec, A.n, kCompactVecs),
+           dim3(256), 0, Cl);
+    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, Al);
+    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
+    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, Al);
+  } else {
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), chunk_grid(nvec, A.n, 2), dim3(256), 0, Cl);
+  }
+  if (B.plan.multipart) {
+    const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST_PARTS, (k_sel_hist_parts<COMP>), pgrid, dim3(1024), 0, Al);
+    LAUNCH(ctx, KID_SEL_EMIT_PARTS, (k_sel_emit_parts<COMP>), pgrid, dim3(1024), 0, Al);
+    LAUNCH(ctx, KID_SEL_FINISH, (k_sel_finish<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
+  } else {
+    LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
+  }
+}
+
 // Layer-wise top_a / random_a: one workgroup or wave per (worker, layer) selects the layer's
-// kept entries; the message kernels and the mix are those of the whole-row path.
+// kept entries (layers above CHOCO_MAX_LAYER_LEN: the select chain of the whole-vector path, layer
+// after layer); the message kernels and the mix are those of the whole-row path.
 template <int COMP, bool NT>
 int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   Args A = F;
@@ -675,7 +829,8 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   Args C = (x_touched || COMP == Q_RANDK) ? A : F;
   if (COMP == Q_RANDK) C.G = nullptr;
   const int kid = (C.G != nullptr) ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
-  const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlarge - nmid;
+  const int nlong = (int)ctx->long_layers.size();   // first in the work list, not for the layer kernel
+  const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlong - nlarge - nmid;
   const int one_launch_blocks = nlarge + nmid + (nsmall + 15) / 16;
   // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the chip
   // still is not full, so one launch does (a launch costs more than idle threads)
@@ -687,13 +842,15 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
       else LAUNCH(ctx, kid, kernel, grid, block, 0, S, first, nblock);
     };
     if (one_launch) {
-      go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)one_launch_blocks, (unsigned)A.n), dim3(1024), 0,
-         nlarge + nmid);
+      if (one_launch_blocks > 0)
+        go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)one_launch_blocks, (unsigned)A.n), dim3(1024), nlong,
+           nlarge + nmid);
     } else {
-      if (nlarge > 0) go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0, nlarge);
+      if (nlarge > 0)
+        go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), nlong, nlarge);
       if (nmid + nsmall > 0)
         go(k_layer_compress<COMP, 256, NT>, dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n), dim3(256),
-           nlarge, nmid);
+           nlong + nlarge, nmid);
     }
   };
   // random_a: this step's masks may already have been drawn on the second stream
@@ -712,6 +869,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   }
   ctx->ahead_map_buf = -1;
   if (!selected) select_layers(C, false);
+  for (int b = 0; b < nlong; ++b) select_long_layer<COMP, NT>(ctx, C, A, b);   // (no look-ahead with long layers)
   ctx->ahead_valid = false;
   if (ahead) {
     Args P = A;
@@ -774,6 +932,7 @@ int gossip_any(choco_ctx* ctx, const Args& A) {
 // so that the local update can ride on it?
 bool first_pass_can_carry_sgd(const choco_ctx* ctx) {
   const int comp = ctx->cfg.compressor;
+  if (ctx->long_silent) return false;   // the select pass skips a long layer that keeps nothing
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX)
     return comp == CHOCO_Q_SIGN || comp == CHOCO_Q_QSGD || comp == CHOCO_Q_TOPK;
@@ -952,11 +1111,14 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sparse = is_sparse(cfg->compressor);
   ctx->mix_form = resolve_mix_form(*cfg);
   ctx->rpw = pick_rpw(cfg->n);
-  // A failed guess (first step, or the distribution moved) is repaired by three extra passes
-  // (sampled histogram, new guess, rebuild) that are launched every step and normally exit at
-  // once.  For short rows even those idle launches show, and the select kernel's own row scan
-  // (one block per worker) is quick enough, so they are left out.
-  ctx->fallback_chain = cfg->d > ((int64_t)1 << 21) && cfg->nlayers == 0;
+  ctx->plan = SelectPlan{};
+  ctx->plan.guess0 = 0xFFFFFFFFu;
+  if (ctx->sparse && cfg->nlayers == 0) ctx->plan = plan_select(cfg->compressor, cfg->d, cfg->k);
+  ctx->fallback_chain = ctx->plan.fallback_chain;
+  ctx->long_rows = cfg->d > ((int64_t)1 << 21);
+  ctx->long_layers = long_layers_of(*cfg);
+  ctx->long_silent = false;
+  for (const LongLayer& B : ctx->long_layers) ctx->long_silent = ctx->long_silent || B.k == 0;
   ctx->nlayers = cfg->nlayers;
   // Non-temporal (streaming) or ordinary cached accesses, by the size of one state array;
   // measured on MI355X with 64 workers on a ring unless said otherwise (ms per step, NT / cached):
@@ -1005,43 +1167,14 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.k = kept_per_worker(*cfg);
   A.hist16 = (uint32_t*)(base + L.hist16);
   A.cand = (uint2*)(base + L.cand);
-  A.cand_cap = L.cand_cap;
-  A.seg_cap = L.seg_cap;
   A.hist_parts = (uint32_t*)(base + L.hist_parts);
   A.small_list = (uint2*)(base + L.small_list);
-  ctx->multipart = L.multipart;
-  uint32_t guess0 = 0xFFFFFFFFu;   // top_a: no guess yet, the first step takes the fallback
-  uint32_t shift0 = 0;
-  if (ctx->sparse && cfg->nlayers == 0) {
-    const double kk = (double)cfg->k, dd = (double)cfg->d;
-    const double extra = extra_candidates(*cfg);
-    A.extra = (uint32_t)extra;
-    A.want = (uint32_t)std::min(want_candidates(*cfg), 4294967295.0);
-    if (cfg->compressor == CHOCO_Q_RANDK) {
-      // keys are uniform on [0, 2^32): the k + extra largest start near (1 - (k+extra)/d) 2^32
-      const double frac = std::min(1.0, (kk + extra) / dd);
-      const double g = (1.0 - frac) * 4294967296.0;
-      guess0 = g <= 0.0 ? 0u : (uint32_t)std::min(g, 4294967295.0);
-      // 2048 candidate bins over the keys above the guess
-      const uint64_t range = 4294967296ull - (uint64_t)guess0;
-      while ((range >> shift0) > (uint64_t)kBins) ++shift0;
-      const double d0 = std::min(extra / dd, 1.0) * 4294967296.0;
-      A.delta0 = (uint32_t)std::min(std::max(d0, 1.0), 4294967295.0);
-    } else {
-      A.delta0 = 1u << 19;   // about 6 % in magnitude
-    }
-    // fallback histogram: aim the rebuilt list at max(2k + extra, capacity / 4), at most
-    // half the capacity, and sample the row so that the aim is still >= ~2000 samples
-    double aim = std::max(2.0 * kk + extra, 0.25 * (double)L.cand_cap);
-    aim = std::min(aim, std::max(0.5 * (double)L.cand_cap, kk));
-    uint32_t stride = 1;
-    if (cfg->d > (1 << 21)) {
-      stride = 16;
-      while (stride > 1 && aim / stride < 2048.0) stride >>= 1;
-    }
-    A.sample_stride = stride;
-    A.sample_need = (uint32_t)std::max(1.0, std::ceil(aim / stride));
-  }
+  ctx->multipart = ctx->plan.multipart;
+  apply_plan(A, ctx->plan);
+  const uint32_t guess0 = ctx->plan.guess0, shift0 = ctx->plan.shift0;
+  A.sel_stride = A.k;
+  A.idx_base = 0;
+  A.vec_base = 0;
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
   A.keptmap = (uint8_t*)(base + L.keptmap);
@@ -1050,7 +1183,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
   ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
   ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
-  if (cfg->compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || cfg->nlayers > 0)) {
+  if (cfg->compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || (cfg->nlayers > 0 && ctx->long_layers.empty()))) {
     ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
     if (cfg->nlayers > 0) ctx->keptmap_buf[1] = (uint8_t*)(base + L.keptmap2);
     else ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
@@ -1091,6 +1224,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     std::stable_sort(work.begin(), work.end(), [](const LayerDesc& a, const LayerDesc& b) { return a.len > b.len; });
     ctx->nlarge = ctx->nmid = 0;
     for (const LayerDesc& D : work) {
+      if (ctx->sparse && D.len > kMaxLayerLen) continue;   // (long layers: first in the list, skipped by the layer kernel)
       if (D.len > kMidLayerLen) ctx->nlarge += 1;
       else if (D.len > kWaveLayerLen) ctx->nmid += 1;
     }
@@ -1180,9 +1314,14 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
                        hipMemcpyHostToDevice, ctx->stream);
   std::vector<WorkerCtl> ctl0;
   if (e == hipSuccess) {
-    ctl0.resize((size_t)cfg->n);
+    const size_t nlong = ctx->long_layers.size();
+    ctl0.resize((size_t)cfg->n * std::max<size_t>(1, nlong));
     std::memset(ctl0.data(), 0, ctl0.size() * sizeof(WorkerCtl));
-    for (auto& c : ctl0) { c.guess_key = guess0; c.bin_shift = shift0; }
+    for (size_t j = 0; j < ctl0.size(); ++j) {
+      const SelectPlan& P = nlong ? ctx->long_layers[j / (size_t)cfg->n].plan : ctx->plan;
+      ctl0[j].guess_key = nlong ? P.guess0 : guess0;
+      ctl0[j].bin_shift = nlong ? P.shift0 : shift0;
+    }
     e = hipMemcpyAsync(base + L.ctl, ctl0.data(), ctl0.size() * sizeof(WorkerCtl), hipMemcpyHostToDevice,
                        ctx->stream);
   }
@@ -1404,7 +1543,19 @@ int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
   const Args& A = ctx->args;
   HIP_TRY(ctx, hipMemcpyAsync(scalars_host, ctx->layer_scal_buf[ctx->last_buf], (size_t)A.n * (size_t)A.nlayers * 4 * sizeof(double),
                               hipMemcpyDeviceToHost, ctx->stream));
+  const size_t nlong = ctx->long_layers.size();
+  std::vector<WorkerCtl> ctl((size_t)A.n * nlong);
+  if (nlong)
+    HIP_TRY(ctx, hipMemcpyAsync(ctl.data(), A.ctl, ctl.size() * sizeof(WorkerCtl), hipMemcpyDeviceToHost, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  for (size_t b = 0; b < nlong; ++b)
+    for (int i = 0; i < A.n; ++i) {
+      const WorkerCtl& c = ctl[b * (size_t)A.n + (size_t)i];
+      double* o = scalars_host + ((size_t)i * (size_t)A.nlayers + (size_t)ctx->long_layers[b].id) * 4;
+      o[0] = (double)(uint32_t)(c.kstar >> 32);
+      o[1] = o[2] = 0.0;
+      o[3] = c.mode == 0u ? 1.0 : 0.0;
+    }
   return CHOCO_OK;
 }
 

@@ -130,8 +130,14 @@ struct Args {
   uint32_t want;       // entries the next guess should leave above it now: extra (+ k for top_a)
   uint32_t extra;      // candidates wanted beyond k: max(k/2, 6 sqrt(k) + 32)
   uint32_t delta0;     // default distance of the guess below the threshold key
-  int32_t* sel_idx;    // n x k
-  float* sel_val;      // n x k
+  int32_t* sel_idx;    // n x sel_stride: kept indices (slot m of worker i at i * sel_stride + m)
+  float* sel_val;      // n x sel_stride: their values
+  // The select kernels see one "row" of d entries per worker of which k are kept.  That is the
+  // whole vector, or one long layer of it: then X, Xhat, G, M and the kept-entry map point at the
+  // layer's first entry, sel_idx / sel_val at the layer's first slot, and
+  int64_t sel_stride;  // slots per worker in sel_idx / sel_val (k for the whole vector)
+  int32_t idx_base;    // is added to the kept indices (the layer's first entry; 0 for the whole vector)
+  uint32_t vec_base;   // is added to the 4-vector number that keys the random words (idx_base / 4)
   uint8_t* keptmap;    // n x ld bytes: byte e of row j non-zero <=> worker j kept entry e this step
   uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
   int64_t bitmap_words;  // 0: use the byte map
@@ -943,7 +949,7 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
 #pragma unroll
     for (int c = 0; c < 4; ++c) a[c] = __float_as_uint(x[c] - xh[c]);
   } else {
-    const uint4 wds = random_words(A, i, (uint32_t)m, STREAM_RANDK);
+    const uint4 wds = random_words(A, i, A.vec_base + (uint32_t)m, STREAM_RANDK);
     a[0] = ~wds.x; a[1] = ~wds.y; a[2] = ~wds.z; a[3] = ~wds.w;
   }
 }
@@ -1192,7 +1198,7 @@ __device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint
     const int64_t o = (int64_t)i * A.ld + t;
     a = __float_as_uint(A.X[o] - A.Xhat[o]);   // top_a never defers the local update
   } else {
-    const uint4 wds = random_words(A, i, t >> 2, STREAM_RANDK);
+    const uint4 wds = random_words(A, i, A.vec_base + (t >> 2), STREAM_RANDK);
     a = ~pick(wds, (int)(t & 3u));
   }
 }
@@ -1304,8 +1310,8 @@ __device__ __forceinline__ void store_kept(const Args& A, int i, uint32_t slot, 
                                            uint32_t* lbits) {
   if (slot >= (uint32_t)A.k) return;
   // top_a carries the value in the entry; random_a gathers it afterwards (k_sel_values)
-  A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
-  if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
+  A.sel_idx[(int64_t)i * A.sel_stride + slot] = A.idx_base + (int32_t)idx;
+  if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.sel_stride + slot] = __uint_as_float(a);
   mark_kept(A, i, idx, lbits);
 }
 
@@ -1409,8 +1415,8 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint3
     if (Digits<COMP>::composite(a, idx) >= kstar) {
       const uint32_t slot = atomicAdd(s_emit, 1u);
       if (slot < (uint32_t)A.k) {
-        A.sel_idx[(int64_t)i * A.k + slot] = (int32_t)idx;
-        if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.k + slot] = __uint_as_float(a);
+        A.sel_idx[(int64_t)i * A.sel_stride + slot] = A.idx_base + (int32_t)idx;
+        if (COMP == Q_TOPK) A.sel_val[(int64_t)i * A.sel_stride + slot] = __uint_as_float(a);
         mark_kept(A, i, idx, lbits);
       }
     }

@@ -145,12 +145,21 @@ def test_layer_tables_are_validated():
 
 
 def test_layer_limits_are_reported_as_unsupported():
-    limit = 40960    # CHOCO_MAX_LAYER_LEN
+    limit = 40960    # CHOCO_MAX_LAYER_LEN: longer top_a / random_a layers take the streaming select
     assert layer_code(limit + 8, [0, 8], [8, limit], [1, 10]) == B.OK
-    assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 10]) == B.E_UNSUPPORTED
+    assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 10]) == B.OK
+    assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 0]) == B.OK       # a long silent layer
     assert layer_code(limit + 9, [0, 8], [8, limit + 1], None, compressor=B.Q_SIGN) == B.OK   # dense: any length
     assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT) == B.E_UNSUPPORTED
     assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_IDENTITY) == B.E_UNSUPPORTED
+
+
+def test_long_layers_bring_candidate_lists_into_the_workspace():
+    start, length, k = synth.layer_table([30000, 70000], fraction=0.01)
+    short = synth.layer_table([30000, 30000, 40000], fraction=0.01)
+    c1, keep1 = cfg(d=100000, layers=(start, length, k))
+    c2, keep2 = cfg(d=100000, layers=short)
+    assert B.workspace_bytes(c1) > B.workspace_bytes(c2)
 
 
 def test_layered_workspace_needs_no_candidate_lists():

@@ -130,3 +130,12 @@ def test_layer_wise_sign_on_the_language_model_sizes():
     layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
     d = synth.layers_dim(layers)
     run(8, d, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, layers=layers, compressor=B.Q_SIGN)
+
+
+@pytest.mark.parametrize("comp", [B.Q_TOPK, B.Q_RANDK])
+def test_layer_wise_selection_on_the_language_model_sizes(comp):
+    # 0.1 % of every layer; the 21.6 M- and 1.69 M-entry layers take the guessed-threshold
+    # select layer after layer, the biases the layer kernel
+    layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
+    d = synth.layers_dim(layers)
+    run(8, d, synth.ring_csr(8), 3, 0.01, 0.05, 0.0, layers=layers, compressor=comp)

@@ -211,3 +211,94 @@ def test_layered_random_masks_selected_ahead_or_not_are_the_same(order):
             pair.check(det, tag="layered lookahead step %d" % t)
     finally:
         pair.close()
+
+
+# layers above CHOCO_MAX_LAYER_LEN take the guessed-threshold select of the whole-vector path,
+# one layer after the other: a one-block select (41,000 / 50,000 / 300,000), a list long enough
+# for the multi-block select (600,000 at 3 %), beside layers of every short class
+LONG_LENGTHS = [432, 50000, 7, 41000, 2561, 600000, 10, 300000, 12000]
+SPARSE = [OPERATORS[0], OPERATORS[1], OPERATORS[2]]
+
+
+def long_layers(fraction=0.03):
+    start, length, k = synth.layer_table(LONG_LENGTHS, fraction=fraction)
+    k[3] = length[3]    # a long layer sent whole
+    return start, length, k
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", SPARSE)
+def test_long_layers_fused_iterations(name, q, order):
+    layers = long_layers()
+    n = 4
+    X0, inside = padded_state(n, layers, seed=31)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=15, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=14, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(4):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            if t == 2:      # separate calls in between
+                pair.sgd_step(G, 0.1)
+                det = pair.gossip_step()
+            else:
+                det = pair.step(G, 0.1)
+            pair.check(det, tag="%s long layers step %d" % (name, t))
+        scal = pair.gpu.layer_scalars()
+        if q["compressor"] == binding.Q_RANDK:
+            assert np.all(scal[:, [1, 5, 7], 3] == 1)   # the guess from the key distribution held
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1]])
+def test_long_layers_momentum_with_a_silent_long_layer(name, q):
+    start, length, k = long_layers(fraction=0.01)
+    k[1] = 0            # a long layer that sends nothing still takes its local update
+    layers = (start, length, k)
+    n = 3
+    X0, inside = padded_state(n, layers, seed=32)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=16, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=15, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(3):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step_momentum(G, 0.05, 0.9, 1e-4)
+            pair.check(det, tag="%s silent long layer step %d" % (name, t))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1]])
+def test_a_layer_long_enough_for_the_histogram_fallback(name, q):
+    # above 2^21 entries a failed guess (top_a: the first step) is repaired by the sampled
+    # histogram and a rebuilt list instead of a scan of the layer
+    layers = synth.layer_table([100, 2_200_000, 45000], fraction=0.001)
+    n = 3
+    X0, inside = padded_state(n, layers, seed=33)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=17, layers=layers, **q)
+    grads = synth.GradientStream(n, pair.d, seed=16, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(3):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step(G, 0.1)
+            pair.check(det, tag="%s 2.2 M-entry layer step %d" % (name, t))
+    finally:
+        pair.close()
+
+
+def test_long_layer_topk_ties_go_to_the_lower_index():
+    layers = synth.layer_table([3000, 120000], fraction=0.2)
+    d = synth.layers_dim(layers)
+    n = 3
+    rng = np.random.default_rng(6)
+    X0 = rng.integers(-2, 3, size=(n, d)).astype(np.float32) * 0.5
+    pair = Pair(X0, synth.ring_csr(n), 0.5, compressor=binding.Q_TOPK, layers=layers)
+    try:
+        for t in range(3):
+            det = pair.gossip_step()
+            pair.check(det, tag="long layer ties step %d" % t)
+    finally:
+        pair.close()
