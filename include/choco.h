@@ -210,9 +210,9 @@ int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
    Layer-wise configurations: a worker's message is the messages of its layers one after
    the other, each with its own scale / step / index slots (these count inside the layer)
    and its own padding to whole words; TOPK pairs carry positions in the whole vector.
-   Not implemented (CHOCO_E_UNSUPPORTED): IDENTITY, RANDK layer by layer or with
-   d > 327,680 (no bitmap to put the values in order).  These calls are not part of the
-   timed path. */
+   RANDK layer by layer: the kept values in ascending position in the whole vector (which
+   is layer after layer).  IDENTITY has no message format (CHOCO_E_UNSUPPORTED).  These
+   calls are not part of the timed path. */
 int choco_paper_message_bits(int32_t compressor, int64_t d, int64_t k, int32_t levels,
                              int64_t *bits_host);
 int choco_message_bytes(choco_ctx *ctx, size_t *bytes_host);

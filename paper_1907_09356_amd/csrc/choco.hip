@@ -75,6 +75,7 @@ struct choco_ctx {
   bool long_silent;       // one of them keeps nothing (its pass cannot carry the local update)
   bool long_rows;         // d > 2^21: four 4-vectors per thread in the streaming kernels
   uint64_t t;             // step counter
+  uint32_t* wire_rank;    // random_a without a bitmap: n x ceil(ld / 1024) chunk ranks of the message encoder
   uint32_t* wire;         // device scratch of the message encoder: n status words, then counters and index slots
   const int64_t* wire_word_off;   // layer by layer: where each layer's message starts / prefix of plane lengths
   const int64_t* wire_plane_off;
@@ -101,7 +102,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
-      chunk_layer, wire, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, mpart, mout, total;
+      chunk_layer, wire, wire_rank, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, mpart, mout, total;
   int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
@@ -372,6 +373,8 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // message encoder: n status words, then per (worker, layer) a counter and the index slots
   const size_t wire_units = (size_t)c.n * (size_t)(layered ? c.nlayers : 1);
   L.wire = take(((size_t)c.n + wire_units * (1 + kOverflowSlots)) * sizeof(uint32_t));
+  L.wire_rank = take(c.compressor == CHOCO_Q_RANDK && !L.bitmap_words
+                         ? (size_t)c.n * (size_t)((ld + 1023) / 1024) * sizeof(uint32_t) : 0);
   L.wire_word_off = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int64_t) : 0);
   L.wire_plane_off = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int64_t) : 0);
   L.wire_words = L.wire_plane_words = 0;
@@ -1015,8 +1018,6 @@ int fused_iteration(choco_ctx* ctx, const LocalUpdate& u) {
 // Which configurations the message kernels cover.
 int wire_supported(const choco_ctx* ctx) {
   if (ctx->cfg.compressor == CHOCO_Q_IDENTITY) return CHOCO_E_UNSUPPORTED;
-  // random_a needs the kept-entry bitmap to order its values (short rows, whole-vector mode)
-  if (ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->args.bitmap_words == 0) return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
 
@@ -1048,7 +1049,19 @@ WireArgs wire_args(const choco_ctx* ctx) {
   Wa.sel_val = A.sel_val;
   Wa.bitmap = ctx->bitmap_buf[ctx->last_buf];
   Wa.bitmap_words = A.bitmap_words;
+  Wa.keptmap = ctx->keptmap_buf[ctx->last_buf];
+  Wa.chunk_rank = ctx->wire_rank;
+  Wa.nchunk = (A.ld + 1023) / 1024;
   return Wa;
+}
+
+// random_a without a bitmap: mark the kept entries of the last step in the (otherwise zero) byte
+// map and count them chunk by chunk, so that a kept entry's rank is a table look-up plus a
+// count inside its own chunk.  The caller clears the marks again.
+void launch_rank_tables(choco_ctx* ctx, const WireArgs& Wa) {
+  LAUNCH(ctx, KID_WIRE, k_wire_mark, dim3((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n), dim3(256), 0, Wa, (uint8_t)1);
+  LAUNCH(ctx, KID_WIRE, k_wire_chunk_counts, dim3((unsigned)Wa.nchunk, (unsigned)Wa.n), dim3(256), 0, Wa);
+  LAUNCH(ctx, KID_WIRE, k_wire_chunk_scan, dim3((unsigned)Wa.n), dim3(1024), 0, Wa);
 }
 
 }  // namespace
@@ -1257,6 +1270,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
   ctx->wire = (uint32_t*)(base + L.wire);
+  ctx->wire_rank = (uint32_t*)(base + L.wire_rank);
   ctx->wire_word_off = (const int64_t*)(base + L.wire_word_off);
   ctx->wire_plane_off = (const int64_t*)(base + L.wire_plane_off);
   ctx->wire_words = L.wire_words;
@@ -1485,8 +1499,15 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
       LAUNCH(ctx, KID_WIRE, k_pack_topk, kgrid, dim3(256), 0, Wa, msg);
       break;
     case CHOCO_Q_RANDK:
-      LAUNCH(ctx, KID_WIRE, k_pack_randk, dim3((unsigned)Wa.n), dim3(1024), (size_t)Wa.bitmap_words * sizeof(uint32_t),
-             Wa, msg);
+      if (Wa.bitmap_words) {
+        LAUNCH(ctx, KID_WIRE, k_pack_randk, dim3((unsigned)Wa.n), dim3(1024),
+               (size_t)Wa.bitmap_words * sizeof(uint32_t), Wa, msg);
+      } else {
+        launch_rank_tables(ctx, Wa);
+        LAUNCH(ctx, KID_WIRE, k_pack_randk_ranked, dim3((unsigned)((Wa.k + 3) / 4), (unsigned)Wa.n), dim3(256), 0, Wa,
+               msg);
+        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, (uint8_t)0);
+      }
       break;
     default: return CHOCO_E_UNSUPPORTED;
   }
@@ -1520,8 +1541,15 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
       break;
     case CHOCO_Q_TOPK: LAUNCH(ctx, KID_WIRE, k_unpack_topk, kgrid, dim3(256), 0, Wa, msg, q_dev); break;
     case CHOCO_Q_RANDK:
-      LAUNCH(ctx, KID_WIRE, k_unpack_randk, dim3((unsigned)Wa.n), dim3(1024),
-             (size_t)Wa.bitmap_words * sizeof(uint32_t), Wa, msg, q_dev);
+      if (Wa.bitmap_words) {
+        LAUNCH(ctx, KID_WIRE, k_unpack_randk, dim3((unsigned)Wa.n), dim3(1024),
+               (size_t)Wa.bitmap_words * sizeof(uint32_t), Wa, msg, q_dev);
+      } else {
+        launch_rank_tables(ctx, Wa);
+        LAUNCH(ctx, KID_WIRE, k_unpack_randk_ranked, dim3((unsigned)((Wa.k + 3) / 4), (unsigned)Wa.n), dim3(256), 0,
+               Wa, msg, q_dev);
+        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, (uint8_t)0);
+      }
       break;
     default: return CHOCO_E_UNSUPPORTED;
   }

@@ -36,6 +36,11 @@ struct WireArgs {
   const float* sel_val;
   const uint32_t* bitmap;
   int64_t bitmap_words;
+  // random_a without a bitmap (long rows, layer by layer): ranks come from the byte map of kept
+  // entries, marked anew from the kept-index list for the duration of the call
+  uint8_t* keptmap;         // n x ld bytes, all zero between steps
+  uint32_t* chunk_rank;     // n x nchunk: kept entries of a worker below each 1024-entry chunk
+  int64_t nchunk;           // ceil(ld / 1024)
   // layer by layer: a worker's message is its layers' messages one after the other
   const LayerDesc* layers;
   int32_t nlayers;
@@ -389,6 +394,105 @@ __global__ __launch_bounds__(1024) void k_unpack_randk(WireArgs A, const uint32_
       q[(int64_t)i * A.ld + 32 * w + j] = __uint_as_float(in[rank++]);
     }
   }
+}
+
+// ---- random_a without a bitmap: ranks from the byte map ----
+
+// keptmap[i][e] = value for the kept entries of the last step.  grid (ceil(k / 256), n)
+__global__ __launch_bounds__(256) void k_wire_mark(WireArgs A, uint8_t value) {
+  const int i = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= A.k) return;
+  A.keptmap[(int64_t)i * A.ld + A.sel_idx[(int64_t)i * A.k + m]] = value;
+}
+
+// Marked bytes (each 0 or 1) of a 4-byte word of the map that lie below entry `limit`; the word
+// covers entries pos .. pos + 3.
+__device__ __forceinline__ uint32_t marked_below(uint32_t word, int64_t pos, int64_t limit) {
+  if (pos >= limit) return 0u;
+  if (pos + 4 > limit) word &= (1u << (8 * (uint32_t)(limit - pos))) - 1u;
+  return (uint32_t)__popc(word & 0x01010101u);
+}
+
+// chunk_rank[i][c] = marked entries of worker i in chunk c.  grid (nchunk, n), block 256
+__global__ __launch_bounds__(256) void k_wire_chunk_counts(WireArgs A) {
+  __shared__ uint32_t sh[4];
+  const int i = blockIdx.y;
+  const int64_t pos = (int64_t)blockIdx.x * 1024 + 4 * (int64_t)threadIdx.x;
+  uint32_t c = 0;
+  if (pos < A.ld) c = marked_below(*reinterpret_cast<const uint32_t*>(A.keptmap + (int64_t)i * A.ld + pos), pos, A.ld);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) c += __shfl_down(c, off, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) A.chunk_rank[(int64_t)i * A.nchunk + blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// In place: chunk_rank[i][c] = marked entries of worker i in the chunks before c.  grid n, block 1024
+__global__ __launch_bounds__(1024) void k_wire_chunk_scan(WireArgs A) {
+  __shared__ uint32_t sh_wave[16];
+  __shared__ uint32_t sh_carry;
+  uint32_t* r = A.chunk_rank + (int64_t)blockIdx.x * A.nchunk;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) sh_carry = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < A.nchunk; base += 1024) {
+    const int64_t c = base + tid;
+    const uint32_t mine = c < A.nchunk ? r[c] : 0u;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) sh_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = sh_carry;
+    for (int w = 0; w < wave; ++w) before += sh_wave[w];
+    if (c < A.nchunk) r[c] = before + incl - mine;
+    __syncthreads();
+    if (tid == 1023) sh_carry = before + incl;
+    __syncthreads();
+  }
+}
+
+// Rank of kept entry e of worker i among the worker's kept entries; all 64 lanes of a wave
+// call it with the same e and get the same result (they share the 1 KiB of the map before e).
+__device__ __forceinline__ uint32_t rank_by_map(const WireArgs& A, int i, int64_t e) {
+  const int lane = threadIdx.x & 63;
+  const int64_t chunk = e >> 10;
+  const uint8_t* row = A.keptmap + (int64_t)i * A.ld;
+  uint32_t c = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t pos = chunk * 1024 + 4 * (int64_t)(lane + 64 * u);
+    if (pos < e) c += marked_below(*reinterpret_cast<const uint32_t*>(row + pos), pos, e);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
+  return A.chunk_rank[(int64_t)i * A.nchunk + chunk] + c;
+}
+
+// The value of kept entry e goes to position rank(e).  One wave per kept entry:
+// grid (ceil(k / 4), n), block 256
+__global__ __launch_bounds__(256) void k_pack_randk_ranked(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= A.k) return;
+  const int64_t e = A.sel_idx[(int64_t)i * A.k + m];
+  const uint32_t rank = rank_by_map(A, i, e);
+  if ((threadIdx.x & 63) == 0) msg[(int64_t)i * A.words + rank] = __float_as_uint(A.sel_val[(int64_t)i * A.k + m]);
+}
+
+// after k_wire_zero; the mask is the kept-index list of the last step (the draw a receiver
+// repeats from the shared seed).  grid (ceil(k / 4), n), block 256
+__global__ __launch_bounds__(256) void k_unpack_randk_ranked(WireArgs A, const uint32_t* msg, float* q) {
+  const int i = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= A.k) return;
+  const int64_t e = A.sel_idx[(int64_t)i * A.k + m];
+  const uint32_t rank = rank_by_map(A, i, e);
+  if ((threadIdx.x & 63) == 0) q[(int64_t)i * A.ld + e] = __uint_as_float(msg[(int64_t)i * A.words + rank]);
 }
 
 }  // namespace choco

@@ -139,3 +139,27 @@ def test_layer_wise_selection_on_the_language_model_sizes(comp):
     layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
     d = synth.layers_dim(layers)
     run(8, d, synth.ring_csr(8), 3, 0.01, 0.05, 0.0, layers=layers, compressor=comp)
+
+
+def test_random_k_messages_of_the_large_model_shape():
+    # d = 28 M, k = 28,000: ranks through the byte map (27,344 chunks per worker)
+    from oracle import choco_ref as ref
+    n, d, k = 8, 28_000_000, 28_000
+    X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
+    pair = Pair(X0, synth.ring_csr(n), 0.01, seed=7, compressor=B.Q_RANDK, k=k)
+    grads = synth.GradientStream(n, d, seed=11, noise_std=0.01, bias_std=0.0)
+    try:
+        pair.sgd_step(grads.next(), 0.05)
+        v = pair.ref.X - pair.ref.Xhat
+        det = pair.gossip_step()
+        pair.check(det, tag="step 0")
+        msgs = pair.gpu.pack_messages()
+        dense = pair.gpu.unpack_messages(msgs)
+        pair.gpu.sync()
+        got = msgs.cpu().numpy().view(np.uint32)
+        for i in (0, 5):
+            q, want = ref.pack_message(B.Q_RANDK, v[i], k=k, seed=7, t=0, worker=i)
+            assert np.array_equal(got[i], want)
+            assert np.array_equal(dense[i, :d].cpu().numpy(), q)
+    finally:
+        pair.close()

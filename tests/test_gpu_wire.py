@@ -99,9 +99,8 @@ def test_message_calls_say_what_they_do_not_cover():
         g.pack_messages()
     assert err.value.code == binding.E_INVAL
     g.close()
-    layers = synth.layer_table([200, 400], fraction=0.1)
-    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_RANDK, layers=layers)
-    with pytest.raises(binding.ChocoError) as err:      # random_a layer by layer: no bitmap to rank by
+    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_IDENTITY)
+    with pytest.raises(binding.ChocoError) as err:      # nothing is compressed: no message format
         g.message_bytes()
     assert err.value.code == binding.E_UNSUPPORTED
     g.close()
@@ -109,6 +108,8 @@ def test_message_calls_say_what_they_do_not_cover():
 
 LAYERED = [
     ("topk", dict(compressor=binding.Q_TOPK)),
+    ("randk", dict(compressor=binding.Q_RANDK)),
+    ("randk_rescaled", dict(compressor=binding.Q_RANDK, randk_rescale=1)),
     ("sign", dict(compressor=binding.Q_SIGN)),
     ("qsgd8", dict(compressor=binding.Q_QSGD, levels=8)),
     ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
@@ -137,7 +138,8 @@ def test_layered_messages_match_the_oracle(name, q):
         pair.sgd_step(G, 0.1)
         v = pair.ref.X - pair.ref.Xhat
         want = [ref.pack_layers(q["compressor"], v[i], layers, levels=q.get("levels", 1),
-                                qsgd_biased=q.get("qsgd_biased", 1), seed=pair.ref.seed, t=t, worker=i)
+                                qsgd_biased=q.get("qsgd_biased", 1), randk_rescale=q.get("randk_rescale", 0),
+                                seed=pair.ref.seed, t=t, worker=i)
                 for i in range(n)]
         det = pair.gossip_step()
         pair.check(det, tag="%s step %d" % (name, t))
@@ -156,3 +158,30 @@ def test_layered_messages_match_the_oracle(name, q):
             assert np.array_equal(dense[i, :d], want[i][0])
         assert not dense[:, d:].any()
     pair.close()
+
+
+@pytest.mark.parametrize("rescale", [0, 1])
+def test_random_k_messages_on_rows_too_long_for_a_bitmap(rescale):
+    # above 327,680 entries the kept entries are ranked through the byte map and per-chunk
+    # counts (the row ends inside a 1024-entry chunk and inside a 4-byte word of the map)
+    n, d, k = 3, 400_003, 4000
+    q = dict(compressor=binding.Q_RANDK, k=k, randk_rescale=rescale)
+    X0 = synth.normal_state(n, d, seed=35)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=10, **q)
+    grads = synth.GradientStream(n, d, seed=7, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(2):
+            pair.sgd_step(grads.next(), 0.1)
+            want_msgs, want_q = oracle_messages(pair, q, t)
+            det = pair.gossip_step()
+            pair.check(det, tag="long row random-k step %d" % t)
+            for rep in range(2):        # the marks are cleared again: a second call gives the same
+                msgs = pair.gpu.pack_messages()
+                assert np.array_equal(msgs.cpu().numpy().view(np.uint32), want_msgs)
+            dense = pair.gpu.unpack_messages(msgs)
+            pair.gpu.sync()
+            dense = dense.cpu().numpy()
+            assert np.array_equal(dense[:, :d], want_q)
+            assert not dense[:, d:].any()
+    finally:
+        pair.close()
