@@ -234,9 +234,9 @@ int choco_set_step(choco_ctx *ctx, uint64_t t);
 int choco_set_profiling(choco_ctx *ctx, int enable);
 int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
 
-/* RANDK in whole-vector mode with d <= 327,680, and RANDK layer by layer: the mask of a step
-   depends on (seed, step, worker) only (Appendix C, random_a: the receiver can recover it from the seed), so while
-   one step's messages and mix run on the caller's stream the library already selects the
+/* RANDK: the mask of a step depends on (seed, step, worker) only (Appendix C, random_a: the
+   receiver can recover it from the seed), so while one step's messages and mix run on the
+   caller's stream the library already selects the
    NEXT step's mask on a stream of its own (created by choco_init, default priority, joined
    with events; no device memory is allocated).  Results do not change.  On by default
    where it applies; switch it off (enable = 0) if every call must leave all of its work

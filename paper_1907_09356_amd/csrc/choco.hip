@@ -47,9 +47,10 @@ struct choco_ctx {
   // a step's messages and mix run on the caller's stream the NEXT step's selection already
   // runs on this one.  Two copies of the kept-index lists and of the bitmap take turns.
   hipStream_t aux_stream;
+  hipStream_t launch_stream;   // where LAUNCH puts kernels: the caller's stream, or aux_stream while selecting ahead
   hipEvent_t ev_fork, ev_ahead;
   bool lookahead;         // the configuration allows it and it has not been switched off
-  bool can_lookahead;     // the configuration allows it (random_a, whole-vector mode, short rows)
+  bool can_lookahead;     // the configuration allows it (random_a)
   bool ahead_pending;     // a selection is in flight (or done) on aux_stream and not yet joined
   bool ahead_valid;       // ... and it is the selection of step ahead_t
   uint64_t ahead_t;
@@ -57,7 +58,7 @@ struct choco_ctx {
   uint32_t* bitmap_buf[2];
   uint8_t* keptmap_buf[2];
   double* layer_scal_buf[2];
-  int ahead_map_buf;      // layer by layer: the byte-map copy that holds a selection made ahead and not yet used (-1: none)
+  int ahead_map_buf;      // rows without a bitmap: the byte-map copy that holds a selection made ahead and not yet used (-1: none)
   int last_buf;           // which copy the last finished step used
   int32_t maxdeg;
   int32_t nnz;
@@ -348,12 +349,12 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.bitmap_words = (guessed && !layered && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
-  // second copies for the look-ahead selection of random_a (short rows, whole-vector mode)
-  // (short rows in whole-vector mode: lists and bitmap; layer by layer: lists and byte map)
-  const bool ahead = c.compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || (layered && longs.empty()));
+  // second copies for the look-ahead selection of random_a: the kept-index lists, the bitmap
+  // (short rows in whole-vector mode) or the byte map, the per-layer scalars
+  const bool ahead = c.compressor == CHOCO_Q_RANDK;
   L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
-  L.keptmap2 = take(ahead && layered ? (size_t)c.n * (size_t)ld : 0);
+  L.keptmap2 = take(ahead && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
   L.layer_scal2 = take(ahead && layered ? (size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double) : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
@@ -482,7 +483,7 @@ struct Timed {
   size_t slot;
   bool on;
   Timed(choco_ctx* c, int kid) : ctx(c), slot(0), on(false) {
-    if (!c->profiling || c->ev_used >= kMaxProfiledLaunches) return;
+    if (!c->profiling || c->launch_stream != c->stream || c->ev_used >= kMaxProfiledLaunches) return;
     if (c->ev_used == c->ev_begin.size()) {
       hipEvent_t a, b;
       if (hipEventCreate(&a) != hipSuccess) return;
@@ -503,7 +504,7 @@ struct Timed {
 #define LAUNCH(ctx, kid, kernel, grid, block, lds, ...)                              \
   do {                                                                               \
     Timed timed_(ctx, kid);                                                          \
-    hipLaunchKernelGGL(kernel, grid, block, lds, (ctx)->stream, __VA_ARGS__);        \
+    hipLaunchKernelGGL(kernel, grid, block, lds, (ctx)->launch_stream, __VA_ARGS__); \
   } while (0)
 
 // One block per 256 * vecs consecutive 4-vectors of a row, one grid row per worker.
@@ -627,6 +628,106 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
   return CHOCO_OK;
 }
 
+// A long pass that selects ahead generates Philox words (ALU work) while the caller's stream
+// runs the bandwidth-bound mix.  Left alone its workgroups fill every wave slot first and the
+// mix waits behind them; 48 KiB of LDS that it does not use hold it to two workgroups per
+// compute unit, so that both make progress (n = 8, 31.8 M entries in 14 layers, ms per step by
+// pad: 0 KiB 1.296, 16 KiB 1.267, 28 KiB 1.223, 48 KiB 1.189; a single workgroup per unit is
+// too slow to finish behind the mix: 1.316).
+size_t ahead_lds_pad(const choco_ctx* ctx, int64_t row_len) {
+  return (ctx->launch_stream != ctx->stream && row_len > ((int64_t)1 << 21)) ? (size_t)48 << 10 : 0;
+}
+
+// The select of the whole-vector path: one pass over the rows appends the candidates, the
+// histogram fallback and the rebuild are no-ops unless a guess failed, then the exact select
+// on the lists.  C is the argument block for the pass over the rows (it may carry the local
+// update and, with fuse_mix, the mix), A the one without.
+template <int COMP, bool NT>
+void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact, bool fuse_mix) {
+  const int32_t nvec = (A.d + 3) >> 2;
+  const int cvecs = ctx->fallback_chain ? kCompactVecs : 2;   // long rows: 4 four-vectors per thread, short: 2
+  const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
+  const size_t pad = ahead_lds_pad(ctx, A.d);
+  if (fuse_mix) {
+    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 2>), cgrid, dim3(256), 0, C);
+    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
+  } else {
+    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), pad, C);
+    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), cgrid, dim3(256), pad, C);
+  }
+  if (ctx->fallback_chain) {
+    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
+    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
+  }
+  if (ctx->multipart) {
+    const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
+    LAUNCH(ctx, KID_SEL_HIST_PARTS, (k_sel_hist_parts<COMP>), pgrid, dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_EMIT_PARTS, (k_sel_emit_parts<COMP>), pgrid, dim3(1024), 0, A);
+    LAUNCH(ctx, KID_SEL_FINISH, (k_sel_finish<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
+  } else {
+    LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
+           (size_t)A.bitmap_words * sizeof(uint32_t), A);
+  }
+}
+
+// random_a selects ahead: the mask of a step depends on (seed, step, worker) only, so the
+// selection of step t + 1 runs on the library's second stream beside the rest of step t.
+// look_ahead_begin: was this step's selection made ahead?  It joins the second stream and, if a
+// selection made ahead is being dropped (counter set, look-ahead or timing switched), clears
+// the marks it left in its copy of the byte map (no xhat update ever would).
+int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) {
+  *selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
+  const int rc = join_lookahead(ctx);
+  if (rc != CHOCO_OK) return rc;
+  if (!*selected && ctx->ahead_map_buf >= 0) {
+    const int64_t words = (int64_t)A.n * A.ld / 4;   // ld is a multiple of 4
+    LAUNCH(ctx, KID_XHAT_UPDATE, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+           (uint32_t*)ctx->keptmap_buf[ctx->ahead_map_buf], words);
+  }
+  ctx->ahead_map_buf = -1;
+  ctx->ahead_valid = false;
+  return CHOCO_OK;
+}
+
+// The argument block of the NEXT step's selection: no local update (the keys are Philox words,
+// no state is read), the other copy of the lists, maps and scalars.
+Args look_ahead_args(const choco_ctx* ctx, const Args& A) {
+  Args P = A;
+  P.G = nullptr;
+  P.M = nullptr;
+  P.deferred_sgd = 0;
+  const uint64_t tn = ctx->t + 1;
+  P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
+  P.t_hi = (uint32_t)(tn >> 32);
+  P.sel_idx = ctx->sel_idx_buf[tn & 1u];
+  P.bitmap = ctx->bitmap_buf[tn & 1u];
+  P.keptmap = ctx->keptmap_buf[tn & 1u];
+  if (ctx->nlayers > 0) P.layer_scal = ctx->layer_scal_buf[tn & 1u];
+  return P;
+}
+
+// Bracket of the launches that select ahead: between fork and join LAUNCH goes to the second
+// stream, which first waits for everything enqueued on the caller's stream so far.
+int look_ahead_fork(choco_ctx* ctx) {
+  HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+  HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+  ctx->launch_stream = ctx->aux_stream;
+  return CHOCO_OK;
+}
+
+int look_ahead_end(choco_ctx* ctx, const Args& A) {
+  ctx->launch_stream = ctx->stream;
+  HIP_TRY(ctx, hipGetLastError());
+  HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
+  ctx->ahead_pending = true;
+  ctx->ahead_valid = true;
+  ctx->ahead_t = ctx->t + 1;
+  if (!A.bitmap_words) ctx->ahead_map_buf = (int)((ctx->t + 1) & 1u);
+  return CHOCO_OK;
+}
+
 // Sparsifying operators (top_a, random_a).
 template <int COMP, bool NT>
 int gossip_sparse(choco_ctx* ctx, const Args& F) {
@@ -637,8 +738,6 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   const bool fused = F.G != nullptr && !F.deferred_sgd;
   const int32_t nvec = (A.d + 3) >> 2;
   const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
-  const int cvecs = ctx->fallback_chain ? kCompactVecs : 2;   // long rows: 4 four-vectors per thread, short: 2
-  const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
   bool fuse_mix = false;     // the mix rides on the select pass (top_a, printed order, incremental sums)
@@ -656,61 +755,24 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   // select: one pass over the rows; histogram fallback and rebuild are no-ops unless a guess failed
   const Args& C = x_touched ? A : F;
   const int kid_compact = (!x_touched && fused) ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
-  // random_a on short rows: this step's selection may already have been made (or be under way)
-  // on the second stream; then it is only waited for
+  // random_a: this step's selection may already have been made (or be under way) on the second
+  // stream; then it is only waited for
   const bool ahead = COMP == Q_RANDK && ctx->lookahead && !ctx->profiling;
-  const bool selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
+  bool selected = false;
   {
-    const int rc = join_lookahead(ctx);
+    const int rc = look_ahead_begin(ctx, A, ahead, &selected);
     if (rc != CHOCO_OK) return rc;
   }
-  if (selected) {
-    // nothing to launch
-  } else if (fuse_mix) {
-    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 2>), cgrid, dim3(256), 0, C);
-    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
-  } else {
-    if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), 0, C);
-    else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
-  }
-  if (ctx->fallback_chain) {
-    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
-    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
-    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
-  }
-  if (ctx->multipart) {
-    const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
-    LAUNCH(ctx, KID_SEL_HIST_PARTS, (k_sel_hist_parts<COMP>), pgrid, dim3(1024), 0, A);
-    LAUNCH(ctx, KID_SEL_EMIT_PARTS, (k_sel_emit_parts<COMP>), pgrid, dim3(1024), 0, A);
-    LAUNCH(ctx, KID_SEL_FINISH, (k_sel_finish<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-  } else if (!selected) {
-    LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024),
-           (size_t)A.bitmap_words * sizeof(uint32_t), A);
-  }
-  ctx->ahead_valid = false;
+  if (!selected) launch_select<COMP, NT>(ctx, C, A, kid_compact, fuse_mix);
   if (ahead) {
-    // the NEXT step's selection, into the other copy of the lists and of the bitmap, side by
-    // side with the rest of this step (it reads no state: the keys are Philox words)
-    Args P = A;
-    P.G = nullptr;
-    P.M = nullptr;
-    P.deferred_sgd = 0;
-    const uint64_t tn = ctx->t + 1;
-    P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
-    P.t_hi = (uint32_t)(tn >> 32);
-    P.sel_idx = ctx->sel_idx_buf[tn & 1u];
-    P.bitmap = ctx->bitmap_buf[tn & 1u];
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
-    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
-    hipLaunchKernelGGL((k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), 0, ctx->aux_stream, P);
-    hipLaunchKernelGGL((k_sel_refine<COMP>), dim3((unsigned)A.n), dim3(1024), (size_t)A.bitmap_words * sizeof(uint32_t),
-                       ctx->aux_stream, P);
-    HIP_TRY(ctx, hipGetLastError());
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
-    ctx->ahead_pending = true;
-    ctx->ahead_valid = true;
-    ctx->ahead_t = tn;
+    // the NEXT step's selection, into the other copy of the lists and of the map, side by side
+    // with the rest of this step
+    const Args P = look_ahead_args(ctx, A);
+    int rc = look_ahead_fork(ctx);
+    if (rc != CHOCO_OK) return rc;
+    launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
+    rc = look_ahead_end(ctx, A);
+    if (rc != CHOCO_OK) return rc;
   }
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
@@ -794,7 +856,7 @@ void select_long_layer(choco_ctx* ctx, const Args& C, const Args& A, int which) 
   const int32_t nvec = (B.len + 3) >> 2;
   if (B.plan.fallback_chain) {
     LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), chunk_grid(nvec, A.n, kCompactVecs),
-           dim3(256), 0, Cl);
+           dim3(256), ahead_lds_pad(ctx, B.len), Cl);
     const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
     LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, Al);
     LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
@@ -831,69 +893,47 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   // random_a never reads X in the layer kernel, so it cannot carry the local update
   Args C = (x_touched || COMP == Q_RANDK) ? A : F;
   if (COMP == Q_RANDK) C.G = nullptr;
-  const int kid = (C.G != nullptr) ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
   const int nlong = (int)ctx->long_layers.size();   // first in the work list, not for the layer kernel
   const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlong - nlarge - nmid;
   const int one_launch_blocks = nlarge + nmid + (nsmall + 15) / 16;
   // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the chip
   // still is not full, so one launch does (a launch costs more than idle threads)
   const bool one_launch = (int64_t)one_launch_blocks * A.n <= 256;
-  // the layer kernel(s), timed on the caller's stream or plain on the look-ahead stream
-  auto select_layers = [&](const Args& S, bool on_aux) {
-    auto go = [&](auto kernel, dim3 grid, dim3 block, int32_t first, int32_t nblock) {
-      if (on_aux) hipLaunchKernelGGL(kernel, grid, block, 0, ctx->aux_stream, S, first, nblock);
-      else LAUNCH(ctx, kid, kernel, grid, block, 0, S, first, nblock);
-    };
+  // the layer kernel(s) for the layers within its reach, then the long layers one after the other
+  auto select_layers = [&](const Args& S) {
+    const int kid = S.G ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
     if (one_launch) {
       if (one_launch_blocks > 0)
-        go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)one_launch_blocks, (unsigned)A.n), dim3(1024), nlong,
-           nlarge + nmid);
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)one_launch_blocks, (unsigned)A.n),
+               dim3(1024), 0, S, nlong, nlarge + nmid);
     } else {
       if (nlarge > 0)
-        go(k_layer_compress<COMP, 1024, NT>, dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), nlong, nlarge);
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0, S,
+               nlong, nlarge);
       if (nmid + nsmall > 0)
-        go(k_layer_compress<COMP, 256, NT>, dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n), dim3(256),
-           nlong + nlarge, nmid);
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
+               dim3(256), 0, S, nlong + nlarge, nmid);
     }
+    Args Q = S;
+    Q.G = nullptr;
+    Q.M = nullptr;
+    for (int b = 0; b < nlong; ++b) select_long_layer<COMP, NT>(ctx, S, Q, b);
   };
   // random_a: this step's masks may already have been drawn on the second stream
   const bool ahead = COMP == Q_RANDK && ctx->lookahead && !ctx->profiling;
-  const bool selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
+  bool selected = false;
   {
-    const int rc = join_lookahead(ctx);
+    const int rc = look_ahead_begin(ctx, A, ahead, &selected);
     if (rc != CHOCO_OK) return rc;
   }
-  if (!selected && ctx->ahead_map_buf >= 0) {
-    // a selection made ahead is dropped (counter set, look-ahead or timing switched): its
-    // marks would never be cleared by an xhat update
-    const int64_t words = (int64_t)A.n * A.ld / 4;   // ld is a multiple of 4
-    LAUNCH(ctx, KID_XHAT_UPDATE, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
-           (uint32_t*)ctx->keptmap_buf[ctx->ahead_map_buf], words);
-  }
-  ctx->ahead_map_buf = -1;
-  if (!selected) select_layers(C, false);
-  for (int b = 0; b < nlong; ++b) select_long_layer<COMP, NT>(ctx, C, A, b);   // (no look-ahead with long layers)
-  ctx->ahead_valid = false;
+  if (!selected) select_layers(C);
   if (ahead) {
-    Args P = A;
-    P.G = nullptr;
-    P.M = nullptr;
-    P.deferred_sgd = 0;
-    const uint64_t tn = ctx->t + 1;
-    P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
-    P.t_hi = (uint32_t)(tn >> 32);
-    P.sel_idx = ctx->sel_idx_buf[tn & 1u];
-    P.keptmap = ctx->keptmap_buf[tn & 1u];
-    P.layer_scal = ctx->layer_scal_buf[tn & 1u];
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
-    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
-    select_layers(P, true);
-    HIP_TRY(ctx, hipGetLastError());
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
-    ctx->ahead_pending = true;
-    ctx->ahead_valid = true;
-    ctx->ahead_t = tn;
-    ctx->ahead_map_buf = (int)(tn & 1u);
+    const Args P = look_ahead_args(ctx, A);
+    int rc = look_ahead_fork(ctx);
+    if (rc != CHOCO_OK) return rc;
+    select_layers(P);
+    rc = look_ahead_end(ctx, A);
+    if (rc != CHOCO_OK) return rc;
   }
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
   if (COMP == Q_RANDK)
@@ -1114,6 +1154,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->cfg.layer_k_host = nullptr;
   ctx->stream = (hipStream_t)cfg->stream;
   ctx->aux_stream = nullptr;
+  ctx->launch_stream = ctx->stream;
   ctx->ev_fork = ctx->ev_ahead = nullptr;
   ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = ctx->ahead_valid = false;
   ctx->ahead_t = 0;
@@ -1196,10 +1237,10 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
   ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
   ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
-  if (cfg->compressor == CHOCO_Q_RANDK && (L.bitmap_words > 0 || (cfg->nlayers > 0 && ctx->long_layers.empty()))) {
+  if (cfg->compressor == CHOCO_Q_RANDK) {
     ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
-    if (cfg->nlayers > 0) ctx->keptmap_buf[1] = (uint8_t*)(base + L.keptmap2);
-    else ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
+    if (L.bitmap_words > 0) ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
+    else ctx->keptmap_buf[1] = (uint8_t*)(base + L.keptmap2);
     hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);

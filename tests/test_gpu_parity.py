@@ -487,3 +487,42 @@ def test_random_masks_selected_ahead_or_not_are_the_same(order):
             pair.check(det, tag="lookahead step %d" % t)
     finally:
         pair.close()
+
+
+def test_random_masks_selected_ahead_on_rows_without_a_bitmap():
+    # above 327,680 entries the kept entries are marked in a byte map; it exists twice and a
+    # mask that was drawn ahead and then dropped (set_step) has its marks cleared again
+    n, d, k = 3, 400_003, 3000
+    X0 = synth.normal_state(n, d, seed=52)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, compressor=B.Q_RANDK, k=k)
+    grads = synth.GradientStream(n, d, seed=13, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(9):
+            if t == 3:
+                pair.gpu.set_lookahead(False)
+            if t == 5:
+                pair.gpu.set_lookahead(True)
+            if t == 7:
+                pair.gpu.set_step(70)
+                pair.ref.t = 70
+            if t % 2 == 0:
+                det = pair.step(grads.next(), 0.05)
+                pair.check(det, tag="lookahead, byte map, step %d" % t)
+                continue
+            # separate calls, and the message encoder, which marks and clears the same map
+            from oracle import choco_ref as ref
+            pair.sgd_step(grads.next(), 0.05)
+            v = pair.ref.X - pair.ref.Xhat
+            tt = pair.ref.t
+            det = pair.gossip_step()
+            pair.check(det, tag="lookahead, byte map, step %d" % t)
+            msgs = pair.gpu.pack_messages()
+            dense = pair.gpu.unpack_messages(msgs)
+            pair.gpu.sync()
+            got = msgs.cpu().numpy().view(np.uint32)
+            for i in range(n):
+                q, want = ref.pack_message(B.Q_RANDK, v[i], k=k, seed=9, t=tt, worker=i)
+                assert np.array_equal(got[i], want)
+                assert np.array_equal(dense[i, :d].cpu().numpy(), q)
+    finally:
+        pair.close()
