@@ -135,8 +135,8 @@ KERNEL_BYTES_PER_ELEM = {
 # counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("large_topk", "k_sel_compact_sgd"): 3_588_875_055,
-    ("large_topk", "k_mix_incremental"): 3_583_998_976,
+    ("large_topk", "k_sel_compact_sgd"): 3_588_944_585,
+    ("large_topk", "k_mix_incremental"): 3_583_997_952,
 }
 
 
@@ -336,7 +336,7 @@ def step_bytes_per_elem(w, kernels):
     return total / (w["n"] * w["d"])
 
 
-def cpu_baseline(w, budget_s=20.0):
+def cpu_baseline(w, budget_s=15.0):
     """The oracle as it stands, one thread, on a bounded sample of the same workload: the
     same n, topology, operator and hyper-parameters with d cut to d/10 (k cut alike)."""
     import numpy as np
@@ -367,7 +367,7 @@ def cpu_baseline(w, budget_s=20.0):
         st.gossip_step()
         steps += 1
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= 20:
+        if el > budget_s or steps >= 400:
             break
     elem_rate = steps * n * d / el
     return dict(value=elem_rate / (n * w["d"]), unit="steps/s", cores=1, kind="oracle",
