@@ -125,6 +125,11 @@ def test_peer_to_peer_ring_topk_100_steps():
     long_run(64, 270_000, synth.ring_csr(64), 100, 0.02, 0.1, compressor=B.Q_TOPK, k=2700)
 
 
+def test_peer_to_peer_torus_randk_100_steps():
+    # the masks of steps 1..99 are all drawn ahead on the second stream
+    long_run(64, 270_000, synth.torus_csr(8, 8), 100, 0.02, 0.1, compressor=B.Q_RANDK, k=2700)
+
+
 def test_layer_wise_sign_on_the_language_model_sizes():
     # layers of up to 21.6 M entries (5,281 group sums: the third tree level wraps 20 times)
     layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
