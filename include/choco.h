@@ -174,7 +174,9 @@ int choco_nsum(choco_ctx *ctx, float **s_dev);
    gsgd: {sum v^2, ||v||_2, s/||v||_2, ||v||_2/(tau s), 0, 0} (the scales as rounded to fp32);
    TOPK/RANDK: {threshold key, tie cut-off index, kept count, select mode of the last step
    (0 = guessed threshold held, 1 = list rebuilt from the histogram, 2 = row scan), number of
-   steps so far that needed mode 1 or 2, length of the last candidate list}.  Synchronises. */
+   steps so far that needed mode 1 or 2, length of the last candidate list}; for RANDK with the
+   look-ahead on (choco_set_lookahead) these are the figures of the selection made last, which
+   is the NEXT step's.  Synchronises. */
 int choco_last_selection(choco_ctx *ctx, int32_t *idx_dev, float *val_dev);
 int choco_set_capture(choco_ctx *ctx, int32_t *codes_dev);
 int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
