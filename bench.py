@@ -195,9 +195,20 @@ def calibration_copy(torch, nbytes=896_000_000, reps=10):
         b.copy_(a)
     torch.cuda.synchronize()
     el = (time.perf_counter() - t0) / reps
-    del a, b
+    # the same arrays through a library triad c = a + 2 b (reads 2 x nbytes, writes nbytes): with the
+    # copy above, the practical ceiling that the streaming kernels' GB/s can be held against
+    c = torch.empty_like(a)
+    torch.add(a, b, alpha=2.0, out=c)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        torch.add(a, b, alpha=2.0, out=c)
+    torch.cuda.synchronize()
+    el3 = (time.perf_counter() - t0) / reps
+    del a, b, c
     torch.cuda.empty_cache()
-    return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9)
+    return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9,
+                triad_ms=1e3 * el3, triad_GBps=3 * nbytes / el3 / 1e9)
 
 
 def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=None, momentum=False):
