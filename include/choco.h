@@ -245,10 +245,13 @@ int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
    on the caller's stream, e.g. under stream capture.  A no-op for other configurations. */
 int choco_set_lookahead(choco_ctx *ctx, int enable);
 
-int choco_sync(choco_ctx *ctx);    /* hipStreamSynchronize on the context's stream */
-/* Frees the context (host memory and its profiling events) without waiting for the stream:
-   call choco_sync first if X or the workspace are to be freed or reused right away.  The
-   handle is invalid afterwards.  NULL is allowed. */
+/* Waits for everything the library has enqueued: the context's stream and, where RANDK
+   selects ahead, the library's own stream (that selection writes the workspace). */
+int choco_sync(choco_ctx *ctx);
+/* Frees the context (host memory, its profiling events, its own stream after waiting for
+   it) without waiting for the caller's stream: call choco_sync first if X or the workspace
+   are to be freed or reused right away.  The handle is invalid afterwards.  NULL is
+   allowed. */
 int choco_destroy(choco_ctx *ctx);
 const char *choco_strerror(int code);
 int choco_last_hip_error(choco_ctx *ctx); /* raw hipError_t of the last CHOCO_E_HIP */

@@ -1685,6 +1685,7 @@ int choco_set_lookahead(choco_ctx* ctx, int enable) {
 int choco_sync(choco_ctx* ctx) {
   if (!ctx) return CHOCO_E_INVAL;
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  if (ctx->aux_stream) HIP_TRY(ctx, hipStreamSynchronize(ctx->aux_stream));   // a selection made ahead writes the workspace
   return CHOCO_OK;
 }
 
