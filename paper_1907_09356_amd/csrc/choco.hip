@@ -1520,7 +1520,9 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
     case CHOCO_Q_QSGD: {
       if (!Wa.codes) return CHOCO_E_INVAL;
       if (Wa.nlayers) {
-        HIP_TRY(ctx, hipMemsetAsync(Wa.status, 0, (size_t)Wa.n * sizeof(uint32_t), ctx->stream));
+        // (a fill kernel, not a memset node: the call may sit in a captured graph)
+        LAUNCH(ctx, KID_ZERO_WORDS, k_zero_words, dim3((unsigned)((Wa.n + 255) / 256)), dim3(256), 0, Wa.status,
+               (int64_t)Wa.n);
         LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg);
         LAUNCH(ctx, KID_WIRE, k_pack_gsgd_layers_finish, dim3((unsigned)Wa.nlayers, (unsigned)Wa.n), dim3(64), 0, Wa,
                msg);
