@@ -1617,6 +1617,10 @@ int choco_layer_scalars(choco_ctx* ctx, double* scalars_host) {
                               hipMemcpyDeviceToHost, ctx->stream));
   const size_t nlong = ctx->long_layers.size();
   std::vector<WorkerCtl> ctl((size_t)A.n * nlong);
+  if (nlong) {
+    const int rc = join_lookahead(ctx);   // the control blocks may be under the next step's selection
+    if (rc != CHOCO_OK) return rc;
+  }
   if (nlong)
     HIP_TRY(ctx, hipMemcpyAsync(ctl.data(), A.ctl, ctl.size() * sizeof(WorkerCtl), hipMemcpyDeviceToHost, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
