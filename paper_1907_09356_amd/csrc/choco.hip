@@ -737,8 +737,6 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   // entries of x; otherwise only the first pass may see it
   if (!F.deferred_sgd) A.G = nullptr;
   const bool fused = F.G != nullptr && !F.deferred_sgd;
-  const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
   bool fuse_mix = false;     // the mix rides on the select pass (top_a, printed order, incremental sums)
@@ -883,8 +881,6 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   Args A = F;
   if (!F.deferred_sgd) A.G = nullptr;
   const bool fused = F.G != nullptr && !F.deferred_sgd;
-  const int32_t nvec = (A.d + 3) >> 2;
-  const dim3 sgrid = chunk_grid(nvec, A.n, kStreamVecs);
   const bool mix_first = ctx->cfg.order == CHOCO_ORDER_MIX_THEN_COMPRESS;
   bool x_touched = false;
   if (mix_first) {
