@@ -1,0 +1,90 @@
+"""GPU parity on randomly drawn configurations: sizes, topologies, operators, orders, mix forms,
+layer tables and call sequences come from a seeded generator, so that corners nobody thought of
+get a turn (every case is reproducible from its number)."""
+import numpy as np
+import pytest
+
+from paper_1907_09356_amd import binding as B
+from paper_1907_09356_amd import synth
+from tests.parity_util import Pair
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(case):
+    rng = np.random.default_rng(1000 + case)
+    comp = [B.Q_TOPK, B.Q_RANDK, B.Q_SIGN, B.Q_QSGD][case % 4]
+    sparse = comp in (B.Q_TOPK, B.Q_RANDK)
+    n = int(rng.choice([1, 2, 3, 5, 8, 9, 12, 16, 17]))
+    topo_kind = rng.choice(["ring", "torus", "irregular"]) if n >= 4 else "ring"
+    if topo_kind == "torus":
+        side = {4: (2, 2), 5: (1, 5), 8: (2, 4), 9: (3, 3), 12: (3, 4), 16: (4, 4), 17: (1, 17)}
+        a, b = side.get(n, (1, n))
+        topo = synth.torus_csr(a, b) if a > 1 and b > 1 else synth.ring_csr(n)
+    elif topo_kind == "irregular":
+        topo = synth.metropolis_csr(synth.irregular_graph(n, min(n - 1, 6), seed=case))
+    else:
+        topo = synth.ring_csr(n)
+    kw = dict(compressor=comp, order=int(rng.choice([B.ORDER_COMPRESS_THEN_MIX, B.ORDER_MIX_THEN_COMPRESS])),
+              seed=int(rng.integers(0, 2 ** 40)))
+    layered = bool(rng.random() < 0.4)
+    layers = None
+    if layered:
+        nl = int(rng.integers(1, 9))
+        lengths = [int(x) for x in rng.choice([1, 2, 3, 5, 17, 255, 256, 257, 1000, 2561, 4099, 10241, 12000], size=nl)]
+        if rng.random() < 0.25:
+            lengths[int(rng.integers(0, nl))] = int(rng.choice([40961, 45000, 70001]))   # a long layer
+        start, length, k = synth.layer_table(lengths, fraction=float(rng.choice([0.01, 0.05, 0.3])))
+        if sparse and nl > 1 and rng.random() < 0.3:
+            k[int(rng.integers(0, nl))] = 0
+            if k.sum() == 0:
+                k[0] = 1
+        layers = (start, length, k)
+        d = synth.layers_dim(layers)
+    else:
+        d = int(rng.choice([1, 3, 4, 5, 63, 64, 257, 1000, 4097, 30011, 65536, 100003]))
+        if sparse:
+            kw["k"] = int(max(1, min(d, rng.choice([1, 2, d // 100 + 1, d // 10 + 1, d]))))
+        if sparse and rng.random() < 0.5:
+            kw["mix_form"] = int(rng.choice([B.MIX_INCREMENTAL_S, B.MIX_DIRECT]))
+    if comp == B.Q_QSGD:
+        kw["levels"] = int(rng.choice([1, 2, 3, 16, 255]))
+        kw["qsgd_biased"] = int(rng.integers(0, 2))
+    if comp == B.Q_RANDK:
+        kw["randk_rescale"] = int(rng.integers(0, 2))
+    ld_align = int(rng.choice([4, 4, 64]))
+    calls = [str(c) for c in rng.choice(["step", "separate", "gossip", "momentum"], size=4)]
+    return dict(n=n, d=d, topo=topo, kw=kw, layers=layers, ld_align=ld_align, calls=calls,
+                gamma=float(rng.choice([0.05, 0.3, 0.9])), std=float(rng.choice([1.0, 0.05, 1e-3])))
+
+
+@pytest.mark.parametrize("case", range(160))
+def test_random_configuration(case):
+    c = draw_case(case)
+    n, d = c["n"], c["d"]
+    X0 = synth.normal_state(n, d, seed=case, std=c["std"])
+    inside = np.ones(d, dtype=bool)
+    if c["layers"] is not None:
+        inside[:] = False
+        for a, ln in zip(c["layers"][0], c["layers"][1]):
+            inside[a:a + ln] = True
+        X0[:, ~inside] = 0.0
+    pair = Pair(X0, c["topo"], c["gamma"], layers=c["layers"], ld_align=c["ld_align"], **c["kw"])
+    grads = synth.GradientStream(n, d, seed=case + 7, noise_std=0.05 * c["std"], bias_std=0.02 * c["std"])
+    tag = "case %d %s" % (case, {k: v for k, v in c.items() if k not in ("topo", "layers")})
+    try:
+        for t, call in enumerate(c["calls"]):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            if call == "step":
+                det = pair.step(G, 0.1)
+            elif call == "separate":
+                pair.sgd_step(G, 0.1)
+                det = pair.gossip_step()
+            elif call == "momentum":
+                det = pair.step_momentum(G, 0.05, 0.9, 1e-4)
+            else:
+                det = pair.gossip_step()
+            pair.check(det, tag="%s, call %d (%s)" % (tag, t, call))
+    finally:
+        pair.close()
