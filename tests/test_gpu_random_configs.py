@@ -88,3 +88,53 @@ def test_random_configuration(case):
             pair.check(det, tag="%s, call %d (%s)" % (tag, t, call))
     finally:
         pair.close()
+
+
+def draw_large_case(case):
+    """Shapes that fill the chip (and run the look-ahead selection beside real work)."""
+    rng = np.random.default_rng(5000 + case)
+    comp = [B.Q_RANDK, B.Q_TOPK, B.Q_RANDK, B.Q_SIGN, B.Q_QSGD][case % 5]
+    n = int(rng.choice([32, 48, 64]))
+    topo = synth.ring_csr(n) if rng.random() < 0.5 else synth.torus_csr(8, n // 8)
+    kw = dict(compressor=comp, seed=int(rng.integers(0, 2 ** 40)),
+              order=int(rng.choice([B.ORDER_COMPRESS_THEN_MIX, B.ORDER_MIX_THEN_COMPRESS])))
+    layers = None
+    if rng.random() < 0.6:
+        nl = int(rng.integers(8, 40))
+        lengths = [int(x) for x in rng.choice([16, 64, 432, 2304, 4608, 9216, 18432, 36864, 40960], size=nl)]
+        if rng.random() < 0.3:
+            lengths[0] = int(rng.choice([41000, 147456]))
+        layers = synth.layer_table(lengths, fraction=float(rng.choice([0.01, 0.03])))
+        d = synth.layers_dim(layers)
+    else:
+        d = int(rng.choice([100_003, 270_000, 327_680, 327_684, 400_001]))
+        if comp in (B.Q_TOPK, B.Q_RANDK):
+            kw["k"] = max(1, d // int(rng.choice([100, 1000])))
+    if comp == B.Q_QSGD:
+        kw["levels"] = int(rng.choice([4, 16]))
+    if comp == B.Q_RANDK:
+        kw["randk_rescale"] = int(rng.integers(0, 2))
+    return dict(n=n, d=d, topo=topo, kw=kw, layers=layers)
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_configuration_that_fills_the_chip(case):
+    c = draw_large_case(case)
+    n, d = c["n"], c["d"]
+    X0 = synth.normal_state(n, d, seed=case, std=0.05)
+    inside = np.ones(d, dtype=bool)
+    if c["layers"] is not None:
+        inside[:] = False
+        for a, ln in zip(c["layers"][0], c["layers"][1]):
+            inside[a:a + ln] = True
+        X0[:, ~inside] = 0.0
+    pair = Pair(X0, c["topo"], 0.05, layers=c["layers"], ld_align=64, **c["kw"])
+    grads = synth.GradientStream(n, d, seed=case + 7, noise_std=0.01, bias_std=0.001)
+    try:
+        for t in range(4):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step(G, 0.1)
+            pair.check(det, tag="large case %d (n=%d, d=%d, %s) step %d" % (case, n, d, c["kw"], t))
+    finally:
+        pair.close()
