@@ -137,6 +137,9 @@ KERNEL_BYTES_PER_ELEM = {
 MEASURED_TRAFFIC_BYTES = {
     ("large_topk", "k_sel_compact_sgd"): 3_588_944_585,
     ("large_topk", "k_mix_incremental"): 3_583_997_952,
+    # profiles/large_qsgd_trace_and_hbm_counters.txt
+    ("large_qsgd", "k_dense_stat_sgd"): 3_585_801_727,
+    ("large_qsgd", "k_dense_apply_mix"): 3_584_029_593,
 }
 
 
