@@ -74,6 +74,8 @@ struct choco_ctx {
   SelectPlan plan;        // whole-vector top_a / random_a
   std::vector<LongLayer> long_layers;   // top_a / random_a layer by layer: layers above CHOCO_MAX_LAYER_LEN
   bool long_silent;       // one of them keeps nothing (its pass cannot carry the local update)
+  bool overlap_long;      // top_a, several long layers: a layer's select runs on the second stream beside the next layer's pass
+  size_t set_hist16, set_cand, set_hist_parts, set_small_list;   // bytes from one long layer's select scratch to the next
   bool long_rows;         // d > 2^21: four 4-vectors per thread in the streaming kernels
   uint64_t t;             // step counter
   uint32_t* wire_rank;    // random_a without a bitmap: n x ceil(ld / 1024) chunk ranks of the message encoder
@@ -109,6 +111,8 @@ struct Layout {
   uint32_t cand_cap, seg_cap;
   int64_t bitmap_words;
   bool multipart;
+  int32_t select_sets;   // copies of the select scratch (candidate lists, histograms, short list)
+  size_t hist16_bytes, cand_bytes, hist_parts_bytes, small_list_bytes;   // size of one copy
   int32_t nchunks, ngroups;
 };
 
@@ -337,13 +341,20 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   }
   L.cand_cap = (uint32_t)cap;
   L.seg_cap = (uint32_t)seg_cap;
-  L.hist16 = take(guessed ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
-  L.cand = take(guessed ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
+  // top_a with several long layers: a set of select scratch per long layer, so that one layer's
+  // select can run (on the library's second stream) beside the next layer's pass over the rows
+  L.select_sets = (c.compressor == CHOCO_Q_TOPK && longs.size() >= 2) ? (int32_t)longs.size() : 1;
+  L.hist16_bytes = align_up(guessed ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
+  L.cand_bytes = align_up(guessed ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
+  L.hist16 = take(L.hist16_bytes * (size_t)L.select_sets);
+  L.cand = take(L.cand_bytes * (size_t)L.select_sets);
   L.sel_idx = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.sel_val = take(sparse ? (size_t)c.n * (size_t)kept * sizeof(float) : 0);
   L.multipart = guessed && multipart;
-  L.hist_parts = take(L.multipart ? (size_t)c.n * kRefineParts * kBins * sizeof(uint32_t) : 0);
-  L.small_list = take(L.multipart ? (size_t)c.n * kSmallCap * sizeof(uint2) : 0);
+  L.hist_parts_bytes = align_up(L.multipart ? (size_t)c.n * kRefineParts * kBins * sizeof(uint32_t) : 0);
+  L.small_list_bytes = align_up(L.multipart ? (size_t)c.n * kSmallCap * sizeof(uint2) : 0);
+  L.hist_parts = take(L.hist_parts_bytes * (size_t)L.select_sets);
+  L.small_list = take(L.small_list_bytes * (size_t)L.select_sets);
   // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
   // beside its other arrays), else one byte per entry
   L.bitmap_words = (guessed && !layered && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
@@ -827,41 +838,59 @@ int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
 }
 
 // The guessed-threshold select of one long layer (number `which` of ctx->long_layers): the
-// launches of the whole-vector path on argument blocks that point at the layer's piece of the
-// rows.  C is the block for the first pass (it may carry the local update), A the one without.
+// launches of the whole-vector path on an argument block that points at the layer's piece of
+// the rows (and, where the layers' selects overlap, at the layer's own select scratch).
+Args long_layer_args(const choco_ctx* ctx, const Args& src, int which) {
+  const LongLayer& B = ctx->long_layers[(size_t)which];
+  Args R = src;
+  R.X += B.start;
+  R.Xhat += B.start;
+  if (R.G) R.G += B.start;
+  if (R.M) R.M += B.start;
+  R.keptmap += B.start;
+  R.d = B.len;
+  R.k = B.k;
+  R.ctl = src.ctl + (int64_t)which * src.n;
+  R.sel_idx += B.sel_base;     // sel_stride stays the worker's whole list
+  R.sel_val += B.sel_base;
+  R.idx_base = B.start;
+  R.vec_base = (uint32_t)B.start >> 2;
+  apply_plan(R, B.plan);
+  if (ctx->overlap_long) {
+    R.hist16 = (uint32_t*)((char*)src.hist16 + (size_t)which * ctx->set_hist16);
+    R.cand = (uint2*)((char*)src.cand + (size_t)which * ctx->set_cand);
+    R.hist_parts = (uint32_t*)((char*)src.hist_parts + (size_t)which * ctx->set_hist_parts);
+    R.small_list = (uint2*)((char*)src.small_list + (size_t)which * ctx->set_small_list);
+  }
+  return R;
+}
+
+// ... its pass over the rows (C may carry the local update) ...
 template <int COMP, bool NT>
-void select_long_layer(choco_ctx* ctx, const Args& C, const Args& A, int which) {
+void long_layer_pass(choco_ctx* ctx, const Args& C, int which) {
   const LongLayer& B = ctx->long_layers[(size_t)which];
   if (B.k == 0) return;
-  auto narrow = [&](const Args& src) {
-    Args R = src;
-    R.X += B.start;
-    R.Xhat += B.start;
-    if (R.G) R.G += B.start;
-    if (R.M) R.M += B.start;
-    R.keptmap += B.start;
-    R.d = B.len;
-    R.k = B.k;
-    R.ctl = src.ctl + (int64_t)which * src.n;
-    R.sel_idx += B.sel_base;     // sel_stride stays the worker's whole list
-    R.sel_val += B.sel_base;
-    R.idx_base = B.start;
-    R.vec_base = (uint32_t)B.start >> 2;
-    apply_plan(R, B.plan);
-    return R;
-  };
-  const Args Cl = narrow(C), Al = narrow(A);
+  const Args Cl = long_layer_args(ctx, C, which);
   const int kid_compact = Cl.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
   const int32_t nvec = (B.len + 3) >> 2;
-  if (B.plan.fallback_chain) {
-    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), chunk_grid(nvec, A.n, kCompactVecs),
+  if (B.plan.fallback_chain)
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), chunk_grid(nvec, C.n, kCompactVecs),
            dim3(256), ahead_lds_pad(ctx, B.len), Cl);
+  else
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), chunk_grid(nvec, C.n, 2), dim3(256), 0, Cl);
+}
+
+// ... and the exact select on its candidates (A: no local update).
+template <int COMP, bool NT>
+void long_layer_select(choco_ctx* ctx, const Args& A, int which) {
+  const LongLayer& B = ctx->long_layers[(size_t)which];
+  if (B.k == 0) return;
+  const Args Al = long_layer_args(ctx, A, which);
+  if (B.plan.fallback_chain) {
     const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
     LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, Al);
     LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
     LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, Al);
-  } else {
-    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), chunk_grid(nvec, A.n, 2), dim3(256), 0, Cl);
   }
   if (B.plan.multipart) {
     const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
@@ -896,8 +925,24 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the chip
   // still is not full, so one launch does (a launch costs more than idle threads)
   const bool one_launch = (int64_t)one_launch_blocks * A.n <= 256;
-  // the layer kernel(s) for the layers within its reach, then the long layers one after the other
-  auto select_layers = [&](const Args& S) {
+  // the long layers one after the other, then the layer kernel(s) for the layers within its reach
+  auto select_layers = [&](const Args& S) -> int {
+    Args Q = S;
+    Q.G = nullptr;
+    Q.M = nullptr;
+    // top_a with several long layers: a layer's select (a few small launches that wait on
+    // memory) goes to the second stream and runs beside the next layer's pass over the rows
+    const bool overlap = COMP == Q_TOPK && ctx->overlap_long && !ctx->profiling && ctx->launch_stream == ctx->stream;
+    for (int b = 0; b < nlong; ++b) {
+      long_layer_pass<COMP, NT>(ctx, S, b);
+      if (overlap) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+        HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+        ctx->launch_stream = ctx->aux_stream;
+      }
+      long_layer_select<COMP, NT>(ctx, Q, b);
+      ctx->launch_stream = overlap ? ctx->stream : ctx->launch_stream;
+    }
     const int kid = S.G ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
     if (one_launch) {
       if (one_launch_blocks > 0)
@@ -911,10 +956,11 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
         LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
                dim3(256), 0, S, nlong + nlarge, nmid);
     }
-    Args Q = S;
-    Q.G = nullptr;
-    Q.M = nullptr;
-    for (int b = 0; b < nlong; ++b) select_long_layer<COMP, NT>(ctx, S, Q, b);
+    if (overlap && nlong > 0) {   // the caller's stream goes on when the last select is done
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_ahead, 0));
+    }
+    return CHOCO_OK;
   };
   // random_a: this step's masks may already have been drawn on the second stream
   const bool ahead = COMP == Q_RANDK && ctx->lookahead && !ctx->profiling;
@@ -923,12 +969,15 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     const int rc = look_ahead_begin(ctx, A, ahead, &selected);
     if (rc != CHOCO_OK) return rc;
   }
-  if (!selected) select_layers(C);
+  if (!selected) {
+    const int rc = select_layers(C);
+    if (rc != CHOCO_OK) return rc;
+  }
   if (ahead) {
     const Args P = look_ahead_args(ctx, A);
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
-    select_layers(P);
+    (void)select_layers(P);
     rc = look_ahead_end(ctx, A);
     if (rc != CHOCO_OK) return rc;
   }
@@ -1234,6 +1283,20 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
   ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
   ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
+  ctx->overlap_long = L.select_sets > 1;
+  ctx->set_hist16 = L.hist16_bytes;
+  ctx->set_cand = L.cand_bytes;
+  ctx->set_hist_parts = L.hist_parts_bytes;
+  ctx->set_small_list = L.small_list_bytes;
+  if (ctx->overlap_long) {
+    hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
+    if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
+    if (se != hipSuccess) {
+      release_ctx(ctx);
+      return CHOCO_E_HIP;
+    }
+  }
   if (cfg->compressor == CHOCO_Q_RANDK) {
     ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
     if (L.bitmap_words > 0) ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
