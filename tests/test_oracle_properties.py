@@ -91,3 +91,34 @@ def test_a_gossip_step_preserves_the_average_of_the_iterates(seed, n, d, comp, o
     mean = st_.X.astype(np.float64).mean(axis=0)
     scale = max(1.0, float(np.abs(X0).max()))
     assert np.max(np.abs(mean - mean0)) <= 2e-5 * scale
+
+
+@settings(max_examples=40, deadline=None)
+@given(seed=st.integers(0, 2 ** 31), lengths=st.lists(st.integers(1, 200), min_size=1, max_size=6),
+       comp=st.sampled_from(["topk", "randk", "sign", "qsgd"]), frac=st.floats(0.0, 1.0))
+def test_layer_by_layer_is_the_operator_on_every_slice_and_its_messages_decode(seed, lengths, comp, frac):
+    # Section 5: the operator is applied to every layer on its own; a worker's message is the
+    # layers' messages one after the other
+    start, pos = [], 0
+    for ln in lengths:
+        start.append(pos)
+        pos = (pos + ln + 3) // 4 * 4
+    d = start[-1] + lengths[-1]
+    k = [max(1, min(ln, int(round(frac * ln)))) for ln in lengths]
+    layers = (np.array(start, dtype=np.int64), np.array(lengths, dtype=np.int64), np.array(k, dtype=np.int64))
+    v = vector(seed, d, 0)
+    for a, ln in zip(start, lengths):       # the padding between layers is never sent
+        v[a + ln:(a + ln + 3) // 4 * 4] = 0.0
+    c = {"topk": ref.TOPK, "randk": ref.RANDK, "sign": ref.SIGN, "qsgd": ref.QSGD}[comp]
+    kw = dict(levels=3, seed=seed, t=4, worker=1)
+    try:
+        q, msg = ref.pack_layers(c, v, layers, **kw)
+    except ValueError:
+        assert comp == "qsgd"
+        return
+    assert msg.size == ref.layers_message_words(c, layers, 3)
+    assert np.array_equal(ref.unpack_layers(c, d, msg, layers, **kw), q)
+    if comp in ("topk", "sign"):            # no randomness: the slice alone gives the same
+        for a, ln, kl in zip(start, lengths, k):
+            alone = ref.compress(c, v[a:a + ln], k=kl)["q"]
+            assert np.array_equal(q[a:a + ln], alone)
