@@ -7,7 +7,8 @@
 // load it.
 //
 // What follows the paper and what is a reading of it:
-//   * Algorithm 1 (CHOCO-SGD), lines 2-7 and 9, and the matrix form of
+//   * Algorithm 1 (CHOCO-SGD): its mixing, compression, exchange and local
+//     gradient steps, and the matrix form of
 //     CHOCO-Gossip in Appendix A ("Example: CHOCO-SGD"):
 //         X+ = X + gamma * Xhat (W - I),   Xhat+ = Xhat + Q(X+ - Xhat).
 //   * Appendix C (compression schemes): gsgd_b, random_a, top_a, sign.
@@ -263,17 +264,17 @@ void compress(const QParams& P, int64_t d, const R* v, uint64_t t, int worker, R
 }
 
 // ---------------------------------------------------------------------------
-// One CHOCO-Gossip step for all n workers (Algorithm 1, lines 2-7).
+// One CHOCO-Gossip step for all n workers (Algorithm 1 without its gradient step).
 //   X, Xhat, S: n x d row-major.  S_i = sum_j w_ij xhat_j is the third vector
 //   a node keeps (Section 3, remark after Algorithm 1); it is only read and
 //   written when mix_form == MIX_INCREMENTAL_S.
 //   W: CSR with the self-loop stored explicitly, columns ascending in a row.
 // Order of the two halves:
-//   ORDER_MIX_THEN_COMPRESS  Algorithm 1 as printed: line 2, then lines 3-7.
-//   ORDER_COMPRESS_THEN_MIX  lines 3-7 first, then line 2 with the new xhat.
+//   ORDER_MIX_THEN_COMPRESS  Algorithm 1 as printed: the mixing step, then compression and exchange.
+//   ORDER_COMPRESS_THEN_MIX  compression and exchange first, then the mixing step with the new xhat.
 // Mix forms (same mathematics, different fp rounding):
 //   MIX_DIRECT         acc = sum_p w_p (xhat_j - xhat_i) in CSR order from 0;
-//                      x_i += gamma * acc                       (line 2 as printed)
+//                      x_i += gamma * acc                       (the mixing step as printed)
 //   MIX_INCREMENTAL_S  s_i += w_p q_j in CSR order (only kept entries of q_j
 //                      for the sparsifying operators); x_i += gamma (s_i - xhat_i),
 //                      valid because rows of W sum to one (Assumption 1).
@@ -336,7 +337,7 @@ void compress_half(const QParams& P, const Segments& G, int n, int64_t d, const 
   std::vector<R> Qall((size_t)n * (size_t)d, (R)0);
   std::vector<int32_t> sel_all((size_t)n * (size_t)ktot);
   std::vector<R> v((size_t)d);
-  for (int i = 0; i < n; ++i) {  // line 3: q_i = Q(x_i - xhat_i), layer by layer
+  for (int i = 0; i < n; ++i) {  // compression: q_i = Q(x_i - xhat_i), layer by layer
     for (int64_t e = 0; e < d; ++e) v[(size_t)e] = X[(int64_t)i * d + e] - Xhat[(int64_t)i * d + e];
     int64_t filled = 0;
     for (int32_t l = 0; l < nseg; ++l) {
@@ -357,7 +358,7 @@ void compress_half(const QParams& P, const Segments& G, int n, int64_t d, const 
     }
   }
   if (sparse && sel_out && ktot > 0) std::memcpy(sel_out, sel_all.data(), sel_all.size() * sizeof(int32_t));
-  for (int j = 0; j < n; ++j) {  // line 6: xhat_j += q_j (one copy stands for all replicas)
+  for (int j = 0; j < n; ++j) {  // exchange: xhat_j += q_j (one copy stands for all replicas)
     R* xh = Xhat + (int64_t)j * d;
     const R* q = Qall.data() + (int64_t)j * d;
     if (sparse) {
@@ -639,7 +640,7 @@ void unpack_layers(const QParams& P, const Segments& G, int64_t d, uint64_t t, i
   }
 }
 
-// Algorithm 1, line 9: x_i <- x_i - eta g_i  (product rounded, then the difference).
+// Algorithm 1, local gradient step: x_i <- x_i - eta g_i  (product rounded, then the difference).
 template <class R>
 void sgd_step(int n, int64_t d, R* X, const R* G, R lr) {
   for (int64_t a = 0; a < (int64_t)n * d; ++a) {
@@ -648,7 +649,7 @@ void sgd_step(int n, int64_t d, R* X, const R* G, R lr) {
   }
 }
 
-// Algorithm 2, lines 9-10: v <- (g + lambda x) + beta v;  x <- x - eta v.
+// Algorithm 2, momentum and local step: v <- (g + lambda x) + beta v;  x <- x - eta v.
 template <class R>
 void momentum_step(int n, int64_t d, R* X, R* V, const R* G, R lr, R beta, R lambda) {
   for (int64_t a = 0; a < (int64_t)n * d; ++a) {

@@ -23,7 +23,7 @@ OPERATORS = [
 
 def oracle_messages(pair, q, t):
     """Messages and dense q of all workers for the compress half about to run on the oracle."""
-    v = pair.ref.X - pair.ref.Xhat          # line 3 of Algorithm 1, fp32 like both sides
+    v = pair.ref.X - pair.ref.Xhat          # what Algorithm 1 compresses, fp32 like both sides
     msgs, dense = [], []
     for i in range(pair.n):
         dq, m = ref.pack_message(q["compressor"], v[i], k=q.get("k", 1), levels=q.get("levels", 1),

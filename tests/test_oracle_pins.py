@@ -259,7 +259,7 @@ def test_topology_spectral_gaps_match_the_paper():
 
 
 # --------------------------------------------------------------------------
-# the gossip step (Algorithm 1 lines 2-7; Appendix A matrix form)
+# the gossip step (Algorithm 1 without its gradient step; Appendix A matrix form)
 # --------------------------------------------------------------------------
 ALL_Q = [
     dict(compressor=ref.IDENTITY),
@@ -350,22 +350,22 @@ def replica_simulation(X0, W, gamma, k, steps, grads, lr):
     x = [list(map(float, X0[i])) for i in range(n)]
     rep = [{j: [0.0] * d for j in nbrs[i]} for i in range(n)]
     for t in range(steps):
-        for i in range(n):                                   # line 2
+        for i in range(n):                                   # mixing step
             for e in range(d):
                 acc = 0.0
                 for j in nbrs[i]:
                     acc += float(W[i, j]) * (rep[i][j][e] - rep[i][i][e])
                 x[i][e] += gamma * acc
         msgs = []
-        for i in range(n):                                   # line 3
+        for i in range(n):                                   # compression
             v = [x[i][e] - rep[i][i][e] for e in range(d)]
             keep = sorted(range(d), key=lambda e: (-abs(v[e]), e))[:k]
             msgs.append({e: v[e] for e in keep})
-        for i in range(n):                                   # lines 4-7
+        for i in range(n):                                   # exchange, update of the replicas
             for j in nbrs[i]:
                 for e, val in msgs[j].items():
                     rep[i][j][e] += val
-        for i in range(n):                                   # lines 8-9
+        for i in range(n):                                   # local gradient step
             for e in range(d):
                 x[i][e] -= lr * float(grads[t][i, e])
     return np.array(x), np.array([rep[i][i] for i in range(n)])
@@ -535,7 +535,7 @@ def test_sgd_and_momentum_steps():
     X = rng.standard_normal((3, 17)).astype(np.float32)
     G = rng.standard_normal((3, 17)).astype(np.float32)
     st = ref.RefState(X, *synth.ring_csr(3), gamma=0.1, compressor=ref.IDENTITY)
-    st.sgd_step(G, 0.125)                                      # Algorithm 1 line 9
+    st.sgd_step(G, 0.125)                                      # Algorithm 1, local gradient step
     assert np.array_equal(st.X, X - np.float32(0.125) * G)
     # Algorithm 2: v <- (g + lambda x) + beta v ; x <- x - eta v, against numpy in fp64
     X64 = X.astype(np.float64)
