@@ -6,7 +6,7 @@
  *   Xhat  n x ld fp32, row i = public copy  xhat_i           (in the workspace)
  *   S     n x ld fp32, row i = sum_j w_ij xhat_j             (in the workspace)
  * following Algorithm 1 (CHOCO-SGD) of the paper and the remark after it that a
- * node needs three vectors.  "send q_i / receive q_j" (Algorithm 1, lines 4-6)
+ * node needs three vectors.  "send q_i / receive q_j" (the exchange of Algorithm 1)
  * is plain device-memory traffic here because all replicas of xhat_j are equal.
  *
  * Conventions
@@ -52,11 +52,11 @@ enum {
 
 /* Order of the two halves of one gossip step. */
 enum {
-  CHOCO_ORDER_COMPRESS_THEN_MIX = 0, /* Algorithm 1 lines 3-7, then line 2 with the new xhat */
-  CHOCO_ORDER_MIX_THEN_COMPRESS = 1  /* Algorithm 1 as printed: line 2, then lines 3-7       */
+  CHOCO_ORDER_COMPRESS_THEN_MIX = 0, /* compression and exchange, then the mixing step with the new xhat */
+  CHOCO_ORDER_MIX_THEN_COMPRESS = 1  /* Algorithm 1 as printed: mixing step, then compression and exchange */
 };
 
-/* How line 2 of Algorithm 1, x_i += gamma * sum_j w_ij (xhat_j - xhat_i), is evaluated. */
+/* How the mixing step of Algorithm 1, x_i += gamma * sum_j w_ij (xhat_j - xhat_i), is evaluated. */
 enum {
   CHOCO_MIX_AUTO = 0,          /* INCREMENTAL_S for top_a/random_a, DIRECT otherwise        */
   CHOCO_MIX_INCREMENTAL_S = 1, /* S_i += sum_j w_ij q_j (CSR order); x_i += gamma (S_i - xhat_i) */
@@ -71,7 +71,7 @@ typedef struct {
                          a multiple of 64 (rows on 256-byte boundaries) streams fastest.
                          Columns d..ld-1 are never compressed, selected or sent         */
   /* Mixing matrix W of Assumption 1 as CSR.  HOST pointers, copied during choco_init.
-     Row i lists the neighbours of i INCLUDING i itself (Algorithm 1, line 4), columns
+     Row i lists the neighbours of i INCLUDING i itself (the exchange of Algorithm 1), columns
      strictly ascending.  W must be symmetric with non-negative entries and rows summing
      to 1, each to within 1e-6.  The values are used as given (never renormalised).      */
   const int32_t *row_ptr_host; /* n + 1 entries */
@@ -124,30 +124,30 @@ int choco_workspace_bytes(const choco_config *cfg, size_t *bytes_host);
 int choco_init(const choco_config *cfg, float *x_dev, void *workspace_dev, size_t workspace_bytes,
                choco_ctx **out);
 
-/* One CHOCO-Gossip round for all workers (Algorithm 1 lines 2-7; matrix form in
+/* One CHOCO-Gossip round for all workers (Algorithm 1 without its gradient step; matrix form in
    Appendix A, "Example: CHOCO-SGD"): v_i = x_i - xhat_i, q_i = Q(v_i), xhat_j += q_j,
    x_i += gamma sum_j w_ij (xhat_j - xhat_i), in the configured order.  Asynchronous;
    advances the step counter t used to key the random operators. */
 int choco_gossip_step(choco_ctx *ctx);
 
-/* Algorithm 1 line 9: x_i <- x_i - lr * g_i.  g_dev: n*ld floats, 16-byte aligned. */
+/* The local gradient step of Algorithm 1: x_i <- x_i - lr * g_i.  g_dev: n*ld floats, 16-byte aligned. */
 int choco_sgd_step(choco_ctx *ctx, const float *g_dev, float lr);
 
-/* One whole iteration in the order of Algorithm 3 (Appendix A): the stochastic gradient
-   update of line 2 there (= Algorithm 1 line 9) with (g, lr), then the gossip step.  The
+/* One whole iteration in the order of Algorithm 3 (Appendix A): its stochastic gradient
+   update (the local gradient step of Algorithm 1) with (g, lr), then the gossip step.  The
    result is bit for bit that of choco_sgd_step followed by choco_gossip_step; where the
    configured operator starts with a dense pass over X (sign, gsgd, top_a; or the mix of the
    printed order) the local update is folded into that pass, which saves one read and one
    write of X.  g_dev: n*ld floats, 16-byte aligned.  Asynchronous; advances t. */
 int choco_step(choco_ctx *ctx, const float *g_dev, float lr);
 
-/* Algorithm 2 lines 9-10 (momentum with weight decay):
+/* The momentum and gradient steps of Algorithm 2 (momentum with weight decay):
    m_i <- (g_i + lambda x_i) + beta m_i;  x_i <- x_i - lr m_i.
    m_dev: n*ld floats of caller-owned momentum memory, zero before the first call. */
 int choco_momentum_step(choco_ctx *ctx, const float *g_dev, float *m_dev, float lr, float beta,
                         float lambda);
 
-/* One whole iteration of the momentum variant (Algorithm 2): lines 9-10 there, then the
+/* One whole iteration of the momentum variant (Algorithm 2): its local update, then the
    gossip step; bit for bit choco_momentum_step followed by choco_gossip_step, with the
    local update folded into a dense pass over X like choco_step.  m_dev as above. */
 int choco_step_momentum(choco_ctx *ctx, const float *g_dev, float *m_dev, float lr, float beta,

@@ -102,7 +102,7 @@ struct Args {
   WorkerCtl* ctl;
   float gamma;
   // fused local update (choco_step): when G is non-null the first pass over X of the step
-  // also does x <- x - lr * g (Algorithm 1 line 9) before using x
+  // also does x <- x - lr * g (Algorithm 1, local gradient step) before using x
   const float* G;
   float lr;
   float* M;              // momentum memory (Algorithm 2) or null for plain SGD
@@ -222,7 +222,7 @@ __device__ __forceinline__ void store4(float* p, vf4 v) {
   else *q = v;
 }
 // The local update of one 4-vector at offset o, riding on a pass that has x in registers:
-//   plain (Algorithm 1 line 9):      x <- x - lr g
+//   plain (Algorithm 1, gradient step): x <- x - lr g
 //   momentum (Algorithm 2, l. 9-10): m <- (g + lambda x) + beta m (stored);  x <- x - lr m
 // Every product and sum rounded on its own, as in k_sgd / k_momentum.
 template <bool NT, class ArgsT>
@@ -367,7 +367,7 @@ __device__ __forceinline__ float encode(float v, const RowScale<COMP>& sc, uint3
   return neg ? -mag : mag;
 }
 
-// xhat += Q(x - xhat) on one 4-vector (Algorithm 1 lines 3 and 6).
+// xhat += Q(x - xhat) on one 4-vector (Algorithm 1: compression and update of the public copy).
 template <int COMP>
 __device__ __forceinline__ vf4 absorb(const vf4& x, vf4 xh, const RowScale<COMP>& sc, const uint4& words,
                                       vi4& code) {
@@ -383,7 +383,7 @@ __device__ __forceinline__ vf4 absorb(const vf4& x, vf4 xh, const RowScale<COMP>
 }
 
 // ---------------------------------------------------------------------------
-// Local updates (Algorithm 1 line 9; Algorithm 2 lines 9-10).
+// Local updates (the gradient step of Algorithm 1; the momentum and gradient steps of Algorithm 2).
 // grid (ceil(nvec / (256 * kStreamVecs)), n)
 // ---------------------------------------------------------------------------
 template <bool NT>
@@ -618,8 +618,8 @@ __global__ __launch_bounds__(256) void k_group_reduce(Args A) {
 // One block owns a tile of 256 consecutive columns for ALL n rows, so every
 // xhat row is read from HBM once and shared through LDS by the (at most 5)
 // workers that mix with it:
-//   phase 1  q = Q(x - xhat), xhat += q   (Algorithm 1 lines 3-6), new xhat -> HBM + LDS
-//   phase 2  x += gamma * sum_p w_p (xhat_j - xhat_i)   (line 2), CSR order, from LDS
+//   phase 1  q = Q(x - xhat), xhat += q   (Algorithm 1, compression and exchange), new xhat -> HBM + LDS
+//   phase 2  x += gamma * sum_p w_p (xhat_j - xhat_i)   (its mixing step), CSR order, from LDS
 // A block has NW waves (4 for n <= 16, else 16); wave w owns rows w, w+NW, ...; RPW = rows
 // per wave (compile-time bound, x stays in registers between the phases).  Dynamic LDS:
 // n * 256 floats (64 KiB at n = 64: two 1024-thread blocks per CU keep it fully occupied).
@@ -710,7 +710,7 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
 }
 
 // ---------------------------------------------------------------------------
-// Tile mix with the xhat that is in memory now (Algorithm 1 line 2, direct
+// Tile mix with the xhat that is in memory now (Algorithm 1, mixing step, direct
 // form), optionally followed by the chunk sums of v = x_new - xhat for the
 // printed order (mix, then compress).  Same tiling as above; the tile is one
 // first-level norm chunk, so the chunk sum falls out of one wave butterfly.
@@ -758,7 +758,7 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
   }
 }
 
-// Element-wise xhat += Q(x - xhat) (Algorithm 1 lines 3-6) with no mixing.
+// Element-wise xhat += Q(x - xhat) (Algorithm 1, compression and exchange) with no mixing.
 // grid (ceil(nvec / (256 * kStreamVecs)), n)
 template <int COMP, bool CAPTURE, bool NT, bool LAYERED>
 __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
@@ -842,7 +842,7 @@ __global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
       if (A.G) x[u] = local_update4<NT>(A, o, x[u]);
       if (A.fold_xhat) {
         // short rows, compress-then-mix order: xhat += q for this step's kept entries
-        // (Algorithm 1 line 6) rides on this pass, read off the worker's bitmap
+        // (Algorithm 1, update of the public copies) rides on this pass, read off the worker's bitmap
         const uint32_t e = 4u * (uint32_t)m;
         const uint32_t bits = (A.bitmap[(int64_t)i * A.bitmap_words + (e >> 5)] >> (e & 31u)) & 0xFu;
         if (bits) {
@@ -1775,7 +1775,7 @@ __global__ __launch_bounds__(256) void k_zero_words(uint32_t* p, int64_t words) 
   if (o < words) p[o] = 0u;
 }
 
-// xhat_j[e] += q_j[e] for the kept entries (Algorithm 1 line 6); clears the
+// xhat_j[e] += q_j[e] for the kept entries (Algorithm 1, update of the public copies); clears the
 // kept-map bytes it used.  grid (ceil(k/256), n)
 __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int j = blockIdx.y;
