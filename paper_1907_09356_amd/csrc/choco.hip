@@ -56,9 +56,9 @@ struct choco_ctx {
   uint64_t ahead_t;
   int32_t* sel_idx_buf[2];
   uint32_t* bitmap_buf[2];
-  uint8_t* keptmap_buf[2];
+  uint32_t* keptmap_buf[2];
   double* layer_scal_buf[2];
-  int ahead_map_buf;      // rows without a bitmap: the byte-map copy that holds a selection made ahead and not yet used (-1: none)
+  int ahead_map_buf;      // rows without an LDS bitmap: the bit-map copy that holds a selection made ahead and not yet used (-1: none)
   int last_buf;           // which copy the last finished step used
   int32_t maxdeg;
   int32_t nnz;
@@ -358,14 +358,15 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
   // beside its other arrays), else one byte per entry
   L.bitmap_words = (guessed && !layered && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
-  L.keptmap = take(sparse && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
+  const size_t map_bytes = (size_t)c.n * (size_t)((ld + 31) / 32) * sizeof(uint32_t);   // a bit per entry
+  L.keptmap = take(sparse && !L.bitmap_words ? map_bytes : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   // second copies for the look-ahead selection of random_a: the kept-index lists, the bitmap
-  // (short rows in whole-vector mode) or the byte map, the per-layer scalars
+  // (short rows in whole-vector mode) or the bit map in global memory, the per-layer scalars
   const bool ahead = c.compressor == CHOCO_Q_RANDK;
   L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
   L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
-  L.keptmap2 = take(ahead && !L.bitmap_words ? (size_t)c.n * (size_t)ld : 0);
+  L.keptmap2 = take(ahead && !L.bitmap_words ? map_bytes : 0);
   L.layer_scal2 = take(ahead && layered ? (size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double) : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
@@ -688,15 +689,15 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
 // selection of step t + 1 runs on the library's second stream beside the rest of step t.
 // look_ahead_begin: was this step's selection made ahead?  It joins the second stream and, if a
 // selection made ahead is being dropped (counter set, look-ahead or timing switched), clears
-// the marks it left in its copy of the byte map (no xhat update ever would).
+// the marks it left in its copy of the bit map (no xhat update ever would).
 int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) {
   *selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
   const int rc = join_lookahead(ctx);
   if (rc != CHOCO_OK) return rc;
   if (!*selected && ctx->ahead_map_buf >= 0) {
-    const int64_t words = (int64_t)A.n * A.ld / 4;   // ld is a multiple of 4
+    const int64_t words = (int64_t)A.n * A.map_words;
     LAUNCH(ctx, KID_ZERO_WORDS, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
-           (uint32_t*)ctx->keptmap_buf[ctx->ahead_map_buf], words);
+           ctx->keptmap_buf[ctx->ahead_map_buf], words);
   }
   ctx->ahead_map_buf = -1;
   ctx->ahead_valid = false;
@@ -847,7 +848,6 @@ Args long_layer_args(const choco_ctx* ctx, const Args& src, int which) {
   R.Xhat += B.start;
   if (R.G) R.G += B.start;
   if (R.M) R.M += B.start;
-  R.keptmap += B.start;
   R.d = B.len;
   R.k = B.k;
   R.ctl = src.ctl + (int64_t)which * src.n;
@@ -1136,6 +1136,7 @@ WireArgs wire_args(const choco_ctx* ctx) {
   Wa.bitmap = ctx->bitmap_buf[ctx->last_buf];
   Wa.bitmap_words = A.bitmap_words;
   Wa.keptmap = ctx->keptmap_buf[ctx->last_buf];
+  Wa.map_words = A.map_words;
   Wa.chunk_rank = ctx->wire_rank;
   Wa.nchunk = (A.ld + 1023) / 1024;
   return Wa;
@@ -1145,8 +1146,8 @@ WireArgs wire_args(const choco_ctx* ctx) {
 // map and count them chunk by chunk, so that a kept entry's rank is a table look-up plus a
 // count inside its own chunk.  The caller clears the marks again.
 void launch_rank_tables(choco_ctx* ctx, const WireArgs& Wa) {
-  LAUNCH(ctx, KID_WIRE, k_wire_mark, dim3((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n), dim3(256), 0, Wa, (uint8_t)1);
-  LAUNCH(ctx, KID_WIRE, k_wire_chunk_counts, dim3((unsigned)Wa.nchunk, (unsigned)Wa.n), dim3(256), 0, Wa);
+  LAUNCH(ctx, KID_WIRE, k_wire_mark, dim3((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n), dim3(256), 0, Wa, 1);
+  LAUNCH(ctx, KID_WIRE, k_wire_chunk_counts, dim3((unsigned)((Wa.nchunk + 7) / 8), (unsigned)Wa.n), dim3(256), 0, Wa);
   LAUNCH(ctx, KID_WIRE, k_wire_chunk_scan, dim3((unsigned)Wa.n), dim3(1024), 0, Wa);
 }
 
@@ -1277,7 +1278,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.vec_base = 0;
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
-  A.keptmap = (uint8_t*)(base + L.keptmap);
+  A.keptmap = (uint32_t*)(base + L.keptmap);
+  A.map_words = (A.ld + 31) / 32;
   A.bitmap = (uint32_t*)(base + L.bitmap);
   A.bitmap_words = L.bitmap_words;
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
@@ -1300,7 +1302,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   if (cfg->compressor == CHOCO_Q_RANDK) {
     ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
     if (L.bitmap_words > 0) ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
-    else ctx->keptmap_buf[1] = (uint8_t*)(base + L.keptmap2);
+    else ctx->keptmap_buf[1] = (uint32_t*)(base + L.keptmap2);
     hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
@@ -1609,7 +1611,7 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
         launch_rank_tables(ctx, Wa);
         LAUNCH(ctx, KID_WIRE, k_pack_randk_ranked, dim3((unsigned)((Wa.k + 3) / 4), (unsigned)Wa.n), dim3(256), 0, Wa,
                msg);
-        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, (uint8_t)0);
+        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, 0);
       }
       break;
     default: return CHOCO_E_UNSUPPORTED;
@@ -1651,7 +1653,7 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
         launch_rank_tables(ctx, Wa);
         LAUNCH(ctx, KID_WIRE, k_unpack_randk_ranked, dim3((unsigned)((Wa.k + 3) / 4), (unsigned)Wa.n), dim3(256), 0,
                Wa, msg, q_dev);
-        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, (uint8_t)0);
+        LAUNCH(ctx, KID_WIRE, k_wire_mark, kgrid, dim3(256), 0, Wa, 0);
       }
       break;
     default: return CHOCO_E_UNSUPPORTED;

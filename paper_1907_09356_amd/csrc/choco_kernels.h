@@ -138,9 +138,12 @@ struct Args {
   int64_t sel_stride;  // slots per worker in sel_idx / sel_val (k for the whole vector)
   int32_t idx_base;    // is added to the kept indices (the layer's first entry; 0 for the whole vector)
   uint32_t vec_base;   // is added to the 4-vector number that keys the random words (idx_base / 4)
-  uint8_t* keptmap;    // n x ld bytes: byte e of row j non-zero <=> worker j kept entry e this step
+  uint32_t* keptmap;   // n x map_words: bit e of row j set <=> worker j kept entry e this step (rows without a
+                       // bitmap built in LDS: set with atomics by the select, cleared by the xhat update; a bit
+                       // per entry keeps the scatter's look-ups in the caches, bytes did not)
+  int64_t map_words;   // ceil(ld / 32)
   uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
-  int64_t bitmap_words;  // 0: use the byte map
+  int64_t bitmap_words;  // 0: use the bit map in global memory (keptmap)
   int32_t fold_xhat;     // the final mix also applies xhat += q (bitmap rows, compress-then-mix)
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
@@ -1278,17 +1281,18 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, uint32_t* grp, uin
 // Hand one kept entry to the message list of worker i (wave-aggregated slot).
 // Every lane of the wave must call it (keep = false for lanes with nothing).
 // Record that worker i kept entry idx: in the block's LDS bitmap when the row is short
-// enough to have one (it is copied to global memory at the end), else as a byte of the
-// kept-map (plain store: no two kept entries share a byte).
+// enough to have one (it is copied to global memory at the end), else as a bit of the
+// kept-entry map in global memory (idx counts from the start of the piece the select works on).
 __device__ __forceinline__ void mark_kept(const Args& A, int i, uint32_t idx, uint32_t* lbits) {
-  if (A.bitmap_words) atomicOr(&lbits[idx >> 5], 1u << (idx & 31u));
-  else A.keptmap[(int64_t)i * A.ld + idx] = 1;
+  // (lbits is null in the kernels that never see a row with an LDS bitmap)
+  if (lbits != nullptr && A.bitmap_words) atomicOr(&lbits[idx >> 5], 1u << (idx & 31u));
+  else atomicOr(&A.keptmap[(int64_t)i * A.map_words + ((idx + (uint32_t)A.idx_base) >> 5)], 1u << ((idx + (uint32_t)A.idx_base) & 31u));
 }
 
 // Did worker j keep entry e in this step?
 __device__ __forceinline__ bool was_kept(const Args& A, int j, int e) {
   if (A.bitmap_words) return (A.bitmap[(int64_t)j * A.bitmap_words + ((uint32_t)e >> 5)] >> ((uint32_t)e & 31u)) & 1u;
-  return A.keptmap[(int64_t)j * A.ld + e] != 0;
+  return (A.keptmap[(int64_t)j * A.map_words + ((uint32_t)e >> 5)] >> ((uint32_t)e & 31u)) & 1u;
 }
 
 // Copy the block's LDS bitmap of kept entries to global memory (rows short enough to have one).
@@ -1784,7 +1788,8 @@ __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int e = A.sel_idx[(int64_t)j * A.k + m];
   float* xh = A.Xhat + (int64_t)j * A.ld + e;
   *xh = *xh + A.sel_val[(int64_t)j * A.k + m];
-  if (!A.bitmap_words) A.keptmap[(int64_t)j * A.ld + e] = 0;   // the bitmap is rewritten whole every step
+  // (the bitmap is rewritten whole every step; the words of the bit map are cleared by whoever kept an entry in them)
+  if (!A.bitmap_words) A.keptmap[(int64_t)j * A.map_words + ((uint32_t)e >> 5)] = 0u;
 }
 
 // ---------------------------------------------------------------------------

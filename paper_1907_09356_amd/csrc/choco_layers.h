@@ -306,7 +306,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
               const int64_t dst = (int64_t)i * A.k + L.sel_base + slot;
               A.sel_idx[dst] = L.start + e;
               if (COMP == Q_TOPK) A.sel_val[dst] = v[it][c];
-              A.keptmap[row + e] = 1;
+              atomicOr(&A.keptmap[(int64_t)i * A.map_words + ((uint32_t)(L.start + e) >> 5)], 1u << ((uint32_t)(L.start + e) & 31u));
             }
           }
         }

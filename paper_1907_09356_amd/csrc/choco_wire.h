@@ -36,9 +36,10 @@ struct WireArgs {
   const float* sel_val;
   const uint32_t* bitmap;
   int64_t bitmap_words;
-  // random_a without a bitmap (long rows, layer by layer): ranks come from the byte map of kept
-  // entries, marked anew from the kept-index list for the duration of the call
-  uint8_t* keptmap;         // n x ld bytes, all zero between steps
+  // random_a without a bitmap built by the select (long rows, layer by layer): ranks come from the
+  // bit map of kept entries, marked anew from the kept-index list for the duration of the call
+  uint32_t* keptmap;        // n x map_words, all zero between steps
+  int64_t map_words;        // ceil(ld / 32)
   uint32_t* chunk_rank;     // n x nchunk: kept entries of a worker below each 1024-entry chunk
   int64_t nchunk;           // ceil(ld / 1024)
   // layer by layer: a worker's message is its layers' messages one after the other
@@ -396,36 +397,29 @@ __global__ __launch_bounds__(1024) void k_unpack_randk(WireArgs A, const uint32_
   }
 }
 
-// ---- random_a without a bitmap: ranks from the byte map ----
+// ---- random_a without a bitmap built by the select: ranks from the bit map in global memory ----
 
-// keptmap[i][e] = value for the kept entries of the last step.  grid (ceil(k / 256), n)
-__global__ __launch_bounds__(256) void k_wire_mark(WireArgs A, uint8_t value) {
+// Set (or clear the words of) the bits of the entries kept in the last step.  grid (ceil(k / 256), n)
+__global__ __launch_bounds__(256) void k_wire_mark(WireArgs A, int set) {
   const int i = blockIdx.y;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= A.k) return;
-  A.keptmap[(int64_t)i * A.ld + A.sel_idx[(int64_t)i * A.k + m]] = value;
+  const uint32_t e = (uint32_t)A.sel_idx[(int64_t)i * A.k + m];
+  uint32_t* word = A.keptmap + (int64_t)i * A.map_words + (e >> 5);
+  if (set) atomicOr(word, 1u << (e & 31u));
+  else *word = 0u;
 }
 
-// Marked bytes (each 0 or 1) of a 4-byte word of the map that lie below entry `limit`; the word
-// covers entries pos .. pos + 3.
-__device__ __forceinline__ uint32_t marked_below(uint32_t word, int64_t pos, int64_t limit) {
-  if (pos >= limit) return 0u;
-  if (pos + 4 > limit) word &= (1u << (8 * (uint32_t)(limit - pos))) - 1u;
-  return (uint32_t)__popc(word & 0x01010101u);
-}
-
-// chunk_rank[i][c] = marked entries of worker i in chunk c.  grid (nchunk, n), block 256
+// chunk_rank[i][c] = marked entries of worker i in chunk c (1024 entries = 32 words of the map).
+// Eight chunks per block, a word per thread.  grid (ceil(nchunk / 8), n), block 256
 __global__ __launch_bounds__(256) void k_wire_chunk_counts(WireArgs A) {
-  __shared__ uint32_t sh[4];
   const int i = blockIdx.y;
-  const int64_t pos = (int64_t)blockIdx.x * 1024 + 4 * (int64_t)threadIdx.x;
-  uint32_t c = 0;
-  if (pos < A.ld) c = marked_below(*reinterpret_cast<const uint32_t*>(A.keptmap + (int64_t)i * A.ld + pos), pos, A.ld);
+  const int64_t chunk = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+  const int64_t w = chunk * 32 + (threadIdx.x & 31);
+  uint32_t c = (chunk < A.nchunk && w < A.map_words) ? (uint32_t)__popc(A.keptmap[(int64_t)i * A.map_words + w]) : 0u;
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) c += __shfl_down(c, off, 64);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) A.chunk_rank[(int64_t)i * A.nchunk + blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+  for (int off = 16; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);   // stays inside the 32 lanes of a chunk
+  if ((threadIdx.x & 31) == 0 && chunk < A.nchunk) A.chunk_rank[(int64_t)i * A.nchunk + chunk] = c;
 }
 
 // In place: chunk_rank[i][c] = marked entries of worker i in the chunks before c.  grid n, block 1024
@@ -457,16 +451,16 @@ __global__ __launch_bounds__(1024) void k_wire_chunk_scan(WireArgs A) {
 }
 
 // Rank of kept entry e of worker i among the worker's kept entries; all 64 lanes of a wave
-// call it with the same e and get the same result (they share the 1 KiB of the map before e).
+// call it with the same e and get the same result (they share the words of e's chunk).
 __device__ __forceinline__ uint32_t rank_by_map(const WireArgs& A, int i, int64_t e) {
   const int lane = threadIdx.x & 63;
   const int64_t chunk = e >> 10;
-  const uint8_t* row = A.keptmap + (int64_t)i * A.ld;
+  const int64_t w = chunk * 32 + lane, we = e >> 5;
   uint32_t c = 0;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int64_t pos = chunk * 1024 + 4 * (int64_t)(lane + 64 * u);
-    if (pos < e) c += marked_below(*reinterpret_cast<const uint32_t*>(row + pos), pos, e);
+  if (lane < 32 && w <= we) {
+    uint32_t bits = A.keptmap[(int64_t)i * A.map_words + w];
+    if (w == we) bits &= (1u << ((uint32_t)e & 31u)) - 1u;
+    c = (uint32_t)__popc(bits);
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);

@@ -147,7 +147,7 @@ def test_layer_wise_selection_on_the_language_model_sizes(comp):
 
 
 def test_random_k_messages_of_the_large_model_shape():
-    # d = 28 M, k = 28,000: ranks through the byte map (27,344 chunks per worker)
+    # d = 28 M, k = 28,000: ranks through the bit map in global memory (27,344 chunks per worker)
     from oracle import choco_ref as ref
     n, d, k = 8, 28_000_000, 28_000
     X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)

@@ -490,7 +490,7 @@ def test_random_masks_selected_ahead_or_not_are_the_same(order):
 
 
 def test_random_masks_selected_ahead_on_rows_without_a_bitmap():
-    # above 327,680 entries the kept entries are marked in a byte map; it exists twice and a
+    # above 327,680 entries the kept entries are marked in a bit map in global memory; it exists twice and a
     # mask that was drawn ahead and then dropped (set_step) has its marks cleared again
     n, d, k = 3, 400_003, 3000
     X0 = synth.normal_state(n, d, seed=52)
@@ -507,7 +507,7 @@ def test_random_masks_selected_ahead_on_rows_without_a_bitmap():
                 pair.ref.t = 70
             if t % 2 == 0:
                 det = pair.step(grads.next(), 0.05)
-                pair.check(det, tag="lookahead, byte map, step %d" % t)
+                pair.check(det, tag="lookahead, bit map, step %d" % t)
                 continue
             # separate calls, and the message encoder, which marks and clears the same map
             from oracle import choco_ref as ref
@@ -515,7 +515,7 @@ def test_random_masks_selected_ahead_on_rows_without_a_bitmap():
             v = pair.ref.X - pair.ref.Xhat
             tt = pair.ref.t
             det = pair.gossip_step()
-            pair.check(det, tag="lookahead, byte map, step %d" % t)
+            pair.check(det, tag="lookahead, bit map, step %d" % t)
             msgs = pair.gpu.pack_messages()
             dense = pair.gpu.unpack_messages(msgs)
             pair.gpu.sync()

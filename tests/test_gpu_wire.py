@@ -162,7 +162,7 @@ def test_layered_messages_match_the_oracle(name, q):
 
 @pytest.mark.parametrize("rescale", [0, 1])
 def test_random_k_messages_on_rows_too_long_for_a_bitmap(rescale):
-    # above 327,680 entries the kept entries are ranked through the byte map and per-chunk
+    # above 327,680 entries the kept entries are ranked through the bit map in global memory and per-chunk
     # counts (the row ends inside a 1024-entry chunk and inside a 4-byte word of the map)
     n, d, k = 3, 400_003, 4000
     q = dict(compressor=binding.Q_RANDK, k=k, randk_rescale=rescale)
