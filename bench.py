@@ -135,8 +135,8 @@ KERNEL_BYTES_PER_ELEM = {
 # counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("large_topk", "k_sel_compact_sgd"): 3_588_944_585,
-    ("large_topk", "k_mix_incremental"): 3_583_997_952,
+    ("large_topk", "k_sel_compact_sgd"): 3_588_893_385,
+    ("large_topk", "k_mix_incremental"): 3_583_990_784,
     # profiles/large_qsgd_trace_and_hbm_counters.txt
     ("large_qsgd", "k_dense_stat_sgd"): 3_585_801_727,
     ("large_qsgd", "k_dense_apply_mix"): 3_584_029_593,
