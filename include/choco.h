@@ -159,6 +159,23 @@ int choco_step_momentum(choco_ctx *ctx, const float *g_dev, float *m_dev, float 
 int choco_metrics(choco_ctx *ctx, double *consensus_host, double *mean_norm_host,
                   double *psi_host);
 
+/* For callers that cannot allocate or wait: code under HIP graph capture, tight serving loops,
+   harnesses that forbid hipMalloc.  The figures of choco_metrics, finished on the device and
+   written to out_dev (3 doubles, 8-byte aligned, caller-owned device memory): {consensus
+   distance, ||xbar||_2, Psi}.  Same kernels as choco_metrics, but their partial sums go to an
+   array that is part of the loaded library (CHOCO_NOALLOC_SCRATCH_BYTES of device memory on
+   every GPU the library runs on, held until the process ends) instead of the workspace, the
+   result is not copied to the host and nothing is waited for: the call enqueues two kernels on
+   the context's stream and calls no allocating routine.  The address of the array on the
+   context's GPU is looked up once, by choco_init.  CHOCO_E_UNSUPPORTED for d above
+   CHOCO_NOALLOC_MAX_D (or a GPU number above 63); CHOCO_E_INVAL if the GPU current at the call
+   is not the one that was current in choco_init.  All contexts on one GPU share the array:
+   calls that overlap on one GPU (different streams) race; calls on one stream do not.  The
+   array keeps the last call's partial sums; a call overwrites every slot it reads. */
+#define CHOCO_NOALLOC_MAX_D (1 << 28)
+#define CHOCO_NOALLOC_SCRATCH_BYTES (1024 * 3 * 8)
+int choco_metrics_noalloc(choco_ctx *ctx, double *out_dev);
+
 /* Device pointers to Xhat and S (n*ld floats each, inside the workspace). */
 int choco_xhat(choco_ctx *ctx, float **xhat_dev);
 int choco_nsum(choco_ctx *ctx, float **s_dev);

@@ -23,7 +23,7 @@ EXPORTS = [
     "choco_set_capture", "choco_last_scalars", "choco_layer_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
     "choco_profile_report", "choco_paper_message_bits", "choco_message_bytes", "choco_pack_messages",
-    "choco_unpack_messages", "choco_set_lookahead",
+    "choco_unpack_messages", "choco_set_lookahead", "choco_metrics_noalloc",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
         L.choco_step_momentum.argtypes = [vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         dp = ctypes.POINTER(ctypes.c_double)
         L.choco_metrics.argtypes = [vp, dp, dp, dp]
+        L.choco_metrics_noalloc.argtypes = [vp, vp]
         L.choco_xhat.argtypes = [vp, ctypes.POINTER(vp)]
         L.choco_nsum.argtypes = [vp, ctypes.POINTER(vp)]
         L.choco_last_selection.argtypes = [vp, vp, vp]
@@ -243,6 +244,11 @@ class Choco:
         _check(lib().choco_metrics(self.ctx, ctypes.byref(c), ctypes.byref(m), ctypes.byref(p)),
                "choco_metrics")
         return dict(consensus=c.value, mean_norm=m.value, psi=p.value)
+
+    def metrics_noalloc(self, out):
+        """The three figures of metrics() written to `out` (3 float64 on the device); no wait."""
+        assert out.is_cuda and out.is_contiguous() and out.dtype == self.torch.float64 and out.numel() == 3
+        _check(lib().choco_metrics_noalloc(self.ctx, out.data_ptr()), "choco_metrics_noalloc")
 
     def _view(self, ptr):
         off = ptr - self.workspace.data_ptr()

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -38,6 +39,14 @@ struct LongLayer {
   int32_t start, len, k, sel_base, id;
   SelectPlan plan;
 };
+
+// Partial sums of choco_metrics_noalloc: the same three doubles per block that choco_metrics
+// keeps in the caller's workspace, here in device memory that belongs to the loaded library
+// (24 KiB on every GPU the library runs on, until the process ends).  In host code this name
+// is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr int kNoAllocBlocks = 1024;
+static __device__ __align__(256) double scratch[kNoAllocBlocks * 3];
+static_assert(sizeof(double) * kNoAllocBlocks * 3 == CHOCO_NOALLOC_SCRATCH_BYTES, "header states the size of the array");
 
 struct choco_ctx {
   choco_config cfg;       // scalar fields as given (host CSR pointers are not kept)
@@ -83,6 +92,8 @@ struct choco_ctx {
   const int64_t* wire_word_off;   // layer by layer: where each layer's message starts / prefix of plane lengths
   const int64_t* wire_plane_off;
   int64_t wire_words, wire_plane_words;
+  int device;             // the GPU that was current in choco_init
+  double* noalloc_scratch;   // address of `scratch` on that GPU (null: more GPUs than the table holds)
   double* metrics_part;   // device scratch of the metrics kernels
   double* metrics_out;
   int metrics_blocks;
@@ -452,6 +463,30 @@ int hip_fail(choco_ctx* ctx, hipError_t e) {
   } while (0)
 
 #define LAUNCH_CHECK(ctx) HIP_TRY(ctx, hipGetLastError())
+
+// Every GPU holds its own copy of `scratch` at its own address: resolved once per device, with
+// that device current, and kept.
+constexpr int kMaxGpus = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_addr[kMaxGpus] = {nullptr};
+
+hipError_t resolve_scratch(int* device_out, double** addr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  *device_out = dev;
+  *addr_out = nullptr;
+  if (dev < 0 || dev >= kMaxGpus) return hipSuccess;   // no table slot: the no-alloc call reports it
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_addr[dev] = (double*)p;
+  }
+  *addr_out = g_scratch_addr[dev];
+  return hipSuccess;
+}
 
 // Frees the host-side objects of a context (its own stream and events; never device memory).
 void release_ctx(choco_ctx* ctx) {
@@ -1394,6 +1429,17 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->metrics_out = (double*)(base + L.mout);
   ctx->metrics_blocks = kMetricsBlocks;
 
+  // the library's own scratch array on this GPU (used by choco_metrics_noalloc only)
+  ctx->device = -1;
+  ctx->noalloc_scratch = nullptr;
+  {
+    const hipError_t se = resolve_scratch(&ctx->device, &ctx->noalloc_scratch);
+    if (se != hipSuccess) {
+      release_ctx(ctx);
+      return CHOCO_E_HIP;
+    }
+  }
+
   // zero everything but the caller's X: xhat^(0) = 0, S = 0, counters, histograms, kept-entry map
   hipError_t e = hipMemsetAsync(workspace_dev, 0, L.total, ctx->stream);
   if (e == hipSuccess)
@@ -1506,6 +1552,26 @@ int choco_metrics(choco_ctx* ctx, double* consensus_host, double* mean_norm_host
   if (consensus_host) *consensus_host = out[0] / (double)A.n;
   if (mean_norm_host) *mean_norm_host = std::sqrt(out[1]);
   if (psi_host) *psi_host = out[0] + out[2];
+  return CHOCO_OK;
+}
+
+int choco_metrics_noalloc(choco_ctx* ctx, double* out_dev) {
+  if (!ctx || !out_dev || ((uintptr_t)out_dev & 7u) != 0) return CHOCO_E_INVAL;
+  const Args& A = ctx->args;
+  if ((int64_t)A.d > (int64_t)CHOCO_NOALLOC_MAX_D) return CHOCO_E_UNSUPPORTED;
+  if (!ctx->noalloc_scratch) return CHOCO_E_UNSUPPORTED;   // GPU number beyond the table of scratch addresses
+  int dev = -1;
+  HIP_TRY(ctx, hipGetDevice(&dev));
+  if (dev != ctx->device) return CHOCO_E_INVAL;            // the address kept is that GPU's
+  int blocks = (A.d + 255) / 256;
+  if (blocks > kNoAllocBlocks) blocks = kNoAllocBlocks;
+  // every block writes its three partial sums and the last kernel reads exactly `blocks` of them,
+  // so what an earlier (larger) call left behind in the array is never read: nothing to clear
+  hipLaunchKernelGGL(k_metrics_partial, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, A,
+                     ctx->noalloc_scratch);
+  hipLaunchKernelGGL(k_metrics_final_dev, dim3(1), dim3(64), 0, ctx->stream, ctx->noalloc_scratch, blocks,
+                     A.n, out_dev);
+  LAUNCH_CHECK(ctx);
   return CHOCO_OK;
 }
 

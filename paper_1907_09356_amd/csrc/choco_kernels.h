@@ -1832,4 +1832,22 @@ __global__ void k_metrics_final(const double* part, int nblocks, double* out) {
   }
 }
 
+// The same last step with the three figures finished on the device (no host arithmetic):
+//   out[0] = consensus distance (1/n) sum_i ||x_i - xbar||^2, out[1] = ||xbar||_2,
+//   out[2] = Psi = ||X - Xbar||_F^2 + ||X - Xhat||_F^2
+__global__ void k_metrics_final_dev(const double* part, int nblocks, int n, double* out) {
+  __shared__ double sums[3];
+  if (threadIdx.x < 3) {
+    double acc = 0.0;
+    for (int b = 0; b < nblocks; ++b) acc += part[3 * b + threadIdx.x];
+    sums[threadIdx.x] = acc;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    out[0] = sums[0] / (double)n;
+    out[1] = sqrt(sums[1]);
+    out[2] = sums[0] + sums[2];
+  }
+}
+
 }  // namespace choco
