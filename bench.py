@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the CHOCO-SGD iteration (local SGD step + CHOCO-Gossip step) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all] [--only]
 
 One "step" is one pass of the whole hot path over all n workers: choco_sgd_step followed by
 choco_gossip_step (difference, statistic/select, encode, public-copy update, neighbour sums,
@@ -9,10 +9,13 @@ mix).  Inputs are synthetic, seeded, generated on the device, and resident in HB
 timed region.  Prints ONE JSON line.
 
 The headline workload is the large-model shape (n = 8 ring, d = 28,000,000, top-k 0.1 %),
-the largest single-GPU configuration and the one where the HBM roofline is meaningful;
---all adds the same workload in the other supported formulations ("alternatives"), short
-runs of the other shapes, the layer-wise ones among them ("other_workloads"), and the time
-of the message encoder and decoder ("wire").
+the largest single-GPU configuration and the one where the HBM roofline is meaningful.  The
+same line also carries, in "alternatives", that workload in the other supported formulations
+(Algorithm 1 in its printed order; the other form of the mix) and, in "configs", a compact
+record of every other benchmark shape (d = 270,000 with n = 8 sign and n = 64 ring / torus x
+top-k / random-k; d = 28,000,000 with gsgd).  --all adds the layer-wise workloads
+("other_workloads") and the time of the message encoder and decoder ("wire"); --only runs the
+one workload and nothing else (the form the rocprofv3 runs use).
 """
 import argparse
 import json
@@ -131,16 +134,45 @@ KERNEL_BYTES_PER_ELEM = {
 }
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
-# counter scaled by what it reads for the 896,000,000-byte calibration copy (FETCH_SIZE x 2.000,
-# WRITE_SIZE x 1.000); see profiles/large_topk_hbm_counters.txt.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC_BYTES = {
-    ("large_topk", "k_sel_compact_sgd"): 3_588_893_385,
-    ("large_topk", "k_mix_incremental"): 3_583_990_784,
-    # profiles/large_qsgd_trace_and_hbm_counters.txt
-    ("large_qsgd", "k_dense_stat_sgd"): 3_585_801_727,
-    ("large_qsgd", "k_dense_apply_mix"): 3_584_029_593,
-}
+def profile_traffic(workload, kernel, mix, order, launched):
+    """HBM bytes per launch of `kernel` as the committed rocprofv3 counter summary of this
+    workload states them (profiles/<workload>_hbm_counters.txt: FETCH_SIZE and WRITE_SIZE per
+    dispatch, each scaled by what the counter read for the calibration copy).  The summary
+    names the formulation and the kernels of the run it was taken from; if this run's differ,
+    the figure would describe other code, and None is returned with the reason."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_counters.txt" % workload)
+    rel = os.path.relpath(path, ROOT)
+    if not os.path.exists(path):
+        return None, "no counter summary %s" % rel
+    traffic, kernels, form = {}, None, {}
+    for line in open(path):
+        parts = line.split()
+        if line.startswith("traffic:"):
+            kv = dict(p.split("=", 1) for p in parts[1:])
+            traffic[kv["kernel"]] = int(kv["bytes"])
+        elif line.startswith("kernels:"):
+            kernels = set(parts[1:])
+        elif line.startswith("formulation:"):
+            form = dict(p.split("=", 1) for p in parts[1:])
+    if form.get("mix") != mix or form.get("order") != order:
+        return None, "%s was taken with mix=%s order=%s, this run is mix=%s order=%s" % (
+            rel, form.get("mix"), form.get("order"), mix, order)
+    if kernels is None or kernels != set(launched):
+        return None, "%s lists kernels %s, this run launched %s" % (
+            rel, sorted(kernels or []), sorted(launched))
+    if kernel not in traffic:
+        return None, "%s has no traffic line for %s" % (rel, kernel)
+    return traffic[kernel], rel
+
+
+def message_bits_per_entry(w):
+    """Bits per entry that the encoding pass of a dense operator writes as the message
+    (Appendix C: 1 for sign, b = 1 + log2(s) for gsgd with s = 2^(b-1) levels)."""
+    if w["comp"] == "sign":
+        return 1
+    if w["comp"] == "qsgd":
+        return 1 + max(1, (w["levels"] - 1).bit_length())
+    return 0
 
 
 def make_topology(w):
@@ -208,10 +240,20 @@ def calibration_copy(torch, nbytes=896_000_000, reps=10):
         torch.add(a, b, alpha=2.0, out=c)
     torch.cuda.synchronize()
     el3 = (time.perf_counter() - t0) / reps
-    del a, b, c
+    # and a library 3-read / 1-write stream e = a + b * c (the access pattern of the mix pass)
+    e = torch.empty_like(a)
+    torch.addcmul(a, b, c, out=e)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        torch.addcmul(a, b, c, out=e)
+    torch.cuda.synchronize()
+    el4 = (time.perf_counter() - t0) / reps
+    del a, b, c, e
     torch.cuda.empty_cache()
     return dict(bytes_read=nbytes, bytes_written=nbytes, ms=1e3 * el, GBps=2 * nbytes / el / 1e9,
-                triad_ms=1e3 * el3, triad_GBps=3 * nbytes / el3 / 1e9)
+                triad_ms=1e3 * el3, triad_GBps=3 * nbytes / el3 / 1e9,
+                stream_3r1w_ms=1e3 * el4, stream_3r1w_GBps=4 * nbytes / el4 / 1e9)
 
 
 def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=None, momentum=False):
@@ -276,6 +318,9 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
                 bpe += 4 if name.endswith("_sgd") else 8   # the mix rides on this pass: + read s (+ write x)
             if bpe is not None and momentum and name.endswith("_sgd"):
                 bpe += 8                                   # + read and write the momentum memory
+            if bpe is not None and name in ("k_dense_apply_mix", "k_dense_apply"):
+                # + the message itself: one sign bit per entry (sign), b bits per entry (gsgd)
+                bpe += message_bits_per_entry(w) / 8.0
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
                 per_launch = bpe * elems
                 if "layers" in w and (name.startswith("k_layer_compress") or name.startswith("k_sel_compact")):
@@ -299,6 +344,7 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
         out["select"] = dict(k=w["k"], layers=int(len(lengths)),
                              bracket_hit_fraction=float(sc[:, :, 3].mean()),
                              bracket_hit_fraction_large_layers=float(sc[:, lengths > 10240, 3].mean()))
+    out["mix"] = {B.MIX_INCREMENTAL_S: "incremental", B.MIX_DIRECT: "direct"}[ctx.mix_form()]
     m = ctx.metrics()
     out["consensus_error"] = m["consensus"]
     out["mean_norm"] = m["mean_norm"]
@@ -350,45 +396,135 @@ def step_bytes_per_elem(w, kernels):
     return total / (w["n"] * w["d"])
 
 
-def cpu_baseline(w, budget_s=15.0):
-    """The oracle as it stands, one thread, on a bounded sample of the same workload: the
-    same n, topology, operator and hyper-parameters with d cut to d/10 (k cut alike)."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def host_inputs(w, seed=20190709):
+    """The workload's inputs in host memory at full size (float32, made row by row): x0 shared
+    by all workers, two gradient buffers g = b_i + eps."""
+    import numpy as np
+    n, d = w["n"], w["d"]
+    rng = np.random.default_rng(seed)
+    row = rng.standard_normal(d, dtype=np.float32) * np.float32(0.05)
+    X0 = np.repeat(row[None, :], n, axis=0)
+    bias = None
+    if w["bias_std"] > 0:
+        bias = rng.standard_normal((n, d), dtype=np.float32) * np.float32(w["bias_std"])
+    G = []
+    for _ in range(2):
+        g = np.empty((n, d), dtype=np.float32)
+        for i in range(n):
+            g[i] = rng.standard_normal(d, dtype=np.float32) * np.float32(0.01)
+        if bias is not None:
+            g += bias
+        G.append(g)
+    return X0, G
+
+
+def cpu_baseline(w, mix, order, steps=3):
+    """The oracle as it stands on the SAME workload at full size: `steps` iterations of
+    sgd_step + gossip_step after one warm-up iteration, one thread (the oracle is
+    single-threaded).  Second figure: min(n, host cores) threads, each stepping ONE worker's
+    row at full d through the same oracle (a one-node graph: that worker's difference,
+    statistic / select, encode, public-copy update and mix; the neighbours' terms of the mix
+    are left out), which is what one core per simulated worker would give.  The threads
+    run in the oracle's compiled code (ctypes releases the interpreter lock)."""
+    import threading
     import numpy as np
     from oracle import choco_ref as ref
-    from paper_1907_09356_amd import synth
-    frac = 10 if w["d"] >= 1_000_000 else 1
-    d = w["d"] // frac
-    n = w["n"]
+    n, d = w["n"], w["d"]
     comp = {"topk": ref.TOPK, "randk": ref.RANDK, "sign": ref.SIGN, "qsgd": ref.QSGD}[w["comp"]]
-    kw = dict(compressor=comp)
+    kw = dict(compressor=comp, mix_form={"incremental": ref.INCREMENTAL_S, "direct": ref.DIRECT}[mix],
+              order={"compress_then_mix": ref.COMPRESS_THEN_MIX, "mix_then_compress": ref.MIX_THEN_COMPRESS}[order])
     if "k" in w:
-        kw["k"] = max(1, w["k"] // frac)
+        kw["k"] = w["k"]
     if "levels" in w:
         kw["levels"] = w["levels"]
     layers = layer_table_of(w)
     if layers is not None:
         kw["layers"] = layers
-    X0 = synth.normal_state(n, d, seed=1, std=0.05, shared=True)
-    st = ref.RefState(X0, *make_topology(w), gamma=w["gamma"], seed=7, **kw)
-    grads = synth.GradientStream(n, d, seed=2, noise_std=0.01, bias_std=w["bias_std"])
-    G = [grads.next(), grads.next()]
-    st.sgd_step(G[0], w["lr"])   # warm-up step (page in, first-touch)
-    st.gossip_step()
-    steps = 0
     t0 = time.perf_counter()
-    while True:
-        st.sgd_step(G[steps & 1], w["lr"])
+    X0, G = host_inputs(w)
+    gen_s = time.perf_counter() - t0
+    st = ref.RefState(X0, *make_topology(w), gamma=w["gamma"], seed=7, **kw)
+    st.sgd_step(G[0], w["lr"])   # warm-up iteration (pages in the state, first touch)
+    st.gossip_step()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        st.sgd_step(G[(t + 1) & 1], w["lr"])
         st.gossip_step()
-        steps += 1
-        el = time.perf_counter() - t0
-        if el > budget_s or steps >= 400:
-            break
-    elem_rate = steps * n * d / el
-    return dict(value=elem_rate / (n * w["d"]), unit="steps/s", cores=1, kind="oracle",
-                element_updates_per_s=elem_rate,
-                sample="n=%d, d=%d (1/%d of the vector, k scaled alike), %d steps of sgd+gossip in "
-                       "%.1f s, single thread; value = measured element-updates/s divided by the "
-                       "full n*d" % (n, d, frac, steps, el))
+    el = time.perf_counter() - t0
+    del st
+    # one core per simulated worker
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    cores = max(1, min(n, avail, 16))
+    one = (np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32), np.array([1.0], dtype=np.float32))
+    states = [ref.RefState(X0[i:i + 1], *one, gamma=w["gamma"], seed=7, **kw) for i in range(n)]
+
+    def work(rank, first, count):
+        for i in range(rank, n, cores):
+            for t in range(first, first + count):
+                states[i].sgd_step(G[t & 1][i:i + 1], w["lr"])
+                states[i].gossip_step()
+
+    def run_threads(first, count):
+        th = [threading.Thread(target=work, args=(r, first, count)) for r in range(cores)]
+        for x in th:
+            x.start()
+        for x in th:
+            x.join()
+
+    run_threads(0, 1)             # warm-up
+    t0 = time.perf_counter()
+    run_threads(1, steps)
+    elp = time.perf_counter() - t0
+    return dict(value=steps / el, unit="steps/s", cores=1, kind="oracle",
+                element_updates_per_s=steps * n * d / el, seconds_per_step=el / steps,
+                cpu_model=cpu_model(), host_cores_available=avail,
+                sample="the full workload: n=%d, d=%d, %s, mix=%s, order=%s; %d iterations of sgd_step + gossip_step "
+                       "after 1 warm-up iteration, %.1f s; inputs generated on the host in %.1f s (not timed)"
+                       % (n, d, w["comp"], mix, order, steps, el, gen_s),
+                workers_in_parallel=dict(
+                    value=steps / elp, unit="steps/s", cores=cores, seconds_per_step=elp / steps,
+                    element_updates_per_s=steps * n * d / elp,
+                    what="%d threads, each stepping one worker's row at full d through the same oracle "
+                         "(one-node graph: the neighbours' terms of the mix are left out); %d iterations after "
+                         "1 warm-up" % (cores, steps)))
+
+
+def compact_record(name, w, r, steps):
+    """One line per workload for the "configs" array: time, rate and algorithmic bandwidth."""
+    elems = w["n"] * w["d"]
+    bpe = step_bytes_per_elem(w, r["kernels"])
+    gbps = bpe * elems * r["steps_per_s"] / 1e9
+    timed = {k: v for k, v in r["kernels"].items() if "alg_GBps" in v}
+    rec = dict(name=name, workload=w["desc"], n=w["n"], d=w["d"], mix=r["mix"], steps=steps,
+               ms_per_step=r["ms_per_step"], steps_per_s=r["steps_per_s"],
+               element_updates_per_s=r["steps_per_s"] * elems,
+               alg_bytes_per_elem=bpe, alg_GBps=gbps, frac_of_hbm_peak=gbps / HBM_PEAK_GBS,
+               kernels_us={k: round(1e3 * v["ms_per_step"], 2) for k, v in r["kernels"].items()})
+    if timed:
+        dom = max(timed, key=lambda k: timed[k]["ms_per_step"])
+        rec["dominant_kernel"] = dict(kernel=dom, avg_us=round(1e3 * timed[dom]["avg_ms"], 2),
+                                      alg_GBps=round(timed[dom]["alg_GBps"], 1),
+                                      frac_of_hbm_peak=round(timed[dom]["alg_GBps"] / HBM_PEAK_GBS, 4))
+    if "select" in r:
+        rec["select"] = r["select"]
+    return rec
+
+
+CONFIG_WORKLOADS = ["dc_sign", "p2p_ring_topk", "p2p_torus_topk", "p2p_ring_randk", "p2p_torus_randk",
+                    "large_qsgd"]
 
 
 def main():
@@ -397,11 +533,14 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large_topk", choices=sorted(WORKLOADS))
-    ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
+    ap.add_argument("--all", action="store_true",
+                    help="also time the layer-wise workloads and the message encoder / decoder")
+    ap.add_argument("--only", action="store_true",
+                    help="the one workload and nothing else: no alternatives, no other configs, no CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mix", choices=["auto", "incremental", "direct"], default="auto",
-                    help="evaluation of the mix: auto = incremental neighbour sums for top-k/random-k "
-                         "(the library default), direct = LDS-tiled, no S array")
+                    help="evaluation of the mix: auto = the library's choice (direct, LDS-tiled, no S array, "
+                         "wherever the tile of all rows fits; else incremental neighbour sums)")
     ap.add_argument("--order", choices=["compress_then_mix", "mix_then_compress"],
                     default="compress_then_mix",
                     help="order of the two halves of the gossip step (the second is Algorithm 1 as printed)")
@@ -421,8 +560,8 @@ def main():
     copy_ref = calibration_copy(torch)
     from paper_1907_09356_amd import binding as B
     mix_form = {"auto": None, "incremental": B.MIX_INCREMENTAL_S, "direct": B.MIX_DIRECT}[args.mix]
-    if w["comp"] in ("sign", "qsgd"):
-        mix_form = None   # dense operators always use the direct form
+    if w["comp"] in ("sign", "qsgd") or "layers" in w:
+        mix_form = None   # dense operators always use the direct form; layer tables take the library's choice
     order = (B.ORDER_MIX_THEN_COMPRESS if args.order == "mix_then_compress"
              else B.ORDER_COMPRESS_THEN_MIX)
     res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form, order=order,
@@ -432,12 +571,13 @@ def main():
     timed = {k: v for k, v in kernels.items() if "alg_GBps" in v}
     dominant = max(timed, key=lambda k: timed[k]["ms_per_step"])
     dk = timed[dominant]
+    traffic, traffic_source = None, "not a default run (unfused or momentum)"
+    if not args.unfused and not args.momentum:
+        traffic, traffic_source = profile_traffic(args.workload, dominant, res["mix"], args.order, kernels.keys())
     roofline = dict(bound="hbm", kernel=dominant, achieved=dk["alg_GBps"], peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=dk["alg_GBps"] / HBM_PEAK_GBS,
                     alg_bytes_per_launch=dk["alg_bytes_per_launch"], avg_launch_ms=dk["avg_ms"],
-                    traffic=(MEASURED_TRAFFIC_BYTES.get((args.workload, dominant))
-                             if args.mix == "auto" and args.order == "compress_then_mix" and not args.unfused and not args.momentum
-                             else None))
+                    traffic=traffic, traffic_source=traffic_source)
     bpe = step_bytes_per_elem(w, kernels)
     line = {
         "metric": "choco_gossip_steps_per_s",
@@ -456,7 +596,7 @@ def main():
                    "step": ("choco_sgd_step + choco_gossip_step" if args.unfused else
                             "choco_step (= choco_sgd_step + choco_gossip_step, local update fused "
                             "into the first pass)"),
-                   "order": args.order, "mix": args.mix,
+                   "order": args.order, "mix": res["mix"], "mix_requested": args.mix,
                    "local_update": "momentum 0.9, weight decay 1e-4 (Algorithm 2)" if args.momentum else "sgd"},
         "element_updates_per_s": res["steps_per_s"] * elems,
         "step_alg_bytes_per_elem": bpe,
@@ -471,45 +611,52 @@ def main():
     }
     if "select" in res:
         line["select"] = res["select"]
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w)
-    if args.all:
-        # the same workload in the other supported formulations (same results as the oracle's
-        # corresponding form): Algorithm 1's printed order, and the direct mix without S
+    if not args.only:
+        # the same workload in the other supported formulations (each has its own form of the
+        # oracle): the other evaluation of the mix, and Algorithm 1's printed order
         alts = []
+        variants = []
         if w["comp"] in ("topk", "randk") and "layers" not in w:
-            variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=mix_form)),
-                        ("mix=direct", dict(order=order, mix_form=B.MIX_DIRECT))]
-        else:
-            variants = [("order=mix_then_compress", dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=None))]
-        for label, kw in variants:
+            other = B.MIX_INCREMENTAL_S if res["mix"] == "direct" else B.MIX_DIRECT
+            variants.append(dict(order=order, mix_form=other))
+            variants.append(dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=B.MIX_INCREMENTAL_S))
+            variants.append(dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=B.MIX_DIRECT))
+        elif "layers" not in w:
+            variants.append(dict(order=B.ORDER_MIX_THEN_COMPRESS, mix_form=None))
+        for kw in variants:
             k = min(args.steps, 50)
             r = run_gpu(w, k, min(args.warmup, 10), fused=not args.unfused, momentum=args.momentum, **kw)
-            b = step_bytes_per_elem(w, r["kernels"])
-            alts.append(dict(variant=label, steps=k, ms_per_step=r["ms_per_step"],
-                             steps_per_s=r["steps_per_s"], step_alg_bytes_per_elem=b,
-                             step_alg_GBps=b * elems * r["steps_per_s"] / 1e9))
+            rec = compact_record(args.workload, w, r, k)
+            rec["order"] = ("mix_then_compress" if kw["order"] == B.ORDER_MIX_THEN_COMPRESS
+                            else "compress_then_mix")
+            del rec["workload"]
+            alts.append(rec)
         line["alternatives"] = alts
+        # every other benchmark shape, briefly (the library's default formulation)
+        confs = []
+        for name in CONFIG_WORKLOADS:
+            if name == args.workload:
+                continue
+            ow = WORKLOADS[name]
+            k = min(args.steps, 100)
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=None, order=order,
+                        momentum=args.momentum)
+            confs.append(compact_record(name, ow, r, k))
+        line["configs"] = confs
+    if not args.only and not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, res["mix"], args.order)
+    if args.all and not args.only:
         # encoder / decoder of the messages (Appendix C sizes) for the shapes they cover
         line["wire"] = [dict(name=name, **wire_bench(WORKLOADS[name]))
                         for name in ("dc_sign", "large_qsgd", "p2p_ring_topk", "p2p_ring_randk", "large_topk")]
         others = []
         for name, ow in WORKLOADS.items():
-            if name == args.workload:
+            if name == args.workload or name in CONFIG_WORKLOADS:
                 continue
             k = min(args.steps, 100)
-            omix = None if (ow["comp"] in ("sign", "qsgd") or "layers" in ow) else mix_form
-            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=omix, order=order,
+            r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=None, order=order,
                         momentum=args.momentum)
-            b = step_bytes_per_elem(ow, r["kernels"])
-            e = ow["n"] * ow["d"]
-            others.append(dict(name=name, workload=ow["desc"], steps=k, ms_per_step=r["ms_per_step"],
-                               steps_per_s=r["steps_per_s"],
-                               element_updates_per_s=r["steps_per_s"] * e,
-                               step_alg_bytes_per_elem=b,
-                               step_alg_GBps=b * e * r["steps_per_s"] / 1e9,
-                               select=r.get("select"),
-                               kernels={kk: round(v["ms_per_step"], 6) for kk, v in r["kernels"].items()}))
+            others.append(compact_record(name, ow, r, k))
         line["other_workloads"] = others
     print(json.dumps(line))
 

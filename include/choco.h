@@ -18,7 +18,7 @@
  *   - work is enqueued on the caller's stream (one documented exception: the look-ahead
  *     selection of RANDK, see choco_set_lookahead) and the calls return without
  *     synchronising, except choco_metrics, choco_last_scalars, choco_layer_scalars,
- *     choco_profile_report, choco_sync and (for QSGD) choco_pack_messages;
+ *     choco_profile_report, choco_sync and choco_last_message (when it returns a scale);
  *   - inputs must be finite; NaN/Inf give unspecified selections.
  */
 #ifndef CHOCO_H
@@ -65,7 +65,7 @@ enum {
 
 typedef struct {
   int32_t n;          /* number of workers, >= 1                                         */
-  int64_t d;          /* coordinates per worker, 1 <= d < 2^31                           */
+  int64_t d;          /* coordinates per worker, 1 <= d <= CHOCO_MAX_D                   */
   int64_t ld;         /* row stride of X, G and the internal arrays in floats; 0 means d
                          rounded up to a multiple of 4.  Must be >= d and a multiple of 4;
                          a multiple of 64 (rows on 256-byte boundaries) streams fastest.
@@ -95,10 +95,15 @@ typedef struct {
      compressed as a vector of its own - its own norm and its own length in the scales of
      SIGN and QSGD, layer_k[l] kept entries (0 <= layer_k[l] <= layer_len[l], at least one
      entry kept over all layers) for TOPK and RANDK, the field k above is then ignored.
-     The layers must tile the vector in order, each start padded to a multiple of 4:
-     layer_start[0] = 0, layer_start[l+1] = layer_start[l] + layer_len[l] rounded up to a
-     multiple of 4, d = layer_start[nlayers-1] + layer_len[nlayers-1].  The padding entries
-     are never transmitted (keep them zero in X and G).  Layers may have any length; for
+     The layers are any disjoint slices in ascending order (layer_start[l] >= layer_start[l-1] +
+     layer_len[l-1], layer_len[l] >= 1, the last one ends at or before d): a flat parameter
+     vector can be handed over as it is.  Entries that lie in no layer (gaps, padding) are never
+     compressed or transmitted - q is zero there whatever X and G hold - but they are part of x:
+     the local update and the mix apply to them like to any entry.  Fastest is a table whose
+     layers each start on a multiple of 4 and follow one another with only that padding between
+     them, from entry 0 to d: its layer passes use 16-byte accesses throughout and carry the
+     fused local update; any other table takes per-entry layer look-ups and the local update as a
+     pass of its own (same results).  Layers may have any length; for
      TOPK and RANDK one workgroup selects a layer of up to CHOCO_MAX_LAYER_LEN entries out
      of its registers and longer layers take the whole-vector select one after the other
      (they cost workspace for its candidate lists).  IDENTITY and a non-default mix_form
@@ -110,6 +115,7 @@ typedef struct {
 } choco_config;
 
 #define CHOCO_MAX_LAYER_LEN 40960
+#define CHOCO_MAX_D (((int64_t)1 << 31) - ((int64_t)1 << 19)) /* rows are indexed in 32 bits with some headroom */
 
 /* Bytes of device workspace choco_init needs for this configuration (Xhat, S, the CSR
    copy and scratch for the operators).  Validates the scalar fields of cfg only. */
@@ -118,7 +124,7 @@ int choco_workspace_bytes(const choco_config *cfg, size_t *bytes_host);
 /* Algorithm 1, input line: takes X = x^(-1/2) as it stands in x_dev (n*ld floats, 16-byte
    aligned, caller-owned, updated in place by every step), sets xhat_i^(0) = 0, S = 0,
    t = 0.  workspace_dev must be 256-byte aligned.  CHOCO_E_INVAL for n < 1, d out of
-   range, bad ld, k outside [1, d], levels < 1, gamma <= 0 or not finite, null pointers,
+   range (above CHOCO_MAX_D), bad ld, k outside [1, d], levels < 1, gamma <= 0 or not finite, null pointers,
    malformed CSR, or a W that violates Assumption 1; CHOCO_E_NOMEM if the workspace is
    too small.  On error *out is NULL. */
 int choco_init(const choco_config *cfg, float *x_dev, void *workspace_dev, size_t workspace_bytes,
@@ -208,6 +214,21 @@ int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
    and choco_last_scalars is CHOCO_E_UNSUPPORTED.  Synchronises the stream. */
 int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
 
+/* What one worker sent in the last gossip step (the q_i of Algorithm 1's exchange), in one call:
+   TOPK / RANDK: its k kept (index, value) pairs to idx_dev / val_dev (k entries each, order
+   unspecified; with layers sum(layer_k) pairs, layer after layer);
+   SIGN / QSGD: its bit planes to bits_dev, W = ceil(d/32) words each, bit e%32 of word e/32:
+   plane 0 = the entry was sent negative (QSGD: and its level is not zero), then for QSGD mb
+   planes with the bits of min(level, 2^mb - 1), lowest first (mb as in choco_pack_messages);
+   scale_host: SIGN the scale ||v||_1/d, QSGD the step ||v||_2/(tau s), 0 for the others; with
+   layers these differ per layer (choco_layer_scalars) and scale_host must be NULL, and the
+   planes count bits from the start of the whole vector.
+   Pointers that do not apply to the operator, or that are NULL, are skipped.  The copies are
+   asynchronous on the context's stream; a non-NULL scale_host synchronises it.
+   CHOCO_E_INVAL for a worker outside [0, n) and for IDENTITY. */
+int choco_last_message(choco_ctx *ctx, int32_t worker, int32_t *idx_dev, float *val_dev,
+                       uint32_t *bits_dev, float *scale_host);
+
 /* Messages on the wire (Appendix C states a size with each operator).
    choco_paper_message_bits: that size in bits, host arithmetic only: SIGN d + 32, TOPK
    2*32*k, RANDK 32*k, QSGD b*d + 32 with b = log2(levels) + 1, IDENTITY 32*d.
@@ -221,9 +242,12 @@ int choco_layer_scalars(choco_ctx *ctx, double *scalars_host);
             mb = bit length of levels - 1 (at least 1): b bits per entry for levels = 2^(b-1)
      TOPK   k pairs [index][value as float], order of the pairs unspecified
      RANDK  k values as float, ascending index (the receiver repeats the draw of the mask)
-   SIGN and QSGD read the codes of the last step from the buffer given to choco_set_capture
-   (CHOCO_E_INVAL if capture is off); QSGD synchronises and returns CHOCO_E_UNSUPPORTED if
-   more than 4 entries sit at level `levels`.  choco_unpack_messages is the receiver's
+   For SIGN and QSGD the bits of the message are written by the gossip step itself (the pass
+   that encodes q also writes one sign bit, resp. b bits, per entry into bit planes in the
+   workspace); packing copies them behind the header and needs no capture buffer.  Four index
+   slots always suffice: an entry reaches level `levels` only if it holds more than half of the
+   vector's norm (up to rounding), and the squares of four such shares add up to the whole.
+   Asynchronous for every operator.  choco_unpack_messages is the receiver's
    side: it writes the dense q of every worker (n*ld floats, 16-byte aligned, zero where
    nothing was sent); for RANDK the mask is the one the library drew in the last step.
    Layer-wise configurations: a worker's message is the messages of its layers one after
@@ -239,6 +263,10 @@ int choco_pack_messages(choco_ctx *ctx, void *msgs_dev);
 int choco_unpack_messages(choco_ctx *ctx, const void *msgs_dev, float *q_dev);
 
 
+
+/* The evaluation of the mixing step this context uses, CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT:
+   what CHOCO_MIX_AUTO was resolved to by choco_init (see the enumeration above). */
+int choco_get_mix_form(choco_ctx *ctx, int32_t *mix_form_host);
 
 /* Step counter t (keys the random operators; set it to resume a run exactly). */
 int choco_get_step(choco_ctx *ctx, uint64_t *t_host);

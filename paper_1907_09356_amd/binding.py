@@ -23,7 +23,7 @@ EXPORTS = [
     "choco_set_capture", "choco_last_scalars", "choco_layer_scalars", "choco_get_step", "choco_set_step", "choco_sync",
     "choco_destroy", "choco_strerror", "choco_last_hip_error", "choco_set_profiling",
     "choco_profile_report", "choco_paper_message_bits", "choco_message_bytes", "choco_pack_messages",
-    "choco_unpack_messages", "choco_set_lookahead", "choco_metrics_noalloc",
+    "choco_unpack_messages", "choco_set_lookahead", "choco_metrics_noalloc", "choco_get_mix_form", "choco_last_message",
 ]
 
 
@@ -86,6 +86,7 @@ def lib():
         L.choco_nsum.argtypes = [vp, ctypes.POINTER(vp)]
         L.choco_last_selection.argtypes = [vp, vp, vp]
         L.choco_set_capture.argtypes = [vp, vp]
+        L.choco_last_message.argtypes = [vp, ctypes.c_int32, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
         L.choco_last_scalars.argtypes = [vp, dp]
         L.choco_layer_scalars.argtypes = [vp, dp]
         L.choco_paper_message_bits.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
@@ -93,6 +94,7 @@ def lib():
         L.choco_message_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         L.choco_pack_messages.argtypes = [vp, vp]
         L.choco_unpack_messages.argtypes = [vp, vp, vp]
+        L.choco_get_mix_form.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
         L.choco_get_step.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.choco_set_step.argtypes = [vp, ctypes.c_uint64]
         L.choco_sync.argtypes = [vp]
@@ -273,6 +275,26 @@ class Choco:
                "choco_last_selection")
         return idx, val
 
+    def last_message(self, worker):
+        """What `worker` sent in the last gossip step: dict(idx, val) for top_a / random_a,
+        dict(bits, scale) for sign / gsgd (bits: int32 CUDA tensor (planes, ceil(d/32)))."""
+        torch = self.torch
+        comp = int(self.cfg.compressor)
+        if comp in (Q_TOPK, Q_RANDK):
+            idx = torch.empty(self.k, dtype=torch.int32, device=self.X.device)
+            val = torch.empty(self.k, dtype=torch.float32, device=self.X.device)
+            _check(lib().choco_last_message(self.ctx, int(worker), idx.data_ptr(), val.data_ptr(), None, None),
+                   "choco_last_message")
+            return dict(idx=idx, val=val)
+        planes = 1
+        if comp == Q_QSGD:
+            planes = 1 + max(1, (int(self.cfg.levels) - 1).bit_length())
+        bits = torch.empty((planes, (self.d + 31) // 32), dtype=torch.int32, device=self.X.device)
+        scale = ctypes.c_float()
+        _check(lib().choco_last_message(self.ctx, int(worker), None, None, bits.data_ptr(),
+                                        None if self.nlayers else ctypes.byref(scale)), "choco_last_message")
+        return dict(bits=bits, scale=scale.value)
+
     def set_capture(self, codes):
         """codes: int32 CUDA tensor (n, ld) or None."""
         if codes is not None:
@@ -314,6 +336,12 @@ class Choco:
         q = self.torch.empty_like(self.X)
         _check(lib().choco_unpack_messages(self.ctx, msgs.data_ptr(), q.data_ptr()), "choco_unpack_messages")
         return q
+
+    def mix_form(self):
+        """MIX_INCREMENTAL_S or MIX_DIRECT: what the library resolved MIX_AUTO to."""
+        m = ctypes.c_int32()
+        _check(lib().choco_get_mix_form(self.ctx, ctypes.byref(m)), "choco_get_mix_form")
+        return m.value
 
     def get_step(self):
         t = ctypes.c_uint64()

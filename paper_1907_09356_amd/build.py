@@ -5,7 +5,6 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = [os.path.join(HERE, "csrc", "choco.hip")]
-DEPS = SRC + [os.path.join(HERE, "csrc", "choco_kernels.h"), os.path.join(ROOT, "include", "choco.h")]
 LIB = os.path.join(HERE, "libchoco.so")
 
 # -ffp-contract=off: every product and sum is rounded on its own, which the
@@ -14,12 +13,6 @@ LIB = os.path.join(HERE, "libchoco.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-shared", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
-
-
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    return any(os.path.getmtime(p) > os.path.getmtime(LIB) for p in DEPS)
 
 
 def build(verbose: bool = False) -> str:

@@ -72,6 +72,8 @@ struct choco_ctx {
   int32_t maxdeg;
   int32_t nnz;
   bool sparse;            // top_a / random_a
+  bool fused_sparse_apply;   // ... whose update of xhat rides on the tile mix pass (direct form, compress-then-mix)
+  bool values_in_qv;      // random_a after such a step: the kept values are in Qv, not yet in the list
   int mix_form;           // resolved: CHOCO_MIX_INCREMENTAL_S or CHOCO_MIX_DIRECT
   int rpw;                // rows per wave of the tile kernels, 0 = tile does not fit
   bool fused;             // the step being enqueued carries the local update in its first pass
@@ -79,6 +81,7 @@ struct choco_ctx {
   bool fallback_chain;    // long rows: a failed guess is repaired by the histogram passes, not a row scan
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   int nlayers;            // > 0: the operator is applied layer by layer
+  bool layers_generic;    // ... on a table that is not aligned (see layers_aligned): no pass carries the local update
   int nlarge, nmid;       // layers (by falling length, after the long ones) that take a 1024- / a 256-thread workgroup
   SelectPlan plan;        // whole-vector top_a / random_a
   std::vector<LongLayer> long_layers;   // top_a / random_a layer by layer: layers above CHOCO_MAX_LAYER_LEN
@@ -88,7 +91,7 @@ struct choco_ctx {
   bool long_rows;         // d > 2^21: four 4-vectors per thread in the streaming kernels
   uint64_t t;             // step counter
   uint32_t* wire_rank;    // random_a without a bitmap: n x ceil(ld / 1024) chunk ranks of the message encoder
-  uint32_t* wire;         // device scratch of the message encoder: n status words, then counters and index slots
+  uint64_t last_t;        // step counter the last finished gossip step ran with (tags what it remembered)
   const int64_t* wire_word_off;   // layer by layer: where each layer's message starts / prefix of plane lengths
   const int64_t* wire_plane_off;
   int64_t wire_words, wire_plane_words;
@@ -116,7 +119,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
       layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
-      chunk_layer, wire, wire_rank, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, mpart, mout, total;
+      chunk_layer, planes, ovf_ring, ovf_pos, wire_rank, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, qv, mpart, mout, total;
   int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
   uint32_t cand_cap, seg_cap;
@@ -129,13 +132,29 @@ struct Layout {
 
 bool is_sparse(int compressor) { return compressor == CHOCO_Q_TOPK || compressor == CHOCO_Q_RANDK; }
 
+// CHOCO_MIX_AUTO.  Dense operators: the direct form (the tile kernels, or rows read from global
+// memory).  top_a / random_a: the direct form too wherever the LDS tile of all n rows exists
+// (n <= kMaxTileRows) - one fused pass then applies the sparse update of xhat and the mix, no S
+// array, no scatter: measured faster at every size (n = 64, d = 270 k: 0.101 against 0.118 ms
+// before the passes were fused; n = 8, d = 28 M: 1.09 against 1.27 ms).  The incremental
+// neighbour sums remain for more workers than the tile holds, for layer tables, and for top_a in
+// the printed order, where mix and candidate pass are one 20 B/entry pass over S.
 int resolve_mix_form(const choco_config& c) {
-  if (c.mix_form == CHOCO_MIX_AUTO)
-    return is_sparse(c.compressor) ? CHOCO_MIX_INCREMENTAL_S : CHOCO_MIX_DIRECT;
-  return c.mix_form;
+  if (c.mix_form != CHOCO_MIX_AUTO) return c.mix_form;
+  if (!is_sparse(c.compressor)) return CHOCO_MIX_DIRECT;
+  if (c.nlayers > 0 || c.n > kMaxTileRows) return CHOCO_MIX_INCREMENTAL_S;
+  if (c.compressor == CHOCO_Q_TOPK && c.order == CHOCO_ORDER_MIX_THEN_COMPRESS) return CHOCO_MIX_INCREMENTAL_S;
+  return CHOCO_MIX_DIRECT;
 }
 
 int64_t resolve_ld(const choco_config& c) { return c.ld == 0 ? (c.d + 3) / 4 * 4 : c.ld; }
+
+// top_a / random_a, compress-then-mix order, direct form with the LDS tile: xhat += q is applied
+// by the mix pass itself (k_tile_mix<.., SPARSE>), off the kept-entry bits.
+bool fused_sparse_apply(const choco_config& c) {
+  return is_sparse(c.compressor) && c.nlayers == 0 && c.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
+         resolve_mix_form(c) == CHOCO_MIX_DIRECT && c.n <= kMaxTileRows;
+}
 
 // Kept entries per worker and step: k, or the sum over the layers.
 int64_t kept_per_worker(const choco_config& c) {
@@ -152,29 +171,45 @@ int check_layers(const choco_config* c) {
   if (!c->layer_start_host || !c->layer_len_host) return CHOCO_E_INVAL;
   const bool sparse = is_sparse(c->compressor);
   if (sparse && !c->layer_k_host) return CHOCO_E_INVAL;
-  int64_t expect = 0, end = 0, ktot = 0;
+  int64_t end = 0, ktot = 0;
   for (int32_t l = 0; l < c->nlayers; ++l) {
     const int64_t start = c->layer_start_host[l], len = c->layer_len_host[l];
-    if (start != expect || len < 1) return CHOCO_E_INVAL;
+    if (start < end || len < 1) return CHOCO_E_INVAL;   // disjoint, ascending, not empty
     end = start + len;
     if (end > c->d) return CHOCO_E_INVAL;
-    expect = (end + 3) / 4 * 4;
     if (sparse) {
       const int64_t k = c->layer_k_host[l];
       if (k < 0 || k > len) return CHOCO_E_INVAL;
       ktot += k;
     }
   }
-  if (end != c->d || (sparse && ktot < 1)) return CHOCO_E_INVAL;
+  if (sparse && ktot < 1) return CHOCO_E_INVAL;
   if (c->compressor == CHOCO_Q_IDENTITY || c->mix_form != CHOCO_MIX_AUTO)
     return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
 
+// A layer table is "aligned" if every layer starts on a multiple of 4, the layers follow one
+// another with only the padding to the next multiple of 4 between them, and they cover the
+// vector: a 16-byte 4-vector then never spans two layers and the layer passes can carry the
+// local update.  Any other table (layers that start anywhere, gaps, a vector that goes on
+// after the last layer) takes the generic paths: per-entry layer look-ups, entry-wise loads
+// where a layer's norm tree starts off a 16-byte boundary, the local update as its own pass.
+bool layers_aligned(const choco_config& c) {
+  int64_t expect = 0, end = 0;
+  for (int32_t l = 0; l < c.nlayers; ++l) {
+    if (c.layer_start_host[l] != expect) return false;
+    end = expect + c.layer_len_host[l];
+    expect = (end + 3) / 4 * 4;
+  }
+  return end == c.d;
+}
+
 // Scalar-field validation shared by choco_workspace_bytes and choco_init.
 int check_scalars(const choco_config* c) {
   if (!c) return CHOCO_E_INVAL;
-  if (c->n < 1 || c->d < 1 || c->d >= (int64_t)1 << 31) return CHOCO_E_INVAL;
+  // (the kernels index entries and 4-vectors of a row in int32 and step by up to 2^18 entries)
+  if (c->n < 1 || c->d < 1 || c->d > CHOCO_MAX_D) return CHOCO_E_INVAL;
   if (c->n > 65535) return CHOCO_E_UNSUPPORTED;   // workers are a grid dimension of the launches
   const int64_t ld = resolve_ld(*c);
   if (ld < c->d || (ld & 3) != 0) return CHOCO_E_INVAL;
@@ -270,7 +305,7 @@ std::vector<LongLayer> long_layers_of(const choco_config& c) {
   int64_t sel_base = 0;
   for (int32_t l = 0; l < c.nlayers; ++l) {
     const int64_t len = c.layer_len_host[l], k = c.layer_k_host[l];
-    if (len > kMaxLayerLen) {
+    if (len + (c.layer_start_host[l] & 3) > kMaxLayerLen) {   // (with the entries before it in its first 4-vector)
       LongLayer B{};
       B.start = (int32_t)c.layer_start_host[l];
       B.len = (int32_t)len;
@@ -367,7 +402,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.hist_parts = take(L.hist_parts_bytes * (size_t)L.select_sets);
   L.small_list = take(L.small_list_bytes * (size_t)L.select_sets);
   // kept entries: a bitmap per worker if it fits in the (single-block) select's LDS (40 KiB
-  // beside its other arrays), else one byte per entry
+  // beside its other arrays), else a bit per entry in global memory
   L.bitmap_words = (guessed && !layered && !L.multipart && c.d <= 40 * 1024 * 8) ? (c.d + 31) / 32 : 0;
   const size_t map_bytes = (size_t)c.n * (size_t)((ld + 31) / 32) * sizeof(uint32_t);   // a bit per entry
   L.keptmap = take(sparse && !L.bitmap_words ? map_bytes : 0);
@@ -394,9 +429,13 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_group_sums = take((size_t)c.n * (size_t)items * sizeof(double));
   L.layer_scale = take(dense_layers ? (size_t)c.n * (size_t)c.nlayers * sizeof(LayerScale) : 0);
   L.chunk_layer = take(dense_layers ? (size_t)L.nchunks * sizeof(int4) : 0);
-  // message encoder: n status words, then per (worker, layer) a counter and the index slots
+  // the message of a dense operator: bit planes written by the compress pass (sign: one plane;
+  // gsgd: the sign plane and mb magnitude planes) and, for gsgd, the ring of entries at level s
   const size_t wire_units = (size_t)c.n * (size_t)(layered ? c.nlayers : 1);
-  L.wire = take(((size_t)c.n + wire_units * (1 + kOverflowSlots)) * sizeof(uint32_t));
+  const int nplanes = c.compressor == CHOCO_Q_SIGN ? 1 : c.compressor == CHOCO_Q_QSGD ? 1 + magnitude_bits(c.levels) : 0;
+  L.planes = take((size_t)c.n * (size_t)nplanes * (size_t)((ld + 31) / 32) * sizeof(uint32_t));
+  L.ovf_ring = take(c.compressor == CHOCO_Q_QSGD ? wire_units * kOvfRing * sizeof(uint4) : 0);
+  L.ovf_pos = take(c.compressor == CHOCO_Q_QSGD ? wire_units * sizeof(uint32_t) : 0);
   L.wire_rank = take(c.compressor == CHOCO_Q_RANDK && !L.bitmap_words
                          ? (size_t)c.n * (size_t)((ld + 1023) / 1024) * sizeof(uint32_t) : 0);
   L.wire_word_off = take(dense_layers ? (size_t)(c.nlayers + 1) * sizeof(int64_t) : 0);
@@ -407,6 +446,8 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
       L.wire_words += message_words(c.compressor, c.layer_len_host[l], 0, c.levels);
       L.wire_plane_words += (c.layer_len_host[l] + 31) / 32;
     }
+  // random_a whose update of xhat rides on the fused mix pass: the kept values by entry
+  L.qv = take(fused_sparse_apply(c) && c.compressor == CHOCO_Q_RANDK ? state : 0);
   L.mpart = take((size_t)kMetricsBlocks * 3 * sizeof(double));
   L.mout = take(3 * sizeof(double));
   L.total = off;
@@ -514,12 +555,12 @@ int join_lookahead(choco_ctx* ctx) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_GATHER_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_gather_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
   "k_layer_compress", "k_layer_compress_sgd", "k_layer_stat", "k_layer_stat_sgd", "k_layer_finalise", "k_wire",
   "k_zero_words"};
@@ -562,7 +603,8 @@ dim3 chunk_grid(int32_t nvec, int32_t n, int vecs) {
 }
 
 // Tile kernels: waves per block (8 up to 8 workers - a row per wave measured 4 % faster than
-// two -, 4 up to 16, else 16) and rows per wave.
+// two -, 4 up to 16, else 16) and rows per wave.  (n = 64 with 8-wave workgroups of 8 rows per
+// wave, which leave half of a compute unit's wave slots free: the mix pass 55 against 43 us.)
 int pick_rpw(int n) {
   if (n > kMaxTileRows) return 0;
   const int nw = n <= 8 ? 8 : n <= 16 ? 4 : 16;
@@ -597,12 +639,12 @@ void launch_apply_mix(choco_ctx* ctx, const Args& A) {
 #undef CALL
 }
 
-template <int STAT, bool NT>
+template <int STAT, bool NT, bool SPARSE = false>
 void launch_tile_mix(choco_ctx* ctx, const Args& A, bool fused) {
-  const dim3 grid((unsigned)A.nchunks), block(A.n <= 8 ? 512 : A.n <= 16 ? 256 : 1024);
   const size_t lds = (size_t)A.n * kChunk * sizeof(float);
   const int kid = fused ? KID_TILE_MIX_SGD : KID_TILE_MIX;
-#define CALL(R, W) LAUNCH(ctx, kid, (k_tile_mix<STAT, R, W, NT>), grid, block, lds, A)
+  const dim3 grid((unsigned)A.nchunks), block(A.n <= 8 ? 512 : A.n <= 16 ? 256 : 1024);
+#define CALL(R, W) LAUNCH(ctx, kid, (k_tile_mix<STAT, R, W, NT, SPARSE>), grid, block, lds, A)
   TILE_SWITCH(A.n, ctx->rpw, CALL)
 #undef CALL
 }
@@ -758,8 +800,17 @@ Args look_ahead_args(const choco_ctx* ctx, const Args& A) {
 
 // Bracket of the launches that select ahead: between fork and join LAUNCH goes to the second
 // stream, which first waits for everything enqueued on the caller's stream so far.
-int look_ahead_fork(choco_ctx* ctx) {
+// The point on the caller's stream from which the selection ahead may run; the kernels of this
+// step that follow are enqueued BEFORE the selection's (look_ahead_fork comes after them), so
+// that they get the compute units first and the selection fills in beside them: enqueued the
+// other way round, the selection's many small workgroups take every wave slot and the step's
+// own bandwidth-bound pass waits behind them.
+int look_ahead_mark(choco_ctx* ctx) {
   HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+  return CHOCO_OK;
+}
+
+int look_ahead_fork(choco_ctx* ctx) {
   HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
   ctx->launch_stream = ctx->aux_stream;
   return CHOCO_OK;
@@ -811,25 +862,23 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   }
   if (!selected) launch_select<COMP, NT>(ctx, C, A, kid_compact, fuse_mix);
   if (ahead) {
-    // the NEXT step's selection, into the other copy of the lists and of the map, side by side
-    // with the rest of this step
-    const Args P = look_ahead_args(ctx, A);
-    int rc = look_ahead_fork(ctx);
-    if (rc != CHOCO_OK) return rc;
-    launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
-    rc = look_ahead_end(ctx, A);
+    const int rc = look_ahead_mark(ctx);
     if (rc != CHOCO_OK) return rc;
   }
-  // messages: neighbour sums first (they recompute q from x - xhat), then xhat
+  // messages: neighbour sums first (they recompute q from x - xhat), then xhat.  random_a's
+  // selection knows no values: the first kernel that forms q anyway leaves them in the list
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-  if (COMP == Q_RANDK)
-    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  A.scatter_values = (COMP == Q_RANDK && incremental) ? 1 : 0;
+  A.update_values = (COMP == Q_RANDK && !incremental) ? 1 : 0;
   if (incremental)
     LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256),
            0, A);
-  // short rows: the final mix reads the bitmap and applies xhat += q itself
+  // short rows: the final mix reads the bitmap and applies xhat += q itself; direct form with
+  // the tile kernel: the mix pass applies it off the kept-entry bits whatever the row length
+  const bool fused_apply = ctx->fused_sparse_apply;
   const bool fold_xhat = !mix_first && incremental && A.bitmap_words > 0;
-  if (!fold_xhat) LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  if (!fold_xhat && !fused_apply)
+    LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
     // random_a under choco_step: the deferred local update rides on this last pass
     const bool last_carries = F.deferred_sgd != 0;
@@ -837,10 +886,22 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     if (last_carries) L.G = F.G;
     L.fold_xhat = fold_xhat ? 1 : 0;
     if (incremental) launch_mix_incremental<NT>(ctx, L, last_carries);
+    else if (fused_apply) launch_tile_mix<Q_NONE, NT, true>(ctx, L, last_carries);
     else if (ctx->rpw) launch_tile_mix<Q_NONE, NT>(ctx, L, last_carries);
     else launch_mix_direct_global(ctx, A);
   }
+  ctx->values_in_qv = fused_apply && COMP == Q_RANDK;
   LAUNCH_CHECK(ctx);
+  if (ahead) {
+    // the NEXT step's selection, into the other copy of the lists and of the map, side by side
+    // with the rest of this step (from the mark set above)
+    const Args P = look_ahead_args(ctx, A);
+    int rc = look_ahead_fork(ctx);
+    if (rc != CHOCO_OK) return rc;
+    launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
+    rc = look_ahead_end(ctx, A);
+    if (rc != CHOCO_OK) return rc;
+  }
   return CHOCO_OK;
 }
 
@@ -879,17 +940,21 @@ int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
 Args long_layer_args(const choco_ctx* ctx, const Args& src, int which) {
   const LongLayer& B = ctx->long_layers[(size_t)which];
   Args R = src;
-  R.X += B.start;
-  R.Xhat += B.start;
-  if (R.G) R.G += B.start;
-  if (R.M) R.M += B.start;
-  R.d = B.len;
+  // the piece of the rows from the 4-vector boundary at or below the layer's first entry; the
+  // entries before the layer in that 4-vector do not take part (e_lo)
+  const int32_t head = B.start & 3, base = B.start - head;
+  R.X += base;
+  R.Xhat += base;
+  if (R.G) R.G += base;
+  if (R.M) R.M += base;
+  R.d = B.len + head;
+  R.e_lo = head;
   R.k = B.k;
   R.ctl = src.ctl + (int64_t)which * src.n;
   R.sel_idx += B.sel_base;     // sel_stride stays the worker's whole list
   R.sel_val += B.sel_base;
-  R.idx_base = B.start;
-  R.vec_base = (uint32_t)B.start >> 2;
+  R.idx_base = base;
+  R.vec_base = (uint32_t)base >> 2;
   apply_plan(R, B.plan);
   if (ctx->overlap_long) {
     R.hist16 = (uint32_t*)((char*)src.hist16 + (size_t)which * ctx->set_hist16);
@@ -1009,16 +1074,11 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     if (rc != CHOCO_OK) return rc;
   }
   if (ahead) {
-    const Args P = look_ahead_args(ctx, A);
-    int rc = look_ahead_fork(ctx);
-    if (rc != CHOCO_OK) return rc;
-    (void)select_layers(P);
-    rc = look_ahead_end(ctx, A);
+    const int rc = look_ahead_mark(ctx);
     if (rc != CHOCO_OK) return rc;
   }
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-  if (COMP == Q_RANDK)
-    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  A.scatter_values = COMP == Q_RANDK ? 1 : 0;   // random_a: the scatter forms the kept values and lists them
   LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
   LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {
@@ -1028,6 +1088,14 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     launch_mix_incremental<NT>(ctx, L, last_carries);
   }
   LAUNCH_CHECK(ctx);
+  if (ahead) {   // the next step's masks, enqueued after this step's own kernels (see look_ahead_mark)
+    const Args P = look_ahead_args(ctx, A);
+    int rc = look_ahead_fork(ctx);
+    if (rc != CHOCO_OK) return rc;
+    (void)select_layers(P);
+    rc = look_ahead_end(ctx, A);
+    if (rc != CHOCO_OK) return rc;
+  }
   return CHOCO_OK;
 }
 
@@ -1057,6 +1125,7 @@ int gossip_any(choco_ctx* ctx, const Args& A) {
 bool first_pass_can_carry_sgd(const choco_ctx* ctx) {
   const int comp = ctx->cfg.compressor;
   if (ctx->long_silent) return false;   // the select pass skips a long layer that keeps nothing
+  if (ctx->layers_generic) return false;   // layer passes off 16-byte boundaries load entry by entry and store nothing
   const bool incremental = ctx->mix_form == CHOCO_MIX_INCREMENTAL_S;
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX)
     return comp == CHOCO_Q_SIGN || comp == CHOCO_Q_QSGD || comp == CHOCO_Q_TOPK;
@@ -1078,7 +1147,7 @@ int launch_sgd(choco_ctx* ctx, const float* g_dev, float lr) {
 // Under choco_step with random_a in the compress-then-mix order nothing reads X densely
 // before the final mix, so the local update is deferred into that mix.
 bool last_pass_carries_sgd(const choco_ctx* ctx) {
-  return ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
+  return !ctx->layers_generic && ctx->cfg.compressor == CHOCO_Q_RANDK && ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
          (ctx->mix_form == CHOCO_MIX_INCREMENTAL_S || ctx->rpw != 0);
 }
 
@@ -1109,6 +1178,7 @@ int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   ctx->fused = false;
   if (rc == CHOCO_OK) {
     ctx->last_buf = buf;
+    ctx->last_t = ctx->t;
     ctx->t += 1;
   }
   return rc;
@@ -1154,12 +1224,13 @@ WireArgs wire_args(const choco_ctx* ctx) {
   Wa.W = ((int64_t)A.d + 31) / 32;
   Wa.mb = magnitude_bits(ctx->cfg.levels);
   Wa.levels = ctx->cfg.levels;
-  Wa.codes = A.codes;
+  Wa.planes = A.planes;
+  Wa.plane_words = A.plane_words;
+  Wa.nplanes = A.nplanes;
+  Wa.ovf_ring = A.ovf_ring;
+  Wa.t_lo = (uint32_t)(ctx->last_t & 0xFFFFFFFFu);
+  Wa.t_hi = (uint32_t)(ctx->last_t >> 32);
   Wa.ctl = A.ctl;
-  const size_t units = (size_t)A.n * (size_t)(ctx->nlayers > 0 ? ctx->nlayers : 1);
-  Wa.status = ctx->wire;
-  Wa.ovf_count = ctx->wire + A.n;
-  Wa.ovf_idx = ctx->wire + A.n + units;
   Wa.layers = A.layers;
   Wa.nlayers = dense_layers ? ctx->nlayers : 0;
   Wa.layer_word_off = ctx->wire_word_off;
@@ -1177,7 +1248,7 @@ WireArgs wire_args(const choco_ctx* ctx) {
   return Wa;
 }
 
-// random_a without a bitmap: mark the kept entries of the last step in the (otherwise zero) byte
+// random_a without a bitmap: mark the kept entries of the last step in the (otherwise zero) bit
 // map and count them chunk by chunk, so that a kept entry's rank is a table look-up plus a
 // count inside its own chunk.  The caller clears the marks again.
 void launch_rank_tables(choco_ctx* ctx, const WireArgs& Wa) {
@@ -1246,6 +1317,8 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->nnz = nnz;
   ctx->sparse = is_sparse(cfg->compressor);
   ctx->mix_form = resolve_mix_form(*cfg);
+  ctx->fused_sparse_apply = fused_sparse_apply(*cfg);
+  ctx->values_in_qv = false;
   ctx->rpw = pick_rpw(cfg->n);
   ctx->plan = SelectPlan{};
   ctx->plan.guess0 = 0xFFFFFFFFu;
@@ -1256,6 +1329,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->long_silent = false;
   for (const LongLayer& B : ctx->long_layers) ctx->long_silent = ctx->long_silent || B.k == 0;
   ctx->nlayers = cfg->nlayers;
+  ctx->layers_generic = cfg->nlayers > 0 && !layers_aligned(*cfg);
   // Non-temporal (streaming) or ordinary cached accesses, by the size of one state array;
   // measured on MI355X with 64 workers on a ring unless said otherwise (ms per step, NT / cached):
   //   8.6 MB (n = 8) sign 0.0189 / 0.0216;  16 MB sign 0.0326 / 0.0319;  33 MB sign 0.0567 / 0.0536,
@@ -1314,6 +1388,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.sel_idx = (int32_t*)(base + L.sel_idx);
   A.sel_val = (float*)(base + L.sel_val);
   A.keptmap = (uint32_t*)(base + L.keptmap);
+  A.Qv = (ctx->fused_sparse_apply && cfg->compressor == CHOCO_Q_RANDK) ? (float*)(base + L.qv) : nullptr;
   A.map_words = (A.ld + 31) / 32;
   A.bitmap = (uint32_t*)(base + L.bitmap);
   A.bitmap_words = L.bitmap_words;
@@ -1353,6 +1428,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   // layer tables: descriptors in layer order, and again by falling length (the work list)
   std::vector<LayerDesc> layers((size_t)cfg->nlayers), work;
   A.nlayers = cfg->nlayers;
+  A.layers_generic = ctx->layers_generic ? 1 : 0;
   A.layers = (const LayerDesc*)(base + L.layers);
   A.layer_work = (const LayerDesc*)(base + L.layer_work);
   A.layer_guess = (uint32_t*)(base + L.layer_guess);
@@ -1368,16 +1444,19 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
       D.k = ctx->sparse ? (int32_t)cfg->layer_k_host[l] : 0;
       D.sel_base = (int32_t)sel_base;
       D.id = l;
-      D.pad[0] = D.pad[1] = D.pad[2] = 0;
+      D.head = D.start & 3;
+      D.pad[0] = D.pad[1] = 0;
       sel_base += D.k;
     }
     work = layers;
-    std::stable_sort(work.begin(), work.end(), [](const LayerDesc& a, const LayerDesc& b) { return a.len > b.len; });
+    std::stable_sort(work.begin(), work.end(),
+                     [](const LayerDesc& a, const LayerDesc& b) { return a.len + a.head > b.len + b.head; });
     ctx->nlarge = ctx->nmid = 0;
     for (const LayerDesc& D : work) {
-      if (ctx->sparse && D.len > kMaxLayerLen) continue;   // (long layers: first in the list, skipped by the layer kernel)
-      if (D.len > kMidLayerLen) ctx->nlarge += 1;
-      else if (D.len > kWaveLayerLen) ctx->nmid += 1;
+      const int32_t span = D.len + D.head;   // what the layer kernel holds in registers
+      if (ctx->sparse && span > kMaxLayerLen) continue;   // (long layers: first in the list, skipped by the layer kernel)
+      if (span > kMidLayerLen) ctx->nlarge += 1;
+      else if (span > kWaveLayerLen) ctx->nmid += 1;
     }
   }
   std::vector<LayerGroup> groups;
@@ -1398,7 +1477,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     group_first.push_back((int32_t)groups.size());
     chunk_layer.resize((size_t)L.nchunks);
     int32_t lay = 0;
-    for (int32_t ch = 0; ch < L.nchunks; ++ch) {
+    for (int32_t ch = 0; ch < L.nchunks && !ctx->layers_generic; ++ch) {
       while (lay + 1 < cfg->nlayers && layers[(size_t)lay + 1].start <= ch * kChunk) ++lay;
       const LayerDesc& D = layers[(size_t)lay];
       const int32_t next = lay + 1 < cfg->nlayers ? layers[(size_t)lay + 1].start : INT32_MAX;
@@ -1407,7 +1486,13 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   }
   A.seed_lo = (uint32_t)(cfg->seed & 0xFFFFFFFFu);
   A.seed_hi = (uint32_t)(cfg->seed >> 32);
-  ctx->wire = (uint32_t*)(base + L.wire);
+  A.nplanes = cfg->compressor == CHOCO_Q_SIGN ? 1 : cfg->compressor == CHOCO_Q_QSGD ? 1 + magnitude_bits(cfg->levels) : 0;
+  A.mb = magnitude_bits(cfg->levels);
+  A.plane_words = (A.ld + 31) / 32;
+  A.planes = A.nplanes ? (uint32_t*)(base + L.planes) : nullptr;
+  A.ovf_ring = (uint4*)(base + L.ovf_ring);
+  A.ovf_pos = (uint32_t*)(base + L.ovf_pos);
+  ctx->last_t = 0;
   ctx->wire_rank = (uint32_t*)(base + L.wire_rank);
   ctx->wire_word_off = (const int64_t*)(base + L.wire_word_off);
   ctx->wire_plane_off = (const int64_t*)(base + L.wire_plane_off);
@@ -1587,8 +1672,31 @@ int choco_nsum(choco_ctx* ctx, float** s_dev) {
   return CHOCO_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// random_a after a fused update-and-mix pass: collect the kept values of the last step from Qv
+// into the list (idempotent; read-back and message encoding call it, a step never does).
+int gather_values(choco_ctx* ctx) {
+  if (!ctx->values_in_qv) return CHOCO_OK;
+  Args A = ctx->args;
+  A.sel_idx = ctx->sel_idx_buf[ctx->last_buf];
+  LAUNCH(ctx, KID_GATHER_VALUES, k_gather_values, dim3((unsigned)((A.k + 255) / 256), (unsigned)A.n), dim3(256), 0, A);
+  LAUNCH_CHECK(ctx);
+  return CHOCO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int choco_last_selection(choco_ctx* ctx, int32_t* idx_dev, float* val_dev) {
   if (!ctx || !ctx->sparse) return CHOCO_E_INVAL;
+  {
+    const int rc = gather_values(ctx);
+    if (rc != CHOCO_OK) return rc;
+  }
   const Args& A = ctx->args;
   const size_t count = (size_t)A.n * (size_t)A.k;
   if (idx_dev)
@@ -1597,6 +1705,40 @@ int choco_last_selection(choco_ctx* ctx, int32_t* idx_dev, float* val_dev) {
   if (val_dev)
     HIP_TRY(ctx, hipMemcpyAsync(val_dev, A.sel_val, count * sizeof(float), hipMemcpyDeviceToDevice,
                                 ctx->stream));
+  return CHOCO_OK;
+}
+
+int choco_last_message(choco_ctx* ctx, int32_t worker, int32_t* idx_dev, float* val_dev, uint32_t* bits_dev,
+                       float* scale_host) {
+  if (!ctx || worker < 0 || worker >= ctx->args.n || ctx->cfg.compressor == CHOCO_Q_IDENTITY) return CHOCO_E_INVAL;
+  const Args& A = ctx->args;
+  if (scale_host) *scale_host = 0.0f;
+  if (ctx->sparse) {
+    const int rc = gather_values(ctx);
+    if (rc != CHOCO_OK) return rc;
+    const size_t off = (size_t)worker * (size_t)A.k, count = (size_t)A.k;
+    if (idx_dev)
+      HIP_TRY(ctx, hipMemcpyAsync(idx_dev, ctx->sel_idx_buf[ctx->last_buf] + off, count * sizeof(int32_t),
+                                  hipMemcpyDeviceToDevice, ctx->stream));
+    if (val_dev)
+      HIP_TRY(ctx, hipMemcpyAsync(val_dev, A.sel_val + off, count * sizeof(float), hipMemcpyDeviceToDevice,
+                                  ctx->stream));
+    return CHOCO_OK;
+  }
+  if (scale_host && ctx->nlayers > 0) return CHOCO_E_INVAL;
+  if (bits_dev) {
+    const size_t W = ((size_t)A.d + 31) / 32;
+    HIP_TRY(ctx, hipMemcpy2DAsync(bits_dev, W * sizeof(uint32_t),
+                                  A.planes + (size_t)worker * (size_t)A.nplanes * (size_t)A.plane_words,
+                                  (size_t)A.plane_words * sizeof(uint32_t), W * sizeof(uint32_t), (size_t)A.nplanes,
+                                  hipMemcpyDeviceToDevice, ctx->stream));
+  }
+  if (scale_host) {
+    WorkerCtl c;
+    HIP_TRY(ctx, hipMemcpyAsync(&c, A.ctl + worker, sizeof(c), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    *scale_host = ctx->cfg.compressor == CHOCO_Q_SIGN ? c.scale_c : c.scale_step;
+  }
   return CHOCO_OK;
 }
 
@@ -1633,39 +1775,22 @@ int choco_pack_messages(choco_ctx* ctx, void* msgs_dev) {
   if (!ctx || !msgs_dev || ((uintptr_t)msgs_dev & 3u) != 0) return CHOCO_E_INVAL;
   int rc = wire_supported(ctx);
   if (rc != CHOCO_OK) return rc;
+  rc = gather_values(ctx);   // random_a after a fused update-and-mix pass: the value list is made now
+  if (rc != CHOCO_OK) return rc;
   const WireArgs Wa = wire_args(ctx);
   uint32_t* msg = (uint32_t*)msgs_dev;
-  const dim3 wgrid((unsigned)((Wa.W + 255) / 256), (unsigned)Wa.n);
   const dim3 kgrid((unsigned)((Wa.k + 255) / 256), (unsigned)Wa.n);
   const dim3 lgrid((unsigned)((ctx->wire_plane_words + 255) / 256), (unsigned)Wa.n);
+  const dim3 pgrid((unsigned)((Wa.W + 255) / 256), (unsigned)(Wa.nplanes > 0 ? Wa.nplanes : 1), (unsigned)Wa.n);
   switch (ctx->cfg.compressor) {
     case CHOCO_Q_SIGN:
-      if (!Wa.codes) return CHOCO_E_INVAL;   // the codes of the last step come from choco_set_capture
       if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<false>, lgrid, dim3(256), 0, Wa, msg);
-      else LAUNCH(ctx, KID_WIRE, k_pack_sign, wgrid, dim3(256), 0, Wa, msg);
+      else LAUNCH(ctx, KID_WIRE, k_pack_planes<false>, pgrid, dim3(256), 0, Wa, msg);
       break;
-    case CHOCO_Q_QSGD: {
-      if (!Wa.codes) return CHOCO_E_INVAL;
-      if (Wa.nlayers) {
-        // (a fill kernel, not a memset node: the call may sit in a captured graph)
-        LAUNCH(ctx, KID_ZERO_WORDS, k_zero_words, dim3((unsigned)((Wa.n + 255) / 256)), dim3(256), 0, Wa.status,
-               (int64_t)Wa.n);
-        LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg);
-        LAUNCH(ctx, KID_WIRE, k_pack_gsgd_layers_finish, dim3((unsigned)Wa.nlayers, (unsigned)Wa.n), dim3(64), 0, Wa,
-               msg);
-      } else {
-        LAUNCH(ctx, KID_WIRE, k_pack_gsgd, wgrid, dim3(256), 0, Wa, msg);
-        LAUNCH(ctx, KID_WIRE, k_pack_gsgd_finish, dim3((unsigned)Wa.n), dim3(64), 0, Wa, msg);
-      }
-      LAUNCH_CHECK(ctx);
-      std::vector<uint32_t> status((size_t)Wa.n);
-      HIP_TRY(ctx, hipMemcpyAsync(status.data(), Wa.status, status.size() * sizeof(uint32_t), hipMemcpyDeviceToHost,
-                                  ctx->stream));
-      HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-      for (uint32_t st : status)
-        if (st) return CHOCO_E_UNSUPPORTED;   // more entries at level s than the message has slots for
-      return CHOCO_OK;
-    }
+    case CHOCO_Q_QSGD:
+      if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_pack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg);
+      else LAUNCH(ctx, KID_WIRE, k_pack_planes<true>, pgrid, dim3(256), 0, Wa, msg);
+      break;
     case CHOCO_Q_TOPK:
       LAUNCH(ctx, KID_WIRE, k_pack_topk, kgrid, dim3(256), 0, Wa, msg);
       break;
@@ -1793,6 +1918,12 @@ int choco_last_scalars(choco_ctx* ctx, double* scalars_host) {
       default: break;
     }
   }
+  return CHOCO_OK;
+}
+
+int choco_get_mix_form(choco_ctx* ctx, int32_t* mix_form_host) {
+  if (!ctx || !mix_form_host) return CHOCO_E_INVAL;
+  *mix_form_host = ctx->mix_form;
   return CHOCO_OK;
 }
 

@@ -41,6 +41,7 @@ constexpr int kStatThreads = 256;   // one wave per 4 chunks of a 16-chunk group
 constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
 constexpr int kRefineParts = 16;    // blocks per worker of the select when the candidate lists are long
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
+constexpr int kOvfRing = 8;       // gsgd: remembered entries at the top level per worker (and layer); a step adds at most 4
 
 // Per-worker control block in device memory (written by small "finalise" code,
 // read by the streaming kernels; the host never reads it on the hot path).
@@ -67,12 +68,14 @@ struct WorkerCtl {
 
 // One layer of a worker's vector when the operator is applied layer by layer.
 struct LayerDesc {
-  int32_t start;     // first entry (a multiple of 4)
+  int32_t start;     // first entry
   int32_t len;       // entries
   int32_t k;         // top_a / random_a: entries kept of this layer
   int32_t sel_base;  // where the layer's kept entries start in the worker's selection list
   int32_t id;        // number of the layer in the caller's table
-  int32_t pad[3];
+  int32_t head;      // start mod 4: the kernels that hold a layer in registers load whole 4-vectors
+                     // from start - head and ignore the first `head` entries (0 in an aligned table)
+  int32_t pad[2];
 };
 
 // Scales of one layer of one worker (dense operators applied layer by layer).
@@ -116,6 +119,18 @@ struct Args {
   int32_t levels;      // gsgd: s
   double tau;          // gsgd: 1 + min(d/s^2, sqrt(d)/s) or 1
   int32_t* codes;      // optional capture of the transmitted codes (n x ld)
+  // The message of a dense operator as it goes on the wire, written by the pass that encodes q
+  // (Appendix C: one sign bit per entry for sign; b bits per entry for gsgd_b): bit e%32 of
+  // word e/32 of plane p of row i.  Plane 0: the entry is negative (and, for gsgd, its level
+  // is not zero); planes 1..mb (gsgd): bit p-1 of min(level, 2^mb - 1).
+  uint32_t* planes;    // n x nplanes x plane_words (null: identity, top_a, random_a)
+  int64_t plane_words; // ceil(ld / 32)
+  int32_t nplanes;     // 1 (sign) or 1 + mb (gsgd)
+  int32_t mb;          // gsgd: magnitude bits = bit length of s - 1 (at least 1)
+  // gsgd: an entry at level s when s does not fit the magnitude bits is remembered by index in a
+  // small ring per worker (and layer), tagged with the step: {t_lo, t_hi + 1, index, 0}
+  uint4* ovf_ring;     // n x max(nlayers, 1) x kOvfRing
+  uint32_t* ovf_pos;   // n x max(nlayers, 1): entries appended so far (never reset)
   int32_t fold_finalise;  // ngroups <= 256: the apply kernel does level 3 of the norm tree itself
   // sparse operators
   int64_t k;
@@ -145,11 +160,21 @@ struct Args {
   uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
   int64_t bitmap_words;  // 0: use the bit map in global memory (keptmap)
   int32_t fold_xhat;     // the final mix also applies xhat += q (bitmap rows, compress-then-mix)
+  // random_a: nobody knows the kept values when the selection is made (it reads no state).  They are
+  // written to sel_val by the first kernel that forms q anyway:
+  int32_t scatter_values;  // k_scatter_s computes q_j[e] = x_j[e] - xhat_j[e] itself and its self-loop thread stores it
+  int32_t update_values;   // k_xhat_update computes and stores it (no scatter ran: direct mix)
+  float* Qv;               // or, where one fused pass applies the update and the mix (direct form), to entry
+                           // (j, e) of this n x ld array, from which the list is gathered on request; else null
   int32_t randk_rescale;
   float randk_scale;   // (float)(d / k)
   // layer-wise compression (nlayers = 0: the whole row is compressed as one vector)
-  const LayerDesc* layers;   // sorted by start; they tile the row up to the 4-entry padding
+  const LayerDesc* layers;   // sorted by start, disjoint
   int32_t nlayers;
+  int32_t layers_generic;    // 0: every layer starts on a multiple of 4 and the layers tile the row up to that
+                             // padding (a 4-vector then lies in one layer); 1: any disjoint ascending slices
+  int32_t e_lo;              // select kernels: entries of the row below this index do not take part (the head
+                             // of a long layer that does not start on a multiple of 4; else 0)
   const LayerDesc* layer_work;  // the same by falling length: the order the layer kernel takes them in
   uint32_t* layer_guess;     // n x nlayers: top_a threshold key of the last step (all ones: none yet)
   const LayerGroup* layer_groups;   // ngroup_items work items of the layer-wise norm pass, layer after layer
@@ -173,6 +198,14 @@ __device__ __forceinline__ int layer_of(const Args& A, int e) {
     else hi = mid - 1;
   }
   return lo;
+}
+
+// Generic tables: the layer that holds entry e, or -1 if e lies in no layer.
+__device__ __forceinline__ int layer_holding(const Args& A, int e) {
+  if (e < A.layers[0].start) return -1;
+  const int lay = layer_of(A, e);
+  const LayerDesc L = A.layers[lay];
+  return e < L.start + L.len ? lay : -1;
 }
 
 // The same for the first entry e of a 4-vector through the per-chunk table: the layer
@@ -226,7 +259,7 @@ __device__ __forceinline__ void store4(float* p, vf4 v) {
 }
 // The local update of one 4-vector at offset o, riding on a pass that has x in registers:
 //   plain (Algorithm 1, gradient step): x <- x - lr g
-//   momentum (Algorithm 2, l. 9-10): m <- (g + lambda x) + beta m (stored);  x <- x - lr m
+//   momentum (Algorithm 2, its momentum and gradient steps): m <- (g + lambda x) + beta m (stored);  x <- x - lr m
 // Every product and sum rounded on its own, as in k_sgd / k_momentum.
 template <bool NT, class ArgsT>
 __device__ __forceinline__ vf4 local_update4(const ArgsT& A, int64_t o, vf4 x) {
@@ -297,10 +330,12 @@ __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
       k0 += 0x9E3779B9u;
       k1 += 0xBB67AE85u;
     }
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0);
-    const uint32_t lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2);
-    const uint32_t lo1 = 0xCD9E8D57u * c2;
+    // one 32 x 32 -> 64 bit product per counter word (a single multiply-add instruction on this
+    // target; written as two separate products it costs two quarter-rate multiplies)
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+    const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
     const uint32_t n0 = hi1 ^ c1 ^ k0;
     const uint32_t n2 = hi0 ^ c3 ^ k1;
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
@@ -383,6 +418,112 @@ __device__ __forceinline__ vf4 absorb(const vf4& x, vf4 xh, const RowScale<COMP>
     code[c] = cd;
   }
   return xh;
+}
+
+// The same for a generic layer table (any disjoint ascending slices): every entry takes the
+// scales of the layer that holds it; an entry in no layer keeps its xhat and sends nothing.
+template <int COMP>
+__device__ __forceinline__ vf4 absorb_by_entry(const Args& A, int r, int e, const vf4& x, vf4 xh,
+                                               const uint4& words, vi4& code) {
+  int fl = e >= A.layers[0].start ? layer_of(A, e) : -1;   // last layer that starts at or before the entry
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int ee = e + c;
+    while (fl + 1 < A.nlayers && A.layers[fl + 1].start <= ee) ++fl;
+    code[c] = 0;
+    if (fl < 0 || ee >= A.d) continue;
+    const LayerDesc L = A.layers[fl];
+    if (ee >= L.start + L.len) continue;
+    RowScale<COMP> sc;
+    sc.load(A.layer_scale[(int64_t)r * A.nlayers + fl]);
+    int32_t cd;
+    const float v = x[c] - xh[c];
+    const float qv = encode<COMP>(v, sc, pick(words, c), cd);
+    xh[c] = xh[c] + qv;
+    code[c] = cd;
+  }
+  return xh;
+}
+
+// Workgroups are handed to the eight accelerator dies in turn (workgroup b runs on die b mod 8) and
+// every die has an L2 of its own.  A tile of 256 columns writes 32 bytes of each bit plane, a
+// quarter of a cache line; tile number for workgroup b such that the four tiles of a line run on
+// one die one after the other (b, b + 8, b + 16, b + 24), so that their pieces meet in that die's
+// L2 and leave it as one whole line.  Super-groups of 32 tiles keep the order of the streams
+// otherwise; the last, partial super-group is left as it is.
+__device__ __forceinline__ int line_sharing_tile(int b, int ntiles) {
+  const int base = b & ~31;
+  if (base + 32 > ntiles) return b;
+  return base + ((b & 7) << 2) + ((b >> 3) & 3);
+}
+
+// The bits of a wave's 256 codes (four per lane, entries e..e+3 of row r) go to the row's bit
+// planes: eight lanes share a 32-bit word, their nibbles are combined with three lane moves and
+// the first of the eight stores the word.  Every lane of the wave calls this (lanes without
+// entries pass code 0); `lay` is the layer of the lane's entries (0 without layers).
+template <int COMP>
+__device__ __forceinline__ void emit_code_planes(const Args& A, int r, int e, int lane, const vi4& code, int lay) {
+  if (COMP != Q_SIGN && COMP != Q_QSGD) return;
+  if (!A.planes) return;
+  const int sh = 4 * (lane & 7);
+  const bool writer = (lane & 7) == 0 && e < A.d;
+  uint32_t* P = A.planes + (int64_t)r * A.nplanes * A.plane_words + ((uint32_t)e >> 5);
+  // OR over the eight lanes of a word with three data-parallel-primitive moves (no LDS traffic,
+  // unlike a general lane exchange): lane ^ 1 and lane ^ 2 inside the quad, then the mirror image
+  // inside the group of eight, which lies in the other quad
+  auto word_of = [&](uint32_t nibble) {
+    uint32_t w = nibble << sh;
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    return w;
+  };
+  // bits 0, 8, 16, 24 of y -> bits 0..3
+  auto nibble_of = [](uint32_t y) {
+    y |= y >> 7;
+    y |= y >> 14;
+    return y & 0xFu;
+  };
+  // one byte per entry: bit 7 = negative, bits 0..6 = min(level, 2^mb - 1) (levels above 127 are
+  // handled plane by plane below)
+  const uint32_t negs = ((uint32_t)code[0] >> 31) | (((uint32_t)code[1] >> 31) << 8) |
+                        (((uint32_t)code[2] >> 31) << 16) | (((uint32_t)code[3] >> 31) << 24);
+  // (a plane with no bit set anywhere in the wave - the usual case for the upper magnitude planes
+  // of a long vector, whose levels are nearly all 0 or 1 - is stored as zeros without the lane moves)
+  if (__ballot(negs != 0u) == 0ull) {
+    if (writer) P[0] = 0u;
+  } else {
+    const uint32_t sw = word_of(nibble_of(negs));
+    if (writer) P[0] = sw;
+  }
+  if (COMP == Q_QSGD) {
+    const int32_t maxmag = (1 << A.mb) - 1;
+    int32_t mag[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      mag[c] = code[c] < 0 ? -code[c] : code[c];
+      if (mag[c] > maxmag) {   // the level s itself: at most four entries of a vector can reach it
+        const int lay_c = (A.nlayers && A.layers_generic) ? layer_holding(A, e + c) : lay;
+        const int64_t unit = A.nlayers ? (int64_t)r * A.nlayers + lay_c : (int64_t)r;
+        const int32_t base = A.nlayers ? A.layers[lay_c].start : 0;
+        const uint32_t pos = atomicAdd(A.ovf_pos + unit, 1u);
+        A.ovf_ring[unit * kOvfRing + (pos & (uint32_t)(kOvfRing - 1))] =
+            make_uint4(A.t_lo, A.t_hi + 1u, (uint32_t)(e + c - base), 0u);
+        mag[c] = maxmag;
+      }
+    }
+    for (int p0 = 0; p0 < A.mb; p0 += 8) {   // eight planes at a time out of one byte per entry
+      const uint32_t M = ((uint32_t)(mag[0] >> p0) & 0xFFu) | (((uint32_t)(mag[1] >> p0) & 0xFFu) << 8) |
+                         (((uint32_t)(mag[2] >> p0) & 0xFFu) << 16) | (((uint32_t)(mag[3] >> p0) & 0xFFu) << 24);
+      const int pend = A.mb - p0 < 8 ? A.mb - p0 : 8;
+      for (int p = 0; p < pend; ++p) {
+        const uint32_t y = (M >> p) & 0x01010101u;
+        uint32_t w = 0u;
+        if (__ballot(y != 0u) != 0ull) w = word_of(nibble_of(y));
+        if (writer) P[(int64_t)(1 + p0 + p) * A.plane_words] = w;
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -655,10 +796,12 @@ template <int COMP, int RPW, int NW, bool CAPTURE, bool NT, bool LAYERED>
 __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int e = blockIdx.x * kChunk + lane * 4;
+  const int tile_no = line_sharing_tile((int)blockIdx.x, (int)gridDim.x);
+  const int e = tile_no * kChunk + lane * 4;
   const bool valid = e < A.d;
   int lay = 0, nvalid = A.d - e < 4 ? A.d - e : 4;   // the last 4-vector of a row may end in pad columns
-  if (LAYERED && valid) lay = layer_of_vector(A, e, nvalid);
+  const bool generic = LAYERED && A.layers_generic;   // a 4-vector may span layers and gaps: scales entry by entry
+  if (LAYERED && valid && !generic) lay = layer_of_vector(A, e, nvalid);
   vf4 xr[RPW], xh[RPW];
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
@@ -675,11 +818,11 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + NW * q;
     if (LAYERED) {
-      if (r < A.n && valid) sc[q].load(A.layer_scale[(int64_t)r * A.nlayers + lay]);
+      if (r < A.n && valid && !generic) sc[q].load(A.layer_scale[(int64_t)r * A.nlayers + lay]);
     } else if (r < A.n) {
       if ((COMP == Q_SIGN || COMP == Q_QSGD) && A.fold_finalise) {
         const double total = wave_level3(A, r, lane);
-        scales_from_total<COMP>(A, total, sc[q], (blockIdx.x == 0 && lane == 0) ? A.ctl + r : nullptr);
+        scales_from_total<COMP>(A, total, sc[q], (tile_no == 0 && lane == 0) ? A.ctl + r : nullptr);
       } else {
         sc[q].load(A.ctl + r);
       }
@@ -690,16 +833,21 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
     const int r = wave + NW * q;
     if (r < A.n) {
       vf4 nh = {0.f, 0.f, 0.f, 0.f};
+      vi4 code = {0, 0, 0, 0};
       if (valid) {
         const int64_t o = (int64_t)r * A.ld + e;
         uint4 words = make_uint4(0, 0, 0, 0);
         if (COMP == Q_QSGD) words = random_words(A, r, (uint32_t)(e >> 2), STREAM_DITHER);
-        vi4 code;
-        nh = absorb<COMP>(xr[q], xh[q], sc[q], words, code);
-        mask_padding(nvalid, xh[q], nh, code);
+        if (generic) {
+          nh = absorb_by_entry<COMP>(A, r, e, xr[q], xh[q], words, code);
+        } else {
+          nh = absorb<COMP>(xr[q], xh[q], sc[q], words, code);
+          mask_padding(nvalid, xh[q], nh, code);
+        }
         store4<NT>(A.Xhat + o, nh);
         if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
       }
+      emit_code_planes<COMP>(A, r, e, lane, code, lay);   // the message itself: sign and level bits
       lds_store4(tile + r * kChunk + lane * 4, nh);
     }
   }
@@ -718,25 +866,82 @@ __global__ __launch_bounds__(64 * NW) void k_dense_apply_mix(Args A) {
 // printed order (mix, then compress).  Same tiling as above; the tile is one
 // first-level norm chunk, so the chunk sum falls out of one wave butterfly.
 // ---------------------------------------------------------------------------
-template <int STAT, int RPW, int NW, bool NT>
+// SPARSE (top_a / random_a, compress-then-mix order): the update of the public copies rides on
+// this pass.  The wave that loads (x, xhat) of a row also reads the row's kept-entry bits for its
+// 4-vectors; where a bit is set it forms q = x - xhat (x with this step's local update, which
+// the pass may itself carry), adds it to xhat, stores that 4-vector of xhat and hands the new
+// value to the tile, so that the mix sees the xhat of after the exchange.  Rows whose bits live
+// in the global bit map clear the words they used (as k_xhat_update does).
+template <int STAT, int RPW, int NW, bool NT, bool SPARSE>
 __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
   extern __shared__ float tile[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
+  const bool sgd = A.G != nullptr, mom = sgd && A.M != nullptr;
+  // The loads of (up to) two of the wave's rows first - x, xhat, the gradient, the kept-entry
+  // word -, then their arithmetic and stores: a store, or a test of a loaded word, between two
+  // loads would put the later load behind the round trip of the earlier one.  Two rows at a
+  // time because four rows' loads at once need more than the 64 registers that let two
+  // 1024-thread workgroups share a compute unit at n = 64 (57 against 43 us); the momentum
+  // memory is read row by row for the same reason.
+  constexpr int HB = RPW >= 2 ? 2 : 1;
   vf4 xr[RPW];
 #pragma unroll
-  for (int q = 0; q < RPW; ++q) {
-    const int r = wave + NW * q;
-    if (r < A.n) {
-      vf4 xh = {0.f, 0.f, 0.f, 0.f};
-      if (valid) {
+  for (int q0 = 0; q0 < RPW; q0 += HB) {
+    vf4 xhv[HB], gv[HB];
+    uint32_t word[HB];
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      const int q = q0 + j;
+      const int r = wave + NW * q;
+      word[j] = 0u;
+      if (q < RPW && r < A.n && valid) {
         const int64_t o = (int64_t)r * A.ld + e;
         xr[q] = load4<NT>(A.X + o);
-        xh = load4<NT>(A.Xhat + o);
-        if (A.G) xr[q] = local_update4<NT>(A, o, xr[q]);
+        xhv[j] = load4<NT>(A.Xhat + o);
+        if (sgd) gv[j] = load4<true>(A.G + o);   // a gradient is read once: always streamed
+        if (SPARSE)
+          word[j] = A.bitmap_words ? A.bitmap[(int64_t)r * A.bitmap_words + ((uint32_t)e >> 5)]
+                                   : A.keptmap[(int64_t)r * A.map_words + ((uint32_t)e >> 5)];
       }
-      lds_store4(tile + r * kChunk + lane * 4, xh);
+    }
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+      const int q = q0 + j;
+      const int r = wave + NW * q;
+      if (q < RPW && r < A.n) {
+        vf4 xh = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+          const int64_t o = (int64_t)r * A.ld + e;
+          xh = xhv[j];
+          if (sgd) {
+            vf4 mv = vf4{0.f, 0.f, 0.f, 0.f};
+            if (mom) mv = load4<NT>(A.M + o);
+            xr[q] = local_update_regs(A, xr[q], gv[j], mv);
+            if (mom) store4<NT>(A.M + o, mv);
+          }
+          if (SPARSE) {
+            const uint32_t bits = (word[j] >> ((uint32_t)e & 31u)) & 0xFu;
+            if (bits) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if ((bits >> c) & 1u) {
+                  float qv = xr[q][c] - xh[c];
+                  if (A.randk_rescale) qv = A.randk_scale * qv;
+                  xh[c] = xh[c] + qv;
+                  if (A.Qv) A.Qv[o + c] = qv;
+                }
+              store4<false>(A.Xhat + o, xh);
+            }
+            // eight lanes share a word of 32 entries; the lane of its first 4-vector clears it
+            // (every lane's load of the word has returned by now: the test above needed its value)
+            if (!A.bitmap_words && word[j] != 0u && (lane & 7) == 0)
+              A.keptmap[(int64_t)r * A.map_words + ((uint32_t)e >> 5)] = 0u;
+          }
+        }
+        lds_store4(tile + r * kChunk + lane * 4, xh);
+      }
     }
   }
   __syncthreads();
@@ -783,20 +988,31 @@ __global__ __launch_bounds__(256) void k_dense_apply(Args A) {
 #pragma unroll
   for (int u = 0; u < kStreamVecs; ++u) {
     const int m = m0 + u * 256;
+    vi4 code = {0, 0, 0, 0};
+    int lay = 0;
     if (m < nvec) {
       const int64_t o = (int64_t)i * A.ld + 4 * (int64_t)m;
       const vf4 x = xs[u];
       const vf4 xh = xhs[u];
       uint4 words = make_uint4(0, 0, 0, 0);
       if (COMP == Q_QSGD) words = random_words(A, i, (uint32_t)m, STREAM_DITHER);
-      vi4 code;
       int nvalid = A.d - 4 * m < 4 ? A.d - 4 * m : 4;   // the last 4-vector of a row may end in pad columns
-      if (LAYERED) sc.load(A.layer_scale[(int64_t)i * A.nlayers + layer_of_vector(A, 4 * m, nvalid)]);
-      vf4 nh = absorb<COMP>(x, xh, sc, words, code);
-      mask_padding(nvalid, xh, nh, code);
+      vf4 nh;
+      if (LAYERED && A.layers_generic) {
+        nh = absorb_by_entry<COMP>(A, i, 4 * m, x, xh, words, code);
+      } else {
+        if (LAYERED) {
+          lay = layer_of_vector(A, 4 * m, nvalid);
+          sc.load(A.layer_scale[(int64_t)i * A.nlayers + lay]);
+        }
+        nh = absorb<COMP>(x, xh, sc, words, code);
+        mask_padding(nvalid, xh, nh, code);
+      }
       store4<NT>(A.Xhat + o, nh);
       if (CAPTURE) *reinterpret_cast<vi4*>(A.codes + o) = code;
     }
+    // (every lane of the wave: a wave's 4-vectors are consecutive, eight lanes to a word)
+    emit_code_planes<COMP>(A, i, m < nvec ? 4 * m : A.d, threadIdx.x & 63, code, lay);
   }
 }
 
@@ -1030,7 +1246,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
       for (int c = 0; c < 4; ++c) {
         const int e = 4 * m + c;
         const uint32_t key = Digits<COMP>::key32(a[u][c]);
-        if (e < A.d && key >= guess) {
+        if (e >= A.e_lo && e < A.d && key >= guess) {
           const uint32_t slot = atomicAdd(s_count, 1u);
           if (slot < (uint32_t)kStageCap) {
             stage[slot] = make_uint2(a[u][c], (uint32_t)e);
@@ -1102,7 +1318,7 @@ __global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
     entry_bits<COMP, false, false, false>(A, i, m, a);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      if (4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
+      if (4 * m + c >= A.e_lo && 4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
   }
 }
 
@@ -1212,7 +1428,7 @@ __device__ __forceinline__ void row_entry(const Args& A, int i, uint32_t t, uint
 template <int COMP, bool ROW, class F>
 __device__ __forceinline__ void for_each_entry(const Args& A, int i, const uint32_t* pre, uint32_t total, F f) {
   if (ROW) {
-    for (uint32_t t = threadIdx.x; t < (uint32_t)A.d; t += blockDim.x) {
+    for (uint32_t t = (uint32_t)A.e_lo + threadIdx.x; t < (uint32_t)A.d; t += blockDim.x) {
       uint32_t a, idx;
       row_entry<COMP>(A, i, t, a, idx);
       f(a, idx);
@@ -1395,7 +1611,7 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint3
       // whole-row histogram of the first digit: also tells where rank k + want lies, which
       // becomes the floor of the next step's guess
       uint64_t target = (uint64_t)A.k + (uint64_t)A.want;
-      if (target > (uint64_t)A.d) target = (uint64_t)A.d;
+      if (target > (uint64_t)(A.d - A.e_lo)) target = (uint64_t)(A.d - A.e_lo);
       find_digit(h, grp, (uint32_t)target, s_digit, s_above);
       floor_key = (uint32_t)(((uint64_t)*s_digit << scur) >> 32);
       __syncthreads();
@@ -1727,19 +1943,23 @@ __global__ __launch_bounds__(1024) void k_sel_finish(Args A) {
   if (threadIdx.x == 0) next_guess(A, ctl, s_kstar, total, true, above + need_in_bin, 0u);
 }
 
-// random_a: the kept values q = x - xhat (rescaled on request) are gathered once the
-// indices are known; top_a carries the value in the candidate entry instead.  A launch of
-// its own so that the k*n random reads are spread over all CUs (inside the one-block-per-
-// worker select they took longer than the select itself).  grid (ceil(k/256), n)
-__global__ __launch_bounds__(256) void k_sel_values(Args A) {
+// random_a with the fused update-and-mix pass: the kept values were left at their entries of Qv;
+// collect them into the list (on request only: read-back and message encoding, not a step).
+// grid (ceil(k/256), n)
+__global__ __launch_bounds__(256) void k_gather_values(Args A) {
   const int j = blockIdx.y;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= A.k) return;
   const int e = A.sel_idx[(int64_t)j * A.k + m];
+  A.sel_val[(int64_t)j * A.k + m] = A.Qv[(int64_t)j * A.ld + e];
+}
+
+// q_j[e] = x_j[e] - xhat_j[e] (rescaled on request) as the message kernels recompute it.
+__device__ __forceinline__ float fresh_value(const Args& A, int j, int e) {
   const int64_t o = (int64_t)j * A.ld + e;
-  float val = x_entry(A, o) - A.Xhat[o];
-  if (A.randk_rescale) val = randk_scale_at(A, e) * val;
-  A.sel_val[(int64_t)j * A.k + m] = val;
+  float q = x_entry(A, o) - A.Xhat[o];
+  if (A.randk_rescale) q = randk_scale_at(A, e) * q;
+  return q;
 }
 
 // S_i[e] += sum_p w_p q_j[e] over the neighbours j = col[p] that kept entry e,
@@ -1747,7 +1967,10 @@ __global__ __launch_bounds__(256) void k_sel_values(Args A) {
 // entry m of j); the thread of the FIRST neighbour in row i that kept e owns
 // the whole chain for (i, e), so each S entry has one writer and the order of
 // the additions is fixed.  Must run before xhat is updated (values of other
-// neighbours are recomputed as x - xhat).  grid (ceil(k/256), maxdeg, n)
+// neighbours are recomputed as x - xhat).  With scatter_values (random_a, whose
+// selection knows no values) the thread's own value is recomputed too, and the
+// thread of the self-loop (every row has one) leaves it in the list for the
+// update of xhat and for read-back.  grid (ceil(k/256), maxdeg, n)
 __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   const int i = blockIdx.z;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1756,19 +1979,21 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   if (m >= A.k || p >= pend) return;
   const int j = A.col[p];
   const int e = A.sel_idx[(int64_t)j * A.k + m];
+  float mine;
+  if (A.scatter_values) {
+    mine = fresh_value(A, j, e);
+    if (j == i) A.sel_val[(int64_t)j * A.k + m] = mine;
+  } else {
+    mine = A.sel_val[(int64_t)j * A.k + m];
+  }
   for (int p2 = pbeg; p2 < p; ++p2)
     if (was_kept(A, A.col[p2], e)) return;
   float* s = A.S + (int64_t)i * A.ld + e;
   float acc = *s;
-  acc = acc + A.w[p] * A.sel_val[(int64_t)j * A.k + m];
+  acc = acc + A.w[p] * mine;
   for (int p2 = p + 1; p2 < pend; ++p2) {
     const int j2 = A.col[p2];
-    if (was_kept(A, j2, e)) {
-      const int64_t o = (int64_t)j2 * A.ld + e;
-      float q = x_entry(A, o) - A.Xhat[o];
-      if (A.randk_rescale) q = randk_scale_at(A, e) * q;
-      acc = acc + A.w[p2] * q;
-    }
+    if (was_kept(A, j2, e)) acc = acc + A.w[p2] * fresh_value(A, j2, e);
   }
   *s = acc;
 }
@@ -1780,14 +2005,22 @@ __global__ __launch_bounds__(256) void k_zero_words(uint32_t* p, int64_t words) 
 }
 
 // xhat_j[e] += q_j[e] for the kept entries (Algorithm 1, update of the public copies); clears the
-// kept-map bytes it used.  grid (ceil(k/256), n)
+// words of the bit map it used.  With update_values (random_a where no scatter ran) it forms q
+// itself and leaves it in the list.  grid (ceil(k/256), n)
 __global__ __launch_bounds__(256) void k_xhat_update(Args A) {
   const int j = blockIdx.y;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= A.k) return;
   const int e = A.sel_idx[(int64_t)j * A.k + m];
   float* xh = A.Xhat + (int64_t)j * A.ld + e;
-  *xh = *xh + A.sel_val[(int64_t)j * A.k + m];
+  float q;
+  if (A.update_values) {
+    q = fresh_value(A, j, e);
+    A.sel_val[(int64_t)j * A.k + m] = q;
+  } else {
+    q = A.sel_val[(int64_t)j * A.k + m];
+  }
+  *xh = *xh + q;
   // (the bitmap is rewritten whole every step; the words of the bit map are cleared by whoever kept an entry in them)
   if (!A.bitmap_words) A.keptmap[(int64_t)j * A.map_words + ((uint32_t)e >> 5)] = 0u;
 }

@@ -70,10 +70,14 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
   constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together (5 spills)
   constexpr int kBatches = (kLayerVecs + kBatch - 1) / kBatch;
   constexpr uint32_t CAP = 2 * THREADS;
-  const int nvec = (L.len + 3) >> 2;
+  // local index e counts from the 4-vector boundary at or below the layer's first entry: the
+  // layer's entries are head <= e < end (head = 0 unless the table is generic)
+  const int head = L.head, end = L.head + L.len, base = L.start - L.head;
+  auto inside = [&](int e) { return e >= head && e < end; };
+  const int nvec = (end + 3) >> 2;
   const int nit = (nvec + THREADS - 1) / THREADS;   // sweeps of the threads over the layer (<= kLayerVecs)
   const int lane = tid & 63, wave = tid >> 6;
-  const int64_t row = (int64_t)i * A.ld + L.start;
+  const int64_t row = (int64_t)i * A.ld + base;
   double* scal = A.layer_scal + ((int64_t)i * A.nlayers + L.id) * 4;
   float* __restrict__ X = A.X;
   float* __restrict__ Xhat = A.Xhat;
@@ -94,9 +98,9 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
       const int m = it * THREADS + tid;
       // keys are ~word: the k smallest words are the k largest keys
       uint4 wd = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
-      if (it < nit && m < nvec) wd = random_words(A, i, (uint32_t)(L.start >> 2) + (uint32_t)m, STREAM_RANDK);
+      if (it < nit && m < nvec) wd = random_words(A, i, (uint32_t)(base >> 2) + (uint32_t)m, STREAM_RANDK);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) word_key[it][c] = (4 * m + c < L.len) ? ~pick(wd, c) : 0u;
+      for (int c = 0; c < 4; ++c) word_key[it][c] = inside(4 * m + c) ? ~pick(wd, c) : 0u;
     }
   } else {
 #pragma unroll
@@ -130,7 +134,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
             store4<NT>(X + o, x[j]);
           }
 #pragma unroll
-          for (int c = 0; c < 4; ++c) v[it][c] = (4 * m + c < L.len) ? x[j][c] - h[j][c] : 0.0f;
+          for (int c = 0; c < 4; ++c) v[it][c] = inside(4 * m + c) ? x[j][c] - h[j][c] : 0.0f;
         }
       }
     }
@@ -183,7 +187,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(it, c);
             nhi += wave_count(key >= hi);
-            if (key >= lo && key < hi && 4 * m + c < L.len) {
+            if (key >= lo && key < hi && inside(4 * m + c)) {
               const uint32_t pos = atomicAdd(sh.list_n, 1u);
               if (pos < CAP) sh.list[pos] = make_uint2(key, (uint32_t)(4 * m + c));
             }
@@ -235,7 +239,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     }
     if (COMP == Q_TOPK && tid == 0) *guess = T;
     // entries above the threshold key are all kept; of those equal to it, the first `need`
-    // by index (entries past the layer's end carry key 0 and are told apart by their index)
+    // by index (entries outside the layer carry key 0 and are told apart by their index)
     uint32_t above = 0, equals = 0;
 #pragma unroll
     for (int it = 0; it < kLayerVecs; ++it)
@@ -245,7 +249,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
         for (int c = 0; c < 4; ++c) {
           const uint32_t key = key_of(it, c);
           above += wave_count(key > T);
-          equals += wave_count(key == T && 4 * m + c < L.len);
+          equals += wave_count(key == T && inside(4 * m + c));
         }
       }
     above = block_total<THREADS>(above, sh.cnt, phase);
@@ -267,7 +271,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
         if (ties) {
           uint32_t mine = 0;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) mine += (key_of(it, c) == T && 4 * m + c < L.len) ? 1u : 0u;
+          for (int c = 0; c < 4; ++c) mine += (key_of(it, c) == T && inside(4 * m + c)) ? 1u : 0u;
           uint32_t incl = mine;
 #pragma unroll
           for (int off = 1; off < 64; off <<= 1) {
@@ -296,7 +300,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
           const int e = 4 * m + c;
           const uint32_t key = key_of(it, c);
           bool keep = key > T;
-          if (key == T && e < L.len) {
+          if (key == T && inside(e)) {
             keep = !ties || rank < need;
             ++rank;
           }
@@ -304,9 +308,9 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
             const uint32_t slot = atomicAdd(sh.emit, 1u);
             if (slot < k) {   // exactly k entries pass; the test only keeps a wrong count inside the layer's slots
               const int64_t dst = (int64_t)i * A.k + L.sel_base + slot;
-              A.sel_idx[dst] = L.start + e;
+              A.sel_idx[dst] = base + e;
               if (COMP == Q_TOPK) A.sel_val[dst] = v[it][c];
-              atomicOr(&A.keptmap[(int64_t)i * A.map_words + ((uint32_t)(L.start + e) >> 5)], 1u << ((uint32_t)(L.start + e) & 31u));
+              atomicOr(&A.keptmap[(int64_t)i * A.map_words + ((uint32_t)(base + e) >> 5)], 1u << ((uint32_t)(base + e) & 31u));
             }
           }
         }
@@ -364,11 +368,23 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
   for (int u = 0; u < 4; ++u) {
     e[u] = (4 * wave + u) * kChunk + lane * 4;
     if (e[u] < item.rem) {
-      a[u] = load4<NT>(A.X + row + e[u]);
-      b[u] = load4<NT>(A.Xhat + row + e[u]);
+      if (A.layers_generic) {
+        // the layer may start anywhere: entry by entry, and none past the layer's end (the next
+        // one may be the first of another layer, or lie beyond the array)
+        a[u] = b[u] = vf4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (e[u] + c < item.rem) {
+            a[u][c] = A.X[row + e[u] + c];
+            b[u][c] = A.Xhat[row + e[u] + c];
+          }
+      } else {
+        a[u] = load4<NT>(A.X + row + e[u]);
+        b[u] = load4<NT>(A.Xhat + row + e[u]);
+      }
     }
   }
-  if (A.G) {
+  if (A.G) {   // (never with a generic table: the local update is then a pass of its own)
     vf4 g[4];   // all gradient loads before the first store; the momentum memory is read in turn
 #pragma unroll
     for (int u = 0; u < 4; ++u)

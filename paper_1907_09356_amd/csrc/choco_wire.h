@@ -2,7 +2,9 @@
 // sign, 2*32*k for top_a, 32*k for random_a, b bits per entry for gsgd_b).  These kernels
 // encode the q of the last gossip step into those sizes and decode them again; they are
 // not on the timed path (on one GPU "sending" is memory traffic), they are what a
-// worker-per-GPU mapping would put on the links.
+// worker-per-GPU mapping would put on the links.  For sign and gsgd the bits of the message
+// are written by the compress pass itself (the bit planes of choco_kernels.h); packing is a
+// copy of those planes behind the header (whole vector) or their re-alignment layer by layer.
 //
 // Layout, 32-bit words, W = ceil(d / 32), one message per worker, messages back to back:
 //   sign      [c as float][W words: bit e%32 of word e/32 set iff the entry is -c]
@@ -26,11 +28,12 @@ struct WireArgs {
   int64_t W;                // words per bit plane
   int32_t mb;               // gsgd: magnitude bits
   int32_t levels;
-  const int32_t* codes;     // n x ld transmitted codes of the last step (sign, gsgd)
+  const uint32_t* planes;   // n x nplanes x plane_words: bit planes of the last step's codes (sign, gsgd)
+  int64_t plane_words;      // ceil(ld / 32)
+  int32_t nplanes;
+  const uint4* ovf_ring;    // gsgd: entries at level s remembered by the compress pass, tagged with the step
+  uint32_t t_lo, t_hi;      // the step the messages are of
   const WorkerCtl* ctl;
-  uint32_t* ovf_count;      // n
-  uint32_t* ovf_idx;        // n x kOverflowSlots
-  uint32_t* status;         // n: non-zero if a message could not be encoded
   int64_t k;
   const int32_t* sel_idx;
   const float* sel_val;
@@ -61,17 +64,38 @@ __device__ __forceinline__ int plane_layer(const WireArgs& A, int64_t pw) {
   return lo;
 }
 
-// The 32 codes behind word w of layer L's bit planes; entries past the layer's end read as 0.
-__device__ __forceinline__ void load_layer_codes32(const WireArgs& A, int i, const LayerDesc& L, int64_t w,
-                                                   int32_t (&c)[32]) {
-  const int32_t* src = A.codes + (int64_t)i * A.ld + L.start + 32 * w;   // 16-byte aligned: start is a multiple of 4
+// The index slots of a gsgd message: the entries the compress pass remembered for this step,
+// ascending, 0xFFFFFFFF where unused.  (At most four entries of a vector reach level s: each
+// needs |v| r + u >= s with u < 1, i.e. more than half of the norm up to rounding, and the squares
+// of four such shares already add up to the whole.)
+__device__ __forceinline__ void ring_slots(const WireArgs& A, int64_t unit, uint32_t (&v)[kOverflowSlots]) {
+  int cnt = 0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    vi4 q = vi4{0, 0, 0, 0};
-    if (32 * w + 4 * j < L.len) q = *reinterpret_cast<const vi4*>(src + 4 * j);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) c[4 * j + u] = (32 * w + 4 * j + u < L.len) ? q[u] : 0;
+  for (int j = 0; j < kOverflowSlots; ++j) v[j] = 0xFFFFFFFFu;
+  for (int s = 0; s < kOvfRing; ++s) {
+    const uint4 r = A.ovf_ring[unit * kOvfRing + s];
+    if (r.x == A.t_lo && r.y == A.t_hi + 1u && cnt < kOverflowSlots) v[cnt++] = r.z;
   }
+  for (int a = 1; a < kOverflowSlots; ++a)
+    for (int b = a; b > 0 && v[b] < v[b - 1]; --b) {
+      const uint32_t t = v[b];
+      v[b] = v[b - 1];
+      v[b - 1] = t;
+    }
+}
+
+// Word w of plane p of layer L of worker i: the row's plane holds bit e of the row at bit e%32 of
+// word e/32, the layer's message counts bits from the layer's first entry.
+__device__ __forceinline__ uint32_t layer_plane_word(const WireArgs& A, int i, int p, const LayerDesc& L, int64_t w) {
+  const uint32_t* P = A.planes + ((int64_t)i * A.nplanes + p) * A.plane_words;
+  const int64_t b0 = (int64_t)L.start + 32 * w;
+  const int sh = (int)(b0 & 31);
+  const int64_t i0 = b0 >> 5;
+  uint32_t v = P[i0] >> sh;
+  if (sh && i0 + 1 < A.plane_words) v |= P[i0 + 1] << (32 - sh);
+  const int64_t left = (int64_t)L.len - 32 * w;     // bits of this word that belong to the layer
+  if (left < 32) v &= (1u << left) - 1u;
+  return v;
 }
 
 // sign / gsgd layer by layer.  grid (ceil(total plane words / 256), n): one thread per word position
@@ -88,55 +112,18 @@ __global__ __launch_bounds__(256) void k_pack_dense_layers(WireArgs A, uint32_t*
   uint32_t* out = msg + (int64_t)i * A.words + A.layer_word_off[lay];
   const LayerScale ls = A.layer_scale[(int64_t)i * A.nlayers + lay];
   if (w == 0) out[0] = __float_as_uint(GSGD ? ls.step : ls.c);
-  int32_t c[32];
-  load_layer_codes32(A, i, L, w, c);
-  uint32_t sign = 0;
   if (!GSGD) {
-#pragma unroll
-    for (int j = 0; j < 32; ++j) sign |= (c[j] < 0 ? 1u : 0u) << j;
-    out[1 + w] = sign;
+    out[1 + w] = layer_plane_word(A, i, 0, L, w);
     return;
   }
-  const int32_t maxmag = (1 << A.mb) - 1;
+  if (w == 0) {
+    uint32_t v[kOverflowSlots];
+    ring_slots(A, (int64_t)i * A.nlayers + lay, v);
+#pragma unroll
+    for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
+  }
   uint32_t* planes = out + 1 + kOverflowSlots;
-  const int64_t slot0 = ((int64_t)i * A.nlayers + lay);
-#pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    sign |= (c[j] < 0 ? 1u : 0u) << j;
-    c[j] = c[j] < 0 ? -c[j] : c[j];
-    if (c[j] > maxmag) {
-      const uint32_t slot = atomicAdd(A.ovf_count + slot0, 1u);
-      if (slot < (uint32_t)kOverflowSlots) A.ovf_idx[slot0 * kOverflowSlots + slot] = (uint32_t)(32 * w + j);
-      c[j] = maxmag;
-    }
-  }
-  planes[w] = sign;
-  for (int p = 0; p < A.mb; ++p) {
-    uint32_t bits = 0;
-#pragma unroll
-    for (int j = 0; j < 32; ++j) bits |= (uint32_t)((c[j] >> p) & 1) << j;
-    planes[(int64_t)(1 + p) * W + w] = bits;
-  }
-}
-
-// grid (nlayers, n), one wave: the index slots of every layer's gsgd message
-__global__ __launch_bounds__(64) void k_pack_gsgd_layers_finish(WireArgs A, uint32_t* msg) {
-  const int lay = blockIdx.x, i = blockIdx.y;
-  if (threadIdx.x != 0) return;
-  uint32_t* out = msg + (int64_t)i * A.words + A.layer_word_off[lay];
-  const int64_t slot0 = (int64_t)i * A.nlayers + lay;
-  const uint32_t cnt = A.ovf_count[slot0];
-  uint32_t v[kOverflowSlots];
-  for (int j = 0; j < kOverflowSlots; ++j) v[j] = (uint32_t)j < cnt ? A.ovf_idx[slot0 * kOverflowSlots + j] : 0xFFFFFFFFu;
-  for (int a = 1; a < kOverflowSlots; ++a)
-    for (int b = a; b > 0 && v[b] < v[b - 1]; --b) {
-      const uint32_t t = v[b];
-      v[b] = v[b - 1];
-      v[b - 1] = t;
-    }
-  for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
-  if (cnt > (uint32_t)kOverflowSlots) A.status[i] = 1u;   // cleared by the host before the launch
-  A.ovf_count[slot0] = 0;
+  for (int p = 0; p < A.nplanes; ++p) planes[(int64_t)p * W + w] = layer_plane_word(A, i, p, L, w);
 }
 
 // after k_wire_zero.  grid (ceil(total plane words / 256), n)
@@ -171,81 +158,25 @@ __global__ __launch_bounds__(256) void k_unpack_dense_layers(WireArgs A, const u
   }
 }
 
-// The 32 codes behind word w of a row's bit planes; entries past d read as 0.
-__device__ __forceinline__ void load_codes32(const WireArgs& A, int i, int64_t w, int32_t (&c)[32]) {
-  const int32_t* src = A.codes + (int64_t)i * A.ld + 32 * w;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    vi4 q = vi4{0, 0, 0, 0};
-    if (32 * w + 4 * j < A.d) q = *reinterpret_cast<const vi4*>(src + 4 * j);   // ld is a multiple of 4
-#pragma unroll
-    for (int u = 0; u < 4; ++u) c[4 * j + u] = (32 * w + 4 * j + u < A.d) ? q[u] : 0;
-  }
-}
-
-// grid (ceil(W / 256), n): one thread per word of the sign plane
-__global__ __launch_bounds__(256) void k_pack_sign(WireArgs A, uint32_t* msg) {
-  const int i = blockIdx.y;
+// sign / gsgd on the whole vector: the header (scale or step, and for gsgd the index slots), then
+// the planes as the compress pass wrote them.  grid (ceil(W / 256), nplanes, n)
+template <bool GSGD>
+__global__ __launch_bounds__(256) void k_pack_planes(WireArgs A, uint32_t* msg) {
+  const int i = blockIdx.z, p = blockIdx.y;
   const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
   uint32_t* out = msg + (int64_t)i * A.words;
-  if (w == 0) out[0] = __float_as_uint(A.ctl[i].scale_c);
-  if (w >= A.W) return;
-  int32_t c[32];
-  load_codes32(A, i, w, c);
-  uint32_t bits = 0;
+  if (w == 0 && p == 0) {
+    out[0] = __float_as_uint(GSGD ? A.ctl[i].scale_step : A.ctl[i].scale_c);
+    if (GSGD) {
+      uint32_t v[kOverflowSlots];
+      ring_slots(A, (int64_t)i, v);
 #pragma unroll
-  for (int j = 0; j < 32; ++j) bits |= (c[j] < 0 ? 1u : 0u) << j;
-  out[1 + w] = bits;
-}
-
-// grid (ceil(W / 256), n): one thread per word position, all planes
-__global__ __launch_bounds__(256) void k_pack_gsgd(WireArgs A, uint32_t* msg) {
-  const int i = blockIdx.y;
-  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  uint32_t* out = msg + (int64_t)i * A.words;
-  if (w == 0) out[0] = __float_as_uint(A.ctl[i].scale_step);
-  if (w >= A.W) return;
-  int32_t c[32];
-  load_codes32(A, i, w, c);
-  const int32_t maxmag = (1 << A.mb) - 1;
-  uint32_t* planes = out + 1 + kOverflowSlots;
-  uint32_t sign = 0;
-#pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    sign |= (c[j] < 0 ? 1u : 0u) << j;
-    c[j] = c[j] < 0 ? -c[j] : c[j];
-    if (c[j] > maxmag) {   // the level s itself: rare, goes through the index slots
-      const uint32_t slot = atomicAdd(A.ovf_count + i, 1u);
-      if (slot < (uint32_t)kOverflowSlots) A.ovf_idx[i * kOverflowSlots + slot] = (uint32_t)(32 * w + j);
-      c[j] = maxmag;
+      for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
     }
   }
-  planes[w] = sign;
-  for (int p = 0; p < A.mb; ++p) {
-    uint32_t bits = 0;
-#pragma unroll
-    for (int j = 0; j < 32; ++j) bits |= (uint32_t)((c[j] >> p) & 1) << j;
-    planes[(int64_t)(1 + p) * A.W + w] = bits;
-  }
-}
-
-// grid n, one wave: orders the index slots, flags a message with too many, re-arms the counter
-__global__ __launch_bounds__(64) void k_pack_gsgd_finish(WireArgs A, uint32_t* msg) {
-  const int i = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  uint32_t* out = msg + (int64_t)i * A.words;
-  const uint32_t cnt = A.ovf_count[i];
-  uint32_t v[kOverflowSlots];
-  for (int j = 0; j < kOverflowSlots; ++j) v[j] = (uint32_t)j < cnt ? A.ovf_idx[i * kOverflowSlots + j] : 0xFFFFFFFFu;
-  for (int a = 1; a < kOverflowSlots; ++a)
-    for (int b = a; b > 0 && v[b] < v[b - 1]; --b) {
-      const uint32_t t = v[b];
-      v[b] = v[b - 1];
-      v[b - 1] = t;
-    }
-  for (int j = 0; j < kOverflowSlots; ++j) out[1 + j] = v[j];
-  A.status[i] = cnt > (uint32_t)kOverflowSlots ? 1u : 0u;
-  A.ovf_count[i] = 0;
+  if (w >= A.W) return;
+  const int64_t hdr = GSGD ? 1 + kOverflowSlots : 1;
+  out[hdr + (int64_t)p * A.W + w] = A.planes[((int64_t)i * A.nplanes + p) * A.plane_words + w];
 }
 
 // grid (ceil(k / 256), n)

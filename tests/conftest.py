@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    if not config.pluginmanager.hasplugin("timeout"):
+        # pytest-timeout is in the image; without it the marker is only a label (the GPU runs
+        # then rely on the `timeout` of the command line)
+        config.addinivalue_line("markers", "timeout(seconds): per-test limit, enforced by pytest-timeout")
 
 
 def pytest_collection_modifyitems(config, items):

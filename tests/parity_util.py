@@ -8,13 +8,6 @@ from paper_1907_09356_amd import binding
 REF_MIX = {binding.MIX_INCREMENTAL_S: ref.INCREMENTAL_S, binding.MIX_DIRECT: ref.DIRECT}
 
 
-def resolved_mix(compressor, mix_form):
-    if mix_form != binding.MIX_AUTO:
-        return mix_form
-    sparse = compressor in (binding.Q_TOPK, binding.Q_RANDK)
-    return binding.MIX_INCREMENTAL_S if sparse else binding.MIX_DIRECT
-
-
 def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
@@ -46,7 +39,7 @@ class Pair:
         self.gpu = binding.Choco(self.X, self.d, *topo, gamma, compressor, k=k, levels=levels,
                                  qsgd_biased=qsgd_biased, randk_rescale=randk_rescale, order=order,
                                  mix_form=mix_form, seed=seed, **extra)
-        self.mix = resolved_mix(compressor, mix_form)
+        self.mix = self.gpu.mix_form()   # what the library resolved MIX_AUTO to: the oracle takes the same form
         self.ref = ref.RefState(X0, *topo, gamma=gamma, compressor=compressor, k=k, levels=levels,
                                 qsgd_biased=qsgd_biased, randk_rescale=randk_rescale, order=order,
                                 mix_form=REF_MIX[self.mix], seed=seed, layers=layers)

@@ -52,7 +52,7 @@ def test_workspace_bytes_scales_with_the_state():
 
 
 @pytest.mark.parametrize("over", [
-    dict(n=0), dict(d=0), dict(d=2 ** 31), dict(ld=1001), dict(ld=996), dict(gamma=0.0),
+    dict(n=0), dict(d=0), dict(d=2 ** 31), dict(d=2 ** 31 - 2 ** 19 + 1, k=5), dict(ld=1001), dict(ld=996), dict(gamma=0.0),
     dict(gamma=-1.0), dict(gamma=float("nan")), dict(gamma=float("inf")), dict(compressor=7),
     dict(k=0), dict(k=1001), dict(compressor=B.Q_QSGD, levels=0), dict(order=2), dict(mix_form=3),
 ])
@@ -60,6 +60,28 @@ def test_bad_scalars_are_rejected(over):
     c, keep = cfg(**over)
     out = ctypes.c_size_t()
     assert B.lib().choco_workspace_bytes(ctypes.byref(c), ctypes.byref(out)) == B.E_INVAL
+
+
+def test_largest_vector_is_accepted():
+    c, keep = cfg(d=2 ** 31 - 2 ** 19, k=5)
+    out = ctypes.c_size_t()
+    assert B.lib().choco_workspace_bytes(ctypes.byref(c), ctypes.byref(out)) == B.OK
+    assert out.value > 8 * 4 * (2 ** 31 - 2 ** 19)
+
+
+def test_auto_mix_form_keeps_no_third_vector_up_to_64_workers():
+    # MIX_AUTO: the direct form wherever the LDS tile of all rows exists; incremental
+    # neighbour sums (a third n x d array) above 64 workers and for top_a in the printed order
+    def ws(**over):
+        c, keep = cfg(d=100000, k=1000, **over)
+        return B.workspace_bytes(c)
+    state = 8 * 100000 * 4
+    assert ws(mix_form=B.MIX_INCREMENTAL_S) - ws(mix_form=B.MIX_DIRECT) >= state - 4096
+    assert abs(ws() - ws(mix_form=B.MIX_DIRECT)) < 4096
+    assert abs(ws(order=B.ORDER_MIX_THEN_COMPRESS) - ws(mix_form=B.MIX_INCREMENTAL_S,
+                                                        order=B.ORDER_MIX_THEN_COMPRESS)) < 4096
+    assert abs(ws(compressor=B.Q_RANDK, order=B.ORDER_MIX_THEN_COMPRESS)
+               - ws(compressor=B.Q_RANDK, mix_form=B.MIX_DIRECT, order=B.ORDER_MIX_THEN_COMPRESS)) < 4096
 
 
 def test_unsupported_combination_is_reported():
@@ -133,11 +155,15 @@ def test_layer_tables_are_validated():
     assert layer_code(1000, [0, 400], [398, 600], [4, 6]) == B.OK          # start padded to 4
     assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_SIGN) == B.OK
     assert layer_code(1000, [0, 400], [400, 600], None) == B.E_INVAL       # top_a needs k per layer
-    assert layer_code(1000, [0, 398], [398, 602], [4, 6]) == B.E_INVAL     # start not padded
-    assert layer_code(1000, [0, 404], [400, 596], [4, 6]) == B.E_INVAL     # gap beyond the padding
-    assert layer_code(1000, [0, 400], [400, 500], [4, 6]) == B.E_INVAL     # does not end at d
+    # any disjoint ascending slices are a layer table: no alignment, gaps allowed
+    assert layer_code(1000, [0, 398], [398, 602], [4, 6]) == B.OK          # starts anywhere
+    assert layer_code(1000, [0, 404], [400, 596], [4, 6]) == B.OK          # a gap between layers
+    assert layer_code(1000, [0, 400], [400, 500], [4, 6]) == B.OK          # the vector goes on after the last layer
+    assert layer_code(1000, [4, 400], [396, 600], [4, 6]) == B.OK          # ... and begins before the first
+    assert layer_code(1000, [1, 3, 7], [2, 4, 993], [1, 1, 9]) == B.OK     # several layers inside one 16-byte piece
     assert layer_code(1000, [0, 400], [400, 601], [4, 6]) == B.E_INVAL     # runs past d
-    assert layer_code(1000, [4, 400], [396, 600], [4, 6]) == B.E_INVAL     # does not start at 0
+    assert layer_code(1000, [0, 399], [400, 601], [4, 6]) == B.E_INVAL     # overlap
+    assert layer_code(1000, [400, 0], [600, 400], [6, 4]) == B.E_INVAL     # not ascending
     assert layer_code(1000, [0, 400], [400, 600], [401, 6]) == B.E_INVAL   # k above the length
     assert layer_code(1000, [0, 400], [400, 600], [0, 0]) == B.E_INVAL     # nothing ever sent
     assert layer_code(1000, [0, 400], [400, 600], [0, 6]) == B.OK          # one silent layer is fine

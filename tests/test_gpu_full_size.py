@@ -11,14 +11,20 @@ from tests.parity_util import Pair
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-def run(n, d, topo, steps, gamma, lr, bias_std, fused=True, layers=None, **kw):
-    """fused=True drives choco_step, the call bench.py times; False the two separate calls."""
+MIXES = [B.MIX_INCREMENTAL_S, B.MIX_DIRECT]   # the library's own choice for these shapes is the second
+
+
+def run(n, d, topo, steps, gamma, lr, bias_std, fused=True, layers=None, momentum=False, **kw):
+    """fused=True drives choco_step (momentum=True: choco_step_momentum), the calls bench.py
+    times; False the two separate calls."""
     X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
     pair = Pair(X0, topo, gamma, seed=7, layers=layers, **kw)
     grads = synth.GradientStream(n, d, seed=11, noise_std=0.01, bias_std=bias_std)
     try:
         for t in range(steps):
-            if fused:
+            if momentum:
+                det = pair.step_momentum(grads.next(), lr, 0.9, 1e-4)   # also compares the momentum memory
+            elif fused:
                 det = pair.step(grads.next(), lr)
             else:
                 pair.sgd_step(grads.next(), lr)
@@ -29,22 +35,53 @@ def run(n, d, topo, steps, gamma, lr, bias_std, fused=True, layers=None, **kw):
         pair.close()
 
 
-def test_large_model_shape_topk():
+@pytest.mark.parametrize("mix", MIXES)
+def test_large_model_shape_topk(mix):
     # n = 8 ring, d = 28,000,000, top-k 0.1 %: step 0 takes the histogram fallback, the
-    # later steps the guessed-threshold path
-    scal = run(8, 28_000_000, synth.ring_csr(8), 3, 0.01, 0.05, 0.0, compressor=B.Q_TOPK, k=28_000)
+    # later steps the guessed-threshold path; with the neighbour sums kept incrementally
+    # (scatter) and with the direct mix (the update of xhat rides on the tile pass)
+    scal = run(8, 28_000_000, synth.ring_csr(8), 3, 0.01, 0.05, 0.0, compressor=B.Q_TOPK, k=28_000, mix_form=mix)
     assert np.all(scal[:, 3] == 0)
 
 
+@pytest.mark.parametrize("mix", MIXES)
+def test_large_model_shape_topk_in_the_printed_order(mix):
+    # Algorithm 1 as printed (mix, then compress): with incremental sums ONE pass over the rows
+    # does local update, mix and candidate selection (the 4-vectors-per-thread, non-temporal
+    # instantiation that only rows above 2^21 entries take)
+    run(8, 28_000_000, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, compressor=B.Q_TOPK, k=28_000,
+        order=B.ORDER_MIX_THEN_COMPRESS, mix_form=mix)
+
+
+@pytest.mark.parametrize("mix", MIXES)
+def test_large_model_shape_topk_with_momentum(mix):
+    # Algorithm 2 fused into the first pass (choco_step_momentum), 40 B/entry
+    run(8, 28_000_000, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, momentum=True, compressor=B.Q_TOPK, k=28_000,
+        mix_form=mix)
+
+
+def test_large_model_shape_randk():
+    # the masks of step 1 on are drawn ahead on the second stream; the update of xhat and the
+    # deferred local update ride on the tile pass
+    run(8, 28_000_000, synth.ring_csr(8), 3, 0.01, 0.05, 0.0, compressor=B.Q_RANDK, k=28_000)
+
+
 def test_large_model_shape_qsgd():
-    run(8, 28_000_000, synth.ring_csr(8), 1, 0.01, 0.05, 0.0, compressor=B.Q_QSGD, levels=16)
+    run(8, 28_000_000, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, compressor=B.Q_QSGD, levels=16)
+
+
+@pytest.mark.parametrize("mix", MIXES)
+@pytest.mark.parametrize("comp", [B.Q_TOPK, B.Q_RANDK])
+@pytest.mark.parametrize("topo", ["ring", "torus"])
+def test_peer_to_peer_shape(comp, topo, mix):
+    csr = synth.ring_csr(64) if topo == "ring" else synth.torus_csr(8, 8)
+    run(64, 270_000, csr, 4, 0.02, 0.1, 0.001, compressor=comp, k=2700, mix_form=mix)
 
 
 @pytest.mark.parametrize("comp", [B.Q_TOPK, B.Q_RANDK])
-@pytest.mark.parametrize("topo", ["ring", "torus"])
-def test_peer_to_peer_shape(comp, topo):
-    csr = synth.ring_csr(64) if topo == "ring" else synth.torus_csr(8, 8)
-    run(64, 270_000, csr, 4, 0.02, 0.1, 0.001, compressor=comp, k=2700)
+def test_peer_to_peer_shape_in_the_printed_order(comp):
+    run(64, 270_000, synth.torus_csr(8, 8), 3, 0.02, 0.1, 0.001, compressor=comp, k=2700,
+        order=B.ORDER_MIX_THEN_COMPRESS)
 
 
 @pytest.mark.parametrize("fused", [True, False])
@@ -121,8 +158,9 @@ def test_datacenter_shape_sign_1000_steps():
     long_run(8, 270_000, synth.ring_csr(8), 1000, 0.4, 0.1, compressor=B.Q_SIGN)
 
 
-def test_peer_to_peer_ring_topk_100_steps():
-    long_run(64, 270_000, synth.ring_csr(64), 100, 0.02, 0.1, compressor=B.Q_TOPK, k=2700)
+@pytest.mark.parametrize("mix", MIXES)
+def test_peer_to_peer_ring_topk_100_steps(mix):
+    long_run(64, 270_000, synth.ring_csr(64), 100, 0.02, 0.1, compressor=B.Q_TOPK, k=2700, mix_form=mix)
 
 
 def test_peer_to_peer_torus_randk_100_steps():

@@ -302,3 +302,121 @@ def test_long_layer_topk_ties_go_to_the_lower_index():
             pair.check(det, tag="long layer ties step %d" % t)
     finally:
         pair.close()
+
+
+# --------------------------------------------------------------------------
+# Entries outside the layers, and tables as a model's flat parameter vector has them
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_padding_between_layers_may_hold_anything(name, q, order):
+    # aligned table (layers start on multiples of 4), but x and g are NOT zero in the padding
+    # entries: they are never compressed or sent (q = 0 there), yet the local update and the
+    # mix treat them like any entry - exactly what the oracle does with entries in no slice
+    layers = mixed_layers(fraction=0.05)
+    n = 5
+    d = synth.layers_dim(layers)
+    X0 = synth.normal_state(n, d, seed=21)          # padding entries as random as the rest
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=5, layers=layers, **q)
+    grads = synth.GradientStream(n, d, seed=22, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(4):
+            det = pair.step(grads.next(), 0.1)
+            pair.check(det, tag="%s non-zero padding step %d" % (name, t))
+        inside = np.zeros(d, dtype=bool)
+        for a, ln in zip(layers[0], layers[1]):
+            inside[a:a + ln] = True
+        assert (~inside).any() and not pair.gpu.xhat()[:, :d].cpu().numpy()[:, ~inside].any()
+    finally:
+        pair.close()
+
+
+def generic_table(lengths, gaps, fraction=0.05, lead=0, tail=0):
+    """(start, length, k), d for layers laid out with the given gaps after each (no alignment)."""
+    start, pos = [], lead
+    for ln, g in zip(lengths, gaps):
+        start.append(pos)
+        pos += ln + g
+    length = np.asarray(lengths, dtype=np.int64)
+    k = np.maximum(1, np.floor(fraction * length).astype(np.int64))
+    return (np.asarray(start, dtype=np.int64), length, k), pos + tail
+
+
+# layers that start anywhere: back to back without padding, several inside one 16-byte piece,
+# gaps of 1..9 entries, every size class of the layer kernel, a vector that begins before the
+# first layer and goes on after the last
+GENERIC_LENGTHS = [5, 1, 2, 1, 433, 17, 2561, 3, 10241, 255, 40957, 7, 9001, 64]
+GENERIC_GAPS = [0, 0, 0, 3, 0, 1, 0, 0, 9, 0, 2, 0, 0, 0]
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_layer_tables_without_alignment(name, q, order):
+    layers, d = generic_table(GENERIC_LENGTHS, GENERIC_GAPS, lead=3, tail=6)
+    layers[2][1] = 0 if q["compressor"] in (binding.Q_TOPK, binding.Q_RANDK) else layers[2][1]   # a silent layer
+    assert any(s % 4 for s in layers[0])
+    n = 5
+    X0 = synth.normal_state(n, d, seed=23)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=6, layers=layers, **q)
+    grads = synth.GradientStream(n, d, seed=24, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(4):
+            if t % 2:
+                pair.sgd_step(grads.next(), 0.1)
+                det = pair.gossip_step()
+            else:
+                det = pair.step(grads.next(), 0.1)      # the local update becomes a pass of its own
+            pair.check(det, tag="%s generic table step %d" % (name, t))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3], OPERATORS[4]])
+def test_layer_tables_without_alignment_long_layers_and_momentum(name, q):
+    # layers above 40,960 entries that start off a 16-byte boundary take the streaming select on a
+    # piece of the row whose first entries belong to the layer before
+    layers, d = generic_table([30, 70001, 3, 41000, 5000, 90000], [0, 0, 1, 0, 0, 0], fraction=0.01, lead=1, tail=2)
+    n = 4
+    X0 = synth.normal_state(n, d, seed=25)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers, **q)
+    grads = synth.GradientStream(n, d, seed=26, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(4):
+            det = pair.step_momentum(grads.next(), 0.05, 0.9, 1e-4) if t < 2 else pair.step(grads.next(), 0.05)
+            pair.check(det, tag="%s generic long layers step %d" % (name, t))
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_messages_of_a_layer_table_without_alignment(name, q):
+    from oracle import choco_ref as ref
+    layers, d = generic_table([5, 1, 2, 433, 17, 2561, 3, 4099], [0, 0, 3, 0, 1, 0, 0, 0], lead=2, tail=5)
+    n = 4
+    X0 = synth.normal_state(n, d, seed=27)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, layers=layers, **q)
+    grads = synth.GradientStream(n, d, seed=28, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(2):
+            pair.sgd_step(grads.next(), 0.1)
+            v = pair.ref.X - pair.ref.Xhat
+            want = [ref.pack_layers(q["compressor"], v[i], layers, levels=q.get("levels", 1),
+                                    qsgd_biased=q.get("qsgd_biased", 1), randk_rescale=q.get("randk_rescale", 0),
+                                    seed=pair.ref.seed, t=t, worker=i) for i in range(n)]
+            det = pair.gossip_step()
+            pair.check(det, tag="%s step %d" % (name, t))
+            msgs = pair.gpu.pack_messages()
+            got = msgs.cpu().numpy().view(np.uint32)
+            dense = pair.gpu.unpack_messages(msgs)
+            pair.gpu.sync()
+            dense = dense.cpu().numpy()
+            for i in range(n):
+                if q["compressor"] == binding.Q_TOPK:
+                    a = got[i].reshape(-1, 2)
+                    b = want[i][1].reshape(-1, 2)
+                    assert np.array_equal(a[np.argsort(a[:, 0], kind="stable")], b[np.argsort(b[:, 0], kind="stable")])
+                else:
+                    assert np.array_equal(got[i], want[i][1]), "%s: worker %d message differs" % (name, i)
+                assert np.array_equal(dense[i, :d], want[i][0])
+    finally:
+        pair.close()

@@ -35,10 +35,23 @@ def topo_for(n):
     return synth.ring_csr(n)
 
 
-def run(n, d, comp, order, steps=6, mix_form=B.MIX_AUTO, gamma=0.2, frac=0.01, seed=5, lr=0.05,
+SPARSE_MIXES = [B.MIX_INCREMENTAL_S, B.MIX_DIRECT]
+MIX_NAME = {B.MIX_AUTO: "auto", B.MIX_INCREMENTAL_S: "incremental", B.MIX_DIRECT: "direct"}
+
+
+def run(n, d, comp, order, steps=6, mix_form=None, gamma=0.2, frac=0.01, seed=5, lr=0.05,
         force=False, x0=None):
+    """mix_form=None: the library's choice for the dense operators; for top_a / random_a BOTH
+    evaluations of the mix, one run each (the library's choice is one of the two)."""
     kw = dict(COMPRESSORS[comp])
-    if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+    sparse = kw["compressor"] in (B.Q_TOPK, B.Q_RANDK)
+    if mix_form is None:
+        if sparse:
+            for m in SPARSE_MIXES:
+                run(n, d, comp, order, steps, m, gamma, frac, seed, lr, force, x0)
+            return
+        mix_form = B.MIX_AUTO
+    if sparse:
         kw["k"] = max(1, int(frac * d))
     X0 = synth.normal_state(n, d, seed=seed) if x0 is None else x0
     pair = Pair(X0, topo_for(n), gamma, order=order, mix_form=mix_form, seed=1234 + seed, **kw)
@@ -48,7 +61,7 @@ def run(n, d, comp, order, steps=6, mix_form=B.MIX_AUTO, gamma=0.2, frac=0.01, s
             if force:
                 pair.force_state()
             det = pair.gossip_step()
-            pair.check(det, tag="%s n=%d d=%d order=%d step %d" % (comp, n, d, order, t))
+            pair.check(det, tag="%s n=%d d=%d order=%d mix=%s step %d" % (comp, n, d, order, MIX_NAME[mix_form], t))
             pair.sgd_step(grads.next(), lr)
     finally:
         pair.close()
@@ -70,8 +83,8 @@ def test_step_parity_teacher_forced(comp, order):
 
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp", ["topk", "randk"])
-def test_sparse_operators_with_direct_mix(comp, order):
-    run(8, 6000, comp, order, mix_form=B.MIX_DIRECT)
+def test_sparse_operators_with_both_mix_forms(comp, order):
+    run(8, 6000, comp, order)
 
 
 @pytest.mark.parametrize("order", ORDERS)
@@ -81,11 +94,12 @@ def test_more_workers_than_the_lds_tile_holds(comp, order):
     run(70, 1030, comp, order, steps=3)
 
 
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("d,k", [(1, 1), (3, 2), (5, 5), (300, 1), (300, 300), (4096, 2048)])
 @pytest.mark.parametrize("comp", ["topk", "randk"])
-def test_select_extreme_k(comp, d, k):
+def test_select_extreme_k(comp, d, k, mix):
     kw = dict(COMPRESSORS[comp])
-    pair = Pair(synth.normal_state(4, d, seed=d + k), synth.ring_csr(4), 0.3, k=k, seed=9, **kw)
+    pair = Pair(synth.normal_state(4, d, seed=d + k), synth.ring_csr(4), 0.3, k=k, seed=9, mix_form=mix, **kw)
     try:
         for t in range(3):
             det = pair.gossip_step()
@@ -94,8 +108,9 @@ def test_select_extreme_k(comp, d, k):
         pair.close()
 
 
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("order", ORDERS)
-def test_topk_ties_and_zeros(order):
+def test_topk_ties_and_zeros(order, mix):
     # integer-valued state: thousands of equal magnitudes, so the tie rule (lower index
     # first) decides most of the selection; all-zero rows as well
     rng = np.random.default_rng(3)
@@ -103,7 +118,7 @@ def test_topk_ties_and_zeros(order):
     X0 = rng.integers(-3, 4, size=(n, d)).astype(np.float32)
     X0[2] = 0.0
     X0[3, ::2] = -0.0
-    pair = Pair(X0, synth.ring_csr(n), 0.25, compressor=B.Q_TOPK, k=k, order=order)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, compressor=B.Q_TOPK, k=k, order=order, mix_form=mix)
     try:
         for t in range(5):
             det = pair.gossip_step()
@@ -133,13 +148,14 @@ def test_select_when_one_digit_overflows_the_candidate_list(comp):
         pair.close()
 
 
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp,k", [("topk", 8000), ("randk", 12000), ("randk_rescaled", 12000)])
-def test_long_candidate_lists_take_the_multi_block_select(comp, k, order):
+def test_long_candidate_lists_take_the_multi_block_select(comp, k, order, mix):
     # k + slack above 16384 candidates per worker: histogram parts, parallel emission, finish
     n, d = 4, 200000
     kw = dict(COMPRESSORS[comp])
-    pair = Pair(synth.normal_state(n, d, seed=6), synth.ring_csr(n), 0.2, k=k, order=order, seed=5, **kw)
+    pair = Pair(synth.normal_state(n, d, seed=6), synth.ring_csr(n), 0.2, k=k, order=order, seed=5, mix_form=mix, **kw)
     grads = synth.GradientStream(n, d, seed=7)
     try:
         for t in range(5):
@@ -174,9 +190,10 @@ def test_single_and_two_workers(n, comp, order):
     run(n, 3000, comp, order, steps=3)
 
 
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
-def test_irregular_graph_with_local_degree_weights(comp, order):
+def test_irregular_graph_with_local_degree_weights(comp, order, mix):
     # 32 nodes, maximum degree 14, weights 1/(1 + max(deg i, deg j)) with the remainder on the
     # self loop: rows of different lengths and different weights per edge
     adj = synth.irregular_graph(32, 14, seed=3)
@@ -185,6 +202,9 @@ def test_irregular_graph_with_local_degree_weights(comp, order):
     kw = dict(COMPRESSORS[comp])
     if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
         kw["k"] = 40
+        kw["mix_form"] = mix
+    elif mix != SPARSE_MIXES[0]:
+        pytest.skip("the dense operators have one form of the mix")
     n, d = 32, 4000
     pair = Pair(synth.normal_state(n, d, seed=2), topo, 0.3, order=order, seed=4, **kw)
     grads = synth.GradientStream(n, d, seed=3)
@@ -245,12 +265,14 @@ def test_zero_state_and_zero_norm():
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp", list(COMPRESSORS))
 @pytest.mark.parametrize("n,d,mix_form", [(8, 70001, B.MIX_AUTO), (9, 2000, B.MIX_AUTO), (70, 1030, B.MIX_AUTO),
-                                          (8, 6000, B.MIX_DIRECT)])
+                                          (8, 70001, B.MIX_INCREMENTAL_S), (9, 2000, B.MIX_INCREMENTAL_S),
+                                          (70, 1030, B.MIX_DIRECT), (8, 6000, B.MIX_DIRECT)])
 def test_fused_step_equals_sgd_then_gossip(n, d, mix_form, comp, order):
+    # MIX_AUTO: the direct form up to 64 workers, incremental neighbour sums above
     kw = dict(COMPRESSORS[comp])
     sparse = kw["compressor"] in (B.Q_TOPK, B.Q_RANDK)
-    if mix_form == B.MIX_DIRECT and not sparse:
-        pytest.skip("dense operators already use the direct form")
+    if mix_form != B.MIX_AUTO and not sparse:
+        pytest.skip("the dense operators have one form of the mix")
     if sparse:
         kw["k"] = max(1, d // 100)
     pair = Pair(synth.normal_state(n, d, seed=3), topo_for(n), 0.2, order=order, mix_form=mix_form,
@@ -266,13 +288,14 @@ def test_fused_step_equals_sgd_then_gossip(n, d, mix_form, comp, order):
 
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp", ["identity", "sign", "qsgd16", "topk", "randk", "randk_rescaled"])
-@pytest.mark.parametrize("n,d,mix_form", [(8, 70001, B.MIX_AUTO), (70, 1030, B.MIX_AUTO), (8, 6000, B.MIX_DIRECT)])
+@pytest.mark.parametrize("n,d,mix_form", [(8, 70001, B.MIX_AUTO), (70, 1030, B.MIX_AUTO), (8, 70001, B.MIX_INCREMENTAL_S),
+                                          (8, 6000, B.MIX_DIRECT)])
 def test_fused_momentum_step_equals_momentum_then_gossip(n, d, mix_form, comp, order):
     # Algorithm 2: v <- (g + lambda x) + beta v; x <- x - eta v, then the gossip step
     kw = dict(COMPRESSORS[comp])
     sparse = kw["compressor"] in (B.Q_TOPK, B.Q_RANDK)
-    if mix_form == B.MIX_DIRECT and not sparse:
-        pytest.skip("dense operators already use the direct form")
+    if mix_form != B.MIX_AUTO and not sparse:
+        pytest.skip("the dense operators have one form of the mix")
     if sparse:
         kw["k"] = max(1, d // 100)
     pair = Pair(synth.normal_state(n, d, seed=3), topo_for(n), 0.2, order=order, mix_form=mix_form,
@@ -344,21 +367,24 @@ def test_same_call_twice_is_bitwise_repeatable(comp):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
 
 
-def test_resume_from_step_counter():
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
+def test_resume_from_step_counter(mix):
     # random operators are keyed by (seed, t, worker, index): restoring (X, Xhat, S, t)
     # continues a run exactly
     import torch
     n, d, k = 4, 5000, 50
     topo = synth.ring_csr(n)
     X = torch.from_numpy(synth.normal_state(n, d, seed=3)).cuda().contiguous()
-    a = B.Choco(X, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11)
+    a = B.Choco(X, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11, mix_form=mix)
     for _ in range(3):
         a.gossip_step()
     a.sync()
     X2 = X.clone()
-    b = B.Choco(X2, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11)
+    b = B.Choco(X2, d, *topo, 0.2, B.Q_RANDK, k=k, seed=11, mix_form=mix)
     b.xhat().copy_(a.xhat())
-    b.nsum().copy_(a.nsum())
+    assert (a.nsum() is None) == (mix == B.MIX_DIRECT)    # the direct form keeps no third vector
+    if a.nsum() is not None:
+        b.nsum().copy_(a.nsum())
     b.set_step(a.get_step())
     for _ in range(2):
         a.gossip_step()
@@ -370,13 +396,14 @@ def test_resume_from_step_counter():
     b.close()
 
 
-def test_long_run_statistics_small_workload():
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
+def test_long_run_statistics_small_workload(mix):
     # the small BASELINE workload: ring of 8, d = 4096, top-1% (k = 41), gamma = 0.05,
     # 200 gossip steps from distinct x_i; consensus error per step and the mean agree
     # with the oracle to 1e-4 (free running)
     n, d, k = 8, 4096, 41
     pair = Pair(synth.normal_state(n, d, seed=20190709), synth.ring_csr(n), 0.05,
-                compressor=B.Q_TOPK, k=k)
+                compressor=B.Q_TOPK, k=k, mix_form=mix)
     try:
         for t in range(200):
             pair.gpu.gossip_step()
@@ -462,13 +489,15 @@ def test_row_stride_wider_than_the_vector(comp, order):
     pair.close()
 
 
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("order", ORDERS)
-def test_random_masks_selected_ahead_or_not_are_the_same(order):
+def test_random_masks_selected_ahead_or_not_are_the_same(order, mix):
     # random_a on short rows selects the next step's mask on a second stream; switching that
     # off, on again, moving the step counter and timing the kernels must not change a bit
     n, d, k = 6, 30011, 300
     X0 = synth.normal_state(n, d, seed=51)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=8, compressor=B.Q_RANDK, k=k, randk_rescale=1)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=8, compressor=B.Q_RANDK, k=k, randk_rescale=1,
+                mix_form=mix)
     grads = synth.GradientStream(n, d, seed=12, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(12):
@@ -489,12 +518,13 @@ def test_random_masks_selected_ahead_or_not_are_the_same(order):
         pair.close()
 
 
-def test_random_masks_selected_ahead_on_rows_without_a_bitmap():
+@pytest.mark.parametrize("mix", SPARSE_MIXES)
+def test_random_masks_selected_ahead_on_rows_without_a_bitmap(mix):
     # above 327,680 entries the kept entries are marked in a bit map in global memory; it exists twice and a
     # mask that was drawn ahead and then dropped (set_step) has its marks cleared again
     n, d, k = 3, 400_003, 3000
     X0 = synth.normal_state(n, d, seed=52)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, compressor=B.Q_RANDK, k=k)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=9, compressor=B.Q_RANDK, k=k, mix_form=mix)
     grads = synth.GradientStream(n, d, seed=13, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(9):

@@ -138,3 +138,66 @@ def test_random_configuration_that_fills_the_chip(case):
             pair.check(det, tag="large case %d (n=%d, d=%d, %s) step %d" % (case, n, d, c["kw"], t))
     finally:
         pair.close()
+
+
+def draw_generic_layers_case(case):
+    """Layer tables as a flat parameter vector has them: layers that start anywhere, gaps, entries
+    before the first and after the last layer; nothing outside the layers is zeroed."""
+    rng = np.random.default_rng(9000 + case)
+    comp = [B.Q_TOPK, B.Q_RANDK, B.Q_SIGN, B.Q_QSGD][case % 4]
+    sparse = comp in (B.Q_TOPK, B.Q_RANDK)
+    n = int(rng.choice([1, 2, 3, 5, 8, 17]))
+    topo = synth.ring_csr(n)
+    nl = int(rng.integers(1, 12))
+    lengths = [int(x) for x in rng.choice([1, 1, 2, 3, 5, 6, 17, 255, 257, 1000, 2559, 2561, 4099, 10239, 12000], size=nl)]
+    if rng.random() < 0.25:
+        lengths[int(rng.integers(0, nl))] = int(rng.choice([40958, 40961, 52001]))
+    aligned = rng.random() < 0.25           # every fourth table keeps the 4-entry alignment (with non-zero padding)
+    start, pos = [], int(rng.integers(0, 6)) * (0 if aligned else 1)
+    for ln in lengths:
+        if aligned:
+            pos = (pos + 3) // 4 * 4
+        start.append(pos)
+        pos += ln + (0 if aligned else int(rng.choice([0, 0, 0, 1, 2, 3, 7])))
+    d = pos + (0 if aligned else int(rng.integers(0, 9)))
+    length = np.asarray(lengths, dtype=np.int64)
+    k = np.maximum(1, np.floor(float(rng.choice([0.01, 0.05, 0.3])) * length).astype(np.int64))
+    if sparse and nl > 1 and rng.random() < 0.3:
+        k[int(rng.integers(0, nl))] = 0
+        if k.sum() == 0:
+            k[0] = 1
+    kw = dict(compressor=comp, order=int(rng.choice([B.ORDER_COMPRESS_THEN_MIX, B.ORDER_MIX_THEN_COMPRESS])),
+              seed=int(rng.integers(0, 2 ** 40)))
+    if comp == B.Q_QSGD:
+        kw["levels"] = int(rng.choice([1, 2, 3, 16, 255]))
+        kw["qsgd_biased"] = int(rng.integers(0, 2))
+    if comp == B.Q_RANDK:
+        kw["randk_rescale"] = int(rng.integers(0, 2))
+    calls = [str(c) for c in rng.choice(["step", "separate", "gossip", "momentum"], size=3)]
+    return dict(n=n, d=d, topo=topo, kw=kw, layers=(np.asarray(start, dtype=np.int64), length, k),
+                ld_align=int(rng.choice([4, 64])), calls=calls, gamma=float(rng.choice([0.05, 0.3, 0.9])))
+
+
+@pytest.mark.parametrize("case", range(60))
+def test_random_generic_layer_table(case):
+    c = draw_generic_layers_case(case)
+    n, d = c["n"], c["d"]
+    X0 = synth.normal_state(n, d, seed=case + 100)
+    pair = Pair(X0, c["topo"], c["gamma"], layers=c["layers"], ld_align=c["ld_align"], **c["kw"])
+    grads = synth.GradientStream(n, d, seed=case + 107, noise_std=0.05, bias_std=0.02)
+    tag = "generic case %d %s starts %s lengths %s" % (case, c["kw"], c["layers"][0].tolist(), c["layers"][1].tolist())
+    try:
+        for t, call in enumerate(c["calls"]):
+            G = grads.next()
+            if call == "step":
+                det = pair.step(G, 0.1)
+            elif call == "separate":
+                pair.sgd_step(G, 0.1)
+                det = pair.gossip_step()
+            elif call == "momentum":
+                det = pair.step_momentum(G, 0.05, 0.9, 1e-4)
+            else:
+                det = pair.gossip_step()
+            pair.check(det, tag="%s, call %d (%s)" % (tag, t, call))
+    finally:
+        pair.close()

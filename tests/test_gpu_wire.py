@@ -88,22 +88,102 @@ def test_level_s_goes_through_the_index_slots():
     pair.close()
 
 
-def test_message_calls_say_what_they_do_not_cover():
-    n, d = 4, 600
-    X0 = synth.normal_state(n, d, seed=1)
+def test_dense_messages_need_no_capture_buffer():
+    # the gossip step itself writes the bits of the sign / gsgd messages: a context that never had a
+    # capture buffer packs the same words as the oracle's encoder, layer by layer too
     import torch
-    X = torch.from_numpy(np.pad(X0, ((0, 0), (0, 0)))).cuda().contiguous()
-    g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_SIGN)
-    g.gossip_step()
-    with pytest.raises(binding.ChocoError) as err:      # no capture buffer: the codes are gone
-        g.pack_messages()
-    assert err.value.code == binding.E_INVAL
-    g.close()
+    n, d = 4, 6007
+    X0 = synth.normal_state(n, d, seed=1)
+    lengths = [700, 5, 3000, 33, 2257]
+    layers = synth.layer_table(lengths, fraction=0.05)
+    dl = synth.layers_dim(layers)
+    for q, lay, dd in ((dict(compressor=binding.Q_SIGN), None, d),
+                       (dict(compressor=binding.Q_QSGD, levels=16), None, d),
+                       (dict(compressor=binding.Q_QSGD, levels=5, qsgd_biased=0), None, d),
+                       (dict(compressor=binding.Q_SIGN), layers, dl),
+                       (dict(compressor=binding.Q_QSGD, levels=8), layers, dl)):
+        ld = (dd + 3) // 4 * 4
+        Xh = np.zeros((n, dd), dtype=np.float32)
+        Xh[:, :min(d, dd)] = X0[:, :min(d, dd)]
+        if lay is not None:      # the padding between layers carries nothing
+            inside = np.zeros(dd, dtype=bool)
+            for a0, ln in zip(lay[0], lay[1]):
+                inside[a0:a0 + ln] = True
+            Xh[:, ~inside] = 0.0
+        X = torch.zeros((n, ld), dtype=torch.float32, device="cuda:0")
+        X[:, :dd] = torch.from_numpy(Xh).cuda()
+        extra = dict(layers=lay) if lay is not None else {}
+        g = binding.Choco(X, dd, *synth.ring_csr(n), 0.2, seed=5, **q, **extra)
+        xhat = np.zeros_like(Xh)
+        for t in range(2):
+            v = X[:, :dd].cpu().numpy() - xhat
+            g.gossip_step()
+            msgs = g.pack_messages().cpu().numpy().view(np.uint32)
+            for i in range(n):
+                if lay is None:
+                    _, want = ref.pack_message(q["compressor"], v[i], levels=q.get("levels", 1),
+                                               qsgd_biased=q.get("qsgd_biased", 1), seed=5, t=t, worker=i)
+                else:
+                    _, want = ref.pack_layers(q["compressor"], v[i], lay, levels=q.get("levels", 1),
+                                              qsgd_biased=q.get("qsgd_biased", 1), seed=5, t=t, worker=i)
+                assert np.array_equal(msgs[i], want), (q, lay is not None, t, i)
+            xhat = g.xhat()[:, :dd].cpu().numpy()
+        g.close()
+
+
+def test_identity_has_no_message_format():
+    import torch
+    n, d = 4, 600
+    X = torch.from_numpy(synth.normal_state(n, d, seed=1)).cuda().contiguous()
     g = binding.Choco(X, d, *synth.ring_csr(n), 0.2, binding.Q_IDENTITY)
     with pytest.raises(binding.ChocoError) as err:      # nothing is compressed: no message format
         g.message_bytes()
     assert err.value.code == binding.E_UNSUPPORTED
+    assert binding.lib().choco_last_message(g.ctx, 0, None, None, None, None) == binding.E_INVAL
     g.close()
+
+
+@pytest.mark.parametrize("name,q", OPERATORS)
+def test_last_message_read_back(name, q):
+    # one call per worker returns what it sent: kept pairs, or the bit planes and the scale
+    n, d = 5, 4133
+    pair = Pair(synth.normal_state(n, d, seed=37), synth.ring_csr(n), 0.3, seed=9, **q)
+    grads = synth.GradientStream(n, d, seed=6, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(2):
+            pair.sgd_step(grads.next(), 0.1)
+            v = pair.ref.X - pair.ref.Xhat
+            det = pair.gossip_step()
+            pair.check(det, tag="%s step %d" % (name, t))
+            for i in range(n):
+                m = pair.gpu.last_message(i)
+                pair.gpu.sync()
+                if "idx" in m:
+                    idx, val = m["idx"].cpu().numpy(), m["val"].cpu().numpy()
+                    order = np.argsort(idx, kind="stable")
+                    assert np.array_equal(idx[order], det["sel"][i])
+                    want = v[i][det["sel"][i]]
+                    if q.get("randk_rescale"):
+                        want = np.float32(d / q["k"]) * want
+                    assert np.array_equal(val[order], want)
+                    continue
+                codes = det["codes"][i]
+                bits = m["bits"].cpu().numpy().view(np.uint32)
+                pad = (-d) % 32
+                sign = np.packbits(np.pad(codes < 0, (0, pad)), bitorder="little").view(np.uint32)
+                assert np.array_equal(bits[0], sign)
+                if q["compressor"] == binding.Q_QSGD:
+                    mb = max(1, (q["levels"] - 1).bit_length())
+                    mag = np.minimum(np.abs(codes), (1 << mb) - 1)
+                    for p in range(mb):
+                        plane = np.packbits(np.pad(((mag >> p) & 1).astype(bool), (0, pad)), bitorder="little")
+                        assert np.array_equal(bits[1 + p], plane.view(np.uint32))
+                    assert np.float32(m["scale"]) == np.float32(det["scal"][i][3])
+                else:
+                    assert np.float32(m["scale"]) == np.float32(det["scal"][i][1])
+        assert binding.lib().choco_last_message(pair.gpu.ctx, n, None, None, None, None) == binding.E_INVAL
+    finally:
+        pair.close()
 
 
 LAYERED = [

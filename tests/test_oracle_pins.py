@@ -941,6 +941,27 @@ def test_message_layouts_bit_by_bit():
     assert np.array_equal(msg.view(np.float32), det["q"][det["sel"]])
 
 
+def test_at_most_four_entries_can_reach_the_top_level():
+    # floor(|v| r + u) = s needs |v| r >= s - u > s - 1, i.e. |v| / ||v|| > 1 - 1/s >= 1/2 for s >= 2
+    # (s = 1 has a magnitude bit for its top level): the squares of four shares of one half are
+    # the whole norm, so a fifth cannot exist.  Vectors built to come close: 1 to 5 equal large
+    # entries over a small floor; the message's four index slots always suffice.
+    rng = np.random.default_rng(12)
+    worst = 0
+    for s in (2, 4, 16):
+        for big in (1, 2, 3, 4, 5):
+            for rep in range(60):
+                d = int(rng.integers(big, 40))
+                v = (rng.standard_normal(d) * 1e-6).astype(np.float32)
+                v[rng.choice(d, size=big, replace=False)] = np.float32(rng.choice([-3.0, 3.0]))
+                out = ref.compress(ref.QSGD, v, levels=s, qsgd_biased=int(rep & 1), seed=rep, t=rep, worker=big)
+                top = int((np.abs(out["codes"]) == s).sum())
+                worst = max(worst, top)
+                assert top <= 4
+                ref.pack_message(ref.QSGD, v, levels=s, qsgd_biased=int(rep & 1), seed=rep, t=rep, worker=big)
+    assert worst >= 1      # the construction does reach the top level
+
+
 def test_gsgd_level_s_travels_through_the_index_slots():
     # one entry holds almost the whole norm: floor(s |v| / ||v|| + u) reaches s, which the
     # magnitude bits (0 .. s-1) cannot hold
