@@ -555,12 +555,12 @@ int join_lookahead(choco_ctx* ctx) {
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
   KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_GATHER_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
+  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_GATHER_VALUES, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
   "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_gather_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
+  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_gather_values", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
   "k_layer_compress", "k_layer_compress_sgd", "k_layer_stat", "k_layer_stat_sgd", "k_layer_finalise", "k_wire",
   "k_zero_words"};
@@ -866,10 +866,11 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     if (rc != CHOCO_OK) return rc;
   }
   // messages: neighbour sums first (they recompute q from x - xhat), then xhat.  random_a's
-  // selection knows no values: the first kernel that forms q anyway leaves them in the list
+  // selection knows no values: gathered for the scatter, else listed by the kernel that forms q
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-  A.scatter_values = (COMP == Q_RANDK && incremental) ? 1 : 0;
   A.update_values = (COMP == Q_RANDK && !incremental) ? 1 : 0;
+  if (COMP == Q_RANDK && incremental)
+    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (incremental)
     LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256),
            0, A);
@@ -1078,7 +1079,8 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     if (rc != CHOCO_OK) return rc;
   }
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-  A.scatter_values = COMP == Q_RANDK ? 1 : 0;   // random_a: the scatter forms the kept values and lists them
+  if (COMP == Q_RANDK)
+    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
   LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first) {

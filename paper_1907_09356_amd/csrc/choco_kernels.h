@@ -160,10 +160,10 @@ struct Args {
   uint32_t* bitmap;    // n x bitmap_words: the same as bits, used instead when a row's bitmap fits in LDS
   int64_t bitmap_words;  // 0: use the bit map in global memory (keptmap)
   int32_t fold_xhat;     // the final mix also applies xhat += q (bitmap rows, compress-then-mix)
-  // random_a: nobody knows the kept values when the selection is made (it reads no state).  They are
-  // written to sel_val by the first kernel that forms q anyway:
-  int32_t scatter_values;  // k_scatter_s computes q_j[e] = x_j[e] - xhat_j[e] itself and its self-loop thread stores it
-  int32_t update_values;   // k_xhat_update computes and stores it (no scatter ran: direct mix)
+  // random_a: nobody knows the kept values when the selection is made (it reads no state).  With
+  // incremental sums k_sel_values gathers them for the scatter; otherwise they are listed by the
+  // kernel that forms q anyway:
+  int32_t update_values;   // k_xhat_update computes q_j[e] = x_j[e] - xhat_j[e] itself and stores it (direct mix)
   float* Qv;               // or, where one fused pass applies the update and the mix (direct form), to entry
                            // (j, e) of this n x ld array, from which the list is gathered on request; else null
   int32_t randk_rescale;
@@ -1385,20 +1385,33 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
 // The exact select on the candidates of one worker (device functions shared by the
 // one-block and the multi-block kernels below).
 // ---------------------------------------------------------------------------
-// Lengths and prefix offsets of the candidate sub-lists of worker i (thread 0 writes them to
-// LDS; callers synchronise afterwards).  *good: the list holds the k largest entries.
-__device__ __forceinline__ void list_layout(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
-                                            uint32_t* total_out, uint32_t* good_out) {
-  uint32_t total = 0;
-  for (int s = 0; s < kSegs; ++s) {
-    const uint32_t c = ctl->seg_count[s];
-    lens[s] = c < A.seg_cap ? c : A.seg_cap;
-    pre[s] = total;
-    total += lens[s];
+// Lengths and prefix offsets of the candidate sub-lists of worker i, written to LDS (callers
+// synchronise afterwards); *good: the list holds the k largest entries.
+// By the first wave of a block (threads 0..63 call it): one sub-list per lane, prefix offsets by
+// a wave scan - one round trip to memory instead of a thread's 32 loads in turn.
+__device__ __forceinline__ void list_layout_wave(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
+                                                 uint32_t* total_out, uint32_t* good_out) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t raw = lane < kSegs ? ctl->seg_count[lane] : 0u;
+  const uint32_t len = raw < A.seg_cap ? raw : A.seg_cap;
+  uint32_t incl = len;
+  unsigned long long rawsum = raw;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
+    rawsum += __shfl_xor(rawsum, off, 64);
   }
-  pre[kSegs] = total;
-  *total_out = total;
-  *good_out = list_is_good(ctl, A) ? 1u : 0u;
+  if (lane < kSegs) {
+    lens[lane] = len;
+    pre[lane] = incl - len;
+  }
+  if (lane == kSegs - 1) {
+    pre[kSegs] = incl;
+    *total_out = incl;
+  }
+  const bool fits = __ballot(raw > A.seg_cap) == 0ull;
+  if (lane == 0) *good_out = (fits && rawsum >= (unsigned long long)A.k) ? 1u : 0u;
 }
 
 // Entry at flat position f of the concatenated sub-lists (pre = prefix offsets in LDS).
@@ -1674,8 +1687,8 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
     s_need = (uint32_t)A.k;
     s_emit = 0;
     s_small = 0;
-    list_layout(A, ctl, lens, pre, &s_total, &s_good);
   }
+  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good);
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
@@ -1786,7 +1799,7 @@ __global__ __launch_bounds__(1024) void k_sel_hist_parts(Args A) {
   const int i = blockIdx.y;
   const WorkerCtl* ctl = A.ctl + i;
   for (int b = threadIdx.x; b < kBins; b += 1024) h[b] = 0;
-  if (threadIdx.x == 0) list_layout(A, ctl, lens, pre, &s_total, &s_good);
+  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good);
   __syncthreads();
   if (!s_good) return;
   uint32_t lo, hi;
@@ -1829,7 +1842,7 @@ __global__ __launch_bounds__(1024) void k_sel_emit_parts(Args A) {
   __shared__ uint32_t s_total, s_good, s_digit, s_above, s_count, s_base;
   const int i = blockIdx.y;
   WorkerCtl* ctl = A.ctl + i;
-  if (threadIdx.x == 0) list_layout(A, ctl, lens, pre, &s_total, &s_good);
+  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good);
   __syncthreads();
   if (!s_good) return;
   sum_hist_parts(A, i, h);
@@ -1904,8 +1917,8 @@ __global__ __launch_bounds__(1024) void k_sel_finish(Args A) {
     s_prefix = 0;
     s_need = (uint32_t)A.k;
     s_emit = 0;
-    list_layout(A, ctl, lens, pre, &s_total, &s_good);
   }
+  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good);
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
@@ -1962,15 +1975,24 @@ __device__ __forceinline__ float fresh_value(const Args& A, int j, int e) {
   return q;
 }
 
+// random_a with incremental neighbour sums: the kept values are gathered once the indices are
+// known (top_a carries the value in the candidate entry instead).  A launch of its own: n k
+// gathers spread over all CUs; inside the scatter, where every one of the nnz k threads would
+// gather its own value, they cost more than this launch (n = 64 ring, 65 layers: scatter 47
+// against 21 + 12.5 us).  grid (ceil(k/256), n)
+__global__ __launch_bounds__(256) void k_sel_values(Args A) {
+  const int j = blockIdx.y;
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= A.k) return;
+  A.sel_val[(int64_t)j * A.k + m] = fresh_value(A, j, A.sel_idx[(int64_t)j * A.k + m]);
+}
+
 // S_i[e] += sum_p w_p q_j[e] over the neighbours j = col[p] that kept entry e,
 // in CSR order (the incremental neighbour sums).  One thread per (i, p, kept
 // entry m of j); the thread of the FIRST neighbour in row i that kept e owns
 // the whole chain for (i, e), so each S entry has one writer and the order of
 // the additions is fixed.  Must run before xhat is updated (values of other
-// neighbours are recomputed as x - xhat).  With scatter_values (random_a, whose
-// selection knows no values) the thread's own value is recomputed too, and the
-// thread of the self-loop (every row has one) leaves it in the list for the
-// update of xhat and for read-back.  grid (ceil(k/256), maxdeg, n)
+// neighbours are recomputed as x - xhat).  grid (ceil(k/256), maxdeg, n)
 __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   const int i = blockIdx.z;
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1979,18 +2001,11 @@ __global__ __launch_bounds__(256) void k_scatter_s(Args A) {
   if (m >= A.k || p >= pend) return;
   const int j = A.col[p];
   const int e = A.sel_idx[(int64_t)j * A.k + m];
-  float mine;
-  if (A.scatter_values) {
-    mine = fresh_value(A, j, e);
-    if (j == i) A.sel_val[(int64_t)j * A.k + m] = mine;
-  } else {
-    mine = A.sel_val[(int64_t)j * A.k + m];
-  }
   for (int p2 = pbeg; p2 < p; ++p2)
     if (was_kept(A, A.col[p2], e)) return;
   float* s = A.S + (int64_t)i * A.ld + e;
   float acc = *s;
-  acc = acc + A.w[p] * mine;
+  acc = acc + A.w[p] * A.sel_val[(int64_t)j * A.k + m];
   for (int p2 = p + 1; p2 < pend; ++p2) {
     const int j2 = A.col[p2];
     if (was_kept(A, j2, e)) acc = acc + A.w[p2] * fresh_value(A, j2, e);
