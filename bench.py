@@ -324,10 +324,10 @@ def run_gpu(w, steps, warmup, profile=True, fused=True, mix_form=None, order=Non
             if bpe is not None and not (w["comp"] == "randk" and name == "k_sel_compact"):
                 per_launch = bpe * elems
                 if "layers" in w and (name.startswith("k_layer_compress") or name.startswith("k_sel_compact")):
-                    # layers above 40,960 entries go through k_sel_compact, the others through
+                    # layers above 10,240 entries go through k_sel_compact, the others through
                     # k_layer_compress; the launches of each share its part of one pass over the rows
                     lengths = layer_table_of(w)[1]
-                    long_part = float(lengths[lengths > 40960].sum()) / float(lengths.sum())
+                    long_part = float(lengths[lengths > 10240].sum()) / float(lengths.sum())
                     per_launch *= long_part if name.startswith("k_sel_compact") else 1.0 - long_part
                     per_launch /= entry["launches_per_step"]
                 entry["alg_bytes_per_launch"] = per_launch
@@ -560,8 +560,8 @@ def main():
     copy_ref = calibration_copy(torch)
     from paper_1907_09356_amd import binding as B
     mix_form = {"auto": None, "incremental": B.MIX_INCREMENTAL_S, "direct": B.MIX_DIRECT}[args.mix]
-    if w["comp"] in ("sign", "qsgd") or "layers" in w:
-        mix_form = None   # dense operators always use the direct form; layer tables take the library's choice
+    if w["comp"] in ("sign", "qsgd"):
+        mix_form = None   # dense operators always use the direct form
     order = (B.ORDER_MIX_THEN_COMPRESS if args.order == "mix_then_compress"
              else B.ORDER_COMPRESS_THEN_MIX)
     res = run_gpu(w, args.steps, args.warmup, fused=not args.unfused, mix_form=mix_form, order=order,

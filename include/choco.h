@@ -105,8 +105,8 @@ typedef struct {
      fused local update; any other table takes per-entry layer look-ups and the local update as a
      pass of its own (same results).  Layers may have any length; for
      TOPK and RANDK one workgroup selects a layer of up to CHOCO_MAX_LAYER_LEN entries out
-     of its registers and longer layers take the whole-vector select one after the other
-     (they cost workspace for its candidate lists).  IDENTITY and a non-default mix_form
+     of its registers and longer layers take the whole-vector select, in launches that they
+     share (they cost workspace for its candidate lists, a set per such layer).  IDENTITY and a non-default mix_form
      are CHOCO_E_UNSUPPORTED with layers.  layer_k_host may be NULL for SIGN and QSGD.     */
   int32_t nlayers;
   const int64_t *layer_start_host;
@@ -114,7 +114,7 @@ typedef struct {
   const int64_t *layer_k_host;
 } choco_config;
 
-#define CHOCO_MAX_LAYER_LEN 40960
+#define CHOCO_MAX_LAYER_LEN 10240
 #define CHOCO_MAX_D (((int64_t)1 << 31) - ((int64_t)1 << 19)) /* rows are indexed in 32 bits with some headroom */
 
 /* Bytes of device workspace choco_init needs for this configuration (Xhat, S, the CSR

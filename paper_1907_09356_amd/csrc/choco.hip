@@ -38,6 +38,8 @@ struct SelectPlan {
 struct LongLayer {
   int32_t start, len, k, sel_base, id;
   SelectPlan plan;
+  LongSel sel;      // what the kernels need of it (filled by choco_init)
+  bool batched;     // its pass and its select share a launch with those of the other such layers
 };
 
 // Partial sums of choco_metrics_noalloc: the same three doubles per block that choco_metrics
@@ -82,11 +84,14 @@ struct choco_ctx {
   bool nt;                // non-temporal loads/stores: the state does not fit in cache anyway
   int nlayers;            // > 0: the operator is applied layer by layer
   bool layers_generic;    // ... on a table that is not aligned (see layers_aligned): no pass carries the local update
-  int nlarge, nmid;       // layers (by falling length, after the long ones) that take a 1024- / a 256-thread workgroup
+  int nmid, nsmall;       // layers (by falling length, after the long ones) that take a 1024- / a 256-thread workgroup
   SelectPlan plan;        // whole-vector top_a / random_a
   std::vector<LongLayer> long_layers;   // top_a / random_a layer by layer: layers above CHOCO_MAX_LAYER_LEN
+  const LongSel* long_tab;   // device copy of the batched ones' LongSel, in the order of long_layers
+  int nbatched;           // how many those are, and the 4-vectors of the longest of them
+  int32_t batched_nvec;
   bool long_silent;       // one of them keeps nothing (its pass cannot carry the local update)
-  bool overlap_long;      // top_a, several long layers: a layer's select runs on the second stream beside the next layer's pass
+  bool overlap_long;      // top_a, several long layers with launches of their own: a layer's select runs on the second stream beside the next layer's pass
   size_t set_hist16, set_cand, set_hist_parts, set_small_list;   // bytes from one long layer's select scratch to the next
   bool long_rows;         // d > 2^21: four 4-vectors per thread in the streaming kernels
   uint64_t t;             // step counter
@@ -118,7 +123,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t xhat, s, row_ptr, col, w, ctl, chunk_sums, group_sums, hist16, cand, hist_parts, small_list, sel_idx, sel_val, keptmap, bitmap,
-      layers, layer_work, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
+      layers, layer_work, long_tab, layer_guess, layer_scal, layer_groups, layer_group_first, layer_group_sums, layer_scale,
       chunk_layer, planes, ovf_ring, ovf_pos, wire_rank, wire_word_off, wire_plane_off, sel_idx2, bitmap2, keptmap2, layer_scal2, qv, mpart, mout, total;
   int64_t wire_words, wire_plane_words;   // layer by layer: words of a worker's message / of one bit plane
   int32_t ngroup_items;
@@ -137,12 +142,14 @@ bool is_sparse(int compressor) { return compressor == CHOCO_Q_TOPK || compressor
 // (n <= kMaxTileRows) - one fused pass then applies the sparse update of xhat and the mix, no S
 // array, no scatter: measured faster at every size (n = 64, d = 270 k: 0.101 against 0.118 ms
 // before the passes were fused; n = 8, d = 28 M: 1.09 against 1.27 ms).  The incremental
-// neighbour sums remain for more workers than the tile holds, for layer tables, and for top_a in
-// the printed order, where mix and candidate pass are one 20 B/entry pass over S.
+// neighbour sums remain for more workers than the tile holds, for top_a in the printed order,
+// where mix and candidate pass are one 20 B/entry pass over S, and for layer tables in the
+// printed order (layer by layer only the fused pass is built for the direct form).
 int resolve_mix_form(const choco_config& c) {
   if (c.mix_form != CHOCO_MIX_AUTO) return c.mix_form;
   if (!is_sparse(c.compressor)) return CHOCO_MIX_DIRECT;
-  if (c.nlayers > 0 || c.n > kMaxTileRows) return CHOCO_MIX_INCREMENTAL_S;
+  if (c.n > kMaxTileRows) return CHOCO_MIX_INCREMENTAL_S;
+  if (c.nlayers > 0 && c.order == CHOCO_ORDER_MIX_THEN_COMPRESS) return CHOCO_MIX_INCREMENTAL_S;
   if (c.compressor == CHOCO_Q_TOPK && c.order == CHOCO_ORDER_MIX_THEN_COMPRESS) return CHOCO_MIX_INCREMENTAL_S;
   return CHOCO_MIX_DIRECT;
 }
@@ -152,7 +159,7 @@ int64_t resolve_ld(const choco_config& c) { return c.ld == 0 ? (c.d + 3) / 4 * 4
 // top_a / random_a, compress-then-mix order, direct form with the LDS tile: xhat += q is applied
 // by the mix pass itself (k_tile_mix<.., SPARSE>), off the kept-entry bits.
 bool fused_sparse_apply(const choco_config& c) {
-  return is_sparse(c.compressor) && c.nlayers == 0 && c.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
+  return is_sparse(c.compressor) && c.order == CHOCO_ORDER_COMPRESS_THEN_MIX &&
          resolve_mix_form(c) == CHOCO_MIX_DIRECT && c.n <= kMaxTileRows;
 }
 
@@ -184,8 +191,11 @@ int check_layers(const choco_config* c) {
     }
   }
   if (sparse && ktot < 1) return CHOCO_E_INVAL;
-  if (c->compressor == CHOCO_Q_IDENTITY || c->mix_form != CHOCO_MIX_AUTO)
-    return CHOCO_E_UNSUPPORTED;
+  if (c->compressor == CHOCO_Q_IDENTITY) return CHOCO_E_UNSUPPORTED;
+  // sign / gsgd layer by layer: the direct form only (what AUTO gives them); top_a / random_a:
+  // incremental sums, or the direct form where its fused pass exists
+  if (!sparse && c->mix_form != CHOCO_MIX_AUTO) return CHOCO_E_UNSUPPORTED;
+  if (sparse && c->mix_form == CHOCO_MIX_DIRECT && !fused_sparse_apply(*c)) return CHOCO_E_UNSUPPORTED;
   return CHOCO_OK;
 }
 
@@ -305,7 +315,7 @@ std::vector<LongLayer> long_layers_of(const choco_config& c) {
   int64_t sel_base = 0;
   for (int32_t l = 0; l < c.nlayers; ++l) {
     const int64_t len = c.layer_len_host[l], k = c.layer_k_host[l];
-    if (len + (c.layer_start_host[l] & 3) > kMaxLayerLen) {   // (with the entries before it in its first 4-vector)
+    if (len + (c.layer_start_host[l] & 3) > kMidLayerLen) {   // (with the entries before it in its first 4-vector)
       LongLayer B{};
       B.start = (int32_t)c.layer_start_host[l];
       B.len = (int32_t)len;
@@ -313,6 +323,8 @@ std::vector<LongLayer> long_layers_of(const choco_config& c) {
       B.sel_base = (int32_t)sel_base;
       B.id = l;
       B.plan = plan_select(c.compressor, len, std::max<int64_t>(k, 1));
+      // one block per worker finishes the select, no histogram passes: such layers share launches
+      B.batched = k > 0 && !B.plan.multipart && !B.plan.fallback_chain;
       out.push_back(B);
     }
     sel_base += k;
@@ -387,10 +399,13 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   }
   L.cand_cap = (uint32_t)cap;
   L.seg_cap = (uint32_t)seg_cap;
-  // top_a with several long layers: a set of select scratch per long layer, so that one layer's
-  // select can run (on the library's second stream) beside the next layer's pass over the rows
-  L.select_sets = (c.compressor == CHOCO_Q_TOPK && longs.size() >= 2) ? (int32_t)longs.size() : 1;
-  L.hist16_bytes = align_up(guessed ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
+  // a set of select scratch per long layer: the layers that share launches are selected at the
+  // same time, and the select of one that has launches of its own can run (top_a, on the
+  // library's second stream) beside the next layer's pass over the rows
+  L.select_sets = std::max<int32_t>(1, (int32_t)longs.size());
+  bool chain = !layered;   // the histogram passes: long rows, whole-vector rows of any length
+  for (const SelectPlan& P : plans) chain = chain || P.fallback_chain;
+  L.hist16_bytes = align_up(guessed && chain ? (size_t)c.n * kBins16 * sizeof(uint32_t) : 0);
   L.cand_bytes = align_up(guessed ? (size_t)c.n * kSegs * (size_t)seg_cap * sizeof(uint2) : 0);
   L.hist16 = take(L.hist16_bytes * (size_t)L.select_sets);
   L.cand = take(L.cand_bytes * (size_t)L.select_sets);
@@ -416,6 +431,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   L.layer_scal2 = take(ahead && layered ? (size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double) : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
+  L.long_tab = take(longs.size() * sizeof(LongSel));
   L.layer_guess = take((size_t)c.n * (size_t)c.nlayers * sizeof(uint32_t));
   L.layer_scal = take((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
   // sign / gsgd layer by layer: work items of the norm pass (groups of 16 chunks of one layer)
@@ -939,30 +955,12 @@ int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
 // launches of the whole-vector path on an argument block that points at the layer's piece of
 // the rows (and, where the layers' selects overlap, at the layer's own select scratch).
 Args long_layer_args(const choco_ctx* ctx, const Args& src, int which) {
-  const LongLayer& B = ctx->long_layers[(size_t)which];
-  Args R = src;
-  // the piece of the rows from the 4-vector boundary at or below the layer's first entry; the
-  // entries before the layer in that 4-vector do not take part (e_lo)
-  const int32_t head = B.start & 3, base = B.start - head;
-  R.X += base;
-  R.Xhat += base;
-  if (R.G) R.G += base;
-  if (R.M) R.M += base;
-  R.d = B.len + head;
-  R.e_lo = head;
-  R.k = B.k;
-  R.ctl = src.ctl + (int64_t)which * src.n;
-  R.sel_idx += B.sel_base;     // sel_stride stays the worker's whole list
-  R.sel_val += B.sel_base;
-  R.idx_base = base;
-  R.vec_base = (uint32_t)base >> 2;
-  apply_plan(R, B.plan);
-  if (ctx->overlap_long) {
-    R.hist16 = (uint32_t*)((char*)src.hist16 + (size_t)which * ctx->set_hist16);
-    R.cand = (uint2*)((char*)src.cand + (size_t)which * ctx->set_cand);
-    R.hist_parts = (uint32_t*)((char*)src.hist_parts + (size_t)which * ctx->set_hist_parts);
-    R.small_list = (uint2*)((char*)src.small_list + (size_t)which * ctx->set_small_list);
-  }
+  // the piece of the rows from the 4-vector boundary at or below the layer's first entry (the
+  // entries before the layer in that 4-vector do not take part), the layer's own select scratch
+  Args R = long_view(src, ctx->long_layers[(size_t)which].sel);
+  R.hist16 = (uint32_t*)((char*)src.hist16 + (size_t)which * ctx->set_hist16);
+  R.hist_parts = (uint32_t*)((char*)src.hist_parts + (size_t)which * ctx->set_hist_parts);
+  R.small_list = (uint2*)((char*)src.small_list + (size_t)which * ctx->set_small_list);
   return R;
 }
 
@@ -970,7 +968,7 @@ Args long_layer_args(const choco_ctx* ctx, const Args& src, int which) {
 template <int COMP, bool NT>
 void long_layer_pass(choco_ctx* ctx, const Args& C, int which) {
   const LongLayer& B = ctx->long_layers[(size_t)which];
-  if (B.k == 0) return;
+  if (B.k == 0 || B.batched) return;
   const Args Cl = long_layer_args(ctx, C, which);
   const int kid_compact = Cl.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
   const int32_t nvec = (B.len + 3) >> 2;
@@ -985,7 +983,7 @@ void long_layer_pass(choco_ctx* ctx, const Args& C, int which) {
 template <int COMP, bool NT>
 void long_layer_select(choco_ctx* ctx, const Args& A, int which) {
   const LongLayer& B = ctx->long_layers[(size_t)which];
-  if (B.k == 0) return;
+  if (B.k == 0 || B.batched) return;
   const Args Al = long_layer_args(ctx, A, which);
   if (B.plan.fallback_chain) {
     const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
@@ -1021,16 +1019,25 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   Args C = (x_touched || COMP == Q_RANDK) ? A : F;
   if (COMP == Q_RANDK) C.G = nullptr;
   const int nlong = (int)ctx->long_layers.size();   // first in the work list, not for the layer kernel
-  const int nlarge = ctx->nlarge, nmid = ctx->nmid, nsmall = A.nlayers - nlong - nlarge - nmid;
-  const int one_launch_blocks = nlarge + nmid + (nsmall + 15) / 16;
-  // few workers: every layer above a wave's reach gets a 1024-thread workgroup and the chip
-  // still is not full, so one launch does (a launch costs more than idle threads)
-  const bool one_launch = (int64_t)one_launch_blocks * A.n <= 256;
-  // the long layers one after the other, then the layer kernel(s) for the layers within its reach
+  const int nmid = ctx->nmid, nsmall = ctx->nsmall, ntiny = A.nlayers - nlong - nmid - nsmall;
+  const int wide_blocks = nmid + nsmall + (ntiny + 15) / 16;
+  // few workers: with a 1024-thread workgroup for every layer above a wave's reach (and sixteen
+  // waves' worth of smaller layers in each of the others) the chip still is not full, and one
+  // launch does
+  const bool wide = (int64_t)wide_blocks * A.n <= 256;
+  // the long layers (those that share launches first, then the others one after the other), then
+  // the layer kernel for the layers within its reach
   auto select_layers = [&](const Args& S) -> int {
     Args Q = S;
     Q.G = nullptr;
     Q.M = nullptr;
+    if (ctx->nbatched > 0) {
+      const dim3 cgrid((unsigned)((ctx->batched_nvec + 511) / 512), (unsigned)A.n, (unsigned)ctx->nbatched);
+      LAUNCH(ctx, S.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT, (k_sel_compact<COMP, false, NT, 2, true>), cgrid,
+             dim3(256), 0, S);
+      LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP, true>), dim3((unsigned)A.n, (unsigned)ctx->nbatched), dim3(1024),
+             0, Q);
+    }
     // top_a with several long layers: a layer's select (a few small launches that wait on
     // memory) goes to the second stream and runs beside the next layer's pass over the rows
     const bool overlap = COMP == Q_TOPK && ctx->overlap_long && !ctx->profiling && ctx->launch_stream == ctx->stream;
@@ -1045,17 +1052,17 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
       ctx->launch_stream = overlap ? ctx->stream : ctx->launch_stream;
     }
     const int kid = S.G ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
-    if (one_launch) {
-      if (one_launch_blocks > 0)
-        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)one_launch_blocks, (unsigned)A.n),
-               dim3(1024), 0, S, nlong, nlarge + nmid);
+    if (wide) {
+      if (wide_blocks > 0)
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)wide_blocks, (unsigned)A.n), dim3(1024), 0,
+               S, nlong, nmid + nsmall);
     } else {
-      if (nlarge > 0)
-        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)nlarge, (unsigned)A.n), dim3(1024), 0, S,
-               nlong, nlarge);
-      if (nmid + nsmall > 0)
-        LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nmid + (nsmall + 3) / 4), (unsigned)A.n),
-               dim3(256), 0, S, nlong + nlarge, nmid);
+      if (nmid > 0)
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)nmid, (unsigned)A.n), dim3(1024), 0, S,
+               nlong, nmid);
+      if (nsmall + ntiny > 0)
+        LAUNCH(ctx, kid, (k_layer_compress<COMP, 256, NT>), dim3((unsigned)(nsmall + (ntiny + 3) / 4), (unsigned)A.n),
+               dim3(256), 0, S, nlong + nmid, nsmall);
     }
     if (overlap && nlong > 0) {   // the caller's stream goes on when the last select is done
       HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
@@ -1078,17 +1085,24 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     const int rc = look_ahead_mark(ctx);
     if (rc != CHOCO_OK) return rc;
   }
+  // direct form (compress-then-mix only): one pass applies xhat += q off the kept-entry bits and
+  // mixes; else the messages go into the neighbour sums, then into xhat, and the mix reads S
+  const bool fused_apply = ctx->fused_sparse_apply;
   const unsigned kblocks = (unsigned)((A.k + 255) / 256);
-  if (COMP == Q_RANDK)
-    LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
-  LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
-  LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  if (!fused_apply) {
+    if (COMP == Q_RANDK)
+      LAUNCH(ctx, KID_SEL_VALUES, k_sel_values, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+    LAUNCH(ctx, KID_SCATTER_S, k_scatter_s, dim3(kblocks, (unsigned)ctx->maxdeg, (unsigned)A.n), dim3(256), 0, A);
+    LAUNCH(ctx, KID_XHAT_UPDATE, k_xhat_update, dim3(kblocks, (unsigned)A.n), dim3(256), 0, A);
+  }
   if (!mix_first) {
     const bool last_carries = F.deferred_sgd != 0;
     Args L = A;
     if (last_carries) L.G = F.G;
-    launch_mix_incremental<NT>(ctx, L, last_carries);
+    if (fused_apply) launch_tile_mix<Q_NONE, NT, true>(ctx, L, last_carries);
+    else launch_mix_incremental<NT>(ctx, L, last_carries);
   }
+  ctx->values_in_qv = fused_apply && COMP == Q_RANDK;
   LAUNCH_CHECK(ctx);
   if (ahead) {   // the next step's masks, enqueued after this step's own kernels (see look_ahead_mark)
     const Args P = look_ahead_args(ctx, A);
@@ -1397,7 +1411,40 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
   ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
   ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
-  ctx->overlap_long = L.select_sets > 1;
+  // what the kernels need of each long layer; those that share launches go into a device table
+  std::vector<LongSel> long_tab;
+  ctx->nbatched = 0;
+  ctx->batched_nvec = 0;
+  int nsolo = 0;
+  for (size_t b = 0; b < ctx->long_layers.size(); ++b) {
+    LongLayer& B = ctx->long_layers[b];
+    LongSel& Z = B.sel;
+    Z.e_lo = B.start & 3;
+    Z.base = B.start - Z.e_lo;
+    Z.d = B.len + Z.e_lo;
+    Z.k = B.k;
+    Z.sel_base = B.sel_base;
+    Z.set = (int32_t)b;
+    Z.cand_cap = B.plan.cand_cap;
+    Z.seg_cap = B.plan.seg_cap;
+    Z.extra = B.plan.extra;
+    Z.want = B.plan.want;
+    Z.delta0 = B.plan.delta0;
+    Z.sample_stride = B.plan.sample_stride;
+    Z.sample_need = B.plan.sample_need;
+    Z.set_cand = (int64_t)(L.cand_bytes / sizeof(uint2));
+    if (B.batched && long_tab.size() < 65535) {   // (a grid has that many layers at most)
+      long_tab.push_back(Z);
+      ctx->batched_nvec = std::max(ctx->batched_nvec, (Z.d + 3) >> 2);
+    } else {
+      B.batched = false;
+      nsolo += B.k > 0 ? 1 : 0;
+    }
+  }
+  ctx->nbatched = (int)long_tab.size();
+  ctx->long_tab = (const LongSel*)(base + L.long_tab);
+  A.long_tab = ctx->long_tab;
+  ctx->overlap_long = cfg->compressor == CHOCO_Q_TOPK && nsolo >= 2;
   ctx->set_hist16 = L.hist16_bytes;
   ctx->set_cand = L.cand_bytes;
   ctx->set_hist_parts = L.hist_parts_bytes;
@@ -1453,12 +1500,12 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     work = layers;
     std::stable_sort(work.begin(), work.end(),
                      [](const LayerDesc& a, const LayerDesc& b) { return a.len + a.head > b.len + b.head; });
-    ctx->nlarge = ctx->nmid = 0;
+    ctx->nmid = ctx->nsmall = 0;
     for (const LayerDesc& D : work) {
       const int32_t span = D.len + D.head;   // what the layer kernel holds in registers
-      if (ctx->sparse && span > kMaxLayerLen) continue;   // (long layers: first in the list, skipped by the layer kernel)
-      if (span > kMidLayerLen) ctx->nlarge += 1;
-      else if (span > kWaveLayerLen) ctx->nmid += 1;
+      // (long layers: first in the list, skipped by the layer kernel)
+      if (span <= kMidLayerLen && span > kSmallLayerLen) ctx->nmid += 1;
+      else if (span <= kSmallLayerLen && span > kWaveLayerLen) ctx->nsmall += 1;
     }
   }
   std::vector<LayerGroup> groups;
@@ -1543,6 +1590,9 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
                        ctx->stream);
   if (e == hipSuccess && cfg->nlayers > 0)
     e = hipMemcpyAsync(base + L.layer_work, work.data(), work.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
+                       ctx->stream);
+  if (e == hipSuccess && !long_tab.empty())
+    e = hipMemcpyAsync(base + L.long_tab, long_tab.data(), long_tab.size() * sizeof(LongSel), hipMemcpyHostToDevice,
                        ctx->stream);
   if (e == hipSuccess && cfg->nlayers > 0)   // no threshold guesses yet
     e = hipMemsetAsync(base + L.layer_guess, 0xFF, (size_t)cfg->n * (size_t)cfg->nlayers * sizeof(uint32_t),

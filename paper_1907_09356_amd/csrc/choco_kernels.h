@@ -92,6 +92,19 @@ struct LayerGroup {
   int32_t pad;
 };
 
+// One long layer of a layer-wise top_a / random_a configuration (it takes the guessed-threshold
+// select of the whole-row path on its own piece of the rows).
+struct LongSel {
+  int32_t base;        // the 4-vector boundary at or below the layer's first entry
+  int32_t d;           // entries from there to the layer's end
+  int32_t e_lo;        // ... of which the first e_lo lie before the layer
+  int32_t k;           // kept entries
+  int32_t sel_base;    // the layer's first slot in a worker's kept lists
+  int32_t set;         // which control blocks (n per layer) and which set of select scratch
+  uint32_t cand_cap, seg_cap, extra, want, delta0, sample_stride, sample_need;   // see Args
+  int64_t set_cand;    // candidate entries from one set of lists to the next
+};
+
 struct Args {
   int32_t n;
   int32_t d;
@@ -175,6 +188,7 @@ struct Args {
                              // padding (a 4-vector then lies in one layer); 1: any disjoint ascending slices
   int32_t e_lo;              // select kernels: entries of the row below this index do not take part (the head
                              // of a long layer that does not start on a multiple of 4; else 0)
+  const LongSel* long_tab;   // batched select launches: the long layers that one launch covers (grid.z / grid.y)
   const LayerDesc* layer_work;  // the same by falling length: the order the layer kernel takes them in
   uint32_t* layer_guess;     // n x nlayers: top_a threshold key of the last step (all ones: none yet)
   const LayerGroup* layer_groups;   // ngroup_items work items of the layer-wise norm pass, layer after layer
@@ -188,6 +202,35 @@ struct Args {
   // randomness
   uint32_t seed_lo, seed_hi, t_lo, t_hi;
 };
+
+// The select kernels' view of one long layer: the argument block of the whole-row select made
+// to point at the layer's piece of the rows, its slots of the kept lists, its control blocks
+// and its candidate lists.  The host builds the view for a launch that covers one layer; a
+// launch that covers several builds it per workgroup from the table.
+__host__ __device__ __forceinline__ Args long_view(const Args& src, const LongSel& L) {
+  Args R = src;
+  R.X += L.base;
+  R.Xhat += L.base;
+  if (R.G) R.G += L.base;
+  if (R.M) R.M += L.base;
+  R.d = L.d;
+  R.e_lo = L.e_lo;
+  R.k = L.k;
+  R.ctl = src.ctl + (int64_t)L.set * src.n;
+  R.sel_idx += L.sel_base;     // sel_stride stays the worker's whole list
+  R.sel_val += L.sel_base;
+  R.idx_base = L.base;
+  R.vec_base = (uint32_t)L.base >> 2;
+  R.cand_cap = L.cand_cap;
+  R.seg_cap = L.seg_cap;
+  R.extra = L.extra;
+  R.want = L.want;
+  R.delta0 = L.delta0;
+  R.sample_stride = L.sample_stride;
+  R.sample_need = L.sample_need;
+  R.cand = src.cand + (int64_t)L.set * L.set_cand;
+  return R;
+}
 
 // The layer that holds entry e of a row.
 __device__ __forceinline__ int layer_of(const Args& A, int e) {
@@ -928,7 +971,7 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
               for (int c = 0; c < 4; ++c)
                 if ((bits >> c) & 1u) {
                   float qv = xr[q][c] - xh[c];
-                  if (A.randk_rescale) qv = A.randk_scale * qv;
+                  if (A.randk_rescale) qv = randk_scale_at(A, e + c) * qv;
                   xh[c] = xh[c] + qv;
                   if (A.Qv) A.Qv[o + c] = qv;
                 }
@@ -1273,10 +1316,14 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
 // grid (ceil(nvec / (256 * VECS)), n), block 256.  VECS 4-vectors per thread: 4 for long rows
 // (more loads in flight per thread: 6.0 against 5.5 TB/s at d = 28 M), 2 for short ones (twice
 // the blocks and the occupancy: 49 against 57 us at n = 64, d = 270 k).
-template <int COMP, bool DO_MIX, bool NT, int VECS>
-__global__ __launch_bounds__(256) void k_sel_compact(Args A) {
+// BATCH: grid.z counts the long layers of A.long_tab, grid.x covers the longest of them (the
+// workgroups past a shorter layer's end leave at once).
+template <int COMP, bool DO_MIX, bool NT, int VECS, bool BATCH = false>
+__global__ __launch_bounds__(256) void k_sel_compact(Args A0) {
   __shared__ uint2 stage[kStageCap];
   __shared__ uint32_t s_count, s_base;
+  const Args A = BATCH ? long_view(A0, A0.long_tab[blockIdx.z]) : A0;
+  if (BATCH && (int64_t)blockIdx.x * (256 * VECS) >= (int64_t)((A.d + 3) >> 2)) return;
   if (threadIdx.x == 0) s_count = 0;
   __syncthreads();
   compact_chunk<COMP, DO_MIX, NT, true, VECS>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
@@ -1668,8 +1715,10 @@ __device__ void refine_and_emit(const Args& A, int i, const uint32_t* pre, uint3
 // stay in registers between the two sweeps).  If that bin is crowded (ties) the
 // digit-by-digit select runs on the list; if the list itself is not good, on the row.
 // grid n, block 1024, dynamic LDS = the worker's bitmap (short rows) or nothing.
-template <int COMP>
-__global__ __launch_bounds__(1024) void k_sel_refine(Args A) {
+// BATCH: grid (n, long layers of A.long_tab).
+template <int COMP, bool BATCH = false>
+__global__ __launch_bounds__(1024) void k_sel_refine(Args A0) {
+  const Args A = BATCH ? long_view(A0, A0.long_tab[blockIdx.y]) : A0;
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t grp[256];
   __shared__ uint32_t lens[kSegs];

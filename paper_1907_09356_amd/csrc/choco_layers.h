@@ -7,26 +7,33 @@
 // turns them into the layer's scales, and the apply kernels of the whole-row path look the
 // scale of each 4-vector up by its layer.  Any layer length.
 //
-// top_a / random_a: k_layer_compress.  A layer of a worker is selected by one workgroup
-// (1024 threads above 10,240 entries, 256 threads above 2,560) or by one wave (smaller
-// layers, four to a workgroup), with the layer's x - xhat (or its random words) in
-// registers: kLayerVecs 4-vectors per thread, so 1024 threads hold up to 40,960 entries.
+// top_a / random_a: k_layer_compress, for layers of up to kMidLayerLen = 10,240 entries (longer
+// ones stream through the guessed-threshold select of the whole-row path, all of them in one
+// launch of its pass over the rows and one of its exact select).  A layer of a worker is
+// selected by one 1024-thread workgroup (above 3,072 entries), one 256-thread workgroup (above
+// 768) or one wave (smaller layers, four to a workgroup), with the layer's x - xhat (or its
+// random words) in registers: at most kLayerVecs = 3 4-vectors per thread, all loaded at once -
+// a thread's entries are worked through one after the other, so the time of a layer goes with
+// their number (with 10 per thread the 0.27 M model's layers of 2,304 to 9,216 entries took 35 us,
+// whatever the sweeps cost).
 // The exact k-th largest key: a bracket [lo, hi) around a guess (last step's threshold for
 // top_a, the expected order statistic for random_a) is counted in one sweep over the
 // registers; if the k-th key provably lies inside, only the few keys in the bracket are
 // searched (bit by bit, in LDS); otherwise the whole layer is searched bit by bit (31 or 32
-// sweeps with block-wide counts).  Ties on the threshold key go to the lower index.  No
-// histogram, no global atomics.
+// sweeps with block-wide counts).  Ties on the threshold key go to the lower index.  List
+// positions and kept-entry slots are handed out per wave from a ballot (a wave that has a
+// layer to itself counts in a register); no histogram, no global counters.
 #pragma once
 
 #include "choco_kernels.h"
 
 namespace choco {
 
-constexpr int kLayerVecs = 10;
-constexpr int kMaxLayerLen = 1024 * kLayerVecs * 4;
-constexpr int kWaveLayerLen = 64 * kLayerVecs * 4;   // up to here a single wave takes the layer
-constexpr int kMidLayerLen = 256 * kLayerVecs * 4;   // up to here a 256-thread workgroup does
+constexpr int kLayerVecs = 3;
+constexpr int kWaveLayerLen = 64 * kLayerVecs * 4;     // up to here a single wave takes the layer
+constexpr int kSmallLayerLen = 256 * kLayerVecs * 4;   // up to here a 256-thread workgroup does
+constexpr int kMidLayerLen = 10240;                    // ... and up to here a 1024-thread one
+static_assert(kMidLayerLen <= 1024 * kLayerVecs * 4, "a 1024-thread workgroup holds a layer of this class");
 
 // Block total of per-wave counts (each already uniform over its wave).
 template <int THREADS>
@@ -46,6 +53,37 @@ __device__ __forceinline__ uint32_t block_total(uint32_t wave_count, uint32_t* s
 // lanes of the wave for which pred holds (a compare and a scalar bit count, no cross-lane traffic)
 __device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
 
+// Sum of a small per-lane count over the wave (the same in every lane afterwards).
+__device__ __forceinline__ uint32_t wave_count_sum(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Lanes below this one whose bit is set in a ballot mask.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Positions for the lanes of `mask` (not empty, the same in every lane) in a list shared by
+// the THREADS threads of a layer: one wave counts in a register, several waves take a range
+// each with one LDS atomic by the wave's first such lane.
+template <int THREADS>
+__device__ __forceinline__ uint32_t claim(uint64_t mask, uint32_t& running, uint32_t* shared_count) {
+  const uint32_t cnt = (uint32_t)__popcll(mask);
+  uint32_t base;
+  if (THREADS == 64) {
+    base = running;
+    running += cnt;
+  } else {
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    uint32_t got = 0;
+    if ((int)(threadIdx.x & 63) == leader) got = atomicAdd(shared_count, cnt);
+    base = (uint32_t)__builtin_amdgcn_readlane((int)got, leader);
+  }
+  return base + lanes_below(mask);
+}
+
 // Barrier among the THREADS threads that share a layer (one wave needs none: its LDS
 // accesses execute in order; the fence only stops the compiler from reordering them).
 template <int THREADS>
@@ -56,7 +94,7 @@ __device__ __forceinline__ void layer_sync() {
 
 // The LDS of the THREADS threads that share a layer.
 struct LayerShared {
-  uint32_t* cnt;      // 2 x 16 per-wave counts
+  uint32_t* cnt;      // 2 x 16 per-wave counts, then two words for a result one wave hands to the others
   uint32_t* emit;     // kept entries emitted so far
   uint32_t* list_n;   // keys in the bracket
   uint2* list;        // (key, index in the layer) of the keys in the bracket
@@ -67,7 +105,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
                                            const LayerShared sh) {
   static_assert(COMP == Q_TOPK || COMP == Q_RANDK, "sign and gsgd layers go through k_layer_stat");
   constexpr int NW = THREADS / 64;
-  constexpr int kBatch = 4;   // 4-vectors per thread whose loads are in flight together (5 spills)
+  constexpr int kBatch = kLayerVecs;   // 4-vectors per thread whose loads are in flight together
   constexpr int kBatches = (kLayerVecs + kBatch - 1) / kBatch;
   constexpr uint32_t CAP = 2 * THREADS;
   // local index e counts from the 4-vector boundary at or below the layer's first entry: the
@@ -176,9 +214,10 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     }
     int phase = 0;
     uint32_t T = 0, at_or_above = 0xFFFFFFFFu;
+    uint32_t listed_n = 0;   // one wave per layer: the length of its list
     bool found = false;
     if (have) {                                   // uniform
-      uint32_t nhi = 0;
+      uint32_t nhi = 0, listed = 0;
 #pragma unroll
       for (int it = 0; it < kLayerVecs; ++it)
         if (it < nit) {
@@ -187,31 +226,66 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(it, c);
             nhi += wave_count(key >= hi);
-            if (key >= lo && key < hi && inside(4 * m + c)) {
-              const uint32_t pos = atomicAdd(sh.list_n, 1u);
-              if (pos < CAP) sh.list[pos] = make_uint2(key, (uint32_t)(4 * m + c));
+            const bool in = key >= lo && key < hi && inside(4 * m + c);
+            const uint64_t hits = __ballot(in);
+            if (hits != 0) {                      // uniform over the wave
+              const uint32_t pos = claim<THREADS>(hits, listed, sh.list_n);
+              if (in && pos < CAP) sh.list[pos] = make_uint2(key, (uint32_t)(4 * m + c));
             }
           }
         }
       nhi = block_total<THREADS>(nhi, sh.cnt, phase);
       layer_sync<THREADS>();
-      const uint32_t nin = *sh.list_n;
+      const uint32_t nin = THREADS == 64 ? listed : *sh.list_n;
+      listed_n = listed;
       if (nhi < k && k - nhi <= nin && nin <= CAP) {
         // the k-th largest key is the r-th largest of the list: bit by bit on key - lo
         found = true;
         const uint32_t r = k - nhi;
-        const uint32_t rel0 = (uint32_t)tid < nin ? sh.list[tid].x - lo : 0u;
-        const uint32_t rel1 = (uint32_t)tid + THREADS < nin ? sh.list[tid + THREADS].x - lo : 0u;
-        const bool has0 = (uint32_t)tid < nin, has1 = (uint32_t)tid + THREADS < nin;
         const uint32_t span = hi - lo;            // >= 1: the list is not empty
         uint32_t Trel = 0, got = nin;
-        for (int bit = 31 - __clz((int)(span | 1u)); bit >= 0 && got != r; --bit) {
-          const uint32_t cand = Trel | (1u << bit);
-          uint32_t cnt = wave_count(has0 && rel0 >= cand) + wave_count(has1 && rel1 >= cand);
-          cnt = block_total<THREADS>(cnt, sh.cnt, phase);
-          if (cnt >= r) {
-            Trel = cand;
-            got = cnt;
+        constexpr uint32_t SOLO = 512;     // list lengths that one wave searches on its own
+        if (THREADS > 64 && nin <= SOLO) {
+          // several waves: the first one searches the list on its own, eight keys per lane, and
+          // the others wait once (a block-wide count per bit costs a barrier per bit)
+          if (wave == 0) {
+            uint32_t rel[SOLO / 64];
+#pragma unroll
+            for (int j = 0; j < (int)(SOLO / 64); ++j) {
+              const uint32_t p = (uint32_t)(lane + 64 * j);
+              // (keys of the list lie at or above lo; a slot past the list counts for no candidate >= 1)
+              rel[j] = p < nin ? sh.list[p].x - lo + 1u : 0u;
+            }
+            for (int bit = 31 - __clz((int)(span | 1u)); bit >= 0 && got != r; --bit) {
+              const uint32_t cand = Trel | (1u << bit);
+              uint32_t cnt = 0;
+#pragma unroll
+              for (int j = 0; j < (int)(SOLO / 64); ++j) cnt += wave_count(rel[j] > cand);
+              if (cnt >= r) {
+                Trel = cand;
+                got = cnt;
+              }
+            }
+            if (lane == 0) {
+              sh.cnt[32] = Trel;
+              sh.cnt[33] = got;
+            }
+          }
+          __syncthreads();
+          Trel = sh.cnt[32];
+          got = sh.cnt[33];
+        } else {
+          const uint32_t rel0 = (uint32_t)tid < nin ? sh.list[tid].x - lo : 0u;
+          const uint32_t rel1 = (uint32_t)tid + THREADS < nin ? sh.list[tid + THREADS].x - lo : 0u;
+          const bool has0 = (uint32_t)tid < nin, has1 = (uint32_t)tid + THREADS < nin;
+          for (int bit = 31 - __clz((int)(span | 1u)); bit >= 0 && got != r; --bit) {
+            const uint32_t cand = Trel | (1u << bit);
+            uint32_t cnt = wave_count(has0 && rel0 >= cand) + wave_count(has1 && rel1 >= cand);
+            cnt = block_total<THREADS>(cnt, sh.cnt, phase);
+            if (cnt >= r) {
+              Trel = cand;
+              got = cnt;
+            }
           }
         }
         T = lo + Trel;
@@ -241,19 +315,28 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     // entries above the threshold key are all kept; of those equal to it, the first `need`
     // by index (entries outside the layer carry key 0 and are told apart by their index)
     uint32_t above = 0, equals = 0;
+    if (found) {
+      // the threshold lies in the bracket, so every entry that holds it is in the list
+      const uint32_t nin = THREADS == 64 ? listed_n : *sh.list_n;
+      for (uint32_t p = (uint32_t)tid; p < nin; p += THREADS) equals += sh.list[p].x == T ? 1u : 0u;
+      equals = wave_count_sum(equals);
+      equals = block_total<THREADS>(equals, sh.cnt, phase);
+      above = at_or_above - equals;
+    } else {
 #pragma unroll
-    for (int it = 0; it < kLayerVecs; ++it)
-      if (it < nit) {
-        const int m = it * THREADS + tid;
+      for (int it = 0; it < kLayerVecs; ++it)
+        if (it < nit) {
+          const int m = it * THREADS + tid;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const uint32_t key = key_of(it, c);
-          above += wave_count(key > T);
-          equals += wave_count(key == T && inside(4 * m + c));
+          for (int c = 0; c < 4; ++c) {
+            const uint32_t key = key_of(it, c);
+            above += wave_count(key > T);
+            equals += wave_count(key == T && inside(4 * m + c));
+          }
         }
-      }
-    above = block_total<THREADS>(above, sh.cnt, phase);
-    equals = block_total<THREADS>(equals, sh.cnt, phase);
+      above = block_total<THREADS>(above, sh.cnt, phase);
+      equals = block_total<THREADS>(equals, sh.cnt, phase);
+    }
     const uint32_t need = k - above;
     if (tid == 0) {
       scal[0] = (double)T;
@@ -263,6 +346,7 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
     }
     const bool ties = equals > need;   // uniform over the layer's threads
     uint32_t running = 0;              // threshold-key entries in earlier sweeps (index order)
+    uint32_t emitted = 0;              // one wave per layer: kept entries handed out so far
 #pragma unroll
     for (int it = 0; it < kLayerVecs; ++it) {
       if (it < nit) {
@@ -304,9 +388,10 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
             keep = !ties || rank < need;
             ++rank;
           }
-          if (keep) {
-            const uint32_t slot = atomicAdd(sh.emit, 1u);
-            if (slot < k) {   // exactly k entries pass; the test only keeps a wrong count inside the layer's slots
+          const uint64_t kept = __ballot(keep);
+          if (kept != 0) {   // uniform over the wave
+            const uint32_t slot = claim<THREADS>(kept, emitted, sh.emit);
+            if (keep && slot < k) {   // exactly k entries pass; the test only keeps a wrong count inside the layer's slots
               const int64_t dst = (int64_t)i * A.k + L.sel_base + slot;
               A.sel_idx[dst] = base + e;
               if (COMP == Q_TOPK) A.sel_val[dst] = v[it][c];
@@ -319,17 +404,19 @@ __device__ __forceinline__ void layer_body(const Args& A, const int i, const Lay
   }
 }
 
-// Two launches cover the work list A.layer_work (layers by falling length):
-//   THREADS = 1024: grid (nlarge, n), a workgroup per layer above 10,240 entries;
-//   THREADS = 256:  grid (nmid + ceil(nsmall / 4), n), a workgroup per layer above 2,560
-//                   entries, then a wave per smaller layer, four to a workgroup.
-// `first` is where the launch starts in the work list, `nblock` how many layers from there
-// take a whole workgroup.  (Launch bounds of 1024 hold the code to 128 registers, so four
-// 256-thread workgroups fit a compute unit.)
+// A launch covers a piece of the work list A.layer_work (layers by falling length) from `first`
+// on: the first `nblock` layers from there take a whole workgroup each, any others a wave each,
+//   THREADS = 1024: grid (nmid, n): the layers above 3,072 entries;
+//   THREADS = 256:  grid (nsmall + ceil(ntiny / 4), n): a workgroup per layer above 768
+//                   entries, four smaller layers to a workgroup.
+// Few workers (the chip is not full either way): one launch of 1024-thread workgroups, one for
+// every layer above 768 entries and one for every sixteen smaller ones.
+// (64 registers: two 1024-thread workgroups share a compute unit.)
 template <int COMP, int THREADS, bool NT>
-__global__ __launch_bounds__(1024) void k_layer_compress(Args A, int32_t first, int32_t nblock) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
+void k_layer_compress(Args A, int32_t first, int32_t nblock) {
   constexpr int NW = THREADS / 64;
-  __shared__ uint32_t sh_cnt[32];
+  __shared__ uint32_t sh_cnt[34];   // 2 x 16 per-wave counts, the result of the first wave's search
   __shared__ uint32_t sh_emit[NW];
   __shared__ uint32_t sh_list_n[NW];
   __shared__ uint2 sh_list[2 * THREADS];

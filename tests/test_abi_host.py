@@ -171,18 +171,23 @@ def test_layer_tables_are_validated():
 
 
 def test_layer_limits_are_reported_as_unsupported():
-    limit = 40960    # CHOCO_MAX_LAYER_LEN: longer top_a / random_a layers take the streaming select
+    limit = 10240    # CHOCO_MAX_LAYER_LEN: longer top_a / random_a layers take the streaming select
     assert layer_code(limit + 8, [0, 8], [8, limit], [1, 10]) == B.OK
     assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 10]) == B.OK
     assert layer_code(limit + 9, [0, 8], [8, limit + 1], [1, 0]) == B.OK       # a long silent layer
     assert layer_code(limit + 9, [0, 8], [8, limit + 1], None, compressor=B.Q_SIGN) == B.OK   # dense: any length
-    assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT) == B.E_UNSUPPORTED
+    # top_a / random_a layer by layer: the direct form where its fused pass exists (default order)
+    assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT) == B.OK
+    assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_INCREMENTAL_S) == B.OK
+    assert layer_code(1000, [0, 400], [400, 600], [4, 6], mix_form=B.MIX_DIRECT,
+                      order=B.ORDER_MIX_THEN_COMPRESS) == B.E_UNSUPPORTED
+    assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_SIGN, mix_form=B.MIX_DIRECT) == B.E_UNSUPPORTED
     assert layer_code(1000, [0, 400], [400, 600], None, compressor=B.Q_IDENTITY) == B.E_UNSUPPORTED
 
 
 def test_long_layers_bring_candidate_lists_into_the_workspace():
     start, length, k = synth.layer_table([30000, 70000], fraction=0.01)
-    short = synth.layer_table([30000, 30000, 40000], fraction=0.01)
+    short = synth.layer_table([10000] * 10, fraction=0.01)
     c1, keep1 = cfg(d=100000, layers=(start, length, k))
     c2, keep2 = cfg(d=100000, layers=short)
     assert B.workspace_bytes(c1) > B.workspace_bytes(c2)
@@ -191,7 +196,7 @@ def test_long_layers_bring_candidate_lists_into_the_workspace():
 def test_layered_workspace_needs_no_candidate_lists():
     c, keep = cfg(d=100000, k=1000)
     flat = B.workspace_bytes(c)
-    start, length, k = synth.layer_table([25000] * 4, fraction=0.01)
+    start, length, k = synth.layer_table([10000] * 10, fraction=0.01)
     c2, keep2 = cfg(d=100000, layers=(start, length, k))
     assert B.workspace_bytes(c2) < flat
 

@@ -118,13 +118,15 @@ def test_large_model_shape_topk_separate_calls():
     run(8, 28_000_000, synth.ring_csr(8), 1, 0.01, 0.05, 0.0, fused=False, compressor=B.Q_TOPK, k=28_000)
 
 
-@pytest.mark.parametrize("n,comp", [(8, B.Q_SIGN), (64, B.Q_SIGN), (64, B.Q_TOPK), (64, B.Q_RANDK)])
-def test_layer_wise_shapes(n, comp):
+@pytest.mark.parametrize("n,comp,mix", [(8, B.Q_SIGN, B.MIX_AUTO), (64, B.Q_SIGN, B.MIX_AUTO),
+                                        (64, B.Q_TOPK, B.MIX_DIRECT), (64, B.Q_TOPK, B.MIX_INCREMENTAL_S),
+                                        (64, B.Q_RANDK, B.MIX_DIRECT), (64, B.Q_RANDK, B.MIX_INCREMENTAL_S)])
+def test_layer_wise_shapes(n, comp, mix):
     # the 65 layers of the 0.27 M-parameter model (d = 272,474), 1 % of every layer
     layers = synth.layer_table(synth.resnet20_like_lengths(), fraction=0.01)
     d = synth.layers_dim(layers)
     scal = run(n, d, synth.ring_csr(n), 3, 0.4 if comp == B.Q_SIGN else 0.02, 0.1, 0.001, layers=layers,
-               compressor=comp)
+               compressor=comp, mix_form=mix)
     if comp == B.Q_RANDK:
         big = layers[1] > 10240
         assert np.all(scal[:, big, 3] == 1)     # the bracket around the expected order statistic held
@@ -200,13 +202,14 @@ def test_layer_wise_sign_on_the_language_model_sizes():
     run(8, d, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, layers=layers, compressor=B.Q_SIGN)
 
 
+@pytest.mark.parametrize("mix", [B.MIX_DIRECT, B.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("comp", [B.Q_TOPK, B.Q_RANDK])
-def test_layer_wise_selection_on_the_language_model_sizes(comp):
-    # 0.1 % of every layer; the 21.6 M- and 1.69 M-entry layers take the guessed-threshold
-    # select layer after layer, the biases the layer kernel
+def test_layer_wise_selection_on_the_language_model_sizes(comp, mix):
+    # 0.1 % of every layer; the 21.6 M-entry layer takes the guessed-threshold select on its own,
+    # the 1.69 M-entry layers take it in launches that they share, the biases the layer kernel
     layers = synth.layer_table(synth.lstm_like_lengths(), fraction=0.001)
     d = synth.layers_dim(layers)
-    run(8, d, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, layers=layers, compressor=comp)
+    run(8, d, synth.ring_csr(8), 2, 0.01, 0.05, 0.0, layers=layers, compressor=comp, mix_form=mix)
 
 
 def test_random_k_messages_of_the_large_model_shape():

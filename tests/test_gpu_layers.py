@@ -18,10 +18,27 @@ OPERATORS = [
     ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
 ]
 ORDERS = [binding.ORDER_COMPRESS_THEN_MIX, binding.ORDER_MIX_THEN_COMPRESS]
+# order of the step and form of the mix: what MIX_AUTO picks in either order (top_a / random_a:
+# the direct form with its fused pass, and the neighbour sums in the printed order) and, for
+# top_a / random_a, the neighbour sums in the default order too
+FORMS = [
+    pytest.param(binding.ORDER_COMPRESS_THEN_MIX, binding.MIX_AUTO, id="compress_mix"),
+    pytest.param(binding.ORDER_MIX_THEN_COMPRESS, binding.MIX_AUTO, id="mix_compress"),
+    pytest.param(binding.ORDER_COMPRESS_THEN_MIX, binding.MIX_INCREMENTAL_S, id="compress_mix_sums"),
+]
+SPARSE_OPS = (binding.Q_TOPK, binding.Q_RANDK)
 
-# every size class of the layer kernel (up to 2,560 / 10,240 / 40,960 entries), ragged
-# lengths, one-entry and sub-vector layers, chunk and group boundaries of the norm tree
-MIXED_LENGTHS = [432, 16, 1, 3, 2304, 255, 256, 257, 2560, 2561, 4097, 9216, 10240, 10241, 36864, 7, 40960, 10]
+
+def form(q, order, mix_form):
+    if mix_form != binding.MIX_AUTO and q["compressor"] not in SPARSE_OPS:
+        pytest.skip("sign and gsgd layer by layer have the direct form only")
+    return dict(order=order, mix_form=mix_form)
+
+# every size class of the layer kernel (up to 768 / 3,072 / 10,240 entries) and the streaming
+# select above it, ragged lengths, one-entry and sub-vector layers, chunk and group boundaries
+# of the norm tree
+MIXED_LENGTHS = [432, 16, 1, 3, 2304, 255, 256, 257, 768, 769, 2560, 2561, 3072, 3073, 4097, 9216, 10240, 10241,
+                 36864, 7, 40960, 10]
 
 
 def mixed_layers(fraction=0.01):
@@ -41,26 +58,26 @@ def padded_state(n, layers, seed, std=1.0):
     return X, inside
 
 
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", OPERATORS)
-def test_layered_gossip_steps(name, q, order):
+def test_layered_gossip_steps(name, q, order, mix_form):
     layers = mixed_layers()
     n = 5
     X0, _ = padded_state(n, layers, seed=11)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=5, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=5, layers=layers, **form(q, order, mix_form), **q)
     for t in range(4):
         det = pair.gossip_step()
         pair.check(det, tag="%s step %d" % (name, t))
     pair.close()
 
 
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", OPERATORS)
-def test_layered_fused_iterations(name, q, order):
+def test_layered_fused_iterations(name, q, order, mix_form):
     layers = mixed_layers(fraction=0.05)
     n = 6
     X0, inside = padded_state(n, layers, seed=12)
-    pair = Pair(X0, synth.torus_csr(2, 3), 0.2, order=order, seed=6, layers=layers, **q)
+    pair = Pair(X0, synth.torus_csr(2, 3), 0.2, seed=6, layers=layers, **form(q, order, mix_form), **q)
     grads = synth.GradientStream(n, pair.d, seed=3, noise_std=0.05, bias_std=0.02)
     for t in range(4):
         G = grads.next()
@@ -70,12 +87,14 @@ def test_layered_fused_iterations(name, q, order):
     pair.close()
 
 
+@pytest.mark.parametrize("mix_form", [binding.MIX_AUTO, binding.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3]])
-def test_layered_momentum_iterations(name, q):
+def test_layered_momentum_iterations(name, q, mix_form):
     layers = mixed_layers(fraction=0.02)
     n = 4
     X0, inside = padded_state(n, layers, seed=13)
-    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers,
+                **form(q, binding.ORDER_COMPRESS_THEN_MIX, mix_form), **q)
     grads = synth.GradientStream(n, pair.d, seed=4, noise_std=0.05, bias_std=0.02)
     for t in range(3):
         G = grads.next()
@@ -85,8 +104,8 @@ def test_layered_momentum_iterations(name, q):
     pair.close()
 
 
-@pytest.mark.parametrize("order", ORDERS)
-def test_layered_topk_ties_go_to_the_lower_index(order):
+@pytest.mark.parametrize("order,mix_form", FORMS)
+def test_layered_topk_ties_go_to_the_lower_index(order, mix_form):
     # few distinct magnitudes, many exact zeros: the threshold key is shared by far more
     # entries than may be kept, in every size class
     lengths = [100, 2500, 9000, 30000]
@@ -95,7 +114,7 @@ def test_layered_topk_ties_go_to_the_lower_index(order):
     n = 3
     rng = np.random.default_rng(5)
     X0 = rng.integers(-2, 3, size=(n, d)).astype(np.float32) * 0.5
-    pair = Pair(X0, synth.ring_csr(n), 0.5, compressor=binding.Q_TOPK, order=order, layers=layers)
+    pair = Pair(X0, synth.ring_csr(n), 0.5, compressor=binding.Q_TOPK, order=order, mix_form=mix_form, layers=layers)
     for t in range(3):
         det = pair.gossip_step()
         pair.check(det, tag="ties step %d" % t)
@@ -134,16 +153,16 @@ def test_layers_of_the_small_image_model(name, q):
     pair.close()
 
 
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", [OPERATORS[3], OPERATORS[4]])
-def test_dense_layers_of_any_length(name, q, order):
+def test_dense_layers_of_any_length(name, q, order, mix_form):
     # sign / gsgd stream the rows with per-layer norms: layers far above what one workgroup
     # could hold, with more than 256 group sums (the third tree level wraps), next to tiny ones
     lengths = [5, 1_200_001, 16, 100_003, 4096, 4097, 36864]
     layers = synth.layer_table(lengths, fraction=0.01)
     n = 3
     X0, inside = padded_state(n, layers, seed=15)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=4, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=4, layers=layers, **form(q, order, mix_form), **q)
     grads = synth.GradientStream(n, pair.d, seed=7, noise_std=0.05, bias_std=0.02)
     for t in range(3):
         G = grads.next()
@@ -181,15 +200,15 @@ def test_layers_with_a_wider_row_stride(name, q):
     pair.close()
 
 
-@pytest.mark.parametrize("order", ORDERS)
-def test_layered_random_masks_selected_ahead_or_not_are_the_same(order):
+@pytest.mark.parametrize("order,mix_form", FORMS)
+def test_layered_random_masks_selected_ahead_or_not_are_the_same(order, mix_form):
     # layer-wise random_a draws the next step's masks on a second stream; switching that off
     # and on, moving the step counter (a mask drawn for step 9 is dropped, its marks with it)
     # and timing the kernels must not change a bit
     layers = mixed_layers(fraction=0.03)
     n = 6
     X0, inside = padded_state(n, layers, seed=21)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=9, layers=layers, compressor=binding.Q_RANDK,
+    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, mix_form=mix_form, seed=9, layers=layers, compressor=binding.Q_RANDK,
                 randk_rescale=1)
     grads = synth.GradientStream(n, pair.d, seed=13, noise_std=0.05, bias_std=0.02)
     try:
@@ -226,13 +245,13 @@ def long_layers(fraction=0.03):
     return start, length, k
 
 
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", SPARSE)
-def test_long_layers_fused_iterations(name, q, order):
+def test_long_layers_fused_iterations(name, q, order, mix_form):
     layers = long_layers()
     n = 4
     X0, inside = padded_state(n, layers, seed=31)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=15, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=15, layers=layers, **form(q, order, mix_form), **q)
     grads = synth.GradientStream(n, pair.d, seed=14, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(4):
@@ -251,14 +270,16 @@ def test_long_layers_fused_iterations(name, q, order):
         pair.close()
 
 
+@pytest.mark.parametrize("mix_form", [binding.MIX_AUTO, binding.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1]])
-def test_long_layers_momentum_with_a_silent_long_layer(name, q):
+def test_long_layers_momentum_with_a_silent_long_layer(name, q, mix_form):
     start, length, k = long_layers(fraction=0.01)
     k[1] = 0            # a long layer that sends nothing still takes its local update
     layers = (start, length, k)
     n = 3
     X0, inside = padded_state(n, layers, seed=32)
-    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=16, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=16, layers=layers,
+                **form(q, binding.ORDER_COMPRESS_THEN_MIX, mix_form), **q)
     grads = synth.GradientStream(n, pair.d, seed=15, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(3):
@@ -307,9 +328,9 @@ def test_long_layer_topk_ties_go_to_the_lower_index():
 # --------------------------------------------------------------------------
 # Entries outside the layers, and tables as a model's flat parameter vector has them
 # --------------------------------------------------------------------------
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", OPERATORS)
-def test_padding_between_layers_may_hold_anything(name, q, order):
+def test_padding_between_layers_may_hold_anything(name, q, order, mix_form):
     # aligned table (layers start on multiples of 4), but x and g are NOT zero in the padding
     # entries: they are never compressed or sent (q = 0 there), yet the local update and the
     # mix treat them like any entry - exactly what the oracle does with entries in no slice
@@ -317,7 +338,7 @@ def test_padding_between_layers_may_hold_anything(name, q, order):
     n = 5
     d = synth.layers_dim(layers)
     X0 = synth.normal_state(n, d, seed=21)          # padding entries as random as the rest
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=5, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=5, layers=layers, **form(q, order, mix_form), **q)
     grads = synth.GradientStream(n, d, seed=22, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(4):
@@ -349,15 +370,15 @@ GENERIC_LENGTHS = [5, 1, 2, 1, 433, 17, 2561, 3, 10241, 255, 40957, 7, 9001, 64]
 GENERIC_GAPS = [0, 0, 0, 3, 0, 1, 0, 0, 9, 0, 2, 0, 0, 0]
 
 
-@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("order,mix_form", FORMS)
 @pytest.mark.parametrize("name,q", OPERATORS)
-def test_layer_tables_without_alignment(name, q, order):
+def test_layer_tables_without_alignment(name, q, order, mix_form):
     layers, d = generic_table(GENERIC_LENGTHS, GENERIC_GAPS, lead=3, tail=6)
     layers[2][1] = 0 if q["compressor"] in (binding.Q_TOPK, binding.Q_RANDK) else layers[2][1]   # a silent layer
     assert any(s % 4 for s in layers[0])
     n = 5
     X0 = synth.normal_state(n, d, seed=23)
-    pair = Pair(X0, synth.ring_csr(n), 0.3, order=order, seed=6, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=6, layers=layers, **form(q, order, mix_form), **q)
     grads = synth.GradientStream(n, d, seed=24, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(4):
@@ -371,14 +392,16 @@ def test_layer_tables_without_alignment(name, q, order):
         pair.close()
 
 
+@pytest.mark.parametrize("mix_form", [binding.MIX_AUTO, binding.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3], OPERATORS[4]])
-def test_layer_tables_without_alignment_long_layers_and_momentum(name, q):
+def test_layer_tables_without_alignment_long_layers_and_momentum(name, q, mix_form):
     # layers above 40,960 entries that start off a 16-byte boundary take the streaming select on a
     # piece of the row whose first entries belong to the layer before
     layers, d = generic_table([30, 70001, 3, 41000, 5000, 90000], [0, 0, 1, 0, 0, 0], fraction=0.01, lead=1, tail=2)
     n = 4
     X0 = synth.normal_state(n, d, seed=25)
-    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers, **q)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=7, layers=layers,
+                **form(q, binding.ORDER_COMPRESS_THEN_MIX, mix_form), **q)
     grads = synth.GradientStream(n, d, seed=26, noise_std=0.05, bias_std=0.02)
     try:
         for t in range(4):

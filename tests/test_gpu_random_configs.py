@@ -31,7 +31,7 @@ def draw_case(case):
     layers = None
     if layered:
         nl = int(rng.integers(1, 9))
-        lengths = [int(x) for x in rng.choice([1, 2, 3, 5, 17, 255, 256, 257, 1000, 2561, 4099, 10241, 12000], size=nl)]
+        lengths = [int(x) for x in rng.choice([1, 2, 3, 5, 17, 255, 256, 257, 768, 769, 1000, 2561, 3072, 3073, 4099, 10240, 10241, 12000], size=nl)]
         if rng.random() < 0.25:
             lengths[int(rng.integers(0, nl))] = int(rng.choice([40961, 45000, 70001]))   # a long layer
         start, length, k = synth.layer_table(lengths, fraction=float(rng.choice([0.01, 0.05, 0.3])))
@@ -52,6 +52,10 @@ def draw_case(case):
         kw["qsgd_biased"] = int(rng.integers(0, 2))
     if comp == B.Q_RANDK:
         kw["randk_rescale"] = int(rng.integers(0, 2))
+    # top_a / random_a layer by layer, default order: MIX_AUTO is the direct form; every other
+    # case takes the neighbour sums instead
+    if layers is not None and comp in (B.Q_TOPK, B.Q_RANDK) and kw["order"] == B.ORDER_COMPRESS_THEN_MIX and case % 2 == 1:
+        kw["mix_form"] = B.MIX_INCREMENTAL_S
     ld_align = int(rng.choice([4, 4, 64]))
     calls = [str(c) for c in rng.choice(["step", "separate", "gossip", "momentum"], size=4)]
     return dict(n=n, d=d, topo=topo, kw=kw, layers=layers, ld_align=ld_align, calls=calls,
@@ -114,6 +118,10 @@ def draw_large_case(case):
         kw["levels"] = int(rng.choice([4, 16]))
     if comp == B.Q_RANDK:
         kw["randk_rescale"] = int(rng.integers(0, 2))
+    # top_a / random_a layer by layer, default order: MIX_AUTO is the direct form; every other
+    # case takes the neighbour sums instead
+    if layers is not None and comp in (B.Q_TOPK, B.Q_RANDK) and kw["order"] == B.ORDER_COMPRESS_THEN_MIX and case % 2 == 1:
+        kw["mix_form"] = B.MIX_INCREMENTAL_S
     return dict(n=n, d=d, topo=topo, kw=kw, layers=layers)
 
 
@@ -149,7 +157,7 @@ def draw_generic_layers_case(case):
     n = int(rng.choice([1, 2, 3, 5, 8, 17]))
     topo = synth.ring_csr(n)
     nl = int(rng.integers(1, 12))
-    lengths = [int(x) for x in rng.choice([1, 1, 2, 3, 5, 6, 17, 255, 257, 1000, 2559, 2561, 4099, 10239, 12000], size=nl)]
+    lengths = [int(x) for x in rng.choice([1, 1, 2, 3, 5, 6, 17, 255, 257, 767, 769, 1000, 2559, 3071, 3073, 4099, 10239, 12000], size=nl)]
     if rng.random() < 0.25:
         lengths[int(rng.integers(0, nl))] = int(rng.choice([40958, 40961, 52001]))
     aligned = rng.random() < 0.25           # every fourth table keeps the 4-entry alignment (with non-zero padding)
@@ -173,6 +181,10 @@ def draw_generic_layers_case(case):
         kw["qsgd_biased"] = int(rng.integers(0, 2))
     if comp == B.Q_RANDK:
         kw["randk_rescale"] = int(rng.integers(0, 2))
+    # top_a / random_a layer by layer, default order: MIX_AUTO is the direct form; every other
+    # case takes the neighbour sums instead
+    if length is not None and comp in (B.Q_TOPK, B.Q_RANDK) and kw["order"] == B.ORDER_COMPRESS_THEN_MIX and case % 2 == 1:
+        kw["mix_form"] = B.MIX_INCREMENTAL_S
     calls = [str(c) for c in rng.choice(["step", "separate", "gossip", "momentum"], size=3)]
     return dict(n=n, d=d, topo=topo, kw=kw, layers=(np.asarray(start, dtype=np.int64), length, k),
                 ld_align=int(rng.choice([4, 64])), calls=calls, gamma=float(rng.choice([0.05, 0.3, 0.9])))
