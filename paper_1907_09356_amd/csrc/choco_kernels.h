@@ -811,6 +811,90 @@ __global__ __launch_bounds__(256) void k_group_reduce(Args A) {
 // per wave (compile-time bound, x stays in registers between the phases).  Dynamic LDS:
 // n * 256 floats (64 KiB at n = 64: two 1024-thread blocks per CU keep it fully occupied).
 // ---------------------------------------------------------------------------
+// The rows of W that a wave mixes (up to four), fetched when the kernel starts, beside the loads
+// of x and xhat: lane 16 q + j holds neighbour j of the wave's q-th row - its weight, and its
+// column with the row's length above it - and the mix reads them back lane by lane (readlane:
+// no memory access in the loop but the tile's).  A row with more than 16 neighbours is read from
+// memory in the loop instead.  (Read there for every row - the row pointers, then the columns
+// and weights, then the tile rows - this was a chain of dependent fetches during which the
+// workgroup had no load in flight: 4.0 of the 13.6 us a workgroup lived at n = 64.  Scalar loads
+// inside the loop were slower still: they share a counter with the LDS loads, and every wait
+// for one is a wait for all.)
+constexpr int kNbrLanes = 16;
+
+struct RowNbrs {
+  int col_deg;   // column | row length << 8
+  float w;
+};
+
+// In two steps, so that a kernel can put the first behind the loads it issues first and the
+// second where those have returned: where the lane's row starts and how long it is ...
+struct RowSpan {
+  int beg, deg;
+};
+
+template <int RPW, int NW>
+__device__ __forceinline__ RowSpan nbr_span(const Args& A, int wave, int lane) {
+  static_assert(RPW * kNbrLanes <= 64, "a lane group per row of the wave");
+  RowSpan sp{0, 0};
+  const int q = lane / kNbrLanes;
+  const int r = wave + NW * q;
+  if (q < RPW && r < A.n) {
+    sp.beg = A.row_ptr[r];
+    sp.deg = A.row_ptr[r + 1] - sp.beg;
+  }
+  return sp;
+}
+
+// ... and the lane's neighbour of that row.
+__device__ __forceinline__ RowNbrs nbr_fetch(const Args& A, const RowSpan& sp, int lane) {
+  RowNbrs nb{sp.deg << 8, 0.0f};
+  const int j = lane % kNbrLanes;
+  if (j < sp.deg) {
+    nb.col_deg |= A.col[sp.beg + j];
+    nb.w = A.w[sp.beg + j];
+  }
+  return nb;
+}
+
+template <int RPW, int NW>
+__device__ __forceinline__ void tile_mix_rows_staged(const Args& A, const float* tile, int wave, int lane,
+                                                     bool valid, vf4 (&xr)[RPW], const RowNbrs& nb) {
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = wave + NW * q;
+    if (r < A.n) {                                   // uniform over the wave (readlane takes every lane)
+      const vf4 me = lds_load4(tile + r * kChunk + lane * 4);
+      vf4 acc = {0.f, 0.f, 0.f, 0.f};
+      const int deg = __builtin_amdgcn_readlane(nb.col_deg, q * kNbrLanes) >> 8;
+      if (deg <= kNbrLanes) {                        // neighbours in the order of the CSR row
+        for (int j = 0; j < deg; ++j) {
+          const int cj = __builtin_amdgcn_readlane(nb.col_deg, q * kNbrLanes + j) & 0xFF;
+          const float wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(nb.w), q * kNbrLanes + j));
+          const vf4 o = lds_load4(tile + cj * kChunk + lane * 4);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[c] = acc[c] + wj * (o[c] - me[c]);
+        }
+      } else {
+        const int pbeg = A.row_ptr[r];
+        for (int p = pbeg; p < pbeg + deg; ++p) {
+          const float wj = A.w[p];
+          const vf4 o = lds_load4(tile + A.col[p] * kChunk + lane * 4);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[c] = acc[c] + wj * (o[c] - me[c]);
+        }
+      }
+      if (valid) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) xr[q][c] = xr[q][c] + A.gamma * acc[c];
+      }
+    }
+  }
+}
+
+// The same with every row of W read from memory in the loop (k_dense_apply_mix, whose registers
+// and issue slots before the barrier are spoken for by the encoding: staged rows made it 3-7 %
+// slower at n = 8 and no faster at n = 64).
 template <int RPW, int NW>
 __device__ __forceinline__ void tile_mix_rows(const Args& A, const float* tile, int wave, int lane,
                                               bool valid, vf4 (&xr)[RPW]) {
@@ -922,6 +1006,8 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
   const int e = blockIdx.x * kChunk + lane * 4;
   const bool valid = e < A.d;
   const bool sgd = A.G != nullptr, mom = sgd && A.M != nullptr;
+  RowSpan span{0, 0};
+  RowNbrs nb{0, 0.0f};
   // The loads of (up to) two of the wave's rows first - x, xhat, the gradient, the kept-entry
   // word -, then their arithmetic and stores: a store, or a test of a loaded word, between two
   // loads would put the later load behind the round trip of the earlier one.  Two rows at a
@@ -949,10 +1035,14 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
                                    : A.keptmap[(int64_t)r * A.map_words + ((uint32_t)e >> 5)];
       }
     }
+    // the rows of W for the mix: the row pointers behind the first rows' loads, the neighbours
+    // where those have returned (the arithmetic below waits for them anyway)
+    if (q0 == 0) span = nbr_span<RPW, NW>(A, wave, lane);
 #pragma unroll
     for (int j = 0; j < HB; ++j) {
       const int q = q0 + j;
       const int r = wave + NW * q;
+      if (q0 == 0 && j == 0) nb = nbr_fetch(A, span, lane);
       if (q < RPW && r < A.n) {
         vf4 xh = {0.f, 0.f, 0.f, 0.f};
         if (valid) {
@@ -988,7 +1078,7 @@ __global__ __launch_bounds__(64 * NW) void k_tile_mix(Args A) {
     }
   }
   __syncthreads();
-  tile_mix_rows<RPW, NW>(A, tile, wave, lane, valid, xr);
+  tile_mix_rows_staged<RPW, NW>(A, tile, wave, lane, valid, xr, nb);
 #pragma unroll
   for (int q = 0; q < RPW; ++q) {
     const int r = wave + NW * q;

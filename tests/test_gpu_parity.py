@@ -190,6 +190,36 @@ def test_single_and_two_workers(n, comp, order):
     run(n, 3000, comp, order, steps=3)
 
 
+@pytest.mark.parametrize("graph", ["hub", "complete"])
+@pytest.mark.parametrize("comp", ["sign", "topk", "randk"])
+def test_rows_of_w_longer_than_the_mix_kernel_stages(comp, graph):
+    # the tile mix keeps up to 16 neighbours of a row in a lane group and reads longer rows from
+    # memory: a hub of degree 30 among short rows (both paths in one workgroup), and the complete
+    # graph on 20 nodes (every row long)
+    if graph == "hub":
+        n = 40
+        adj = synth.irregular_graph(n, 30, seed=5)
+        assert adj.sum(1).max() == 30 and adj.sum(1).min() < 15
+        topo = synth.metropolis_csr(adj)
+    else:
+        n = 20
+        topo = synth.complete_csr(n)
+    kw = dict(COMPRESSORS[comp])
+    if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+        kw["k"] = 30
+    d = 3000
+    pair = Pair(synth.normal_state(n, d, seed=12), topo, 0.3, seed=14, **kw)
+    grads = synth.GradientStream(n, d, seed=13)
+    try:
+        if kw["compressor"] in (B.Q_TOPK, B.Q_RANDK):
+            assert pair.mix == B.MIX_DIRECT      # the fused tile pass
+        for t in range(4):
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="%s graph %s step %d" % (graph, comp, t))
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("mix", SPARSE_MIXES)
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("comp", ["sign", "qsgd16", "topk", "randk"])
