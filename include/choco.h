@@ -199,7 +199,7 @@ int choco_nsum(choco_ctx *ctx, float **s_dev);
    (0 = guessed threshold held, 1 = list rebuilt from the histogram, 2 = row scan), number of
    steps so far that needed mode 1 or 2, length of the last candidate list}; for RANDK with the
    look-ahead on (choco_set_lookahead) these are the figures of the selection made last, which
-   is the NEXT step's.  Synchronises. */
+   is a LATER step's (up to seven steps on).  Synchronises. */
 int choco_last_selection(choco_ctx *ctx, int32_t *idx_dev, float *val_dev);
 int choco_set_capture(choco_ctx *ctx, int32_t *codes_dev);
 int choco_last_scalars(choco_ctx *ctx, double *scalars_host);
@@ -282,10 +282,12 @@ int choco_set_profiling(choco_ctx *ctx, int enable);
 int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
 
 /* RANDK: the mask of a step depends on (seed, step, worker) only (Appendix C, random_a: the
-   receiver can recover it from the seed), so while one step's messages and mix run on the
-   caller's stream the library already selects the
-   NEXT step's mask on a stream of its own (created by choco_init, default priority, joined
-   with events; no device memory is allocated).  Results do not change.  On by default
+   receiver can recover it from the seed), so while the messages and mixes of four steps run on
+   the caller's stream the library already selects the masks of the NEXT four steps on a stream
+   of its own (created by choco_init, default priority, joined with two events per four steps;
+   the kept lists and maps of eight steps are part of the workspace, no device memory is
+   allocated).  Results do not change, whatever the calls in between (a moved step counter
+   drops what was selected for other steps).  On by default
    where it applies; switch it off (enable = 0) if every call must leave all of its work
    on the caller's stream, e.g. under stream capture.  A no-op for other configurations. */
 int choco_set_lookahead(choco_ctx *ctx, int enable);

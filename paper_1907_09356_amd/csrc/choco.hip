@@ -42,6 +42,16 @@ struct LongLayer {
   bool batched;     // its pass and its select share a launch with those of the other such layers
 };
 
+// random_a selects ahead in batches of this many steps (two event operations on the caller's
+// stream per batch instead of per step: they cost 11 us of idle queue each time, n = 64,
+// d = 270 k).
+constexpr int kAheadSteps = 4;
+constexpr int kAheadBufs = 2 * kAheadSteps;
+struct AheadBatch {
+  uint64_t base;   // selections of steps base .. base + kAheadSteps - 1
+  bool valid;
+};
+
 // Partial sums of choco_metrics_noalloc: the same three doubles per block that choco_metrics
 // keeps in the caller's workspace, here in device memory that belongs to the loaded library
 // (24 KiB on every GPU the library runs on, until the process ends).  In host code this name
@@ -54,22 +64,22 @@ struct choco_ctx {
   choco_config cfg;       // scalar fields as given (host CSR pointers are not kept)
   Args args;              // kernel arguments (device pointers into the workspace)
   hipStream_t stream;
-  // random_a on short rows: the mask of a step depends on (seed, step, worker) only, so while
-  // a step's messages and mix run on the caller's stream the NEXT step's selection already
-  // runs on this one.  Two copies of the kept-index lists and of the bitmap take turns.
+  // random_a: the mask of a step depends on (seed, step, worker) only, so while the steps of one
+  // batch (kAheadSteps of them) run on the caller's stream the selections of the NEXT batch
+  // already run on this one.  2 * kAheadSteps copies of the kept-index lists and of the bitmap
+  // take turns: step t uses copy t mod (2 * kAheadSteps).
   hipStream_t aux_stream;
   hipStream_t launch_stream;   // where LAUNCH puts kernels: the caller's stream, or aux_stream while selecting ahead
   hipEvent_t ev_fork, ev_ahead;
   bool lookahead;         // the configuration allows it and it has not been switched off
   bool can_lookahead;     // the configuration allows it (random_a)
-  bool ahead_pending;     // a selection is in flight (or done) on aux_stream and not yet joined
-  bool ahead_valid;       // ... and it is the selection of step ahead_t
-  uint64_t ahead_t;
-  int32_t* sel_idx_buf[2];
-  uint32_t* bitmap_buf[2];
-  uint32_t* keptmap_buf[2];
-  double* layer_scal_buf[2];
-  int ahead_map_buf;      // rows without an LDS bitmap: the bit-map copy that holds a selection made ahead and not yet used (-1: none)
+  bool ahead_pending;     // the batch `nxt` is in flight (or done) on aux_stream and not yet joined
+  AheadBatch cur, nxt;    // the batch whose selections the steps are using / the one selected beside them
+  int32_t* sel_idx_buf[kAheadBufs];
+  uint32_t* bitmap_buf[kAheadBufs];
+  uint32_t* keptmap_buf[kAheadBufs];
+  double* layer_scal_buf[kAheadBufs];
+  uint32_t dirty_maps;    // rows without an LDS bitmap: the bit-map copies that hold a selection made ahead and not yet used
   int last_buf;           // which copy the last finished step used
   int32_t maxdeg;
   int32_t nnz;
@@ -132,6 +142,7 @@ struct Layout {
   bool multipart;
   int32_t select_sets;   // copies of the select scratch (candidate lists, histograms, short list)
   size_t hist16_bytes, cand_bytes, hist_parts_bytes, small_list_bytes;   // size of one copy
+  size_t sel_idx_bytes, bitmap_bytes, keptmap_bytes, layer_scal_bytes;   // ... of what a selection made ahead writes
   int32_t nchunks, ngroups;
 };
 
@@ -425,10 +436,15 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // second copies for the look-ahead selection of random_a: the kept-index lists, the bitmap
   // (short rows in whole-vector mode) or the bit map in global memory, the per-layer scalars
   const bool ahead = c.compressor == CHOCO_Q_RANDK;
-  L.sel_idx2 = take(ahead ? (size_t)c.n * (size_t)kept * sizeof(int32_t) : 0);
-  L.bitmap2 = take(ahead ? (size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t) : 0);
-  L.keptmap2 = take(ahead && !L.bitmap_words ? map_bytes : 0);
-  L.layer_scal2 = take(ahead && layered ? (size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double) : 0);
+  const size_t more = kAheadBufs - 1;
+  L.sel_idx_bytes = align_up((size_t)c.n * (size_t)kept * sizeof(int32_t));
+  L.bitmap_bytes = align_up((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
+  L.keptmap_bytes = align_up(map_bytes);
+  L.layer_scal_bytes = align_up((size_t)c.n * (size_t)c.nlayers * 4 * sizeof(double));
+  L.sel_idx2 = take(ahead ? more * L.sel_idx_bytes : 0);
+  L.bitmap2 = take(ahead ? more * L.bitmap_bytes : 0);
+  L.keptmap2 = take(ahead && !L.bitmap_words ? more * L.keptmap_bytes : 0);
+  L.layer_scal2 = take(ahead && layered ? more * L.layer_scal_bytes : 0);
   L.layers = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.layer_work = take((size_t)c.nlayers * sizeof(LayerDesc));
   L.long_tab = take(longs.size() * sizeof(LongSel));
@@ -751,7 +767,10 @@ size_t ahead_lds_pad(const choco_ctx* ctx, int64_t row_len) {
 template <int COMP, bool NT>
 void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact, bool fuse_mix) {
   const int32_t nvec = (A.d + 3) >> 2;
-  const int cvecs = ctx->fallback_chain ? kCompactVecs : 2;   // long rows: 4 four-vectors per thread, short: 2
+  // long rows: 4 four-vectors per thread, short ones 2; random_a 4 at any length (its pass draws
+  // Philox words beside the step's bandwidth-bound pass: half as many workgroups get in that pass's
+  // way less, n = 64, d = 270 k: 79.4 -> 75.3 us per step; 8 per thread: 76.3)
+  const int cvecs = (ctx->fallback_chain || COMP == Q_RANDK) ? kCompactVecs : 2;
   const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
   const size_t pad = ahead_lds_pad(ctx, A.d);
   if (fuse_mix) {
@@ -783,34 +802,59 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
 // look_ahead_begin: was this step's selection made ahead?  It joins the second stream and, if a
 // selection made ahead is being dropped (counter set, look-ahead or timing switched), clears
 // the marks it left in its copy of the bit map (no xhat update ever would).
+bool in_batch(const AheadBatch& b, uint64_t t) { return b.valid && t >= b.base && t - b.base < (uint64_t)kAheadSteps; }
+
 int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) {
-  *selected = ahead && ctx->ahead_valid && ctx->ahead_t == ctx->t;
-  const int rc = join_lookahead(ctx);
-  if (rc != CHOCO_OK) return rc;
-  if (!*selected && ctx->ahead_map_buf >= 0) {
-    const int64_t words = (int64_t)A.n * A.map_words;
-    LAUNCH(ctx, KID_ZERO_WORDS, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
-           ctx->keptmap_buf[ctx->ahead_map_buf], words);
+  const uint64_t t = ctx->t;
+  if (ahead && in_batch(ctx->nxt, t)) {   // the first step of a batch: wait for its selections, once
+    const int rc = join_lookahead(ctx);
+    if (rc != CHOCO_OK) return rc;
+    ctx->cur = ctx->nxt;
+    ctx->nxt.valid = false;
   }
-  ctx->ahead_map_buf = -1;
-  ctx->ahead_valid = false;
+  *selected = ahead && in_batch(ctx->cur, t);
+  if (!*selected) {
+    // this step selects in line (with the same control blocks and candidate lists): nothing may
+    // be under way, and what was selected ahead for other steps is dropped
+    const int rc = join_lookahead(ctx);
+    if (rc != CHOCO_OK) return rc;
+    for (int b = 0; b < kAheadBufs; ++b)
+      if ((ctx->dirty_maps >> b) & 1u) {
+        const int64_t words = (int64_t)A.n * A.map_words;
+        LAUNCH(ctx, KID_ZERO_WORDS, k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+               ctx->keptmap_buf[b], words);
+      }
+    ctx->dirty_maps = 0;
+    ctx->cur.valid = ctx->nxt.valid = false;
+  } else {
+    ctx->dirty_maps &= ~(1u << (unsigned)(t % kAheadBufs));   // this step's own pass clears the marks it uses
+  }
   return CHOCO_OK;
 }
 
-// The argument block of the NEXT step's selection: no local update (the keys are Philox words,
-// no state is read), the other copy of the lists, maps and scalars.
-Args look_ahead_args(const choco_ctx* ctx, const Args& A) {
+// Will this step start the selections of the next batch?  At the first step of a batch whose
+// own selections were made ahead (the steps after it then select nothing in line), or at the
+// last step before a batch boundary (the start of a run: one step of head start).
+bool look_ahead_due(const choco_ctx* ctx, bool ahead) {
+  if (!ahead || ctx->nxt.valid) return false;
+  const uint64_t t = ctx->t, nb = (t / kAheadSteps + 1) * kAheadSteps;
+  return in_batch(ctx->cur, t) || t == nb - 1;
+}
+
+// The argument block of the selection of a later step tn: no local update (the keys are Philox
+// words, no state is read), that step's copy of the lists, maps and scalars.
+Args look_ahead_args(const choco_ctx* ctx, const Args& A, uint64_t tn) {
   Args P = A;
   P.G = nullptr;
   P.M = nullptr;
   P.deferred_sgd = 0;
-  const uint64_t tn = ctx->t + 1;
   P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
   P.t_hi = (uint32_t)(tn >> 32);
-  P.sel_idx = ctx->sel_idx_buf[tn & 1u];
-  P.bitmap = ctx->bitmap_buf[tn & 1u];
-  P.keptmap = ctx->keptmap_buf[tn & 1u];
-  if (ctx->nlayers > 0) P.layer_scal = ctx->layer_scal_buf[tn & 1u];
+  const int buf = (int)(tn % kAheadBufs);
+  P.sel_idx = ctx->sel_idx_buf[buf];
+  P.bitmap = ctx->bitmap_buf[buf];
+  P.keptmap = ctx->keptmap_buf[buf];
+  if (ctx->nlayers > 0) P.layer_scal = ctx->layer_scal_buf[buf];
   return P;
 }
 
@@ -832,14 +876,15 @@ int look_ahead_fork(choco_ctx* ctx) {
   return CHOCO_OK;
 }
 
-int look_ahead_end(choco_ctx* ctx, const Args& A) {
+int look_ahead_end(choco_ctx* ctx, const Args& A, uint64_t base) {
   ctx->launch_stream = ctx->stream;
   HIP_TRY(ctx, hipGetLastError());
   HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
   ctx->ahead_pending = true;
-  ctx->ahead_valid = true;
-  ctx->ahead_t = ctx->t + 1;
-  if (!A.bitmap_words) ctx->ahead_map_buf = (int)((ctx->t + 1) & 1u);
+  ctx->nxt.base = base;
+  ctx->nxt.valid = true;
+  if (!A.bitmap_words)
+    for (int u = 0; u < kAheadSteps; ++u) ctx->dirty_maps |= 1u << (unsigned)((base + (uint64_t)u) % kAheadBufs);
   return CHOCO_OK;
 }
 
@@ -877,7 +922,8 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
     if (rc != CHOCO_OK) return rc;
   }
   if (!selected) launch_select<COMP, NT>(ctx, C, A, kid_compact, fuse_mix);
-  if (ahead) {
+  const bool due = look_ahead_due(ctx, ahead);
+  if (due) {
     const int rc = look_ahead_mark(ctx);
     if (rc != CHOCO_OK) return rc;
   }
@@ -909,14 +955,17 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   }
   ctx->values_in_qv = fused_apply && COMP == Q_RANDK;
   LAUNCH_CHECK(ctx);
-  if (ahead) {
-    // the NEXT step's selection, into the other copy of the lists and of the map, side by side
-    // with the rest of this step (from the mark set above)
-    const Args P = look_ahead_args(ctx, A);
+  if (due) {
+    // the selections of the next batch of steps, into those steps' copies of the lists and of the
+    // map, side by side with this step and the ones after it (from the mark set above)
+    const uint64_t base = (ctx->t / kAheadSteps + 1) * kAheadSteps;
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
-    launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
-    rc = look_ahead_end(ctx, A);
+    for (int u = 0; u < kAheadSteps; ++u) {
+      const Args P = look_ahead_args(ctx, A, base + (uint64_t)u);
+      launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
+    }
+    rc = look_ahead_end(ctx, A, base);
     if (rc != CHOCO_OK) return rc;
   }
   return CHOCO_OK;
@@ -1081,7 +1130,8 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     const int rc = select_layers(C);
     if (rc != CHOCO_OK) return rc;
   }
-  if (ahead) {
+  const bool due = look_ahead_due(ctx, ahead);
+  if (due) {
     const int rc = look_ahead_mark(ctx);
     if (rc != CHOCO_OK) return rc;
   }
@@ -1104,12 +1154,12 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   }
   ctx->values_in_qv = fused_apply && COMP == Q_RANDK;
   LAUNCH_CHECK(ctx);
-  if (ahead) {   // the next step's masks, enqueued after this step's own kernels (see look_ahead_mark)
-    const Args P = look_ahead_args(ctx, A);
+  if (due) {   // the next batch's masks, enqueued after this step's own kernels (see look_ahead_mark)
+    const uint64_t base = (ctx->t / kAheadSteps + 1) * kAheadSteps;
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
-    (void)select_layers(P);
-    rc = look_ahead_end(ctx, A);
+    for (int u = 0; u < kAheadSteps; ++u) (void)select_layers(look_ahead_args(ctx, A, base + (uint64_t)u));
+    rc = look_ahead_end(ctx, A, base);
     if (rc != CHOCO_OK) return rc;
   }
   return CHOCO_OK;
@@ -1184,7 +1234,7 @@ int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   A.beta = u.beta;
   A.lambda = u.lambda;
   A.deferred_sgd = deferred ? 1 : 0;
-  const int buf = (int)(ctx->t & 1u);      // the two copies take turns (they are one and the same
+  const int buf = (int)(ctx->t % kAheadBufs);   // the copies take turns (they are one and the same
   A.sel_idx = ctx->sel_idx_buf[buf];       // unless the configuration selects ahead)
   A.bitmap = ctx->bitmap_buf[buf];
   A.keptmap = ctx->keptmap_buf[buf];
@@ -1325,10 +1375,10 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->aux_stream = nullptr;
   ctx->launch_stream = ctx->stream;
   ctx->ev_fork = ctx->ev_ahead = nullptr;
-  ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = ctx->ahead_valid = false;
-  ctx->ahead_t = 0;
+  ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = false;
+  ctx->cur = ctx->nxt = AheadBatch{0, false};
   ctx->last_buf = 0;
-  ctx->ahead_map_buf = -1;
+  ctx->dirty_maps = 0;
   ctx->maxdeg = maxdeg;
   ctx->nnz = nnz;
   ctx->sparse = is_sparse(cfg->compressor);
@@ -1408,9 +1458,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.map_words = (A.ld + 31) / 32;
   A.bitmap = (uint32_t*)(base + L.bitmap);
   A.bitmap_words = L.bitmap_words;
-  ctx->sel_idx_buf[0] = ctx->sel_idx_buf[1] = A.sel_idx;
-  ctx->bitmap_buf[0] = ctx->bitmap_buf[1] = A.bitmap;
-  ctx->keptmap_buf[0] = ctx->keptmap_buf[1] = A.keptmap;
+  for (int b = 0; b < kAheadBufs; ++b) {
+    ctx->sel_idx_buf[b] = A.sel_idx;
+    ctx->bitmap_buf[b] = A.bitmap;
+    ctx->keptmap_buf[b] = A.keptmap;
+  }
   // what the kernels need of each long layer; those that share launches go into a device table
   std::vector<LongSel> long_tab;
   ctx->nbatched = 0;
@@ -1459,9 +1511,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     }
   }
   if (cfg->compressor == CHOCO_Q_RANDK) {
-    ctx->sel_idx_buf[1] = (int32_t*)(base + L.sel_idx2);
-    if (L.bitmap_words > 0) ctx->bitmap_buf[1] = (uint32_t*)(base + L.bitmap2);
-    else ctx->keptmap_buf[1] = (uint32_t*)(base + L.keptmap2);
+    for (int b = 1; b < kAheadBufs; ++b) {
+      ctx->sel_idx_buf[b] = (int32_t*)(base + L.sel_idx2 + (size_t)(b - 1) * L.sel_idx_bytes);
+      if (L.bitmap_words > 0) ctx->bitmap_buf[b] = (uint32_t*)(base + L.bitmap2 + (size_t)(b - 1) * L.bitmap_bytes);
+      else ctx->keptmap_buf[b] = (uint32_t*)(base + L.keptmap2 + (size_t)(b - 1) * L.keptmap_bytes);
+    }
     hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
@@ -1482,8 +1536,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.layer_work = (const LayerDesc*)(base + L.layer_work);
   A.layer_guess = (uint32_t*)(base + L.layer_guess);
   A.layer_scal = (double*)(base + L.layer_scal);
-  ctx->layer_scal_buf[0] = ctx->layer_scal_buf[1] = A.layer_scal;
-  if (ctx->can_lookahead && cfg->nlayers > 0) ctx->layer_scal_buf[1] = (double*)(base + L.layer_scal2);
+  for (int b = 0; b < kAheadBufs; ++b) {
+    ctx->layer_scal_buf[b] = A.layer_scal;
+    if (b > 0 && ctx->can_lookahead && cfg->nlayers > 0)
+      ctx->layer_scal_buf[b] = (double*)(base + L.layer_scal2 + (size_t)(b - 1) * L.layer_scal_bytes);
+  }
   if (cfg->nlayers > 0) {
     int64_t sel_base = 0;
     for (int32_t l = 0; l < cfg->nlayers; ++l) {
@@ -1987,7 +2044,7 @@ int choco_get_step(choco_ctx* ctx, uint64_t* t_host) {
 
 int choco_set_step(choco_ctx* ctx, uint64_t t) {
   if (!ctx) return CHOCO_E_INVAL;
-  if (t != ctx->t) ctx->ahead_valid = false;   // a selection made ahead was for the old counter
+  if (t != ctx->t) ctx->cur.valid = ctx->nxt.valid = false;   // selections made ahead were for the old counter
   ctx->t = t;
   return CHOCO_OK;
 }
@@ -1995,7 +2052,7 @@ int choco_set_step(choco_ctx* ctx, uint64_t t) {
 int choco_set_lookahead(choco_ctx* ctx, int enable) {
   if (!ctx) return CHOCO_E_INVAL;
   ctx->lookahead = ctx->can_lookahead && enable != 0;
-  if (!ctx->lookahead) ctx->ahead_valid = false;   // a selection already under way is joined and made again
+  if (!ctx->lookahead) ctx->cur.valid = ctx->nxt.valid = false;   // selections already under way are joined and made again
   return CHOCO_OK;
 }
 

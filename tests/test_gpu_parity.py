@@ -548,6 +548,39 @@ def test_random_masks_selected_ahead_or_not_are_the_same(order, mix):
         pair.close()
 
 
+@pytest.mark.parametrize("d,k", [(30011, 300), (400_003, 2000)])
+def test_random_masks_selected_ahead_in_batches(d, k):
+    # the masks are drawn four steps at a time, a batch ahead: whole batches used up one after the
+    # other, and batches cut short at their first, a middle and their last step by a moved step
+    # counter (forwards, into the middle of a batch, backwards), by the look-ahead switched off and
+    # on and by timed steps; with the bitmap of short rows and with the bit map in global memory,
+    # where a batch that is dropped half used leaves marks to clear
+    n = 3
+    X0 = synth.normal_state(n, d, seed=53)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=10, compressor=B.Q_RANDK, k=k)
+    grads = synth.GradientStream(n, d, seed=14, noise_std=0.05, bias_std=0.02)
+    moves = {14: 21, 19: 100, 24: 7, 29: 29}          # step of the test -> counter set before it
+    off, on = {17, 31, 36}, {18, 33, 37}
+    timed_on, timed_off = {26}, {27}
+    try:
+        for step in range(44):
+            if step in moves:
+                pair.gpu.set_step(moves[step])
+                pair.ref.t = moves[step]
+            if step in off:
+                pair.gpu.set_lookahead(False)
+            if step in on:
+                pair.gpu.set_lookahead(True)
+            if step in timed_on:
+                pair.gpu.set_profiling(True)
+            if step in timed_off:
+                pair.gpu.set_profiling(False)
+            det = pair.step(grads.next(), 0.05)
+            pair.check(det, tag="batched lookahead step %d (t = %d)" % (step, pair.ref.t - 1))
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("mix", SPARSE_MIXES)
 def test_random_masks_selected_ahead_on_rows_without_a_bitmap(mix):
     # above 327,680 entries the kept entries are marked in a bit map in global memory; it exists twice and a
