@@ -42,13 +42,16 @@ struct LongLayer {
   bool batched;     // its pass and its select share a launch with those of the other such layers
 };
 
-// random_a selects ahead in batches of this many steps (two event operations on the caller's
-// stream per batch instead of per step: they cost 11 us of idle queue each time, n = 64,
-// d = 270 k).
+// random_a selects ahead in batches of up to this many steps (two event operations on the
+// caller's stream per batch instead of per step: they cost 11 us of idle queue each time, n = 64,
+// d = 270 k).  Rows above 2^21 entries take batches of one step: there the event operations do
+// not show, and four candidate passes in a row (0.25 ms of Philox arithmetic each) beside the
+// first step of a batch slow its bandwidth-bound pass more than they save (n = 8, 31.8 M
+// entries in 14 layers: 0.877 against 0.927 ms per step).
 constexpr int kAheadSteps = 4;
 constexpr int kAheadBufs = 2 * kAheadSteps;
 struct AheadBatch {
-  uint64_t base;   // selections of steps base .. base + kAheadSteps - 1
+  uint64_t base;   // selections of steps base .. base + (batch length) - 1
   bool valid;
 };
 
@@ -65,9 +68,9 @@ struct choco_ctx {
   Args args;              // kernel arguments (device pointers into the workspace)
   hipStream_t stream;
   // random_a: the mask of a step depends on (seed, step, worker) only, so while the steps of one
-  // batch (kAheadSteps of them) run on the caller's stream the selections of the NEXT batch
-  // already run on this one.  2 * kAheadSteps copies of the kept-index lists and of the bitmap
-  // take turns: step t uses copy t mod (2 * kAheadSteps).
+  // batch (ahead_steps of them) run on the caller's stream the selections of the NEXT batch
+  // already run on this one.  2 * ahead_steps copies of the kept-index lists and of the bitmap
+  // take turns: step t uses copy t mod (2 * ahead_steps).
   hipStream_t aux_stream;
   hipStream_t launch_stream;   // where LAUNCH puts kernels: the caller's stream, or aux_stream while selecting ahead
   hipEvent_t ev_fork, ev_ahead;
@@ -75,6 +78,7 @@ struct choco_ctx {
   bool can_lookahead;     // the configuration allows it (random_a)
   bool ahead_pending;     // the batch `nxt` is in flight (or done) on aux_stream and not yet joined
   AheadBatch cur, nxt;    // the batch whose selections the steps are using / the one selected beside them
+  int ahead_steps;        // steps per batch: kAheadSteps, or 1 for long rows; step t uses copy t mod (2 * ahead_steps)
   int32_t* sel_idx_buf[kAheadBufs];
   uint32_t* bitmap_buf[kAheadBufs];
   uint32_t* keptmap_buf[kAheadBufs];
@@ -436,7 +440,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   // second copies for the look-ahead selection of random_a: the kept-index lists, the bitmap
   // (short rows in whole-vector mode) or the bit map in global memory, the per-layer scalars
   const bool ahead = c.compressor == CHOCO_Q_RANDK;
-  const size_t more = kAheadBufs - 1;
+  const size_t more = c.d > ((int64_t)1 << 21) ? 1 : kAheadBufs - 1;   // (long rows select one step ahead)
   L.sel_idx_bytes = align_up((size_t)c.n * (size_t)kept * sizeof(int32_t));
   L.bitmap_bytes = align_up((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
   L.keptmap_bytes = align_up(map_bytes);
@@ -802,17 +806,20 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
 // look_ahead_begin: was this step's selection made ahead?  It joins the second stream and, if a
 // selection made ahead is being dropped (counter set, look-ahead or timing switched), clears
 // the marks it left in its copy of the bit map (no xhat update ever would).
-bool in_batch(const AheadBatch& b, uint64_t t) { return b.valid && t >= b.base && t - b.base < (uint64_t)kAheadSteps; }
+bool in_batch(const choco_ctx* ctx, const AheadBatch& b, uint64_t t) {
+  return b.valid && t >= b.base && t - b.base < (uint64_t)ctx->ahead_steps;
+}
+int ahead_buf(const choco_ctx* ctx, uint64_t t) { return (int)(t % (uint64_t)(2 * ctx->ahead_steps)); }
 
 int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) {
   const uint64_t t = ctx->t;
-  if (ahead && in_batch(ctx->nxt, t)) {   // the first step of a batch: wait for its selections, once
+  if (ahead && in_batch(ctx, ctx->nxt, t)) {   // the first step of a batch: wait for its selections, once
     const int rc = join_lookahead(ctx);
     if (rc != CHOCO_OK) return rc;
     ctx->cur = ctx->nxt;
     ctx->nxt.valid = false;
   }
-  *selected = ahead && in_batch(ctx->cur, t);
+  *selected = ahead && in_batch(ctx, ctx->cur, t);
   if (!*selected) {
     // this step selects in line (with the same control blocks and candidate lists): nothing may
     // be under way, and what was selected ahead for other steps is dropped
@@ -827,7 +834,7 @@ int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) 
     ctx->dirty_maps = 0;
     ctx->cur.valid = ctx->nxt.valid = false;
   } else {
-    ctx->dirty_maps &= ~(1u << (unsigned)(t % kAheadBufs));   // this step's own pass clears the marks it uses
+    ctx->dirty_maps &= ~(1u << (unsigned)ahead_buf(ctx, t));   // this step's own pass clears the marks it uses
   }
   return CHOCO_OK;
 }
@@ -837,8 +844,8 @@ int look_ahead_begin(choco_ctx* ctx, const Args& A, bool ahead, bool* selected) 
 // last step before a batch boundary (the start of a run: one step of head start).
 bool look_ahead_due(const choco_ctx* ctx, bool ahead) {
   if (!ahead || ctx->nxt.valid) return false;
-  const uint64_t t = ctx->t, nb = (t / kAheadSteps + 1) * kAheadSteps;
-  return in_batch(ctx->cur, t) || t == nb - 1;
+  const uint64_t B = (uint64_t)ctx->ahead_steps, t = ctx->t, nb = (t / B + 1) * B;
+  return in_batch(ctx, ctx->cur, t) || t == nb - 1;
 }
 
 // The argument block of the selection of a later step tn: no local update (the keys are Philox
@@ -850,7 +857,7 @@ Args look_ahead_args(const choco_ctx* ctx, const Args& A, uint64_t tn) {
   P.deferred_sgd = 0;
   P.t_lo = (uint32_t)(tn & 0xFFFFFFFFu);
   P.t_hi = (uint32_t)(tn >> 32);
-  const int buf = (int)(tn % kAheadBufs);
+  const int buf = ahead_buf(ctx, tn);
   P.sel_idx = ctx->sel_idx_buf[buf];
   P.bitmap = ctx->bitmap_buf[buf];
   P.keptmap = ctx->keptmap_buf[buf];
@@ -884,7 +891,7 @@ int look_ahead_end(choco_ctx* ctx, const Args& A, uint64_t base) {
   ctx->nxt.base = base;
   ctx->nxt.valid = true;
   if (!A.bitmap_words)
-    for (int u = 0; u < kAheadSteps; ++u) ctx->dirty_maps |= 1u << (unsigned)((base + (uint64_t)u) % kAheadBufs);
+    for (int u = 0; u < ctx->ahead_steps; ++u) ctx->dirty_maps |= 1u << (unsigned)ahead_buf(ctx, base + (uint64_t)u);
   return CHOCO_OK;
 }
 
@@ -958,10 +965,10 @@ int gossip_sparse(choco_ctx* ctx, const Args& F) {
   if (due) {
     // the selections of the next batch of steps, into those steps' copies of the lists and of the
     // map, side by side with this step and the ones after it (from the mark set above)
-    const uint64_t base = (ctx->t / kAheadSteps + 1) * kAheadSteps;
+    const uint64_t base = (ctx->t / (uint64_t)ctx->ahead_steps + 1) * (uint64_t)ctx->ahead_steps;
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
-    for (int u = 0; u < kAheadSteps; ++u) {
+    for (int u = 0; u < ctx->ahead_steps; ++u) {
       const Args P = look_ahead_args(ctx, A, base + (uint64_t)u);
       launch_select<COMP, NT>(ctx, P, P, KID_SEL_COMPACT, false);
     }
@@ -1155,10 +1162,10 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
   ctx->values_in_qv = fused_apply && COMP == Q_RANDK;
   LAUNCH_CHECK(ctx);
   if (due) {   // the next batch's masks, enqueued after this step's own kernels (see look_ahead_mark)
-    const uint64_t base = (ctx->t / kAheadSteps + 1) * kAheadSteps;
+    const uint64_t base = (ctx->t / (uint64_t)ctx->ahead_steps + 1) * (uint64_t)ctx->ahead_steps;
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
-    for (int u = 0; u < kAheadSteps; ++u) (void)select_layers(look_ahead_args(ctx, A, base + (uint64_t)u));
+    for (int u = 0; u < ctx->ahead_steps; ++u) (void)select_layers(look_ahead_args(ctx, A, base + (uint64_t)u));
     rc = look_ahead_end(ctx, A, base);
     if (rc != CHOCO_OK) return rc;
   }
@@ -1234,7 +1241,7 @@ int run_gossip(choco_ctx* ctx, const LocalUpdate& u, bool deferred = false) {
   A.beta = u.beta;
   A.lambda = u.lambda;
   A.deferred_sgd = deferred ? 1 : 0;
-  const int buf = (int)(ctx->t % kAheadBufs);   // the copies take turns (they are one and the same
+  const int buf = ahead_buf(ctx, ctx->t);       // the copies take turns (they are one and the same
   A.sel_idx = ctx->sel_idx_buf[buf];       // unless the configuration selects ahead)
   A.bitmap = ctx->bitmap_buf[buf];
   A.keptmap = ctx->keptmap_buf[buf];
@@ -1377,6 +1384,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->ev_fork = ctx->ev_ahead = nullptr;
   ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = false;
   ctx->cur = ctx->nxt = AheadBatch{0, false};
+  ctx->ahead_steps = cfg->d > ((int64_t)1 << 21) ? 1 : kAheadSteps;
   ctx->last_buf = 0;
   ctx->dirty_maps = 0;
   ctx->maxdeg = maxdeg;
@@ -1511,7 +1519,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     }
   }
   if (cfg->compressor == CHOCO_Q_RANDK) {
-    for (int b = 1; b < kAheadBufs; ++b) {
+    for (int b = 1; b < 2 * ctx->ahead_steps; ++b) {
       ctx->sel_idx_buf[b] = (int32_t*)(base + L.sel_idx2 + (size_t)(b - 1) * L.sel_idx_bytes);
       if (L.bitmap_words > 0) ctx->bitmap_buf[b] = (uint32_t*)(base + L.bitmap2 + (size_t)(b - 1) * L.bitmap_bytes);
       else ctx->keptmap_buf[b] = (uint32_t*)(base + L.keptmap2 + (size_t)(b - 1) * L.keptmap_bytes);
@@ -1538,7 +1546,7 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.layer_scal = (double*)(base + L.layer_scal);
   for (int b = 0; b < kAheadBufs; ++b) {
     ctx->layer_scal_buf[b] = A.layer_scal;
-    if (b > 0 && ctx->can_lookahead && cfg->nlayers > 0)
+    if (b > 0 && b < 2 * ctx->ahead_steps && ctx->can_lookahead && cfg->nlayers > 0)
       ctx->layer_scal_buf[b] = (double*)(base + L.layer_scal2 + (size_t)(b - 1) * L.layer_scal_bytes);
   }
   if (cfg->nlayers > 0) {
