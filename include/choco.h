@@ -58,7 +58,10 @@ enum {
 
 /* How the mixing step of Algorithm 1, x_i += gamma * sum_j w_ij (xhat_j - xhat_i), is evaluated. */
 enum {
-  CHOCO_MIX_AUTO = 0,          /* INCREMENTAL_S for top_a/random_a, DIRECT otherwise        */
+  CHOCO_MIX_AUTO = 0,          /* DIRECT for sign / gsgd / identity and, up to 64 workers, for
+                                  top_a / random_a; INCREMENTAL_S for top_a / random_a with more
+                                  workers, for top_a in the printed order and for layer tables in
+                                  the printed order (choco_get_mix_form tells which)           */
   CHOCO_MIX_INCREMENTAL_S = 1, /* S_i += sum_j w_ij q_j (CSR order); x_i += gamma (S_i - xhat_i) */
   CHOCO_MIX_DIRECT = 2         /* acc = sum_j w_ij (xhat_j - xhat_i) in CSR order from 0    */
 };
@@ -106,8 +109,10 @@ typedef struct {
      pass of its own (same results).  Layers may have any length; for
      TOPK and RANDK one workgroup selects a layer of up to CHOCO_MAX_LAYER_LEN entries out
      of its registers and longer layers take the whole-vector select, in launches that they
-     share (they cost workspace for its candidate lists, a set per such layer).  IDENTITY and a non-default mix_form
-     are CHOCO_E_UNSUPPORTED with layers.  layer_k_host may be NULL for SIGN and QSGD.     */
+     share (they cost workspace for its candidate lists, a set per such layer).  With
+     layers, IDENTITY is CHOCO_E_UNSUPPORTED, SIGN and QSGD take CHOCO_MIX_AUTO only, and
+     TOPK / RANDK take CHOCO_MIX_DIRECT in the default order and up to 64 workers only.
+     layer_k_host may be NULL for SIGN and QSGD.     */
   int32_t nlayers;
   const int64_t *layer_start_host;
   const int64_t *layer_len_host;
