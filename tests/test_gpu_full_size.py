@@ -164,11 +164,11 @@ def test_messages_at_full_size(n, kw):
         pair.close()
 
 
-def long_run(n, d, topo, steps, gamma, lr, **kw):
+def long_run(n, d, topo, steps, gamma, lr, layers=None, **kw):
     """Free-running fused iterations at full size; the long-run statistics to 1e-4 and (the
     two sides never having parted) the final state bit for bit."""
     X0 = synth.normal_state(n, d, seed=20190709, std=0.05, shared=True)
-    pair = Pair(X0, topo, gamma, seed=7, **kw)
+    pair = Pair(X0, topo, gamma, seed=7, layers=layers, **kw)
     grads = GradientPool(n, d, seed=11, noise_std=0.01, bias_std=0.001)
     try:
         for t in range(steps):
@@ -191,8 +191,17 @@ def test_peer_to_peer_ring_topk_60_steps(mix):
 
 
 def test_peer_to_peer_torus_randk_60_steps():
-    # the masks of steps 1..59 are all drawn ahead on the second stream
+    # the masks of steps 4..59 are all drawn ahead on the second stream, four steps at a time
     long_run(64, 270_000, synth.torus_csr(8, 8), 60, 0.02, 0.1, compressor=B.Q_RANDK, k=2700)
+
+
+@pytest.mark.parametrize("comp", [B.Q_TOPK, B.Q_RANDK])
+def test_peer_to_peer_layer_wise_30_steps(comp):
+    # the 65 layers of the 0.27 M-parameter model, free-running: long layers streamed in shared
+    # launches, short ones in the layer kernel, the fused direct mix; random_a draws ahead in batches
+    layers = synth.layer_table(synth.resnet20_like_lengths(), fraction=0.01)
+    d = synth.layers_dim(layers)
+    long_run(64, d, synth.ring_csr(64), 30, 0.02, 0.1, layers=layers, compressor=comp)
 
 
 def test_layer_wise_sign_on_the_language_model_sizes():
