@@ -395,7 +395,7 @@ def test_layer_tables_without_alignment(name, q, order, mix_form):
 @pytest.mark.parametrize("mix_form", [binding.MIX_AUTO, binding.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1], OPERATORS[3], OPERATORS[4]])
 def test_layer_tables_without_alignment_long_layers_and_momentum(name, q, mix_form):
-    # layers above 40,960 entries that start off a 16-byte boundary take the streaming select on a
+    # layers above 10,240 entries that start off a 16-byte boundary take the streaming select on a
     # piece of the row whose first entries belong to the layer before
     layers, d = generic_table([30, 70001, 3, 41000, 5000, 90000], [0, 0, 1, 0, 0, 0], fraction=0.01, lead=1, tail=2)
     n = 4
