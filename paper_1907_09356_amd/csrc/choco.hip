@@ -437,7 +437,7 @@ Layout make_layout(const choco_config& c, int32_t nnz) {
   const size_t map_bytes = (size_t)c.n * (size_t)((ld + 31) / 32) * sizeof(uint32_t);   // a bit per entry
   L.keptmap = take(sparse && !L.bitmap_words ? map_bytes : 0);
   L.bitmap = take((size_t)c.n * (size_t)L.bitmap_words * sizeof(uint32_t));
-  // second copies for the look-ahead selection of random_a: the kept-index lists, the bitmap
+  // further copies for the selections random_a makes ahead: the kept-index lists, the bitmap
   // (short rows in whole-vector mode) or the bit map in global memory, the per-layer scalars
   const bool ahead = c.compressor == CHOCO_Q_RANDK;
   const size_t more = c.d > ((int64_t)1 << 21) ? 1 : kAheadBufs - 1;   // (long rows select one step ahead)
