@@ -1526,8 +1526,11 @@ __global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
 // synchronise afterwards); *good: the list holds the k largest entries.
 // By the first wave of a block (threads 0..63 call it): one sub-list per lane, prefix offsets by
 // a wave scan - one round trip to memory instead of a thread's 32 loads in turn.
+constexpr uint32_t kSpecPerSeg = 256;   // entries of a sub-list that k_sel_refine fetches before it knows the lengths
+
 __device__ __forceinline__ void list_layout_wave(const Args& A, const WorkerCtl* ctl, uint32_t* lens, uint32_t* pre,
-                                                 uint32_t* total_out, uint32_t* good_out) {
+                                                 uint32_t* total_out, uint32_t* good_out,
+                                                 uint32_t* short_out = nullptr) {
   const int lane = threadIdx.x & 63;
   const uint32_t raw = lane < kSegs ? ctl->seg_count[lane] : 0u;
   const uint32_t len = raw < A.seg_cap ? raw : A.seg_cap;
@@ -1548,7 +1551,11 @@ __device__ __forceinline__ void list_layout_wave(const Args& A, const WorkerCtl*
     *total_out = incl;
   }
   const bool fits = __ballot(raw > A.seg_cap) == 0ull;
-  if (lane == 0) *good_out = (fits && rawsum >= (unsigned long long)A.k) ? 1u : 0u;
+  const bool all_short = __ballot(raw > kSpecPerSeg) == 0ull;
+  if (lane == 0) {
+    *good_out = (fits && rawsum >= (unsigned long long)A.k) ? 1u : 0u;
+    if (short_out) *short_out = all_short ? 1u : 0u;
+  }
 }
 
 // Entry at flat position f of the concatenated sub-lists (pre = prefix offsets in LDS).
@@ -1815,10 +1822,27 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A0) {
   __shared__ uint32_t pre[kSegs + 1];
   __shared__ uint2 small[kSmallCap];
   __shared__ uint64_t s_prefix, s_kstar;
-  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good, s_small;
+  __shared__ uint32_t s_need, s_digit, s_above, s_emit, s_total, s_good, s_small, s_short;
   extern __shared__ uint32_t lbits[];   // bitmap_words words: kept entries of this worker (short rows)
   const int i = blockIdx.x;
   WorkerCtl* ctl = A.ctl + i;
+  // The first kSpecPerSeg entries of every sub-list are fetched before the lengths are known (32
+  // threads per sub-list, eight entries each; what lies beyond a list's end is old data inside
+  // the list's capacity and is masked below): one round trip to memory instead of two when no
+  // sub-list is longer, which is the rule at the list lengths this kernel is launched for.
+  // (Not for the long layers of a layer table: their lists are a few hundred entries, hundreds of
+  // workgroups fetch at once, and the 64 KiB per workgroup cost more than the round trip saved:
+  // 18.1 against 15.8 us.)
+  constexpr bool SPECULATE = !BATCH;
+  uint2 c[8];
+  bool have[8];
+  const int sseg = threadIdx.x >> 5, sj = threadIdx.x & 31;
+  static_assert(kSegs * 32 == 1024 && kSpecPerSeg == 8 * 32, "32 threads per sub-list, eight entries each");
+  if (SPECULATE) {
+    const uint2* seg = A.cand + ((int64_t)i * kSegs + sseg) * A.seg_cap;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c[u] = (uint32_t)(sj + 32 * u) < A.seg_cap ? seg[sj + 32 * u] : make_uint2(0u, 0u);
+  }
   for (int b = threadIdx.x; b < kBins; b += 1024) h[b] = 0;
   for (int64_t wd = threadIdx.x; wd < A.bitmap_words; wd += 1024) lbits[wd] = 0;
   if (threadIdx.x == 0) {
@@ -1827,7 +1851,7 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A0) {
     s_emit = 0;
     s_small = 0;
   }
-  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good);
+  if (threadIdx.x < 64) list_layout_wave(A, ctl, lens, pre, &s_total, &s_good, &s_short);
   __syncthreads();
   const uint32_t total = s_total;
   if (!s_good) {
@@ -1839,19 +1863,27 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A0) {
   auto bin_of = [&](uint32_t a) -> uint32_t { return cand_bin<COMP>(a, guess, shift); };
   // sweep 1: histogram of the candidates by their distance above the guess (eight
   // entries per thread in flight; a list of up to 8192 entries stays in registers)
-  uint2 c[8];
-  bool have[8];
-  const bool resident = total <= 1024u * 8u;
-  for (uint32_t base = 0; base < total; base += 1024u * 8u) {
+  const bool fetched = SPECULATE && s_short != 0u;   // the entries fetched above are the whole list
+  const bool resident = fetched || total <= 1024u * 8u;
+  if (fetched) {
+    const uint32_t len = lens[sseg];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
-      have[u] = f < total;
-      if (have[u]) c[u] = entry_at(f);
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
+      have[u] = (uint32_t)(sj + 32 * u) < len;
       if (have[u]) atomicAdd(&h[bin_of(c[u].x)], 1u);
+    }
+  } else {
+    for (uint32_t base = 0; base < total; base += 1024u * 8u) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t f = base + (uint32_t)u * 1024u + threadIdx.x;
+        have[u] = f < total;
+        if (have[u]) c[u] = entry_at(f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (have[u]) atomicAdd(&h[bin_of(c[u].x)], 1u);
+    }
   }
   __syncthreads();
   find_digit(h, grp, (uint32_t)A.k, &s_digit, &s_above);
@@ -1864,6 +1896,39 @@ __global__ __launch_bounds__(1024) void k_sel_refine(Args A0) {
     return;
   }
   // sweep 2: emit everything above the threshold bin, collect the bin itself
+  if (resident) {
+    // the list is in registers: a thread counts its entries above the bin, a scan over the wave
+    // and one LDS atomic per wave give it its slots (instead of a ballot and an atomic per entry)
+    uint32_t mine = 0;
+    bool above[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      above[u] = false;
+      if (have[u]) {
+        const uint32_t bin = bin_of(c[u].x);
+        above[u] = bin > tbin;
+        if (bin == tbin) {
+          const uint32_t pos = atomicAdd(&s_small, 1u);
+          if (pos < (uint32_t)kSmallCap) small[pos] = c[u];
+        }
+      }
+      mine += above[u] ? 1u : 0u;
+    }
+    const int lane = threadIdx.x & 63;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    uint32_t wave_base = 0;
+    if (lane == 63 && incl != 0u) wave_base = atomicAdd(&s_emit, incl);
+    wave_base = __shfl(wave_base, 63, 64);
+    uint32_t slot = wave_base + incl - mine;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (above[u]) store_kept<COMP>(A, i, slot++, c[u].x, c[u].y, lbits);
+  } else
   for (uint32_t base = 0; base < total; base += 1024u * 8u) {
     if (!resident) {
 #pragma unroll
