@@ -201,6 +201,24 @@ def test_layered_workspace_needs_no_candidate_lists():
     assert B.workspace_bytes(c2) < flat
 
 
+def test_random_k_workspace_holds_the_selections_made_ahead():
+    # random_a selects four steps ahead on rows up to 2^21 entries (eight copies of the kept lists
+    # and maps), one step ahead above (two copies); top_a keeps one copy
+    n, d, k = 8, 100_000, 1000
+    base, _ = cfg(n=n, d=d, k=k, compressor=B.Q_TOPK)
+    rk, _ = cfg(n=n, d=d, k=k, compressor=B.Q_RANDK)
+    lists = n * k * 4                               # kept indices of one step
+    bitmap = n * ((d + 31) // 32) * 4               # kept-entry bitmap of one step
+    extra = B.workspace_bytes(rk) - B.workspace_bytes(base)
+    assert extra >= 7 * (lists + bitmap)            # (random_a also keeps Qv, the kept values by entry)
+    d2 = (1 << 21) + 4
+    base2, _ = cfg(n=n, d=d2, k=k, compressor=B.Q_TOPK, mix_form=B.MIX_INCREMENTAL_S)
+    rk2, _ = cfg(n=n, d=d2, k=k, compressor=B.Q_RANDK, mix_form=B.MIX_INCREMENTAL_S)
+    extra2 = B.workspace_bytes(rk2) - B.workspace_bytes(base2)
+    keptmap = n * ((d2 + 31) // 32) * 4
+    assert lists + keptmap <= extra2 < 3 * (lists + keptmap)
+
+
 def test_paper_message_bits_is_host_arithmetic():
     # Appendix C: d + 32 (sign), 2*32*k (top_a), 32*k (random_a), b bits per entry (gsgd_b)
     assert B.paper_message_bits(B.Q_SIGN, 272474) == 272474 + 32
