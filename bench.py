@@ -13,9 +13,11 @@ the largest single-GPU configuration and the one where the HBM roofline is meani
 same line also carries, in "alternatives", that workload in the other supported formulations
 (Algorithm 1 in its printed order; the other form of the mix) and, in "configs", a compact
 record of every other benchmark shape (d = 270,000 with n = 8 sign and n = 64 ring / torus x
-top-k / random-k; d = 28,000,000 with gsgd).  --all adds the layer-wise workloads
-("other_workloads") and the time of the message encoder and decoder ("wire"); --only runs the
-one workload and nothing else (the form the rocprofv3 runs use).
+top-k / random-k; d = 28,000,000 with gsgd) and, in "layer_wise", of the operators applied
+layer by layer on the 65 layers of the 0.27 M-parameter model.  --all adds the layer-wise
+workloads at the language-model sizes ("other_workloads") and the time of the message encoder
+and decoder ("wire"); --only runs the one workload and nothing else (the form the rocprofv3
+runs use).
 """
 import argparse
 import json
@@ -525,6 +527,7 @@ def compact_record(name, w, r, steps):
 
 CONFIG_WORKLOADS = ["dc_sign", "p2p_ring_topk", "p2p_torus_topk", "p2p_ring_randk", "p2p_torus_randk",
                     "large_qsgd"]
+LAYER_WORKLOADS = ["dc_sign_layers", "p2p_ring_sign_layers", "p2p_ring_topk_layers", "p2p_ring_randk_layers"]
 
 
 def main():
@@ -646,6 +649,12 @@ def main():
                         order=order, momentum=args.momentum)
             confs.append(compact_record(name, ow, r, k))
         line["configs"] = confs
+        # the operator applied layer by layer (Section 5 set-up), on the 65 layers of the 0.27 M model
+        line["layer_wise"] = []
+        for name in LAYER_WORKLOADS:
+            ow = WORKLOADS[name]
+            r = run_gpu(ow, 100, 10, fused=not args.unfused, mix_form=None, order=order, momentum=args.momentum)
+            line["layer_wise"].append(compact_record(name, ow, r, 100))
     if not args.only and not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, res["mix"], args.order)
     if args.all and not args.only:
@@ -654,7 +663,7 @@ def main():
                         for name in ("dc_sign", "large_qsgd", "p2p_ring_topk", "p2p_ring_randk", "large_topk")]
         others = []
         for name, ow in WORKLOADS.items():
-            if name == args.workload or name in CONFIG_WORKLOADS:
+            if name == args.workload or name in CONFIG_WORKLOADS or name in LAYER_WORKLOADS:
                 continue
             k = min(args.steps, 100)
             r = run_gpu(ow, k, min(args.warmup, 10), fused=not args.unfused, mix_form=None, order=order,
