@@ -723,7 +723,7 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
   const dim3 stat_grid((unsigned)A.ngroups, (unsigned)A.n);
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX) {
     if (needs_stat) {
-      LAUNCH(ctx, fused ? KID_DENSE_STAT_SGD : KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid,
+      LAUNCH(ctx, fused ? KID_DENSE_STAT_SGD : KID_DENSE_STAT, (k_dense_stat<STATK, NT, kStatCpw>), stat_grid,
              dim3(kStatThreads), 0, F);
       if (!A.fold_finalise)
         LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
@@ -744,7 +744,7 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
     } else {
       launch_mix_direct_global(ctx, A);
       if (needs_stat)
-        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid, dim3(kStatThreads), 0, A);
+        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT, kStatCpw>), stat_grid, dim3(kStatThreads), 0, A);
     }
     if (needs_stat)
       LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);

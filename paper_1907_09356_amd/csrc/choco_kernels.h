@@ -37,7 +37,8 @@ constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kerne
 constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass (long rows; short rows take 2)
 constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
 constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
-constexpr int kStatThreads = 256;   // one wave per 4 chunks of a 16-chunk group
+constexpr int kStatCpw = 1;          // chunks per wave in the norm passes: a wave per chunk of a 16-chunk group
+constexpr int kStatThreads = 64 * (16 / kStatCpw);
 constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
 constexpr int kRefineParts = 16;    // blocks per worker of the select when the candidate lists are long
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
@@ -733,20 +734,23 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
 }
 
 // Dense operators, statistic pass (compress-then-mix order): v = x - xhat, one
-// block per group of 16 chunks (4096 entries), one wave per 4 chunks, all four
-// in flight at once.  grid (ngroups, n), block 256.
-template <int COMP, bool NT>
-__global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
+// block per group of 16 chunks (4096 entries), one wave per CPW chunks, all of them
+// in flight at once.  grid (ngroups, n), block 64 * 16 / CPW.  One chunk per wave (1024 threads)
+// measured faster than four (256 threads) at both ends: n = 8, d = 270 k 10.8 against 11.8 us
+// (the launch is a single round of workgroups and lasts as long as one of them), d = 28 M 571
+// against 597 us.
+template <int COMP, bool NT, int CPW>
+__global__ __launch_bounds__(64 * (kGroup / CPW)) void k_dense_stat(Args A) {
   __shared__ double cs[kGroup];
   const int i = blockIdx.y, g = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const float* x = A.X + (int64_t)i * A.ld;
   const float* xh = A.Xhat + (int64_t)i * A.ld;
-  vf4 a[4], b[4];
-  int e[4];
+  vf4 a[CPW], b[CPW];
+  int e[CPW];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int c = g * kGroup + 4 * wave + u;
+  for (int u = 0; u < CPW; ++u) {
+    const int c = g * kGroup + CPW * wave + u;
     e[u] = c < A.nchunks ? c * kChunk + lane * 4 : A.d;   // chunks past the end hold nothing
     if (e[u] < A.d) {
       a[u] = load4<NT>(x + e[u]);
@@ -755,13 +759,13 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
   }
   if (A.G) {   // fused local update: x <- x - lr g, stored for the apply pass
     float* xw = A.X + (int64_t)i * A.ld;
-    vf4 g[4];   // all gradient loads before the first store (see compact_chunk); the momentum
+    vf4 g[CPW];   // all gradient loads before the first store (see compact_chunk); the momentum
                 // memory, when there is one, is read in turn: registers for it would cost occupancy
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < CPW; ++u)
       if (e[u] < A.d) g[u] = load4<true>(A.G + (int64_t)i * A.ld + e[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < CPW; ++u) {
       if (e[u] < A.d) {
         vf4 mm = vf4{0.f, 0.f, 0.f, 0.f};
         if (A.M) mm = load4<NT>(A.M + (int64_t)i * A.ld + e[u]);
@@ -772,14 +776,14 @@ __global__ __launch_bounds__(kStatThreads) void k_dense_stat(Args A) {
     }
   }
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < CPW; ++u) {
     double t = 0.0;
     if (e[u] < A.d) {
       const vf4 v = a[u] - b[u];
       t = lane_terms<COMP>(v, e[u], A.d);
     }
     t = wave_tree_sum(t);
-    if (lane == 0) cs[4 * wave + u] = t;
+    if (lane == 0) cs[CPW * wave + u] = t;
   }
   __syncthreads();
   if (wave == 0) {

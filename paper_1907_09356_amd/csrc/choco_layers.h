@@ -439,9 +439,9 @@ void k_layer_compress(Args A, int32_t first, int32_t nblock) {
 // ---------------------------------------------------------------------------
 
 // v = x - xhat over one group (up to 16 chunks = 4096 entries) of one layer: chunk and
-// group sums of the layer's norm tree.  One wave per 4 chunks, all four in flight at once
-// (the shape of k_dense_stat); carries the fused local update.  The work items tile every
-// row, padding included, so the update reaches every entry.  grid (ngroup_items, n), block 256.
+// group sums of the layer's norm tree.  One wave per chunk (the shape of k_dense_stat);
+// carries the fused local update.  The work items tile every row, padding included, so the
+// update reaches every entry.  grid (ngroup_items, n), block kStatThreads.
 template <int COMP, bool NT>
 __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
   __shared__ double cs[kGroup];
@@ -449,11 +449,12 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
   const LayerGroup item = A.layer_groups[blockIdx.x];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int64_t row = (int64_t)i * A.ld + item.off;
-  vf4 a[4], b[4];
-  int e[4];   // index of the lane's first entry counted from the group's start
+  constexpr int CPW = kStatCpw;
+  vf4 a[CPW], b[CPW];
+  int e[CPW];   // index of the lane's first entry counted from the group's start
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    e[u] = (4 * wave + u) * kChunk + lane * 4;
+  for (int u = 0; u < CPW; ++u) {
+    e[u] = (CPW * wave + u) * kChunk + lane * 4;
     if (e[u] < item.rem) {
       if (A.layers_generic) {
         // the layer may start anywhere: entry by entry, and none past the layer's end (the next
@@ -472,12 +473,12 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
     }
   }
   if (A.G) {   // (never with a generic table: the local update is then a pass of its own)
-    vf4 g[4];   // all gradient loads before the first store; the momentum memory is read in turn
+    vf4 g[CPW];   // all gradient loads before the first store; the momentum memory is read in turn
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < CPW; ++u)
       if (e[u] < item.rem) g[u] = load4<true>(A.G + row + e[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < CPW; ++u) {
       if (e[u] < item.rem) {
         vf4 mm = vf4{0.f, 0.f, 0.f, 0.f};
         if (A.M) mm = load4<NT>(A.M + row + e[u]);
@@ -488,14 +489,14 @@ __global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
     }
   }
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < CPW; ++u) {
     double t = 0.0;
     if (e[u] < item.rem) {
       const vf4 v = a[u] - b[u];
       t = lane_terms<COMP>(v, e[u], item.rem);
     }
     t = wave_tree_sum(t);
-    if (lane == 0) cs[4 * wave + u] = t;
+    if (lane == 0) cs[CPW * wave + u] = t;
   }
   __syncthreads();
   if (wave == 0) {
