@@ -777,11 +777,17 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
   const int cvecs = (ctx->fallback_chain || COMP == Q_RANDK) ? kCompactVecs : 2;
   const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
   const size_t pad = ahead_lds_pad(ctx, A.d);
+  // top_a on long rows: the same 4096-entry chunks as one 4-vector per thread of a 1024-thread
+  // workgroup (measured against four per thread of 256 threads: 580 against 597 us at d = 28 M;
+  // two per thread of 512: 603; short rows gain nothing from wider workgroups: 47.9 against 46.2 us)
+  constexpr bool kWide = COMP == Q_TOPK;
   if (fuse_mix) {
     if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 2>), cgrid, dim3(256), 0, C);
+    else if (kWide) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, 1, false, 1024>), cgrid, dim3(1024), 0, C);
     else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, COMP == Q_TOPK, NT, kCompactVecs>), cgrid, dim3(256), 0, C);
   } else {
     if (cvecs == 2) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 2>), cgrid, dim3(256), pad, C);
+    else if (kWide) LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 1, false, 1024>), cgrid, dim3(1024), pad, C);
     else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), cgrid, dim3(256), pad, C);
   }
   if (ctx->fallback_chain) {
@@ -1027,8 +1033,11 @@ void long_layer_pass(choco_ctx* ctx, const Args& C, int which) {
   if (B.k == 0 || B.batched) return;
   const Args Cl = long_layer_args(ctx, C, which);
   const int kid_compact = Cl.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT;
-  const int32_t nvec = (B.len + 3) >> 2;
-  if (B.plan.fallback_chain)
+  const int32_t nvec = (B.sel.d + 3) >> 2;   // (with the entries before the layer in its first 4-vector)
+  if (B.plan.fallback_chain && COMP == Q_TOPK)   // (the shape of the whole-row pass on long rows)
+    LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, 1, false, 1024>), chunk_grid(nvec, C.n, kCompactVecs),
+           dim3(1024), 0, Cl);
+  else if (B.plan.fallback_chain)
     LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), chunk_grid(nvec, C.n, kCompactVecs),
            dim3(256), ahead_lds_pad(ctx, B.len), Cl);
   else

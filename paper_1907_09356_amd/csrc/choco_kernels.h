@@ -1313,7 +1313,7 @@ __device__ __forceinline__ void entry_bits(const Args& A, int i, int m, uint32_t
 // Append the candidates (key32 >= guess) among the 256 * VECS 4-vectors of
 // one chunk of worker i to sub-list chunk % kSegs.  Hits are staged in LDS and
 // flushed with one global atomic per block.
-template <int COMP, bool DO_MIX, bool NT, bool FIRST, int VECS>
+template <int COMP, bool DO_MIX, bool NT, bool FIRST, int VECS, int THREADS = 256>
 __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, uint2* stage,
                                               uint32_t* s_count, uint32_t* s_base) {
   WorkerCtl* ctl = A.ctl + i;
@@ -1322,7 +1322,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
   uint2* cand = A.cand + ((int64_t)i * kSegs + seg) * A.seg_cap;
   const int nvec = (A.d + 3) >> 2;
   // a wave's VECS 4-vectors are consecutive 1 KiB pieces of the row
-  const int m0 = chunk * (256 * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
+  const int m0 = chunk * (THREADS * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
   uint32_t a[VECS][4];
   if (COMP == Q_TOPK) {
     // all loads of the chunk first, then the arithmetic and the stores: a store to X between
@@ -1401,7 +1401,7 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
     if (threadIdx.x == 0) *s_base = atomicAdd(&ctl->seg_count[seg], count);
     __syncthreads();
     const uint32_t base = *s_base;
-    for (uint32_t t = threadIdx.x; t < count; t += 256)
+    for (uint32_t t = threadIdx.x; t < count; t += THREADS)
       if (base + t < A.seg_cap) cand[base + t] = stage[t];
   }
 }
@@ -1412,15 +1412,15 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
 // the blocks and the occupancy: 49 against 57 us at n = 64, d = 270 k).
 // BATCH: grid.z counts the long layers of A.long_tab, grid.x covers the longest of them (the
 // workgroups past a shorter layer's end leave at once).
-template <int COMP, bool DO_MIX, bool NT, int VECS, bool BATCH = false>
-__global__ __launch_bounds__(256) void k_sel_compact(Args A0) {
+template <int COMP, bool DO_MIX, bool NT, int VECS, bool BATCH = false, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void k_sel_compact(Args A0) {
   __shared__ uint2 stage[kStageCap];
   __shared__ uint32_t s_count, s_base;
   const Args A = BATCH ? long_view(A0, A0.long_tab[blockIdx.z]) : A0;
-  if (BATCH && (int64_t)blockIdx.x * (256 * VECS) >= (int64_t)((A.d + 3) >> 2)) return;
+  if (BATCH && (int64_t)blockIdx.x * (THREADS * VECS) >= (int64_t)((A.d + 3) >> 2)) return;
   if (threadIdx.x == 0) s_count = 0;
   __syncthreads();
-  compact_chunk<COMP, DO_MIX, NT, true, VECS>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
+  compact_chunk<COMP, DO_MIX, NT, true, VECS, THREADS>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
 }
 
 // The rebuild pass of the fallback: only workers in mode 1; a few blocks per

@@ -411,6 +411,34 @@ def test_layer_tables_without_alignment_long_layers_and_momentum(name, q, mix_fo
         pair.close()
 
 
+@pytest.mark.parametrize("lead", [1, 3])
+def test_long_layers_off_alignment_end_on_a_block_boundary(lead):
+    # long layers whose lengths are whole numbers of 2048- and 4096-entry pieces of the streaming
+    # pass, started 1 and 3 entries off a 16-byte boundary: their last entries fall into one more
+    # piece.  From the second step on the gradient makes those entries the largest of their layers,
+    # so a pass that stops a piece short loses kept entries.  One layer takes the multi-block select with launches of its own (3 % of
+    # 606,208), the others share launches.
+    lengths = [606208, 12288, 20480, 40960]
+    layers, d = generic_table(lengths, [0, 0, 5, 0], fraction=0.03, lead=lead, tail=2)
+    n = 3
+    X0 = synth.normal_state(n, d, seed=35)
+    pair = Pair(X0, synth.ring_csr(n), 0.25, seed=8, layers=layers, compressor=binding.Q_TOPK)
+    grads = synth.GradientStream(n, d, seed=36, noise_std=0.05, bias_std=0.02)
+    ends = np.asarray([a + ln - 1 for a, ln in zip(layers[0], layers[1])])
+    try:
+        for t in range(4):
+            G = grads.next()
+            if t >= 1:      # (step 0 scans the rows themselves: no threshold guess yet)
+                G[:, ends] = -1000.0 * (t + 1)
+                G[:, ends - 1] = 800.0 * (t + 1)
+            det = pair.step(G, 0.05)
+            pair.check(det, tag="block-boundary layers step %d" % t)
+            if t >= 1:
+                assert np.all(np.isin(ends, det["sel"][0]))     # (the oracle keeps them, so the parity check bites)
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("name,q", OPERATORS)
 def test_messages_of_a_layer_table_without_alignment(name, q):
     from oracle import choco_ref as ref
