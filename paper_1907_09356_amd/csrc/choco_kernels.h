@@ -1180,12 +1180,12 @@ __global__ __launch_bounds__(256) void k_mix_direct_global(Args A) {
 // grid (ceil(nvec / (256 * VECS)), n).  VECS 4-vectors per thread, a wave's pieces consecutive
 // (VECS KiB per array and wave): 4 for long rows (6.1 against 6.0 TB/s at d = 28 M), 2 for
 // short ones (twice the blocks: 50 against 53 us at n = 64, d = 270 k).
-template <bool NT, int VECS>
-__global__ __launch_bounds__(256) void k_mix_incremental(Args A) {
+template <bool NT, int VECS, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void k_mix_incremental(Args A) {
   const int i = blockIdx.y;
   const int nvec = (A.d + 3) >> 2;
   // a wave's VECS 4-vectors are consecutive 1 KiB pieces (wave-contiguous)
-  const int m0 = blockIdx.x * (256 * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
+  const int m0 = blockIdx.x * (THREADS * VECS) + (threadIdx.x >> 6) * (64 * VECS) + (threadIdx.x & 63);
   vf4 x[VECS], s[VECS], xh[VECS];
 #pragma unroll
   for (int u = 0; u < VECS; ++u) {
@@ -1407,9 +1407,11 @@ __device__ __forceinline__ void compact_chunk(const Args& A, int i, int chunk, u
 }
 
 // The one pass of the fast path: every worker, one block per chunk.
-// grid (ceil(nvec / (256 * VECS)), n), block 256.  VECS 4-vectors per thread: 4 for long rows
-// (more loads in flight per thread: 6.0 against 5.5 TB/s at d = 28 M), 2 for short ones (twice
-// the blocks and the occupancy: 49 against 57 us at n = 64, d = 270 k).
+// grid (ceil(nvec / (THREADS * VECS)), n), block THREADS.  Chunks of 4096 entries for long rows,
+// of 2048 for short ones (twice the blocks and the occupancy: 49 against 57 us at n = 64,
+// d = 270 k).  A long row's chunk: top_a one 4-vector per thread of 1024 threads (6.2 TB/s at
+// d = 28 M; four per thread of 256 threads 6.0; two per thread 5.5), random_a four per thread of
+// 256 threads (its pass draws Philox words beside another pass and should get in its way little).
 // BATCH: grid.z counts the long layers of A.long_tab, grid.x covers the longest of them (the
 // workgroups past a shorter layer's end leave at once).
 template <int COMP, bool DO_MIX, bool NT, int VECS, bool BATCH = false, int THREADS = 256>
