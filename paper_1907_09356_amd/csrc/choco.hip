@@ -723,8 +723,8 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
   const dim3 stat_grid((unsigned)A.ngroups, (unsigned)A.n);
   if (ctx->cfg.order == CHOCO_ORDER_COMPRESS_THEN_MIX) {
     if (needs_stat) {
-      LAUNCH(ctx, fused ? KID_DENSE_STAT_SGD : KID_DENSE_STAT, (k_dense_stat<STATK, NT, kStatCpw>), stat_grid,
-             dim3(kStatThreads), 0, F);
+      LAUNCH(ctx, fused ? KID_DENSE_STAT_SGD : KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid,
+             dim3(stat_threads(NT)), 0, F);
       if (!A.fold_finalise)
         LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
     }
@@ -744,7 +744,7 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
     } else {
       launch_mix_direct_global(ctx, A);
       if (needs_stat)
-        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT, kStatCpw>), stat_grid, dim3(kStatThreads), 0, A);
+        LAUNCH(ctx, KID_DENSE_STAT, (k_dense_stat<STATK, NT>), stat_grid, dim3(stat_threads(NT)), 0, A);
     }
     if (needs_stat)
       LAUNCH(ctx, KID_DENSE_FINALISE, (k_dense_finalise<STATK>), dim3((unsigned)A.n), dim3(256), 0, A);
@@ -1000,7 +1000,7 @@ int gossip_layers_dense(choco_ctx* ctx, const Args& F) {
   }
   const Args& C = x_touched ? A : F;
   LAUNCH(ctx, C.G ? KID_LAYER_STAT_SGD : KID_LAYER_STAT, (k_layer_stat<COMP, NT>),
-         dim3((unsigned)A.ngroup_items, (unsigned)A.n), dim3(kStatThreads), 0, C);
+         dim3((unsigned)A.ngroup_items, (unsigned)A.n), dim3(stat_threads(NT)), 0, C);
   LAUNCH(ctx, KID_LAYER_FINALISE, (k_layer_finalise<COMP>), dim3((unsigned)A.nlayers, (unsigned)A.n), dim3(256), 0, A);
   if (!mix_first && ctx->rpw) {
     if (A.codes) launch_apply_mix<COMP, true, NT, true>(ctx, A);

@@ -37,8 +37,13 @@ constexpr int kStreamVecs = 2;    // 4-vectors per thread in the streaming kerne
 constexpr int kCompactVecs = 4;   // 4-vectors per thread in the select pass (long rows; short rows take 2)
 constexpr int kStageCap = 1024;   // candidates one block stages in LDS before its single append
 constexpr int kSmallCap = 1024;   // entries of the threshold bin the select ranks directly in LDS
-constexpr int kStatCpw = 1;          // chunks per wave in the norm passes: a wave per chunk of a 16-chunk group
-constexpr int kStatThreads = 64 * (16 / kStatCpw);
+// Chunks per wave in the norm passes (a workgroup takes a group of 16 chunks): one, in
+// 1024-thread workgroups, where the state is streamed past the caches (large states, and the
+// small ones that are latency-bound), two, in 512-thread workgroups, where it is read through
+// them (n = 64, d = 270 k, layer by layer: 47 against 52 us; the other way round the large
+// and the small states lose 3-4 %).
+constexpr int stat_cpw(bool nt) { return nt ? 1 : 2; }
+constexpr int stat_threads(bool nt) { return 64 * (16 / stat_cpw(nt)); }
 constexpr int kFallbackBlocks = 64; // blocks per worker of the (normally idle) fallback passes
 constexpr int kRefineParts = 16;    // blocks per worker of the select when the candidate lists are long
 constexpr int kSegs = 32;         // candidate sub-lists per worker (spreads the append counter)
@@ -735,12 +740,13 @@ __global__ __launch_bounds__(256) void k_dense_finalise(Args A) {
 
 // Dense operators, statistic pass (compress-then-mix order): v = x - xhat, one
 // block per group of 16 chunks (4096 entries), one wave per CPW chunks, all of them
-// in flight at once.  grid (ngroups, n), block 64 * 16 / CPW.  One chunk per wave (1024 threads)
-// measured faster than four (256 threads) at both ends: n = 8, d = 270 k 10.8 against 11.8 us
-// (the launch is a single round of workgroups and lasts as long as one of them), d = 28 M 571
-// against 597 us.
-template <int COMP, bool NT, int CPW>
-__global__ __launch_bounds__(64 * (kGroup / CPW)) void k_dense_stat(Args A) {
+// in flight at once (CPW = stat_cpw(NT)).  grid (ngroups, n), block stat_threads(NT).  One chunk
+// per wave (1024 threads) against four (256 threads): n = 8, d = 270 k 10.8 against 11.8 us (the
+// launch is a single round of workgroups and lasts as long as one of them), d = 28 M 571 against
+// 597 us.
+template <int COMP, bool NT>
+__global__ __launch_bounds__(stat_threads(NT)) void k_dense_stat(Args A) {
+  constexpr int CPW = stat_cpw(NT);
   __shared__ double cs[kGroup];
   const int i = blockIdx.y, g = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

@@ -439,17 +439,17 @@ void k_layer_compress(Args A, int32_t first, int32_t nblock) {
 // ---------------------------------------------------------------------------
 
 // v = x - xhat over one group (up to 16 chunks = 4096 entries) of one layer: chunk and
-// group sums of the layer's norm tree.  One wave per chunk (the shape of k_dense_stat);
+// group sums of the layer's norm tree.  One wave per one or two chunks (the shape of k_dense_stat);
 // carries the fused local update.  The work items tile every row, padding included, so the
-// update reaches every entry.  grid (ngroup_items, n), block kStatThreads.
+// update reaches every entry.  grid (ngroup_items, n), block stat_threads(NT).
 template <int COMP, bool NT>
-__global__ __launch_bounds__(kStatThreads) void k_layer_stat(Args A) {
+__global__ __launch_bounds__(stat_threads(NT)) void k_layer_stat(Args A) {
   __shared__ double cs[kGroup];
   const int i = blockIdx.y;
   const LayerGroup item = A.layer_groups[blockIdx.x];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int64_t row = (int64_t)i * A.ld + item.off;
-  constexpr int CPW = kStatCpw;
+  constexpr int CPW = stat_cpw(NT);
   vf4 a[CPW], b[CPW];
   int e[CPW];   // index of the lane's first entry counted from the group's start
 #pragma unroll
