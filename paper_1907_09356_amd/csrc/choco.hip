@@ -1096,10 +1096,17 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     Args Q = S;
     Q.G = nullptr;
     Q.M = nullptr;
-    if (ctx->nbatched > 0) {
+    if (ctx->nbatched > 0 && NT && COMP == Q_TOPK) {
+      // (large states, streamed past the caches: the workgroup shape of the whole-row pass on long rows)
+      const dim3 cgrid((unsigned)((ctx->batched_nvec + 1023) / 1024), (unsigned)A.n, (unsigned)ctx->nbatched);
+      LAUNCH(ctx, S.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT, (k_sel_compact<COMP, false, NT, 1, true, 1024>), cgrid,
+             dim3(1024), 0, S);
+    } else if (ctx->nbatched > 0) {
       const dim3 cgrid((unsigned)((ctx->batched_nvec + 511) / 512), (unsigned)A.n, (unsigned)ctx->nbatched);
       LAUNCH(ctx, S.G ? KID_SEL_COMPACT_SGD : KID_SEL_COMPACT, (k_sel_compact<COMP, false, NT, 2, true>), cgrid,
              dim3(256), 0, S);
+    }
+    if (ctx->nbatched > 0) {
       LAUNCH(ctx, KID_SEL_REFINE, (k_sel_refine<COMP, true>), dim3((unsigned)A.n, (unsigned)ctx->nbatched), dim3(1024),
              0, Q);
     }
