@@ -1966,7 +1966,10 @@ int choco_unpack_messages(choco_ctx* ctx, const void* msgs_dev, float* q_dev) {
       break;
     case CHOCO_Q_QSGD:
       if (Wa.nlayers) LAUNCH(ctx, KID_WIRE, k_unpack_dense_layers<true>, lgrid, dim3(256), 0, Wa, msg, q_dev);
-      else LAUNCH(ctx, KID_WIRE, k_unpack_gsgd, wgrid, dim3(256), 0, Wa, msg, q_dev);
+      else if (Wa.levels < 256)
+        LAUNCH(ctx, KID_WIRE, k_unpack_gsgd<true>, wgrid, dim3(256), (size_t)(1 + Wa.mb) * 1024, Wa, msg, q_dev);
+      else
+        LAUNCH(ctx, KID_WIRE, k_unpack_gsgd<false>, wgrid, dim3(256), (size_t)(1 + Wa.mb) * 1024, Wa, msg, q_dev);
       break;
     case CHOCO_Q_TOPK: LAUNCH(ctx, KID_WIRE, k_unpack_topk, kgrid, dim3(256), 0, Wa, msg, q_dev); break;
     case CHOCO_Q_RANDK:

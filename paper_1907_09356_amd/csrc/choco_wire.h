@@ -240,62 +240,91 @@ __global__ __launch_bounds__(256) void k_wire_zero(float* q, int64_t ld) {
   if (o < ld) *reinterpret_cast<vf4*>(q + (int64_t)blockIdx.y * ld + o) = vf4{0.0f, 0.0f, 0.0f, 0.0f};
 }
 
-__device__ __forceinline__ void store32(const WireArgs& A, float* q, int i, int64_t w, const float (&v)[32]) {
-  float* dst = q + (int64_t)i * A.ld + 32 * w;
+// The dense decoders: a workgroup decodes 256 words of every plane (8192 entries), a thread one
+// 4-vector of q per turn with the 4-vectors of a wave next to each other, so that a store
+// instruction fills whole lines (a thread that decodes a word of its own stores 128 bytes apart
+// from its neighbour's: 800 us for the 896 MB of q at n = 8, d = 28 M).  The eight lanes that
+// share a plane word read it through the vector cache.  Pad columns of the last 4-vector get
+// zeros; grid (ceil(W / 256), n); the gsgd decoder takes (1 + mb) KiB of dynamic LDS.
+__device__ __forceinline__ void store_vec(const WireArgs& A, float* q, int i, int64_t vec, const float (&v)[4]) {
+  vf4 o;
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-    if (32 * w + 4 * j < A.d) {   // pad columns of the last 4-vector get the zeros set by the caller of this helper
-      vf4 o;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) o[u] = (32 * w + 4 * j + u < A.d) ? v[4 * j + u] : 0.0f;
-      *reinterpret_cast<vf4*>(dst + 4 * j) = o;
-    }
+  for (int u = 0; u < 4; ++u) o[u] = (4 * vec + u < A.d) ? v[u] : 0.0f;
+  *reinterpret_cast<vf4*>(q + (int64_t)i * A.ld + 4 * vec) = o;
 }
 
 __global__ __launch_bounds__(256) void k_unpack_sign(WireArgs A, const uint32_t* msg, float* q) {
   const int i = blockIdx.y;
-  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (w >= A.W) return;
   const uint32_t* in = msg + (int64_t)i * A.words;
   const float c = __uint_as_float(in[0]);
-  const uint32_t bits = in[1 + w];
-  float v[32];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) v[j] = ((bits >> j) & 1u) ? -c : c;
-  store32(A, q, i, w, v);
+  for (int j = 0; j < 8; ++j) {
+    const int64_t vec = (int64_t)blockIdx.x * 2048 + j * 256 + threadIdx.x;
+    if (4 * vec >= A.d) break;
+    const uint32_t bits = in[1 + (vec >> 3)] >> ((int)(vec & 7) * 4);
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = ((bits >> u) & 1u) ? -c : c;
+    store_vec(A, q, i, vec, v);
+  }
 }
 
+// PACKED (levels < 256): the four levels of a 4-vector are the four bytes of one word.
+template <bool PACKED>
 __global__ __launch_bounds__(256) void k_unpack_gsgd(WireArgs A, const uint32_t* msg, float* q) {
   const int i = blockIdx.y;
-  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (w >= A.W) return;
   const uint32_t* in = msg + (int64_t)i * A.words;
   const float step = __uint_as_float(in[0]);
   const uint32_t* planes = in + 1 + kOverflowSlots;
-  int32_t level[32];
+  uint32_t ovf[kOverflowSlots];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) level[j] = 0;
-  for (int p = 0; p < A.mb; ++p) {
-    const uint32_t bits = planes[(int64_t)(1 + p) * A.W + w];
-#pragma unroll
-    for (int j = 0; j < 32; ++j) level[j] |= (int32_t)((bits >> j) & 1u) << p;
+  for (int s = 0; s < kOverflowSlots; ++s) ovf[s] = in[1 + s];
+  // the workgroup's 256 words of every plane through LDS: one load per thread and plane, all
+  // in flight together, instead of a round trip to memory in each of the eight turns
+  extern __shared__ uint32_t pl[];   // (1 + mb) x 256
+  {
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (int p = 0; p <= A.mb; ++p) pl[p * 256 + threadIdx.x] = w < A.W ? planes[(int64_t)p * A.W + w] : 0u;
   }
-  for (int s = 0; s < kOverflowSlots; ++s) {
-    const uint32_t e = in[1 + s];
-    if (e != 0xFFFFFFFFu && (int64_t)(e >> 5) == w) {
+  __syncthreads();
+  const int sh = (int)(threadIdx.x & 7) * 4;
 #pragma unroll
-      for (int j = 0; j < 32; ++j)
-        if ((int)(e & 31u) == j) level[j] = A.levels;
+  for (int j = 0; j < 8; ++j) {
+    const int64_t vec = (int64_t)blockIdx.x * 2048 + j * 256 + threadIdx.x;
+    if (4 * vec >= A.d) break;
+    const int lw = j * 32 + (int)(threadIdx.x >> 3);
+    uint32_t level[4] = {0, 0, 0, 0};
+    for (int p = 0; p < A.mb; ++p) {
+      const uint32_t nib = (pl[(1 + p) * 256 + lw] >> sh) & 15u;
+      if (PACKED) {
+        // a plane's nibble times 0x204081 puts bit u at bit 8 u (and other bits elsewhere)
+        level[0] |= ((nib * 0x204081u) & 0x01010101u) << p;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) level[u] |= ((nib >> u) & 1u) << p;
+      }
     }
-  }
-  const uint32_t sign = planes[w];
-  float v[32];
+    if (PACKED) {
 #pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    const float mag = (float)level[j] * step;
-    v[j] = ((sign >> j) & 1u) ? -mag : mag;
+      for (int u = 1; u < 4; ++u) level[u] = (level[0] >> (8 * u)) & 0xFFu;
+      level[0] &= 0xFFu;
+    }
+#pragma unroll
+    for (int s = 0; s < kOverflowSlots; ++s)
+      if (ovf[s] != 0xFFFFFFFFu && (int64_t)(ovf[s] >> 2) == vec) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if ((int)(ovf[s] & 3u) == u) level[u] = (uint32_t)A.levels;
+      }
+    const uint32_t sign = pl[lw] >> sh;
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float mag = (float)level[u] * step;
+      v[u] = __uint_as_float(__float_as_uint(mag) | (((sign >> u) & 1u) << 31));
+    }
+    store_vec(A, q, i, vec, v);
   }
-  store32(A, q, i, w, v);
 }
 
 // after k_wire_zero.  grid (ceil(k / 256), n)

@@ -18,6 +18,8 @@ OPERATORS = [
     ("qsgd16", dict(compressor=binding.Q_QSGD, levels=16)),
     ("qsgd2_unbiased", dict(compressor=binding.Q_QSGD, levels=2, qsgd_biased=0)),
     ("qsgd3", dict(compressor=binding.Q_QSGD, levels=3)),
+    ("qsgd255", dict(compressor=binding.Q_QSGD, levels=255)),     # the largest level that fits a byte
+    ("qsgd300", dict(compressor=binding.Q_QSGD, levels=300)),     # nine magnitude planes
 ]
 
 
