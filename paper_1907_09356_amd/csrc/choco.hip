@@ -773,7 +773,8 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
   const int32_t nvec = (A.d + 3) >> 2;
   // long rows: 4 four-vectors per thread, short ones 2; random_a 4 at any length (its pass draws
   // Philox words beside the step's bandwidth-bound pass: half as many workgroups get in that pass's
-  // way less, n = 64, d = 270 k: 79.4 -> 75.3 us per step; 8 per thread: 76.3)
+  // way less, n = 64, d = 270 k: 79.4 -> 75.3 us per step; 8 per thread: 76.3; one per thread of a
+  // 1024-thread workgroup, the shape top_a's long rows take: 73.7 against 66.4 us as the step stands now)
   const int cvecs = (ctx->fallback_chain || COMP == Q_RANDK) ? kCompactVecs : 2;
   const dim3 cgrid = chunk_grid(nvec, A.n, cvecs);
   const size_t pad = ahead_lds_pad(ctx, A.d);
