@@ -291,7 +291,9 @@ int choco_profile_report(choco_ctx *ctx, char *buf_host, size_t buf_bytes);
    the caller's stream the library already selects the masks of the NEXT four steps on a stream
    of its own (created by choco_init, default priority, joined with two events per four steps;
    the kept lists and maps of eight steps are part of the workspace, no device memory is
-   allocated; rows above 2^21 entries: one step at a time, two copies).  Results do not
+   allocated; rows above 2^21 entries: one step at a time, two copies; with a layer table a
+   second such stream takes half of the selection's launches, forked from and joined to the
+   first).  Results do not
    change, whatever the calls in between (a moved step counter drops what was selected for
    other steps).  On by default
    where it applies; switch it off (enable = 0) if every call must leave all of its work

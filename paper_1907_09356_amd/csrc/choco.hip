@@ -74,6 +74,13 @@ struct choco_ctx {
   hipStream_t aux_stream;
   hipStream_t launch_stream;   // where LAUNCH puts kernels: the caller's stream, or aux_stream while selecting ahead
   hipEvent_t ev_fork, ev_ahead;
+  // layer tables: a selection made ahead is several short chains of launches that do not depend
+  // on one another (the layers that share launches, those with launches of their own, the layer
+  // kernel); on one stream they wait for each other and the whole takes longer than the step
+  // beside it, so half of them goes to a third stream, forked from and joined to aux_stream
+  hipStream_t aux_stream2;
+  hipEvent_t ev_fork2, ev_join2;
+  bool split_ahead;       // between that fork and join
   bool lookahead;         // the configuration allows it and it has not been switched off
   bool can_lookahead;     // the configuration allows it (random_a)
   bool ahead_pending;     // the batch `nxt` is in flight (or done) on aux_stream and not yet joined
@@ -571,6 +578,12 @@ void release_ctx(choco_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->aux_stream);
     (void)hipStreamDestroy(ctx->aux_stream);
   }
+  if (ctx->aux_stream2) {
+    (void)hipStreamSynchronize(ctx->aux_stream2);
+    (void)hipStreamDestroy(ctx->aux_stream2);
+  }
+  if (ctx->ev_fork2) (void)hipEventDestroy(ctx->ev_fork2);
+  if (ctx->ev_join2) (void)hipEventDestroy(ctx->ev_join2);
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   if (ctx->ev_ahead) (void)hipEventDestroy(ctx->ev_ahead);
   for (hipEvent_t e : ctx->ev_begin) (void)hipEventDestroy(e);
@@ -1097,6 +1110,18 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     Args Q = S;
     Q.G = nullptr;
     Q.M = nullptr;
+    // a selection made ahead: the chains that do not depend on one another on two streams - the
+    // layers with launches of their own on the one, everything else on the other; without such
+    // layers the ones that share launches on the one, the layer kernel on the other
+    // (forked and joined once for all the steps of a batch: a chain of one step follows the same
+    // chain of the step before on its stream, which is all the order the steps need - they share
+    // the control blocks and candidate lists of a chain, and nothing across chains)
+    const bool split = ctx->split_ahead;
+    const bool solo = nlong > ctx->nbatched;
+    auto second = [&](bool yes) {
+      if (split) ctx->launch_stream = yes ? ctx->aux_stream2 : ctx->aux_stream;
+    };
+    second(solo);
     if (ctx->nbatched > 0 && NT && COMP == Q_TOPK) {
       // (large states, streamed past the caches: the workgroup shape of the whole-row pass on long rows)
       const dim3 cgrid((unsigned)((ctx->batched_nvec + 1023) / 1024), (unsigned)A.n, (unsigned)ctx->nbatched);
@@ -1114,6 +1139,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     // top_a with several long layers: a layer's select (a few small launches that wait on
     // memory) goes to the second stream and runs beside the next layer's pass over the rows
     const bool overlap = COMP == Q_TOPK && ctx->overlap_long && !ctx->profiling && ctx->launch_stream == ctx->stream;
+    second(false);
     for (int b = 0; b < nlong; ++b) {
       long_layer_pass<COMP, NT>(ctx, S, b);
       if (overlap) {
@@ -1125,6 +1151,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
       ctx->launch_stream = overlap ? ctx->stream : ctx->launch_stream;
     }
     const int kid = S.G ? KID_LAYER_COMPRESS_SGD : KID_LAYER_COMPRESS;
+    second(true);
     if (wide) {
       if (wide_blocks > 0)
         LAUNCH(ctx, kid, (k_layer_compress<COMP, 1024, NT>), dim3((unsigned)wide_blocks, (unsigned)A.n), dim3(1024), 0,
@@ -1141,6 +1168,7 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
       HIP_TRY(ctx, hipEventRecord(ctx->ev_ahead, ctx->aux_stream));
       HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_ahead, 0));
     }
+    second(false);
     return CHOCO_OK;
   };
   // random_a: this step's masks may already have been drawn on the second stream
@@ -1182,7 +1210,17 @@ int gossip_layers_sparse(choco_ctx* ctx, const Args& F) {
     const uint64_t base = (ctx->t / (uint64_t)ctx->ahead_steps + 1) * (uint64_t)ctx->ahead_steps;
     int rc = look_ahead_fork(ctx);
     if (rc != CHOCO_OK) return rc;
+    if (ctx->aux_stream2 != nullptr) {
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_fork2, ctx->aux_stream));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream2, ctx->ev_fork2, 0));
+      ctx->split_ahead = true;
+    }
     for (int u = 0; u < ctx->ahead_steps; ++u) (void)select_layers(look_ahead_args(ctx, A, base + (uint64_t)u));
+    if (ctx->split_ahead) {
+      ctx->split_ahead = false;
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_join2, ctx->aux_stream2));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_join2, 0));
+    }
     rc = look_ahead_end(ctx, A, base);
     if (rc != CHOCO_OK) return rc;
   }
@@ -1399,6 +1437,9 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   ctx->aux_stream = nullptr;
   ctx->launch_stream = ctx->stream;
   ctx->ev_fork = ctx->ev_ahead = nullptr;
+  ctx->aux_stream2 = nullptr;
+  ctx->ev_fork2 = ctx->ev_join2 = nullptr;
+  ctx->split_ahead = false;
   ctx->lookahead = ctx->can_lookahead = ctx->ahead_pending = false;
   ctx->cur = ctx->nxt = AheadBatch{0, false};
   ctx->ahead_steps = cfg->d > ((int64_t)1 << 21) ? 1 : kAheadSteps;
@@ -1544,6 +1585,11 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
     hipError_t se = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_ahead, hipEventDisableTiming);
+    if (cfg->nlayers > 0) {
+      if (se == hipSuccess) se = hipStreamCreateWithFlags(&ctx->aux_stream2, hipStreamNonBlocking);
+      if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_fork2, hipEventDisableTiming);
+      if (se == hipSuccess) se = hipEventCreateWithFlags(&ctx->ev_join2, hipEventDisableTiming);
+    }
     if (se != hipSuccess) {
       release_ctx(ctx);
       return CHOCO_E_HIP;
