@@ -270,6 +270,32 @@ def test_long_layers_fused_iterations(name, q, order, mix_form):
         pair.close()
 
 
+def test_long_layers_random_masks_selected_ahead_over_several_batches():
+    # a selection made ahead is spread over two streams of the library (layers with launches of
+    # their own; layers that share launches and the layer kernel): eleven steps cross two batch
+    # boundaries, with the look-ahead switched off and on and the step counter moved in between
+    layers = long_layers(fraction=0.02)
+    n = 3
+    X0, inside = padded_state(n, layers, seed=35)
+    pair = Pair(X0, synth.ring_csr(n), 0.3, seed=19, layers=layers, compressor=binding.Q_RANDK)
+    grads = synth.GradientStream(n, pair.d, seed=18, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(11):
+            if t == 5:
+                pair.gpu.set_lookahead(False)
+            if t == 6:
+                pair.gpu.set_lookahead(True)
+            if t == 9:      # in the middle of a batch: what was selected for the old counter is dropped
+                pair.gpu.set_step(101)
+                pair.ref.t = 101
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step(G, 0.1)
+            pair.check(det, tag="long layers selected ahead, step %d" % t)
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("mix_form", [binding.MIX_AUTO, binding.MIX_INCREMENTAL_S])
 @pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1]])
 def test_long_layers_momentum_with_a_silent_long_layer(name, q, mix_form):
