@@ -131,7 +131,12 @@ int choco_workspace_bytes(const choco_config *cfg, size_t *bytes_host);
    t = 0.  workspace_dev must be 256-byte aligned.  CHOCO_E_INVAL for n < 1, d out of
    range (above CHOCO_MAX_D), bad ld, k outside [1, d], levels < 1, gamma <= 0 or not finite, null pointers,
    malformed CSR, or a W that violates Assumption 1; CHOCO_E_NOMEM if the workspace is
-   too small.  On error *out is NULL. */
+   too small.  On error *out is NULL.
+   Reads one environment variable, CHOCO_FALLBACK_SPIN_LIMIT (decimal; default 65536): TOPK /
+   RANDK on rows above 2^21 entries repair a failed threshold guess in one launch whose
+   workgroups wait for one of their number in a bounded poll; this is the bound.  A workgroup
+   that reaches it leaves and the exact select scans the row instead: same result, slower.  0
+   forces that path (a test of it); there is no reason to set it otherwise. */
 int choco_init(const choco_config *cfg, float *x_dev, void *workspace_dev, size_t workspace_bytes,
                choco_ctx **out);
 

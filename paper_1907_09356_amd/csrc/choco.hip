@@ -603,13 +603,13 @@ int join_lookahead(choco_ctx* ctx) {
 
 enum KernelId {
   KID_SGD, KID_MOMENTUM, KID_DENSE_STAT, KID_GROUP_REDUCE, KID_DENSE_FINALISE, KID_DENSE_APPLY_MIX, KID_TILE_MIX,
-  KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_HIST16,
-  KID_SEL_FINAL16, KID_SEL_REBUILD, KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_GATHER_VALUES, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
+  KID_DENSE_APPLY, KID_MIX_DIRECT_GLOBAL, KID_MIX_INCREMENTAL, KID_SEL_COMPACT, KID_SEL_FALLBACK,
+  KID_SEL_REFINE, KID_SCATTER_S, KID_XHAT_UPDATE, KID_GATHER_VALUES, KID_SEL_VALUES, KID_SEL_HIST_PARTS, KID_SEL_EMIT_PARTS, KID_SEL_FINISH, KID_DENSE_STAT_SGD, KID_SEL_COMPACT_SGD, KID_TILE_MIX_SGD, KID_MIX_INCREMENTAL_SGD, KID_LAYER_COMPRESS, KID_LAYER_COMPRESS_SGD, KID_LAYER_STAT, KID_LAYER_STAT_SGD, KID_LAYER_FINALISE, KID_WIRE, KID_ZERO_WORDS, KID_COUNT
 };
 const char* const kKernelNames[KID_COUNT] = {
   "k_sgd", "k_momentum", "k_dense_stat", "k_group_reduce", "k_dense_finalise", "k_dense_apply_mix", "k_tile_mix",
-  "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_hist16",
-  "k_sel_final16", "k_sel_rebuild", "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_gather_values", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
+  "k_dense_apply", "k_mix_direct_global", "k_mix_incremental", "k_sel_compact", "k_sel_fallback",
+  "k_sel_refine", "k_scatter_s", "k_xhat_update", "k_gather_values", "k_sel_values", "k_sel_hist_parts", "k_sel_emit_parts", "k_sel_finish",
   "k_dense_stat_sgd", "k_sel_compact_sgd", "k_tile_mix_sgd", "k_mix_incremental_sgd",
   "k_layer_compress", "k_layer_compress_sgd", "k_layer_stat", "k_layer_stat_sgd", "k_layer_finalise", "k_wire",
   "k_zero_words"};
@@ -767,6 +767,13 @@ int gossip_dense(choco_ctx* ctx, const Args& F) {
   return CHOCO_OK;
 }
 
+// Workgroups of the fallback launch: kFallbackBlocks per worker while all of them fit the chip
+// together (those of a worker wait for each other inside the kernel), one per worker beyond.
+dim3 fallback_grid(int n) {
+  const int per = (int64_t)kFallbackBlocks * n <= 1024 ? kFallbackBlocks : std::max(1, 1024 / n);
+  return dim3((unsigned)per, (unsigned)n);
+}
+
 // A long pass that selects ahead generates Philox words (ALU work) while the caller's stream
 // runs the bandwidth-bound mix.  Left alone its workgroups fill every wave slot first and the
 // mix waits behind them; 48 KiB of LDS that it does not use hold it to two workgroups per
@@ -805,10 +812,7 @@ void launch_select(choco_ctx* ctx, const Args& C, const Args& A, int kid_compact
     else LAUNCH(ctx, kid_compact, (k_sel_compact<COMP, false, NT, kCompactVecs>), cgrid, dim3(256), pad, C);
   }
   if (ctx->fallback_chain) {
-    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
-    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, A);
-    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, A);
-    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, A);
+    LAUNCH(ctx, KID_SEL_FALLBACK, (k_sel_fallback<COMP>), fallback_grid(A.n), dim3(256), 0, A);
   }
   if (ctx->multipart) {
     const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
@@ -1065,10 +1069,7 @@ void long_layer_select(choco_ctx* ctx, const Args& A, int which) {
   if (B.k == 0 || B.batched) return;
   const Args Al = long_layer_args(ctx, A, which);
   if (B.plan.fallback_chain) {
-    const dim3 fgrid((unsigned)kFallbackBlocks, (unsigned)A.n);
-    LAUNCH(ctx, KID_SEL_HIST16, (k_sel_hist16<COMP>), fgrid, dim3(256), 0, Al);
-    LAUNCH(ctx, KID_SEL_FINAL16, (k_sel_final16<COMP>), dim3((unsigned)A.n), dim3(1024), 0, Al);
-    LAUNCH(ctx, KID_SEL_REBUILD, (k_sel_rebuild<COMP>), fgrid, dim3(256), 0, Al);
+    LAUNCH(ctx, KID_SEL_FALLBACK, (k_sel_fallback<COMP>), fallback_grid(A.n), dim3(256), 0, Al);
   }
   if (B.plan.multipart) {
     const dim3 pgrid((unsigned)kRefineParts, (unsigned)A.n);
@@ -1492,6 +1493,10 @@ int choco_init(const choco_config* cfg, float* x_dev, void* workspace_dev, size_
   A.col = (const int32_t*)(base + L.col);
   A.w = (const float*)(base + L.w);
   A.ctl = (WorkerCtl*)(base + L.ctl);
+  // polls of about 2 us each: a tenth of a second before a workgroup of the fallback stops waiting
+  // for its worker's others (CHOCO_FALLBACK_SPIN_LIMIT: for tests of that path, which scans the row)
+  A.spin_limit = 1u << 16;
+  if (const char* sl = std::getenv("CHOCO_FALLBACK_SPIN_LIMIT")) A.spin_limit = (uint32_t)std::strtoul(sl, nullptr, 10);
   A.gamma = cfg->gamma;
   A.chunk_sums = (double*)(base + L.chunk_sums);
   A.group_sums = (double*)(base + L.group_sums);

@@ -69,6 +69,10 @@ struct WorkerCtl {
   uint32_t last_candidates;  // length of the candidate list the last select worked on
   uint32_t emit_count;  // multi-block select: kept entries emitted so far
   uint32_t small_count; // multi-block select: entries of the threshold bin collected so far
+  // the fallback's workgroups of this worker: how many have histogrammed their share so far (never
+  // reset: 'the last one in' is by remainder), the number of the round whose guess is placed, and
+  // 'a workgroup gave up waiting: do not trust the list' (cleared when the next guess is placed)
+  uint32_t fb_arrive, fb_go, fb_abort;
   uint64_t kstar;       // composite key of the k-th largest entry: kept <=> key >= kstar
 };
 
@@ -161,6 +165,7 @@ struct Args {
   uint32_t cand_cap;   // largest total the fallback aims to stay under
   uint32_t sample_stride;  // the fallback histogram looks at every sample_stride-th 4-vector
   uint32_t sample_need;    // rank (within the sample) at which the fallback puts the guess
+  uint32_t spin_limit;     // polls after which a waiting workgroup of the fallback gives up
   uint32_t want;       // entries the next guess should leave above it now: extra (+ k for top_a)
   uint32_t extra;      // candidates wanted beyond k: max(k/2, 6 sqrt(k) + 32)
   uint32_t delta0;     // default distance of the guess below the threshold key
@@ -1431,102 +1436,137 @@ __global__ __launch_bounds__(THREADS) void k_sel_compact(Args A0) {
   compact_chunk<COMP, DO_MIX, NT, true, VECS, THREADS>(A, blockIdx.y, blockIdx.x, stage, &s_count, &s_base);
 }
 
-// The rebuild pass of the fallback: only workers in mode 1; a few blocks per
-// worker loop over the chunks, so that the launch costs next to nothing when no
-// worker needs it.  grid (kFallbackBlocks, n), block 256.
+// The fallback of a failed guess on a long row, one launch.  A workgroup whose worker's list is
+// good leaves at once: a step whose guesses held pays for one launch of workgroups that read one
+// control block each.  For a worker whose list is not good, its workgroups
+//   1. histogram the top 16 bits of key32 over a sample of the row (every sample_stride-th
+//      4-vector; stride 1 = the whole row) and then count themselves in; the last one in
+//   2. walks the histogram from the top to the bucket at which the count reaches sample_need,
+//      puts the guess at its floor, sets the worker's mode for this step (with the whole row
+//      histogrammed it also knows whether the rebuilt list will fit; a sampled histogram lets
+//      the rebuild find out, and the select scans the row if it does not), clears the histogram
+//      and lets the others go, which wait for that in a bounded poll; then all of them
+//   3. rebuild the candidate list with the new guess, a few chunks each.
+// The wait needs the worker's workgroups resident together: the host launches at most 1024 of
+// them in all (one per worker above that, which waits for nobody).  A workgroup that polls
+// spin_limit times in vain (a device shared with work that never ends) marks the worker's list
+// as not to be trusted and leaves; the select then scans the row, which needs no list.
+// grid (blocks per worker, n), block 256.
 template <int COMP>
-__global__ __launch_bounds__(256) void k_sel_rebuild(Args A) {
+__global__ __launch_bounds__(256) void k_sel_fallback(Args A) {
   __shared__ uint2 stage[kStageCap];
   __shared__ uint32_t s_count, s_base;
+  __shared__ uint32_t part[256];
+  __shared__ uint32_t s_grp, s_above, s_last, s_gen, s_go;
   const int i = blockIdx.y;
-  if (A.ctl[i].mode != 1u) return;
-  const int nvec = (A.d + 3) >> 2;
-  const int nchunk = (nvec + 256 * kCompactVecs - 1) / (256 * kCompactVecs);
-  for (int chunk = blockIdx.x; chunk < nchunk; chunk += gridDim.x) {
-    __syncthreads();
-    if (threadIdx.x == 0) s_count = 0;
-    __syncthreads();
-    compact_chunk<COMP, false, false, false, kCompactVecs>(A, i, chunk, stage, &s_count, &s_base);
-  }
-}
-
-// Fallback, step 1: 16-bit histogram of key32 over a sample (every
-// sample_stride-th 4-vector; stride 1 = the whole row) of the rows whose list
-// is not good.  grid (kFallbackBlocks, n), block 256.
-template <int COMP>
-__global__ __launch_bounds__(256) void k_sel_hist16(Args A) {
-  const int i = blockIdx.y;
-  const WorkerCtl* ctl = A.ctl + i;
-  if (list_is_good(ctl, A)) return;
-  uint32_t* hist = A.hist16 + (int64_t)i * kBins16;
-  const int nvec = (A.d + 3) >> 2;
-  const int64_t nsample = ((int64_t)nvec + A.sample_stride - 1) / A.sample_stride;
-  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nsample; j += (int64_t)gridDim.x * 256) {
-    const int m = (int)(j * (int64_t)A.sample_stride);
-    uint32_t a[4];
-    entry_bits<COMP, false, false, false>(A, i, m, a);
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (4 * m + c >= A.e_lo && 4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
-  }
-}
-
-// Fallback, step 2: walk the (sampled) histogram from the top to the bucket at
-// which the count reaches sample_need and put the guess at its floor; with the
-// whole row histogrammed, also check that the rebuilt list will fit.  Sets the
-// mode of every worker for this step and clears the histogram it used.
-// grid n, block 1024.
-template <int COMP>
-__global__ __launch_bounds__(1024) void k_sel_final16(Args A) {
-  __shared__ uint32_t part[1024];
-  __shared__ uint32_t s_grp, s_above;
-  const int i = blockIdx.x;
   WorkerCtl* ctl = A.ctl + i;
   if (list_is_good(ctl, A)) {
-    if (threadIdx.x == 0) ctl->mode = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) ctl->mode = 0;
     return;
   }
   uint32_t* hist = A.hist16 + (int64_t)i * kBins16;
+  const int nvec = (A.d + 3) >> 2;
   const int t = threadIdx.x;
-  uint32_t mine[64];
-  uint32_t sum = 0;
+  {
+    const int64_t nsample = ((int64_t)nvec + A.sample_stride - 1) / A.sample_stride;
+    for (int64_t j = (int64_t)blockIdx.x * 256 + t; j < nsample; j += (int64_t)gridDim.x * 256) {
+      const int m = (int)(j * (int64_t)A.sample_stride);
+      uint32_t a[4];
+      entry_bits<COMP, false, false, false>(A, i, m, a);
 #pragma unroll
-  for (int b = 0; b < 64; ++b) {
-    mine[b] = hist[64 * t + b];
-    hist[64 * t + b] = 0;
-    sum += mine[b];
+      for (int c = 0; c < 4; ++c)
+        if (4 * m + c >= A.e_lo && 4 * m + c < A.d) atomicAdd(&hist[Digits<COMP>::bin16(a[c])], 1u);
+    }
   }
-  part[t] = sum;
   __syncthreads();
-  const uint64_t need = A.sample_need;
   if (t == 0) {
-    uint32_t cum = 0;
-    int g = 1023;
-    for (; g > 0; --g) {
-      if ((uint64_t)cum + part[g] >= need) break;
-      cum += part[g];
-    }
-    s_grp = (uint32_t)g;
-    s_above = cum;
+    __threadfence();   // the workgroup's counts (complete at the barrier) before it counts itself in
+    const uint32_t ticket = atomicAdd(&ctl->fb_arrive, 1u);
+    s_last = (ticket % gridDim.x == gridDim.x - 1u) ? 1u : 0u;
+    s_gen = ticket / gridDim.x + 1u;
   }
   __syncthreads();
-  if ((uint32_t)t == s_grp) {
-    uint32_t cum = s_above;
-    int b = 63;
-    for (; b > 0; --b) {
-      if ((uint64_t)cum + mine[b] >= need) break;
-      cum += mine[b];
+  if (s_last) {
+    __threadfence();
+    // thread t owns the 256 buckets from 256 t
+    static_assert(kBins16 == 256 * 256, "256 buckets per thread of a 256-thread workgroup");
+    // (plain loads: the fence above has dropped what the caches held of the histogram, and the
+    // others' counts were written back before they counted themselves in)
+    const uint4* mine = reinterpret_cast<const uint4*>(hist + 256 * t);
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (int b = 0; b < 64; ++b) {
+      const uint4 v = mine[b];
+      sum += v.x + v.y + v.z + v.w;
     }
-    const uint32_t bin = 64u * (uint32_t)t + (uint32_t)b;
-    const uint64_t listed = (uint64_t)cum + (uint64_t)mine[b];   // sampled entries with key32 >= floor(bin)
-    ctl->guess_key = Digits<COMP>::bin16_floor(bin);
-    ctl->bin_shift = COMP == Q_TOPK ? 9u : 10u;   // 64 candidate bins per 16-bit bucket
-    // an exact histogram knows whether the rebuilt list fits; a sampled one lets the
-    // rebuild find out (the select then scans the row if it does not)
-    ctl->mode = (A.sample_stride > 1u || listed <= (uint64_t)A.cand_cap) ? 1u : 2u;
-    if (ctl->mode == 1u) ctl->fallbacks += 1;
-    if (ctl->mode == 1u)
-      for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
+    part[t] = sum;
+    __syncthreads();
+    const uint64_t need = A.sample_need;
+    if (t == 0) {
+      uint32_t cum = 0;
+      int g = 255;
+      for (; g > 0; --g) {
+        if ((uint64_t)cum + part[g] >= need) break;
+        cum += part[g];
+      }
+      s_grp = (uint32_t)g;
+      s_above = cum;
+    }
+    __syncthreads();
+    // the buckets of that group, one per thread, then one thread walks them
+    const uint32_t grp = s_grp;
+    part[t] = hist[256u * grp + (uint32_t)t];
+    __syncthreads();
+    if (t == 0) {
+      uint32_t cum = s_above, in_b = 0;
+      int b = 255;
+      for (; b >= 0; --b) {
+        in_b = part[b];
+        if (b == 0 || (uint64_t)cum + in_b >= need) break;
+        cum += in_b;
+      }
+      const uint32_t bin = 256u * grp + (uint32_t)b;
+      const uint64_t listed = (uint64_t)cum + (uint64_t)in_b;   // sampled entries with key32 >= floor(bin)
+      ctl->guess_key = Digits<COMP>::bin16_floor(bin);
+      ctl->bin_shift = COMP == Q_TOPK ? 9u : 10u;   // 64 candidate bins per 16-bit bucket
+      const uint32_t mode = (A.sample_stride > 1u || listed <= (uint64_t)A.cand_cap) ? 1u : 2u;
+      ctl->mode = mode;
+      if (mode == 1u) {
+        ctl->fallbacks += 1;
+        for (int sg = 0; sg < kSegs; ++sg) ctl->seg_count[sg] = 0;
+      }
+    }
+    if (t == 0) {
+      __threadfence();
+      __hip_atomic_store(&ctl->fb_go, s_gen, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    for (int b = 0; b < 256; ++b) hist[256 * b + t] = 0;   // (nobody reads it again in this launch)
+    __syncthreads();   // the mode that thread 0 has set is read by all below
+  } else {
+    if (t == 0) {
+      uint32_t ok = 0;
+      for (uint32_t it = 0; it < A.spin_limit; ++it) {
+        const uint32_t go = __hip_atomic_load(&ctl->fb_go, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+        if ((int32_t)(go - s_gen) >= 0) {
+          ok = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(64);
+      }
+      if (!ok) __hip_atomic_store(&ctl->fb_abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_go = ok;
+    }
+    __syncthreads();
+    if (!s_go) return;
+    __threadfence();
+  }
+  if (__hip_atomic_load(&ctl->mode, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 1u) return;
+  const int nchunk = (nvec + 256 * kCompactVecs - 1) / (256 * kCompactVecs);
+  for (int chunk = blockIdx.x; chunk < nchunk; chunk += gridDim.x) {
+    __syncthreads();
+    if (t == 0) s_count = 0;
+    __syncthreads();
+    compact_chunk<COMP, false, false, false, kCompactVecs>(A, i, chunk, stage, &s_count, &s_base);
   }
 }
 
@@ -1565,7 +1605,7 @@ __device__ __forceinline__ void list_layout_wave(const Args& A, const WorkerCtl*
   const bool fits = __ballot(raw > A.seg_cap) == 0ull;
   const bool all_short = __ballot(raw > kSpecPerSeg) == 0ull;
   if (lane == 0) {
-    *good_out = (fits && rawsum >= (unsigned long long)A.k) ? 1u : 0u;
+    *good_out = (fits && rawsum >= (unsigned long long)A.k && ctl->fb_abort == 0u) ? 1u : 0u;
     if (short_out) *short_out = all_short ? 1u : 0u;
   }
 }
@@ -1747,6 +1787,7 @@ __device__ __forceinline__ void next_guess(const Args& A, WorkerCtl* ctl, uint64
   ctl->mode = mode;
   ctl->emit_count = 0;
   ctl->small_count = 0;
+  ctl->fb_abort = 0;
   if (mode == 2u) ctl->fallbacks += 1;
   for (int s = 0; s < kSegs; ++s) ctl->seg_count[s] = 0;
 }

@@ -336,6 +336,42 @@ def test_a_layer_long_enough_for_the_histogram_fallback(name, q):
         pair.close()
 
 
+@pytest.mark.parametrize("polls", ["0", None])
+@pytest.mark.parametrize("layered", [True, False])
+@pytest.mark.parametrize("name,q", [OPERATORS[0], OPERATORS[1]])
+def test_fallback_workgroups_that_stop_waiting_leave_the_select_to_scan_the_row(name, q, layered, polls, monkeypatch):
+    # the workgroups of the fallback launch wait for the one that places the new guess, in a
+    # bounded poll; with a bound of zero polls (set from the host) every one of them gives up at
+    # once, the list is marked as not to be trusted and the exact select scans the row: same result
+    # (polls = None: the library's own bound; the list is rebuilt from the histogram)
+    if polls is not None:
+        monkeypatch.setenv("CHOCO_FALLBACK_SPIN_LIMIT", polls)
+    n = 3
+    if layered:
+        layers = synth.layer_table([100, 2_200_000, 45000], fraction=0.001)
+        X0, inside = padded_state(n, layers, seed=36)
+        pair = Pair(X0, synth.ring_csr(n), 0.3, seed=20, layers=layers, **q)
+    else:
+        d = 2_300_003
+        X0, inside = synth.normal_state(n, d, seed=36), np.ones(d, dtype=bool)
+        pair = Pair(X0, synth.ring_csr(n), 0.3, seed=20, k=2300, **q)
+    grads = synth.GradientStream(n, pair.d, seed=19, noise_std=0.05, bias_std=0.02)
+    try:
+        for t in range(3):
+            G = grads.next()
+            G[:, ~inside] = 0.0
+            det = pair.step(G, 0.1)
+            pair.check(det, tag="%s fallback without the wait, step %d" % (name, t))
+            if not layered and t == 0 and q["compressor"] == binding.Q_TOPK:
+                # top_a has no guess at the first step: the fallback ran (counted once per worker)
+                # and ended in the row scan (mode 2), or the select took the rebuilt list (mode 0)
+                scal = pair.gpu.last_scalars()
+                assert np.all(scal[:, 4] >= 1)
+                assert np.all(scal[:, 3] == (2 if polls == "0" else 0))
+    finally:
+        pair.close()
+
+
 def test_long_layer_topk_ties_go_to_the_lower_index():
     layers = synth.layer_table([3000, 120000], fraction=0.2)
     d = synth.layers_dim(layers)
