@@ -277,6 +277,23 @@ def test_guess_survives_a_sudden_change_of_scale():
         pair.close()
 
 
+def test_guess_fails_again_and_again_on_long_rows():
+    # rows above 2^21 entries repair a failed guess in one launch whose workgroups count themselves
+    # in per worker: several failures in one run (the scale of the difference jumps both ways), and
+    # enough workers that each gets fewer workgroups than the usual 64
+    n, d, k = 20, 2_100_003, 2100
+    pair = Pair(synth.normal_state(n, d, seed=3), synth.ring_csr(n), 0.2, compressor=B.Q_TOPK, k=k)
+    try:
+        rng = np.random.default_rng(1)
+        for t, scale in enumerate([1.0, 1e-4, 1e5, 1.0, 1e-3]):
+            G = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+            det = pair.step(G, 1.0)
+            pair.check(det, tag="long rows, scale jump, step %d" % t)
+        assert np.all(pair.gpu.last_scalars()[:, 4] >= 2)    # steps so far that needed the fallback, per worker
+    finally:
+        pair.close()
+
+
 def test_zero_state_and_zero_norm():
     n, d = 4, 1000
     for comp in ("sign", "qsgd16", "topk"):
