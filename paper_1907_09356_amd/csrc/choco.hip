@@ -536,7 +536,12 @@ int check_csr(const choco_config* c, int32_t* nnz_out, int32_t* maxdeg_out) {
 }
 
 int hip_fail(choco_ctx* ctx, hipError_t e) {
-  if (ctx) ctx->last_hip_error = (int)e;
+  if (ctx) {
+    ctx->last_hip_error = (int)e;
+    // an error between a fork and its join: later calls launch on the caller's stream again
+    ctx->launch_stream = ctx->stream;
+    ctx->split_ahead = false;
+  }
   return CHOCO_E_HIP;
 }
 
